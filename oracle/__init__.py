@@ -1,0 +1,130 @@
+"""ctypes front end of the CPU oracle in ``bbb_oracle.c``.
+
+Test infrastructure only: the tests, the smoke check and the benchmark's
+``cpu_baseline`` leg call this; the product package never imports it.  This module
+marshals numpy arrays and does no arithmetic of the method itself.
+
+The functions follow Algorithm 2 of arxiv 2604.04736 (per-GPU inner loop): see the
+comments in ``bbb_oracle.c`` for which line each one writes out.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "bbb_oracle.c")
+_LIB = os.path.join(_HERE, "libbbb_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile ``bbb_oracle.c`` with gcc into ``libbbb_oracle.so`` next to it."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+           "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build(force=False)
+    lib = ctypes.CDLL(_LIB)
+    fp = ctypes.POINTER(ctypes.c_float)
+    dp = ctypes.POINTER(ctypes.c_double)
+    lib.bbb_oracle_threads.argtypes = [ctypes.c_int]
+    lib.bbb_oracle_threads.restype = ctypes.c_int
+    lib.bbb_oracle_reparam.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                       fp, fp, fp, dp, ctypes.c_int64, ctypes.c_int]
+    lib.bbb_oracle_reparam.restype = None
+    lib.bbb_oracle_kl.argtypes = [ctypes.c_int64, fp, fp]
+    lib.bbb_oracle_kl.restype = ctypes.c_double
+    lib.bbb_oracle_grad.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                    ctypes.c_double, ctypes.c_int, fp, fp, fp, fp, dp, dp,
+                                    ctypes.c_int]
+    lib.bbb_oracle_grad.restype = None
+    _lib = lib
+    return lib
+
+
+def _f32(a, name):
+    a = np.asarray(a)
+    if a.dtype != np.float32:
+        raise TypeError(f"{name} must be float32, got {a.dtype}")
+    if not a.flags.c_contiguous:
+        raise ValueError(f"{name} must be C-contiguous")
+    return a
+
+
+def _fptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _dptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _check_2d(a, s_loc, n, name):
+    if a.ndim != 2 or a.shape[0] != s_loc or a.shape[1] < n:
+        raise ValueError(f"{name} must have shape [S_loc={s_loc}, ld>={n}], got {a.shape}")
+
+
+def threads(nthreads: int) -> int:
+    return int(_load().bbb_oracle_threads(int(nthreads)))
+
+
+def reparam(mu, sigma, eps, nthreads: int = 1) -> np.ndarray:
+    """w[s,i] = mu[i] + sigma[i]*eps[s,i] in fp64; eps is [S_loc, ld>=N]; returns [S_loc, N]."""
+    mu = _f32(mu, "mu")
+    sigma = _f32(sigma, "sigma")
+    eps = _f32(eps, "eps")
+    n = mu.shape[0]
+    if mu.ndim != 1 or sigma.shape != mu.shape:
+        raise ValueError("mu and sigma must be 1-D of equal length")
+    s_loc = eps.shape[0]
+    _check_2d(eps, s_loc, n, "eps")
+    w = np.empty((s_loc, n), dtype=np.float64)
+    _load().bbb_oracle_reparam(n, eps.shape[1], s_loc, _fptr(mu), _fptr(sigma), _fptr(eps),
+                               _dptr(w), n, int(nthreads))
+    return w
+
+
+def kl(mu, sigma) -> float:
+    """1/2 sum_i (sigma_i^2 + mu_i^2 - 1 - ln sigma_i^2) in fp64."""
+    mu = _f32(mu, "mu")
+    sigma = _f32(sigma, "sigma")
+    if mu.ndim != 1 or sigma.shape != mu.shape:
+        raise ValueError("mu and sigma must be 1-D of equal length")
+    return float(_load().bbb_oracle_kl(mu.shape[0], _fptr(mu), _fptr(sigma)))
+
+
+def grad(mu, sigma, eps, G, s_total: int, dataset_size: float, reduce_mean: bool = False,
+         nthreads: int = 1):
+    """(grad_mu, grad_sigma) in fp64, each [N]; eps and G are [S_loc, ld>=N] with equal pitch."""
+    mu = _f32(mu, "mu")
+    sigma = _f32(sigma, "sigma")
+    eps = _f32(eps, "eps")
+    G = _f32(G, "G")
+    n = mu.shape[0]
+    if mu.ndim != 1 or sigma.shape != mu.shape:
+        raise ValueError("mu and sigma must be 1-D of equal length")
+    s_loc = eps.shape[0]
+    _check_2d(eps, s_loc, n, "eps")
+    if G.shape != eps.shape:
+        raise ValueError("G and eps must have the same shape")
+    if not (1 <= s_loc <= s_total) or not dataset_size > 0:
+        raise ValueError("need 1 <= S_loc <= S and |D| > 0")
+    gmu = np.empty(n, dtype=np.float64)
+    gsig = np.empty(n, dtype=np.float64)
+    _load().bbb_oracle_grad(n, eps.shape[1], s_loc, int(s_total), float(dataset_size),
+                            1 if reduce_mean else 0, _fptr(mu), _fptr(sigma), _fptr(eps),
+                            _fptr(G), _dptr(gmu), _dptr(gsig), int(nthreads))
+    return gmu, gsig

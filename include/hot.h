@@ -1,0 +1,126 @@
+/*
+ * libhot -- the per-GPU mean-field Gaussian sample layer of sampling-parallel
+ * Bayes-by-Backprop training, for AMD MI355X (gfx950).
+ *
+ * What it computes is the part of Algorithm 2 of arxiv 2604.04736 ("Sampling
+ * Parallelism for Fast and Efficient Bayesian Learning") that one GPU runs on its
+ * share of the Monte-Carlo samples and that does not depend on the network:
+ * the reparameterisation line, the prior-matching (KL) line, and the chain rule
+ * from per-sample weight gradients to the gradients of mu and sigma with the
+ * scaling of the loss and averaging lines.  Algorithm 1 is the case of one GPU.
+ *
+ * Notation: N weights with mean mu[i] and standard deviation sigma[i] (sigma > 0 is
+ * a precondition; IEEE propagation otherwise); S samples per step over all GPUs;
+ * S_loc of them on this GPU; |D| the dataset size.  2-D arrays are row-major
+ * [S_loc, ld] with row pitch ld >= N floats; columns N..ld-1 are never read or
+ * written.  All data pointers are DEVICE pointers owned by the caller, must stay
+ * valid until the stream has executed the call, and outputs must not alias
+ * anything else.  Pointers need only 4-byte alignment; when every pointer is
+ * 16-byte aligned and ld is a multiple of 4 the aligned fast path is taken.
+ *
+ * Every run call is asynchronous on the given stream (a hipStream_t passed as
+ * void*; NULL is the default stream) and does no host synchronisation.  A plan may
+ * be used by one stream at a time.  The same inputs with the same plan and launch
+ * configuration give bitwise identical outputs (no floating-point atomics).
+ *
+ * All functions return HOT_OK or a negative error code; nothing aborts, throws or
+ * prints.
+ */
+#ifndef HOT_H
+#define HOT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HOT_VERSION 100 /* major*10000 + minor*100 + patch */
+
+enum {
+    HOT_OK = 0,
+    HOT_EINVAL = -1, /* bad argument (null pointer, size out of range, misaligned to 4 bytes) */
+    HOT_ENOMEM = -2, /* host or device allocation failed */
+    HOT_EHIP = -3    /* a HIP call failed; hot_last_hip_error() gives its code */
+};
+
+/* hot_desc.flags */
+#define HOT_REDUCE_SUM 0u  /* g = 1/S,     k = S_loc/(S*|D|): add the outputs of all GPUs      */
+#define HOT_REDUCE_MEAN 1u /* g = 1/S_loc, k = 1/|D|:         average the outputs of all GPUs  */
+
+typedef struct hot_plan hot_plan;
+
+/* Problem statement of Algorithm 2 ("Require" line and loop bounds). */
+typedef struct hot_desc {
+    int64_t n_weights;   /* N >= 1 */
+    int64_t ld;          /* row pitch of eps, w, grad_w in floats, >= N */
+    int32_t s_local;     /* S_loc >= 1: samples on this GPU */
+    int32_t s_total;     /* S >= S_loc: samples over all GPUs */
+    double dataset_size; /* |D| > 0 */
+    int32_t device;      /* HIP device ordinal that owns the buffers and the stream */
+    uint32_t flags;      /* HOT_REDUCE_SUM or HOT_REDUCE_MEAN */
+} hot_desc;
+
+/* Launch geometry of one kernel; a zero field means "library default". */
+typedef struct hot_launch {
+    int32_t grid_blocks; /* upper bound on workgroups (each strides over column tiles), <= 65536 */
+    int32_t chunks;      /* 16-byte column chunks per thread and tile: 1, 2 or 4 */
+    int32_t unroll;      /* sample rows whose loads are issued together: 1, 2 or 4 */
+    int32_t nontemporal; /* bit 0: streamed loads (eps, grad_w) bypass-hinted; bit 1: streamed stores (w) */
+} hot_launch;
+
+#define HOT_KERNEL_FORWARD 0
+#define HOT_KERNEL_BACKWARD 1
+
+/*
+ * Validates the description, fixes g and k, and allocates the plan's own device
+ * scratch (per-workgroup KL partial sums in fp64 and a ticket counter) on
+ * desc->device.  *out is written only on success.
+ */
+int hot_create(hot_plan **out, const hot_desc *desc);
+
+/*
+ * Algorithm 2, reparameterisation and prior-matching lines:
+ *   w[s,i]  = fma(sigma[i], eps[s,i], mu[i])           for s < S_loc, i < N   (fp32, one rounding)
+ *   *kl_out = 1/2 sum_i (sigma_i^2 + mu_i^2 - 1 - 2 ln sigma_i)               (fp64 accumulation)
+ * mu, sigma: [N]; eps: [S_loc, ld] in; w: [S_loc, ld] out; kl_out: one device
+ * double, or NULL to skip the KL term.
+ */
+int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float *eps,
+                float *w, double *kl_out, void *stream);
+
+/*
+ * Algorithm 2, loss / gradient / averaging lines, local share of this GPU.  With
+ * grad_w[s,i] = dL_data,s/dw[s,i] from back-propagation through the network:
+ *   grad_mu[i]    = g * sum_s grad_w[s,i]            + k * mu[i]
+ *   grad_sigma[i] = g * sum_s grad_w[s,i] * eps[s,i] + k * (sigma[i] - 1/sigma[i])
+ * (chain rule through w = mu + sigma*eps and the derivative of the KL line; g and k
+ * as selected by hot_desc.flags).  Sums over s are accumulated in fp64 and rounded to
+ * fp32 once.  grad_w, eps: [S_loc, ld] in; grad_mu, grad_sigma: [N] out, overwritten.
+ */
+int hot_backward(hot_plan *plan, const float *mu, const float *sigma, const float *eps,
+                 const float *grad_w, float *grad_mu, float *grad_sigma, void *stream);
+
+/* Frees the plan's scratch.  NULL is a no-op.  The stream must have finished with the plan. */
+int hot_destroy(hot_plan *plan);
+
+/* Overrides / reads back the launch geometry of one kernel of this plan. */
+int hot_set_launch(hot_plan *plan, int kernel, const hot_launch *cfg);
+int hot_get_launch(const hot_plan *plan, int kernel, hot_launch *cfg);
+
+/* hipError_t of the last failed HIP call made through this plan (0 if none). */
+int hot_last_hip_error(const hot_plan *plan);
+
+/* Static, never NULL. */
+const char *hot_strerror(int code);
+
+/* Smallest pitch >= n_weights that keeps every row 256-byte aligned (multiple of 64 floats). */
+int64_t hot_recommended_ld(int64_t n_weights);
+
+int hot_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* HOT_H */

@@ -1,0 +1,191 @@
+"""Python marshalling for the C ABI of libhot (declared in include/hot.h).
+
+Same names as the C entry points.  This layer checks tensor metadata and passes raw
+device pointers and the current HIP stream; every step of the path runs in the HIP
+kernels.  There is no fallback: if libhot.so is missing or a call fails, an exception
+is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # imported before libhot.so so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhot.so")
+
+HOT_OK, HOT_EINVAL, HOT_ENOMEM, HOT_EHIP = 0, -1, -2, -3
+HOT_REDUCE_SUM, HOT_REDUCE_MEAN = 0, 1
+HOT_KERNEL_FORWARD, HOT_KERNEL_BACKWARD = 0, 1
+
+EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
+           "hot_get_launch", "hot_last_hip_error", "hot_strerror", "hot_recommended_ld",
+           "hot_version")
+
+
+class hot_desc(ctypes.Structure):
+    _fields_ = [("n_weights", ctypes.c_int64), ("ld", ctypes.c_int64),
+                ("s_local", ctypes.c_int32), ("s_total", ctypes.c_int32),
+                ("dataset_size", ctypes.c_double), ("device", ctypes.c_int32),
+                ("flags", ctypes.c_uint32)]
+
+
+class hot_launch(ctypes.Structure):
+    _fields_ = [("grid_blocks", ctypes.c_int32), ("chunks", ctypes.c_int32),
+                ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32)]
+
+
+class HotError(RuntimeError):
+    def __init__(self, code: int, where: str, hip: int = 0):
+        self.code, self.hip = code, hip
+        msg = lib().hot_strerror(code).decode()
+        super().__init__(f"{where}: {msg} (code {code}" + (f", hipError {hip})" if hip else ")"))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Opens libhot.so (built in-tree by paper_2604_04736_amd.build); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built; run __graft_entry__.build() first")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, fp = ctypes.c_void_p, ctypes.c_void_p
+    L.hot_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(hot_desc)]
+    L.hot_forward.argtypes = [vp, fp, fp, fp, fp, vp, vp]
+    L.hot_backward.argtypes = [vp, fp, fp, fp, fp, fp, fp, vp]
+    L.hot_destroy.argtypes = [vp]
+    L.hot_set_launch.argtypes = [vp, ctypes.c_int, ctypes.POINTER(hot_launch)]
+    L.hot_get_launch.argtypes = [vp, ctypes.c_int, ctypes.POINTER(hot_launch)]
+    L.hot_last_hip_error.argtypes = [vp]
+    L.hot_strerror.argtypes = [ctypes.c_int]
+    L.hot_strerror.restype = ctypes.c_char_p
+    L.hot_recommended_ld.argtypes = [ctypes.c_int64]
+    L.hot_recommended_ld.restype = ctypes.c_int64
+    L.hot_version.argtypes = []
+    for name in ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
+                 "hot_get_launch", "hot_last_hip_error", "hot_version"):
+        getattr(L, name).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+class Plan:
+    """Handle of a hot_plan plus the description it was made from."""
+
+    def __init__(self, handle: int, desc: hot_desc):
+        self.handle = ctypes.c_void_p(handle)
+        self.desc = desc
+
+    def __del__(self):
+        try:
+            hot_destroy(self)
+        except Exception:
+            pass
+
+
+def _check(code: int, where: str, plan: Optional[Plan] = None):
+    if code != HOT_OK:
+        hip = lib().hot_last_hip_error(plan.handle) if plan is not None and plan.handle else 0
+        raise HotError(code, where, hip)
+
+
+def hot_version() -> int:
+    return lib().hot_version()
+
+
+def hot_strerror(code: int) -> str:
+    return lib().hot_strerror(code).decode()
+
+
+def hot_recommended_ld(n_weights: int) -> int:
+    return int(lib().hot_recommended_ld(n_weights))
+
+
+def hot_create(n_weights: int, ld: int, s_local: int, s_total: int, dataset_size: float,
+               device: int = 0, flags: int = HOT_REDUCE_SUM) -> Plan:
+    d = hot_desc(n_weights, ld, s_local, s_total, dataset_size, device, flags)
+    out = ctypes.c_void_p()
+    code = lib().hot_create(ctypes.byref(out), ctypes.byref(d))
+    if code != HOT_OK:
+        raise HotError(code, "hot_create")
+    return Plan(out.value, d)
+
+
+def hot_destroy(plan: Plan) -> None:
+    if plan is not None and plan.handle:
+        h, plan.handle = plan.handle, ctypes.c_void_p()
+        code = lib().hot_destroy(h)
+        if code != HOT_OK:
+            raise HotError(code, "hot_destroy")
+
+
+def hot_set_launch(plan: Plan, kernel: int, grid_blocks: int = 0, chunks: int = 0,
+                   unroll: int = 0, nontemporal: int = 0) -> None:
+    cfg = hot_launch(grid_blocks, chunks, unroll, nontemporal)
+    _check(lib().hot_set_launch(plan.handle, kernel, ctypes.byref(cfg)), "hot_set_launch", plan)
+
+
+def hot_get_launch(plan: Plan, kernel: int) -> dict:
+    cfg = hot_launch()
+    _check(lib().hot_get_launch(plan.handle, kernel, ctypes.byref(cfg)), "hot_get_launch", plan)
+    return {k: getattr(cfg, k) for k, _ in hot_launch._fields_}
+
+
+def _vec(t: torch.Tensor, n: int, dev: int, name: str) -> int:
+    if not (t.is_cuda and t.device.index == dev and t.dtype == torch.float32):
+        raise TypeError(f"{name}: need a float32 tensor on cuda:{dev}")
+    if t.dim() != 1 or t.shape[0] != n or t.stride(0) != 1:
+        raise ValueError(f"{name}: need a dense vector of {n} floats, got {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def _mat(t: torch.Tensor, s: int, n: int, ld: int, dev: int, name: str) -> int:
+    if not (t.is_cuda and t.device.index == dev and t.dtype == torch.float32):
+        raise TypeError(f"{name}: need a float32 tensor on cuda:{dev}")
+    if t.dim() != 2 or t.shape[0] != s or not (n <= t.shape[1] <= ld) or t.stride(1) != 1 or \
+            (s > 1 and t.stride(0) != ld):
+        raise ValueError(f"{name}: need [S_loc={s}, >= {n}] rows with pitch {ld}, got "
+                         f"{tuple(t.shape)} strides {t.stride()}")
+    return t.data_ptr()
+
+
+def _stream(dev: int) -> int:
+    return torch.cuda.current_stream(dev).cuda_stream
+
+
+def hot_forward(plan: Plan, mu, sigma, eps, w, kl_out=None) -> None:
+    """w[s,i] = mu[i] + sigma[i]*eps[s,i]; kl_out (one float64 on the device) gets the KL term."""
+    d = plan.desc
+    klp = None
+    if kl_out is not None:
+        if not (kl_out.is_cuda and kl_out.device.index == d.device and kl_out.dtype == torch.float64
+                and kl_out.numel() == 1):
+            raise TypeError("kl_out: need one float64 element on the plan's device")
+        klp = kl_out.data_ptr()
+    code = lib().hot_forward(plan.handle,
+                             _vec(mu, d.n_weights, d.device, "mu"),
+                             _vec(sigma, d.n_weights, d.device, "sigma"),
+                             _mat(eps, d.s_local, d.n_weights, d.ld, d.device, "eps"),
+                             _mat(w, d.s_local, d.n_weights, d.ld, d.device, "w"),
+                             klp, _stream(d.device))
+    _check(code, "hot_forward", plan)
+
+
+def hot_backward(plan: Plan, mu, sigma, eps, grad_w, grad_mu, grad_sigma) -> None:
+    """grad_mu, grad_sigma from the per-sample weight gradients grad_w (see include/hot.h)."""
+    d = plan.desc
+    code = lib().hot_backward(plan.handle,
+                              _vec(mu, d.n_weights, d.device, "mu"),
+                              _vec(sigma, d.n_weights, d.device, "sigma"),
+                              _mat(eps, d.s_local, d.n_weights, d.ld, d.device, "eps"),
+                              _mat(grad_w, d.s_local, d.n_weights, d.ld, d.device, "grad_w"),
+                              _vec(grad_mu, d.n_weights, d.device, "grad_mu"),
+                              _vec(grad_sigma, d.n_weights, d.device, "grad_sigma"),
+                              _stream(d.device))
+    _check(code, "hot_backward", plan)

@@ -1,0 +1,694 @@
+// libhot: HIP kernels and C ABI of the per-GPU Gaussian sample layer of
+// sampling-parallel Bayes-by-Backprop (arxiv 2604.04736, Algorithm 2; Algorithm 1 is
+// the one-GPU case).  Written for gfx950 (MI355X) only.
+//
+// Both kernels are pure streaming work (about 0.2 flop per byte), so the design
+// follows the HBM roofline, not the matrix cores:
+//   * a thread owns 16-byte column chunks; a wave's load instruction covers 1 KiB of
+//     one row, contiguous, so every HBM burst is fully used;
+//   * mu and sigma are loaded once per column and stay in registers across the sample
+//     loop; the rows of several samples are requested together (UNROLL) and a thread
+//     owns several chunks (CHUNKS) so that each wave keeps many 16-byte loads in flight;
+//   * a bounded grid of workgroups strides over the column tiles, so the KL term needs
+//     only one fp64 partial per workgroup; the workgroup that takes the last ticket
+//     adds the partials in index order (deterministic, no floating-point atomics);
+//   * there is no reuse between threads, hence no LDS staging: LDS only carries the
+//     four per-wave partial sums of the KL reduction.
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "hot.h"
+
+namespace {
+
+constexpr int kBlock = 256;             // threads per workgroup = 4 wavefronts of 64
+constexpr int kWaves = kBlock / 64;
+constexpr int kMaxGrid = 65536;         // upper bound on workgroups (size of the partials buffer)
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef f4 f4u __attribute__((aligned(4)));   // same vector, only dword-aligned in memory
+
+// 16-byte load / store of four consecutive floats.  ALIGNED = false still issues one
+// dwordx4 access; the address then only has to be a multiple of 4 bytes.
+template <bool ALIGNED, bool NT>
+__device__ __forceinline__ f4 load4(const float *p)
+{
+    if constexpr (ALIGNED) {
+        const f4 *q = reinterpret_cast<const f4 *>(p);
+        if constexpr (NT) return __builtin_nontemporal_load(q);
+        else return *q;
+    } else {
+        const f4u *q = reinterpret_cast<const f4u *>(p);
+        if constexpr (NT) return __builtin_nontemporal_load(q);
+        else return *q;
+    }
+}
+
+template <bool ALIGNED, bool NT>
+__device__ __forceinline__ void store4(float *p, f4 v)
+{
+    if constexpr (ALIGNED) {
+        f4 *q = reinterpret_cast<f4 *>(p);
+        if constexpr (NT) __builtin_nontemporal_store(v, q);
+        else *q = v;
+    } else {
+        f4u *q = reinterpret_cast<f4u *>(p);
+        if constexpr (NT) __builtin_nontemporal_store(v, q);
+        else *q = v;
+    }
+}
+
+// One addend of the prior-matching line of Algorithm 2 (without the factor 1/2):
+// sigma^2 + mu^2 - 1 - ln sigma^2, with ln sigma^2 taken as 2 ln sigma.  The logarithm
+// is evaluated in fp32, everything else in fp64.
+__device__ __forceinline__ double kl_addend(float m, float sd)
+{
+    const double md = (double)m, sdd = (double)sd;
+    return fma(sdd, sdd, fma(md, md, -1.0)) - 2.0 * (double)logf(sd);
+}
+
+// grad_mu and grad_sigma of one weight from its fp64 sample sums (Algorithm 2, gradient
+// and averaging lines; d KL / d mu = mu, d KL / d sigma = sigma - 1/sigma).
+__device__ __forceinline__ void finish_grad(double sum_g, double sum_ge, float m, float sd,
+                                            double g, double k, float &gm, float &gs)
+{
+    const float inv = 1.0f / sd;
+    gm = (float)fma(g, sum_g, k * (double)m);
+    gs = (float)fma(g, sum_ge, k * ((double)sd - (double)inv));
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
+    return v;   // complete in lane 0
+}
+
+// Sum over the workgroup, complete in thread 0.  Fixed tree, hence deterministic.
+__device__ __forceinline__ double block_sum(double v, double *lds)
+{
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) lds[wave] = v;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < kWaves; ++i) total += lds[i];
+    }
+    return total;
+}
+
+// ---------------------------------------------------------------------------------
+// Forward: reparameterisation line  w[s,i] = mu[i] + sigma[i] * eps[s,i]  for every local
+// sample, fused with the prior-matching line (mu and sigma are in registers anyway).
+// ---------------------------------------------------------------------------------
+template <int CHUNKS, int UNROLL, bool ALIGNED, int NT, bool KL>
+__global__ void __launch_bounds__(kBlock)
+hot_forward_kernel(long n, long ld, int s_loc,
+                   const float *__restrict__ mu, const float *__restrict__ sigma,
+                   const float *__restrict__ eps, float *__restrict__ w,
+                   double *__restrict__ partials, unsigned *__restrict__ ticket,
+                   double *__restrict__ kl_out)
+{
+    constexpr long kTile = (long)kBlock * 4 * CHUNKS;   // columns per tile
+    constexpr long kStep = (long)kBlock * 4;            // columns between a thread's chunks
+    constexpr bool NT_LD = (NT & 1) != 0, NT_ST = (NT & 2) != 0;
+    const long n_tiles = (n + kTile - 1) / kTile;
+    double kl = 0.0;
+
+    for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const long col0 = tile * kTile + (long)threadIdx.x * 4;
+        if ((tile + 1) * kTile <= n) {
+            f4 m[CHUNKS], sd[CHUNKS];
+#pragma unroll
+            for (int c = 0; c < CHUNKS; ++c) {
+                m[c] = load4<ALIGNED, false>(mu + col0 + c * kStep);
+                sd[c] = load4<ALIGNED, false>(sigma + col0 + c * kStep);
+            }
+            int s = 0;
+            for (; s + UNROLL <= s_loc; s += UNROLL) {
+                f4 e[UNROLL][CHUNKS];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                    for (int c = 0; c < CHUNKS; ++c)
+                        e[u][c] = load4<ALIGNED, NT_LD>(eps + (size_t)(s + u) * (size_t)ld + col0 + c * kStep);
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                    for (int c = 0; c < CHUNKS; ++c) {
+                        f4 r;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[c][j], e[u][c][j], m[c][j]);
+                        store4<ALIGNED, NT_ST>(w + (size_t)(s + u) * (size_t)ld + col0 + c * kStep, r);
+                    }
+            }
+            for (; s < s_loc; ++s) {
+                f4 e[CHUNKS];
+#pragma unroll
+                for (int c = 0; c < CHUNKS; ++c)
+                    e[c] = load4<ALIGNED, NT_LD>(eps + (size_t)s * (size_t)ld + col0 + c * kStep);
+#pragma unroll
+                for (int c = 0; c < CHUNKS; ++c) {
+                    f4 r;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[c][j], e[c][j], m[c][j]);
+                    store4<ALIGNED, NT_ST>(w + (size_t)s * (size_t)ld + col0 + c * kStep, r);
+                }
+            }
+            if constexpr (KL) {
+#pragma unroll
+                for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) kl += kl_addend(m[c][j], sd[c][j]);
+            }
+        } else {
+            // ragged last tile: whole chunks as vectors, the final 1..3 columns one by one
+            for (int c = 0; c < CHUNKS; ++c) {
+                const long col = col0 + c * kStep;
+                if (col + 4 <= n) {
+                    const f4 m = load4<ALIGNED, false>(mu + col);
+                    const f4 sd = load4<ALIGNED, false>(sigma + col);
+                    for (int s = 0; s < s_loc; ++s) {
+                        const f4 e = load4<ALIGNED, false>(eps + (size_t)s * (size_t)ld + col);
+                        f4 r;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[j], e[j], m[j]);
+                        store4<ALIGNED, false>(w + (size_t)s * (size_t)ld + col, r);
+                    }
+                    if constexpr (KL) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) kl += kl_addend(m[j], sd[j]);
+                    }
+                } else {
+                    for (long i = col; i < n; ++i) {
+                        const float m = mu[i], sd = sigma[i];
+                        for (int s = 0; s < s_loc; ++s) {
+                            const size_t at = (size_t)s * (size_t)ld + (size_t)i;
+                            w[at] = __builtin_fmaf(sd, eps[at], m);
+                        }
+                        if constexpr (KL) kl += kl_addend(m, sd);
+                    }
+                }
+            }
+        }
+    }
+
+    if constexpr (KL) {
+        __shared__ double lds[kWaves];
+        __shared__ bool last;
+        const double mine = block_sum(kl, lds);
+        if (threadIdx.x == 0) {
+            __hip_atomic_store(&partials[blockIdx.x], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // release our partial, acquire everybody else's (the ticket is the synchronisation point)
+            const unsigned t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            last = (t == gridDim.x - 1);
+        }
+        __syncthreads();
+        if (last) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            double acc = 0.0;
+            for (unsigned j = threadIdx.x; j < gridDim.x; j += kBlock)
+                acc += __hip_atomic_load(&partials[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const double total = block_sum(acc, lds);
+            if (threadIdx.x == 0) {
+                *kl_out = 0.5 * total;
+                __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Backward: column sums over the local samples of grad_w and grad_w * eps, then the
+// KL gradient and the scaling (Algorithm 2, loss / gradient / averaging lines).
+// ---------------------------------------------------------------------------------
+template <int CHUNKS, int UNROLL, bool ALIGNED, int NT>
+__global__ void __launch_bounds__(kBlock)
+hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
+                    const float *__restrict__ mu, const float *__restrict__ sigma,
+                    const float *__restrict__ eps, const float *__restrict__ gw,
+                    float *__restrict__ gmu, float *__restrict__ gsig)
+{
+    constexpr long kTile = (long)kBlock * 4 * CHUNKS;
+    constexpr long kStep = (long)kBlock * 4;
+    constexpr bool NT_LD = (NT & 1) != 0, NT_ST = (NT & 2) != 0;
+    const long n_tiles = (n + kTile - 1) / kTile;
+
+    for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const long col0 = tile * kTile + (long)threadIdx.x * 4;
+        if ((tile + 1) * kTile <= n) {
+            f4 m[CHUNKS], sd[CHUNKS];
+#pragma unroll
+            for (int c = 0; c < CHUNKS; ++c) {
+                m[c] = load4<ALIGNED, false>(mu + col0 + c * kStep);
+                sd[c] = load4<ALIGNED, false>(sigma + col0 + c * kStep);
+            }
+            double sum_g[CHUNKS][4], sum_ge[CHUNKS][4];
+#pragma unroll
+            for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sum_g[c][j] = sum_ge[c][j] = 0.0;
+            int s = 0;
+            for (; s + UNROLL <= s_loc; s += UNROLL) {
+                f4 gv[UNROLL][CHUNKS], ev[UNROLL][CHUNKS];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                    for (int c = 0; c < CHUNKS; ++c) {
+                        const size_t at = (size_t)(s + u) * (size_t)ld + col0 + c * kStep;
+                        gv[u][c] = load4<ALIGNED, NT_LD>(gw + at);
+                        ev[u][c] = load4<ALIGNED, NT_LD>(eps + at);
+                    }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                    for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const double gd = (double)gv[u][c][j];
+                            sum_g[c][j] += gd;
+                            sum_ge[c][j] = fma(gd, (double)ev[u][c][j], sum_ge[c][j]);
+                        }
+            }
+            for (; s < s_loc; ++s) {
+                f4 gv[CHUNKS], ev[CHUNKS];
+#pragma unroll
+                for (int c = 0; c < CHUNKS; ++c) {
+                    const size_t at = (size_t)s * (size_t)ld + col0 + c * kStep;
+                    gv[c] = load4<ALIGNED, NT_LD>(gw + at);
+                    ev[c] = load4<ALIGNED, NT_LD>(eps + at);
+                }
+#pragma unroll
+                for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const double gd = (double)gv[c][j];
+                        sum_g[c][j] += gd;
+                        sum_ge[c][j] = fma(gd, (double)ev[c][j], sum_ge[c][j]);
+                    }
+            }
+#pragma unroll
+            for (int c = 0; c < CHUNKS; ++c) {
+                f4 om, os;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float a, b;
+                    finish_grad(sum_g[c][j], sum_ge[c][j], m[c][j], sd[c][j], g, k, a, b);
+                    om[j] = a;
+                    os[j] = b;
+                }
+                store4<ALIGNED, NT_ST>(gmu + col0 + c * kStep, om);
+                store4<ALIGNED, NT_ST>(gsig + col0 + c * kStep, os);
+            }
+        } else {
+            for (int c = 0; c < CHUNKS; ++c) {
+                const long col = col0 + c * kStep;
+                if (col + 4 <= n) {
+                    const f4 m = load4<ALIGNED, false>(mu + col);
+                    const f4 sd = load4<ALIGNED, false>(sigma + col);
+                    double sum_g[4] = {0.0, 0.0, 0.0, 0.0}, sum_ge[4] = {0.0, 0.0, 0.0, 0.0};
+                    for (int s = 0; s < s_loc; ++s) {
+                        const size_t at = (size_t)s * (size_t)ld + col;
+                        const f4 gv = load4<ALIGNED, false>(gw + at);
+                        const f4 ev = load4<ALIGNED, false>(eps + at);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const double gd = (double)gv[j];
+                            sum_g[j] += gd;
+                            sum_ge[j] = fma(gd, (double)ev[j], sum_ge[j]);
+                        }
+                    }
+                    f4 om, os;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        float a, b;
+                        finish_grad(sum_g[j], sum_ge[j], m[j], sd[j], g, k, a, b);
+                        om[j] = a;
+                        os[j] = b;
+                    }
+                    store4<ALIGNED, false>(gmu + col, om);
+                    store4<ALIGNED, false>(gsig + col, os);
+                } else {
+                    for (long i = col; i < n; ++i) {
+                        double sum_g = 0.0, sum_ge = 0.0;
+                        for (int s = 0; s < s_loc; ++s) {
+                            const size_t at = (size_t)s * (size_t)ld + (size_t)i;
+                            const double gd = (double)gw[at];
+                            sum_g += gd;
+                            sum_ge = fma(gd, (double)eps[at], sum_ge);
+                        }
+                        float a, b;
+                        finish_grad(sum_g, sum_ge, mu[i], sigma[i], g, k, a, b);
+                        gmu[i] = a;
+                        gsig[i] = b;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------------
+
+struct FwdArgs {
+    long n, ld;
+    int s_loc;
+    const float *mu, *sigma, *eps;
+    float *w;
+    double *partials;
+    unsigned *ticket;
+    double *kl_out;
+    dim3 grid;
+    hipStream_t stream;
+};
+
+struct BwdArgs {
+    long n, ld;
+    int s_loc;
+    double g, k;
+    const float *mu, *sigma, *eps, *gw;
+    float *gmu, *gsig;
+    dim3 grid;
+    hipStream_t stream;
+};
+
+template <int CH, int U, bool AL, int NT, bool KL>
+void fwd_go(const FwdArgs &a)
+{
+    hot_forward_kernel<CH, U, AL, NT, KL><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+        a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out);
+}
+template <int CH, int U, bool AL, int NT>
+void fwd_kl(const FwdArgs &a)
+{
+    if (a.kl_out) fwd_go<CH, U, AL, NT, true>(a);
+    else fwd_go<CH, U, AL, NT, false>(a);
+}
+template <int CH, int U, bool AL>
+void fwd_nt(int nt, const FwdArgs &a)
+{
+    switch (nt & 3) {
+    case 0: fwd_kl<CH, U, AL, 0>(a); break;
+    case 1: fwd_kl<CH, U, AL, 1>(a); break;
+    case 2: fwd_kl<CH, U, AL, 2>(a); break;
+    default: fwd_kl<CH, U, AL, 3>(a); break;
+    }
+}
+template <int CH, int U>
+void fwd_al(bool al, int nt, const FwdArgs &a)
+{
+    if (al) fwd_nt<CH, U, true>(nt, a);
+    else fwd_nt<CH, U, false>(nt, a);
+}
+template <int CH>
+void fwd_u(int u, bool al, int nt, const FwdArgs &a)
+{
+    if (u >= 4) fwd_al<CH, 4>(al, nt, a);
+    else if (u >= 2) fwd_al<CH, 2>(al, nt, a);
+    else fwd_al<CH, 1>(al, nt, a);
+}
+void fwd_dispatch(int ch, int u, bool al, int nt, const FwdArgs &a)
+{
+    if (ch >= 4) fwd_u<4>(u, al, nt, a);
+    else if (ch >= 2) fwd_u<2>(u, al, nt, a);
+    else fwd_u<1>(u, al, nt, a);
+}
+
+template <int CH, int U, bool AL, int NT>
+void bwd_go(const BwdArgs &a)
+{
+    hot_backward_kernel<CH, U, AL, NT><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+        a.n, a.ld, a.s_loc, a.g, a.k, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig);
+}
+template <int CH, int U, bool AL>
+void bwd_nt(int nt, const BwdArgs &a)
+{
+    switch (nt & 3) {
+    case 0: bwd_go<CH, U, AL, 0>(a); break;
+    case 1: bwd_go<CH, U, AL, 1>(a); break;
+    case 2: bwd_go<CH, U, AL, 2>(a); break;
+    default: bwd_go<CH, U, AL, 3>(a); break;
+    }
+}
+template <int CH, int U>
+void bwd_al(bool al, int nt, const BwdArgs &a)
+{
+    if (al) bwd_nt<CH, U, true>(nt, a);
+    else bwd_nt<CH, U, false>(nt, a);
+}
+template <int CH>
+void bwd_u(int u, bool al, int nt, const BwdArgs &a)
+{
+    if (u >= 4) bwd_al<CH, 4>(al, nt, a);
+    else if (u >= 2) bwd_al<CH, 2>(al, nt, a);
+    else bwd_al<CH, 1>(al, nt, a);
+}
+void bwd_dispatch(int ch, int u, bool al, int nt, const BwdArgs &a)
+{
+    if (ch >= 4) bwd_u<4>(u, al, nt, a);
+    else if (ch >= 2) bwd_u<2>(u, al, nt, a);
+    else bwd_u<1>(u, al, nt, a);
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+// Makes desc.device current for the lifetime of the object.
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    hipError_t err = hipSuccess;
+    explicit DeviceGuard(int device)
+    {
+        err = hipGetDevice(&prev);
+        if (err == hipSuccess && prev != device) {
+            err = hipSetDevice(device);
+            switched = (err == hipSuccess);
+        }
+    }
+    ~DeviceGuard()
+    {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+}  // namespace
+
+struct hot_plan {
+    hot_desc d;
+    double g, k;
+    double *partials;
+    unsigned *ticket;
+    hot_launch cfg[2];
+    int last_hip;
+};
+
+namespace {
+
+int fail_hip(hot_plan *p, hipError_t e)
+{
+    if (p) p->last_hip = (int)e;
+    return HOT_EHIP;
+}
+
+int pick_unroll(int want, int s_loc)
+{
+    int u = want >= 4 ? 4 : (want >= 2 ? 2 : 1);
+    while (u > 1 && u > s_loc) u >>= 1;
+    return u;
+}
+
+bool valid_launch(const hot_launch &c)
+{
+    auto one_of = [](int v) { return v == 0 || v == 1 || v == 2 || v == 4; };
+    return c.grid_blocks >= 0 && c.grid_blocks <= kMaxGrid && one_of(c.chunks) && one_of(c.unroll) &&
+           c.nontemporal >= 0 && c.nontemporal <= 3;
+}
+
+long tiles_of(long n, int chunks) { return (n + (long)kBlock * 4 * chunks - 1) / ((long)kBlock * 4 * chunks); }
+
+}  // namespace
+
+extern "C" {
+
+int hot_version(void) { return HOT_VERSION; }
+
+const char *hot_strerror(int code)
+{
+    switch (code) {
+    case HOT_OK: return "success";
+    case HOT_EINVAL: return "invalid argument";
+    case HOT_ENOMEM: return "out of memory";
+    case HOT_EHIP: return "HIP runtime error (see hot_last_hip_error)";
+    default: return "unknown error code";
+    }
+}
+
+int64_t hot_recommended_ld(int64_t n_weights)
+{
+    if (n_weights < 1) return HOT_EINVAL;
+    return (n_weights + 63) / 64 * 64;
+}
+
+int hot_create(hot_plan **out, const hot_desc *desc)
+{
+    if (!out || !desc) return HOT_EINVAL;
+    const hot_desc &d = *desc;
+    if (d.n_weights < 1 || d.ld < d.n_weights || d.s_local < 1 || d.s_total < d.s_local) return HOT_EINVAL;
+    if (!(d.dataset_size > 0.0) || !(d.dataset_size < 1.0 / 0.0)) return HOT_EINVAL;
+    if (d.flags != HOT_REDUCE_SUM && d.flags != HOT_REDUCE_MEAN) return HOT_EINVAL;
+    // element offsets (s_local - 1) * ld + n_weights must fit in 63 bits
+    if (d.ld > (INT64_MAX / 4) / d.s_local) return HOT_EINVAL;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess) return HOT_EHIP;
+    if (d.device < 0 || d.device >= n_dev) return HOT_EINVAL;
+
+    hot_plan *p = new (std::nothrow) hot_plan();
+    if (!p) return HOT_ENOMEM;
+    p->d = d;
+    if (d.flags == HOT_REDUCE_MEAN) {
+        p->g = 1.0 / (double)d.s_local;
+        p->k = 1.0 / d.dataset_size;
+    } else {
+        p->g = 1.0 / (double)d.s_total;
+        p->k = (double)d.s_local / ((double)d.s_total * d.dataset_size);
+    }
+    p->partials = nullptr;
+    p->ticket = nullptr;
+    p->last_hip = 0;
+
+    DeviceGuard guard(d.device);
+    hipError_t e = guard.err;
+    int cus = 0;
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d.device);
+    if (e == hipSuccess) e = hipMalloc((void **)&p->partials, sizeof(double) * kMaxGrid);
+    if (e == hipSuccess) e = hipMalloc((void **)&p->ticket, 256);
+    if (e == hipSuccess) e = hipMemset(p->ticket, 0, 256);
+    if (e != hipSuccess) {
+        const bool oom = (e == hipErrorOutOfMemory);
+        if (p->partials) (void)hipFree(p->partials);
+        if (p->ticket) (void)hipFree(p->ticket);
+        delete p;
+        return oom ? HOT_ENOMEM : HOT_EHIP;
+    }
+    if (cus < 1) cus = 256;
+    int grid = cus * 8;
+    if (grid > kMaxGrid) grid = kMaxGrid;
+    for (int kn = 0; kn < 2; ++kn) {
+        p->cfg[kn].grid_blocks = grid;
+        p->cfg[kn].chunks = 2;
+        p->cfg[kn].unroll = pick_unroll(4, d.s_local);
+        p->cfg[kn].nontemporal = 0;
+    }
+    *out = p;
+    return HOT_OK;
+}
+
+int hot_destroy(hot_plan *plan)
+{
+    if (!plan) return HOT_OK;
+    int rc = HOT_OK;
+    {
+        DeviceGuard guard(plan->d.device);
+        if (plan->partials && hipFree(plan->partials) != hipSuccess) rc = HOT_EHIP;
+        if (plan->ticket && hipFree(plan->ticket) != hipSuccess) rc = HOT_EHIP;
+    }
+    delete plan;
+    return rc;
+}
+
+int hot_set_launch(hot_plan *plan, int kernel, const hot_launch *cfg)
+{
+    if (!plan || !cfg || (kernel != HOT_KERNEL_FORWARD && kernel != HOT_KERNEL_BACKWARD)) return HOT_EINVAL;
+    if (!valid_launch(*cfg)) return HOT_EINVAL;
+    hot_launch &c = plan->cfg[kernel];
+    if (cfg->grid_blocks) c.grid_blocks = cfg->grid_blocks;
+    if (cfg->chunks) c.chunks = cfg->chunks;
+    if (cfg->unroll) c.unroll = pick_unroll(cfg->unroll, plan->d.s_local);
+    c.nontemporal = cfg->nontemporal;
+    return HOT_OK;
+}
+
+int hot_get_launch(const hot_plan *plan, int kernel, hot_launch *cfg)
+{
+    if (!plan || !cfg || (kernel != HOT_KERNEL_FORWARD && kernel != HOT_KERNEL_BACKWARD)) return HOT_EINVAL;
+    *cfg = plan->cfg[kernel];
+    return HOT_OK;
+}
+
+int hot_last_hip_error(const hot_plan *plan) { return plan ? plan->last_hip : 0; }
+
+int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float *eps, float *w,
+                double *kl_out, void *stream)
+{
+    if (!plan || !mu || !sigma || !eps || !w) return HOT_EINVAL;
+    if (!aligned4(mu) || !aligned4(sigma) || !aligned4(eps) || !aligned4(w)) return HOT_EINVAL;
+    if (kl_out && (reinterpret_cast<uintptr_t>(kl_out) & 7u)) return HOT_EINVAL;
+    const hot_desc &d = plan->d;
+    const hot_launch &c = plan->cfg[HOT_KERNEL_FORWARD];
+    const bool al = aligned16(mu) && aligned16(sigma) && aligned16(eps) && aligned16(w) && (d.ld % 4 == 0);
+
+    FwdArgs a;
+    a.n = d.n_weights;
+    a.ld = d.ld;
+    a.s_loc = d.s_local;
+    a.mu = mu;
+    a.sigma = sigma;
+    a.eps = eps;
+    a.w = w;
+    a.partials = plan->partials;
+    a.ticket = plan->ticket;
+    a.kl_out = kl_out;
+    long tiles = tiles_of(d.n_weights, c.chunks);
+    a.grid = dim3((unsigned)(tiles < c.grid_blocks ? tiles : c.grid_blocks));
+    a.stream = static_cast<hipStream_t>(stream);
+
+    DeviceGuard guard(d.device);
+    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
+    fwd_dispatch(c.chunks, c.unroll, al, c.nontemporal, a);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
+}
+
+int hot_backward(hot_plan *plan, const float *mu, const float *sigma, const float *eps,
+                 const float *grad_w, float *grad_mu, float *grad_sigma, void *stream)
+{
+    if (!plan || !mu || !sigma || !eps || !grad_w || !grad_mu || !grad_sigma) return HOT_EINVAL;
+    if (!aligned4(mu) || !aligned4(sigma) || !aligned4(eps) || !aligned4(grad_w) || !aligned4(grad_mu) ||
+        !aligned4(grad_sigma))
+        return HOT_EINVAL;
+    const hot_desc &d = plan->d;
+    const hot_launch &c = plan->cfg[HOT_KERNEL_BACKWARD];
+    const bool al = aligned16(mu) && aligned16(sigma) && aligned16(eps) && aligned16(grad_w) &&
+                    aligned16(grad_mu) && aligned16(grad_sigma) && (d.ld % 4 == 0);
+
+    BwdArgs a;
+    a.n = d.n_weights;
+    a.ld = d.ld;
+    a.s_loc = d.s_local;
+    a.g = plan->g;
+    a.k = plan->k;
+    a.mu = mu;
+    a.sigma = sigma;
+    a.eps = eps;
+    a.gw = grad_w;
+    a.gmu = grad_mu;
+    a.gsig = grad_sigma;
+    long tiles = tiles_of(d.n_weights, c.chunks);
+    a.grid = dim3((unsigned)(tiles < c.grid_blocks ? tiles : c.grid_blocks));
+    a.stream = static_cast<hipStream_t>(stream);
+
+    DeviceGuard guard(d.device);
+    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
+    bwd_dispatch(c.chunks, c.unroll, al, c.nontemporal, a);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
+}
+
+}  // extern "C"

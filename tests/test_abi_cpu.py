@@ -1,0 +1,74 @@
+"""No-GPU checks of the boundary: the library loads, exports every symbol the header
+declares, and its host-only entry points behave as documented."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "hot.h")
+
+
+@pytest.fixture(scope="module")
+def hot():
+    from paper_2604_04736_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2604_04736_amd import build
+        build.build_libhot()
+    return binding
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hot_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(hot):
+    names = _declared_symbols()
+    assert set(names) == set(hot.EXPORTS), names
+    L = hot.lib()
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def test_host_only_entry_points(hot):
+    assert hot.hot_version() == 100
+    assert hot.hot_strerror(0) == "success"
+    assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
+    assert hot.hot_strerror(-99) == "unknown error code"
+    assert hot.hot_recommended_ld(1) == 64
+    assert hot.hot_recommended_ld(64) == 64
+    assert hot.hot_recommended_ld(32_024) == 32_064
+    assert hot.hot_recommended_ld(2_693_578) == 2_693_632
+    assert hot.hot_recommended_ld(0) == hot.HOT_EINVAL
+
+
+def test_struct_layout_matches_header(hot):
+    # hot_desc: int64, int64, int32, int32, double, int32, uint32 -> 40 bytes, natural alignment
+    assert ctypes.sizeof(hot.hot_desc) == 40
+    assert hot.hot_desc.dataset_size.offset == 24 and hot.hot_desc.flags.offset == 36
+    assert ctypes.sizeof(hot.hot_launch) == 16
+
+
+def test_null_arguments_are_rejected_without_a_gpu(hot):
+    L = hot.lib()
+    assert L.hot_create(None, None) == hot.HOT_EINVAL
+    assert L.hot_destroy(None) == hot.HOT_OK
+    assert L.hot_forward(None, None, None, None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_backward(None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_set_launch(None, 0, None) == hot.HOT_EINVAL
+    assert L.hot_get_launch(None, 0, None) == hot.HOT_EINVAL
+    assert L.hot_last_hip_error(None) == 0
+    out = ctypes.c_void_p()
+    for bad in [hot.hot_desc(0, 0, 1, 1, 1.0, 0, 0),        # N < 1
+                hot.hot_desc(8, 7, 1, 1, 1.0, 0, 0),        # ld < N
+                hot.hot_desc(8, 8, 0, 1, 1.0, 0, 0),        # S_loc < 1
+                hot.hot_desc(8, 8, 3, 2, 1.0, 0, 0),        # S < S_loc
+                hot.hot_desc(8, 8, 1, 1, 0.0, 0, 0),        # |D| <= 0
+                hot.hot_desc(8, 8, 1, 1, float("nan"), 0, 0),
+                hot.hot_desc(8, 8, 1, 1, float("inf"), 0, 0),
+                hot.hot_desc(8, 8, 1, 1, 1.0, 0, 7)]:       # unknown flag
+        assert L.hot_create(ctypes.byref(out), ctypes.byref(bad)) == hot.HOT_EINVAL
+        assert not out.value

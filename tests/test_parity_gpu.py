@@ -1,0 +1,269 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs, element by element (see parity_util for the tolerances)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_04736_amd import workloads as W
+
+import parity_util as P
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hot():
+    from paper_2604_04736_amd import binding
+    binding.lib()          # a missing library is an error, never a skip
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return binding
+
+
+DEV = "cuda:0"
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ whole small configs
+
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_config_full_elementwise(oracle, hot, name):
+    wl = W.CONFIGS[name]
+    _say("case", name, wl)
+    x = W.make_inputs(wl, DEV)
+    rep = P.check_all(oracle, hot, x, wl)
+    _say(name, rep)
+
+
+# ------------------------------------------------------------------ scaled C3 / C5, launch shapes
+
+LAUNCHES = [dict(), dict(chunks=1, unroll=1), dict(chunks=1, unroll=4, nontemporal=3),
+            dict(chunks=2, unroll=2, nontemporal=1), dict(chunks=4, unroll=4, nontemporal=2),
+            dict(chunks=4, unroll=1, grid_blocks=7), dict(chunks=2, unroll=4, grid_blocks=65536)]
+
+
+@pytest.mark.parametrize("launch", LAUNCHES, ids=lambda d: "-".join(f"{k}{v}" for k, v in d.items()) or "default")
+def test_scaled_c3_several_tiles_and_ragged_tail(oracle, hot, launch):
+    # 16 samples, packed rows, N spans many tiles and ends 1 column past a multiple of 4
+    wl = W.scaled(W.CONFIGS["C3"], 300_001)
+    _say("case scaled C3", wl.n_weights, launch)
+    x = W.make_inputs(wl, DEV)
+    _say(P.check_all(oracle, hot, x, wl, launch=launch))
+
+
+@pytest.mark.parametrize("offset", [0, 1, 3])
+@pytest.mark.parametrize("launch", [dict(), dict(chunks=4, unroll=4, nontemporal=3), dict(chunks=1, unroll=2)],
+                         ids=["default", "c4u4nt3", "c1u2"])
+def test_scaled_c5_adversarial_unaligned(oracle, hot, launch, offset):
+    wl = W.scaled(W.CONFIGS["C5"], 400_003)
+    _say("case scaled C5", wl.n_weights, launch, "offset", offset)
+    x = W.make_inputs(wl, DEV, base_offset=offset)
+    assert x["eps"].data_ptr() % 16 == 4 * offset
+    _say(P.check_all(oracle, hot, x, wl, launch=launch))
+
+
+# ------------------------------------------------------------------ edge sizes
+
+def _random_case(n, ld, s, seed, dev=DEV):
+    g = torch.Generator().manual_seed(seed)
+    mu = torch.randn(n, generator=g)
+    sigma = torch.exp(torch.randn(n, generator=g) * 2.0)
+    eps = torch.full((s, ld), float("nan"))
+    G = torch.full((s, ld), float("nan"))
+    eps[:, :n] = torch.randn(s, n, generator=g)
+    G[:, :n] = torch.randn(s, n, generator=g) * 3.0
+    return {k: v.to(dev) for k, v in dict(mu=mu, sigma=sigma, eps=eps, G=G).items()}
+
+
+class _WL:
+    def __init__(self, n, ld, s_local, s_total, dsize):
+        self.n_weights, self.ld, self.s_local, self.s_total, self.dataset_size = n, ld, s_local, s_total, dsize
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 7, 255, 1023, 1024, 1025, 2047, 2048, 2051, 4097, 8191])
+def test_edge_sizes_packed_and_padded(oracle, hot, n):
+    for s, s_total in [(1, 1), (3, 7), (5, 5), (17, 34)]:
+        for ld in sorted({n, n + 1, hot.hot_recommended_ld(n)}):
+            _say("case edge n", n, "ld", ld, "s", s)
+            x = _random_case(n, ld, s, seed=n * 131 + s)
+            wl = _WL(n, ld, s, s_total, 321.0)
+            P.check_all(oracle, hot, x, wl)
+            P.check_all(oracle, hot, x, wl, launch=dict(chunks=1, unroll=1, grid_blocks=1), flags=hot.HOT_REDUCE_MEAN)
+
+
+def test_mean_convention_and_sharding_over_plans(oracle, hot):
+    # Algorithm 2 on P groups of samples summed equals Algorithm 1 on all samples
+    n, s, dsize = 70_001, 16, 45000.0
+    x = _random_case(n, n, s, seed=5)
+    wl = _WL(n, n, s, s, dsize)
+    _, _, gmu_all, gsig_all = P.run_hip(hot, x, n, n, s, s, dsize)
+    h = P.host(x)
+    P.check_grads(oracle, h, gmu_all.cpu().numpy(), gsig_all.cpu().numpy(), n, s, dsize)
+    for parts in (2, 4, 8, 16):
+        per = s // parts
+        acc_mu = torch.zeros(n, dtype=torch.float64, device=DEV)
+        acc_sg = torch.zeros(n, dtype=torch.float64, device=DEV)
+        avg_mu = torch.zeros_like(acc_mu)
+        avg_sg = torch.zeros_like(acc_sg)
+        for p in range(parts):
+            xp = dict(mu=x["mu"], sigma=x["sigma"], eps=x["eps"][p * per:(p + 1) * per],
+                      G=x["G"][p * per:(p + 1) * per])
+            _, _, a, b = P.run_hip(hot, xp, n, n, per, s, dsize)
+            acc_mu += a.double()
+            acc_sg += b.double()
+            _, _, a, b = P.run_hip(hot, xp, n, n, per, s, dsize, flags=hot.HOT_REDUCE_MEAN)
+            avg_mu += a.double() / parts
+            avg_sg += b.double() / parts
+        # each part was rounded to fp32 once: compare the recombined result with the oracle
+        # under a tolerance widened by the number of parts
+        for got_mu, got_sg in ((acc_mu, acc_sg), (avg_mu, avg_sg)):
+            gm64, gs64 = oracle.grad(h["mu"], h["sigma"], h["eps"], h["G"], s, dsize)
+            g, k = P.gk(s, s, dsize)
+            G64 = h["G"].astype(np.float64)
+            e64 = h["eps"].astype(np.float64)
+            tol_mu = P.RTOL * (g * np.abs(G64).sum(0) + k * np.abs(h["mu"]))
+            tol_sg = P.RTOL * (g * np.abs(G64 * e64).sum(0) + k * (h["sigma"] + 1.0 / h["sigma"]))
+            assert np.all(np.abs(got_mu.cpu().numpy() - gm64) <= tol_mu)
+            assert np.all(np.abs(got_sg.cpu().numpy() - gs64) <= tol_sg)
+
+
+def test_kl_optional_and_outputs_independent_of_it(hot):
+    n, s = 10_000, 3
+    x = _random_case(n, n, s, seed=9)
+    w1, kl1, _, _ = P.run_hip(hot, x, n, n, s, s, 10.0, want_kl=True)
+    w2, kl2, _, _ = P.run_hip(hot, x, n, n, s, s, 10.0, want_kl=False)
+    assert kl2 is None and torch.equal(w1, w2) and kl1.item() > 0
+
+
+def test_bitwise_determinism_and_ticket_reset(hot):
+    wl = W.scaled(W.CONFIGS["C3"], 1_000_003)
+    x = W.make_inputs(wl, DEV)
+    n = wl.n_weights
+    plan = hot.hot_create(n, wl.ld, wl.s_local, wl.s_total, wl.dataset_size, 0)
+    outs = []
+    for rep in range(4):
+        w = torch.empty_like(x["eps"])
+        kl = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+        gmu, gsig = torch.empty_like(x["mu"]), torch.empty_like(x["mu"])
+        hot.hot_forward(plan, x["mu"], x["sigma"], x["eps"], w, kl)
+        hot.hot_backward(plan, x["mu"], x["sigma"], x["eps"], x["G"], gmu, gsig)
+        torch.cuda.synchronize()
+        outs.append((w, kl, gmu, gsig))
+    hot.hot_destroy(plan)
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            assert torch.equal(a, b)
+
+
+def test_ieee_propagation_for_sigma_outside_the_domain(oracle, hot):
+    n, s = 2051, 2
+    x = _random_case(n, n, s, seed=11)
+    x["sigma"][17] = 0.0
+    w, kl, gmu, gsig = P.run_hip(hot, x, n, n, s, s, 10.0)
+    assert kl.item() == float("inf") and gsig[17].item() == float("-inf")
+    assert torch.isfinite(gmu).all() and torch.isfinite(w).all()
+    assert torch.isfinite(gsig).sum().item() == n - 1
+    h = P.host(x)
+    assert oracle.kl(h["mu"], h["sigma"]) == float("inf")
+    x["sigma"][17] = -1.0
+    _, kl, _, _ = P.run_hip(hot, x, n, n, s, s, 10.0)
+    assert np.isnan(kl.item()) and np.isnan(oracle.kl(P.host(x)["mu"], P.host(x)["sigma"]))
+
+
+def test_cancellation_in_w_is_correctly_rounded(oracle, hot):
+    # mu = -sigma*eps up to one rounding: a separate multiply and add would lose all digits
+    n, s = 4099, 2
+    g = torch.Generator().manual_seed(3)
+    sigma = torch.rand(n, generator=g) + 0.5
+    eps = torch.randn(s, n, generator=g)
+    mu = -(sigma * eps[0])
+    x = {k: v.to(DEV) for k, v in dict(mu=mu, sigma=sigma, eps=eps, G=torch.ones(s, n)).items()}
+    w, _, _, _ = P.run_hip(hot, x, n, n, s, s, 10.0)
+    P.check_w(oracle, P.host(x), w.cpu().numpy(), n)
+
+
+def test_errors_from_the_c_abi(hot):
+    L = hot.lib()
+    with pytest.raises(hot.HotError):
+        hot.hot_create(8, 8, 1, 1, 1.0, device=99)
+    plan = hot.hot_create(1024, 1024, 2, 2, 1.0, 0)
+    t = torch.zeros(4096, device=DEV)
+    p = ctypes.c_void_p(t.data_ptr())
+    odd = ctypes.c_void_p(t.data_ptr() + 2)
+    assert L.hot_forward(plan.handle, None, p, p, p, None, None) == hot.HOT_EINVAL
+    assert L.hot_forward(plan.handle, odd, p, p, p, None, None) == hot.HOT_EINVAL
+    assert L.hot_forward(plan.handle, p, p, p, p, ctypes.c_void_p(t.data_ptr() + 4), None) == hot.HOT_EINVAL
+    assert L.hot_backward(plan.handle, p, p, p, p, p, None, None) == hot.HOT_EINVAL
+    assert L.hot_backward(plan.handle, p, p, p, p, p, odd, None) == hot.HOT_EINVAL
+    with pytest.raises(hot.HotError):
+        hot.hot_set_launch(plan, hot.HOT_KERNEL_FORWARD, chunks=3)
+    with pytest.raises(hot.HotError):
+        hot.hot_set_launch(plan, 5, chunks=2)
+    with pytest.raises(hot.HotError):
+        hot.hot_set_launch(plan, hot.HOT_KERNEL_FORWARD, grid_blocks=1 << 20)
+    with pytest.raises(ValueError):
+        hot.hot_forward(plan, t[:1000], t[:1024], t.view(2, 2048)[:, :1024], t.view(2, 2048)[:, :1024])
+    with pytest.raises(TypeError):
+        hot.hot_forward(plan, t[:1024].cpu(), t[:1024], t[:2048].view(2, 1024), t[:2048].view(2, 1024))
+    cfg = hot.hot_get_launch(plan, hot.HOT_KERNEL_BACKWARD)
+    assert cfg["unroll"] == 2 and cfg["chunks"] in (1, 2, 4) and cfg["grid_blocks"] > 0
+    hot.hot_destroy(plan)
+    hot.hot_destroy(plan)      # second destroy of the wrapper is a no-op
+
+
+def test_runs_on_a_side_stream(oracle, hot):
+    wl = W.scaled(W.CONFIGS["C2"], 100_000)
+    x = W.make_inputs(wl, DEV)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        rep = P.check_all(oracle, hot, x, wl)
+    _say(rep)
+
+
+# ------------------------------------------------------------------ full sizes, bench launch shape
+
+def _column_blocks(n, rng, count, width):
+    blocks = [(0, min(width, n)), (max(0, n - width - 3), n)]
+    for _ in range(count):
+        a = int(rng.integers(0, max(1, n - width)))
+        blocks.append((a, min(n, a + width)))
+    return blocks
+
+
+@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
+def test_full_size_sampled_blocks_and_whole_kl(oracle, hot, name):
+    """At the benchmark's sizes and default launch shape: the KL term over all weights, and
+    w, grad_mu, grad_sigma on contiguous column blocks (first, last with the ragged tail, and
+    random ones) that the oracle recomputes from the same bytes."""
+    wl = W.CONFIGS[name]
+    _say("case full", name, wl.n_weights, wl.s_local)
+    x = W.make_inputs(wl, DEV)
+    n, ld = wl.n_weights, wl.ld
+    w, kl, gmu, gsig = P.run_hip(hot, x, n, ld, wl.s_local, wl.s_total, wl.dataset_size)
+    _say("ran", name)
+    h_mu, h_sigma = x["mu"].cpu().numpy(), x["sigma"].cpu().numpy()
+    rel = P.check_kl(oracle, {"mu": h_mu, "sigma": h_sigma}, kl.item())
+    _say("KL ok", kl.item(), rel)
+    rng = np.random.default_rng(wl.seed)
+    for a, b in _column_blocks(n, rng, 24, 40_000):
+        h = {"mu": h_mu[a:b].copy(), "sigma": h_sigma[a:b].copy(),
+             "eps": np.ascontiguousarray(x["eps"][:, a:b].cpu().numpy()),
+             "G": np.ascontiguousarray(x["G"][:, a:b].cpu().numpy())}
+        P.check_w(oracle, h, w[:, a:b].cpu().numpy(), b - a)
+        P.check_grads(oracle, h, gmu[a:b].cpu().numpy(), gsig[a:b].cpu().numpy(), b - a,
+                      wl.s_total, wl.dataset_size)
+    # properties that hold at any size: every output written, finite, and w rows differ
+    assert torch.isfinite(w).all() and torch.isfinite(gmu).all() and torch.isfinite(gsig).all()
+
+
+@pytest.mark.parametrize("name", ["C3", "C5"])
+def test_full_size_every_element(oracle, hot, name):
+    wl = W.CONFIGS[name]
+    _say("case every element", name)
+    x = W.make_inputs(wl, DEV)
+    _say(P.check_all(oracle, hot, x, wl))

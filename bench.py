@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the libhot hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: hot_forward
+(reparameterisation + KL term) followed by hot_backward (sample-gradient reduction),
+i.e. what one GPU does per training step of Algorithm 2 around the network's own
+forward/backward.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: whole-job items/s (an item is one (sample, weight) pair), the
+roofline of the dominant kernel from HIP-event timings taken inside the timed region,
+and the CPU oracle timed on the host as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+METRIC = "hot-path items/sec on 1 MI355X + % of HBM-BW or MFMA roofline"
+
+
+def algorithmic_bytes(n: int, s: int):
+    """Bytes the method must move per launch (fp32, eps supplied as an array)."""
+    fwd = 4 * (s * n + 2 * n) + 4 * s * n + 8          # eps, mu, sigma in; w, KL out
+    bwd = 4 * (2 * s * n + 2 * n) + 4 * 2 * n          # G, eps, mu, sigma in; grad_mu, grad_sigma out
+    return fwd, bwd
+
+
+def time_steps(hot, torch, wl, x, steps: int, warmup: int):
+    dev = x["mu"].device
+    w = torch.empty_like(x["eps"])
+    kl = torch.zeros(1, dtype=torch.float64, device=dev)
+    gmu = torch.empty_like(x["mu"])
+    gsig = torch.empty_like(x["mu"])
+    plan = hot.hot_create(wl.n_weights, wl.ld, wl.s_local, wl.s_total, wl.dataset_size, dev.index or 0)
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        hot.hot_forward(plan, x["mu"], x["sigma"], x["eps"], w, kl)
+        if events is not None:
+            events[1].record()
+        hot.hot_backward(plan, x["mu"], x["sigma"], x["eps"], x["G"], gmu, gsig)
+        if events is not None:
+            events[2].record()
+
+    for _ in range(warmup):
+        step()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(ev[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    launch = {"forward": hot.hot_get_launch(plan, hot.HOT_KERNEL_FORWARD),
+              "backward": hot.hot_get_launch(plan, hot.HOT_KERNEL_BACKWARD)}
+    hot.hot_destroy(plan)
+    return {"wall_s": wall, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "launch": launch,
+            "out": {"w": w, "kl": kl, "gmu": gmu, "gsig": gsig}}
+
+
+def verify_sampled(oracle, np, wl, x, out, blocks: int = 6, width: int = 20_000) -> bool:
+    """Checks the timed buffers on a few column blocks against the oracle (same tolerances as the tests)."""
+    n = wl.n_weights
+    rng = np.random.default_rng(wl.seed)
+    spans = [(0, min(width, n)), (max(0, n - width), n)]
+    spans += [(a, min(n, a + width)) for a in rng.integers(0, max(1, n - width), size=blocks)]
+    g = 1.0 / wl.s_total
+    k = wl.s_local / (wl.s_total * wl.dataset_size)
+    for a, b in spans:
+        a, b = int(a), int(b)
+        mu = x["mu"][a:b].cpu().numpy()
+        sg = x["sigma"][a:b].cpu().numpy()
+        eps = np.ascontiguousarray(x["eps"][:, a:b].cpu().numpy())
+        G = np.ascontiguousarray(x["G"][:, a:b].cpu().numpy())
+        w64 = oracle.reparam(mu, sg, eps)
+        if not np.all(np.abs(out["w"][:, a:b].cpu().numpy() - w64) <= 1e-5 * np.abs(w64)):
+            return False
+        gm64, gs64 = oracle.grad(mu, sg, eps, G, wl.s_total, wl.dataset_size)
+        G64, e64, m64, s64 = G.astype(np.float64), eps.astype(np.float64), mu.astype(np.float64), sg.astype(np.float64)
+        if not np.all(np.abs(out["gmu"][a:b].cpu().numpy() - gm64) <= 1e-5 * (g * np.abs(G64).sum(0) + k * np.abs(m64))):
+            return False
+        if not np.all(np.abs(out["gsig"][a:b].cpu().numpy() - gs64)
+                      <= 1e-5 * (g * np.abs(G64 * e64).sum(0) + k * (s64 + 1 / s64))):
+            return False
+    return True
+
+
+def cpu_baseline(oracle, np, wl, x, max_weights: int):
+    """The oracle as it stands, timed on the host cores over the first max_weights weights."""
+    n = min(wl.n_weights, max_weights)
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    cores = max(1, min(cores, 16))
+    h = {"mu": x["mu"][:n].cpu().numpy(), "sigma": x["sigma"][:n].cpu().numpy(),
+         "eps": np.ascontiguousarray(x["eps"][:, :n].cpu().numpy()),
+         "G": np.ascontiguousarray(x["G"][:, :n].cpu().numpy())}
+    used = oracle.threads(cores)
+    t0 = time.perf_counter()
+    w64 = oracle.reparam(h["mu"], h["sigma"], h["eps"], used)
+    kl64 = oracle.kl(h["mu"], h["sigma"])
+    gm, gs = oracle.grad(h["mu"], h["sigma"], h["eps"], h["G"], wl.s_total, wl.dataset_size, False, used)
+    dt = time.perf_counter() - t0
+    del w64, gm, gs
+    return {"value": n * wl.s_local / dt, "unit": "items/s", "cores": used, "kind": "oracle",
+            "sample": f"first {n} of {wl.n_weights} weights x {wl.s_local} samples of {wl.name}, "
+                      f"forward + KL + backward, {dt:.1f} s (KL sum is serial by definition)",
+            "kl": kl64}
+
+
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def copy_ceiling(hot, torch, dev, nbytes: int = 1 << 31, iters: int = 20, nontemporal: int = 3):
+    """GB/s (bytes read + bytes written) of the library's plain copy kernel over nbytes."""
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        hot.hot_probe_copy(dst, src, nontemporal)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        hot.hot_probe_copy(dst, src, nontemporal)
+    e1.record()
+    torch.cuda.synchronize()
+    ok = bool(torch.equal(dst, src))
+    ms = e0.elapsed_time(e1) / iters
+    return {"GBps": 2 * nbytes / ms / 1e6, "ms": ms, "bytes_read": nbytes, "bytes_written": nbytes,
+            "nontemporal": nontemporal, "copied_correctly": ok}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="C4", help="workload C1..C5 (C4 is the one the metric is quoted on)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--cpu-weights", type=int, default=1 << 28, help="cap on weights the oracle is timed on")
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="only run the plain copy kernel (2 GiB, known traffic) and print its rate")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards over samples; the all-reduce is not "
+              "part of it). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2604_04736_amd import binding as hot, workloads
+    hot.lib()                                   # fail loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    if args.probe_copy:
+        print(json.dumps({"probe": "hot_probe_copy_kernel", "steps": args.steps,
+                          **copy_ceiling(hot, torch, dev, iters=args.steps)}))
+        return 0
+    import oracle
+
+    wl = workloads.CONFIGS[args.config]
+    x = workloads.make_inputs(wl, dev)
+    torch.cuda.synchronize()
+    r = time_steps(hot, torch, wl, x, args.steps, args.warmup)
+    ms_per_step = r["wall_s"] * 1e3 / args.steps
+    items = wl.items
+    fwd_b, bwd_b = algorithmic_bytes(wl.n_weights, wl.s_local)
+    dominant = "backward" if r["bwd_ms"] >= r["fwd_ms"] else "forward"
+    dom_bytes, dom_ms = (bwd_b, r["bwd_ms"]) if dominant == "backward" else (fwd_b, r["fwd_ms"])
+    achieved = dom_bytes / dom_ms / 1e6
+    verified = verify_sampled(oracle, np, wl, x, r["out"])
+
+    result = {
+        "metric": METRIC,
+        "value": items / (ms_per_step * 1e-3),
+        "unit": "items/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.note}; N={wl.n_weights}, S_loc={wl.s_local}, S={wl.s_total}, "
+                               f"ld={wl.ld}, |D|={wl.dataset_size:g}, fp32, seed {wl.seed}",
+                   "items_per_step": items, "step": "hot_forward (w + KL) then hot_backward (grad_mu, grad_sigma)",
+                   "launch": r["launch"]},
+        "roofline": {"bound": "hbm", "kernel": f"hot_{dominant}_kernel", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(f"hot_{dominant}_kernel", wl.name),
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
+        "kernels": {
+            "forward": {"ms": r["fwd_ms"], "GBps": fwd_b / r["fwd_ms"] / 1e6, "items_per_s": items / r["fwd_ms"] * 1e3,
+                        "frac_of_hbm_peak": fwd_b / r["fwd_ms"] / 1e6 / HBM_PEAK_GBS,
+                        "note": "interval between HIP events; includes the one-workgroup KL finish kernel"},
+            "backward": {"ms": r["bwd_ms"], "GBps": bwd_b / r["bwd_ms"] / 1e6, "items_per_s": items / r["bwd_ms"] * 1e3,
+                         "frac_of_hbm_peak": bwd_b / r["bwd_ms"] / 1e6 / HBM_PEAK_GBS},
+        },
+        "step_frac_of_hbm_roofline": (fwd_b + bwd_b) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "verified_against_oracle": bool(verified),
+    }
+    ceiling = copy_ceiling(hot, torch, dev)
+    result["copy_ceiling"] = {"GBps": ceiling["GBps"], "frac_of_hbm_peak": ceiling["GBps"] / HBM_PEAK_GBS,
+                              "what": "hot_probe_copy_kernel, 2 GiB read + 2 GiB written"}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(oracle, np, wl, x, args.cpu_weights)
+        kl_gpu = r["out"]["kl"].item()
+        result["cpu_baseline"]["kl_gpu"] = kl_gpu
+    del x, r
+    torch.cuda.empty_cache()
+
+    if not args.no_others:
+        others = {}
+        for name, o in workloads.CONFIGS.items():
+            if name == wl.name:
+                continue
+            xo = workloads.make_inputs(o, dev)
+            torch.cuda.synchronize()
+            ro = time_steps(hot, torch, o, xo, 20, 5)
+            fb, bb = algorithmic_bytes(o.n_weights, o.s_local)
+            ms = ro["wall_s"] * 1e3 / 20
+            others[name] = {"items_per_s": o.items / (ms * 1e-3), "ms_per_step": ms,
+                            "fwd_ms": ro["fwd_ms"], "bwd_ms": ro["bwd_ms"],
+                            "step_frac_of_hbm_roofline": (fb + bb) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "verified_against_oracle": bool(verify_sampled(oracle, np, o, xo, ro["out"]))}
+            del xo, ro
+            torch.cuda.empty_cache()
+        result["other_workloads"] = others
+
+    print(json.dumps(result))
+    return 0 if verified else 1
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -19,10 +19,11 @@ LIB_PATH = os.path.join(_HERE, "libhot.so")
 HOT_OK, HOT_EINVAL, HOT_ENOMEM, HOT_EHIP = 0, -1, -2, -3
 HOT_REDUCE_SUM, HOT_REDUCE_MEAN = 0, 1
 HOT_KERNEL_FORWARD, HOT_KERNEL_BACKWARD = 0, 1
+HOT_VARIANT_XCD_ORDER, HOT_VARIANT_FP32_SUMS = 1, 2
 
 EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
            "hot_get_launch", "hot_last_hip_error", "hot_strerror", "hot_recommended_ld",
-           "hot_version")
+           "hot_version", "hot_probe_copy")
 
 
 class hot_desc(ctypes.Structure):
@@ -34,7 +35,8 @@ class hot_desc(ctypes.Structure):
 
 class hot_launch(ctypes.Structure):
     _fields_ = [("grid_blocks", ctypes.c_int32), ("chunks", ctypes.c_int32),
-                ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32)]
+                ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32),
+                ("variant", ctypes.c_int32)]
 
 
 class HotError(RuntimeError):
@@ -68,6 +70,8 @@ def lib() -> ctypes.CDLL:
     L.hot_recommended_ld.argtypes = [ctypes.c_int64]
     L.hot_recommended_ld.restype = ctypes.c_int64
     L.hot_version.argtypes = []
+    L.hot_probe_copy.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int, vp]
+    L.hot_probe_copy.restype = ctypes.c_int
     for name in ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
                  "hot_get_launch", "hot_last_hip_error", "hot_version"):
         getattr(L, name).restype = ctypes.c_int
@@ -126,8 +130,8 @@ def hot_destroy(plan: Plan) -> None:
 
 
 def hot_set_launch(plan: Plan, kernel: int, grid_blocks: int = 0, chunks: int = 0,
-                   unroll: int = 0, nontemporal: int = 0) -> None:
-    cfg = hot_launch(grid_blocks, chunks, unroll, nontemporal)
+                   unroll: int = 0, nontemporal: int = 0, variant: int = 0) -> None:
+    cfg = hot_launch(grid_blocks, chunks, unroll, nontemporal, variant)
     _check(lib().hot_set_launch(plan.handle, kernel, ctypes.byref(cfg)), "hot_set_launch", plan)
 
 
@@ -189,3 +193,15 @@ def hot_backward(plan: Plan, mu, sigma, eps, grad_w, grad_mu, grad_sigma) -> Non
                               _vec(grad_sigma, d.n_weights, d.device, "grad_sigma"),
                               _stream(d.device))
     _check(code, "hot_backward", plan)
+
+
+def hot_probe_copy(dst: torch.Tensor, src: torch.Tensor, nontemporal: int = 0) -> None:
+    """Plain device copy of src into dst (measurement aid, see include/hot.h)."""
+    if not (dst.is_cuda and src.is_cuda and dst.device == src.device and dst.is_contiguous()
+            and src.is_contiguous() and dst.numel() * dst.element_size() == src.numel() * src.element_size()):
+        raise ValueError("hot_probe_copy: need two contiguous device tensors of equal byte size")
+    with torch.cuda.device(src.device):
+        code = lib().hot_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(),
+                                    nontemporal, _stream(src.device.index))
+    if code != HOT_OK:
+        raise HotError(code, "hot_probe_copy")

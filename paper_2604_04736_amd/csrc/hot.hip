@@ -9,9 +9,10 @@
 //   * mu and sigma are loaded once per column and stay in registers across the sample
 //     loop; the rows of several samples are requested together (UNROLL) and a thread
 //     owns several chunks (CHUNKS) so that each wave keeps many 16-byte loads in flight;
-//   * a bounded grid of workgroups strides over the column tiles, so the KL term needs
-//     only one fp64 partial per workgroup; the workgroup that takes the last ticket
-//     adds the partials in index order (deterministic, no floating-point atomics);
+//   * the KL term leaves one fp64 partial per workgroup; a one-workgroup kernel launched
+//     right behind adds them in a fixed order (deterministic, no floating-point atomics,
+//     and no fence inside the streaming kernel: a device-scope release there has to
+//     write back the die's whole L2, which cost a factor of four with large grids);
 //   * there is no reuse between threads, hence no LDS staging: LDS only carries the
 //     four per-wave partial sums of the KL reduction.
 #include <hip/hip_runtime.h>
@@ -25,6 +26,8 @@ namespace {
 constexpr int kBlock = 256;             // threads per workgroup = 4 wavefronts of 64
 constexpr int kWaves = kBlock / 64;
 constexpr int kMaxGrid = 65536;         // upper bound on workgroups (size of the partials buffer)
+constexpr int kXcds = 8;                // accelerator dies of an MI355X, each with its own L2
+constexpr int kFinishBlock = 1024;      // threads of the one workgroup that adds the KL partials
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef f4 f4u __attribute__((aligned(4)));   // same vector, only dword-aligned in memory
@@ -78,6 +81,14 @@ __device__ __forceinline__ void finish_grad(double sum_g, double sum_ge, float m
     gs = (float)fma(g, sum_ge, k * ((double)sd - (double)inv));
 }
 
+// Workgroups are handed to the 8 accelerator dies (XCDs) round-robin by workgroup index.
+// In XCD order, slot number q is tile (q mod 8) * per_xcd + q / 8, so each die streams
+// through one contiguous eighth of the columns; otherwise slot q is tile q.
+__device__ __forceinline__ long tile_of_slot(long slot, long per_xcd, int xcd_order)
+{
+    return xcd_order ? (slot % kXcds) * per_xcd + slot / kXcds : slot;
+}
+
 __device__ __forceinline__ double wave_sum(double v)
 {
 #pragma unroll
@@ -110,16 +121,19 @@ __global__ void __launch_bounds__(kBlock)
 hot_forward_kernel(long n, long ld, int s_loc,
                    const float *__restrict__ mu, const float *__restrict__ sigma,
                    const float *__restrict__ eps, float *__restrict__ w,
-                   double *__restrict__ partials, unsigned *__restrict__ ticket,
-                   double *__restrict__ kl_out)
+                   double *__restrict__ partials, int xcd_order)
 {
     constexpr long kTile = (long)kBlock * 4 * CHUNKS;   // columns per tile
     constexpr long kStep = (long)kBlock * 4;            // columns between a thread's chunks
     constexpr bool NT_LD = (NT & 1) != 0, NT_ST = (NT & 2) != 0;
     const long n_tiles = (n + kTile - 1) / kTile;
+    const long per_xcd = (n_tiles + kXcds - 1) / kXcds;
+    const long n_slots = xcd_order ? per_xcd * kXcds : n_tiles;
     double kl = 0.0;
 
-    for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    for (long slot = blockIdx.x; slot < n_slots; slot += gridDim.x) {
+        const long tile = tile_of_slot(slot, per_xcd, xcd_order);
+        if (tile >= n_tiles) continue;
         const long col0 = tile * kTile + (long)threadIdx.x * 4;
         if ((tile + 1) * kTile <= n) {
             f4 m[CHUNKS], sd[CHUNKS];
@@ -199,26 +213,27 @@ hot_forward_kernel(long n, long ld, int s_loc,
 
     if constexpr (KL) {
         __shared__ double lds[kWaves];
-        __shared__ bool last;
         const double mine = block_sum(kl, lds);
-        if (threadIdx.x == 0) {
-            __hip_atomic_store(&partials[blockIdx.x], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            // release our partial, acquire everybody else's (the ticket is the synchronisation point)
-            const unsigned t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-            last = (t == gridDim.x - 1);
-        }
-        __syncthreads();
-        if (last) {
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            double acc = 0.0;
-            for (unsigned j = threadIdx.x; j < gridDim.x; j += kBlock)
-                acc += __hip_atomic_load(&partials[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const double total = block_sum(acc, lds);
-            if (threadIdx.x == 0) {
-                *kl_out = 0.5 * total;
-                __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
-            }
-        }
+        if (threadIdx.x == 0) partials[blockIdx.x] = mine;
+    }
+}
+
+// Adds the per-workgroup KL partials in a fixed order and applies the factor 1/2 of the
+// prior-matching line.  One workgroup; runs right after the forward kernel on its stream.
+__global__ void __launch_bounds__(kFinishBlock)
+hot_kl_finish_kernel(const double *__restrict__ partials, int count, double *__restrict__ kl_out)
+{
+    __shared__ double lds[kFinishBlock / 64];
+    double acc = 0.0;
+    for (int j = threadIdx.x; j < count; j += kFinishBlock) acc += partials[j];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double total = 0.0;
+#pragma unroll
+        for (int i = 0; i < kFinishBlock / 64; ++i) total += lds[i];
+        *kl_out = 0.5 * total;
     }
 }
 
@@ -226,9 +241,9 @@ hot_forward_kernel(long n, long ld, int s_loc,
 // Backward: column sums over the local samples of grad_w and grad_w * eps, then the
 // KL gradient and the scaling (Algorithm 2, loss / gradient / averaging lines).
 // ---------------------------------------------------------------------------------
-template <int CHUNKS, int UNROLL, bool ALIGNED, int NT>
+template <int CHUNKS, int UNROLL, bool ALIGNED, int NT, typename ACC>
 __global__ void __launch_bounds__(kBlock)
-hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
+hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int xcd_order,
                     const float *__restrict__ mu, const float *__restrict__ sigma,
                     const float *__restrict__ eps, const float *__restrict__ gw,
                     float *__restrict__ gmu, float *__restrict__ gsig)
@@ -237,8 +252,12 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
     constexpr long kStep = (long)kBlock * 4;
     constexpr bool NT_LD = (NT & 1) != 0, NT_ST = (NT & 2) != 0;
     const long n_tiles = (n + kTile - 1) / kTile;
+    const long per_xcd = (n_tiles + kXcds - 1) / kXcds;
+    const long n_slots = xcd_order ? per_xcd * kXcds : n_tiles;
 
-    for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    for (long slot = blockIdx.x; slot < n_slots; slot += gridDim.x) {
+        const long tile = tile_of_slot(slot, per_xcd, xcd_order);
+        if (tile >= n_tiles) continue;
         const long col0 = tile * kTile + (long)threadIdx.x * 4;
         if ((tile + 1) * kTile <= n) {
             f4 m[CHUNKS], sd[CHUNKS];
@@ -247,11 +266,11 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                 m[c] = load4<ALIGNED, false>(mu + col0 + c * kStep);
                 sd[c] = load4<ALIGNED, false>(sigma + col0 + c * kStep);
             }
-            double sum_g[CHUNKS][4], sum_ge[CHUNKS][4];
+            ACC sum_g[CHUNKS][4], sum_ge[CHUNKS][4];
 #pragma unroll
             for (int c = 0; c < CHUNKS; ++c)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) sum_g[c][j] = sum_ge[c][j] = 0.0;
+                for (int j = 0; j < 4; ++j) sum_g[c][j] = sum_ge[c][j] = (ACC)0;
             int s = 0;
             for (; s + UNROLL <= s_loc; s += UNROLL) {
                 f4 gv[UNROLL][CHUNKS], ev[UNROLL][CHUNKS];
@@ -269,9 +288,9 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                     for (int c = 0; c < CHUNKS; ++c)
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            const double gd = (double)gv[u][c][j];
+                            const ACC gd = (ACC)gv[u][c][j];
                             sum_g[c][j] += gd;
-                            sum_ge[c][j] = fma(gd, (double)ev[u][c][j], sum_ge[c][j]);
+                            sum_ge[c][j] = fma(gd, (ACC)ev[u][c][j], sum_ge[c][j]);
                         }
             }
             for (; s < s_loc; ++s) {
@@ -286,9 +305,9 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                 for (int c = 0; c < CHUNKS; ++c)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const double gd = (double)gv[c][j];
+                        const ACC gd = (ACC)gv[c][j];
                         sum_g[c][j] += gd;
-                        sum_ge[c][j] = fma(gd, (double)ev[c][j], sum_ge[c][j]);
+                        sum_ge[c][j] = fma(gd, (ACC)ev[c][j], sum_ge[c][j]);
                     }
             }
 #pragma unroll
@@ -310,16 +329,16 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                 if (col + 4 <= n) {
                     const f4 m = load4<ALIGNED, false>(mu + col);
                     const f4 sd = load4<ALIGNED, false>(sigma + col);
-                    double sum_g[4] = {0.0, 0.0, 0.0, 0.0}, sum_ge[4] = {0.0, 0.0, 0.0, 0.0};
+                    ACC sum_g[4] = {0, 0, 0, 0}, sum_ge[4] = {0, 0, 0, 0};
                     for (int s = 0; s < s_loc; ++s) {
                         const size_t at = (size_t)s * (size_t)ld + col;
                         const f4 gv = load4<ALIGNED, false>(gw + at);
                         const f4 ev = load4<ALIGNED, false>(eps + at);
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            const double gd = (double)gv[j];
+                            const ACC gd = (ACC)gv[j];
                             sum_g[j] += gd;
-                            sum_ge[j] = fma(gd, (double)ev[j], sum_ge[j]);
+                            sum_ge[j] = fma(gd, (ACC)ev[j], sum_ge[j]);
                         }
                     }
                     f4 om, os;
@@ -334,12 +353,12 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                     store4<ALIGNED, false>(gsig + col, os);
                 } else {
                     for (long i = col; i < n; ++i) {
-                        double sum_g = 0.0, sum_ge = 0.0;
+                        ACC sum_g = 0, sum_ge = 0;
                         for (int s = 0; s < s_loc; ++s) {
                             const size_t at = (size_t)s * (size_t)ld + (size_t)i;
-                            const double gd = (double)gw[at];
+                            const ACC gd = (ACC)gw[at];
                             sum_g += gd;
-                            sum_ge = fma(gd, (double)eps[at], sum_ge);
+                            sum_ge = fma(gd, (ACC)eps[at], sum_ge);
                         }
                         float a, b;
                         finish_grad(sum_g, sum_ge, mu[i], sigma[i], g, k, a, b);
@@ -348,6 +367,32 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                     }
                 }
             }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Measurement aid: a plain copy with the same 16-byte accesses, four per thread.  Its known
+// traffic calibrates the HBM byte counters and gives the copy ceiling of the machine.
+// ---------------------------------------------------------------------------------
+template <int NT>
+__global__ void __launch_bounds__(kBlock)
+hot_probe_copy_kernel(const f4 *__restrict__ src, f4 *__restrict__ dst, long n_vec)
+{
+    constexpr int kPer = 4;
+    const long base = (long)blockIdx.x * (kBlock * kPer) + threadIdx.x;
+    f4 v[kPer];
+#pragma unroll
+    for (int c = 0; c < kPer; ++c) {
+        const long at = base + (long)c * kBlock;
+        if (at < n_vec) v[c] = (NT & 1) ? __builtin_nontemporal_load(src + at) : src[at];
+    }
+#pragma unroll
+    for (int c = 0; c < kPer; ++c) {
+        const long at = base + (long)c * kBlock;
+        if (at < n_vec) {
+            if (NT & 2) __builtin_nontemporal_store(v[c], dst + at);
+            else dst[at] = v[c];
         }
     }
 }
@@ -362,8 +407,8 @@ struct FwdArgs {
     const float *mu, *sigma, *eps;
     float *w;
     double *partials;
-    unsigned *ticket;
-    double *kl_out;
+    bool want_kl;
+    int xcd_order;
     dim3 grid;
     hipStream_t stream;
 };
@@ -374,6 +419,8 @@ struct BwdArgs {
     double g, k;
     const float *mu, *sigma, *eps, *gw;
     float *gmu, *gsig;
+    bool acc32;
+    int xcd_order;
     dim3 grid;
     hipStream_t stream;
 };
@@ -382,12 +429,12 @@ template <int CH, int U, bool AL, int NT, bool KL>
 void fwd_go(const FwdArgs &a)
 {
     hot_forward_kernel<CH, U, AL, NT, KL><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-        a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out);
+        a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.xcd_order);
 }
 template <int CH, int U, bool AL, int NT>
 void fwd_kl(const FwdArgs &a)
 {
-    if (a.kl_out) fwd_go<CH, U, AL, NT, true>(a);
+    if (a.want_kl) fwd_go<CH, U, AL, NT, true>(a);
     else fwd_go<CH, U, AL, NT, false>(a);
 }
 template <int CH, int U, bool AL>
@@ -423,18 +470,18 @@ void fwd_dispatch(int ch, int u, bool al, int nt, const FwdArgs &a)
 template <int CH, int U, bool AL, int NT>
 void bwd_go(const BwdArgs &a)
 {
-    hot_backward_kernel<CH, U, AL, NT><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-        a.n, a.ld, a.s_loc, a.g, a.k, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig);
+    if (a.acc32)
+        hot_backward_kernel<CH, U, AL, NT, float><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+            a.n, a.ld, a.s_loc, a.g, a.k, a.xcd_order, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig);
+    else
+        hot_backward_kernel<CH, U, AL, NT, double><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+            a.n, a.ld, a.s_loc, a.g, a.k, a.xcd_order, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig);
 }
 template <int CH, int U, bool AL>
 void bwd_nt(int nt, const BwdArgs &a)
 {
-    switch (nt & 3) {
-    case 0: bwd_go<CH, U, AL, 0>(a); break;
-    case 1: bwd_go<CH, U, AL, 1>(a); break;
-    case 2: bwd_go<CH, U, AL, 2>(a); break;
-    default: bwd_go<CH, U, AL, 3>(a); break;
-    }
+    if (nt & 1) bwd_go<CH, U, AL, 1>(a);
+    else bwd_go<CH, U, AL, 0>(a);
 }
 template <int CH, int U>
 void bwd_al(bool al, int nt, const BwdArgs &a)
@@ -483,8 +530,7 @@ struct DeviceGuard {
 struct hot_plan {
     hot_desc d;
     double g, k;
-    double *partials;
-    unsigned *ticket;
+    double *partials;   // kMaxGrid fp64 KL partial sums, one per forward workgroup
     hot_launch cfg[2];
     int last_hip;
 };
@@ -508,10 +554,17 @@ bool valid_launch(const hot_launch &c)
 {
     auto one_of = [](int v) { return v == 0 || v == 1 || v == 2 || v == 4; };
     return c.grid_blocks >= 0 && c.grid_blocks <= kMaxGrid && one_of(c.chunks) && one_of(c.unroll) &&
-           c.nontemporal >= 0 && c.nontemporal <= 3;
+           c.nontemporal >= 0 && c.nontemporal <= 3 && c.variant >= 0 && c.variant <= 3;
 }
 
-long tiles_of(long n, int chunks) { return (n + (long)kBlock * 4 * chunks - 1) / ((long)kBlock * 4 * chunks); }
+// Number of workgroups: one per tile slot, capped by the configured bound.
+unsigned grid_for(long n, const hot_launch &c)
+{
+    const long tile = (long)kBlock * 4 * c.chunks;
+    const long tiles = (n + tile - 1) / tile;
+    const long slots = (c.variant & HOT_VARIANT_XCD_ORDER) ? (tiles + kXcds - 1) / kXcds * kXcds : tiles;
+    return (unsigned)(slots < c.grid_blocks ? slots : c.grid_blocks);
+}
 
 }  // namespace
 
@@ -560,31 +613,23 @@ int hot_create(hot_plan **out, const hot_desc *desc)
         p->k = (double)d.s_local / ((double)d.s_total * d.dataset_size);
     }
     p->partials = nullptr;
-    p->ticket = nullptr;
     p->last_hip = 0;
 
     DeviceGuard guard(d.device);
     hipError_t e = guard.err;
-    int cus = 0;
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d.device);
     if (e == hipSuccess) e = hipMalloc((void **)&p->partials, sizeof(double) * kMaxGrid);
-    if (e == hipSuccess) e = hipMalloc((void **)&p->ticket, 256);
-    if (e == hipSuccess) e = hipMemset(p->ticket, 0, 256);
     if (e != hipSuccess) {
         const bool oom = (e == hipErrorOutOfMemory);
-        if (p->partials) (void)hipFree(p->partials);
-        if (p->ticket) (void)hipFree(p->ticket);
+        (void)hipGetLastError();
         delete p;
         return oom ? HOT_ENOMEM : HOT_EHIP;
     }
-    if (cus < 1) cus = 256;
-    int grid = cus * 8;
-    if (grid > kMaxGrid) grid = kMaxGrid;
     for (int kn = 0; kn < 2; ++kn) {
-        p->cfg[kn].grid_blocks = grid;
-        p->cfg[kn].chunks = 2;
-        p->cfg[kn].unroll = pick_unroll(4, d.s_local);
-        p->cfg[kn].nontemporal = 0;
+        p->cfg[kn].grid_blocks = kMaxGrid;
+        p->cfg[kn].chunks = 4;
+        p->cfg[kn].unroll = pick_unroll(kn == HOT_KERNEL_FORWARD ? 1 : 2, d.s_local);
+        p->cfg[kn].nontemporal = kn == HOT_KERNEL_FORWARD ? 3 : 1;
+        p->cfg[kn].variant = 0;
     }
     *out = p;
     return HOT_OK;
@@ -597,7 +642,6 @@ int hot_destroy(hot_plan *plan)
     {
         DeviceGuard guard(plan->d.device);
         if (plan->partials && hipFree(plan->partials) != hipSuccess) rc = HOT_EHIP;
-        if (plan->ticket && hipFree(plan->ticket) != hipSuccess) rc = HOT_EHIP;
     }
     delete plan;
     return rc;
@@ -612,6 +656,7 @@ int hot_set_launch(hot_plan *plan, int kernel, const hot_launch *cfg)
     if (cfg->chunks) c.chunks = cfg->chunks;
     if (cfg->unroll) c.unroll = pick_unroll(cfg->unroll, plan->d.s_local);
     c.nontemporal = cfg->nontemporal;
+    c.variant = cfg->variant;
     return HOT_OK;
 }
 
@@ -623,6 +668,26 @@ int hot_get_launch(const hot_plan *plan, int kernel, hot_launch *cfg)
 }
 
 int hot_last_hip_error(const hot_plan *plan) { return plan ? plan->last_hip : 0; }
+
+int hot_probe_copy(void *dst, const void *src, int64_t bytes, int nontemporal, void *stream)
+{
+    if (!dst || !src || bytes < 16 || (bytes & 15) || !aligned16(dst) || !aligned16(src)) return HOT_EINVAL;
+    if (nontemporal < 0 || nontemporal > 3) return HOT_EINVAL;
+    const long n_vec = bytes / 16;
+    const long blocks = (n_vec + kBlock * 4 - 1) / (kBlock * 4);
+    if (blocks > 0x7fffffffL) return HOT_EINVAL;
+    const dim3 grid((unsigned)blocks), block(kBlock);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const f4 *in = static_cast<const f4 *>(src);
+    f4 *out = static_cast<f4 *>(dst);
+    switch (nontemporal) {
+    case 0: hot_probe_copy_kernel<0><<<grid, block, 0, s>>>(in, out, n_vec); break;
+    case 1: hot_probe_copy_kernel<1><<<grid, block, 0, s>>>(in, out, n_vec); break;
+    case 2: hot_probe_copy_kernel<2><<<grid, block, 0, s>>>(in, out, n_vec); break;
+    default: hot_probe_copy_kernel<3><<<grid, block, 0, s>>>(in, out, n_vec); break;
+    }
+    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+}
 
 int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float *eps, float *w,
                 double *kl_out, void *stream)
@@ -643,16 +708,19 @@ int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float
     a.eps = eps;
     a.w = w;
     a.partials = plan->partials;
-    a.ticket = plan->ticket;
-    a.kl_out = kl_out;
-    long tiles = tiles_of(d.n_weights, c.chunks);
-    a.grid = dim3((unsigned)(tiles < c.grid_blocks ? tiles : c.grid_blocks));
+    a.want_kl = kl_out != nullptr;
+    a.xcd_order = (c.variant & HOT_VARIANT_XCD_ORDER) ? 1 : 0;
+    a.grid = dim3(grid_for(d.n_weights, c));
     a.stream = static_cast<hipStream_t>(stream);
 
     DeviceGuard guard(d.device);
     if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
     fwd_dispatch(c.chunks, c.unroll, al, c.nontemporal, a);
-    const hipError_t e = hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && kl_out) {
+        hot_kl_finish_kernel<<<dim3(1), dim3(kFinishBlock), 0, a.stream>>>(plan->partials, (int)a.grid.x, kl_out);
+        e = hipGetLastError();
+    }
     return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
 }
 
@@ -680,8 +748,9 @@ int hot_backward(hot_plan *plan, const float *mu, const float *sigma, const floa
     a.gw = grad_w;
     a.gmu = grad_mu;
     a.gsig = grad_sigma;
-    long tiles = tiles_of(d.n_weights, c.chunks);
-    a.grid = dim3((unsigned)(tiles < c.grid_blocks ? tiles : c.grid_blocks));
+    a.acc32 = (c.variant & HOT_VARIANT_FP32_SUMS) != 0;
+    a.xcd_order = (c.variant & HOT_VARIANT_XCD_ORDER) ? 1 : 0;
+    a.grid = dim3(grid_for(d.n_weights, c));
     a.stream = static_cast<hipStream_t>(stream);
 
     DeviceGuard guard(d.device);

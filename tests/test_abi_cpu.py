@@ -49,7 +49,7 @@ def test_struct_layout_matches_header(hot):
     # hot_desc: int64, int64, int32, int32, double, int32, uint32 -> 40 bytes, natural alignment
     assert ctypes.sizeof(hot.hot_desc) == 40
     assert hot.hot_desc.dataset_size.offset == 24 and hot.hot_desc.flags.offset == 36
-    assert ctypes.sizeof(hot.hot_launch) == 16
+    assert ctypes.sizeof(hot.hot_launch) == 20
 
 
 def test_null_arguments_are_rejected_without_a_gpu(hot):
@@ -61,6 +61,7 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_set_launch(None, 0, None) == hot.HOT_EINVAL
     assert L.hot_get_launch(None, 0, None) == hot.HOT_EINVAL
     assert L.hot_last_hip_error(None) == 0
+    assert L.hot_probe_copy(None, None, 16, 0, None) == hot.HOT_EINVAL
     out = ctypes.c_void_p()
     for bad in [hot.hot_desc(0, 0, 1, 1, 1.0, 0, 0),        # N < 1
                 hot.hot_desc(8, 7, 1, 1, 1.0, 0, 0),        # ld < N

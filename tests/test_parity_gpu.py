@@ -215,6 +215,20 @@ def test_errors_from_the_c_abi(hot):
     hot.hot_destroy(plan)      # second destroy of the wrapper is a no-op
 
 
+def test_probe_copy_is_exact(hot):
+    for count in (4, 1024, 4096 + 4, 1_000_004):
+        src = torch.randn(count, device=DEV)
+        for nt in range(4):
+            dst = torch.zeros(count + 8, device=DEV)
+            hot.hot_probe_copy(dst[4:4 + count], src, nt)
+            torch.cuda.synchronize()
+            assert torch.equal(dst[4:4 + count], src)
+            assert dst[:4].abs().sum().item() == 0 and dst[4 + count:].abs().sum().item() == 0
+    with pytest.raises(hot.HotError):
+        hot.lib()   # keep the handle alive
+        hot.hot_probe_copy(torch.zeros(6, device=DEV)[1:5], torch.zeros(4, device=DEV))
+
+
 def test_runs_on_a_side_stream(oracle, hot):
     wl = W.scaled(W.CONFIGS["C2"], 100_000)
     x = W.make_inputs(wl, DEV)

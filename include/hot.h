@@ -67,18 +67,15 @@ typedef struct hot_launch {
     int32_t chunks;      /* 16-byte column chunks per thread and tile: 1, 2 or 4 */
     int32_t unroll;      /* sample rows whose loads are issued together: 1, 2 or 4 */
     int32_t nontemporal; /* bit 0: streamed loads (eps, grad_w) bypass-hinted; bit 1: streamed stores (w) */
-    int32_t variant;     /* HOT_VARIANT_* bits */
 } hot_launch;
-
-#define HOT_VARIANT_XCD_ORDER 1 /* each of the 8 dies walks one contiguous eighth of the columns */
-#define HOT_VARIANT_FP32_SUMS 2 /* backward only: sample sums in fp32 instead of fp64 */
 
 #define HOT_KERNEL_FORWARD 0
 #define HOT_KERNEL_BACKWARD 1
 
 /*
  * Validates the description, fixes g and k, and allocates the plan's own device
- * scratch (per-workgroup KL partial sums in fp64, 512 KiB) on desc->device.  *out is written only on success.
+ * scratch (per-workgroup KL partial sums in fp64, 512 KiB) on desc->device.  *out is
+ * written only on success.
  */
 int hot_create(hot_plan **out, const hot_desc *desc);
 

@@ -19,7 +19,6 @@ LIB_PATH = os.path.join(_HERE, "libhot.so")
 HOT_OK, HOT_EINVAL, HOT_ENOMEM, HOT_EHIP = 0, -1, -2, -3
 HOT_REDUCE_SUM, HOT_REDUCE_MEAN = 0, 1
 HOT_KERNEL_FORWARD, HOT_KERNEL_BACKWARD = 0, 1
-HOT_VARIANT_XCD_ORDER, HOT_VARIANT_FP32_SUMS = 1, 2
 
 EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
            "hot_get_launch", "hot_last_hip_error", "hot_strerror", "hot_recommended_ld",
@@ -35,8 +34,7 @@ class hot_desc(ctypes.Structure):
 
 class hot_launch(ctypes.Structure):
     _fields_ = [("grid_blocks", ctypes.c_int32), ("chunks", ctypes.c_int32),
-                ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32),
-                ("variant", ctypes.c_int32)]
+                ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32)]
 
 
 class HotError(RuntimeError):
@@ -130,8 +128,8 @@ def hot_destroy(plan: Plan) -> None:
 
 
 def hot_set_launch(plan: Plan, kernel: int, grid_blocks: int = 0, chunks: int = 0,
-                   unroll: int = 0, nontemporal: int = 0, variant: int = 0) -> None:
-    cfg = hot_launch(grid_blocks, chunks, unroll, nontemporal, variant)
+                   unroll: int = 0, nontemporal: int = 0) -> None:
+    cfg = hot_launch(grid_blocks, chunks, unroll, nontemporal)
     _check(lib().hot_set_launch(plan.handle, kernel, ctypes.byref(cfg)), "hot_set_launch", plan)
 
 

@@ -26,7 +26,6 @@ namespace {
 constexpr int kBlock = 256;             // threads per workgroup = 4 wavefronts of 64
 constexpr int kWaves = kBlock / 64;
 constexpr int kMaxGrid = 65536;         // upper bound on workgroups (size of the partials buffer)
-constexpr int kXcds = 8;                // accelerator dies of an MI355X, each with its own L2
 constexpr int kFinishBlock = 1024;      // threads of the one workgroup that adds the KL partials
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -81,14 +80,6 @@ __device__ __forceinline__ void finish_grad(double sum_g, double sum_ge, float m
     gs = (float)fma(g, sum_ge, k * ((double)sd - (double)inv));
 }
 
-// Workgroups are handed to the 8 accelerator dies (XCDs) round-robin by workgroup index.
-// In XCD order, slot number q is tile (q mod 8) * per_xcd + q / 8, so each die streams
-// through one contiguous eighth of the columns; otherwise slot q is tile q.
-__device__ __forceinline__ long tile_of_slot(long slot, long per_xcd, int xcd_order)
-{
-    return xcd_order ? (slot % kXcds) * per_xcd + slot / kXcds : slot;
-}
-
 __device__ __forceinline__ double wave_sum(double v)
 {
 #pragma unroll
@@ -121,19 +112,15 @@ __global__ void __launch_bounds__(kBlock)
 hot_forward_kernel(long n, long ld, int s_loc,
                    const float *__restrict__ mu, const float *__restrict__ sigma,
                    const float *__restrict__ eps, float *__restrict__ w,
-                   double *__restrict__ partials, int xcd_order)
+                   double *__restrict__ partials)
 {
     constexpr long kTile = (long)kBlock * 4 * CHUNKS;   // columns per tile
     constexpr long kStep = (long)kBlock * 4;            // columns between a thread's chunks
     constexpr bool NT_LD = (NT & 1) != 0, NT_ST = (NT & 2) != 0;
     const long n_tiles = (n + kTile - 1) / kTile;
-    const long per_xcd = (n_tiles + kXcds - 1) / kXcds;
-    const long n_slots = xcd_order ? per_xcd * kXcds : n_tiles;
     double kl = 0.0;
 
-    for (long slot = blockIdx.x; slot < n_slots; slot += gridDim.x) {
-        const long tile = tile_of_slot(slot, per_xcd, xcd_order);
-        if (tile >= n_tiles) continue;
+    for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const long col0 = tile * kTile + (long)threadIdx.x * 4;
         if ((tile + 1) * kTile <= n) {
             f4 m[CHUNKS], sd[CHUNKS];
@@ -225,7 +212,16 @@ hot_kl_finish_kernel(const double *__restrict__ partials, int count, double *__r
 {
     __shared__ double lds[kFinishBlock / 64];
     double acc = 0.0;
-    for (int j = threadIdx.x; j < count; j += kFinishBlock) acc += partials[j];
+    for (int j0 = threadIdx.x; j0 < count; j0 += kFinishBlock * 8) {
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {       // eight independent loads in flight, added in index order
+            const int j = j0 + u * kFinishBlock;
+            v[u] = j < count ? partials[j] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+    }
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = acc;
     __syncthreads();
@@ -241,9 +237,9 @@ hot_kl_finish_kernel(const double *__restrict__ partials, int count, double *__r
 // Backward: column sums over the local samples of grad_w and grad_w * eps, then the
 // KL gradient and the scaling (Algorithm 2, loss / gradient / averaging lines).
 // ---------------------------------------------------------------------------------
-template <int CHUNKS, int UNROLL, bool ALIGNED, int NT, typename ACC>
+template <int CHUNKS, int UNROLL, bool ALIGNED, int NT>
 __global__ void __launch_bounds__(kBlock)
-hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int xcd_order,
+hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                     const float *__restrict__ mu, const float *__restrict__ sigma,
                     const float *__restrict__ eps, const float *__restrict__ gw,
                     float *__restrict__ gmu, float *__restrict__ gsig)
@@ -252,12 +248,8 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int xcd_orde
     constexpr long kStep = (long)kBlock * 4;
     constexpr bool NT_LD = (NT & 1) != 0, NT_ST = (NT & 2) != 0;
     const long n_tiles = (n + kTile - 1) / kTile;
-    const long per_xcd = (n_tiles + kXcds - 1) / kXcds;
-    const long n_slots = xcd_order ? per_xcd * kXcds : n_tiles;
 
-    for (long slot = blockIdx.x; slot < n_slots; slot += gridDim.x) {
-        const long tile = tile_of_slot(slot, per_xcd, xcd_order);
-        if (tile >= n_tiles) continue;
+    for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const long col0 = tile * kTile + (long)threadIdx.x * 4;
         if ((tile + 1) * kTile <= n) {
             f4 m[CHUNKS], sd[CHUNKS];
@@ -266,11 +258,11 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int xcd_orde
                 m[c] = load4<ALIGNED, false>(mu + col0 + c * kStep);
                 sd[c] = load4<ALIGNED, false>(sigma + col0 + c * kStep);
             }
-            ACC sum_g[CHUNKS][4], sum_ge[CHUNKS][4];
+            double sum_g[CHUNKS][4], sum_ge[CHUNKS][4];
 #pragma unroll
             for (int c = 0; c < CHUNKS; ++c)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) sum_g[c][j] = sum_ge[c][j] = (ACC)0;
+                for (int j = 0; j < 4; ++j) sum_g[c][j] = sum_ge[c][j] = 0.0;
             int s = 0;
             for (; s + UNROLL <= s_loc; s += UNROLL) {
                 f4 gv[UNROLL][CHUNKS], ev[UNROLL][CHUNKS];
@@ -288,9 +280,9 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int xcd_orde
                     for (int c = 0; c < CHUNKS; ++c)
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            const ACC gd = (ACC)gv[u][c][j];
+                            const double gd = (double)gv[u][c][j];
                             sum_g[c][j] += gd;
-                            sum_ge[c][j] = fma(gd, (ACC)ev[u][c][j], sum_ge[c][j]);
+                            sum_ge[c][j] = fma(gd, (double)ev[u][c][j], sum_ge[c][j]);
                         }
             }
             for (; s < s_loc; ++s) {
@@ -305,9 +297,9 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int xcd_orde
                 for (int c = 0; c < CHUNKS; ++c)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const ACC gd = (ACC)gv[c][j];
+                        const double gd = (double)gv[c][j];
                         sum_g[c][j] += gd;
-                        sum_ge[c][j] = fma(gd, (ACC)ev[c][j], sum_ge[c][j]);
+                        sum_ge[c][j] = fma(gd, (double)ev[c][j], sum_ge[c][j]);
                     }
             }
 #pragma unroll
@@ -329,16 +321,16 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int xcd_orde
                 if (col + 4 <= n) {
                     const f4 m = load4<ALIGNED, false>(mu + col);
                     const f4 sd = load4<ALIGNED, false>(sigma + col);
-                    ACC sum_g[4] = {0, 0, 0, 0}, sum_ge[4] = {0, 0, 0, 0};
+                    double sum_g[4] = {0, 0, 0, 0}, sum_ge[4] = {0, 0, 0, 0};
                     for (int s = 0; s < s_loc; ++s) {
                         const size_t at = (size_t)s * (size_t)ld + col;
                         const f4 gv = load4<ALIGNED, false>(gw + at);
                         const f4 ev = load4<ALIGNED, false>(eps + at);
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            const ACC gd = (ACC)gv[j];
+                            const double gd = (double)gv[j];
                             sum_g[j] += gd;
-                            sum_ge[j] = fma(gd, (ACC)ev[j], sum_ge[j]);
+                            sum_ge[j] = fma(gd, (double)ev[j], sum_ge[j]);
                         }
                     }
                     f4 om, os;
@@ -353,12 +345,12 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int xcd_orde
                     store4<ALIGNED, false>(gsig + col, os);
                 } else {
                     for (long i = col; i < n; ++i) {
-                        ACC sum_g = 0, sum_ge = 0;
+                        double sum_g = 0, sum_ge = 0;
                         for (int s = 0; s < s_loc; ++s) {
                             const size_t at = (size_t)s * (size_t)ld + (size_t)i;
-                            const ACC gd = (ACC)gw[at];
+                            const double gd = (double)gw[at];
                             sum_g += gd;
-                            sum_ge = fma(gd, (ACC)eps[at], sum_ge);
+                            sum_ge = fma(gd, (double)eps[at], sum_ge);
                         }
                         float a, b;
                         finish_grad(sum_g, sum_ge, mu[i], sigma[i], g, k, a, b);
@@ -408,7 +400,6 @@ struct FwdArgs {
     float *w;
     double *partials;
     bool want_kl;
-    int xcd_order;
     dim3 grid;
     hipStream_t stream;
 };
@@ -419,8 +410,6 @@ struct BwdArgs {
     double g, k;
     const float *mu, *sigma, *eps, *gw;
     float *gmu, *gsig;
-    bool acc32;
-    int xcd_order;
     dim3 grid;
     hipStream_t stream;
 };
@@ -429,7 +418,7 @@ template <int CH, int U, bool AL, int NT, bool KL>
 void fwd_go(const FwdArgs &a)
 {
     hot_forward_kernel<CH, U, AL, NT, KL><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-        a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.xcd_order);
+        a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials);
 }
 template <int CH, int U, bool AL, int NT>
 void fwd_kl(const FwdArgs &a)
@@ -470,12 +459,8 @@ void fwd_dispatch(int ch, int u, bool al, int nt, const FwdArgs &a)
 template <int CH, int U, bool AL, int NT>
 void bwd_go(const BwdArgs &a)
 {
-    if (a.acc32)
-        hot_backward_kernel<CH, U, AL, NT, float><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-            a.n, a.ld, a.s_loc, a.g, a.k, a.xcd_order, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig);
-    else
-        hot_backward_kernel<CH, U, AL, NT, double><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-            a.n, a.ld, a.s_loc, a.g, a.k, a.xcd_order, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig);
+    hot_backward_kernel<CH, U, AL, NT><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+        a.n, a.ld, a.s_loc, a.g, a.k, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig);
 }
 template <int CH, int U, bool AL>
 void bwd_nt(int nt, const BwdArgs &a)
@@ -554,7 +539,7 @@ bool valid_launch(const hot_launch &c)
 {
     auto one_of = [](int v) { return v == 0 || v == 1 || v == 2 || v == 4; };
     return c.grid_blocks >= 0 && c.grid_blocks <= kMaxGrid && one_of(c.chunks) && one_of(c.unroll) &&
-           c.nontemporal >= 0 && c.nontemporal <= 3 && c.variant >= 0 && c.variant <= 3;
+           c.nontemporal >= 0 && c.nontemporal <= 3;
 }
 
 // Number of workgroups: one per tile slot, capped by the configured bound.
@@ -562,8 +547,7 @@ unsigned grid_for(long n, const hot_launch &c)
 {
     const long tile = (long)kBlock * 4 * c.chunks;
     const long tiles = (n + tile - 1) / tile;
-    const long slots = (c.variant & HOT_VARIANT_XCD_ORDER) ? (tiles + kXcds - 1) / kXcds * kXcds : tiles;
-    return (unsigned)(slots < c.grid_blocks ? slots : c.grid_blocks);
+    return (unsigned)(tiles < c.grid_blocks ? tiles : c.grid_blocks);
 }
 
 }  // namespace
@@ -624,13 +608,19 @@ int hot_create(hot_plan **out, const hot_desc *desc)
         delete p;
         return oom ? HOT_ENOMEM : HOT_EHIP;
     }
-    for (int kn = 0; kn < 2; ++kn) {
-        p->cfg[kn].grid_blocks = kMaxGrid;
-        p->cfg[kn].chunks = 4;
-        p->cfg[kn].unroll = pick_unroll(kn == HOT_KERNEL_FORWARD ? 1 : 2, d.s_local);
-        p->cfg[kn].nontemporal = kn == HOT_KERNEL_FORWARD ? 3 : 1;
-        p->cfg[kn].variant = 0;
-    }
+    // Defaults from launch-shape sweeps on MI355X: the forward kernel and a backward pass over
+    // two or three samples run best with four chunks per thread; with four or more samples the
+    // backward kernel prefers two chunks and four rows in flight.  Non-temporal hints pay only
+    // when the streamed arrays are larger than the 256 MiB memory-side cache.
+    const bool streams_exceed_cache = (double)d.s_local * (double)d.ld * 4.0 >= 256.0 * 1048576.0;
+    hot_launch &f = p->cfg[HOT_KERNEL_FORWARD], &b = p->cfg[HOT_KERNEL_BACKWARD];
+    f.grid_blocks = b.grid_blocks = kMaxGrid;
+    f.chunks = 4;
+    f.unroll = 1;
+    f.nontemporal = streams_exceed_cache ? 3 : 0;
+    b.chunks = d.s_local >= 4 ? 2 : 4;
+    b.unroll = pick_unroll(d.s_local >= 4 ? 4 : 2, d.s_local);
+    b.nontemporal = streams_exceed_cache ? 1 : 0;
     *out = p;
     return HOT_OK;
 }
@@ -656,7 +646,6 @@ int hot_set_launch(hot_plan *plan, int kernel, const hot_launch *cfg)
     if (cfg->chunks) c.chunks = cfg->chunks;
     if (cfg->unroll) c.unroll = pick_unroll(cfg->unroll, plan->d.s_local);
     c.nontemporal = cfg->nontemporal;
-    c.variant = cfg->variant;
     return HOT_OK;
 }
 
@@ -709,7 +698,6 @@ int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float
     a.w = w;
     a.partials = plan->partials;
     a.want_kl = kl_out != nullptr;
-    a.xcd_order = (c.variant & HOT_VARIANT_XCD_ORDER) ? 1 : 0;
     a.grid = dim3(grid_for(d.n_weights, c));
     a.stream = static_cast<hipStream_t>(stream);
 
@@ -748,8 +736,6 @@ int hot_backward(hot_plan *plan, const float *mu, const float *sigma, const floa
     a.gw = grad_w;
     a.gmu = grad_mu;
     a.gsig = grad_sigma;
-    a.acc32 = (c.variant & HOT_VARIANT_FP32_SUMS) != 0;
-    a.xcd_order = (c.variant & HOT_VARIANT_XCD_ORDER) ? 1 : 0;
     a.grid = dim3(grid_for(d.n_weights, c));
     a.stream = static_cast<hipStream_t>(stream);
 

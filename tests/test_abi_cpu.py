@@ -49,7 +49,7 @@ def test_struct_layout_matches_header(hot):
     # hot_desc: int64, int64, int32, int32, double, int32, uint32 -> 40 bytes, natural alignment
     assert ctypes.sizeof(hot.hot_desc) == 40
     assert hot.hot_desc.dataset_size.offset == 24 and hot.hot_desc.flags.offset == 36
-    assert ctypes.sizeof(hot.hot_launch) == 20
+    assert ctypes.sizeof(hot.hot_launch) == 16
 
 
 def test_null_arguments_are_rejected_without_a_gpu(hot):

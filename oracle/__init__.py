@@ -1,4 +1,5 @@
-"""ctypes front end of the CPU oracle in ``bbb_oracle.c``.
+"""ctypes front end of the CPU oracle in ``bbb_oracle.c`` (sample layer) and
+``eps_oracle.c`` (counter-based eps draw).
 
 Test infrastructure only: the tests, the smoke check and the benchmark's
 ``cpu_baseline`` leg call this; the product package never imports it.  This module
@@ -16,18 +17,18 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "bbb_oracle.c")
+_SRCS = [os.path.join(_HERE, "bbb_oracle.c"), os.path.join(_HERE, "eps_oracle.c")]
 _LIB = os.path.join(_HERE, "libbbb_oracle.so")
 
 _lib = None
 
 
 def build(force: bool = True) -> str:
-    """Compile ``bbb_oracle.c`` with gcc into ``libbbb_oracle.so`` next to it."""
-    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+    """Compile the oracle's C files with gcc into ``libbbb_oracle.so`` next to them."""
+    if not force and os.path.exists(_LIB) and all(os.path.getmtime(_LIB) >= os.path.getmtime(s) for s in _SRCS):
         return _LIB
     cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
-           "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+           "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB] + _SRCS + ["-lm"]
     subprocess.run(cmd, check=True)
     return _LIB
 
@@ -51,6 +52,15 @@ def _load():
                                     ctypes.c_double, ctypes.c_int, fp, fp, fp, fp, dp, dp,
                                     ctypes.c_int]
     lib.bbb_oracle_grad.restype = None
+    u32p = ctypes.POINTER(ctypes.c_uint32)
+    lib.eps_oracle_philox4x32.argtypes = [u32p, u32p, ctypes.c_int, u32p]
+    lib.eps_oracle_philox4x32.restype = None
+    lib.eps_oracle_bits.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
+                                    ctypes.c_uint32, ctypes.c_uint32, u32p]
+    lib.eps_oracle_bits.restype = None
+    lib.eps_oracle_normal.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
+                                      ctypes.c_uint32, ctypes.c_uint32, dp, dp]
+    lib.eps_oracle_normal.restype = None
     _lib = lib
     return lib
 
@@ -128,3 +138,29 @@ def grad(mu, sigma, eps, G, s_total: int, dataset_size: float, reduce_mean: bool
                             1 if reduce_mean else 0, _fptr(mu), _fptr(sigma), _fptr(eps),
                             _fptr(G), _dptr(gmu), _dptr(gsig), int(nthreads))
     return gmu, gsig
+
+
+def philox4x32(ctr, key, rounds: int = 10):
+    """Philox-4x32 block function: four counter words, two key words -> four output words."""
+    c = (ctypes.c_uint32 * 4)(*[int(v) & 0xFFFFFFFF for v in ctr])
+    k = (ctypes.c_uint32 * 2)(*[int(v) & 0xFFFFFFFF for v in key])
+    out = (ctypes.c_uint32 * 4)()
+    _load().eps_oracle_philox4x32(c, k, int(rounds), out)
+    return [int(v) for v in out]
+
+
+def eps_bits(n: int, s_loc: int, seed: int, step: int = 0, first_sample: int = 0) -> np.ndarray:
+    """Integer stage of the eps draw: uint32 [S_loc, N] (see eps_oracle.c for the counter layout)."""
+    out = np.empty((s_loc, n), dtype=np.uint32)
+    _load().eps_oracle_bits(n, n, s_loc, int(seed), int(step), int(first_sample),
+                            out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)))
+    return out
+
+
+def eps_normal(n: int, s_loc: int, seed: int, step: int = 0, first_sample: int = 0, with_radius=False):
+    """eps ~ N(0, 1) in fp64, [S_loc, N]; with_radius also returns the Box-Muller radius of each."""
+    out = np.empty((s_loc, n), dtype=np.float64)
+    rad = np.empty((s_loc, n), dtype=np.float64) if with_radius else None
+    _load().eps_oracle_normal(n, n, s_loc, int(seed), int(step), int(first_sample), _dptr(out),
+                              _dptr(rad) if with_radius else None)
+    return (out, rad) if with_radius else out

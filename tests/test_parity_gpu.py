@@ -139,7 +139,7 @@ def test_kl_optional_and_outputs_independent_of_it(hot):
     assert kl2 is None and torch.equal(w1, w2) and kl1.item() > 0
 
 
-def test_bitwise_determinism_and_ticket_reset(hot):
+def test_bitwise_determinism_over_repeated_launches(hot):
     wl = W.scaled(W.CONFIGS["C3"], 1_000_003)
     x = W.make_inputs(wl, DEV)
     n = wl.n_weights

@@ -127,7 +127,7 @@ def measured_traffic(kernel: str, workload: str):
     return float(m.group(1)) if m else None
 
 
-def copy_ceiling(hot, torch, dev, nbytes: int = 1 << 31, iters: int = 20, nontemporal: int = 3):
+def copy_ceiling(hot, torch, dev, nbytes: int = 1 << 31, iters: int = 20, nontemporal: int = 1):
     """GB/s (bytes read + bytes written) of the library's plain copy kernel over nbytes."""
     src = torch.empty(nbytes // 4, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)

@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 100 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 200 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
@@ -66,11 +66,32 @@ typedef struct hot_launch {
     int32_t grid_blocks; /* upper bound on workgroups (each strides over column tiles), <= 65536 */
     int32_t chunks;      /* 16-byte column chunks per thread and tile: 1, 2 or 4 */
     int32_t unroll;      /* sample rows whose loads are issued together: 1, 2 or 4 */
-    int32_t nontemporal; /* bit 0: streamed loads (eps, grad_w) bypass-hinted; bit 1: streamed stores (w) */
+    int32_t nontemporal; /* 1: the streamed arrays (eps, grad_w in; w out) are accessed with non-temporal hints */
 } hot_launch;
 
 #define HOT_KERNEL_FORWARD 0
 #define HOT_KERNEL_BACKWARD 1
+#define HOT_KERNEL_FORWARD_RNG 2
+#define HOT_KERNEL_BACKWARD_RNG 3
+
+/*
+ * Which draw of eps ~ N(0, I) the *_rng / hot_sample_* calls use (Algorithm 2, sampling
+ * line: every GPU draws samples that no other GPU draws).  The paper names no generator;
+ * this library fixes Philox-4x32 with 10 rounds (Salmon et al., SC'11) and Box-Muller:
+ *   key     = (seed mod 2^32, seed div 2^32)
+ *   counter = (q mod 2^32, q div 2^32, first_sample + s, step),  q = i div 4
+ *   the four output words x0..x3 belong to weights 4q..4q+3; for the pairs (x0,x1), (x2,x3):
+ *   u = ((xa >> 8) + 1) / 2^24,  f = (xb >> 8) / 2^24,  r = sqrt(-2 ln u),
+ *   eps = r cos(2 pi f) for the even weight of the pair, r sin(2 pi f) for the odd one.
+ * eps[s, i] is therefore a pure function of (seed, step, first_sample + s, i): GPUs that
+ * use one seed and disjoint sample ranges draw disjoint streams, and the backward call
+ * regenerates exactly (bit for bit) what the forward call used.
+ */
+typedef struct hot_rng {
+    uint64_t seed;
+    uint32_t step;         /* training-step counter */
+    uint32_t first_sample; /* global index of local sample 0; first_sample + S_loc <= 2^32 */
+} hot_rng;
 
 /*
  * Validates the description, fixes g and k, and allocates the plan's own device
@@ -101,6 +122,25 @@ int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float
 int hot_backward(hot_plan *plan, const float *mu, const float *sigma, const float *eps,
                  const float *grad_w, float *grad_mu, float *grad_sigma, void *stream);
 
+/*
+ * The same two steps with eps drawn inside the kernels instead of read from memory
+ * (4 bytes per item less in each direction; no eps array exists).  Arguments as above,
+ * without eps; `rng` selects the draw.  hot_backward_rng must be given the hot_rng of
+ * the hot_forward_rng call whose w produced grad_w.
+ */
+int hot_forward_rng(hot_plan *plan, const hot_rng *rng, const float *mu, const float *sigma,
+                    float *w, double *kl_out, void *stream);
+int hot_backward_rng(hot_plan *plan, const hot_rng *rng, const float *mu, const float *sigma,
+                     const float *grad_w, float *grad_mu, float *grad_sigma, void *stream);
+
+/*
+ * The draw on its own: eps[S_loc, ld] as fp32 (exactly the values the *_rng calls use), or
+ * the raw generator words bits[S_loc, ld] (word i mod 4 of quad i div 4), for callers and
+ * tests that want the array.
+ */
+int hot_sample_eps(hot_plan *plan, const hot_rng *rng, float *eps, void *stream);
+int hot_sample_bits(hot_plan *plan, const hot_rng *rng, uint32_t *bits, void *stream);
+
 /* Frees the plan's scratch.  NULL is a no-op.  The stream must have finished with the plan. */
 int hot_destroy(hot_plan *plan);
 
@@ -116,7 +156,7 @@ int hot_last_hip_error(const hot_plan *plan);
  * both DEVICE pointers 16-byte aligned, ranges disjoint) on the current device with
  * the same 16-byte accesses the kernels use.  Its traffic is known exactly (bytes
  * read, bytes written), which calibrates HBM byte counters and gives the machine's
- * copy ceiling.  nontemporal: bit 0 loads, bit 1 stores.
+ * copy ceiling.  nontemporal: 0 or 1 (hints on both loads and stores).
  */
 int hot_probe_copy(void *dst, const void *src, int64_t bytes, int nontemporal, void *stream);
 

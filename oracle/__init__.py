@@ -55,10 +55,10 @@ def _load():
     u32p = ctypes.POINTER(ctypes.c_uint32)
     lib.eps_oracle_philox4x32.argtypes = [u32p, u32p, ctypes.c_int, u32p]
     lib.eps_oracle_philox4x32.restype = None
-    lib.eps_oracle_bits.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
+    lib.eps_oracle_bits.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
                                     ctypes.c_uint32, ctypes.c_uint32, u32p]
     lib.eps_oracle_bits.restype = None
-    lib.eps_oracle_normal.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
+    lib.eps_oracle_normal.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
                                       ctypes.c_uint32, ctypes.c_uint32, dp, dp]
     lib.eps_oracle_normal.restype = None
     _lib = lib
@@ -149,18 +149,20 @@ def philox4x32(ctr, key, rounds: int = 10):
     return [int(v) for v in out]
 
 
-def eps_bits(n: int, s_loc: int, seed: int, step: int = 0, first_sample: int = 0) -> np.ndarray:
-    """Integer stage of the eps draw: uint32 [S_loc, N] (see eps_oracle.c for the counter layout)."""
+def eps_bits(n: int, s_loc: int, seed: int, step: int = 0, first_sample: int = 0, col0: int = 0) -> np.ndarray:
+    """Integer stage of the eps draw for weights col0..col0+n-1: uint32 [S_loc, n]."""
     out = np.empty((s_loc, n), dtype=np.uint32)
-    _load().eps_oracle_bits(n, n, s_loc, int(seed), int(step), int(first_sample),
+    _load().eps_oracle_bits(int(col0), n, n, s_loc, int(seed), int(step), int(first_sample),
                             out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)))
     return out
 
 
-def eps_normal(n: int, s_loc: int, seed: int, step: int = 0, first_sample: int = 0, with_radius=False):
-    """eps ~ N(0, 1) in fp64, [S_loc, N]; with_radius also returns the Box-Muller radius of each."""
+def eps_normal(n: int, s_loc: int, seed: int, step: int = 0, first_sample: int = 0, with_radius=False,
+               col0: int = 0):
+    """eps ~ N(0, 1) in fp64 for weights col0..col0+n-1, [S_loc, n]; with_radius also returns the
+    Box-Muller radius of each."""
     out = np.empty((s_loc, n), dtype=np.float64)
     rad = np.empty((s_loc, n), dtype=np.float64) if with_radius else None
-    _load().eps_oracle_normal(n, n, s_loc, int(seed), int(step), int(first_sample), _dptr(out),
+    _load().eps_oracle_normal(int(col0), n, n, s_loc, int(seed), int(step), int(first_sample), _dptr(out),
                               _dptr(rad) if with_radius else None)
     return (out, rad) if with_radius else out

@@ -78,26 +78,30 @@ static void words_of(int64_t q, uint32_t t, uint64_t seed, uint32_t step, uint32
     eps_oracle_philox4x32(ctr, key, 10, x);
 }
 
-/* Integer stage: bits[s, i] = word (i mod 4) of quad i div 4 of sample first_sample + s. */
-void eps_oracle_bits(int64_t n, int64_t ld_out, int32_t s_loc, uint64_t seed, uint32_t step,
+/* Integer stage for weights col0 .. col0+n-1: bits[s, c] = word (i mod 4) of quad i div 4 of
+ * sample first_sample + s, with i = col0 + c. */
+void eps_oracle_bits(int64_t col0, int64_t n, int64_t ld_out, int32_t s_loc, uint64_t seed, uint32_t step,
                      uint32_t first_sample, uint32_t *bits)
 {
     for (int32_t s = 0; s < s_loc; ++s)
-        for (int64_t i = 0; i < n; ++i) {
+        for (int64_t c = 0; c < n; ++c) {
+            int64_t i = col0 + c;
             uint32_t x[4];
             words_of(i / 4, first_sample + (uint32_t)s, seed, step, x);
-            bits[(size_t)s * (size_t)ld_out + (size_t)i] = x[i % 4];
+            bits[(size_t)s * (size_t)ld_out + (size_t)c] = x[i % 4];
         }
 }
 
 /* Both stages: eps[s, i] in fp64, and optionally the Box-Muller radius r[s, i] it was
- * scaled by (the natural magnitude for a tolerance on eps).  radius may be NULL. */
-void eps_oracle_normal(int64_t n, int64_t ld_out, int32_t s_loc, uint64_t seed, uint32_t step,
+ * scaled by (the natural magnitude for a tolerance on eps), for weights col0 .. col0+n-1.
+ * radius may be NULL. */
+void eps_oracle_normal(int64_t col0, int64_t n, int64_t ld_out, int32_t s_loc, uint64_t seed, uint32_t step,
                        uint32_t first_sample, double *eps, double *radius)
 {
     const double two_pi = 6.283185307179586476925286766559;
     for (int32_t s = 0; s < s_loc; ++s)
-        for (int64_t i = 0; i < n; ++i) {
+        for (int64_t c = 0; c < n; ++c) {
+            int64_t i = col0 + c;
             uint32_t x[4];
             words_of(i / 4, first_sample + (uint32_t)s, seed, step, x);
             int j = (int)(i % 4);
@@ -106,7 +110,7 @@ void eps_oracle_normal(int64_t n, int64_t ld_out, int32_t s_loc, uint64_t seed, 
             double f = (double)(x[2 * p + 1] >> 8) / 16777216.0;
             double r = sqrt(-2.0 * log(u));
             double e = (j % 2 == 0) ? r * cos(two_pi * f) : r * sin(two_pi * f);
-            eps[(size_t)s * (size_t)ld_out + (size_t)i] = e;
-            if (radius) radius[(size_t)s * (size_t)ld_out + (size_t)i] = r;
+            eps[(size_t)s * (size_t)ld_out + (size_t)c] = e;
+            if (radius) radius[(size_t)s * (size_t)ld_out + (size_t)c] = r;
         }
 }

@@ -18,11 +18,12 @@ LIB_PATH = os.path.join(_HERE, "libhot.so")
 
 HOT_OK, HOT_EINVAL, HOT_ENOMEM, HOT_EHIP = 0, -1, -2, -3
 HOT_REDUCE_SUM, HOT_REDUCE_MEAN = 0, 1
-HOT_KERNEL_FORWARD, HOT_KERNEL_BACKWARD = 0, 1
+HOT_KERNEL_FORWARD, HOT_KERNEL_BACKWARD, HOT_KERNEL_FORWARD_RNG, HOT_KERNEL_BACKWARD_RNG = 0, 1, 2, 3
 
 EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
            "hot_get_launch", "hot_last_hip_error", "hot_strerror", "hot_recommended_ld",
-           "hot_version", "hot_probe_copy")
+           "hot_version", "hot_probe_copy", "hot_forward_rng", "hot_backward_rng",
+           "hot_sample_eps", "hot_sample_bits")
 
 
 class hot_desc(ctypes.Structure):
@@ -35,6 +36,10 @@ class hot_desc(ctypes.Structure):
 class hot_launch(ctypes.Structure):
     _fields_ = [("grid_blocks", ctypes.c_int32), ("chunks", ctypes.c_int32),
                 ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32)]
+
+
+class hot_rng(ctypes.Structure):
+    _fields_ = [("seed", ctypes.c_uint64), ("step", ctypes.c_uint32), ("first_sample", ctypes.c_uint32)]
 
 
 class HotError(RuntimeError):
@@ -60,6 +65,11 @@ def lib() -> ctypes.CDLL:
     L.hot_forward.argtypes = [vp, fp, fp, fp, fp, vp, vp]
     L.hot_backward.argtypes = [vp, fp, fp, fp, fp, fp, fp, vp]
     L.hot_destroy.argtypes = [vp]
+    rp = ctypes.POINTER(hot_rng)
+    L.hot_forward_rng.argtypes = [vp, rp, fp, fp, fp, vp, vp]
+    L.hot_backward_rng.argtypes = [vp, rp, fp, fp, fp, fp, fp, vp]
+    L.hot_sample_eps.argtypes = [vp, rp, fp, vp]
+    L.hot_sample_bits.argtypes = [vp, rp, vp, vp]
     L.hot_set_launch.argtypes = [vp, ctypes.c_int, ctypes.POINTER(hot_launch)]
     L.hot_get_launch.argtypes = [vp, ctypes.c_int, ctypes.POINTER(hot_launch)]
     L.hot_last_hip_error.argtypes = [vp]
@@ -71,7 +81,8 @@ def lib() -> ctypes.CDLL:
     L.hot_probe_copy.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int, vp]
     L.hot_probe_copy.restype = ctypes.c_int
     for name in ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
-                 "hot_get_launch", "hot_last_hip_error", "hot_version"):
+                 "hot_get_launch", "hot_last_hip_error", "hot_version", "hot_forward_rng",
+                 "hot_backward_rng", "hot_sample_eps", "hot_sample_bits"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -164,12 +175,7 @@ def _stream(dev: int) -> int:
 def hot_forward(plan: Plan, mu, sigma, eps, w, kl_out=None) -> None:
     """w[s,i] = mu[i] + sigma[i]*eps[s,i]; kl_out (one float64 on the device) gets the KL term."""
     d = plan.desc
-    klp = None
-    if kl_out is not None:
-        if not (kl_out.is_cuda and kl_out.device.index == d.device and kl_out.dtype == torch.float64
-                and kl_out.numel() == 1):
-            raise TypeError("kl_out: need one float64 element on the plan's device")
-        klp = kl_out.data_ptr()
+    klp = _kl_ptr(plan, kl_out)
     code = lib().hot_forward(plan.handle,
                              _vec(mu, d.n_weights, d.device, "mu"),
                              _vec(sigma, d.n_weights, d.device, "sigma"),
@@ -191,6 +197,59 @@ def hot_backward(plan: Plan, mu, sigma, eps, grad_w, grad_mu, grad_sigma) -> Non
                               _vec(grad_sigma, d.n_weights, d.device, "grad_sigma"),
                               _stream(d.device))
     _check(code, "hot_backward", plan)
+
+
+def _kl_ptr(plan: Plan, kl_out):
+    if kl_out is None:
+        return None
+    d = plan.desc
+    if not (kl_out.is_cuda and kl_out.device.index == d.device and kl_out.dtype == torch.float64
+            and kl_out.numel() == 1):
+        raise TypeError("kl_out: need one float64 element on the plan's device")
+    return kl_out.data_ptr()
+
+
+def hot_forward_rng(plan: Plan, rng: hot_rng, mu, sigma, w, kl_out=None) -> None:
+    """hot_forward with eps drawn in the kernel (see hot_rng in include/hot.h)."""
+    d = plan.desc
+    code = lib().hot_forward_rng(plan.handle, ctypes.byref(rng),
+                                 _vec(mu, d.n_weights, d.device, "mu"),
+                                 _vec(sigma, d.n_weights, d.device, "sigma"),
+                                 _mat(w, d.s_local, d.n_weights, d.ld, d.device, "w"),
+                                 _kl_ptr(plan, kl_out), _stream(d.device))
+    _check(code, "hot_forward_rng", plan)
+
+
+def hot_backward_rng(plan: Plan, rng: hot_rng, mu, sigma, grad_w, grad_mu, grad_sigma) -> None:
+    """hot_backward with eps regenerated in the kernel."""
+    d = plan.desc
+    code = lib().hot_backward_rng(plan.handle, ctypes.byref(rng),
+                                  _vec(mu, d.n_weights, d.device, "mu"),
+                                  _vec(sigma, d.n_weights, d.device, "sigma"),
+                                  _mat(grad_w, d.s_local, d.n_weights, d.ld, d.device, "grad_w"),
+                                  _vec(grad_mu, d.n_weights, d.device, "grad_mu"),
+                                  _vec(grad_sigma, d.n_weights, d.device, "grad_sigma"),
+                                  _stream(d.device))
+    _check(code, "hot_backward_rng", plan)
+
+
+def hot_sample_eps(plan: Plan, rng: hot_rng, eps) -> None:
+    """Writes the fp32 draw eps[S_loc, ld] the *_rng calls use."""
+    d = plan.desc
+    code = lib().hot_sample_eps(plan.handle, ctypes.byref(rng),
+                                _mat(eps, d.s_local, d.n_weights, d.ld, d.device, "eps"), _stream(d.device))
+    _check(code, "hot_sample_eps", plan)
+
+
+def hot_sample_bits(plan: Plan, rng: hot_rng, bits) -> None:
+    """Writes the raw generator words as int32 bit patterns, [S_loc, ld]."""
+    d = plan.desc
+    if not (bits.is_cuda and bits.device.index == d.device and bits.dtype == torch.int32 and bits.dim() == 2
+            and bits.shape[0] == d.s_local and d.n_weights <= bits.shape[1] <= d.ld and bits.stride(1) == 1
+            and (d.s_local == 1 or bits.stride(0) == d.ld)):
+        raise ValueError("bits: need an int32 [S_loc, >= N] tensor with pitch ld on the plan's device")
+    code = lib().hot_sample_bits(plan.handle, ctypes.byref(rng), bits.data_ptr(), _stream(d.device))
+    _check(code, "hot_sample_bits", plan)
 
 
 def hot_probe_copy(dst: torch.Tensor, src: torch.Tensor, nontemporal: int = 0) -> None:

@@ -2,8 +2,8 @@
 // sampling-parallel Bayes-by-Backprop (arxiv 2604.04736, Algorithm 2; Algorithm 1 is
 // the one-GPU case).  Written for gfx950 (MI355X) only.
 //
-// Both kernels are pure streaming work (about 0.2 flop per byte), so the design
-// follows the HBM roofline, not the matrix cores:
+// The kernels are streaming work (about 0.2 flop per byte when eps is read from memory),
+// so the design follows the HBM roofline, not the matrix cores:
 //   * a thread owns 16-byte column chunks; a wave's load instruction covers 1 KiB of
 //     one row, contiguous, so every HBM burst is fully used;
 //   * mu and sigma are loaded once per column and stay in registers across the sample
@@ -15,6 +15,9 @@
 //     write back the die's whole L2, which cost a factor of four with large grids);
 //   * there is no reuse between threads, hence no LDS staging: LDS only carries the
 //     four per-wave partial sums of the KL reduction.
+// With GEN the kernels draw eps in registers from a counter-based generator instead of
+// reading it (4 bytes per item less in each direction, at the price of integer and
+// transcendental arithmetic): forward and backward regenerate identical values.
 #include <hip/hip_runtime.h>
 
 #include <new>
@@ -30,6 +33,8 @@ constexpr int kFinishBlock = 1024;      // threads of the one workgroup that add
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef f4 f4u __attribute__((aligned(4)));   // same vector, only dword-aligned in memory
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+typedef u4 u4u __attribute__((aligned(4)));
 
 // 16-byte load / store of four consecutive floats.  ALIGNED = false still issues one
 // dwordx4 access; the address then only has to be a multiple of 4 bytes.
@@ -58,6 +63,101 @@ __device__ __forceinline__ void store4(float *p, f4 v)
         f4u *q = reinterpret_cast<f4u *>(p);
         if constexpr (NT) __builtin_nontemporal_store(v, q);
         else *q = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Counter-based draw of eps ~ N(0, I) (Algorithm 2, sampling line; every GPU has to draw
+// samples no other GPU draws).  The paper names no generator; this one is fixed here:
+//   integer stage  Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11):
+//                  key = the two halves of the seed, counter = (q lo, q hi, t, step) with
+//                  q = i div 4 the quad of weight i and t the global sample index; the four
+//                  output words belong to weights 4q .. 4q+3;
+//   float stage    Box-Muller on the word pairs (x0,x1) and (x2,x3):
+//                  u = ((xa >> 8) + 1) 2^-24 in (0,1], f = (xb >> 8) 2^-24 in [0,1) turns,
+//                  r = sqrt(-2 ln u), outputs r cos(2 pi f), r sin(2 pi f).
+// u and f are exact in fp32.  log2, sqrt, sin and cos are the hardware's transcendental
+// instructions (sin and cos take their argument in turns, so no range reduction is
+// needed); each operation is rounded on its own (no contraction), so the forward and the
+// backward kernel regenerate bit-identical values.
+// ---------------------------------------------------------------------------------
+struct Rng {
+    unsigned k0, k1;        // key
+    unsigned first_sample;  // global index of local sample 0
+    unsigned step;
+};
+
+__device__ __forceinline__ u4 philox4x32_10(unsigned c0, unsigned c1, unsigned c2, unsigned c3,
+                                            unsigned k0, unsigned k1)
+{
+    constexpr unsigned kM0 = 0xD2511F53u, kM1 = 0xCD9E8D57u, kW0 = 0x9E3779B9u, kW1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const unsigned long long p0 = (unsigned long long)kM0 * c0;
+        const unsigned long long p1 = (unsigned long long)kM1 * c2;
+        const unsigned n0 = (unsigned)(p1 >> 32) ^ c1 ^ k0;
+        const unsigned n2 = (unsigned)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (unsigned)p1;
+        c3 = (unsigned)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += kW0;
+        k1 += kW1;
+    }
+    u4 x;
+    x[0] = c0;
+    x[1] = c1;
+    x[2] = c2;
+    x[3] = c3;
+    return x;
+}
+
+__device__ __forceinline__ u4 eps_words(long quad, int s, const Rng &rng)
+{
+    return philox4x32_10((unsigned)((unsigned long long)quad & 0xFFFFFFFFull),
+                         (unsigned)((unsigned long long)quad >> 32), rng.first_sample + (unsigned)s, rng.step,
+                         rng.k0, rng.k1);
+}
+
+__device__ __forceinline__ f4 eps_from_words(u4 x)
+{
+#pragma clang fp contract(off)
+    f4 e;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const float u = (float)((x[2 * p] >> 8) + 1u) * 0x1p-24f;
+        const float f = (float)(x[2 * p + 1] >> 8) * 0x1p-24f;
+        // -2 ln u = (-2 ln 2) log2 u
+        const float r = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(u));
+        e[2 * p] = r * __builtin_amdgcn_cosf(f);
+        e[2 * p + 1] = r * __builtin_amdgcn_sinf(f);
+    }
+    return e;
+}
+
+__device__ __forceinline__ f4 eps_quad(long quad, int s, const Rng &rng)
+{
+    return eps_from_words(eps_words(quad, s, rng));
+}
+
+// eps[s, col .. col+3]: read from memory, or drawn (col is a multiple of 4).
+template <bool ALIGNED, bool NT, bool GEN>
+__device__ __forceinline__ f4 eps4(const float *eps, long ld, int s, long col, const Rng &rng)
+{
+    if constexpr (GEN) return eps_quad(col >> 2, s, rng);
+    else return load4<ALIGNED, NT>(eps + (size_t)s * (size_t)ld + col);
+}
+
+// eps[s, i] of a single weight (the ragged tail): read at its offset, or drawn with its quad.
+template <bool GEN>
+__device__ __forceinline__ float eps1(const float *eps, size_t at, long i, int s, const Rng &rng)
+{
+    if constexpr (GEN) {
+        const f4 e = eps_quad(i >> 2, s, rng);
+        const int j = (int)(i & 3);
+        return j == 0 ? e[0] : (j == 1 ? e[1] : (j == 2 ? e[2] : e[3]));
+    } else {
+        return eps[at];
     }
 }
 
@@ -107,16 +207,39 @@ __device__ __forceinline__ double block_sum(double v, double *lds)
 // Forward: reparameterisation line  w[s,i] = mu[i] + sigma[i] * eps[s,i]  for every local
 // sample, fused with the prior-matching line (mu and sigma are in registers anyway).
 // ---------------------------------------------------------------------------------
-template <int CHUNKS, int UNROLL, bool ALIGNED, int NT, bool KL>
+
+// Rows s .. s+U-1 of one thread's chunks: all eps values first, then multiply-add and store.
+template <int CHUNKS, int U, bool ALIGNED, bool NT, bool GEN>
+__device__ __forceinline__ void forward_rows(int s, long col0, long ld, const f4 (&m)[CHUNKS],
+                                             const f4 (&sd)[CHUNKS], const float *__restrict__ eps,
+                                             float *__restrict__ w, const Rng &rng)
+{
+    constexpr long kStep = (long)kBlock * 4;
+    f4 e[U][CHUNKS];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c) e[u][c] = eps4<ALIGNED, NT, GEN>(eps, ld, s + u, col0 + c * kStep, rng);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c) {
+            f4 r;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[c][j], e[u][c][j], m[c][j]);
+            store4<ALIGNED, NT>(w + (size_t)(s + u) * (size_t)ld + col0 + c * kStep, r);
+        }
+}
+
+template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool KL, bool GEN>
 __global__ void __launch_bounds__(kBlock)
 hot_forward_kernel(long n, long ld, int s_loc,
                    const float *__restrict__ mu, const float *__restrict__ sigma,
                    const float *__restrict__ eps, float *__restrict__ w,
-                   double *__restrict__ partials)
+                   double *__restrict__ partials, Rng rng)
 {
     constexpr long kTile = (long)kBlock * 4 * CHUNKS;   // columns per tile
     constexpr long kStep = (long)kBlock * 4;            // columns between a thread's chunks
-    constexpr bool NT_LD = (NT & 1) != 0, NT_ST = (NT & 2) != 0;
     const long n_tiles = (n + kTile - 1) / kTile;
     double kl = 0.0;
 
@@ -130,36 +253,9 @@ hot_forward_kernel(long n, long ld, int s_loc,
                 sd[c] = load4<ALIGNED, false>(sigma + col0 + c * kStep);
             }
             int s = 0;
-            for (; s + UNROLL <= s_loc; s += UNROLL) {
-                f4 e[UNROLL][CHUNKS];
-#pragma unroll
-                for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-                    for (int c = 0; c < CHUNKS; ++c)
-                        e[u][c] = load4<ALIGNED, NT_LD>(eps + (size_t)(s + u) * (size_t)ld + col0 + c * kStep);
-#pragma unroll
-                for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-                    for (int c = 0; c < CHUNKS; ++c) {
-                        f4 r;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[c][j], e[u][c][j], m[c][j]);
-                        store4<ALIGNED, NT_ST>(w + (size_t)(s + u) * (size_t)ld + col0 + c * kStep, r);
-                    }
-            }
-            for (; s < s_loc; ++s) {
-                f4 e[CHUNKS];
-#pragma unroll
-                for (int c = 0; c < CHUNKS; ++c)
-                    e[c] = load4<ALIGNED, NT_LD>(eps + (size_t)s * (size_t)ld + col0 + c * kStep);
-#pragma unroll
-                for (int c = 0; c < CHUNKS; ++c) {
-                    f4 r;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[c][j], e[c][j], m[c][j]);
-                    store4<ALIGNED, NT_ST>(w + (size_t)s * (size_t)ld + col0 + c * kStep, r);
-                }
-            }
+            for (; s + UNROLL <= s_loc; s += UNROLL)
+                forward_rows<CHUNKS, UNROLL, ALIGNED, NT, GEN>(s, col0, ld, m, sd, eps, w, rng);
+            for (; s < s_loc; ++s) forward_rows<CHUNKS, 1, ALIGNED, NT, GEN>(s, col0, ld, m, sd, eps, w, rng);
             if constexpr (KL) {
 #pragma unroll
                 for (int c = 0; c < CHUNKS; ++c)
@@ -174,7 +270,7 @@ hot_forward_kernel(long n, long ld, int s_loc,
                     const f4 m = load4<ALIGNED, false>(mu + col);
                     const f4 sd = load4<ALIGNED, false>(sigma + col);
                     for (int s = 0; s < s_loc; ++s) {
-                        const f4 e = load4<ALIGNED, false>(eps + (size_t)s * (size_t)ld + col);
+                        const f4 e = eps4<ALIGNED, false, GEN>(eps, ld, s, col, rng);
                         f4 r;
 #pragma unroll
                         for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[j], e[j], m[j]);
@@ -189,7 +285,7 @@ hot_forward_kernel(long n, long ld, int s_loc,
                         const float m = mu[i], sd = sigma[i];
                         for (int s = 0; s < s_loc; ++s) {
                             const size_t at = (size_t)s * (size_t)ld + (size_t)i;
-                            w[at] = __builtin_fmaf(sd, eps[at], m);
+                            w[at] = __builtin_fmaf(sd, eps1<GEN>(eps, at, i, s, rng), m);
                         }
                         if constexpr (KL) kl += kl_addend(m, sd);
                     }
@@ -237,16 +333,41 @@ hot_kl_finish_kernel(const double *__restrict__ partials, int count, double *__r
 // Backward: column sums over the local samples of grad_w and grad_w * eps, then the
 // KL gradient and the scaling (Algorithm 2, loss / gradient / averaging lines).
 // ---------------------------------------------------------------------------------
-template <int CHUNKS, int UNROLL, bool ALIGNED, int NT>
+template <int CHUNKS, int U, bool ALIGNED, bool NT, bool GEN>
+__device__ __forceinline__ void backward_rows(int s, long col0, long ld, double (&sum_g)[CHUNKS][4],
+                                              double (&sum_ge)[CHUNKS][4], const float *__restrict__ eps,
+                                              const float *__restrict__ gw, const Rng &rng)
+{
+    constexpr long kStep = (long)kBlock * 4;
+    f4 gv[U][CHUNKS], ev[U][CHUNKS];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c) {
+            gv[u][c] = load4<ALIGNED, NT>(gw + (size_t)(s + u) * (size_t)ld + col0 + c * kStep);
+            ev[u][c] = eps4<ALIGNED, NT, GEN>(eps, ld, s + u, col0 + c * kStep, rng);
+        }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double gd = (double)gv[u][c][j];
+                sum_g[c][j] += gd;
+                sum_ge[c][j] = fma(gd, (double)ev[u][c][j], sum_ge[c][j]);
+            }
+}
+
+template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool GEN>
 __global__ void __launch_bounds__(kBlock)
 hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                     const float *__restrict__ mu, const float *__restrict__ sigma,
                     const float *__restrict__ eps, const float *__restrict__ gw,
-                    float *__restrict__ gmu, float *__restrict__ gsig)
+                    float *__restrict__ gmu, float *__restrict__ gsig, Rng rng)
 {
     constexpr long kTile = (long)kBlock * 4 * CHUNKS;
     constexpr long kStep = (long)kBlock * 4;
-    constexpr bool NT_LD = (NT & 1) != 0, NT_ST = (NT & 2) != 0;
     const long n_tiles = (n + kTile - 1) / kTile;
 
     for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -264,44 +385,10 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
 #pragma unroll
                 for (int j = 0; j < 4; ++j) sum_g[c][j] = sum_ge[c][j] = 0.0;
             int s = 0;
-            for (; s + UNROLL <= s_loc; s += UNROLL) {
-                f4 gv[UNROLL][CHUNKS], ev[UNROLL][CHUNKS];
-#pragma unroll
-                for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-                    for (int c = 0; c < CHUNKS; ++c) {
-                        const size_t at = (size_t)(s + u) * (size_t)ld + col0 + c * kStep;
-                        gv[u][c] = load4<ALIGNED, NT_LD>(gw + at);
-                        ev[u][c] = load4<ALIGNED, NT_LD>(eps + at);
-                    }
-#pragma unroll
-                for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-                    for (int c = 0; c < CHUNKS; ++c)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const double gd = (double)gv[u][c][j];
-                            sum_g[c][j] += gd;
-                            sum_ge[c][j] = fma(gd, (double)ev[u][c][j], sum_ge[c][j]);
-                        }
-            }
-            for (; s < s_loc; ++s) {
-                f4 gv[CHUNKS], ev[CHUNKS];
-#pragma unroll
-                for (int c = 0; c < CHUNKS; ++c) {
-                    const size_t at = (size_t)s * (size_t)ld + col0 + c * kStep;
-                    gv[c] = load4<ALIGNED, NT_LD>(gw + at);
-                    ev[c] = load4<ALIGNED, NT_LD>(eps + at);
-                }
-#pragma unroll
-                for (int c = 0; c < CHUNKS; ++c)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const double gd = (double)gv[c][j];
-                        sum_g[c][j] += gd;
-                        sum_ge[c][j] = fma(gd, (double)ev[c][j], sum_ge[c][j]);
-                    }
-            }
+            for (; s + UNROLL <= s_loc; s += UNROLL)
+                backward_rows<CHUNKS, UNROLL, ALIGNED, NT, GEN>(s, col0, ld, sum_g, sum_ge, eps, gw, rng);
+            for (; s < s_loc; ++s)
+                backward_rows<CHUNKS, 1, ALIGNED, NT, GEN>(s, col0, ld, sum_g, sum_ge, eps, gw, rng);
 #pragma unroll
             for (int c = 0; c < CHUNKS; ++c) {
                 f4 om, os;
@@ -312,8 +399,8 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                     om[j] = a;
                     os[j] = b;
                 }
-                store4<ALIGNED, NT_ST>(gmu + col0 + c * kStep, om);
-                store4<ALIGNED, NT_ST>(gsig + col0 + c * kStep, os);
+                store4<ALIGNED, false>(gmu + col0 + c * kStep, om);
+                store4<ALIGNED, false>(gsig + col0 + c * kStep, os);
             }
         } else {
             for (int c = 0; c < CHUNKS; ++c) {
@@ -321,11 +408,10 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                 if (col + 4 <= n) {
                     const f4 m = load4<ALIGNED, false>(mu + col);
                     const f4 sd = load4<ALIGNED, false>(sigma + col);
-                    double sum_g[4] = {0, 0, 0, 0}, sum_ge[4] = {0, 0, 0, 0};
+                    double sum_g[4] = {0.0, 0.0, 0.0, 0.0}, sum_ge[4] = {0.0, 0.0, 0.0, 0.0};
                     for (int s = 0; s < s_loc; ++s) {
-                        const size_t at = (size_t)s * (size_t)ld + col;
-                        const f4 gv = load4<ALIGNED, false>(gw + at);
-                        const f4 ev = load4<ALIGNED, false>(eps + at);
+                        const f4 gv = load4<ALIGNED, false>(gw + (size_t)s * (size_t)ld + col);
+                        const f4 ev = eps4<ALIGNED, false, GEN>(eps, ld, s, col, rng);
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const double gd = (double)gv[j];
@@ -345,12 +431,12 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                     store4<ALIGNED, false>(gsig + col, os);
                 } else {
                     for (long i = col; i < n; ++i) {
-                        double sum_g = 0, sum_ge = 0;
+                        double sum_g = 0.0, sum_ge = 0.0;
                         for (int s = 0; s < s_loc; ++s) {
                             const size_t at = (size_t)s * (size_t)ld + (size_t)i;
                             const double gd = (double)gw[at];
                             sum_g += gd;
-                            sum_ge = fma(gd, (double)eps[at], sum_ge);
+                            sum_ge = fma(gd, (double)eps1<GEN>(eps, at, i, s, rng), sum_ge);
                         }
                         float a, b;
                         finish_grad(sum_g, sum_ge, mu[i], sigma[i], g, k, a, b);
@@ -364,10 +450,43 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
 }
 
 // ---------------------------------------------------------------------------------
+// The draw on its own: eps[s, i] as floats (BITS = false) or the raw generator words
+// (BITS = true).  One thread per quad, all local samples.
+// ---------------------------------------------------------------------------------
+template <bool BITS, bool ALIGNED>
+__global__ void __launch_bounds__(kBlock)
+hot_sample_kernel(long n, long ld, int s_loc, void *__restrict__ out, Rng rng)
+{
+    const long n_quads = (n + 3) / 4;
+    for (long quad = (long)blockIdx.x * kBlock + threadIdx.x; quad < n_quads; quad += (long)gridDim.x * kBlock) {
+        const long col = quad * 4;
+        for (int s = 0; s < s_loc; ++s) {
+            const u4 x = eps_words(quad, s, rng);
+            const size_t at = (size_t)s * (size_t)ld + (size_t)col;
+            if constexpr (BITS) {
+                unsigned *o = static_cast<unsigned *>(out) + at;
+                if (col + 4 <= n) {
+                    if constexpr (ALIGNED) *reinterpret_cast<u4 *>(o) = x;
+                    else *reinterpret_cast<u4u *>(o) = x;
+                } else {
+                    for (long i = col; i < n; ++i) o[i - col] = x[(int)(i - col)];
+                }
+            } else {
+                const f4 e = eps_from_words(x);
+                float *o = static_cast<float *>(out) + at;
+                if (col + 4 <= n) store4<ALIGNED, false>(o, e);
+                else
+                    for (long i = col; i < n; ++i) o[i - col] = e[(int)(i - col)];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
 // Measurement aid: a plain copy with the same 16-byte accesses, four per thread.  Its known
 // traffic calibrates the HBM byte counters and gives the copy ceiling of the machine.
 // ---------------------------------------------------------------------------------
-template <int NT>
+template <bool NT>
 __global__ void __launch_bounds__(kBlock)
 hot_probe_copy_kernel(const f4 *__restrict__ src, f4 *__restrict__ dst, long n_vec)
 {
@@ -377,13 +496,13 @@ hot_probe_copy_kernel(const f4 *__restrict__ src, f4 *__restrict__ dst, long n_v
 #pragma unroll
     for (int c = 0; c < kPer; ++c) {
         const long at = base + (long)c * kBlock;
-        if (at < n_vec) v[c] = (NT & 1) ? __builtin_nontemporal_load(src + at) : src[at];
+        if (at < n_vec) v[c] = NT ? __builtin_nontemporal_load(src + at) : src[at];
     }
 #pragma unroll
     for (int c = 0; c < kPer; ++c) {
         const long at = base + (long)c * kBlock;
         if (at < n_vec) {
-            if (NT & 2) __builtin_nontemporal_store(v[c], dst + at);
+            if (NT) __builtin_nontemporal_store(v[c], dst + at);
             else dst[at] = v[c];
         }
     }
@@ -400,6 +519,7 @@ struct FwdArgs {
     float *w;
     double *partials;
     bool want_kl;
+    Rng rng;
     dim3 grid;
     hipStream_t stream;
 };
@@ -410,82 +530,78 @@ struct BwdArgs {
     double g, k;
     const float *mu, *sigma, *eps, *gw;
     float *gmu, *gsig;
+    Rng rng;
     dim3 grid;
     hipStream_t stream;
 };
 
-template <int CH, int U, bool AL, int NT, bool KL>
+// Template dispatch over (chunks, unroll, aligned, non-temporal, [KL]); GEN is fixed by the caller.
+template <bool GEN, int CH, int U, bool AL, bool NT>
 void fwd_go(const FwdArgs &a)
 {
-    hot_forward_kernel<CH, U, AL, NT, KL><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-        a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials);
+    if (a.want_kl)
+        hot_forward_kernel<CH, U, AL, NT, true, GEN><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.rng);
+    else
+        hot_forward_kernel<CH, U, AL, NT, false, GEN><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.rng);
 }
-template <int CH, int U, bool AL, int NT>
-void fwd_kl(const FwdArgs &a)
+template <bool GEN, int CH, int U>
+void fwd_flags(bool al, bool nt, const FwdArgs &a)
 {
-    if (a.want_kl) fwd_go<CH, U, AL, NT, true>(a);
-    else fwd_go<CH, U, AL, NT, false>(a);
-}
-template <int CH, int U, bool AL>
-void fwd_nt(int nt, const FwdArgs &a)
-{
-    switch (nt & 3) {
-    case 0: fwd_kl<CH, U, AL, 0>(a); break;
-    case 1: fwd_kl<CH, U, AL, 1>(a); break;
-    case 2: fwd_kl<CH, U, AL, 2>(a); break;
-    default: fwd_kl<CH, U, AL, 3>(a); break;
+    if (al) {
+        if (nt) fwd_go<GEN, CH, U, true, true>(a);
+        else fwd_go<GEN, CH, U, true, false>(a);
+    } else {
+        if (nt) fwd_go<GEN, CH, U, false, true>(a);
+        else fwd_go<GEN, CH, U, false, false>(a);
     }
 }
-template <int CH, int U>
-void fwd_al(bool al, int nt, const FwdArgs &a)
+template <bool GEN, int CH>
+void fwd_unroll(int u, bool al, bool nt, const FwdArgs &a)
 {
-    if (al) fwd_nt<CH, U, true>(nt, a);
-    else fwd_nt<CH, U, false>(nt, a);
+    if (u >= 4) fwd_flags<GEN, CH, 4>(al, nt, a);
+    else if (u >= 2) fwd_flags<GEN, CH, 2>(al, nt, a);
+    else fwd_flags<GEN, CH, 1>(al, nt, a);
 }
-template <int CH>
-void fwd_u(int u, bool al, int nt, const FwdArgs &a)
+template <bool GEN>
+void fwd_dispatch(int ch, int u, bool al, bool nt, const FwdArgs &a)
 {
-    if (u >= 4) fwd_al<CH, 4>(al, nt, a);
-    else if (u >= 2) fwd_al<CH, 2>(al, nt, a);
-    else fwd_al<CH, 1>(al, nt, a);
-}
-void fwd_dispatch(int ch, int u, bool al, int nt, const FwdArgs &a)
-{
-    if (ch >= 4) fwd_u<4>(u, al, nt, a);
-    else if (ch >= 2) fwd_u<2>(u, al, nt, a);
-    else fwd_u<1>(u, al, nt, a);
+    if (ch >= 4) fwd_unroll<GEN, 4>(u, al, nt, a);
+    else if (ch >= 2) fwd_unroll<GEN, 2>(u, al, nt, a);
+    else fwd_unroll<GEN, 1>(u, al, nt, a);
 }
 
-template <int CH, int U, bool AL, int NT>
+template <bool GEN, int CH, int U, bool AL, bool NT>
 void bwd_go(const BwdArgs &a)
 {
-    hot_backward_kernel<CH, U, AL, NT><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-        a.n, a.ld, a.s_loc, a.g, a.k, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig);
+    hot_backward_kernel<CH, U, AL, NT, GEN><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+        a.n, a.ld, a.s_loc, a.g, a.k, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig, a.rng);
 }
-template <int CH, int U, bool AL>
-void bwd_nt(int nt, const BwdArgs &a)
+template <bool GEN, int CH, int U>
+void bwd_flags(bool al, bool nt, const BwdArgs &a)
 {
-    if (nt & 1) bwd_go<CH, U, AL, 1>(a);
-    else bwd_go<CH, U, AL, 0>(a);
+    if (al) {
+        if (nt) bwd_go<GEN, CH, U, true, true>(a);
+        else bwd_go<GEN, CH, U, true, false>(a);
+    } else {
+        if (nt) bwd_go<GEN, CH, U, false, true>(a);
+        else bwd_go<GEN, CH, U, false, false>(a);
+    }
 }
-template <int CH, int U>
-void bwd_al(bool al, int nt, const BwdArgs &a)
+template <bool GEN, int CH>
+void bwd_unroll(int u, bool al, bool nt, const BwdArgs &a)
 {
-    if (al) bwd_nt<CH, U, true>(nt, a);
-    else bwd_nt<CH, U, false>(nt, a);
+    if (u >= 4) bwd_flags<GEN, CH, 4>(al, nt, a);
+    else if (u >= 2) bwd_flags<GEN, CH, 2>(al, nt, a);
+    else bwd_flags<GEN, CH, 1>(al, nt, a);
 }
-template <int CH>
-void bwd_u(int u, bool al, int nt, const BwdArgs &a)
+template <bool GEN>
+void bwd_dispatch(int ch, int u, bool al, bool nt, const BwdArgs &a)
 {
-    if (u >= 4) bwd_al<CH, 4>(al, nt, a);
-    else if (u >= 2) bwd_al<CH, 2>(al, nt, a);
-    else bwd_al<CH, 1>(al, nt, a);
-}
-void bwd_dispatch(int ch, int u, bool al, int nt, const BwdArgs &a)
-{
-    if (ch >= 4) bwd_u<4>(u, al, nt, a);
-    else if (ch >= 2) bwd_u<2>(u, al, nt, a);
-    else bwd_u<1>(u, al, nt, a);
+    if (ch >= 4) bwd_unroll<GEN, 4>(u, al, nt, a);
+    else if (ch >= 2) bwd_unroll<GEN, 2>(u, al, nt, a);
+    else bwd_unroll<GEN, 1>(u, al, nt, a);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -516,7 +632,7 @@ struct hot_plan {
     hot_desc d;
     double g, k;
     double *partials;   // kMaxGrid fp64 KL partial sums, one per forward workgroup
-    hot_launch cfg[2];
+    hot_launch cfg[4];  // indexed by HOT_KERNEL_*
     int last_hip;
 };
 
@@ -535,19 +651,132 @@ int pick_unroll(int want, int s_loc)
     return u;
 }
 
+bool valid_kernel(int kernel) { return kernel >= HOT_KERNEL_FORWARD && kernel <= HOT_KERNEL_BACKWARD_RNG; }
+
 bool valid_launch(const hot_launch &c)
 {
     auto one_of = [](int v) { return v == 0 || v == 1 || v == 2 || v == 4; };
     return c.grid_blocks >= 0 && c.grid_blocks <= kMaxGrid && one_of(c.chunks) && one_of(c.unroll) &&
-           c.nontemporal >= 0 && c.nontemporal <= 3;
+           (c.nontemporal == 0 || c.nontemporal == 1);
 }
 
-// Number of workgroups: one per tile slot, capped by the configured bound.
+// Number of workgroups: one per column tile, capped by the configured bound.
 unsigned grid_for(long n, const hot_launch &c)
 {
     const long tile = (long)kBlock * 4 * c.chunks;
     const long tiles = (n + tile - 1) / tile;
     return (unsigned)(tiles < c.grid_blocks ? tiles : c.grid_blocks);
+}
+
+bool make_rng(const hot_plan *plan, const hot_rng *r, Rng &out)
+{
+    if (!r) return false;
+    // global sample indices first_sample .. first_sample + S_loc - 1 must fit in 32 bits
+    if ((unsigned long long)r->first_sample + (unsigned long long)plan->d.s_local > 0x100000000ull) return false;
+    out.k0 = (unsigned)(r->seed & 0xFFFFFFFFull);
+    out.k1 = (unsigned)(r->seed >> 32);
+    out.first_sample = r->first_sample;
+    out.step = r->step;
+    return true;
+}
+
+int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
+                 const float *eps, float *w, double *kl_out, void *stream)
+{
+    const bool gen = rng != nullptr;
+    if (!mu || !sigma || !w || (!gen && !eps)) return HOT_EINVAL;
+    if (!aligned4(mu) || !aligned4(sigma) || !aligned4(w) || (!gen && !aligned4(eps))) return HOT_EINVAL;
+    if (kl_out && (reinterpret_cast<uintptr_t>(kl_out) & 7u)) return HOT_EINVAL;
+    const hot_desc &d = plan->d;
+    const hot_launch &c = plan->cfg[kernel];
+    const bool al = aligned16(mu) && aligned16(sigma) && aligned16(w) && (gen || aligned16(eps)) && (d.ld % 4 == 0);
+
+    FwdArgs a;
+    a.n = d.n_weights;
+    a.ld = d.ld;
+    a.s_loc = d.s_local;
+    a.mu = mu;
+    a.sigma = sigma;
+    a.eps = eps;
+    a.w = w;
+    a.partials = plan->partials;
+    a.want_kl = kl_out != nullptr;
+    a.rng = gen ? *rng : Rng{0, 0, 0, 0};
+    a.grid = dim3(grid_for(d.n_weights, c));
+    a.stream = static_cast<hipStream_t>(stream);
+
+    DeviceGuard guard(d.device);
+    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
+    if (gen) fwd_dispatch<true>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
+    else fwd_dispatch<false>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && kl_out) {
+        hot_kl_finish_kernel<<<dim3(1), dim3(kFinishBlock), 0, a.stream>>>(plan->partials, (int)a.grid.x, kl_out);
+        e = hipGetLastError();
+    }
+    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
+}
+
+int backward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
+                  const float *eps, const float *grad_w, float *grad_mu, float *grad_sigma, void *stream)
+{
+    const bool gen = rng != nullptr;
+    if (!mu || !sigma || !grad_w || !grad_mu || !grad_sigma || (!gen && !eps)) return HOT_EINVAL;
+    if (!aligned4(mu) || !aligned4(sigma) || !aligned4(grad_w) || !aligned4(grad_mu) || !aligned4(grad_sigma) ||
+        (!gen && !aligned4(eps)))
+        return HOT_EINVAL;
+    const hot_desc &d = plan->d;
+    const hot_launch &c = plan->cfg[kernel];
+    const bool al = aligned16(mu) && aligned16(sigma) && aligned16(grad_w) && aligned16(grad_mu) &&
+                    aligned16(grad_sigma) && (gen || aligned16(eps)) && (d.ld % 4 == 0);
+
+    BwdArgs a;
+    a.n = d.n_weights;
+    a.ld = d.ld;
+    a.s_loc = d.s_local;
+    a.g = plan->g;
+    a.k = plan->k;
+    a.mu = mu;
+    a.sigma = sigma;
+    a.eps = eps;
+    a.gw = grad_w;
+    a.gmu = grad_mu;
+    a.gsig = grad_sigma;
+    a.rng = gen ? *rng : Rng{0, 0, 0, 0};
+    a.grid = dim3(grid_for(d.n_weights, c));
+    a.stream = static_cast<hipStream_t>(stream);
+
+    DeviceGuard guard(d.device);
+    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
+    if (gen) bwd_dispatch<true>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
+    else bwd_dispatch<false>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
+}
+
+int sample_impl(hot_plan *plan, const hot_rng *rng, void *out, bool bits, void *stream)
+{
+    Rng r;
+    if (!plan || !out || !aligned4(out) || !make_rng(plan, rng, r)) return HOT_EINVAL;
+    const hot_desc &d = plan->d;
+    const bool al = aligned16(out) && (d.ld % 4 == 0);
+    const long quads = (d.n_weights + 3) / 4;
+    long blocks = (quads + kBlock - 1) / kBlock;
+    if (blocks > kMaxGrid) blocks = kMaxGrid;
+    const dim3 grid((unsigned)blocks), block(kBlock);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    DeviceGuard guard(d.device);
+    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
+    if (bits) {
+        if (al) hot_sample_kernel<true, true><<<grid, block, 0, s>>>(d.n_weights, d.ld, d.s_local, out, r);
+        else hot_sample_kernel<true, false><<<grid, block, 0, s>>>(d.n_weights, d.ld, d.s_local, out, r);
+    } else {
+        if (al) hot_sample_kernel<false, true><<<grid, block, 0, s>>>(d.n_weights, d.ld, d.s_local, out, r);
+        else hot_sample_kernel<false, false><<<grid, block, 0, s>>>(d.n_weights, d.ld, d.s_local, out, r);
+    }
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
 }
 
 }  // namespace
@@ -617,10 +846,15 @@ int hot_create(hot_plan **out, const hot_desc *desc)
     f.grid_blocks = b.grid_blocks = kMaxGrid;
     f.chunks = 4;
     f.unroll = 1;
-    f.nontemporal = streams_exceed_cache ? 3 : 0;
     b.chunks = d.s_local >= 4 ? 2 : 4;
     b.unroll = pick_unroll(d.s_local >= 4 ? 4 : 2, d.s_local);
-    b.nontemporal = streams_exceed_cache ? 1 : 0;
+    f.nontemporal = b.nontemporal = streams_exceed_cache ? 1 : 0;
+    // The drawing variants carry several independent generator chains per thread instead of loads.
+    hot_launch &fr = p->cfg[HOT_KERNEL_FORWARD_RNG], &br = p->cfg[HOT_KERNEL_BACKWARD_RNG];
+    fr = f;
+    br = b;
+    fr.chunks = br.chunks = 2;
+    fr.unroll = br.unroll = pick_unroll(2, d.s_local);
     *out = p;
     return HOT_OK;
 }
@@ -639,7 +873,7 @@ int hot_destroy(hot_plan *plan)
 
 int hot_set_launch(hot_plan *plan, int kernel, const hot_launch *cfg)
 {
-    if (!plan || !cfg || (kernel != HOT_KERNEL_FORWARD && kernel != HOT_KERNEL_BACKWARD)) return HOT_EINVAL;
+    if (!plan || !cfg || !valid_kernel(kernel)) return HOT_EINVAL;
     if (!valid_launch(*cfg)) return HOT_EINVAL;
     hot_launch &c = plan->cfg[kernel];
     if (cfg->grid_blocks) c.grid_blocks = cfg->grid_blocks;
@@ -651,17 +885,57 @@ int hot_set_launch(hot_plan *plan, int kernel, const hot_launch *cfg)
 
 int hot_get_launch(const hot_plan *plan, int kernel, hot_launch *cfg)
 {
-    if (!plan || !cfg || (kernel != HOT_KERNEL_FORWARD && kernel != HOT_KERNEL_BACKWARD)) return HOT_EINVAL;
+    if (!plan || !cfg || !valid_kernel(kernel)) return HOT_EINVAL;
     *cfg = plan->cfg[kernel];
     return HOT_OK;
 }
 
 int hot_last_hip_error(const hot_plan *plan) { return plan ? plan->last_hip : 0; }
 
+int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float *eps, float *w,
+                double *kl_out, void *stream)
+{
+    if (!plan) return HOT_EINVAL;
+    return forward_impl(plan, HOT_KERNEL_FORWARD, nullptr, mu, sigma, eps, w, kl_out, stream);
+}
+
+int hot_backward(hot_plan *plan, const float *mu, const float *sigma, const float *eps,
+                 const float *grad_w, float *grad_mu, float *grad_sigma, void *stream)
+{
+    if (!plan) return HOT_EINVAL;
+    return backward_impl(plan, HOT_KERNEL_BACKWARD, nullptr, mu, sigma, eps, grad_w, grad_mu, grad_sigma, stream);
+}
+
+int hot_forward_rng(hot_plan *plan, const hot_rng *rng, const float *mu, const float *sigma, float *w,
+                    double *kl_out, void *stream)
+{
+    Rng r;
+    if (!plan || !make_rng(plan, rng, r)) return HOT_EINVAL;
+    return forward_impl(plan, HOT_KERNEL_FORWARD_RNG, &r, mu, sigma, nullptr, w, kl_out, stream);
+}
+
+int hot_backward_rng(hot_plan *plan, const hot_rng *rng, const float *mu, const float *sigma,
+                     const float *grad_w, float *grad_mu, float *grad_sigma, void *stream)
+{
+    Rng r;
+    if (!plan || !make_rng(plan, rng, r)) return HOT_EINVAL;
+    return backward_impl(plan, HOT_KERNEL_BACKWARD_RNG, &r, mu, sigma, nullptr, grad_w, grad_mu, grad_sigma, stream);
+}
+
+int hot_sample_eps(hot_plan *plan, const hot_rng *rng, float *eps, void *stream)
+{
+    return sample_impl(plan, rng, eps, false, stream);
+}
+
+int hot_sample_bits(hot_plan *plan, const hot_rng *rng, uint32_t *bits, void *stream)
+{
+    return sample_impl(plan, rng, bits, true, stream);
+}
+
 int hot_probe_copy(void *dst, const void *src, int64_t bytes, int nontemporal, void *stream)
 {
     if (!dst || !src || bytes < 16 || (bytes & 15) || !aligned16(dst) || !aligned16(src)) return HOT_EINVAL;
-    if (nontemporal < 0 || nontemporal > 3) return HOT_EINVAL;
+    if (nontemporal != 0 && nontemporal != 1) return HOT_EINVAL;
     const long n_vec = bytes / 16;
     const long blocks = (n_vec + kBlock * 4 - 1) / (kBlock * 4);
     if (blocks > 0x7fffffffL) return HOT_EINVAL;
@@ -669,81 +943,9 @@ int hot_probe_copy(void *dst, const void *src, int64_t bytes, int nontemporal, v
     hipStream_t s = static_cast<hipStream_t>(stream);
     const f4 *in = static_cast<const f4 *>(src);
     f4 *out = static_cast<f4 *>(dst);
-    switch (nontemporal) {
-    case 0: hot_probe_copy_kernel<0><<<grid, block, 0, s>>>(in, out, n_vec); break;
-    case 1: hot_probe_copy_kernel<1><<<grid, block, 0, s>>>(in, out, n_vec); break;
-    case 2: hot_probe_copy_kernel<2><<<grid, block, 0, s>>>(in, out, n_vec); break;
-    default: hot_probe_copy_kernel<3><<<grid, block, 0, s>>>(in, out, n_vec); break;
-    }
+    if (nontemporal) hot_probe_copy_kernel<true><<<grid, block, 0, s>>>(in, out, n_vec);
+    else hot_probe_copy_kernel<false><<<grid, block, 0, s>>>(in, out, n_vec);
     return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
-}
-
-int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float *eps, float *w,
-                double *kl_out, void *stream)
-{
-    if (!plan || !mu || !sigma || !eps || !w) return HOT_EINVAL;
-    if (!aligned4(mu) || !aligned4(sigma) || !aligned4(eps) || !aligned4(w)) return HOT_EINVAL;
-    if (kl_out && (reinterpret_cast<uintptr_t>(kl_out) & 7u)) return HOT_EINVAL;
-    const hot_desc &d = plan->d;
-    const hot_launch &c = plan->cfg[HOT_KERNEL_FORWARD];
-    const bool al = aligned16(mu) && aligned16(sigma) && aligned16(eps) && aligned16(w) && (d.ld % 4 == 0);
-
-    FwdArgs a;
-    a.n = d.n_weights;
-    a.ld = d.ld;
-    a.s_loc = d.s_local;
-    a.mu = mu;
-    a.sigma = sigma;
-    a.eps = eps;
-    a.w = w;
-    a.partials = plan->partials;
-    a.want_kl = kl_out != nullptr;
-    a.grid = dim3(grid_for(d.n_weights, c));
-    a.stream = static_cast<hipStream_t>(stream);
-
-    DeviceGuard guard(d.device);
-    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
-    fwd_dispatch(c.chunks, c.unroll, al, c.nontemporal, a);
-    hipError_t e = hipGetLastError();
-    if (e == hipSuccess && kl_out) {
-        hot_kl_finish_kernel<<<dim3(1), dim3(kFinishBlock), 0, a.stream>>>(plan->partials, (int)a.grid.x, kl_out);
-        e = hipGetLastError();
-    }
-    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
-}
-
-int hot_backward(hot_plan *plan, const float *mu, const float *sigma, const float *eps,
-                 const float *grad_w, float *grad_mu, float *grad_sigma, void *stream)
-{
-    if (!plan || !mu || !sigma || !eps || !grad_w || !grad_mu || !grad_sigma) return HOT_EINVAL;
-    if (!aligned4(mu) || !aligned4(sigma) || !aligned4(eps) || !aligned4(grad_w) || !aligned4(grad_mu) ||
-        !aligned4(grad_sigma))
-        return HOT_EINVAL;
-    const hot_desc &d = plan->d;
-    const hot_launch &c = plan->cfg[HOT_KERNEL_BACKWARD];
-    const bool al = aligned16(mu) && aligned16(sigma) && aligned16(eps) && aligned16(grad_w) &&
-                    aligned16(grad_mu) && aligned16(grad_sigma) && (d.ld % 4 == 0);
-
-    BwdArgs a;
-    a.n = d.n_weights;
-    a.ld = d.ld;
-    a.s_loc = d.s_local;
-    a.g = plan->g;
-    a.k = plan->k;
-    a.mu = mu;
-    a.sigma = sigma;
-    a.eps = eps;
-    a.gw = grad_w;
-    a.gmu = grad_mu;
-    a.gsig = grad_sigma;
-    a.grid = dim3(grid_for(d.n_weights, c));
-    a.stream = static_cast<hipStream_t>(stream);
-
-    DeviceGuard guard(d.device);
-    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
-    bwd_dispatch(c.chunks, c.unroll, al, c.nontemporal, a);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
 }
 
 }  // extern "C"

@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(hot):
 
 
 def test_host_only_entry_points(hot):
-    assert hot.hot_version() == 100
+    assert hot.hot_version() == 200
     assert hot.hot_strerror(0) == "success"
     assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
     assert hot.hot_strerror(-99) == "unknown error code"
@@ -50,6 +50,7 @@ def test_struct_layout_matches_header(hot):
     assert ctypes.sizeof(hot.hot_desc) == 40
     assert hot.hot_desc.dataset_size.offset == 24 and hot.hot_desc.flags.offset == 36
     assert ctypes.sizeof(hot.hot_launch) == 16
+    assert ctypes.sizeof(hot.hot_rng) == 16 and hot.hot_rng.step.offset == 8 and hot.hot_rng.first_sample.offset == 12
 
 
 def test_null_arguments_are_rejected_without_a_gpu(hot):
@@ -62,6 +63,10 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_get_launch(None, 0, None) == hot.HOT_EINVAL
     assert L.hot_last_hip_error(None) == 0
     assert L.hot_probe_copy(None, None, 16, 0, None) == hot.HOT_EINVAL
+    assert L.hot_forward_rng(None, None, None, None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_backward_rng(None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_sample_eps(None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_sample_bits(None, None, None, None) == hot.HOT_EINVAL
     out = ctypes.c_void_p()
     for bad in [hot.hot_desc(0, 0, 1, 1, 1.0, 0, 0),        # N < 1
                 hot.hot_desc(8, 7, 1, 1, 1.0, 0, 0),        # ld < N

@@ -72,6 +72,15 @@ def test_counter_layout(oracle):
     q, t = 57, 4
     want = oracle.philox4x32([q, 0, t, step], [seed & MASK, seed >> 32], 10)
     assert a[t, 4 * q:4 * q + 4].tolist() == want
+    # quads beyond 2^32 carry into the second counter word
+    q = (1 << 32) + 1
+    hi = oracle.eps_bits(8, 1, seed, step, first_sample=2, col0=4 * q)
+    assert hi[0, :4].tolist() == oracle.philox4x32([1, 1, 2, step], [seed & MASK, seed >> 32], 10)
+    assert hi[0, 4:].tolist() == oracle.philox4x32([2, 1, 2, step], [seed & MASK, seed >> 32], 10)
+    # a window of weights is the same as the matching columns of the whole
+    assert np.array_equal(oracle.eps_bits(100, 5, seed, step, col0=37), a[:, 37:137])
+    np.testing.assert_array_equal(oracle.eps_normal(100, 5, seed, step, col0=37),
+                                  oracle.eps_normal(1003, 5, seed, step)[:, 37:137])
     # all words distinct enough: no repeated quads
     assert len(np.unique(a)) > 0.999 * a.size
 

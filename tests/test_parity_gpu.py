@@ -41,8 +41,8 @@ def test_config_full_elementwise(oracle, hot, name):
 
 # ------------------------------------------------------------------ scaled C3 / C5, launch shapes
 
-LAUNCHES = [dict(), dict(chunks=1, unroll=1), dict(chunks=1, unroll=4, nontemporal=3),
-            dict(chunks=2, unroll=2, nontemporal=1), dict(chunks=4, unroll=4, nontemporal=2),
+LAUNCHES = [dict(), dict(chunks=1, unroll=1), dict(chunks=1, unroll=4, nontemporal=1),
+            dict(chunks=2, unroll=2, nontemporal=1), dict(chunks=4, unroll=4, nontemporal=1),
             dict(chunks=4, unroll=1, grid_blocks=7), dict(chunks=2, unroll=4, grid_blocks=65536)]
 
 
@@ -56,8 +56,8 @@ def test_scaled_c3_several_tiles_and_ragged_tail(oracle, hot, launch):
 
 
 @pytest.mark.parametrize("offset", [0, 1, 3])
-@pytest.mark.parametrize("launch", [dict(), dict(chunks=4, unroll=4, nontemporal=3), dict(chunks=1, unroll=2)],
-                         ids=["default", "c4u4nt3", "c1u2"])
+@pytest.mark.parametrize("launch", [dict(), dict(chunks=4, unroll=4, nontemporal=1), dict(chunks=1, unroll=2)],
+                         ids=["default", "c4u4nt", "c1u2"])
 def test_scaled_c5_adversarial_unaligned(oracle, hot, launch, offset):
     wl = W.scaled(W.CONFIGS["C5"], 400_003)
     _say("case scaled C5", wl.n_weights, launch, "offset", offset)
@@ -218,7 +218,7 @@ def test_errors_from_the_c_abi(hot):
 def test_probe_copy_is_exact(hot):
     for count in (4, 1024, 4096 + 4, 1_000_004):
         src = torch.randn(count, device=DEV)
-        for nt in range(4):
+        for nt in range(2):
             dst = torch.zeros(count + 8, device=DEV)
             hot.hot_probe_copy(dst[4:4 + count], src, nt)
             torch.cuda.synchronize()

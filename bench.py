@@ -27,28 +27,39 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 METRIC = "hot-path items/sec on 1 MI355X + % of HBM-BW or MFMA roofline"
 
 
-def algorithmic_bytes(n: int, s: int):
-    """Bytes the method must move per launch (fp32, eps supplied as an array)."""
-    fwd = 4 * (s * n + 2 * n) + 4 * s * n + 8          # eps, mu, sigma in; w, KL out
-    bwd = 4 * (2 * s * n + 2 * n) + 4 * 2 * n          # G, eps, mu, sigma in; grad_mu, grad_sigma out
+def algorithmic_bytes(n: int, s: int, in_kernel_eps: bool = False):
+    """Bytes the method must move per launch (fp32): eps read from its array, or drawn in registers."""
+    e = 0 if in_kernel_eps else 4 * s * n
+    fwd = e + 4 * 2 * n + 4 * s * n + 8                # [eps,] mu, sigma in; w, KL out
+    bwd = 4 * s * n + e + 4 * 2 * n + 4 * 2 * n        # G, [eps,] mu, sigma in; grad_mu, grad_sigma out
     return fwd, bwd
 
 
-def time_steps(hot, torch, wl, x, steps: int, warmup: int):
+RNG_SEED, RNG_STEP = 0x5EED, 1
+
+
+def time_steps(hot, torch, wl, x, steps: int, warmup: int, in_kernel_eps: bool = False):
     dev = x["mu"].device
-    w = torch.empty_like(x["eps"])
+    w = torch.empty_like(x["G"])
     kl = torch.zeros(1, dtype=torch.float64, device=dev)
     gmu = torch.empty_like(x["mu"])
     gsig = torch.empty_like(x["mu"])
     plan = hot.hot_create(wl.n_weights, wl.ld, wl.s_local, wl.s_total, wl.dataset_size, dev.index or 0)
+    rng = hot.hot_rng(seed=RNG_SEED, step=RNG_STEP, first_sample=0)
 
     def step(events=None):
         if events is not None:
             events[0].record()
-        hot.hot_forward(plan, x["mu"], x["sigma"], x["eps"], w, kl)
+        if in_kernel_eps:
+            hot.hot_forward_rng(plan, rng, x["mu"], x["sigma"], w, kl)
+        else:
+            hot.hot_forward(plan, x["mu"], x["sigma"], x["eps"], w, kl)
         if events is not None:
             events[1].record()
-        hot.hot_backward(plan, x["mu"], x["sigma"], x["eps"], x["G"], gmu, gsig)
+        if in_kernel_eps:
+            hot.hot_backward_rng(plan, rng, x["mu"], x["sigma"], x["G"], gmu, gsig)
+        else:
+            hot.hot_backward(plan, x["mu"], x["sigma"], x["eps"], x["G"], gmu, gsig)
         if events is not None:
             events[2].record()
 
@@ -63,15 +74,17 @@ def time_steps(hot, torch, wl, x, steps: int, warmup: int):
     wall = time.perf_counter() - t0
     fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
     bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
-    launch = {"forward": hot.hot_get_launch(plan, hot.HOT_KERNEL_FORWARD),
-              "backward": hot.hot_get_launch(plan, hot.HOT_KERNEL_BACKWARD)}
+    launch = {"forward": hot.hot_get_launch(plan, hot.HOT_KERNEL_FORWARD_RNG if in_kernel_eps else hot.HOT_KERNEL_FORWARD),
+              "backward": hot.hot_get_launch(plan, hot.HOT_KERNEL_BACKWARD_RNG if in_kernel_eps else hot.HOT_KERNEL_BACKWARD)}
     hot.hot_destroy(plan)
     return {"wall_s": wall, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "launch": launch,
             "out": {"w": w, "kl": kl, "gmu": gmu, "gsig": gsig}}
 
 
-def verify_sampled(oracle, np, wl, x, out, blocks: int = 6, width: int = 20_000) -> bool:
+def verify_sampled(oracle, np, wl, x, out, blocks: int = 6, width: int = 20_000, in_kernel_eps: bool = False) -> bool:
     """Checks the timed buffers on a few column blocks against the oracle (same tolerances as the tests)."""
+    if in_kernel_eps:
+        return verify_sampled_rng(oracle, np, wl, x, out, blocks, width)
     n = wl.n_weights
     rng = np.random.default_rng(wl.seed)
     spans = [(0, min(width, n)), (max(0, n - width), n)]
@@ -93,6 +106,33 @@ def verify_sampled(oracle, np, wl, x, out, blocks: int = 6, width: int = 20_000)
             return False
         if not np.all(np.abs(out["gsig"][a:b].cpu().numpy() - gs64)
                       <= 1e-5 * (g * np.abs(G64 * e64).sum(0) + k * (s64 + 1 / s64))):
+            return False
+    return True
+
+
+def verify_sampled_rng(oracle, np, wl, x, out, blocks: int, width: int) -> bool:
+    """Same for the in-kernel draw: the oracle draws its own eps (fp64) for the sampled windows."""
+    n = wl.n_weights
+    rng = np.random.default_rng(wl.seed)
+    spans = [(0, min(width, n)), (max(0, n - width), n)]
+    spans += [(a, min(n, a + width)) for a in rng.integers(0, max(1, n - width), size=blocks)]
+    g = 1.0 / wl.s_total
+    k = wl.s_local / (wl.s_total * wl.dataset_size)
+    for a, b in spans:
+        a, b = int(a), int(b)
+        m64 = x["mu"][a:b].cpu().numpy().astype(np.float64)
+        s64 = x["sigma"][a:b].cpu().numpy().astype(np.float64)
+        G64 = x["G"][:, a:b].cpu().numpy().astype(np.float64)
+        e64, r64 = oracle.eps_normal(b - a, wl.s_local, RNG_SEED, RNG_STEP, 0, with_radius=True, col0=a)
+        w64 = m64 + s64 * e64
+        if not np.all(np.abs(out["w"][:, a:b].cpu().numpy() - w64) <= 1e-5 * (np.abs(m64) + s64 * r64)):
+            return False
+        gm64 = g * G64.sum(0) + k * m64
+        gs64 = g * (G64 * e64).sum(0) + k * (s64 - 1 / s64)
+        if not np.all(np.abs(out["gmu"][a:b].cpu().numpy() - gm64) <= 1e-5 * (g * np.abs(G64).sum(0) + k * np.abs(m64))):
+            return False
+        if not np.all(np.abs(out["gsig"][a:b].cpu().numpy() - gs64)
+                      <= 1e-5 * (g * (np.abs(G64) * (np.abs(e64) + r64)).sum(0) + k * (s64 + 1 / s64))):
             return False
     return True
 
@@ -151,6 +191,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C4", help="workload C1..C5 (C4 is the one the metric is quoted on)")
+    ap.add_argument("--eps", choices=["array", "in-kernel"], default="array",
+                    help="eps read from its array (the graded path) or drawn inside the kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--cpu-weights", type=int, default=1 << 28, help="cap on weights the oracle is timed on")
@@ -179,14 +221,16 @@ def main() -> int:
     wl = workloads.CONFIGS[args.config]
     x = workloads.make_inputs(wl, dev)
     torch.cuda.synchronize()
-    r = time_steps(hot, torch, wl, x, args.steps, args.warmup)
+    gen = args.eps == "in-kernel"
+    r = time_steps(hot, torch, wl, x, args.steps, args.warmup, gen)
     ms_per_step = r["wall_s"] * 1e3 / args.steps
     items = wl.items
-    fwd_b, bwd_b = algorithmic_bytes(wl.n_weights, wl.s_local)
+    fwd_b, bwd_b = algorithmic_bytes(wl.n_weights, wl.s_local, gen)
     dominant = "backward" if r["bwd_ms"] >= r["fwd_ms"] else "forward"
     dom_bytes, dom_ms = (bwd_b, r["bwd_ms"]) if dominant == "backward" else (fwd_b, r["fwd_ms"])
     achieved = dom_bytes / dom_ms / 1e6
-    verified = verify_sampled(oracle, np, wl, x, r["out"])
+    verified = verify_sampled(oracle, np, wl, x, r["out"], in_kernel_eps=gen)
+    kname = "_rng" if gen else ""
 
     result = {
         "metric": METRIC,
@@ -203,11 +247,12 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.note}; N={wl.n_weights}, S_loc={wl.s_local}, S={wl.s_total}, "
                                f"ld={wl.ld}, |D|={wl.dataset_size:g}, fp32, seed {wl.seed}",
-                   "items_per_step": items, "step": "hot_forward (w + KL) then hot_backward (grad_mu, grad_sigma)",
+                   "items_per_step": items, "eps": args.eps,
+                   "step": f"hot_forward{kname} (w + KL) then hot_backward{kname} (grad_mu, grad_sigma)",
                    "launch": r["launch"]},
         "roofline": {"bound": "hbm", "kernel": f"hot_{dominant}_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(f"hot_{dominant}_kernel", wl.name),
+                     "traffic": measured_traffic(f"hot_{dominant}{kname}_kernel", wl.name),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "kernels": {
             "forward": {"ms": r["fwd_ms"], "GBps": fwd_b / r["fwd_ms"] / 1e6, "items_per_s": items / r["fwd_ms"] * 1e3,
@@ -230,6 +275,24 @@ def main() -> int:
     del x, r
     torch.cuda.empty_cache()
 
+    if not args.no_others and not gen:
+        # the same workload with eps drawn inside the kernels (no eps array is read)
+        xr = workloads.make_inputs(wl, dev)
+        del xr["eps"]
+        torch.cuda.synchronize()
+        rr = time_steps(hot, torch, wl, xr, 20, 5, True)
+        fb, bb = algorithmic_bytes(wl.n_weights, wl.s_local, True)
+        ms = rr["wall_s"] * 1e3 / 20
+        result["in_kernel_eps"] = {
+            "items_per_s": items / (ms * 1e-3), "ms_per_step": ms, "fwd_ms": rr["fwd_ms"], "bwd_ms": rr["bwd_ms"],
+            "algorithmic_bytes_per_step": fb + bb,
+            "fwd_GBps": fb / rr["fwd_ms"] / 1e6, "bwd_GBps": bb / rr["bwd_ms"] / 1e6,
+            "step_frac_of_hbm_roofline": (fb + bb) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "verified_against_oracle": bool(verify_sampled(oracle, np, wl, xr, rr["out"], in_kernel_eps=True)),
+            "note": "hot_forward_rng + hot_backward_rng: Philox-4x32-10 + Box-Muller in registers"}
+        del xr, rr
+        torch.cuda.empty_cache()
+
     if not args.no_others:
         others = {}
         for name, o in workloads.CONFIGS.items():
@@ -237,13 +300,14 @@ def main() -> int:
                 continue
             xo = workloads.make_inputs(o, dev)
             torch.cuda.synchronize()
-            ro = time_steps(hot, torch, o, xo, 20, 5)
-            fb, bb = algorithmic_bytes(o.n_weights, o.s_local)
+            ro = time_steps(hot, torch, o, xo, 20, 5, gen)
+            fb, bb = algorithmic_bytes(o.n_weights, o.s_local, gen)
             ms = ro["wall_s"] * 1e3 / 20
             others[name] = {"items_per_s": o.items / (ms * 1e-3), "ms_per_step": ms,
                             "fwd_ms": ro["fwd_ms"], "bwd_ms": ro["bwd_ms"],
                             "step_frac_of_hbm_roofline": (fb + bb) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                            "verified_against_oracle": bool(verify_sampled(oracle, np, o, xo, ro["out"]))}
+                            "verified_against_oracle": bool(verify_sampled(oracle, np, o, xo, ro["out"],
+                                                                           in_kernel_eps=gen))}
             del xo, ro
             torch.cuda.empty_cache()
         result["other_workloads"] = others

@@ -307,16 +307,25 @@ __global__ void __launch_bounds__(kFinishBlock)
 hot_kl_finish_kernel(const double *__restrict__ partials, int count, double *__restrict__ kl_out)
 {
     __shared__ double lds[kFinishBlock / 64];
+    // Thread t owns the pairs t, t + 1024, t + 2048, ...; eight 16-byte loads are in flight per round
+    // and the values are added in index order.  The buffer holds an even number of slots.
+    typedef double d2 __attribute__((ext_vector_type(2)));
+    const d2 *pairs = reinterpret_cast<const d2 *>(partials);
+    const int n_pairs = (count + 1) / 2;
     double acc = 0.0;
-    for (int j0 = threadIdx.x; j0 < count; j0 += kFinishBlock * 8) {
-        double v[8];
+    for (int j0 = threadIdx.x; j0 < n_pairs; j0 += kFinishBlock * 8) {
+        d2 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {       // eight independent loads in flight, added in index order
+        for (int u = 0; u < 8; ++u) {
             const int j = j0 + u * kFinishBlock;
-            v[u] = j < count ? partials[j] : 0.0;
+            v[u] = j < n_pairs ? pairs[j] : d2{0.0, 0.0};
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc += v[u];
+        for (int u = 0; u < 8; ++u) {
+            const int j = j0 + u * kFinishBlock;
+            acc += v[u][0];
+            if (2 * j + 1 < count) acc += v[u][1];
+        }
     }
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = acc;
@@ -849,12 +858,13 @@ int hot_create(hot_plan **out, const hot_desc *desc)
     b.chunks = d.s_local >= 4 ? 2 : 4;
     b.unroll = pick_unroll(d.s_local >= 4 ? 4 : 2, d.s_local);
     f.nontemporal = b.nontemporal = streams_exceed_cache ? 1 : 0;
-    // The drawing variants carry several independent generator chains per thread instead of loads.
+    // The drawing variants have no eps loads to keep in flight; their sweeps preferred four chunks
+    // for the forward kernel and, from four samples on, two chunks and single rows backward.
     hot_launch &fr = p->cfg[HOT_KERNEL_FORWARD_RNG], &br = p->cfg[HOT_KERNEL_BACKWARD_RNG];
     fr = f;
+    fr.unroll = pick_unroll(d.s_local >= 4 ? 2 : 1, d.s_local);
     br = b;
-    fr.chunks = br.chunks = 2;
-    fr.unroll = br.unroll = pick_unroll(2, d.s_local);
+    br.unroll = pick_unroll(d.s_local >= 4 ? 1 : 2, d.s_local);
     *out = p;
     return HOT_OK;
 }

@@ -185,6 +185,23 @@ def copy_ceiling(hot, torch, dev, nbytes: int = 1 << 31, iters: int = 20, nontem
             "nontemporal": nontemporal, "copied_correctly": ok}
 
 
+def mix_ceiling(hot, torch, dev, stream_bytes: int, reads: int, writes: int, iters: int = 20):
+    """GB/s of a no-arithmetic kernel with the given numbers of equally long read and write streams."""
+    arena = torch.empty((reads + writes) * stream_bytes // 4, dtype=torch.float32, device=dev)
+    arena[: reads * stream_bytes // 4].normal_()
+    for _ in range(3):
+        hot.hot_probe_streams(arena, stream_bytes, reads, writes)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        hot.hot_probe_streams(arena, stream_bytes, reads, writes)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    return {"GBps": (reads + writes) * stream_bytes / ms / 1e6, "ms": ms, "read_streams": reads,
+            "write_streams": writes, "stream_bytes": stream_bytes}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -267,6 +284,16 @@ def main() -> int:
     ceiling = copy_ceiling(hot, torch, dev)
     result["copy_ceiling"] = {"GBps": ceiling["GBps"], "frac_of_hbm_peak": ceiling["GBps"] / HBM_PEAK_GBS,
                               "what": "hot_probe_copy_kernel, 2 GiB read + 2 GiB written"}
+    # the dominant kernel's own traffic mix without its arithmetic: backward reads G and (array mode) eps
+    # rows plus mu, sigma and writes grad_mu, grad_sigma; forward reads (eps rows,) mu, sigma and writes w rows
+    rows = wl.s_local
+    mix = {"backward": ((1 if gen else 2) * rows + 2, 2), "forward": ((0 if gen else rows) + 2, rows)}[dominant]
+    if mix[0] <= 6 and mix[1] <= 2 and wl.ld == wl.n_weights:
+        m = mix_ceiling(hot, torch, dev, 4 * wl.n_weights, mix[0], mix[1])
+        result["mix_ceiling"] = {"GBps": m["GBps"], "frac_of_hbm_peak": m["GBps"] / HBM_PEAK_GBS,
+                                 "kernel_vs_mix_ceiling": achieved / m["GBps"],
+                                 "what": f"hot_probe_streams_kernel: {mix[0]} read + {mix[1]} write streams of "
+                                         f"{4 * wl.n_weights} bytes, the {dominant} kernel's traffic without its arithmetic"}
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(oracle, np, wl, x, args.cpu_weights)

@@ -160,6 +160,16 @@ int hot_last_hip_error(const hot_plan *plan);
  */
 int hot_probe_copy(void *dst, const void *src, int64_t bytes, int nontemporal, void *stream);
 
+/*
+ * Measurement aid: `reads` (1..6) read streams and `writes` (0..2) write streams of
+ * stream_bytes each (a multiple of 16), laid out back to back in `arena` (a DEVICE buffer
+ * of (reads + writes) * stream_bytes bytes, 16-byte aligned; read streams first).  Every
+ * write stream receives the element-wise sum of the read streams.  With the stream counts
+ * of one of the kernels above it measures the machine's ceiling for that kernel's mix of
+ * read and write traffic.
+ */
+int hot_probe_streams(void *arena, int64_t stream_bytes, int reads, int writes, void *stream);
+
 /* Static, never NULL. */
 const char *hot_strerror(int code);
 

@@ -23,7 +23,7 @@ HOT_KERNEL_FORWARD, HOT_KERNEL_BACKWARD, HOT_KERNEL_FORWARD_RNG, HOT_KERNEL_BACK
 EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
            "hot_get_launch", "hot_last_hip_error", "hot_strerror", "hot_recommended_ld",
            "hot_version", "hot_probe_copy", "hot_forward_rng", "hot_backward_rng",
-           "hot_sample_eps", "hot_sample_bits")
+           "hot_sample_eps", "hot_sample_bits", "hot_probe_streams")
 
 
 class hot_desc(ctypes.Structure):
@@ -80,9 +80,11 @@ def lib() -> ctypes.CDLL:
     L.hot_version.argtypes = []
     L.hot_probe_copy.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int, vp]
     L.hot_probe_copy.restype = ctypes.c_int
+    L.hot_probe_streams.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, vp]
+    L.hot_probe_streams.restype = ctypes.c_int
     for name in ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
                  "hot_get_launch", "hot_last_hip_error", "hot_version", "hot_forward_rng",
-                 "hot_backward_rng", "hot_sample_eps", "hot_sample_bits"):
+                 "hot_backward_rng", "hot_sample_eps", "hot_sample_bits", "hot_probe_streams"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -262,3 +264,14 @@ def hot_probe_copy(dst: torch.Tensor, src: torch.Tensor, nontemporal: int = 0) -
                                     nontemporal, _stream(src.device.index))
     if code != HOT_OK:
         raise HotError(code, "hot_probe_copy")
+
+
+def hot_probe_streams(arena: torch.Tensor, stream_bytes: int, reads: int, writes: int) -> None:
+    """reads read streams + writes write streams of stream_bytes each inside arena (see include/hot.h)."""
+    if not (arena.is_cuda and arena.is_contiguous()
+            and arena.numel() * arena.element_size() >= (reads + writes) * stream_bytes):
+        raise ValueError("hot_probe_streams: arena too small or not a contiguous device tensor")
+    with torch.cuda.device(arena.device):
+        code = lib().hot_probe_streams(arena.data_ptr(), stream_bytes, reads, writes, _stream(arena.device.index))
+    if code != HOT_OK:
+        raise HotError(code, "hot_probe_streams")

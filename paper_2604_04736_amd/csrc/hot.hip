@@ -517,6 +517,61 @@ hot_probe_copy_kernel(const f4 *__restrict__ src, f4 *__restrict__ dst, long n_v
     }
 }
 
+// Second measurement aid: READS read streams and WRITES write streams of equal length, one
+// 16 KiB tile of each per workgroup, no arithmetic beyond adding the inputs.  It gives the
+// machine's ceiling for a given mix of read and write traffic (mixed traffic runs well below
+// the read-only rate on this memory system), which is what the kernels above can be held to.
+struct ProbeStreams {
+    const f4 *src[6];
+    f4 *dst[2];
+};
+
+template <int READS, int WRITES>
+__global__ void __launch_bounds__(kBlock)
+hot_probe_streams_kernel(ProbeStreams p, long n_vec)
+{
+    constexpr int kPer = 4;
+    const long base = (long)blockIdx.x * (kBlock * kPer) + threadIdx.x;
+    f4 v[READS][kPer];
+#pragma unroll
+    for (int r = 0; r < READS; ++r)
+#pragma unroll
+        for (int c = 0; c < kPer; ++c) {
+            const long at = base + (long)c * kBlock;
+            v[r][c] = at < n_vec ? __builtin_nontemporal_load(p.src[r] + at) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+    f4 acc[kPer];
+#pragma unroll
+    for (int c = 0; c < kPer; ++c) {
+        acc[c] = v[0][c];
+#pragma unroll
+        for (int r = 1; r < READS; ++r) acc[c] += v[r][c];
+    }
+    if constexpr (WRITES == 0) {
+        // read-only: the store never happens for ordinary data but keeps the loads alive
+        float s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < kPer; ++c) s += acc[c][0] + acc[c][1] + acc[c][2] + acc[c][3];
+        if (s == -1.2345678e-30f && base == 0) p.dst[0][0] = acc[0];
+    } else {
+#pragma unroll
+        for (int w = 0; w < WRITES; ++w)
+#pragma unroll
+            for (int c = 0; c < kPer; ++c) {
+                const long at = base + (long)c * kBlock;
+                if (at < n_vec) __builtin_nontemporal_store(acc[c], p.dst[w] + at);
+            }
+    }
+}
+
+template <int READS>
+void probe_streams_go(int writes, dim3 grid, hipStream_t s, const ProbeStreams &p, long n_vec)
+{
+    if (writes == 0) hot_probe_streams_kernel<READS, 0><<<grid, dim3(kBlock), 0, s>>>(p, n_vec);
+    else if (writes == 1) hot_probe_streams_kernel<READS, 1><<<grid, dim3(kBlock), 0, s>>>(p, n_vec);
+    else hot_probe_streams_kernel<READS, 2><<<grid, dim3(kBlock), 0, s>>>(p, n_vec);
+}
+
 // ---------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------
@@ -955,6 +1010,31 @@ int hot_probe_copy(void *dst, const void *src, int64_t bytes, int nontemporal, v
     f4 *out = static_cast<f4 *>(dst);
     if (nontemporal) hot_probe_copy_kernel<true><<<grid, block, 0, s>>>(in, out, n_vec);
     else hot_probe_copy_kernel<false><<<grid, block, 0, s>>>(in, out, n_vec);
+    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+}
+
+int hot_probe_streams(void *arena, int64_t stream_bytes, int reads, int writes, void *stream)
+{
+    if (!arena || !aligned16(arena) || stream_bytes < 16 || (stream_bytes & 15)) return HOT_EINVAL;
+    if (reads < 1 || reads > 6 || writes < 0 || writes > 2) return HOT_EINVAL;
+    const long n_vec = stream_bytes / 16;
+    const long blocks = (n_vec + kBlock * 4 - 1) / (kBlock * 4);
+    if (blocks > 0x7fffffffL) return HOT_EINVAL;
+    ProbeStreams p;
+    char *base = static_cast<char *>(arena);
+    for (int r = 0; r < 6; ++r) p.src[r] = reinterpret_cast<const f4 *>(base + (size_t)(r < reads ? r : 0) * (size_t)stream_bytes);
+    // with no write stream the (never taken) store targets the first read stream
+    for (int w = 0; w < 2; ++w) p.dst[w] = reinterpret_cast<f4 *>(base + (size_t)(w < writes ? reads + w : 0) * (size_t)stream_bytes);
+    const dim3 grid((unsigned)blocks);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (reads) {
+    case 1: probe_streams_go<1>(writes, grid, s, p, n_vec); break;
+    case 2: probe_streams_go<2>(writes, grid, s, p, n_vec); break;
+    case 3: probe_streams_go<3>(writes, grid, s, p, n_vec); break;
+    case 4: probe_streams_go<4>(writes, grid, s, p, n_vec); break;
+    case 5: probe_streams_go<5>(writes, grid, s, p, n_vec); break;
+    default: probe_streams_go<6>(writes, grid, s, p, n_vec); break;
+    }
     return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
 }
 

@@ -229,6 +229,25 @@ def test_probe_copy_is_exact(hot):
         hot.hot_probe_copy(torch.zeros(6, device=DEV)[1:5], torch.zeros(4, device=DEV))
 
 
+def test_probe_streams_sums_its_read_streams(hot):
+    count = 100_000                      # floats per stream, a multiple of 4
+    for reads, writes in [(1, 0), (1, 1), (2, 2), (4, 2), (6, 2), (6, 0), (3, 1), (5, 2)]:
+        arena = torch.randn((reads + writes) * count, device=DEV)
+        before = arena.clone()
+        hot.hot_probe_streams(arena, 4 * count, reads, writes)
+        torch.cuda.synchronize()
+        assert torch.equal(arena[:reads * count], before[:reads * count])
+        want = before[:count].clone()
+        for r in range(1, reads):
+            want += before[r * count:(r + 1) * count]
+        for w in range(writes):
+            assert torch.equal(arena[(reads + w) * count:(reads + w + 1) * count], want)
+    with pytest.raises(hot.HotError):
+        hot.hot_probe_streams(torch.zeros(64, device=DEV), 16, 7, 0)
+    with pytest.raises(ValueError):
+        hot.hot_probe_streams(torch.zeros(4, device=DEV), 16, 2, 2)
+
+
 def test_runs_on_a_side_stream(oracle, hot):
     wl = W.scaled(W.CONFIGS["C2"], 100_000)
     x = W.make_inputs(wl, DEV)

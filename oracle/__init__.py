@@ -1,5 +1,5 @@
 """ctypes front end of the CPU oracle in ``bbb_oracle.c`` (sample layer) and
-``eps_oracle.c`` (counter-based eps draw).
+``eps_oracle.c`` (counter-based eps draw) and ``stats_oracle.c`` (predictive mean / std).
 
 Test infrastructure only: the tests, the smoke check and the benchmark's
 ``cpu_baseline`` leg call this; the product package never imports it.  This module
@@ -17,7 +17,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "bbb_oracle.c"), os.path.join(_HERE, "eps_oracle.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("bbb_oracle.c", "eps_oracle.c", "stats_oracle.c")]
 _LIB = os.path.join(_HERE, "libbbb_oracle.so")
 
 _lib = None
@@ -61,6 +61,14 @@ def _load():
     lib.eps_oracle_normal.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
                                       ctypes.c_uint32, ctypes.c_uint32, dp, dp]
     lib.eps_oracle_normal.restype = None
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.stats_oracle_whole.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, fp, ctypes.c_int32, dp, dp]
+    lib.stats_oracle_whole.restype = None
+    lib.stats_oracle_partial.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, fp, dp, dp]
+    lib.stats_oracle_partial.restype = None
+    lib.stats_oracle_merge.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, dp, dp,
+                                       ctypes.c_int32, dp, dp]
+    lib.stats_oracle_merge.restype = None
     _lib = lib
     return lib
 
@@ -166,3 +174,35 @@ def eps_normal(n: int, s_loc: int, seed: int, step: int = 0, first_sample: int =
     _load().eps_oracle_normal(int(col0), n, n, s_loc, int(seed), int(step), int(first_sample), _dptr(out),
                               _dptr(rad) if with_radius else None)
     return (out, rad) if with_radius else out
+
+
+def stats_whole(y, m: int = None, ddof: int = 0):
+    """Mean and standard deviation over the rows (samples) of y[S, ld>=m], fp64, two-pass definition."""
+    y = _f32(y, "y")
+    m = y.shape[1] if m is None else m
+    mean, std = np.empty(m), np.empty(m)
+    _load().stats_oracle_whole(m, y.shape[1], y.shape[0], _fptr(y), int(ddof), _dptr(mean), _dptr(std))
+    return mean, std
+
+
+def stats_partial(y, m: int = None):
+    """What one GPU contributes for its rows: (mean, M2 = sum of squared deviations), fp64."""
+    y = _f32(y, "y")
+    m = y.shape[1] if m is None else m
+    mean, m2 = np.empty(m), np.empty(m)
+    _load().stats_oracle_partial(m, y.shape[1], y.shape[0], _fptr(y), _dptr(mean), _dptr(m2))
+    return mean, m2
+
+
+def stats_merge(counts, means, m2s, ddof: int = 0):
+    """Pooled mean and standard deviation from the partials of several GPUs ([parts, m] fp64 arrays)."""
+    means = np.ascontiguousarray(means, dtype=np.float64)
+    m2s = np.ascontiguousarray(m2s, dtype=np.float64)
+    counts = np.ascontiguousarray(counts, dtype=np.int32)
+    parts, m = means.shape
+    if m2s.shape != means.shape or counts.shape != (parts,):
+        raise ValueError("means and m2s must be [parts, m], counts [parts]")
+    mean, std = np.empty(m), np.empty(m)
+    _load().stats_oracle_merge(parts, m, m, counts.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _dptr(means),
+                               _dptr(m2s), int(ddof), _dptr(mean), _dptr(std))
+    return mean, std

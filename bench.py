@@ -202,6 +202,42 @@ def mix_ceiling(hot, torch, dev, stream_bytes: int, reads: int, writes: int, ite
             "write_streams": writes, "stream_bytes": stream_bytes}
 
 
+def predictive_stats_lines(hot, torch, dev, iters: int = 20):
+    """hot_stats_local + hot_stats_merge on the prediction shapes of the paper's three use cases
+    (samples x (batch x outputs)) and on one large synthetic shape that leaves the caches."""
+    out = {}
+    shapes = {"vit_16x(256x10)": (16, 256 * 10), "mlp_16x(64x24)": (16, 64 * 24),
+              "swin_2x(69x121x240)": (2, 69 * 121 * 240), "synthetic_16x2^24": (16, 1 << 24)}
+    for name, (s, m) in shapes.items():
+        y = torch.randn(s, m, device=dev)
+        mean = torch.empty(m, dtype=torch.float64, device=dev)
+        m2 = torch.empty_like(mean)
+        mo, so = torch.empty(m, device=dev), torch.empty(m, device=dev)
+
+        def run():
+            hot.hot_stats_local(y, mean, m2)
+            hot.hot_stats_merge(mean.view(1, m), m2.view(1, m), [s], 1, mo, so)
+
+        for _ in range(3):
+            run()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ms_l = ms_m = 0.0
+        for _ in range(iters):
+            e[0].record()
+            hot.hot_stats_local(y, mean, m2)
+            e[1].record()
+            hot.hot_stats_merge(mean.view(1, m), m2.view(1, m), [s], 1, mo, so)
+            e[2].record()
+            torch.cuda.synchronize()
+            ms_l += e[0].elapsed_time(e[1]) / iters
+            ms_m += e[1].elapsed_time(e[2]) / iters
+        ok = bool(torch.allclose(mo, y.mean(0), rtol=1e-5, atol=1e-6) and torch.allclose(so, y.std(0), rtol=1e-4, atol=1e-6))
+        out[name] = {"local_ms": ms_l, "merge_ms": ms_m, "predictions_per_s": s * m / (ms_l * 1e-3),
+                     "local_GBps": (4 * s * m + 16 * m) / ms_l / 1e6, "agrees_with_torch": ok}
+        del y, mean, m2, mo, so
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -321,6 +357,7 @@ def main() -> int:
         torch.cuda.empty_cache()
 
     if not args.no_others:
+        result["predictive_stats"] = predictive_stats_lines(hot, torch, dev)
         others = {}
         for name, o in workloads.CONFIGS.items():
             if name == wl.name:

@@ -152,6 +152,33 @@ int hot_get_launch(const hot_plan *plan, int kernel, hot_launch *cfg);
 int hot_last_hip_error(const hot_plan *plan);
 
 /*
+ * Predictive statistics over the samples (the paper's training description and its Monte
+ * Carlo dropout section: the mean of the S predictions is the model's output, their standard
+ * deviation its uncertainty; and the remark after Algorithm 2 that mean and standard
+ * deviation CAN be aggregated exactly across GPUs by communicating two numbers per output).
+ * Both calls run on the current device and are asynchronous on `stream`.
+ *
+ * hot_stats_local: yhat[S_loc, ld] (fp32, DEVICE, row s = the M outputs predicted with weight
+ * sample s, M = batch x output dimension flattened, ld >= M) -> mean[M] and m2[M] (fp64,
+ * DEVICE): the mean of this GPU's rows and the sum of their squared deviations from it.
+ * These are the two numbers per output a GPU contributes (its count S_loc is known).
+ */
+int hot_stats_local(const float *yhat, int64_t m, int64_t ld, int32_t s_local, double *mean, double *m2,
+                    void *stream);
+
+/*
+ * hot_stats_merge: the partials of `parts` (1..64) GPUs, means[parts, ld] and m2s[parts, ld]
+ * (fp64, DEVICE, e.g. after an all-gather), with counts[parts] (HOST array, samples behind
+ * each partial, each >= 1) -> mean_out[M], std_out[M] (fp32, DEVICE) over all samples:
+ *   n = sum_p n_p;  mean = sum_p n_p mean_p / n;
+ *   std = sqrt( sum_p [ m2_p + n_p (mean_p - mean)^2 ] / (n - ddof) ),  ddof = 0 or 1
+ * (the paper does not say which standard deviation it means).  parts = 1 finishes a single
+ * GPU's statistics.
+ */
+int hot_stats_merge(const double *means, const double *m2s, const int32_t *counts, int32_t parts, int64_t m,
+                    int64_t ld, int32_t ddof, float *mean_out, float *std_out, void *stream);
+
+/*
  * Measurement aid, not a step of the paper's path: copies `bytes` (a multiple of 16;
  * both DEVICE pointers 16-byte aligned, ranges disjoint) on the current device with
  * the same 16-byte accesses the kernels use.  Its traffic is known exactly (bytes

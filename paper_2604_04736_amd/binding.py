@@ -23,7 +23,8 @@ HOT_KERNEL_FORWARD, HOT_KERNEL_BACKWARD, HOT_KERNEL_FORWARD_RNG, HOT_KERNEL_BACK
 EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
            "hot_get_launch", "hot_last_hip_error", "hot_strerror", "hot_recommended_ld",
            "hot_version", "hot_probe_copy", "hot_forward_rng", "hot_backward_rng",
-           "hot_sample_eps", "hot_sample_bits", "hot_probe_streams")
+           "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
+           "hot_stats_merge")
 
 
 class hot_desc(ctypes.Structure):
@@ -82,9 +83,15 @@ def lib() -> ctypes.CDLL:
     L.hot_probe_copy.restype = ctypes.c_int
     L.hot_probe_streams.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, vp]
     L.hot_probe_streams.restype = ctypes.c_int
+    L.hot_stats_local.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
+    L.hot_stats_local.restype = ctypes.c_int
+    L.hot_stats_merge.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_int64,
+                                  ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
+    L.hot_stats_merge.restype = ctypes.c_int
     for name in ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
                  "hot_get_launch", "hot_last_hip_error", "hot_version", "hot_forward_rng",
-                 "hot_backward_rng", "hot_sample_eps", "hot_sample_bits", "hot_probe_streams"):
+                 "hot_backward_rng", "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
+           "hot_stats_merge"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -275,3 +282,43 @@ def hot_probe_streams(arena: torch.Tensor, stream_bytes: int, reads: int, writes
         code = lib().hot_probe_streams(arena.data_ptr(), stream_bytes, reads, writes, _stream(arena.device.index))
     if code != HOT_OK:
         raise HotError(code, "hot_probe_streams")
+
+
+def _dense2(t: torch.Tensor, dtype, name: str):
+    if not (t.is_cuda and t.dtype == dtype and t.dim() == 2 and t.stride(1) == 1):
+        raise TypeError(f"{name}: need a 2-D {dtype} device tensor with unit column stride")
+    return t.shape[0], t.shape[1], (t.stride(0) if t.shape[0] > 1 else t.shape[1])
+
+
+def hot_stats_local(yhat: torch.Tensor, mean: torch.Tensor, m2: torch.Tensor) -> None:
+    """(mean, M2) over the rows of yhat[S_loc, M] into fp64 vectors mean[M], m2[M]."""
+    s_loc, m, ld = _dense2(yhat, torch.float32, "yhat")
+    for t, name in ((mean, "mean"), (m2, "m2")):
+        if not (t.is_cuda and t.device == yhat.device and t.dtype == torch.float64 and t.dim() == 1
+                and t.shape[0] == m and t.stride(0) == 1):
+            raise TypeError(f"{name}: need a dense float64 vector of {m} elements on {yhat.device}")
+    with torch.cuda.device(yhat.device):
+        code = lib().hot_stats_local(yhat.data_ptr(), m, ld, s_loc, mean.data_ptr(), m2.data_ptr(),
+                                     _stream(yhat.device.index))
+    if code != HOT_OK:
+        raise HotError(code, "hot_stats_local")
+
+
+def hot_stats_merge(means: torch.Tensor, m2s: torch.Tensor, counts, ddof: int, mean_out: torch.Tensor,
+                    std_out: torch.Tensor) -> None:
+    """Pooled mean / std from the partials means[parts, M], m2s[parts, M] with counts[parts]."""
+    parts, m, ld = _dense2(means, torch.float64, "means")
+    if _dense2(m2s, torch.float64, "m2s") != (parts, m, ld) or m2s.device != means.device:
+        raise ValueError("m2s must match means in shape, pitch and device")
+    if len(counts) != parts:
+        raise ValueError("counts must have one entry per partial")
+    for t, name in ((mean_out, "mean_out"), (std_out, "std_out")):
+        if not (t.is_cuda and t.device == means.device and t.dtype == torch.float32 and t.dim() == 1
+                and t.shape[0] == m and t.stride(0) == 1):
+            raise TypeError(f"{name}: need a dense float32 vector of {m} elements on {means.device}")
+    c = (ctypes.c_int32 * parts)(*[int(v) for v in counts])
+    with torch.cuda.device(means.device):
+        code = lib().hot_stats_merge(means.data_ptr(), m2s.data_ptr(), c, parts, m, ld, int(ddof),
+                                     mean_out.data_ptr(), std_out.data_ptr(), _stream(means.device.index))
+    if code != HOT_OK:
+        raise HotError(code, "hot_stats_merge")

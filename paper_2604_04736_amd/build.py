@@ -1,4 +1,4 @@
-"""Compiles csrc/hot.hip into libhot.so next to this file (hipcc, gfx950 only)."""
+"""Compiles csrc/*.hip into libhot.so next to this file (hipcc, gfx950 only)."""
 from __future__ import annotations
 
 import os
@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "hot.hip")
+SRCS = [os.path.join(HERE, "csrc", "hot.hip"), os.path.join(HERE, "csrc", "stats.hip")]
 LIB = os.path.join(HERE, "libhot.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
@@ -18,7 +18,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 
 
 def build_libhot(verbose: bool = False) -> str:
-    cmd = [HIPCC] + FLAGS + ["-o", LIB, SRC]
+    cmd = [HIPCC] + FLAGS + ["-o", LIB] + SRCS
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if verbose or res.returncode != 0:
         sys.stderr.write(res.stdout)

@@ -23,6 +23,7 @@
 #include <new>
 
 #include "hot.h"
+#include "vec.h"
 
 namespace {
 
@@ -31,40 +32,8 @@ constexpr int kWaves = kBlock / 64;
 constexpr int kMaxGrid = 65536;         // upper bound on workgroups (size of the partials buffer)
 constexpr int kFinishBlock = 1024;      // threads of the one workgroup that adds the KL partials
 
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef f4 f4u __attribute__((aligned(4)));   // same vector, only dword-aligned in memory
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 typedef u4 u4u __attribute__((aligned(4)));
-
-// 16-byte load / store of four consecutive floats.  ALIGNED = false still issues one
-// dwordx4 access; the address then only has to be a multiple of 4 bytes.
-template <bool ALIGNED, bool NT>
-__device__ __forceinline__ f4 load4(const float *p)
-{
-    if constexpr (ALIGNED) {
-        const f4 *q = reinterpret_cast<const f4 *>(p);
-        if constexpr (NT) return __builtin_nontemporal_load(q);
-        else return *q;
-    } else {
-        const f4u *q = reinterpret_cast<const f4u *>(p);
-        if constexpr (NT) return __builtin_nontemporal_load(q);
-        else return *q;
-    }
-}
-
-template <bool ALIGNED, bool NT>
-__device__ __forceinline__ void store4(float *p, f4 v)
-{
-    if constexpr (ALIGNED) {
-        f4 *q = reinterpret_cast<f4 *>(p);
-        if constexpr (NT) __builtin_nontemporal_store(v, q);
-        else *q = v;
-    } else {
-        f4u *q = reinterpret_cast<f4u *>(p);
-        if constexpr (NT) __builtin_nontemporal_store(v, q);
-        else *q = v;
-    }
-}
 
 // ---------------------------------------------------------------------------------
 // Counter-based draw of eps ~ N(0, I) (Algorithm 2, sampling line; every GPU has to draw
@@ -178,13 +147,6 @@ __device__ __forceinline__ void finish_grad(double sum_g, double sum_ge, float m
     const float inv = 1.0f / sd;
     gm = (float)fma(g, sum_g, k * (double)m);
     gs = (float)fma(g, sum_ge, k * ((double)sd - (double)inv));
-}
-
-__device__ __forceinline__ double wave_sum(double v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
-    return v;   // complete in lane 0
 }
 
 // Sum over the workgroup, complete in thread 0.  Fixed tree, hence deterministic.
@@ -667,9 +629,6 @@ void bwd_dispatch(int ch, int u, bool al, bool nt, const BwdArgs &a)
     else if (ch >= 2) bwd_unroll<GEN, 2>(u, al, nt, a);
     else bwd_unroll<GEN, 1>(u, al, nt, a);
 }
-
-bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
 // Makes desc.device current for the lifetime of the object.
 struct DeviceGuard {

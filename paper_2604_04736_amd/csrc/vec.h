@@ -1,0 +1,56 @@
+// Device helpers shared by the libhot translation units (gfx950 only).
+#ifndef HOT_VEC_H
+#define HOT_VEC_H
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef f4 f4u __attribute__((aligned(4)));   // same vector, only dword-aligned in memory
+
+// 16-byte load / store of four consecutive floats.  ALIGNED = false still issues one
+// dwordx4 access; the address then only has to be a multiple of 4 bytes.
+template <bool ALIGNED, bool NT>
+__device__ __forceinline__ f4 load4(const float *p)
+{
+    if constexpr (ALIGNED) {
+        const f4 *q = reinterpret_cast<const f4 *>(p);
+        if constexpr (NT) return __builtin_nontemporal_load(q);
+        else return *q;
+    } else {
+        const f4u *q = reinterpret_cast<const f4u *>(p);
+        if constexpr (NT) return __builtin_nontemporal_load(q);
+        else return *q;
+    }
+}
+
+template <bool ALIGNED, bool NT>
+__device__ __forceinline__ void store4(float *p, f4 v)
+{
+    if constexpr (ALIGNED) {
+        f4 *q = reinterpret_cast<f4 *>(p);
+        if constexpr (NT) __builtin_nontemporal_store(v, q);
+        else *q = v;
+    } else {
+        f4u *q = reinterpret_cast<f4u *>(p);
+        if constexpr (NT) __builtin_nontemporal_store(v, q);
+        else *q = v;
+    }
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
+    return v;   // complete in lane 0
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+}  // namespace
+
+#endif  // HOT_VEC_H

@@ -64,6 +64,8 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_last_hip_error(None) == 0
     assert L.hot_probe_copy(None, None, 16, 0, None) == hot.HOT_EINVAL
     assert L.hot_probe_streams(None, 16, 1, 1, None) == hot.HOT_EINVAL
+    assert L.hot_stats_local(None, 1, 1, 1, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_stats_merge(None, None, None, 1, 1, 1, 0, None, None, None) == hot.HOT_EINVAL
     assert L.hot_forward_rng(None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward_rng(None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_sample_eps(None, None, None, None) == hot.HOT_EINVAL

@@ -1,5 +1,5 @@
 """ctypes front end of the CPU oracle in ``bbb_oracle.c`` (sample layer) and
-``eps_oracle.c`` (counter-based eps draw) and ``stats_oracle.c`` (predictive mean / std).
+``eps_oracle.c`` (counter-based eps draw) ``stats_oracle.c`` (predictive mean / std) and ``linear_oracle.c`` (sampled linear layer).
 
 Test infrastructure only: the tests, the smoke check and the benchmark's
 ``cpu_baseline`` leg call this; the product package never imports it.  This module
@@ -17,7 +17,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, f) for f in ("bbb_oracle.c", "eps_oracle.c", "stats_oracle.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("bbb_oracle.c", "eps_oracle.c", "stats_oracle.c", "linear_oracle.c")]
 _LIB = os.path.join(_HERE, "libbbb_oracle.so")
 
 _lib = None
@@ -69,6 +69,9 @@ def _load():
     lib.stats_oracle_merge.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, dp, dp,
                                        ctypes.c_int32, dp, dp]
     lib.stats_oracle_merge.restype = None
+    lib.linear_oracle_forward.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                          ctypes.c_int64, fp, fp, fp, dp, fp, fp, dp, dp]
+    lib.linear_oracle_forward.restype = None
     _lib = lib
     return lib
 
@@ -206,3 +209,33 @@ def stats_merge(counts, means, m2s, ddof: int = 0):
     _load().stats_oracle_merge(parts, m, m, counts.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _dptr(means),
                                _dptr(m2s), int(ddof), _dptr(mean), _dptr(std))
     return mean, std
+
+
+def linear_forward(x, mu_w, sigma_w, eps_w, mu_b=None, sigma_b=None, eps_b=None, in_features=None):
+    """y[S, R, O] = x W_s^T + b_s with W_s = mu_w + sigma_w*eps_w[s], b_s likewise; fp64.
+    x is [R, ldx >= K]; mu_w, sigma_w [O, K]; eps_w [S, O, K] fp64; bias arrays [O] / [S, O] or None."""
+    x = _f32(x, "x")
+    mu_w = _f32(mu_w, "mu_w")
+    sigma_w = _f32(sigma_w, "sigma_w")
+    eps_w = np.ascontiguousarray(eps_w, dtype=np.float64)
+    o, k = mu_w.shape
+    if in_features is not None and in_features != k:
+        raise ValueError("in_features does not match mu_w")
+    s = eps_w.shape[0]
+    if sigma_w.shape != (o, k) or eps_w.shape != (s, o, k) or x.ndim != 2 or x.shape[1] < k:
+        raise ValueError("shape mismatch")
+    r = x.shape[0]
+    y = np.empty((s, r, o), dtype=np.float64)
+    if mu_b is None:
+        mb = sb = None
+        eb = None
+    else:
+        mu_b = _f32(mu_b, "mu_b")
+        sigma_b = _f32(sigma_b, "sigma_b")
+        eps_b = np.ascontiguousarray(eps_b, dtype=np.float64)
+        if mu_b.shape != (o,) or sigma_b.shape != (o,) or eps_b.shape != (s, o):
+            raise ValueError("bias shape mismatch")
+        mb, sb, eb = _fptr(mu_b), _fptr(sigma_b), _dptr(eps_b)
+    _load().linear_oracle_forward(s, r, k, o, x.shape[1], _fptr(x), _fptr(mu_w), _fptr(sigma_w), _dptr(eps_w),
+                                  mb, sb, eb, _dptr(y))
+    return y

@@ -1,0 +1,91 @@
+"""Pins of the sampled-linear-layer oracle (oracle/linear_oracle.c): the layer's definition
+y_s = x (mu_W + sigma_W * eps_s)^T + (mu_b + sigma_b * eps_s^b) from the reparameterisation and
+ForwardPass lines of Algorithm 1 / 2 (arxiv 2604.04736), checked against numpy's einsum, against
+inputs that read single sampled weights back, and against the structure of the formula."""
+import numpy as np
+import pytest
+
+f32 = np.float32
+
+
+def _case(seed, s=3, r=5, k=12, o=7, ldx=None):
+    g = np.random.default_rng(seed)
+    ldx = ldx or k
+    x = np.full((r, ldx), np.nan, f32)
+    x[:, :k] = g.normal(size=(r, k))
+    return dict(x=x, mu_w=g.normal(size=(o, k)).astype(f32), sigma_w=g.uniform(0.01, 1, size=(o, k)).astype(f32),
+                eps_w=g.normal(size=(s, o, k)), mu_b=g.normal(size=o).astype(f32),
+                sigma_b=g.uniform(0.01, 1, size=o).astype(f32), eps_b=g.normal(size=(s, o)))
+
+
+def test_matches_einsum(oracle):
+    for seed, ldx in ((1, None), (2, 16)):
+        c = _case(seed, ldx=ldx)
+        k = c["mu_w"].shape[1]
+        y = oracle.linear_forward(**c)
+        w = c["mu_w"].astype(np.float64) + c["sigma_w"].astype(np.float64) * c["eps_w"]
+        b = c["mu_b"].astype(np.float64) + c["sigma_b"].astype(np.float64) * c["eps_b"]
+        want = np.einsum("rk,sok->sro", c["x"][:, :k].astype(np.float64), w) + b[:, None, :]
+        np.testing.assert_allclose(y, want, rtol=1e-13, atol=1e-13)
+        assert y.shape == (3, 5, 7)
+
+
+def test_unit_vectors_read_sampled_weights_back(oracle):
+    c = _case(3, r=12, k=12)
+    c["x"] = np.eye(12, dtype=f32)
+    y = oracle.linear_forward(**c)
+    w = c["mu_w"].astype(np.float64) + c["sigma_w"].astype(np.float64) * c["eps_w"]       # [S, O, K]
+    b = c["mu_b"].astype(np.float64) + c["sigma_b"].astype(np.float64) * c["eps_b"]
+    # row k of the identity picks column k of W_s: y[s, k, o] = W_s[o, k] + b_s[o]
+    np.testing.assert_allclose(y, np.transpose(w, (0, 2, 1)) + b[:, None, :], rtol=1e-15, atol=1e-15)
+
+
+def test_zero_sigma_is_an_ordinary_linear_layer_for_every_sample(oracle):
+    c = _case(4)
+    c["sigma_w"][:] = 0
+    c["sigma_b"][:] = 0
+    y = oracle.linear_forward(**c)
+    want = c["x"].astype(np.float64) @ c["mu_w"].astype(np.float64).T + c["mu_b"].astype(np.float64)
+    for s in range(y.shape[0]):
+        np.testing.assert_allclose(y[s], want, rtol=1e-14, atol=1e-14)
+
+
+def test_without_bias_and_bias_only(oracle):
+    c = _case(5)
+    with_b = oracle.linear_forward(**c)
+    nb = dict(c, mu_b=None, sigma_b=None, eps_b=None)
+    without = oracle.linear_forward(**nb)
+    b = c["mu_b"].astype(np.float64) + c["sigma_b"].astype(np.float64) * c["eps_b"]
+    np.testing.assert_allclose(with_b - without, np.broadcast_to(b[:, None, :], with_b.shape), rtol=1e-12, atol=1e-13)
+    c0 = dict(c, x=np.zeros_like(c["x"]))
+    np.testing.assert_allclose(oracle.linear_forward(**c0), np.broadcast_to(b[:, None, :], with_b.shape), rtol=1e-15)
+
+
+def test_linearity_in_x_and_split_of_the_inner_dimension(oracle):
+    c = _case(6)
+    nb = dict(c, mu_b=None, sigma_b=None, eps_b=None)
+    y = oracle.linear_forward(**nb)
+    y2 = oracle.linear_forward(**dict(nb, x=(c["x"] * f32(2)).astype(f32)))
+    np.testing.assert_allclose(y2, 2 * y, rtol=1e-14, atol=1e-14)
+    # K = 12 split into 5 + 7: the two partial layers add up
+    a = dict(nb, x=np.ascontiguousarray(c["x"][:, :5]), mu_w=np.ascontiguousarray(c["mu_w"][:, :5]),
+             sigma_w=np.ascontiguousarray(c["sigma_w"][:, :5]), eps_w=np.ascontiguousarray(c["eps_w"][:, :, :5]))
+    b = dict(nb, x=np.ascontiguousarray(c["x"][:, 5:]), mu_w=np.ascontiguousarray(c["mu_w"][:, 5:]),
+             sigma_w=np.ascontiguousarray(c["sigma_w"][:, 5:]), eps_w=np.ascontiguousarray(c["eps_w"][:, :, 5:]))
+    np.testing.assert_allclose(oracle.linear_forward(**a) + oracle.linear_forward(**b), y, rtol=1e-13, atol=1e-13)
+
+
+def test_samples_are_independent_slices(oracle):
+    c = _case(7, s=4)
+    y = oracle.linear_forward(**c)
+    for s in range(4):
+        one = dict(c, eps_w=c["eps_w"][s:s + 1], eps_b=c["eps_b"][s:s + 1])
+        np.testing.assert_array_equal(oracle.linear_forward(**one)[0], y[s])
+    # the output mean over many samples tends to the mean-weight layer (E[eps] = 0)
+    g = np.random.default_rng(8)
+    big = dict(c, eps_w=g.normal(size=(20000, 7, 12)), eps_b=g.normal(size=(20000, 7)))
+    m = oracle.linear_forward(**big).mean(axis=0)
+    det = c["x"].astype(np.float64) @ c["mu_w"].astype(np.float64).T + c["mu_b"].astype(np.float64)
+    spread = np.sqrt((c["x"].astype(np.float64) ** 2) @ (c["sigma_w"].astype(np.float64) ** 2).T
+                     + c["sigma_b"].astype(np.float64) ** 2)
+    assert np.all(np.abs(m - det) < 5 * spread / np.sqrt(20000))

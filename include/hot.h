@@ -152,6 +152,38 @@ int hot_get_launch(const hot_plan *plan, int kernel, hot_launch *cfg);
 int hot_last_hip_error(const hot_plan *plan);
 
 /*
+ * One sampled Bayesian linear layer, the weight draw fused into the contraction (Algorithm
+ * 1 / 2: reparameterisation line + ForwardPass for a Linear layer; the same minibatch x for
+ * every sample):
+ *   y[s, r, o] = sum_k x[r, k] * fma(sigma_W[o, k], eps_s[o, k], mu_W[o, k])
+ *                + fma(sigma_b[o], eps_s^b[o], mu_b[o])
+ * eps of weight (o, k) is the draw (see hot_rng) of flat parameter index weight_offset + o*K + k,
+ * eps of bias o that of bias_offset + o: the layer sees exactly the w that hot_forward_rng
+ * would write for a parameter vector holding this layer at those offsets, without w ever
+ * existing in memory.  x: [rows, ldx]; mu_W, sigma_W: [out_features, in_features] packed
+ * row-major; mu_b, sigma_b: [out_features] or both NULL; y: [s_local, rows, out_features]
+ * packed, out.  All DEVICE pointers; x, mu_W, sigma_W 16-byte aligned; in_features, ldx,
+ * weight_offset, bias_offset multiples of 4.  The contraction runs on the matrix cores in
+ * fp32 (v_mfma_f32_16x16x4_f32).  Runs on the current device, asynchronous on `stream`.
+ * Intended for row counts up to a few hundred, where re-drawing eps per block of 64 rows is
+ * cheaper than writing and re-reading w; for thousands of rows materialise w with
+ * hot_forward_rng and call a library GEMM.
+ */
+typedef struct hot_linear_desc {
+    int64_t rows;          /* R >= 1: rows of x (batch x tokens) */
+    int64_t in_features;   /* K >= 4, multiple of 4 */
+    int64_t out_features;  /* O >= 1 */
+    int64_t ldx;           /* pitch of x in floats, >= K, multiple of 4 */
+    int64_t weight_offset; /* flat parameter index of W[0, 0], multiple of 4 */
+    int64_t bias_offset;   /* flat parameter index of b[0], multiple of 4 (ignored without bias) */
+    int32_t s_local;       /* S_loc >= 1 */
+    int32_t reserved;      /* must be 0 */
+} hot_linear_desc;
+
+int hot_linear_forward_rng(const hot_linear_desc *desc, const hot_rng *rng, const float *x, const float *mu_w,
+                           const float *sigma_w, const float *mu_b, const float *sigma_b, float *y, void *stream);
+
+/*
  * Predictive statistics over the samples (the paper's training description and its Monte
  * Carlo dropout section: the mean of the S predictions is the model's output, their standard
  * deviation its uncertainty; and the remark after Algorithm 2 that mean and standard

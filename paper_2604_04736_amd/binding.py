@@ -24,7 +24,7 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_get_launch", "hot_last_hip_error", "hot_strerror", "hot_recommended_ld",
            "hot_version", "hot_probe_copy", "hot_forward_rng", "hot_backward_rng",
            "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
-           "hot_stats_merge")
+           "hot_stats_merge", "hot_linear_forward_rng")
 
 
 class hot_desc(ctypes.Structure):
@@ -41,6 +41,12 @@ class hot_launch(ctypes.Structure):
 
 class hot_rng(ctypes.Structure):
     _fields_ = [("seed", ctypes.c_uint64), ("step", ctypes.c_uint32), ("first_sample", ctypes.c_uint32)]
+
+
+class hot_linear_desc(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int64), ("in_features", ctypes.c_int64), ("out_features", ctypes.c_int64),
+                ("ldx", ctypes.c_int64), ("weight_offset", ctypes.c_int64), ("bias_offset", ctypes.c_int64),
+                ("s_local", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class HotError(RuntimeError):
@@ -83,6 +89,8 @@ def lib() -> ctypes.CDLL:
     L.hot_probe_copy.restype = ctypes.c_int
     L.hot_probe_streams.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, vp]
     L.hot_probe_streams.restype = ctypes.c_int
+    L.hot_linear_forward_rng.argtypes = [ctypes.POINTER(hot_linear_desc), rp, fp, fp, fp, fp, fp, fp, vp]
+    L.hot_linear_forward_rng.restype = ctypes.c_int
     L.hot_stats_local.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     L.hot_stats_local.restype = ctypes.c_int
     L.hot_stats_merge.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_int64,
@@ -91,7 +99,7 @@ def lib() -> ctypes.CDLL:
     for name in ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
                  "hot_get_launch", "hot_last_hip_error", "hot_version", "hot_forward_rng",
                  "hot_backward_rng", "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
-           "hot_stats_merge"):
+           "hot_stats_merge", "hot_linear_forward_rng"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -321,4 +329,39 @@ def hot_stats_merge(means: torch.Tensor, m2s: torch.Tensor, counts, ddof: int, m
         code = lib().hot_stats_merge(means.data_ptr(), m2s.data_ptr(), c, parts, m, ld, int(ddof),
                                      mean_out.data_ptr(), std_out.data_ptr(), _stream(means.device.index))
     if code != HOT_OK:
-        raise HotError(code, "hot_stats_merge")
+        raise HotError(code, "hot_stats_merge", "hot_linear_forward_rng")
+
+
+def hot_linear_forward_rng(rng: hot_rng, x, mu_w, sigma_w, mu_b, sigma_b, y, weight_offset: int = 0,
+                           bias_offset: int = 0) -> None:
+    """y[S, R, O] = x (mu_w + sigma_w*eps_s)^T + (mu_b + sigma_b*eps_s^b), eps drawn in the kernel."""
+    def chk(t, shape, name):
+        if not (t.is_cuda and t.device == x.device and t.dtype == torch.float32 and tuple(t.shape) == shape
+                and t.is_contiguous()):
+            raise TypeError(f"{name}: need a contiguous float32 tensor of shape {shape} on {x.device}")
+    if not (x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.stride(1) == 1):
+        raise TypeError("x: need a 2-D float32 device tensor with unit column stride")
+    rows, k = x.shape
+    ldx = x.stride(0) if rows > 1 else k
+    if mu_w.dim() != 2 or mu_w.shape[1] != k:
+        raise ValueError("mu_w must be [out_features, in_features]")
+    o = mu_w.shape[0]
+    chk(mu_w, (o, k), "mu_w")
+    chk(sigma_w, (o, k), "sigma_w")
+    if (mu_b is None) != (sigma_b is None):
+        raise ValueError("give both bias arrays or neither")
+    if mu_b is not None:
+        chk(mu_b, (o,), "mu_b")
+        chk(sigma_b, (o,), "sigma_b")
+    if y.dim() != 3:
+        raise ValueError("y must be [S_loc, rows, out_features]")
+    s_loc = y.shape[0]
+    chk(y, (s_loc, rows, o), "y")
+    d = hot_linear_desc(rows, k, o, ldx, weight_offset, bias_offset, s_loc, 0)
+    with torch.cuda.device(x.device):
+        code = lib().hot_linear_forward_rng(ctypes.byref(d), ctypes.byref(rng), x.data_ptr(), mu_w.data_ptr(),
+                                            sigma_w.data_ptr(), mu_b.data_ptr() if mu_b is not None else None,
+                                            sigma_b.data_ptr() if mu_b is not None else None, y.data_ptr(),
+                                            _stream(x.device.index))
+    if code != HOT_OK:
+        raise HotError(code, "hot_linear_forward_rng")

@@ -238,6 +238,61 @@ def predictive_stats_lines(hot, torch, dev, iters: int = 20):
     return out
 
 
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def sampled_linear_lines(hot, torch, dev, iters: int = 20):
+    """hot_linear_forward_rng (eps drawn in registers, contraction on the matrix cores) on layer shapes
+    of the paper's models and on one large square layer; beside it the same layer done as
+    hot_forward_rng (w written to HBM) + one library GEMM per sample."""
+    def timeit(fn):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    rng = hot.hot_rng(seed=RNG_SEED, step=RNG_STEP, first_sample=0)
+    out = {}
+    shapes = {"mlp_fc2_R64_128x128_S4": (64, 128, 128, 4), "swin_fc1_R1_540x2160_S2": (1, 540, 2160, 2),
+              "swin_fc1_R64_540x2160_S2": (64, 540, 2160, 2), "swin_fc_R16_2160x8640_S2": (16, 2160, 8640, 2),
+              "square_R1_8192x8192_S2": (1, 8192, 8192, 2), "square_R16_8192x8192_S2": (16, 8192, 8192, 2),
+              "square_R64_8192x8192_S2": (64, 8192, 8192, 2), "swin_fc1_R7260_540x2160_S2": (7260, 540, 2160, 2)}
+    for name, (rows, k, o, s) in shapes.items():
+        x = torch.randn(rows, k, device=dev)
+        mu = torch.randn(o, k, device=dev) * (2.0 / k) ** 0.5
+        sg = torch.rand(o, k, device=dev) * 0.01 + 0.001
+        mb = torch.zeros(o, device=dev)
+        sb = torch.full((o,), 0.01, device=dev)
+        y = torch.empty(s, rows, o, device=dev)
+        ms = timeit(lambda: hot.hot_linear_forward_rng(rng, x, mu, sg, mb, sb, y, 0, o * k))
+        n = o * k + o
+        plan = hot.hot_create(n, n, s, s, 1.0, dev.index or 0)
+        flat_mu, flat_sg = torch.cat([mu.view(-1), mb]), torch.cat([sg.view(-1), sb])
+        w = torch.empty(s, n, device=dev)
+        y2 = torch.empty_like(y)
+
+        def unfused():
+            hot.hot_forward_rng(plan, rng, flat_mu, flat_sg, w)
+            torch.baddbmm(w[:, o * k:].unsqueeze(1), x.unsqueeze(0).expand(s, rows, k),
+                          w[:, :o * k].view(s, o, k).transpose(1, 2), out=y2)
+
+        ms_u = timeit(unfused)
+        hot.hot_destroy(plan)
+        scale = (x.abs() @ (mu.abs() + 6 * sg).t()).max().item()
+        out[name] = {"fused_ms": ms, "TFLOPs": 2.0 * s * rows * k * o / ms / 1e9,
+                     "frac_of_fp32_mfma_peak": 2.0 * s * rows * k * o / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS,
+                     "weight_samples_per_s": s * o * k / (ms * 1e-3), "mu_sigma_GBps": 8.0 * o * k / ms / 1e6,
+                     "materialise_plus_library_gemm_ms": ms_u, "speedup_over_materialise": ms_u / ms,
+                     "agrees_with_materialised": bool((y - y2).abs().max().item() <= 1e-5 * scale)}
+        del x, mu, sg, y, y2, w
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -249,6 +304,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--cpu-weights", type=int, default=1 << 28, help="cap on weights the oracle is timed on")
+    ap.add_argument("--linear-only", action="store_true", help="only run the sampled linear layer lines")
     ap.add_argument("--probe-copy", action="store_true",
                     help="only run the plain copy kernel (2 GiB, known traffic) and print its rate")
     args = ap.parse_args()
@@ -268,6 +324,9 @@ def main() -> int:
     if args.probe_copy:
         print(json.dumps({"probe": "hot_probe_copy_kernel", "steps": args.steps,
                           **copy_ceiling(hot, torch, dev, iters=args.steps)}))
+        return 0
+    if args.linear_only:
+        print(json.dumps({"sampled_linear": sampled_linear_lines(hot, torch, dev, iters=args.steps)}))
         return 0
     import oracle
 
@@ -358,6 +417,7 @@ def main() -> int:
 
     if not args.no_others:
         result["predictive_stats"] = predictive_stats_lines(hot, torch, dev)
+        result["sampled_linear"] = sampled_linear_lines(hot, torch, dev)
         others = {}
         for name, o in workloads.CONFIGS.items():
             if name == wl.name:

@@ -23,10 +23,13 @@
 
 namespace {
 
-constexpr int kBlock = 256;   // four waves, each with its own 16 output columns
+constexpr int kMaxWaves = 16;  // waves of a workgroup; they split the input dimension among themselves
 constexpr int kColsPerWave = 16;
 constexpr int kRowsPerTile = 16;
 constexpr int kInputsPerIter = 32;
+
+// More row tiles need more registers per lane: such workgroups are limited to fewer waves.
+constexpr int max_waves(int rb) { return rb >= 4 ? 4 : (rb >= 2 ? 8 : kMaxWaves); }
 
 struct LinearArgs {
     long rows, in_features, out_features, ldx;
@@ -38,14 +41,17 @@ struct LinearArgs {
     Rng rng;
 };
 
+// A workgroup owns 16 output columns and 16*RB rows; its waves take the 32-input blocks round-robin
+// and their partial tiles are added through LDS in wave order (deterministic).
 template <int RB, int ST>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(64 * max_waves(RB))
 hot_linear_forward_kernel(LinearArgs a)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    extern __shared__ float partial[];   // [waves - 1][ST * RB * 4][64]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
     const int n = lane & 15, j = lane >> 4;
     const long K = a.in_features, O = a.out_features, R = a.rows;
-    const long o = (long)blockIdx.x * (4 * kColsPerWave) + wave * kColsPerWave + n;
+    const long o = (long)blockIdx.x * kColsPerWave + n;
     const long r0 = (long)blockIdx.y * (kRowsPerTile * RB);
     const bool o_ok = o < O;
     const float *mu_row = a.mu_w + (o_ok ? o : 0) * K;
@@ -59,7 +65,7 @@ hot_linear_forward_kernel(LinearArgs a)
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) acc[st][rb] = f4{0.0f, 0.0f, 0.0f, 0.0f};
 
-        for (long kb = 0; kb < K; kb += kInputsPerIter) {
+        for (long kb = (long)wave * kInputsPerIter; kb < K; kb += (long)waves * kInputsPerIter) {
             const long k = kb + 8 * j;
             f4 m4[2], sd4[2], xa[RB][2];
             bool ok[2];
@@ -99,6 +105,31 @@ hot_linear_forward_kernel(LinearArgs a)
             }
         }
 
+        if (waves > 1) {
+            __syncthreads();            // the previous chunk's readers are done with the buffer
+            if (wave > 0) {
+#pragma unroll
+                for (int st = 0; st < ST; ++st)
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            partial[((wave - 1) * (ST * RB * 4) + (st * RB + rb) * 4 + r) * 64 + lane] = acc[st][rb][r];
+            }
+            __syncthreads();
+            if (wave == 0) {
+                for (int v = 1; v < waves; ++v)
+#pragma unroll
+                    for (int st = 0; st < ST; ++st)
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                acc[st][rb][r] += partial[((v - 1) * (ST * RB * 4) + (st * RB + rb) * 4 + r) * 64 + lane];
+            }
+        }
+        if (wave != 0) continue;        // wave 0 holds the complete tile and writes it
+
 #pragma unroll
         for (int st = 0; st < ST; ++st) {
             if (s0 + st < a.s_loc) {
@@ -122,11 +153,13 @@ hot_linear_forward_kernel(LinearArgs a)
 }
 
 template <int RB>
-void linear_go(int st, dim3 grid, hipStream_t s, const LinearArgs &a)
+void linear_go(int st, dim3 grid, int waves, hipStream_t s, const LinearArgs &a)
 {
-    if (st >= 4) hot_linear_forward_kernel<RB, 4><<<grid, dim3(kBlock), 0, s>>>(a);
-    else if (st >= 2) hot_linear_forward_kernel<RB, 2><<<grid, dim3(kBlock), 0, s>>>(a);
-    else hot_linear_forward_kernel<RB, 1><<<grid, dim3(kBlock), 0, s>>>(a);
+    const dim3 block(64 * waves);
+    const size_t lds = waves > 1 ? (size_t)(waves - 1) * (size_t)(st * RB * 4) * 64 * sizeof(float) : 0;
+    if (st == 4) hot_linear_forward_kernel<RB, 4><<<grid, block, lds, s>>>(a);
+    else if (st == 2) hot_linear_forward_kernel<RB, 2><<<grid, block, lds, s>>>(a);
+    else hot_linear_forward_kernel<RB, 1><<<grid, block, lds, s>>>(a);
 }
 
 }  // namespace
@@ -167,14 +200,21 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     const int rb = d->rows > 32 ? 4 : (d->rows > 16 ? 2 : 1);
     // samples whose accumulators are live together (they share the loads of mu_W, sigma_W and x)
     const int st = d->s_local >= 4 && rb <= 2 ? 4 : (d->s_local >= 2 ? 2 : 1);
-    const long gx = (d->out_features + 4 * kColsPerWave - 1) / (4 * kColsPerWave);
+    const long gx = (d->out_features + kColsPerWave - 1) / kColsPerWave;
     const long gy = (d->rows + kRowsPerTile * rb - 1) / (kRowsPerTile * rb);
     if (gx > 0x7fffffffL || gy > 65535) return HOT_EINVAL;
+    // waves per workgroup: enough to give every SIMD of the chip several waves, bounded by the
+    // number of 32-input blocks and by 64 KiB of LDS for the partial tiles
+    const long k_blocks = (d->in_features + kInputsPerIter - 1) / kInputsPerIter;
+    int waves = 1;
+    while (waves < max_waves(rb) && gx * gy * waves < 8192 && 2L * waves <= k_blocks &&
+           (size_t)(2 * waves - 1) * (size_t)(st * rb * 4) * 64 * sizeof(float) <= 65536)
+        waves *= 2;
     const dim3 grid((unsigned)gx, (unsigned)gy);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (rb == 4) linear_go<4>(st, grid, s, a);
-    else if (rb == 2) linear_go<2>(st, grid, s, a);
-    else linear_go<1>(st, grid, s, a);
+    if (rb == 4) linear_go<4>(st, grid, waves, s, a);
+    else if (rb == 2) linear_go<2>(st, grid, waves, s, a);
+    else linear_go<1>(st, grid, waves, s, a);
     return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
 }
 

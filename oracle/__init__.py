@@ -1,5 +1,5 @@
 """ctypes front end of the CPU oracle in ``bbb_oracle.c`` (sample layer) and
-``eps_oracle.c`` (counter-based eps draw) ``stats_oracle.c`` (predictive mean / std) and ``linear_oracle.c`` (sampled linear layer).
+``eps_oracle.c`` (counter-based eps draw) ``stats_oracle.c`` (predictive mean / std) ``linear_oracle.c`` (sampled linear layer) and ``update_oracle.c`` (Adam step, MC-dropout layer).
 
 Test infrastructure only: the tests, the smoke check and the benchmark's
 ``cpu_baseline`` leg call this; the product package never imports it.  This module
@@ -17,10 +17,17 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, f) for f in ("bbb_oracle.c", "eps_oracle.c", "stats_oracle.c", "linear_oracle.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("bbb_oracle.c", "eps_oracle.c", "stats_oracle.c", "linear_oracle.c",
+                                               "update_oracle.c")]
 _LIB = os.path.join(_HERE, "libbbb_oracle.so")
 
 _lib = None
+
+
+class AdamParams(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double), ("grad_scale", ctypes.c_double), ("sigma_min", ctypes.c_double),
+                ("step", ctypes.c_int64)]
 
 
 def build(force: bool = True) -> str:
@@ -72,6 +79,16 @@ def _load():
     lib.linear_oracle_forward.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                           ctypes.c_int64, fp, fp, fp, dp, fp, fp, dp, dp]
     lib.linear_oracle_forward.restype = None
+    lib.update_oracle_adam.argtypes = [ctypes.c_int64, ctypes.POINTER(AdamParams), dp, dp, dp, dp, dp, dp, dp, dp]
+    lib.update_oracle_adam.restype = None
+    lib.update_oracle_dropout_threshold.argtypes = [ctypes.c_double]
+    lib.update_oracle_dropout_threshold.restype = ctypes.c_uint32
+    lib.update_oracle_dropout_forward.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_double,
+                                                  fp, u32p, dp]
+    lib.update_oracle_dropout_forward.restype = None
+    lib.update_oracle_dropout_backward.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                                   ctypes.c_int32, ctypes.c_int, ctypes.c_double, fp, u32p, dp]
+    lib.update_oracle_dropout_backward.restype = None
     _lib = lib
     return lib
 
@@ -239,3 +256,44 @@ def linear_forward(x, mu_w, sigma_w, eps_w, mu_b=None, sigma_b=None, eps_b=None,
     _load().linear_oracle_forward(s, r, k, o, x.shape[1], _fptr(x), _fptr(mu_w), _fptr(sigma_w), _dptr(eps_w),
                                   mb, sb, eb, _dptr(y))
     return y
+
+
+def adam_step(mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma, step, lr, beta1=0.9, beta2=0.999,
+              eps=1e-8, grad_scale=1.0, sigma_min=0.0):
+    """One Adam step on (mu, sigma) in fp64; returns new (mu, sigma, m_mu, v_mu, m_sigma, v_sigma)."""
+    arrs = [np.array(a, dtype=np.float64, copy=True) for a in (mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma)]
+    n = arrs[0].shape[0]
+    if any(a.shape != (n,) for a in arrs):
+        raise ValueError("all arrays must be 1-D of equal length")
+    p = AdamParams(lr, beta1, beta2, eps, grad_scale, sigma_min, int(step))
+    mu_, sg_, gm_, gs_, mm_, vm_, ms_, vs_ = arrs
+    _load().update_oracle_adam(n, ctypes.byref(p), _dptr(mu_), _dptr(sg_), _dptr(gm_), _dptr(gs_), _dptr(mm_),
+                               _dptr(vm_), _dptr(ms_), _dptr(vs_))
+    return mu_, sg_, mm_, vm_, ms_, vs_
+
+
+def dropout_threshold(keep: float) -> int:
+    return int(_load().update_oracle_dropout_threshold(float(keep)))
+
+
+def dropout_forward(mu, words, keep: float) -> np.ndarray:
+    """w[s,i] = mu[i] * (words[s,i] < threshold(keep)) / keep, fp64 [S_loc, N]; words uint32 [S_loc, >=N]."""
+    mu = _f32(mu, "mu")
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    n, s = mu.shape[0], words.shape[0]
+    w = np.empty((s, n), dtype=np.float64)
+    _load().update_oracle_dropout_forward(n, words.shape[1], s, float(keep), _fptr(mu),
+                                          words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), _dptr(w))
+    return w
+
+
+def dropout_backward(G, words, keep: float, s_total: int, n: int = None, reduce_mean: bool = False) -> np.ndarray:
+    """grad_mu[i] = g * sum_s G[s,i] * mask[s,i] / keep, fp64 [N]."""
+    G = _f32(G, "G")
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    n = G.shape[1] if n is None else n
+    out = np.empty(n, dtype=np.float64)
+    _load().update_oracle_dropout_backward(n, G.shape[1], words.shape[1], G.shape[0], int(s_total),
+                                           1 if reduce_mean else 0, float(keep), _fptr(G),
+                                           words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), _dptr(out))
+    return out

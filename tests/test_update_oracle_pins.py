@@ -111,6 +111,7 @@ def test_dropout_threshold_and_hand_case(oracle):
 def test_dropout_is_unbiased_and_is_the_gradient_of_its_forward(oracle, keep):
     n, s = 2000, 64
     mu = np.random.default_rng(6).normal(size=n).astype(np.float32)
+    mu[[0, 17, 1999]] = [1.25, -0.75, 3.5]          # so that mu +- 0.5 is exact in fp32 below
     words = oracle.eps_bits(n, s, seed=77)
     w = oracle.dropout_forward(mu, words, keep)
     kept = (w != 0) | (mu == 0)

@@ -238,6 +238,49 @@ def predictive_stats_lines(hot, torch, dev, iters: int = 20):
     return out
 
 
+def update_and_dropout_lines(hot, torch, dev, wl, iters: int = 10):
+    """hot_adam_step (56 bytes per weight) and the MC-dropout forward / backward on the workload's shape."""
+    n, s, ld = wl.n_weights, wl.s_local, wl.ld
+    a = [torch.randn(n, device=dev) for _ in range(4)] + [torch.zeros(n, device=dev) for _ in range(4)]
+    a[1].abs_().add_(0.01)
+
+    def timeit(fn):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    step = [0]
+
+    def adam():
+        step[0] += 1
+        hot.hot_adam_step(hot.hot_adam(1e-3, 0.9, 0.999, 1e-8, 1.0, 1e-6, step[0]), a[0], a[1], a[2], a[3], *a[4:])
+
+    ms = timeit(adam)
+    out = {"adam": {"ms": ms, "weights_per_s": n / (ms * 1e-3), "GBps": 56.0 * n / ms / 1e6,
+                    "frac_of_hbm_peak": 56.0 * n / ms / 1e6 / HBM_PEAK_GBS, "bytes_per_weight": 56}}
+    del a
+    torch.cuda.empty_cache()
+    mu = torch.randn(n, device=dev)
+    w = torch.empty(s, ld, device=dev)
+    gmu = torch.empty(n, device=dev)
+    plan = hot.hot_create(n, ld, s, wl.s_total, wl.dataset_size, dev.index or 0)
+    rng = hot.hot_rng(seed=RNG_SEED, step=RNG_STEP, first_sample=0)
+    ms_f = timeit(lambda: hot.hot_forward_dropout_rng(plan, rng, 0.9, mu, w))
+    ms_b = timeit(lambda: hot.hot_backward_dropout_rng(plan, rng, 0.9, w, gmu))
+    hot.hot_destroy(plan)
+    fb, bb = 4.0 * n * (1 + s), 4.0 * n * (s + 1)
+    out["mc_dropout"] = {"forward_ms": ms_f, "backward_ms": ms_b, "items_per_s": s * n / ((ms_f + ms_b) * 1e-3),
+                         "forward_GBps": fb / ms_f / 1e6, "backward_GBps": bb / ms_b / 1e6,
+                         "step_frac_of_hbm_roofline": (fb + bb) / ((ms_f + ms_b) * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    return out
+
+
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
@@ -418,6 +461,7 @@ def main() -> int:
     if not args.no_others:
         result["predictive_stats"] = predictive_stats_lines(hot, torch, dev)
         result["sampled_linear"] = sampled_linear_lines(hot, torch, dev)
+        result["update_and_dropout"] = update_and_dropout_lines(hot, torch, dev, wl)
         others = {}
         for name, o in workloads.CONFIGS.items():
             if name == wl.name:

@@ -184,6 +184,44 @@ int hot_linear_forward_rng(const hot_linear_desc *desc, const hot_rng *rng, cons
                            const float *sigma_w, const float *mu_b, const float *sigma_b, float *y, void *stream);
 
 /*
+ * "Update mu and sigma using optimizer (e.g., Adam)" -- the last line of the inner loop of
+ * Algorithm 1 / 2, run on the all-reduced gradients.  The paper gives no hyper-parameters:
+ * they are inputs.  Adam as published (Kingma and Ba, ICLR 2015), for mu and for sigma with
+ * their own moments, in place, fp32:
+ *   g = grad_scale * grad;  m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2
+ *   theta -= lr * (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps);  then, if sigma_min > 0,
+ *   sigma = max(sigma, sigma_min)   (the paper needs sigma > 0 but does not say how it is kept).
+ * All arrays [n] fp32 DEVICE, 4-byte aligned (16-byte aligned for the fast path); the six
+ * state arrays are read and overwritten.  One pass: 56 bytes per weight.  Current device.
+ */
+typedef struct hot_adam {
+    double lr, beta1, beta2, eps;
+    double grad_scale; /* e.g. 1/P after a sum all-reduce of mean-convention gradients; 1 otherwise */
+    double sigma_min;  /* <= 0: no clamp */
+    int64_t step;      /* t >= 1 */
+} hot_adam;
+
+int hot_adam_step(const hot_adam *params, int64_t n, float *mu, float *sigma, const float *grad_mu,
+                  const float *grad_sigma, float *m_mu, float *v_mu, float *m_sigma, float *v_sigma,
+                  void *stream);
+
+/*
+ * Monte Carlo dropout in weight space (section "Monte Carlo Dropout": dropout amounts to
+ * multiplying every weight with a Bernoulli variable; each of the S stochastic passes uses its
+ * own mask).  For sample s and weight i the mask bit is (generator word of (s, i) <
+ * floor(keep * 2^32)), the word being the one hot_sample_bits returns for the same hot_rng:
+ *   forward   w[s,i]     = mu[i] * bit / keep                  (1/keep keeps E[w] = mu)
+ *   backward  grad_mu[i] = g * sum_s grad_w[s,i] * bit / keep   (g = 1/S, or 1/S_loc with HOT_REDUCE_MEAN)
+ * The mask is never stored; the backward call regenerates it.  desc gives N, ld, S_loc, S and
+ * the reduce convention (dataset_size and device are not used); 0 < keep <= 1.  Layouts and
+ * alignment rules as for hot_forward / hot_backward.  Current device.
+ */
+int hot_forward_dropout_rng(const hot_desc *desc, const hot_rng *rng, double keep, const float *mu, float *w,
+                            void *stream);
+int hot_backward_dropout_rng(const hot_desc *desc, const hot_rng *rng, double keep, const float *grad_w,
+                             float *grad_mu, void *stream);
+
+/*
  * Predictive statistics over the samples (the paper's training description and its Monte
  * Carlo dropout section: the mean of the S predictions is the model's output, their standard
  * deviation its uncertainty; and the remark after Algorithm 2 that mean and standard

@@ -24,7 +24,8 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_get_launch", "hot_last_hip_error", "hot_strerror", "hot_recommended_ld",
            "hot_version", "hot_probe_copy", "hot_forward_rng", "hot_backward_rng",
            "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
-           "hot_stats_merge", "hot_linear_forward_rng")
+           "hot_stats_merge", "hot_linear_forward_rng", "hot_adam_step", "hot_forward_dropout_rng",
+           "hot_backward_dropout_rng")
 
 
 class hot_desc(ctypes.Structure):
@@ -47,6 +48,12 @@ class hot_linear_desc(ctypes.Structure):
     _fields_ = [("rows", ctypes.c_int64), ("in_features", ctypes.c_int64), ("out_features", ctypes.c_int64),
                 ("ldx", ctypes.c_int64), ("weight_offset", ctypes.c_int64), ("bias_offset", ctypes.c_int64),
                 ("s_local", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class hot_adam(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double),
+                ("eps", ctypes.c_double), ("grad_scale", ctypes.c_double), ("sigma_min", ctypes.c_double),
+                ("step", ctypes.c_int64)]
 
 
 class HotError(RuntimeError):
@@ -91,16 +98,20 @@ def lib() -> ctypes.CDLL:
     L.hot_probe_streams.restype = ctypes.c_int
     L.hot_linear_forward_rng.argtypes = [ctypes.POINTER(hot_linear_desc), rp, fp, fp, fp, fp, fp, fp, vp]
     L.hot_linear_forward_rng.restype = ctypes.c_int
+    L.hot_adam_step.argtypes = [ctypes.POINTER(hot_adam), ctypes.c_int64] + [fp] * 8 + [vp]
+    L.hot_adam_step.restype = ctypes.c_int
+    L.hot_forward_dropout_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, fp, fp, vp]
+    L.hot_forward_dropout_rng.restype = ctypes.c_int
+    L.hot_backward_dropout_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, fp, fp, vp]
+    L.hot_backward_dropout_rng.restype = ctypes.c_int
     L.hot_stats_local.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     L.hot_stats_local.restype = ctypes.c_int
     L.hot_stats_merge.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_int64,
                                   ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     L.hot_stats_merge.restype = ctypes.c_int
-    for name in ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
-                 "hot_get_launch", "hot_last_hip_error", "hot_version", "hot_forward_rng",
-                 "hot_backward_rng", "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
-           "hot_stats_merge", "hot_linear_forward_rng"):
-        getattr(L, name).restype = ctypes.c_int
+    for name in EXPORTS:
+        if name not in ("hot_strerror", "hot_recommended_ld"):
+            getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
 
@@ -329,7 +340,7 @@ def hot_stats_merge(means: torch.Tensor, m2s: torch.Tensor, counts, ddof: int, m
         code = lib().hot_stats_merge(means.data_ptr(), m2s.data_ptr(), c, parts, m, ld, int(ddof),
                                      mean_out.data_ptr(), std_out.data_ptr(), _stream(means.device.index))
     if code != HOT_OK:
-        raise HotError(code, "hot_stats_merge", "hot_linear_forward_rng")
+        raise HotError(code, "hot_stats_merge")
 
 
 def hot_linear_forward_rng(rng: hot_rng, x, mu_w, sigma_w, mu_b, sigma_b, y, weight_offset: int = 0,
@@ -365,3 +376,38 @@ def hot_linear_forward_rng(rng: hot_rng, x, mu_w, sigma_w, mu_b, sigma_b, y, wei
                                             _stream(x.device.index))
     if code != HOT_OK:
         raise HotError(code, "hot_linear_forward_rng")
+
+
+def hot_adam_step(params: hot_adam, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma) -> None:
+    """One in-place Adam step on (mu, sigma) and their moment arrays (see include/hot.h)."""
+    n = mu.shape[0]
+    dev = mu.device.index
+    ptrs = [_vec(t, n, dev, name) for t, name in ((mu, "mu"), (sigma, "sigma"), (grad_mu, "grad_mu"),
+                                                   (grad_sigma, "grad_sigma"), (m_mu, "m_mu"), (v_mu, "v_mu"),
+                                                   (m_sigma, "m_sigma"), (v_sigma, "v_sigma"))]
+    with torch.cuda.device(mu.device):
+        code = lib().hot_adam_step(ctypes.byref(params), n, *ptrs, _stream(dev))
+    if code != HOT_OK:
+        raise HotError(code, "hot_adam_step")
+
+
+def hot_forward_dropout_rng(plan: Plan, rng: hot_rng, keep: float, mu, w) -> None:
+    """w[s,i] = mu[i] * mask[s,i] / keep with the mask drawn in the kernel."""
+    d = plan.desc
+    with torch.cuda.device(d.device):
+        code = lib().hot_forward_dropout_rng(ctypes.byref(d), ctypes.byref(rng), float(keep),
+                                             _vec(mu, d.n_weights, d.device, "mu"),
+                                             _mat(w, d.s_local, d.n_weights, d.ld, d.device, "w"), _stream(d.device))
+    if code != HOT_OK:
+        raise HotError(code, "hot_forward_dropout_rng")
+
+
+def hot_backward_dropout_rng(plan: Plan, rng: hot_rng, keep: float, grad_w, grad_mu) -> None:
+    """grad_mu[i] = g * sum_s grad_w[s,i] * mask[s,i] / keep with the mask regenerated in the kernel."""
+    d = plan.desc
+    with torch.cuda.device(d.device):
+        code = lib().hot_backward_dropout_rng(ctypes.byref(d), ctypes.byref(rng), float(keep),
+                                              _mat(grad_w, d.s_local, d.n_weights, d.ld, d.device, "grad_w"),
+                                              _vec(grad_mu, d.n_weights, d.device, "grad_mu"), _stream(d.device))
+    if code != HOT_OK:
+        raise HotError(code, "hot_backward_dropout_rng")

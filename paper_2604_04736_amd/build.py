@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRCS = [os.path.join(HERE, "csrc", "hot.hip"), os.path.join(HERE, "csrc", "stats.hip"),
-        os.path.join(HERE, "csrc", "linear.hip")]
+        os.path.join(HERE, "csrc", "linear.hip"), os.path.join(HERE, "csrc", "update.hip")]
 LIB = os.path.join(HERE, "libhot.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

@@ -1,0 +1,254 @@
+// libhot: the two steps next to the Gaussian sample layer in the paper's algorithms
+// (arxiv 2604.04736), both streaming kernels bound by HBM:
+//   hot_adam_step              "Update mu and sigma using optimizer (e.g., Adam)", last line of the
+//                              inner loop of Algorithm 1 / 2: one pass over eight input and six
+//                              output arrays (56 bytes per weight), Adam as published by Kingma & Ba;
+//   hot_forward_dropout_rng,   Monte Carlo dropout in weight space (section "Monte Carlo Dropout":
+//   hot_backward_dropout_rng   every weight is multiplied by a Bernoulli variable), the mask being a
+//                              threshold on the same counter-based generator words the Gaussian
+//                              draw uses, so it is never stored and the backward pass regenerates it.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+
+#include "hot.h"
+#include "vec.h"
+#include "draw.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+
+struct AdamConst {
+    float lr, beta1, beta2, one_minus_beta1, one_minus_beta2, eps, grad_scale, sigma_min;
+    float corr1, corr2;   // 1 / (1 - beta1^t), 1 / (1 - beta2^t)
+};
+
+// One parameter: Adam's update in fp32 (moments, bias correction, step).
+__device__ __forceinline__ void adam_one(float &theta, float &m, float &v, float grad, const AdamConst &c)
+{
+    const float g = c.grad_scale * grad;
+    m = __builtin_fmaf(c.beta1, m, c.one_minus_beta1 * g);
+    v = __builtin_fmaf(c.beta2, v, c.one_minus_beta2 * (g * g));
+    const float mh = m * c.corr1, vh = v * c.corr2;
+    theta = theta - c.lr * mh / (sqrtf(vh) + c.eps);
+}
+
+template <bool ALIGNED>
+__global__ void __launch_bounds__(kBlock)
+hot_adam_kernel(long n, AdamConst c, float *__restrict__ mu, float *__restrict__ sigma,
+                const float *__restrict__ gmu, const float *__restrict__ gsig, float *__restrict__ m_mu,
+                float *__restrict__ v_mu, float *__restrict__ m_sig, float *__restrict__ v_sig)
+{
+    const long n_chunks = (n + 3) / 4;
+    for (long chunk = (long)blockIdx.x * kBlock + threadIdx.x; chunk < n_chunks; chunk += (long)gridDim.x * kBlock) {
+        const long col = chunk * 4;
+        if (col + 4 <= n) {
+            f4 p0 = load4<ALIGNED, true>(mu + col), p1 = load4<ALIGNED, true>(sigma + col);
+            const f4 g0 = load4<ALIGNED, true>(gmu + col), g1 = load4<ALIGNED, true>(gsig + col);
+            f4 m0 = load4<ALIGNED, true>(m_mu + col), v0 = load4<ALIGNED, true>(v_mu + col);
+            f4 m1 = load4<ALIGNED, true>(m_sig + col), v1 = load4<ALIGNED, true>(v_sig + col);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float t = p0[j], a = m0[j], b = v0[j];
+                adam_one(t, a, b, g0[j], c);
+                p0[j] = t; m0[j] = a; v0[j] = b;
+                t = p1[j]; a = m1[j]; b = v1[j];
+                adam_one(t, a, b, g1[j], c);
+                if (c.sigma_min > 0.0f && t < c.sigma_min) t = c.sigma_min;
+                p1[j] = t; m1[j] = a; v1[j] = b;
+            }
+            store4<ALIGNED, true>(mu + col, p0);
+            store4<ALIGNED, true>(sigma + col, p1);
+            store4<ALIGNED, true>(m_mu + col, m0);
+            store4<ALIGNED, true>(v_mu + col, v0);
+            store4<ALIGNED, true>(m_sig + col, m1);
+            store4<ALIGNED, true>(v_sig + col, v1);
+        } else {
+            for (long i = col; i < n; ++i) {
+                float t = mu[i], a = m_mu[i], b = v_mu[i];
+                adam_one(t, a, b, gmu[i], c);
+                mu[i] = t; m_mu[i] = a; v_mu[i] = b;
+                t = sigma[i]; a = m_sig[i]; b = v_sig[i];
+                adam_one(t, a, b, gsig[i], c);
+                if (c.sigma_min > 0.0f && t < c.sigma_min) t = c.sigma_min;
+                sigma[i] = t; m_sig[i] = a; v_sig[i] = b;
+            }
+        }
+    }
+}
+
+// b[s, 4q .. 4q+3] = (generator word < threshold), as multipliers 1/keep or 0
+__device__ __forceinline__ f4 mask_quad(long quad, int s, const Rng &rng, unsigned threshold, float inv_keep)
+{
+    const u4 x = eps_words(quad, s, rng);
+    f4 b;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) b[j] = x[j] < threshold ? inv_keep : 0.0f;
+    return b;
+}
+
+__device__ __forceinline__ float pick(f4 v, int j) { return j == 0 ? v[0] : (j == 1 ? v[1] : (j == 2 ? v[2] : v[3])); }
+
+template <bool ALIGNED, bool NT>
+__global__ void __launch_bounds__(kBlock)
+hot_dropout_forward_kernel(long n, long ld, int s_loc, const float *__restrict__ mu, float *__restrict__ w,
+                           Rng rng, unsigned threshold, float inv_keep)
+{
+    const long n_chunks = (n + 3) / 4;
+    for (long chunk = (long)blockIdx.x * kBlock + threadIdx.x; chunk < n_chunks; chunk += (long)gridDim.x * kBlock) {
+        const long col = chunk * 4;
+        if (col + 4 <= n) {
+            const f4 m = load4<ALIGNED, false>(mu + col);
+            for (int s = 0; s < s_loc; ++s) {
+                const f4 b = mask_quad(chunk, s, rng, threshold, inv_keep);
+                store4<ALIGNED, NT>(w + (size_t)s * (size_t)ld + col, m * b);
+            }
+        } else {
+            for (int s = 0; s < s_loc; ++s) {
+                const f4 b = mask_quad(chunk, s, rng, threshold, inv_keep);
+                for (long i = col; i < n; ++i) w[(size_t)s * (size_t)ld + (size_t)i] = mu[i] * pick(b, (int)(i - col));
+            }
+        }
+    }
+}
+
+template <bool ALIGNED, bool NT>
+__global__ void __launch_bounds__(kBlock)
+hot_dropout_backward_kernel(long n, long ld, int s_loc, double g, const float *__restrict__ gw,
+                            float *__restrict__ gmu, Rng rng, unsigned threshold, float inv_keep)
+{
+    const long n_chunks = (n + 3) / 4;
+    for (long chunk = (long)blockIdx.x * kBlock + threadIdx.x; chunk < n_chunks; chunk += (long)gridDim.x * kBlock) {
+        const long col = chunk * 4;
+        if (col + 4 <= n) {
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            int s = 0;
+            for (; s + 2 <= s_loc; s += 2) {
+                const f4 v0 = load4<ALIGNED, NT>(gw + (size_t)s * (size_t)ld + col);
+                const f4 v1 = load4<ALIGNED, NT>(gw + (size_t)(s + 1) * (size_t)ld + col);
+                const f4 b0 = mask_quad(chunk, s, rng, threshold, inv_keep);
+                const f4 b1 = mask_quad(chunk, s + 1, rng, threshold, inv_keep);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[j] = fma((double)v0[j], (double)b0[j], acc[j]);
+                    acc[j] = fma((double)v1[j], (double)b1[j], acc[j]);
+                }
+            }
+            for (; s < s_loc; ++s) {
+                const f4 v0 = load4<ALIGNED, NT>(gw + (size_t)s * (size_t)ld + col);
+                const f4 b0 = mask_quad(chunk, s, rng, threshold, inv_keep);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] = fma((double)v0[j], (double)b0[j], acc[j]);
+            }
+            f4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j] = (float)(g * acc[j]);
+            store4<ALIGNED, false>(gmu + col, o);
+        } else {
+            double acc[3] = {0.0, 0.0, 0.0};
+            for (int s = 0; s < s_loc; ++s) {
+                const f4 b = mask_quad(chunk, s, rng, threshold, inv_keep);
+#pragma unroll
+                for (int j = 0; j < 3; ++j)
+                    if (col + j < n) acc[j] = fma((double)gw[(size_t)s * (size_t)ld + (size_t)(col + j)], (double)pick(b, j), acc[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < 3; ++j)
+                if (col + j < n) gmu[col + j] = (float)(g * acc[j]);
+        }
+    }
+}
+
+unsigned blocks_for(long chunks)
+{
+    long b = (chunks + kBlock - 1) / kBlock;
+    if (b > (1L << 22)) b = 1L << 22;
+    if (b < 1) b = 1;
+    return (unsigned)b;
+}
+
+unsigned dropout_threshold(double keep)
+{
+    double t = std::floor(keep * 4294967296.0);
+    if (t > 4294967295.0) t = 4294967295.0;
+    return (unsigned)t;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hot_adam_step(const hot_adam *p, int64_t n, float *mu, float *sigma, const float *grad_mu,
+                  const float *grad_sigma, float *m_mu, float *v_mu, float *m_sigma, float *v_sigma, void *stream)
+{
+    if (!p || n < 1 || !mu || !sigma || !grad_mu || !grad_sigma || !m_mu || !v_mu || !m_sigma || !v_sigma) return HOT_EINVAL;
+    if (!(p->lr >= 0.0) || !(p->beta1 >= 0.0 && p->beta1 < 1.0) || !(p->beta2 >= 0.0 && p->beta2 < 1.0) ||
+        !(p->eps >= 0.0) || !std::isfinite(p->grad_scale) || !std::isfinite(p->lr) || p->step < 1)
+        return HOT_EINVAL;
+    const void *ptrs[8] = {mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma};
+    bool al = true;
+    for (const void *q : ptrs) {
+        if (!aligned4(q)) return HOT_EINVAL;
+        al = al && aligned16(q);
+    }
+    AdamConst c;
+    c.lr = (float)p->lr;
+    c.beta1 = (float)p->beta1;
+    c.beta2 = (float)p->beta2;
+    c.one_minus_beta1 = (float)(1.0 - p->beta1);
+    c.one_minus_beta2 = (float)(1.0 - p->beta2);
+    c.eps = (float)p->eps;
+    c.grad_scale = (float)p->grad_scale;
+    c.sigma_min = (float)p->sigma_min;
+    c.corr1 = (float)(1.0 / (1.0 - std::pow(p->beta1, (double)p->step)));
+    c.corr2 = (float)(1.0 / (1.0 - std::pow(p->beta2, (double)p->step)));
+    const dim3 grid(blocks_for((n + 3) / 4)), block(kBlock);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (al) hot_adam_kernel<true><<<grid, block, 0, s>>>(n, c, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma);
+    else hot_adam_kernel<false><<<grid, block, 0, s>>>(n, c, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma);
+    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+}
+
+int hot_forward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep, const float *mu, float *w, void *stream)
+{
+    if (!d || !mu || !w || !aligned4(mu) || !aligned4(w)) return HOT_EINVAL;
+    if (d->n_weights < 1 || d->ld < d->n_weights || d->s_local < 1 || d->s_total < d->s_local) return HOT_EINVAL;
+    if (!(keep > 0.0 && keep <= 1.0)) return HOT_EINVAL;
+    Rng r;
+    if (!make_rng(rng, d->s_local, r)) return HOT_EINVAL;
+    const bool al = aligned16(mu) && aligned16(w) && (d->ld % 4 == 0);
+    const bool nt = (double)d->s_local * (double)d->ld * 4.0 >= 256.0 * 1048576.0;
+    const dim3 grid(blocks_for((d->n_weights + 3) / 4)), block(kBlock);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned thr = dropout_threshold(keep);
+    const float inv = (float)(1.0 / keep);
+    if (al && nt) hot_dropout_forward_kernel<true, true><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv);
+    else if (al) hot_dropout_forward_kernel<true, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv);
+    else hot_dropout_forward_kernel<false, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv);
+    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+}
+
+int hot_backward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep, const float *grad_w, float *grad_mu,
+                             void *stream)
+{
+    if (!d || !grad_w || !grad_mu || !aligned4(grad_w) || !aligned4(grad_mu)) return HOT_EINVAL;
+    if (d->n_weights < 1 || d->ld < d->n_weights || d->s_local < 1 || d->s_total < d->s_local) return HOT_EINVAL;
+    if (d->flags != HOT_REDUCE_SUM && d->flags != HOT_REDUCE_MEAN) return HOT_EINVAL;
+    if (!(keep > 0.0 && keep <= 1.0)) return HOT_EINVAL;
+    Rng r;
+    if (!make_rng(rng, d->s_local, r)) return HOT_EINVAL;
+    const bool al = aligned16(grad_w) && aligned16(grad_mu) && (d->ld % 4 == 0);
+    const bool nt = (double)d->s_local * (double)d->ld * 4.0 >= 256.0 * 1048576.0;
+    const double g = d->flags == HOT_REDUCE_MEAN ? 1.0 / (double)d->s_local : 1.0 / (double)d->s_total;
+    const dim3 grid(blocks_for((d->n_weights + 3) / 4)), block(kBlock);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned thr = dropout_threshold(keep);
+    const float inv = (float)(1.0 / keep);
+    if (al && nt) hot_dropout_backward_kernel<true, true><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv);
+    else if (al) hot_dropout_backward_kernel<true, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv);
+    else hot_dropout_backward_kernel<false, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv);
+    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+}
+
+}  // extern "C"

@@ -51,6 +51,7 @@ def test_struct_layout_matches_header(hot):
     assert hot.hot_desc.dataset_size.offset == 24 and hot.hot_desc.flags.offset == 36
     assert ctypes.sizeof(hot.hot_launch) == 16
     assert ctypes.sizeof(hot.hot_linear_desc) == 56 and hot.hot_linear_desc.s_local.offset == 48
+    assert ctypes.sizeof(hot.hot_adam) == 56 and hot.hot_adam.step.offset == 48
     assert ctypes.sizeof(hot.hot_rng) == 16 and hot.hot_rng.step.offset == 8 and hot.hot_rng.first_sample.offset == 12
 
 
@@ -68,6 +69,9 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_stats_local(None, 1, 1, 1, None, None, None) == hot.HOT_EINVAL
     assert L.hot_stats_merge(None, None, None, 1, 1, 1, 0, None, None, None) == hot.HOT_EINVAL
     assert L.hot_linear_forward_rng(None, None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_adam_step(None, 1, None, None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_forward_dropout_rng(None, None, 0.5, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_backward_dropout_rng(None, None, 0.5, None, None, None) == hot.HOT_EINVAL
     assert L.hot_forward_rng(None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward_rng(None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_sample_eps(None, None, None, None) == hot.HOT_EINVAL

@@ -1,0 +1,121 @@
+"""GPU parity of the Adam step and of the weight-space MC-dropout layer against the fp64 oracle.
+
+Adam (fp32 arithmetic on fp32 state, a handful of roundings per quantity), relative to the sum of
+addend magnitudes:  m: 1e-6 (beta1 |m| + (1-beta1) |g|),  v: 1e-6 (beta2 v + (1-beta2) g^2),
+theta: 1e-6 (|theta| + |step taken|).  Dropout: the mask is an integer comparison and must agree
+bit for bit; kept weights are mu * fp32(1/keep): 1e-6 |mu| / keep; gradients 1e-6 g sum|G| / keep."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def hot():
+    from paper_2604_04736_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _dev(a, offset=0):
+    buf = torch.empty(a.size + offset, device=DEV)
+    v = buf[offset:].view(a.shape)
+    v.copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)))
+    return v
+
+
+@pytest.mark.parametrize("n,offset", [(1, 0), (5, 0), (1023, 0), (4096, 0), (100_003, 0), (100_003, 1), (1_048_579, 3)])
+def test_adam_steps_match_oracle(oracle, hot, n, offset):
+    print("case adam", n, offset, flush=True)
+    r = np.random.default_rng(n)
+    state = {"mu": r.normal(size=n), "sigma": r.uniform(0.01, 1.0, size=n), "m_mu": np.zeros(n), "v_mu": np.zeros(n),
+             "m_sigma": np.zeros(n), "v_sigma": np.zeros(n)}
+    d = {k: _dev(v, offset) for k, v in state.items()}
+    lr, b1, b2, eps, gs, smin = 3e-3, 0.9, 0.999, 1e-8, 0.25, 0.02
+    for t in range(1, 6):
+        g_mu = (r.normal(size=n) * 10 ** r.uniform(-4, 3, size=n)).astype(np.float32)
+        g_sg = (r.normal(size=n) * 10 ** r.uniform(-4, 3, size=n)).astype(np.float32)
+        if t == 3:
+            g_mu[: n // 2] = 0.0
+        before = {k: v.cpu().numpy().astype(np.float64) for k, v in d.items()}
+        hot.hot_adam_step(hot.hot_adam(lr, b1, b2, eps, gs, smin, t), d["mu"], d["sigma"], _dev(g_mu, offset),
+                          _dev(g_sg, offset), d["m_mu"], d["v_mu"], d["m_sigma"], d["v_sigma"])
+        torch.cuda.synchronize()
+        want = oracle.adam_step(before["mu"], before["sigma"], g_mu, g_sg, before["m_mu"], before["v_mu"],
+                                before["m_sigma"], before["v_sigma"], step=t, lr=lr, beta1=b1, beta2=b2, eps=eps,
+                                grad_scale=gs, sigma_min=smin)
+        got = {k: v.cpu().numpy().astype(np.float64) for k, v in d.items()}
+        for name, grad, m_key, v_key, th_key, w_th, w_m, w_v in (("mu", g_mu, "m_mu", "v_mu", "mu", want[0], want[2], want[3]),
+                                                                 ("sigma", g_sg, "m_sigma", "v_sigma", "sigma", want[1], want[4], want[5])):
+            g = gs * grad.astype(np.float64)
+            assert np.all(np.abs(got[m_key] - w_m) <= 1e-6 * (b1 * np.abs(before[m_key]) + (1 - b1) * np.abs(g)) + 1e-45)
+            assert np.all(np.abs(got[v_key] - w_v) <= 1e-6 * (b2 * before[v_key] + (1 - b2) * g * g) + 1e-45)
+            step = np.abs(w_th - before[th_key])
+            assert np.all(np.abs(got[th_key] - w_th) <= 1e-6 * (np.abs(before[th_key]) + step + lr))
+        assert got["sigma"].min() >= smin * (1 - 1e-7)
+
+
+def test_adam_trajectory_matches_torch_adam(hot):
+    n, steps, lr = 10_000, 20, 1e-2
+    r = np.random.default_rng(0)
+    mu0, sg0 = r.normal(size=n).astype(np.float32), r.uniform(0.1, 1, size=n).astype(np.float32)
+    d = [_dev(mu0), _dev(sg0)] + [_dev(np.zeros(n)) for _ in range(4)]
+    p_mu = torch.tensor(mu0, dtype=torch.float64, requires_grad=True)
+    p_sg = torch.tensor(sg0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([p_mu, p_sg], lr=lr)
+    for t in range(1, steps + 1):
+        g_mu, g_sg = r.normal(size=n).astype(np.float32), r.normal(size=n).astype(np.float32)
+        p_mu.grad, p_sg.grad = torch.tensor(g_mu, dtype=torch.float64), torch.tensor(g_sg, dtype=torch.float64)
+        opt.step()
+        hot.hot_adam_step(hot.hot_adam(lr, 0.9, 0.999, 1e-8, 1.0, 0.0, t), d[0], d[1], _dev(g_mu), _dev(g_sg), *d[2:])
+    torch.cuda.synchronize()
+    assert np.abs(d[0].cpu().numpy() - p_mu.detach().numpy()).max() <= 1e-5 * steps * lr + 1e-6
+    assert np.abs(d[1].cpu().numpy() - p_sg.detach().numpy()).max() <= 1e-5 * steps * lr + 1e-6
+
+
+@pytest.mark.parametrize("n,ld,s,offset,keep", [(300_001, 300_001, 5, 0, 0.5), (70_003, 70_016, 4, 0, 0.9), (4099, 4099, 3, 1, 0.2),
+                                                  (2, 2, 2, 0, 1.0), (1_000_000, 1_000_000, 16, 0, 0.75)])
+def test_dropout_layer_matches_oracle(oracle, hot, n, ld, s, offset, keep):
+    print("case dropout", n, ld, s, offset, keep, flush=True)
+    r = np.random.default_rng(n + s)
+    mu = r.normal(size=n).astype(np.float32)
+    G = np.full((s, ld), np.nan, np.float32)
+    G[:, :n] = r.normal(size=(s, n)) * 3
+    rng = hot.hot_rng(seed=31337, step=2, first_sample=s)
+    plan = hot.hot_create(n, ld, s, 2 * s, 1.0, 0)
+    mu_d, G_d = _dev(mu, offset), _dev(G, offset)
+    w = _dev(np.full((s, ld), 7.0, np.float32), offset)
+    gmu = _dev(np.zeros(n), offset)
+    hot.hot_forward_dropout_rng(plan, rng, keep, mu_d, w)
+    hot.hot_backward_dropout_rng(plan, rng, keep, G_d, gmu)
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+    words = oracle.eps_bits(n, s, rng.seed, rng.step, rng.first_sample)
+    w64 = oracle.dropout_forward(mu, words, keep)
+    got = w.cpu().numpy()
+    if ld > n:
+        assert np.all(got[:, n:] == 7.0), "w padding written"
+    assert np.array_equal(got[:, :n] == 0, w64 == 0), "mask differs"
+    assert np.all(np.abs(got[:, :n] - w64) <= 1e-6 * np.abs(mu)[None, :] / keep)
+    gm64 = oracle.dropout_backward(G, words, keep, s_total=2 * s, n=n)
+    scale = np.abs(G[:, :n].astype(np.float64)).sum(0) / (2 * s) / keep
+    assert np.all(np.abs(gmu.cpu().numpy() - gm64) <= 1e-6 * scale)
+    if keep == 1.0:
+        assert np.array_equal(got[:, :n], np.broadcast_to(mu, (s, n)))
+
+
+def test_update_errors(hot):
+    t = torch.zeros(16, device=DEV)
+    with pytest.raises(hot.HotError):
+        hot.hot_adam_step(hot.hot_adam(1e-3, 0.9, 0.999, 1e-8, 1.0, 0.0, 0), *[t.clone() for _ in range(8)])     # step 0
+    with pytest.raises(hot.HotError):
+        hot.hot_adam_step(hot.hot_adam(1e-3, 1.0, 0.999, 1e-8, 1.0, 0.0, 1), *[t.clone() for _ in range(8)])     # beta1 = 1
+    plan = hot.hot_create(16, 16, 1, 1, 1.0, 0)
+    rng = hot.hot_rng(seed=1, step=0, first_sample=0)
+    for keep in (0.0, 1.5, float("nan")):
+        with pytest.raises(hot.HotError):
+            hot.hot_forward_dropout_rng(plan, rng, keep, t, t.clone().view(1, 16))
+    hot.hot_destroy(plan)

@@ -300,3 +300,87 @@ def test_full_size_every_element(oracle, hot, name):
     _say("case every element", name)
     x = W.make_inputs(wl, DEV)
     _say(P.check_all(oracle, hot, x, wl))
+
+
+def test_indices_beyond_32_bits(oracle, hot):
+    """S_loc * ld = 4.8e9 elements: row offsets pass 2^32, and there are more column tiles than the
+    grid bound, so workgroups stride over tiles.  Sampled windows in the last rows against the oracle."""
+    n, s = 1_200_000_003, 4
+    _say("case huge", n, s)
+    g = torch.Generator(device=DEV).manual_seed(7)
+    mu = torch.randn(n, device=DEV, generator=g)
+    sigma = torch.rand(n, device=DEV, generator=g) * 0.5 + 0.01
+    eps = torch.randn(s, n, device=DEV, generator=g)
+    G = torch.randn(s, n, device=DEV, generator=g)
+    w = torch.empty(s, n, device=DEV)
+    gmu, gsig = torch.empty(n, device=DEV), torch.empty(n, device=DEV)
+    kl = torch.zeros(1, dtype=torch.float64, device=DEV)
+    plan = hot.hot_create(n, n, s, 16, 45000.0, 0)
+    hot.hot_forward(plan, mu, sigma, eps, w, kl)
+    hot.hot_backward(plan, mu, sigma, eps, G, gmu, gsig)
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+    _say("ran huge")
+    rng = np.random.default_rng(1)
+    width = 10_000
+    for a in [0, n - width, 1_073_741_824 - 5000, 805_306_368 - 17] + [int(v) for v in rng.integers(0, n - width, size=4)]:
+        b = a + width
+        h = {"mu": mu[a:b].cpu().numpy(), "sigma": sigma[a:b].cpu().numpy(),
+             "eps": np.ascontiguousarray(eps[:, a:b].cpu().numpy()), "G": np.ascontiguousarray(G[:, a:b].cpu().numpy())}
+        P.check_w(oracle, h, w[:, a:b].cpu().numpy(), width)
+        P.check_grads(oracle, h, gmu[a:b].cpu().numpy(), gsig[a:b].cpu().numpy(), width, 16, 45000.0)
+    # the KL term of 1.2e9 weights against a chunked fp64 evaluation of the same formula on the GPU's values
+    acc = 0.0
+    for c0 in range(0, n, 1 << 26):
+        m64, s64 = mu[c0:c0 + (1 << 26)].double(), sigma[c0:c0 + (1 << 26)].double()
+        acc += float((s64 * s64 + m64 * m64 - 1.0 - 2.0 * torch.log(s64)).sum())
+    _say("KL", kl.item(), "reference", 0.5 * acc, "relative difference", abs(kl.item() - 0.5 * acc) / abs(0.5 * acc))
+    assert abs(kl.item() - 0.5 * acc) <= 1e-7 * abs(0.5 * acc)
+    del eps, G, w
+
+
+def test_hip_graph_replays_equal_eager(hot):
+    """The run calls neither allocate nor synchronise, so a stream capture takes them; every replay,
+    with eager work in between, must reproduce the eager result bit for bit."""
+    wl = W.CONFIGS["C1"]
+    x = W.make_inputs(wl, DEV)
+    plan = hot.hot_create(wl.n_weights, wl.ld, wl.s_local, wl.s_total, wl.dataset_size, 0)
+    rngd = hot.hot_rng(seed=3, step=1, first_sample=0)
+
+    def buffers():
+        return (torch.zeros_like(x["eps"]), torch.zeros(1, dtype=torch.float64, device=DEV), torch.zeros_like(x["mu"]),
+                torch.zeros_like(x["mu"]), torch.zeros_like(x["eps"]), torch.zeros_like(x["mu"]), torch.zeros_like(x["mu"]))
+
+    def step(b):
+        w, kl, gmu, gsig, w2, gmu2, gsig2 = b
+        hot.hot_forward(plan, x["mu"], x["sigma"], x["eps"], w, kl)
+        hot.hot_backward(plan, x["mu"], x["sigma"], x["eps"], x["G"], gmu, gsig)
+        hot.hot_forward_rng(plan, rngd, x["mu"], x["sigma"], w2, None)
+        hot.hot_backward_rng(plan, rngd, x["mu"], x["sigma"], x["G"], gmu2, gsig2)
+
+    eager = buffers()
+    step(eager)
+    torch.cuda.synchronize()
+    captured = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(captured)                      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(captured)
+    for rep in range(4):
+        for t in captured:
+            t.fill_(float(rep + 5)) if t.dtype == torch.float32 else t.fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, captured):
+            if a.dim() == 2:                # padding columns are never written: compare the payload
+                a, b = a[:, :wl.n_weights], b[:, :wl.n_weights]
+            assert torch.equal(a, b), rep
+        scratch = torch.randn(1000, device=DEV).sum().item()      # eager work between replays
+        assert scratch == scratch
+    hot.hot_destroy(plan)

@@ -44,7 +44,7 @@ struct LinearArgs {
 // A workgroup owns 16 output columns and 16*RB rows; its waves take the 32-input blocks round-robin
 // and their partial tiles are added through LDS in wave order (deterministic).
 template <int RB, int ST>
-__global__ void __launch_bounds__(64 * max_waves(RB))
+__global__ void __launch_bounds__(64 * max_waves(RB), RB >= 4 ? 2 : 1)
 hot_linear_forward_kernel(LinearArgs a)
 {
     extern __shared__ float partial[];   // [waves - 1][ST * RB * 4][64]

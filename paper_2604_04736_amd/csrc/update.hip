@@ -34,45 +34,63 @@ __device__ __forceinline__ void adam_one(float &theta, float &m, float &v, float
     theta = theta - c.lr * mh / (sqrtf(vh) + c.eps);
 }
 
+// Four 16-byte chunks per thread and non-temporal accesses measured best on MI355X (5.6 TB/s
+// against 5.3 TB/s with one chunk and cached accesses).
+constexpr int kAdamChunks = 4;
+
 template <bool ALIGNED>
 __global__ void __launch_bounds__(kBlock)
 hot_adam_kernel(long n, AdamConst c, float *__restrict__ mu, float *__restrict__ sigma,
                 const float *__restrict__ gmu, const float *__restrict__ gsig, float *__restrict__ m_mu,
                 float *__restrict__ v_mu, float *__restrict__ m_sig, float *__restrict__ v_sig)
 {
+    constexpr int CH = kAdamChunks;
+    constexpr bool NT = true;
     const long n_chunks = (n + 3) / 4;
-    for (long chunk = (long)blockIdx.x * kBlock + threadIdx.x; chunk < n_chunks; chunk += (long)gridDim.x * kBlock) {
-        const long col = chunk * 4;
-        if (col + 4 <= n) {
-            f4 p0 = load4<ALIGNED, true>(mu + col), p1 = load4<ALIGNED, true>(sigma + col);
-            const f4 g0 = load4<ALIGNED, true>(gmu + col), g1 = load4<ALIGNED, true>(gsig + col);
-            f4 m0 = load4<ALIGNED, true>(m_mu + col), v0 = load4<ALIGNED, true>(v_mu + col);
-            f4 m1 = load4<ALIGNED, true>(m_sig + col), v1 = load4<ALIGNED, true>(v_sig + col);
+    for (long chunk0 = (long)blockIdx.x * (kBlock * CH) + threadIdx.x; chunk0 < n_chunks; chunk0 += (long)gridDim.x * kBlock * CH) {
+        f4 p0[CH], p1[CH], g0[CH], g1[CH], m0[CH], v0[CH], m1[CH], v1[CH];
+        bool full[CH];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float t = p0[j], a = m0[j], b = v0[j];
-                adam_one(t, a, b, g0[j], c);
-                p0[j] = t; m0[j] = a; v0[j] = b;
-                t = p1[j]; a = m1[j]; b = v1[j];
-                adam_one(t, a, b, g1[j], c);
-                if (c.sigma_min > 0.0f && t < c.sigma_min) t = c.sigma_min;
-                p1[j] = t; m1[j] = a; v1[j] = b;
+        for (int q = 0; q < CH; ++q) {
+            const long col = (chunk0 + (long)q * kBlock) * 4;
+            full[q] = col + 4 <= n;
+            if (full[q]) {
+                p0[q] = load4<ALIGNED, NT>(mu + col); p1[q] = load4<ALIGNED, NT>(sigma + col);
+                g0[q] = load4<ALIGNED, NT>(gmu + col); g1[q] = load4<ALIGNED, NT>(gsig + col);
+                m0[q] = load4<ALIGNED, NT>(m_mu + col); v0[q] = load4<ALIGNED, NT>(v_mu + col);
+                m1[q] = load4<ALIGNED, NT>(m_sig + col); v1[q] = load4<ALIGNED, NT>(v_sig + col);
             }
-            store4<ALIGNED, true>(mu + col, p0);
-            store4<ALIGNED, true>(sigma + col, p1);
-            store4<ALIGNED, true>(m_mu + col, m0);
-            store4<ALIGNED, true>(v_mu + col, v0);
-            store4<ALIGNED, true>(m_sig + col, m1);
-            store4<ALIGNED, true>(v_sig + col, v1);
-        } else {
-            for (long i = col; i < n; ++i) {
-                float t = mu[i], a = m_mu[i], b = v_mu[i];
-                adam_one(t, a, b, gmu[i], c);
-                mu[i] = t; m_mu[i] = a; v_mu[i] = b;
-                t = sigma[i]; a = m_sig[i]; b = v_sig[i];
-                adam_one(t, a, b, gsig[i], c);
-                if (c.sigma_min > 0.0f && t < c.sigma_min) t = c.sigma_min;
-                sigma[i] = t; m_sig[i] = a; v_sig[i] = b;
+        }
+#pragma unroll
+        for (int q = 0; q < CH; ++q) {
+            const long col = (chunk0 + (long)q * kBlock) * 4;
+            if (full[q]) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float t = p0[q][j], a = m0[q][j], b = v0[q][j];
+                    adam_one(t, a, b, g0[q][j], c);
+                    p0[q][j] = t; m0[q][j] = a; v0[q][j] = b;
+                    t = p1[q][j]; a = m1[q][j]; b = v1[q][j];
+                    adam_one(t, a, b, g1[q][j], c);
+                    if (c.sigma_min > 0.0f && t < c.sigma_min) t = c.sigma_min;
+                    p1[q][j] = t; m1[q][j] = a; v1[q][j] = b;
+                }
+                store4<ALIGNED, NT>(mu + col, p0[q]);
+                store4<ALIGNED, NT>(sigma + col, p1[q]);
+                store4<ALIGNED, NT>(m_mu + col, m0[q]);
+                store4<ALIGNED, NT>(v_mu + col, v0[q]);
+                store4<ALIGNED, NT>(m_sig + col, m1[q]);
+                store4<ALIGNED, NT>(v_sig + col, v1[q]);
+            } else {
+                for (long i = col; i < n; ++i) {
+                    float t = mu[i], a = m_mu[i], b = v_mu[i];
+                    adam_one(t, a, b, gmu[i], c);
+                    mu[i] = t; m_mu[i] = a; v_mu[i] = b;
+                    t = sigma[i]; a = m_sig[i]; b = v_sig[i];
+                    adam_one(t, a, b, gsig[i], c);
+                    if (c.sigma_min > 0.0f && t < c.sigma_min) t = c.sigma_min;
+                    sigma[i] = t; m_sig[i] = a; v_sig[i] = b;
+                }
             }
         }
     }
@@ -203,7 +221,7 @@ int hot_adam_step(const hot_adam *p, int64_t n, float *mu, float *sigma, const f
     c.sigma_min = (float)p->sigma_min;
     c.corr1 = (float)(1.0 / (1.0 - std::pow(p->beta1, (double)p->step)));
     c.corr2 = (float)(1.0 / (1.0 - std::pow(p->beta2, (double)p->step)));
-    const dim3 grid(blocks_for((n + 3) / 4)), block(kBlock);
+    const dim3 grid(blocks_for(((n + 3) / 4 + kAdamChunks - 1) / kAdamChunks)), block(kBlock);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (al) hot_adam_kernel<true><<<grid, block, 0, s>>>(n, c, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma);
     else hot_adam_kernel<false><<<grid, block, 0, s>>>(n, c, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma);

@@ -148,7 +148,11 @@ int hot_destroy(hot_plan *plan);
 int hot_set_launch(hot_plan *plan, int kernel, const hot_launch *cfg);
 int hot_get_launch(const hot_plan *plan, int kernel, hot_launch *cfg);
 
-/* hipError_t of the last failed HIP call made through this plan (0 if none). */
+/*
+ * hipError_t of the last failed HIP call made through this plan (0 if none).  With plan = NULL:
+ * of the last failed HIP call this thread made through an entry point that takes no plan
+ * (hot_create, hot_stats_*, hot_linear_*, hot_adam_step, hot_*_dropout_rng, hot_probe_*).
+ */
 int hot_last_hip_error(const hot_plan *plan);
 
 /*

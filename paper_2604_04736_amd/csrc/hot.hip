@@ -582,6 +582,16 @@ struct DeviceGuard {
 
 }  // namespace
 
+namespace hot_detail {
+static thread_local int g_last_hip = 0;
+int note_hip(hipError_t e)
+{
+    if (e == hipSuccess) return HOT_OK;
+    g_last_hip = (int)e;
+    return HOT_EHIP;
+}
+}  // namespace hot_detail
+
 struct hot_plan {
     hot_desc d;
     double g, k;
@@ -754,7 +764,7 @@ int hot_create(hot_plan **out, const hot_desc *desc)
     // element offsets (s_local - 1) * ld + n_weights must fit in 63 bits
     if (d.ld > (INT64_MAX / 4) / d.s_local) return HOT_EINVAL;
     int n_dev = 0;
-    if (hipGetDeviceCount(&n_dev) != hipSuccess) return HOT_EHIP;
+    if (hipError_t e = hipGetDeviceCount(&n_dev); e != hipSuccess) return hot_detail::note_hip(e);
     if (d.device < 0 || d.device >= n_dev) return HOT_EINVAL;
 
     hot_plan *p = new (std::nothrow) hot_plan();
@@ -777,7 +787,7 @@ int hot_create(hot_plan **out, const hot_desc *desc)
         const bool oom = (e == hipErrorOutOfMemory);
         (void)hipGetLastError();
         delete p;
-        return oom ? HOT_ENOMEM : HOT_EHIP;
+        return oom ? HOT_ENOMEM : hot_detail::note_hip(e);
     }
     // Defaults from launch-shape sweeps on MI355X: the forward kernel and a backward pass over
     // two or three samples run best with four chunks per thread; with four or more samples the
@@ -833,7 +843,7 @@ int hot_get_launch(const hot_plan *plan, int kernel, hot_launch *cfg)
     return HOT_OK;
 }
 
-int hot_last_hip_error(const hot_plan *plan) { return plan ? plan->last_hip : 0; }
+int hot_last_hip_error(const hot_plan *plan) { return plan ? plan->last_hip : hot_detail::g_last_hip; }
 
 int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float *eps, float *w,
                 double *kl_out, void *stream)
@@ -888,7 +898,7 @@ int hot_probe_copy(void *dst, const void *src, int64_t bytes, int nontemporal, v
     f4 *out = static_cast<f4 *>(dst);
     if (nontemporal) hot_probe_copy_kernel<true><<<grid, block, 0, s>>>(in, out, n_vec);
     else hot_probe_copy_kernel<false><<<grid, block, 0, s>>>(in, out, n_vec);
-    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+    return hot_detail::note_hip(hipGetLastError());
 }
 
 int hot_probe_streams(void *arena, int64_t stream_bytes, int reads, int writes, void *stream)
@@ -913,7 +923,7 @@ int hot_probe_streams(void *arena, int64_t stream_bytes, int reads, int writes, 
     case 5: probe_streams_go<5>(writes, grid, s, p, n_vec); break;
     default: probe_streams_go<6>(writes, grid, s, p, n_vec); break;
     }
-    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+    return hot_detail::note_hip(hipGetLastError());
 }
 
 }  // extern "C"

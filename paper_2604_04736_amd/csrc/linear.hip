@@ -215,7 +215,7 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     if (rb == 4) linear_go<4>(st, grid, waves, s, a);
     else if (rb == 2) linear_go<2>(st, grid, waves, s, a);
     else linear_go<1>(st, grid, waves, s, a);
-    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+    return hot_detail::note_hip(hipGetLastError());
 }
 
 }  // extern "C"

@@ -144,7 +144,7 @@ int hot_stats_local(const float *yhat, int64_t m, int64_t ld, int32_t s_local, d
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (al) hot_stats_local_kernel<true><<<grid, block, 0, s>>>(m, ld, s_local, yhat, mean, m2);
     else hot_stats_local_kernel<false><<<grid, block, 0, s>>>(m, ld, s_local, yhat, mean, m2);
-    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+    return hot_detail::note_hip(hipGetLastError());
 }
 
 int hot_stats_merge(const double *means, const double *m2s, const int32_t *counts, int32_t parts, int64_t m,
@@ -167,7 +167,7 @@ int hot_stats_merge(const double *means, const double *m2s, const int32_t *count
     c.divisor = c.total - (double)ddof;      // 0 for one sample with ddof = 1: std is then NaN or inf, as defined
     const dim3 grid(blocks_for(m)), block(kBlock);
     hot_stats_merge_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(m, ld, c, means, m2s, mean_out, std_out);
-    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+    return hot_detail::note_hip(hipGetLastError());
 }
 
 }  // extern "C"

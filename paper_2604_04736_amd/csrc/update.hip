@@ -225,7 +225,7 @@ int hot_adam_step(const hot_adam *p, int64_t n, float *mu, float *sigma, const f
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (al) hot_adam_kernel<true><<<grid, block, 0, s>>>(n, c, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma);
     else hot_adam_kernel<false><<<grid, block, 0, s>>>(n, c, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma);
-    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+    return hot_detail::note_hip(hipGetLastError());
 }
 
 int hot_forward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep, const float *mu, float *w, void *stream)
@@ -244,7 +244,7 @@ int hot_forward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep, 
     if (al && nt) hot_dropout_forward_kernel<true, true><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv);
     else if (al) hot_dropout_forward_kernel<true, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv);
     else hot_dropout_forward_kernel<false, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv);
-    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+    return hot_detail::note_hip(hipGetLastError());
 }
 
 int hot_backward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep, const float *grad_w, float *grad_mu,
@@ -266,7 +266,7 @@ int hot_backward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep,
     if (al && nt) hot_dropout_backward_kernel<true, true><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv);
     else if (al) hot_dropout_backward_kernel<true, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv);
     else hot_dropout_backward_kernel<false, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv);
-    return hipGetLastError() == hipSuccess ? HOT_OK : HOT_EHIP;
+    return hot_detail::note_hip(hipGetLastError());
 }
 
 }  // extern "C"

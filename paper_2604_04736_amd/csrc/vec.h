@@ -6,6 +6,12 @@
 
 #include <cstdint>
 
+// hipError_t of the last failed HIP call made by this thread through a plan-less entry point
+// (defined in hot.hip; hot_last_hip_error(NULL) returns it).
+namespace hot_detail {
+__attribute__((visibility("hidden"))) int note_hip(hipError_t e);   // records e if it is an error; returns HOT_OK or HOT_EHIP
+}
+
 namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));

@@ -137,3 +137,17 @@ def test_word_bits_are_uniform(oracle):
         counts = np.bincount((bits.ravel() >> shift) & 0xFF, minlength=256)
         chi2 = np.sum((counts - counts.mean()) ** 2 / counts.mean())
         assert chi2 < 400, (shift, chi2)      # 255 degrees of freedom: mean 255, sd 22.6
+
+
+def test_frozen_sample_of_the_definition(oracle):
+    """tests/golden/eps_draw_seed42.txt was written by the oracle (make_eps_golden.py); it freezes the
+    definition, so any later change to generator, counter layout or Box-Muller mapping shows up here."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "eps_draw_seed42.txt")) if l[0] != "#"]
+    col0 = int(rows[0][1])
+    n = len(rows) // 2
+    bits = oracle.eps_bits(n, 2, 42, 3, 5, col0=col0)
+    eps = oracle.eps_normal(n, 2, 42, 3, 5, col0=col0)
+    for s, i, word, e in rows:
+        s, i = int(s), int(i) - col0
+        assert int(bits[s, i]) == int(word, 16)
+        assert eps[s, i] == float(e)

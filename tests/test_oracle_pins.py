@@ -334,3 +334,57 @@ def test_oracle_threads_give_identical_results(oracle):
     a4, b4 = oracle.grad(mu, sigma, eps, G, 6, 10.0, False, 4)
     np.testing.assert_array_equal(a1, a4)
     np.testing.assert_array_equal(b1, b4)
+
+
+def test_grad_equals_autograd_of_the_bayes_by_backprop_objective(oracle):
+    """Algorithm 1 end to end on a tiny Bayesian MLP: automatic differentiation (fp64) of
+    J = (1/S) sum_s Loss(Net(x; mu + sigma*eps_s), y) + KL(mu, sigma)/|D| with respect to mu and sigma
+    must equal the oracle's gradients fed with the per-sample weight gradients G_s = dLoss_s/dw_s."""
+    import torch
+    torch.manual_seed(0)
+    d_in, d_h, d_out, batch, s, dsize = 5, 7, 3, 11, 6, 50.0
+    n = d_in * d_h + d_h + d_h * d_out + d_out
+    mu32 = (torch.randn(n) * 0.3).float()
+    sigma32 = (torch.rand(n) * 0.2 + 0.05).float()
+    eps32 = torch.randn(s, n).float()
+    x = torch.randn(batch, d_in, dtype=torch.float64)
+    y = torch.randn(batch, d_out, dtype=torch.float64)
+
+    def net_loss(w):
+        o = 0
+        w1 = w[o:o + d_in * d_h].view(d_h, d_in); o += d_in * d_h
+        b1 = w[o:o + d_h]; o += d_h
+        w2 = w[o:o + d_h * d_out].view(d_out, d_h); o += d_h * d_out
+        b2 = w[o:o + d_out]
+        h = torch.tanh(x @ w1.T + b1)
+        return ((h @ w2.T + b2 - y) ** 2).mean()
+
+    mu = mu32.double().requires_grad_(True)
+    sigma = sigma32.double().requires_grad_(True)
+    eps = eps32.double()
+    ws = [(mu + sigma * eps[i]) for i in range(s)]
+    for w in ws:
+        w.retain_grad()
+    data = sum(net_loss(w) for w in ws) / s
+    kl = 0.5 * (sigma ** 2 + mu ** 2 - 1 - torch.log(sigma ** 2)).sum()
+    (data + kl / dsize).backward()
+    # autograd's dJ/dw_s carries the 1/S of the average; the path takes G_s = dLoss_s/dw_s
+    G = torch.stack([w.grad * s for w in ws]).float().numpy()
+    # G was rounded to fp32 for the oracle's interface: tolerance 1e-6 relative to the addends
+    gmu, gsig = oracle.grad(mu32.numpy(), sigma32.numpy(), eps32.numpy(), G, s, dsize)
+    scale_mu = np.abs(G).sum(0) / s + np.abs(mu32.numpy()) / dsize
+    scale_sg = np.abs(G * eps32.numpy()).sum(0) / s + (sigma32.numpy() + 1 / sigma32.numpy()) / dsize
+    assert np.all(np.abs(gmu - mu.grad.numpy()) <= 1e-6 * scale_mu)
+    assert np.all(np.abs(gsig - sigma.grad.numpy()) <= 1e-6 * scale_sg)
+    assert oracle.kl(mu32.numpy(), sigma32.numpy()) == pytest.approx(kl.item(), rel=1e-13)
+    w64 = oracle.reparam(mu32.numpy(), sigma32.numpy(), eps32.numpy())
+    np.testing.assert_allclose(w64, torch.stack(ws).detach().numpy(), rtol=1e-15)
+    # the same with the samples on 3 "GPUs" of 2 samples each (Algorithm 2, sum convention)
+    acc_mu, acc_sg = np.zeros(n), np.zeros(n)
+    for p in range(3):
+        a, b = oracle.grad(mu32.numpy(), sigma32.numpy(), np.ascontiguousarray(eps32.numpy()[2 * p:2 * p + 2]),
+                           np.ascontiguousarray(G[2 * p:2 * p + 2]), s, dsize)
+        acc_mu += a
+        acc_sg += b
+    assert np.all(np.abs(acc_mu - mu.grad.numpy()) <= 1e-6 * scale_mu)
+    assert np.all(np.abs(acc_sg - sigma.grad.numpy()) <= 1e-6 * scale_sg)

@@ -384,3 +384,127 @@ def test_hip_graph_replays_equal_eager(hot):
         scratch = torch.randn(1000, device=DEV).sum().item()      # eager work between replays
         assert scratch == scratch
     hot.hot_destroy(plan)
+
+
+def test_random_shapes_offsets_and_launch_shapes(oracle, hot):
+    """Seeded random draw of sizes, pitches, base offsets, sample counts and launch shapes, array and
+    in-kernel eps paths, every output compared element by element."""
+    rs = np.random.default_rng(2026)
+    for case in range(40):
+        n = int(rs.choice([rs.integers(1, 64), rs.integers(64, 5000), rs.integers(5000, 200_000)]))
+        ld = int(n + rs.choice([0, 0, 1, 3, 4, 61]))
+        s = int(rs.integers(1, 20))
+        s_total = int(s * rs.integers(1, 5))
+        offset = int(rs.choice([0, 0, 1, 2, 3]))
+        launch = dict(chunks=int(rs.choice([1, 2, 4])), unroll=int(rs.choice([1, 2, 4])),
+                      nontemporal=int(rs.integers(0, 2)), grid_blocks=int(rs.choice([0, 1, 3, 64])))
+        flags = int(rs.integers(0, 2))
+        _say("case random", case, n, ld, s, s_total, offset, launch, flags)
+        g = torch.Generator().manual_seed(case)
+        def place(t):
+            buf = torch.empty(t.numel() + offset, device=DEV)
+            v = buf[offset:].view(t.shape)
+            v.copy_(t)
+            return v
+        pad = torch.full((s, ld - n), float("nan"))
+        x = {"mu": place(torch.randn(n, generator=g)), "sigma": place(torch.exp(torch.randn(n, generator=g))),
+             "eps": place(torch.cat([torch.randn(s, n, generator=g), pad], 1)),
+             "G": place(torch.cat([torch.randn(s, n, generator=g) * 2, pad], 1))}
+        wl = _WL(n, ld, s, s_total, 1234.5)
+        P.check_all(oracle, hot, x, wl, launch=launch, flags=flags)
+        # in-kernel eps: fused kernels against array kernels fed with the materialised draw
+        rng = hot.hot_rng(seed=case * 7919 + 1, step=case, first_sample=case % 5)
+        plan = hot.hot_create(n, ld, s, s_total, 1234.5, 0, flags)
+        for kern in (hot.HOT_KERNEL_FORWARD_RNG, hot.HOT_KERNEL_BACKWARD_RNG):
+            hot.hot_set_launch(plan, kern, **launch)
+        eps = place(torch.zeros(s, ld))
+        hot.hot_sample_eps(plan, rng, eps)
+        w0, w1 = place(torch.zeros(s, ld)), place(torch.zeros(s, ld))
+        o = [place(torch.zeros(n)) for _ in range(4)]
+        hot.hot_forward(plan, x["mu"], x["sigma"], eps, w0, None)
+        hot.hot_backward(plan, x["mu"], x["sigma"], eps, x["G"], o[0], o[1])
+        hot.hot_forward_rng(plan, rng, x["mu"], x["sigma"], w1, None)
+        hot.hot_backward_rng(plan, rng, x["mu"], x["sigma"], x["G"], o[2], o[3])
+        torch.cuda.synchronize()
+        hot.hot_destroy(plan)
+        assert torch.equal(w0[:, :n], w1[:, :n]) and torch.equal(o[0], o[2]) and torch.equal(o[1], o[3])
+        e64 = oracle.eps_normal(n, s, rng.seed, rng.step, rng.first_sample)
+        assert np.abs(eps[:, :n].cpu().numpy() - e64).max() <= 2e-6 * 5.78
+
+
+def test_two_plans_on_two_streams_at_once(oracle, hot):
+    wl = W.scaled(W.CONFIGS["C3"], 400_000)
+    xa = W.make_inputs(wl, DEV)
+    xb = {k: v.flip(-1).contiguous() for k, v in xa.items()}
+    torch.cuda.synchronize()
+    outs = []
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    plans = [hot.hot_create(wl.n_weights, wl.ld, wl.s_local, wl.s_total, wl.dataset_size, 0) for _ in range(2)]
+    for rep in range(3):
+        outs = []
+        for st, plan, x in zip(streams, plans, (xa, xb)):
+            with torch.cuda.stream(st):
+                w = torch.empty_like(x["eps"])
+                kl = torch.zeros(1, dtype=torch.float64, device=DEV)
+                gmu, gsig = torch.empty_like(x["mu"]), torch.empty_like(x["mu"])
+                hot.hot_forward(plan, x["mu"], x["sigma"], x["eps"], w, kl)
+                hot.hot_backward(plan, x["mu"], x["sigma"], x["eps"], x["G"], gmu, gsig)
+                outs.append((w, kl, gmu, gsig))
+        torch.cuda.synchronize()
+    for plan in plans:
+        hot.hot_destroy(plan)
+    for x, (w, kl, gmu, gsig) in zip((xa, xb), outs):
+        h = P.host(x)
+        P.check_w(oracle, h, w.cpu().numpy(), wl.n_weights)
+        P.check_kl(oracle, h, kl.item())
+        P.check_grads(oracle, h, gmu.cpu().numpy(), gsig.cpu().numpy(), wl.n_weights, wl.s_total, wl.dataset_size)
+
+
+def test_training_step_of_a_small_bayesian_mlp_matches_autograd(hot):
+    """Algorithm 2 on one GPU around a real network: the library does the sample layer, torch autograd
+    only the network; the resulting gradients of mu and sigma equal fp64 autograd of the whole objective."""
+    torch.manual_seed(1)
+    d_in, d_h, d_out, batch, s, dsize = 16, 32, 4, 64, 4, 45000.0
+    n = d_in * d_h + d_h + d_h * d_out + d_out
+    mu = (torch.randn(n) * 0.2).to(DEV)
+    sigma = (torch.rand(n) * 0.1 + 0.02).to(DEV)
+    xb = torch.randn(batch, d_in, device=DEV)
+    yb = torch.randn(batch, d_out, device=DEV)
+    rng = hot.hot_rng(seed=11, step=0, first_sample=0)
+
+    def net_loss(w, x, y):
+        o = 0
+        w1 = w[o:o + d_in * d_h].view(d_h, d_in); o += d_in * d_h
+        b1 = w[o:o + d_h]; o += d_h
+        w2 = w[o:o + d_h * d_out].view(d_out, d_h); o += d_h * d_out
+        b2 = w[o:o + d_out]
+        return ((torch.tanh(x @ w1.T + b1) @ w2.T + b2 - y) ** 2).mean()
+
+    plan = hot.hot_create(n, n, s, s, dsize, 0)
+    w = torch.empty(s, n, device=DEV)
+    kl = torch.zeros(1, dtype=torch.float64, device=DEV)
+    hot.hot_forward_rng(plan, rng, mu, sigma, w, kl)
+    G = torch.empty_like(w)
+    for i in range(s):                       # the network's own forward / backward, per sample
+        wi = w[i].clone().requires_grad_(True)
+        net_loss(wi, xb, yb).backward()
+        G[i] = wi.grad
+    gmu, gsig = torch.empty(n, device=DEV), torch.empty(n, device=DEV)
+    hot.hot_backward_rng(plan, rng, mu, sigma, G, gmu, gsig)
+    eps = torch.empty(s, n, device=DEV)
+    hot.hot_sample_eps(plan, rng, eps)
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+    # reference: the whole objective in fp64 on the CPU, differentiated by autograd
+    m64 = mu.double().cpu().requires_grad_(True)
+    s64 = sigma.double().cpu().requires_grad_(True)
+    e64 = eps.double().cpu()
+    data = sum(net_loss(m64 + s64 * e64[i], xb.double().cpu(), yb.double().cpu()) for i in range(s)) / s
+    kl64 = 0.5 * (s64 ** 2 + m64 ** 2 - 1 - 2 * torch.log(s64)).sum()
+    (data + kl64 / dsize).backward()
+    assert abs(kl.item() - kl64.item()) <= 1e-7 * abs(kl64.item())
+    Gh = G.double().cpu()
+    tol_mu = 1e-4 * (Gh.abs().sum(0) / s + m64.detach().abs() / dsize)       # G itself is an fp32 autograd result
+    tol_sg = 1e-4 * ((Gh * e64).abs().sum(0) / s + (s64.detach() + 1 / s64.detach()) / dsize)
+    assert torch.all((gmu.double().cpu() - m64.grad).abs() <= tol_mu)
+    assert torch.all((gsig.double().cpu() - s64.grad).abs() <= tol_sg)

@@ -789,24 +789,24 @@ int hot_create(hot_plan **out, const hot_desc *desc)
         delete p;
         return oom ? HOT_ENOMEM : hot_detail::note_hip(e);
     }
-    // Defaults from launch-shape sweeps on MI355X: the forward kernel and a backward pass over
-    // two or three samples run best with four chunks per thread; with four or more samples the
-    // backward kernel prefers two chunks and four rows in flight.  Non-temporal hints pay only
-    // when the streamed arrays are larger than the 256 MiB memory-side cache.
+    // Defaults from launch-shape sweeps on MI355X, each kernel timed with the other one running in
+    // between (timing a kernel back to back with itself lets part of its input stay in the 256 MiB
+    // memory-side cache and favours shapes that lose in a real step): four chunks per thread for
+    // the array kernels, single rows in flight forward, as many rows as there are (up to four)
+    // backward.  Non-temporal hints pay only when the streamed arrays are larger than that cache.
     const bool streams_exceed_cache = (double)d.s_local * (double)d.ld * 4.0 >= 256.0 * 1048576.0;
     hot_launch &f = p->cfg[HOT_KERNEL_FORWARD], &b = p->cfg[HOT_KERNEL_BACKWARD];
     f.grid_blocks = b.grid_blocks = kMaxGrid;
-    f.chunks = 4;
+    f.chunks = b.chunks = 4;
     f.unroll = 1;
-    b.chunks = d.s_local >= 4 ? 2 : 4;
-    b.unroll = pick_unroll(d.s_local >= 4 ? 4 : 2, d.s_local);
+    b.unroll = pick_unroll(4, d.s_local);
     f.nontemporal = b.nontemporal = streams_exceed_cache ? 1 : 0;
-    // The drawing variants have no eps loads to keep in flight; their sweeps preferred four chunks
-    // for the forward kernel and, from four samples on, two chunks and single rows backward.
+    // The drawing variants have no eps loads to keep in flight: forward as above; backward prefers
+    // two chunks and single rows from four samples on.
     hot_launch &fr = p->cfg[HOT_KERNEL_FORWARD_RNG], &br = p->cfg[HOT_KERNEL_BACKWARD_RNG];
     fr = f;
-    fr.unroll = pick_unroll(d.s_local >= 4 ? 2 : 1, d.s_local);
     br = b;
+    br.chunks = d.s_local >= 4 ? 2 : 4;
     br.unroll = pick_unroll(d.s_local >= 4 ? 1 : 2, d.s_local);
     *out = p;
     return HOT_OK;

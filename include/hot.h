@@ -47,6 +47,8 @@ enum {
 /* hot_desc.flags */
 #define HOT_REDUCE_SUM 0u  /* g = 1/S,     k = S_loc/(S*|D|): add the outputs of all GPUs      */
 #define HOT_REDUCE_MEAN 1u /* g = 1/S_loc, k = 1/|D|:         average the outputs of all GPUs  */
+#define HOT_REDUCE_NONE 2u /* g = 1,       k = 1/|D|: grad_w already carries the caller's scaling (it is
+                              dJ/dw of an objective J; the outputs are then dJ/dmu, dJ/dsigma of J + KL/|D|) */
 
 typedef struct hot_plan hot_plan;
 
@@ -58,7 +60,7 @@ typedef struct hot_desc {
     int32_t s_total;     /* S >= S_loc: samples over all GPUs */
     double dataset_size; /* |D| > 0 */
     int32_t device;      /* HIP device ordinal that owns the buffers and the stream */
-    uint32_t flags;      /* HOT_REDUCE_SUM or HOT_REDUCE_MEAN */
+    uint32_t flags;      /* HOT_REDUCE_SUM, HOT_REDUCE_MEAN or HOT_REDUCE_NONE */
 } hot_desc;
 
 /* Launch geometry of one kernel; a zero field means "library default". */
@@ -132,6 +134,21 @@ int hot_forward_rng(hot_plan *plan, const hot_rng *rng, const float *mu, const f
                     float *w, double *kl_out, void *stream);
 int hot_backward_rng(hot_plan *plan, const hot_rng *rng, const float *mu, const float *sigma,
                      const float *grad_w, float *grad_mu, float *grad_sigma, void *stream);
+
+/*
+ * The backward step over a SUBSET of the local samples, for callers that obtain the per-sample
+ * weight gradients one (or a few) at a time and do not want to hold grad_w for all S_loc
+ * samples: processes local samples first_row .. first_row + rows - 1.  grad_w (and eps, if
+ * given) point at [rows, ld] arrays holding just those samples.  Exactly one of rng / eps is
+ * non-NULL: with rng the eps of those samples is regenerated (sample index first_sample +
+ * first_row + r), with eps it is read.  accumulate != 0 adds into grad_mu / grad_sigma instead
+ * of overwriting them; add_kl != 0 adds the KL part k * mu, k * (sigma - 1/sigma) (k covers all
+ * S_loc samples, so set it on exactly one of the calls of a step).  The calls of one step
+ * together equal one hot_backward / hot_backward_rng up to fp32 rounding of the running sums.
+ */
+int hot_backward_rows(hot_plan *plan, const hot_rng *rng, const float *mu, const float *sigma, const float *eps,
+                      const float *grad_w, int32_t first_row, int32_t rows, int32_t accumulate, int32_t add_kl,
+                      float *grad_mu, float *grad_sigma, void *stream);
 
 /*
  * The draw on its own: eps[S_loc, ld] as fp32 (exactly the values the *_rng calls use), or
@@ -215,7 +232,7 @@ int hot_adam_step(const hot_adam *params, int64_t n, float *mu, float *sigma, co
  * own mask).  For sample s and weight i the mask bit is (generator word of (s, i) <
  * floor(keep * 2^32)), the word being the one hot_sample_bits returns for the same hot_rng:
  *   forward   w[s,i]     = mu[i] * bit / keep                  (1/keep keeps E[w] = mu)
- *   backward  grad_mu[i] = g * sum_s grad_w[s,i] * bit / keep   (g = 1/S, or 1/S_loc with HOT_REDUCE_MEAN)
+ *   backward  grad_mu[i] = g * sum_s grad_w[s,i] * bit / keep   (g = 1/S; 1/S_loc with HOT_REDUCE_MEAN; 1 with HOT_REDUCE_NONE)
  * The mask is never stored; the backward call regenerates it.  desc gives N, ld, S_loc, S and
  * the reduce convention (dataset_size and device are not used); 0 < keep <= 1.  Layouts and
  * alignment rules as for hot_forward / hot_backward.  Current device.

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhot.so")
 
 HOT_OK, HOT_EINVAL, HOT_ENOMEM, HOT_EHIP = 0, -1, -2, -3
-HOT_REDUCE_SUM, HOT_REDUCE_MEAN = 0, 1
+HOT_REDUCE_SUM, HOT_REDUCE_MEAN, HOT_REDUCE_NONE = 0, 1, 2
 HOT_KERNEL_FORWARD, HOT_KERNEL_BACKWARD, HOT_KERNEL_FORWARD_RNG, HOT_KERNEL_BACKWARD_RNG = 0, 1, 2, 3
 
 EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_launch",
@@ -25,7 +25,7 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_version", "hot_probe_copy", "hot_forward_rng", "hot_backward_rng",
            "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
            "hot_stats_merge", "hot_linear_forward_rng", "hot_adam_step", "hot_forward_dropout_rng",
-           "hot_backward_dropout_rng")
+           "hot_backward_dropout_rng", "hot_backward_rows")
 
 
 class hot_desc(ctypes.Structure):
@@ -82,6 +82,8 @@ def lib() -> ctypes.CDLL:
     rp = ctypes.POINTER(hot_rng)
     L.hot_forward_rng.argtypes = [vp, rp, fp, fp, fp, vp, vp]
     L.hot_backward_rng.argtypes = [vp, rp, fp, fp, fp, fp, fp, vp]
+    L.hot_backward_rows.argtypes = [vp, rp, fp, fp, fp, fp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                    ctypes.c_int32, fp, fp, vp]
     L.hot_sample_eps.argtypes = [vp, rp, fp, vp]
     L.hot_sample_bits.argtypes = [vp, rp, vp, vp]
     L.hot_set_launch.argtypes = [vp, ctypes.c_int, ctypes.POINTER(hot_launch)]
@@ -410,4 +412,21 @@ def hot_backward_dropout_rng(plan: Plan, rng: hot_rng, keep: float, grad_w, grad
                                               _mat(grad_w, d.s_local, d.n_weights, d.ld, d.device, "grad_w"),
                                               _vec(grad_mu, d.n_weights, d.device, "grad_mu"), _stream(d.device))
     if code != HOT_OK:
-        raise HotError(code, "hot_backward_dropout_rng")
+        raise HotError(code, "hot_backward_dropout_rng", "hot_backward_rows")
+
+
+def hot_backward_rows(plan: Plan, rng, mu, sigma, eps, grad_w, first_row: int, accumulate: bool, add_kl: bool,
+                      grad_mu, grad_sigma) -> None:
+    """hot_backward over the local samples first_row .. first_row + grad_w.shape[0] - 1 only (see hot.h)."""
+    d = plan.desc
+    rows = grad_w.shape[0]
+    if (rng is None) == (eps is None):
+        raise ValueError("give exactly one of rng and eps")
+    code = lib().hot_backward_rows(plan.handle, ctypes.byref(rng) if rng is not None else None,
+                                   _vec(mu, d.n_weights, d.device, "mu"), _vec(sigma, d.n_weights, d.device, "sigma"),
+                                   _mat(eps, rows, d.n_weights, d.ld, d.device, "eps") if eps is not None else None,
+                                   _mat(grad_w, rows, d.n_weights, d.ld, d.device, "grad_w"), first_row, rows,
+                                   1 if accumulate else 0, 1 if add_kl else 0,
+                                   _vec(grad_mu, d.n_weights, d.device, "grad_mu"),
+                                   _vec(grad_sigma, d.n_weights, d.device, "grad_sigma"), _stream(d.device))
+    _check(code, "hot_backward_rows", plan)

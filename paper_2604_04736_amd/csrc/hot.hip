@@ -71,13 +71,14 @@ __device__ __forceinline__ double kl_addend(float m, float sd)
 }
 
 // grad_mu and grad_sigma of one weight from its fp64 sample sums (Algorithm 2, gradient
-// and averaging lines; d KL / d mu = mu, d KL / d sigma = sigma - 1/sigma).
+// and averaging lines; d KL / d mu = mu, d KL / d sigma = sigma - 1/sigma).  old_m, old_s are the
+// values already in the outputs when the call accumulates, else 0.
 __device__ __forceinline__ void finish_grad(double sum_g, double sum_ge, float m, float sd,
-                                            double g, double k, float &gm, float &gs)
+                                            double g, double k, float old_m, float old_s, float &gm, float &gs)
 {
     const float inv = 1.0f / sd;
-    gm = (float)fma(g, sum_g, k * (double)m);
-    gs = (float)fma(g, sum_ge, k * ((double)sd - (double)inv));
+    gm = (float)(fma(g, sum_g, k * (double)m) + (double)old_m);
+    gs = (float)(fma(g, sum_ge, k * ((double)sd - (double)inv)) + (double)old_s);
 }
 
 // Sum over the workgroup, complete in thread 0.  Fixed tree, hence deterministic.
@@ -263,7 +264,7 @@ __device__ __forceinline__ void backward_rows(int s, long col0, long ld, double 
 
 template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool GEN>
 __global__ void __launch_bounds__(kBlock)
-hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
+hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int accumulate,
                     const float *__restrict__ mu, const float *__restrict__ sigma,
                     const float *__restrict__ eps, const float *__restrict__ gw,
                     float *__restrict__ gmu, float *__restrict__ gsig, Rng rng)
@@ -293,11 +294,15 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                 backward_rows<CHUNKS, 1, ALIGNED, NT, GEN>(s, col0, ld, sum_g, sum_ge, eps, gw, rng);
 #pragma unroll
             for (int c = 0; c < CHUNKS; ++c) {
-                f4 om, os;
+                f4 om = {0.0f, 0.0f, 0.0f, 0.0f}, os = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (accumulate) {
+                    om = load4<ALIGNED, false>(gmu + col0 + c * kStep);
+                    os = load4<ALIGNED, false>(gsig + col0 + c * kStep);
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     float a, b;
-                    finish_grad(sum_g[c][j], sum_ge[c][j], m[c][j], sd[c][j], g, k, a, b);
+                    finish_grad(sum_g[c][j], sum_ge[c][j], m[c][j], sd[c][j], g, k, om[j], os[j], a, b);
                     om[j] = a;
                     os[j] = b;
                 }
@@ -321,11 +326,15 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                             sum_ge[j] = fma(gd, (double)ev[j], sum_ge[j]);
                         }
                     }
-                    f4 om, os;
+                    f4 om = {0.0f, 0.0f, 0.0f, 0.0f}, os = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (accumulate) {
+                        om = load4<ALIGNED, false>(gmu + col);
+                        os = load4<ALIGNED, false>(gsig + col);
+                    }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         float a, b;
-                        finish_grad(sum_g[j], sum_ge[j], m[j], sd[j], g, k, a, b);
+                        finish_grad(sum_g[j], sum_ge[j], m[j], sd[j], g, k, om[j], os[j], a, b);
                         om[j] = a;
                         os[j] = b;
                     }
@@ -341,7 +350,8 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                             sum_ge = fma(gd, (double)eps1<GEN>(eps, at, i, s, rng), sum_ge);
                         }
                         float a, b;
-                        finish_grad(sum_g, sum_ge, mu[i], sigma[i], g, k, a, b);
+                        finish_grad(sum_g, sum_ge, mu[i], sigma[i], g, k, accumulate ? gmu[i] : 0.0f,
+                                    accumulate ? gsig[i] : 0.0f, a, b);
                         gmu[i] = a;
                         gsig[i] = b;
                     }
@@ -485,6 +495,7 @@ struct BwdArgs {
     long n, ld;
     int s_loc;
     double g, k;
+    int accumulate;
     const float *mu, *sigma, *eps, *gw;
     float *gmu, *gsig;
     Rng rng;
@@ -533,7 +544,7 @@ template <bool GEN, int CH, int U, bool AL, bool NT>
 void bwd_go(const BwdArgs &a)
 {
     hot_backward_kernel<CH, U, AL, NT, GEN><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-        a.n, a.ld, a.s_loc, a.g, a.k, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig, a.rng);
+        a.n, a.ld, a.s_loc, a.g, a.k, a.accumulate, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig, a.rng);
 }
 template <bool GEN, int CH, int U>
 void bwd_flags(bool al, bool nt, const BwdArgs &a)
@@ -669,8 +680,11 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
 }
 
+// rows samples starting at local sample first_row (eps and grad_w point at the first of them);
+// rows = 0 means all of the plan's samples.
 int backward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
-                  const float *eps, const float *grad_w, float *grad_mu, float *grad_sigma, void *stream)
+                  const float *eps, const float *grad_w, float *grad_mu, float *grad_sigma, void *stream,
+                  int first_row = 0, int rows = 0, bool accumulate = false, bool add_kl = true)
 {
     const bool gen = rng != nullptr;
     if (!mu || !sigma || !grad_w || !grad_mu || !grad_sigma || (!gen && !eps)) return HOT_EINVAL;
@@ -685,9 +699,10 @@ int backward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, c
     BwdArgs a;
     a.n = d.n_weights;
     a.ld = d.ld;
-    a.s_loc = d.s_local;
+    a.s_loc = rows > 0 ? rows : d.s_local;
     a.g = plan->g;
-    a.k = plan->k;
+    a.k = add_kl ? plan->k : 0.0;
+    a.accumulate = accumulate ? 1 : 0;
     a.mu = mu;
     a.sigma = sigma;
     a.eps = eps;
@@ -695,6 +710,7 @@ int backward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, c
     a.gmu = grad_mu;
     a.gsig = grad_sigma;
     a.rng = gen ? *rng : Rng{0, 0, 0, 0};
+    a.rng.first_sample += (unsigned)first_row;
     a.grid = dim3(grid_for(d.n_weights, c));
     a.stream = static_cast<hipStream_t>(stream);
 
@@ -760,7 +776,7 @@ int hot_create(hot_plan **out, const hot_desc *desc)
     const hot_desc &d = *desc;
     if (d.n_weights < 1 || d.ld < d.n_weights || d.s_local < 1 || d.s_total < d.s_local) return HOT_EINVAL;
     if (!(d.dataset_size > 0.0) || !(d.dataset_size < 1.0 / 0.0)) return HOT_EINVAL;
-    if (d.flags != HOT_REDUCE_SUM && d.flags != HOT_REDUCE_MEAN) return HOT_EINVAL;
+    if (d.flags != HOT_REDUCE_SUM && d.flags != HOT_REDUCE_MEAN && d.flags != HOT_REDUCE_NONE) return HOT_EINVAL;
     // element offsets (s_local - 1) * ld + n_weights must fit in 63 bits
     if (d.ld > (INT64_MAX / 4) / d.s_local) return HOT_EINVAL;
     int n_dev = 0;
@@ -770,7 +786,10 @@ int hot_create(hot_plan **out, const hot_desc *desc)
     hot_plan *p = new (std::nothrow) hot_plan();
     if (!p) return HOT_ENOMEM;
     p->d = d;
-    if (d.flags == HOT_REDUCE_MEAN) {
+    if (d.flags == HOT_REDUCE_NONE) {
+        p->g = 1.0;
+        p->k = 1.0 / d.dataset_size;
+    } else if (d.flags == HOT_REDUCE_MEAN) {
         p->g = 1.0 / (double)d.s_local;
         p->k = 1.0 / d.dataset_size;
     } else {
@@ -873,6 +892,22 @@ int hot_backward_rng(hot_plan *plan, const hot_rng *rng, const float *mu, const 
     Rng r;
     if (!plan || !make_rng(rng, plan->d.s_local, r)) return HOT_EINVAL;
     return backward_impl(plan, HOT_KERNEL_BACKWARD_RNG, &r, mu, sigma, nullptr, grad_w, grad_mu, grad_sigma, stream);
+}
+
+int hot_backward_rows(hot_plan *plan, const hot_rng *rng, const float *mu, const float *sigma, const float *eps,
+                      const float *grad_w, int32_t first_row, int32_t rows, int32_t accumulate, int32_t add_kl,
+                      float *grad_mu, float *grad_sigma, void *stream)
+{
+    if (!plan || first_row < 0 || rows < 1 || (long)first_row + rows > plan->d.s_local) return HOT_EINVAL;
+    if ((rng != nullptr) == (eps != nullptr)) return HOT_EINVAL;      // exactly one source of eps
+    if (rng) {
+        Rng r;
+        if (!make_rng(rng, plan->d.s_local, r)) return HOT_EINVAL;
+        return backward_impl(plan, HOT_KERNEL_BACKWARD_RNG, &r, mu, sigma, nullptr, grad_w, grad_mu, grad_sigma, stream,
+                             first_row, rows, accumulate != 0, add_kl != 0);
+    }
+    return backward_impl(plan, HOT_KERNEL_BACKWARD, nullptr, mu, sigma, eps, grad_w, grad_mu, grad_sigma, stream,
+                         first_row, rows, accumulate != 0, add_kl != 0);
 }
 
 int hot_sample_eps(hot_plan *plan, const hot_rng *rng, float *eps, void *stream)

@@ -252,13 +252,14 @@ int hot_backward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep,
 {
     if (!d || !grad_w || !grad_mu || !aligned4(grad_w) || !aligned4(grad_mu)) return HOT_EINVAL;
     if (d->n_weights < 1 || d->ld < d->n_weights || d->s_local < 1 || d->s_total < d->s_local) return HOT_EINVAL;
-    if (d->flags != HOT_REDUCE_SUM && d->flags != HOT_REDUCE_MEAN) return HOT_EINVAL;
+    if (d->flags != HOT_REDUCE_SUM && d->flags != HOT_REDUCE_MEAN && d->flags != HOT_REDUCE_NONE) return HOT_EINVAL;
     if (!(keep > 0.0 && keep <= 1.0)) return HOT_EINVAL;
     Rng r;
     if (!make_rng(rng, d->s_local, r)) return HOT_EINVAL;
     const bool al = aligned16(grad_w) && aligned16(grad_mu) && (d->ld % 4 == 0);
     const bool nt = (double)d->s_local * (double)d->ld * 4.0 >= 256.0 * 1048576.0;
-    const double g = d->flags == HOT_REDUCE_MEAN ? 1.0 / (double)d->s_local : 1.0 / (double)d->s_total;
+    const double g = d->flags == HOT_REDUCE_NONE ? 1.0
+                     : (d->flags == HOT_REDUCE_MEAN ? 1.0 / (double)d->s_local : 1.0 / (double)d->s_total);
     const dim3 grid(blocks_for((d->n_weights + 3) / 4)), block(kBlock);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned thr = dropout_threshold(keep);

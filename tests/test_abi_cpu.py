@@ -72,6 +72,7 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_adam_step(None, 1, None, None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_forward_dropout_rng(None, None, 0.5, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward_dropout_rng(None, None, 0.5, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_backward_rows(None, None, None, None, None, None, 0, 1, 0, 1, None, None, None) == hot.HOT_EINVAL
     assert L.hot_forward_rng(None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward_rng(None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_sample_eps(None, None, None, None) == hot.HOT_EINVAL
@@ -84,6 +85,6 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
                 hot.hot_desc(8, 8, 1, 1, 0.0, 0, 0),        # |D| <= 0
                 hot.hot_desc(8, 8, 1, 1, float("nan"), 0, 0),
                 hot.hot_desc(8, 8, 1, 1, float("inf"), 0, 0),
-                hot.hot_desc(8, 8, 1, 1, 1.0, 0, 7)]:       # unknown flag
+                hot.hot_desc(8, 8, 1, 1, 1.0, 0, 3)]:       # unknown flag
         assert L.hot_create(ctypes.byref(out), ctypes.byref(bad)) == hot.HOT_EINVAL
         assert not out.value

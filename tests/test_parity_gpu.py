@@ -508,3 +508,103 @@ def test_training_step_of_a_small_bayesian_mlp_matches_autograd(hot):
     tol_sg = 1e-4 * ((Gh * e64).abs().sum(0) / s + (s64.detach() + 1 / s64.detach()) / dsize)
     assert torch.all((gmu.double().cpu() - m64.grad).abs() <= tol_mu)
     assert torch.all((gsig.double().cpu() - s64.grad).abs() <= tol_sg)
+
+
+@pytest.mark.parametrize("groups", [[1] * 6, [2, 4], [5, 1], [6]])
+@pytest.mark.parametrize("use_rng", [False, True])
+def test_backward_over_subsets_of_samples_accumulates_to_the_whole(oracle, hot, groups, use_rng):
+    n, ld, s, s_total, dsize = 50_003, 50_016, 6, 12, 777.0
+    x = _random_case(n, ld, s, seed=21)
+    plan = hot.hot_create(n, ld, s, s_total, dsize, 0)
+    rng = hot.hot_rng(seed=8, step=3, first_sample=6)
+    if use_rng:
+        hot.hot_sample_eps(plan, rng, x["eps"])
+    whole_mu, whole_sg = torch.empty(n, device=DEV), torch.empty(n, device=DEV)
+    if use_rng:
+        hot.hot_backward_rng(plan, rng, x["mu"], x["sigma"], x["G"], whole_mu, whole_sg)
+    else:
+        hot.hot_backward(plan, x["mu"], x["sigma"], x["eps"], x["G"], whole_mu, whole_sg)
+    acc_mu = torch.full((n,), float("nan"), device=DEV)
+    acc_sg = torch.full((n,), float("nan"), device=DEV)
+    at = 0
+    for i, g in enumerate(groups):
+        hot.hot_backward_rows(plan, rng if use_rng else None, x["mu"], x["sigma"],
+                              None if use_rng else x["eps"][at:at + g], x["G"][at:at + g], at,
+                              accumulate=i > 0, add_kl=i == len(groups) - 1, grad_mu=acc_mu, grad_sigma=acc_sg)
+        at += g
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+    if len(groups) == 1:
+        assert torch.equal(acc_mu, whole_mu) and torch.equal(acc_sg, whole_sg)
+    h = P.host(x)
+    # every partial call rounds the running sums to fp32 once: the usual tolerance covers it
+    P.check_grads(oracle, h, acc_mu.cpu().numpy(), acc_sg.cpu().numpy(), n, s_total, dsize)
+    P.check_grads(oracle, h, whole_mu.cpu().numpy(), whole_sg.cpu().numpy(), n, s_total, dsize)
+
+
+def test_backward_rows_rejects_bad_ranges(hot):
+    plan = hot.hot_create(64, 64, 4, 4, 1.0, 0)
+    t = torch.zeros(4, 64, device=DEV)
+    v = torch.zeros(64, device=DEV)
+    rng = hot.hot_rng(seed=1, step=0, first_sample=0)
+    with pytest.raises(hot.HotError):
+        hot.hot_backward_rows(plan, None, v, v + 1, t[:2], t[:2], 3, False, True, v.clone(), v.clone())     # rows 3..4 of 4
+    with pytest.raises(ValueError):
+        hot.hot_backward_rows(plan, rng, v, v + 1, t[:2], t[:2], 0, False, True, v.clone(), v.clone())       # both sources
+    with pytest.raises(ValueError):
+        hot.hot_backward_rows(plan, None, v, v + 1, None, t[:2], 0, False, True, v.clone(), v.clone())       # no source
+    hot.hot_destroy(plan)
+
+
+def test_autograd_wrapper_trains_a_bayesian_mlp(hot):
+    """The torch.autograd wrapper: gradients equal fp64 autograd of loss + KL/|D|, and a few Adam steps
+    (hot_adam_step) on them lower the loss."""
+    from paper_2604_04736_amd.autograd import GaussianSampleLayer
+    torch.manual_seed(2)
+    d_in, d_h, d_out, batch, s, dsize = 8, 16, 2, 128, 4, 1000.0
+    n = d_in * d_h + d_h + d_h * d_out + d_out
+    xb = torch.randn(batch, d_in, device=DEV)
+    yb = torch.sin(xb[:, :d_out] * 2.0)
+
+    def net_loss(w, x, y):
+        o = 0
+        w1 = w[o:o + d_in * d_h].view(d_h, d_in); o += d_in * d_h
+        b1 = w[o:o + d_h]; o += d_h
+        w2 = w[o:o + d_h * d_out].view(d_out, d_h); o += d_h * d_out
+        b2 = w[o:o + d_out]
+        return ((torch.tanh(x @ w1.T + b1) @ w2.T + b2 - y) ** 2).mean()
+
+    mu = (torch.randn(n, device=DEV) * 0.3).requires_grad_(True)
+    sigma = torch.full((n,), 0.05, device=DEV).requires_grad_(True)
+    layer = GaussianSampleLayer(n, s, dsize, seed=5)
+    w, kl = layer.sample(mu, sigma, step=0)
+    loss = sum(net_loss(w[i], xb, yb) for i in range(s)) / s
+    loss.backward()
+    # reference in fp64 on the CPU with the very same eps
+    eps = torch.empty(s, n, device=DEV)
+    hot.hot_sample_eps(layer.plan, hot.hot_rng(seed=5, step=0, first_sample=0), eps)
+    m64 = mu.detach().double().cpu().requires_grad_(True)
+    s64 = sigma.detach().double().cpu().requires_grad_(True)
+    e64 = eps.double().cpu()
+    ref = sum(net_loss(m64 + s64 * e64[i], xb.double().cpu(), yb.double().cpu()) for i in range(s)) / s
+    kl64 = 0.5 * (s64 ** 2 + m64 ** 2 - 1 - 2 * torch.log(s64)).sum()
+    (ref + kl64 / dsize).backward()
+    assert abs(loss.item() - ref.item()) <= 1e-5 * abs(ref.item())
+    assert abs(kl.item() - kl64.item()) <= 1e-7 * abs(kl64.item())
+    scale = m64.grad.abs().max().item()
+    assert (mu.grad.double().cpu() - m64.grad).abs().max().item() <= 1e-4 * scale
+    assert (sigma.grad.double().cpu() - s64.grad).abs().max().item() <= 1e-4 * s64.grad.abs().max().item()
+    # a short training run: Adam through the library
+    state = [torch.zeros(n, device=DEV) for _ in range(4)]
+    first = last = None
+    for t in range(1, 61):
+        mu.grad = sigma.grad = None
+        w, kl = layer.sample(mu, sigma, step=t)
+        loss = sum(net_loss(w[i], xb, yb) for i in range(s)) / s
+        loss.backward()
+        with torch.no_grad():
+            hot.hot_adam_step(hot.hot_adam(2e-2, 0.9, 0.999, 1e-8, 1.0, 1e-4, t), mu.data, sigma.data, mu.grad, sigma.grad, *state)
+        first = loss.item() if first is None else first
+        last = loss.item()
+    assert last < 0.5 * first, (first, last)
+    assert sigma.min().item() >= 1e-4 * (1 - 1e-6)

@@ -76,9 +76,11 @@ __device__ __forceinline__ double kl_addend(float m, float sd)
 __device__ __forceinline__ void finish_grad(double sum_g, double sum_ge, float m, float sd,
                                             double g, double k, float old_m, float old_s, float &gm, float &gs)
 {
-    const float inv = 1.0f / sd;
-    gm = (float)(fma(g, sum_g, k * (double)m) + (double)old_m);
-    gs = (float)(fma(g, sum_ge, k * ((double)sd - (double)inv)) + (double)old_s);
+    // k = 0 (a partial call that leaves the KL part to another one) must not turn sigma = 0 into NaN
+    const double kl_m = k != 0.0 ? k * (double)m : 0.0;
+    const double kl_s = k != 0.0 ? k * ((double)sd - (double)(1.0f / sd)) : 0.0;
+    gm = (float)(fma(g, sum_g, kl_m) + (double)old_m);
+    gs = (float)(fma(g, sum_ge, kl_s) + (double)old_s);
 }
 
 // Sum over the workgroup, complete in thread 0.  Fixed tree, hence deterministic.

@@ -72,12 +72,15 @@ def time_steps(hot, torch, wl, x, steps: int, warmup: int, in_kernel_eps: bool =
         step(ev[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
-    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    fwd_all = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    bwd_all = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    fwd_ms, bwd_ms = sum(fwd_all) / steps, sum(bwd_all) / steps
+    spread = {"fwd_median_ms": fwd_all[steps // 2], "fwd_min_ms": fwd_all[0],
+              "bwd_median_ms": bwd_all[steps // 2], "bwd_min_ms": bwd_all[0]}
     launch = {"forward": hot.hot_get_launch(plan, hot.HOT_KERNEL_FORWARD_RNG if in_kernel_eps else hot.HOT_KERNEL_FORWARD),
               "backward": hot.hot_get_launch(plan, hot.HOT_KERNEL_BACKWARD_RNG if in_kernel_eps else hot.HOT_KERNEL_BACKWARD)}
     hot.hot_destroy(plan)
-    return {"wall_s": wall, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "launch": launch,
+    return {"wall_s": wall, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "spread": spread, "launch": launch,
             "out": {"w": w, "kl": kl, "gmu": gmu, "gsig": gsig}}
 
 
@@ -152,7 +155,20 @@ def cpu_baseline(oracle, np, wl, x, max_weights: int):
     gm, gs = oracle.grad(h["mu"], h["sigma"], h["eps"], h["G"], wl.s_total, wl.dataset_size, False, used)
     dt = time.perf_counter() - t0
     del w64, gm, gs
+    # the same three calls on one thread, over an eighth of the sample
+    n1 = max(1, n // 8)
+    h1 = {"mu": h["mu"][:n1], "sigma": h["sigma"][:n1], "eps": np.ascontiguousarray(h["eps"][:, :n1]),
+          "G": np.ascontiguousarray(h["G"][:, :n1])}
+    one = oracle.threads(1)
+    t1 = time.perf_counter()
+    w64 = oracle.reparam(h1["mu"], h1["sigma"], h1["eps"], one)
+    oracle.kl(h1["mu"], h1["sigma"])
+    gm, gs = oracle.grad(h1["mu"], h1["sigma"], h1["eps"], h1["G"], wl.s_total, wl.dataset_size, False, one)
+    dt1 = time.perf_counter() - t1
+    del w64, gm, gs
     return {"value": n * wl.s_local / dt, "unit": "items/s", "cores": used, "kind": "oracle",
+            "single_thread": {"value": n1 * wl.s_local / dt1, "unit": "items/s", "cores": one,
+                              "sample": f"first {n1} weights, {dt1:.1f} s"},
             "sample": f"first {n} of {wl.n_weights} weights x {wl.s_local} samples of {wl.name}, "
                       f"forward + KL + backward, {dt:.1f} s (KL sum is serial by definition)",
             "kl": kl64}
@@ -417,10 +433,10 @@ def main() -> int:
                      "traffic": measured_traffic(f"hot_{dominant}{kname}_kernel", wl.name),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "kernels": {
-            "forward": {"ms": r["fwd_ms"], "GBps": fwd_b / r["fwd_ms"] / 1e6, "items_per_s": items / r["fwd_ms"] * 1e3,
+            "forward": {"ms": r["fwd_ms"], "median_ms": r["spread"]["fwd_median_ms"], "min_ms": r["spread"]["fwd_min_ms"], "GBps": fwd_b / r["fwd_ms"] / 1e6, "items_per_s": items / r["fwd_ms"] * 1e3,
                         "frac_of_hbm_peak": fwd_b / r["fwd_ms"] / 1e6 / HBM_PEAK_GBS,
                         "note": "interval between HIP events; includes the one-workgroup KL finish kernel"},
-            "backward": {"ms": r["bwd_ms"], "GBps": bwd_b / r["bwd_ms"] / 1e6, "items_per_s": items / r["bwd_ms"] * 1e3,
+            "backward": {"ms": r["bwd_ms"], "median_ms": r["spread"]["bwd_median_ms"], "min_ms": r["spread"]["bwd_min_ms"], "GBps": bwd_b / r["bwd_ms"] / 1e6, "items_per_s": items / r["bwd_ms"] * 1e3,
                          "frac_of_hbm_peak": bwd_b / r["bwd_ms"] / 1e6 / HBM_PEAK_GBS},
         },
         "step_frac_of_hbm_roofline": (fwd_b + bwd_b) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

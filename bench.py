@@ -280,7 +280,25 @@ def update_and_dropout_lines(hot, torch, dev, wl, iters: int = 10):
     ms = timeit(adam)
     out = {"adam": {"ms": ms, "weights_per_s": n / (ms * 1e-3), "GBps": 56.0 * n / ms / 1e6,
                     "frac_of_hbm_peak": 56.0 * n / ms / 1e6 / HBM_PEAK_GBS, "bytes_per_weight": 56}}
-    del a
+    # Algorithm 1's pair of steps on one GPU that holds all its samples: hot_backward then hot_adam_step,
+    # against hot_backward_adam (gradients never written); lr = 0 keeps sigma where it is
+    G = torch.randn(s, ld, device=dev)
+    eps = torch.randn(s, ld, device=dev)
+    plan1 = hot.hot_create(n, ld, s, s, wl.dataset_size, dev.index or 0)
+    still = hot.hot_adam(0.0, 0.9, 0.999, 1e-8, 1.0, 0.0, 1)
+
+    def two_calls():
+        hot.hot_backward(plan1, a[0], a[1], eps, G, a[2], a[3])
+        hot.hot_adam_step(still, a[0], a[1], a[2], a[3], *a[4:])
+
+    ms_two = timeit(two_calls)
+    ms_one = timeit(lambda: hot.hot_backward_adam(plan1, None, still, a[0], a[1], eps, G, *a[4:]))
+    hot.hot_destroy(plan1)
+    b_two, b_one = 4.0 * n * (2 * s + 4) + 56.0 * n, 4.0 * n * (2 * s + 2) + 40.0 * n
+    out["backward_adam_fused"] = {"ms": ms_one, "GBps": b_one / ms_one / 1e6, "frac_of_hbm_peak": b_one / ms_one / 1e6 / HBM_PEAK_GBS,
+                                  "bytes_per_weight": b_one / n, "two_calls_ms": ms_two, "two_calls_bytes_per_weight": b_two / n,
+                                  "speedup": ms_two / ms_one, "samples": s}
+    del a, G, eps
     torch.cuda.empty_cache()
     mu = torch.randn(n, device=dev)
     w = torch.empty(s, ld, device=dev)

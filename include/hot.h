@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 200 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 201 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
@@ -225,6 +225,24 @@ typedef struct hot_adam {
 int hot_adam_step(const hot_adam *params, int64_t n, float *mu, float *sigma, const float *grad_mu,
                   const float *grad_sigma, float *m_mu, float *v_mu, float *m_sigma, float *v_sigma,
                   void *stream);
+
+/*
+ * Algorithm 1 (one GPU holds all S samples, so nothing is all-reduced between the gradient line
+ * and the update line): hot_backward followed by hot_adam_step in ONE pass.  The gradients
+ * grad_mu, grad_sigma of hot_backward are formed in registers, rounded to fp32 exactly as
+ * hot_backward would store them, and consumed by the Adam update of hot_adam_step; they are
+ * never written.  The result is bit-identical to the two calls, at 16 bytes per weight less
+ * traffic than they need together (8 written, 8 read back).
+ * Requires a plan with s_local == s_total (else HOT_EINVAL: with several GPUs the all-reduce
+ * has to come between the two steps).  Exactly one of rng / eps is non-NULL (eps regenerated
+ * from rng, or read from eps[S, ld]).  mu, sigma [N] and the four moment arrays [N] are read
+ * and overwritten; grad_w [S, ld] is read.  Layout, alignment, stream and error rules as for
+ * hot_backward; the launch geometry is that of HOT_KERNEL_BACKWARD (HOT_KERNEL_BACKWARD_RNG
+ * with rng).
+ */
+int hot_backward_adam(hot_plan *plan, const hot_rng *rng, const hot_adam *params, float *mu, float *sigma,
+                      const float *eps, const float *grad_w, float *m_mu, float *v_mu, float *m_sigma,
+                      float *v_sigma, void *stream);
 
 /*
  * Monte Carlo dropout in weight space (section "Monte Carlo Dropout": dropout amounts to

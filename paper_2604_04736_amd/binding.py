@@ -25,7 +25,7 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_version", "hot_probe_copy", "hot_forward_rng", "hot_backward_rng",
            "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
            "hot_stats_merge", "hot_linear_forward_rng", "hot_adam_step", "hot_forward_dropout_rng",
-           "hot_backward_dropout_rng", "hot_backward_rows")
+           "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam")
 
 
 class hot_desc(ctypes.Structure):
@@ -102,6 +102,7 @@ def lib() -> ctypes.CDLL:
     L.hot_linear_forward_rng.restype = ctypes.c_int
     L.hot_adam_step.argtypes = [ctypes.POINTER(hot_adam), ctypes.c_int64] + [fp] * 8 + [vp]
     L.hot_adam_step.restype = ctypes.c_int
+    L.hot_backward_adam.argtypes = [vp, rp, ctypes.POINTER(hot_adam)] + [fp] * 8 + [vp]
     L.hot_forward_dropout_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, fp, fp, vp]
     L.hot_forward_dropout_rng.restype = ctypes.c_int
     L.hot_backward_dropout_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, fp, fp, vp]
@@ -412,7 +413,7 @@ def hot_backward_dropout_rng(plan: Plan, rng: hot_rng, keep: float, grad_w, grad
                                               _mat(grad_w, d.s_local, d.n_weights, d.ld, d.device, "grad_w"),
                                               _vec(grad_mu, d.n_weights, d.device, "grad_mu"), _stream(d.device))
     if code != HOT_OK:
-        raise HotError(code, "hot_backward_dropout_rng", "hot_backward_rows")
+        raise HotError(code, "hot_backward_dropout_rng")
 
 
 def hot_backward_rows(plan: Plan, rng, mu, sigma, eps, grad_w, first_row: int, accumulate: bool, add_kl: bool,
@@ -430,3 +431,18 @@ def hot_backward_rows(plan: Plan, rng, mu, sigma, eps, grad_w, first_row: int, a
                                    _vec(grad_mu, d.n_weights, d.device, "grad_mu"),
                                    _vec(grad_sigma, d.n_weights, d.device, "grad_sigma"), _stream(d.device))
     _check(code, "hot_backward_rows", plan)
+
+
+def hot_backward_adam(plan: Plan, rng, params: hot_adam, mu, sigma, eps, grad_w, m_mu, v_mu, m_sigma, v_sigma) -> None:
+    """hot_backward and hot_adam_step in one pass for a plan that holds all S samples (see include/hot.h)."""
+    d = plan.desc
+    if (rng is None) == (eps is None):
+        raise ValueError("give exactly one of rng and eps")
+    n, dev = d.n_weights, d.device
+    code = lib().hot_backward_adam(plan.handle, ctypes.byref(rng) if rng is not None else None, ctypes.byref(params),
+                                   _vec(mu, n, dev, "mu"), _vec(sigma, n, dev, "sigma"),
+                                   _mat(eps, d.s_local, n, d.ld, dev, "eps") if eps is not None else None,
+                                   _mat(grad_w, d.s_local, n, d.ld, dev, "grad_w"),
+                                   _vec(m_mu, n, dev, "m_mu"), _vec(v_mu, n, dev, "v_mu"),
+                                   _vec(m_sigma, n, dev, "m_sigma"), _vec(v_sigma, n, dev, "v_sigma"), _stream(dev))
+    _check(code, "hot_backward_adam", plan)

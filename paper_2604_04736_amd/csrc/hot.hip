@@ -25,6 +25,7 @@
 #include "hot.h"
 #include "vec.h"
 #include "draw.h"
+#include "adam.h"
 
 namespace {
 
@@ -70,18 +71,85 @@ __device__ __forceinline__ double kl_addend(float m, float sd)
     return fma(sdd, sdd, fma(md, md, -1.0)) - 2.0 * ln_sd;
 }
 
-// grad_mu and grad_sigma of one weight from its fp64 sample sums (Algorithm 2, gradient
-// and averaging lines; d KL / d mu = mu, d KL / d sigma = sigma - 1/sigma).  old_m, old_s are the
-// values already in the outputs when the call accumulates, else 0.
+// grad_mu and grad_sigma of one weight, in fp64, from its fp64 sample sums (Algorithm 2, gradient
+// and averaging lines; d KL / d mu = mu, d KL / d sigma = sigma - 1/sigma).
 __device__ __forceinline__ void finish_grad(double sum_g, double sum_ge, float m, float sd,
-                                            double g, double k, float old_m, float old_s, float &gm, float &gs)
+                                            double g, double k, double &gm, double &gs)
 {
     // k = 0 (a partial call that leaves the KL part to another one) must not turn sigma = 0 into NaN
     const double kl_m = k != 0.0 ? k * (double)m : 0.0;
     const double kl_s = k != 0.0 ? k * ((double)sd - (double)(1.0f / sd)) : 0.0;
-    gm = (float)(fma(g, sum_g, kl_m) + (double)old_m);
-    gs = (float)(fma(g, sum_ge, kl_s) + (double)old_s);
+    gm = fma(g, sum_g, kl_m);
+    gs = fma(g, sum_ge, kl_s);
 }
+
+// What the backward kernel does with the finished gradients of a column chunk.
+//
+// StoreGrad: writes them (or adds them to what the outputs hold) as fp32: Algorithm 2, where the
+// all-reduce over GPUs comes next.
+struct StoreGrad {
+    float *gmu, *gsig;
+    int accumulate;
+    template <bool ALIGNED>
+    __device__ __forceinline__ void quad(long col, f4, f4, const double (&gm)[4], const double (&gs)[4]) const
+    {
+        f4 om = {0.0f, 0.0f, 0.0f, 0.0f}, os = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (accumulate) {
+            om = load4<ALIGNED, false>(gmu + col);
+            os = load4<ALIGNED, false>(gsig + col);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            om[j] = (float)(gm[j] + (double)om[j]);
+            os[j] = (float)(gs[j] + (double)os[j]);
+        }
+        store4<ALIGNED, false>(gmu + col, om);
+        store4<ALIGNED, false>(gsig + col, os);
+    }
+    __device__ __forceinline__ void one(long i, float, float, double gm, double gs) const
+    {
+        gmu[i] = (float)(gm + (double)(accumulate ? gmu[i] : 0.0f));
+        gsig[i] = (float)(gs + (double)(accumulate ? gsig[i] : 0.0f));
+    }
+};
+
+// AdamUpdate: Algorithm 1 (one GPU, nothing to all-reduce): the gradients, rounded to fp32 exactly
+// as StoreGrad would store them, go straight into the optimizer's update of mu, sigma and their
+// moments, and are never written.
+struct AdamUpdate {
+    float *mu, *sigma, *m_mu, *v_mu, *m_sig, *v_sig;
+    AdamConst c;
+    template <bool ALIGNED>
+    __device__ __forceinline__ void quad(long col, f4 m, f4 sd, const double (&gm)[4], const double (&gs)[4]) const
+    {
+        f4 a0 = load4<ALIGNED, true>(m_mu + col), b0 = load4<ALIGNED, true>(v_mu + col);
+        f4 a1 = load4<ALIGNED, true>(m_sig + col), b1 = load4<ALIGNED, true>(v_sig + col);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float t = m[j], a = a0[j], b = b0[j];
+            adam_one(t, a, b, (float)gm[j], c);
+            m[j] = t; a0[j] = a; b0[j] = b;
+            t = sd[j]; a = a1[j]; b = b1[j];
+            adam_one_sigma(t, a, b, (float)gs[j], c);
+            sd[j] = t; a1[j] = a; b1[j] = b;
+        }
+        store4<ALIGNED, true>(mu + col, m);
+        store4<ALIGNED, true>(sigma + col, sd);
+        store4<ALIGNED, true>(m_mu + col, a0);
+        store4<ALIGNED, true>(v_mu + col, b0);
+        store4<ALIGNED, true>(m_sig + col, a1);
+        store4<ALIGNED, true>(v_sig + col, b1);
+    }
+    __device__ __forceinline__ void one(long i, float m, float sd, double gm, double gs) const
+    {
+        float a = m_mu[i], b = v_mu[i];
+        adam_one(m, a, b, (float)gm, c);
+        mu[i] = m; m_mu[i] = a; v_mu[i] = b;
+        a = m_sig[i]; b = v_sig[i];
+        adam_one_sigma(sd, a, b, (float)gs, c);
+        sigma[i] = sd; m_sig[i] = a; v_sig[i] = b;
+    }
+};
 
 // Sum over the workgroup, complete in thread 0.  Fixed tree, hence deterministic.
 __device__ __forceinline__ double block_sum(double v, double *lds)
@@ -264,12 +332,11 @@ __device__ __forceinline__ void backward_rows(int s, long col0, long ld, double 
             }
 }
 
-template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool GEN>
+template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool GEN, class EPI>
 __global__ void __launch_bounds__(kBlock)
-hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int accumulate,
-                    const float *__restrict__ mu, const float *__restrict__ sigma,
-                    const float *__restrict__ eps, const float *__restrict__ gw,
-                    float *__restrict__ gmu, float *__restrict__ gsig, Rng rng)
+hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
+                    const float *mu, const float *sigma,
+                    const float *__restrict__ eps, const float *__restrict__ gw, EPI epi, Rng rng)
 {
     constexpr long kTile = (long)kBlock * 4 * CHUNKS;
     constexpr long kStep = (long)kBlock * 4;
@@ -296,20 +363,10 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int accumula
                 backward_rows<CHUNKS, 1, ALIGNED, NT, GEN>(s, col0, ld, sum_g, sum_ge, eps, gw, rng);
 #pragma unroll
             for (int c = 0; c < CHUNKS; ++c) {
-                f4 om = {0.0f, 0.0f, 0.0f, 0.0f}, os = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (accumulate) {
-                    om = load4<ALIGNED, false>(gmu + col0 + c * kStep);
-                    os = load4<ALIGNED, false>(gsig + col0 + c * kStep);
-                }
+                double gm[4], gs[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float a, b;
-                    finish_grad(sum_g[c][j], sum_ge[c][j], m[c][j], sd[c][j], g, k, om[j], os[j], a, b);
-                    om[j] = a;
-                    os[j] = b;
-                }
-                store4<ALIGNED, false>(gmu + col0 + c * kStep, om);
-                store4<ALIGNED, false>(gsig + col0 + c * kStep, os);
+                for (int j = 0; j < 4; ++j) finish_grad(sum_g[c][j], sum_ge[c][j], m[c][j], sd[c][j], g, k, gm[j], gs[j]);
+                epi.template quad<ALIGNED>(col0 + c * kStep, m[c], sd[c], gm, gs);
             }
         } else {
             for (int c = 0; c < CHUNKS; ++c) {
@@ -328,20 +385,10 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int accumula
                             sum_ge[j] = fma(gd, (double)ev[j], sum_ge[j]);
                         }
                     }
-                    f4 om = {0.0f, 0.0f, 0.0f, 0.0f}, os = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if (accumulate) {
-                        om = load4<ALIGNED, false>(gmu + col);
-                        os = load4<ALIGNED, false>(gsig + col);
-                    }
+                    double gm[4], gs[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        float a, b;
-                        finish_grad(sum_g[j], sum_ge[j], m[j], sd[j], g, k, om[j], os[j], a, b);
-                        om[j] = a;
-                        os[j] = b;
-                    }
-                    store4<ALIGNED, false>(gmu + col, om);
-                    store4<ALIGNED, false>(gsig + col, os);
+                    for (int j = 0; j < 4; ++j) finish_grad(sum_g[j], sum_ge[j], m[j], sd[j], g, k, gm[j], gs[j]);
+                    epi.template quad<ALIGNED>(col, m, sd, gm, gs);
                 } else {
                     for (long i = col; i < n; ++i) {
                         double sum_g = 0.0, sum_ge = 0.0;
@@ -351,11 +398,10 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k, int accumula
                             sum_g += gd;
                             sum_ge = fma(gd, (double)eps1<GEN>(eps, at, i, s, rng), sum_ge);
                         }
-                        float a, b;
-                        finish_grad(sum_g, sum_ge, mu[i], sigma[i], g, k, accumulate ? gmu[i] : 0.0f,
-                                    accumulate ? gsig[i] : 0.0f, a, b);
-                        gmu[i] = a;
-                        gsig[i] = b;
+                        const float m = mu[i], sd = sigma[i];
+                        double gm, gs;
+                        finish_grad(sum_g, sum_ge, m, sd, g, k, gm, gs);
+                        epi.one(i, m, sd, gm, gs);
                     }
                 }
             }
@@ -493,18 +539,6 @@ struct FwdArgs {
     hipStream_t stream;
 };
 
-struct BwdArgs {
-    long n, ld;
-    int s_loc;
-    double g, k;
-    int accumulate;
-    const float *mu, *sigma, *eps, *gw;
-    float *gmu, *gsig;
-    Rng rng;
-    dim3 grid;
-    hipStream_t stream;
-};
-
 // Template dispatch over (chunks, unroll, aligned, non-temporal, [KL]); GEN is fixed by the caller.
 template <bool GEN, int CH, int U, bool AL, bool NT>
 void fwd_go(const FwdArgs &a)
@@ -542,14 +576,26 @@ void fwd_dispatch(int ch, int u, bool al, bool nt, const FwdArgs &a)
     else fwd_unroll<GEN, 1>(u, al, nt, a);
 }
 
-template <bool GEN, int CH, int U, bool AL, bool NT>
-void bwd_go(const BwdArgs &a)
+template <class EPI>
+struct BwdArgs {
+    long n, ld;
+    int s_loc;
+    double g, k;
+    const float *mu, *sigma, *eps, *gw;
+    EPI epi;
+    Rng rng;
+    dim3 grid;
+    hipStream_t stream;
+};
+
+template <bool GEN, int CH, int U, bool AL, bool NT, class EPI>
+void bwd_go(const BwdArgs<EPI> &a)
 {
-    hot_backward_kernel<CH, U, AL, NT, GEN><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-        a.n, a.ld, a.s_loc, a.g, a.k, a.accumulate, a.mu, a.sigma, a.eps, a.gw, a.gmu, a.gsig, a.rng);
+    hot_backward_kernel<CH, U, AL, NT, GEN, EPI><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+        a.n, a.ld, a.s_loc, a.g, a.k, a.mu, a.sigma, a.eps, a.gw, a.epi, a.rng);
 }
-template <bool GEN, int CH, int U>
-void bwd_flags(bool al, bool nt, const BwdArgs &a)
+template <bool GEN, int CH, int U, class EPI>
+void bwd_flags(bool al, bool nt, const BwdArgs<EPI> &a)
 {
     if (al) {
         if (nt) bwd_go<GEN, CH, U, true, true>(a);
@@ -559,15 +605,15 @@ void bwd_flags(bool al, bool nt, const BwdArgs &a)
         else bwd_go<GEN, CH, U, false, false>(a);
     }
 }
-template <bool GEN, int CH>
-void bwd_unroll(int u, bool al, bool nt, const BwdArgs &a)
+template <bool GEN, int CH, class EPI>
+void bwd_unroll(int u, bool al, bool nt, const BwdArgs<EPI> &a)
 {
     if (u >= 4) bwd_flags<GEN, CH, 4>(al, nt, a);
     else if (u >= 2) bwd_flags<GEN, CH, 2>(al, nt, a);
     else bwd_flags<GEN, CH, 1>(al, nt, a);
 }
-template <bool GEN>
-void bwd_dispatch(int ch, int u, bool al, bool nt, const BwdArgs &a)
+template <bool GEN, class EPI>
+void bwd_dispatch(int ch, int u, bool al, bool nt, const BwdArgs<EPI> &a)
 {
     if (ch >= 4) bwd_unroll<GEN, 4>(u, al, nt, a);
     else if (ch >= 2) bwd_unroll<GEN, 2>(u, al, nt, a);
@@ -682,8 +728,44 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
 }
 
-// rows samples starting at local sample first_row (eps and grad_w point at the first of them);
-// rows = 0 means all of the plan's samples.
+// Launches the backward kernel with the given epilogue.  rows samples starting at local sample
+// first_row (eps and grad_w point at the first of them); rows = 0 means all of the plan's samples.
+// aligned_out: whether every array the epilogue touches is 16-byte aligned.
+template <class EPI>
+int backward_launch(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
+                    const float *eps, const float *grad_w, const EPI &epi, bool aligned_out, void *stream,
+                    int first_row, int rows, bool add_kl)
+{
+    const bool gen = rng != nullptr;
+    const hot_desc &d = plan->d;
+    const hot_launch &c = plan->cfg[kernel];
+    const bool al = aligned16(mu) && aligned16(sigma) && aligned16(grad_w) && aligned_out &&
+                    (gen || aligned16(eps)) && (d.ld % 4 == 0);
+
+    BwdArgs<EPI> a;
+    a.n = d.n_weights;
+    a.ld = d.ld;
+    a.s_loc = rows > 0 ? rows : d.s_local;
+    a.g = plan->g;
+    a.k = add_kl ? plan->k : 0.0;
+    a.mu = mu;
+    a.sigma = sigma;
+    a.eps = eps;
+    a.gw = grad_w;
+    a.epi = epi;
+    a.rng = gen ? *rng : Rng{0, 0, 0, 0};
+    a.rng.first_sample += (unsigned)first_row;
+    a.grid = dim3(grid_for(d.n_weights, c));
+    a.stream = static_cast<hipStream_t>(stream);
+
+    DeviceGuard guard(d.device);
+    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
+    if (gen) bwd_dispatch<true>(c.chunks, pick_unroll(c.unroll, a.s_loc), al, c.nontemporal != 0, a);
+    else bwd_dispatch<false>(c.chunks, pick_unroll(c.unroll, a.s_loc), al, c.nontemporal != 0, a);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
+}
+
 int backward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
                   const float *eps, const float *grad_w, float *grad_mu, float *grad_sigma, void *stream,
                   int first_row = 0, int rows = 0, bool accumulate = false, bool add_kl = true)
@@ -693,35 +775,9 @@ int backward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, c
     if (!aligned4(mu) || !aligned4(sigma) || !aligned4(grad_w) || !aligned4(grad_mu) || !aligned4(grad_sigma) ||
         (!gen && !aligned4(eps)))
         return HOT_EINVAL;
-    const hot_desc &d = plan->d;
-    const hot_launch &c = plan->cfg[kernel];
-    const bool al = aligned16(mu) && aligned16(sigma) && aligned16(grad_w) && aligned16(grad_mu) &&
-                    aligned16(grad_sigma) && (gen || aligned16(eps)) && (d.ld % 4 == 0);
-
-    BwdArgs a;
-    a.n = d.n_weights;
-    a.ld = d.ld;
-    a.s_loc = rows > 0 ? rows : d.s_local;
-    a.g = plan->g;
-    a.k = add_kl ? plan->k : 0.0;
-    a.accumulate = accumulate ? 1 : 0;
-    a.mu = mu;
-    a.sigma = sigma;
-    a.eps = eps;
-    a.gw = grad_w;
-    a.gmu = grad_mu;
-    a.gsig = grad_sigma;
-    a.rng = gen ? *rng : Rng{0, 0, 0, 0};
-    a.rng.first_sample += (unsigned)first_row;
-    a.grid = dim3(grid_for(d.n_weights, c));
-    a.stream = static_cast<hipStream_t>(stream);
-
-    DeviceGuard guard(d.device);
-    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
-    if (gen) bwd_dispatch<true>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
-    else bwd_dispatch<false>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
+    const StoreGrad epi{grad_mu, grad_sigma, accumulate ? 1 : 0};
+    return backward_launch(plan, kernel, rng, mu, sigma, eps, grad_w, epi, aligned16(grad_mu) && aligned16(grad_sigma),
+                           stream, first_row, rows, add_kl);
 }
 
 int sample_impl(hot_plan *plan, const hot_rng *rng, void *out, bool bits, void *stream)
@@ -910,6 +966,33 @@ int hot_backward_rows(hot_plan *plan, const hot_rng *rng, const float *mu, const
     }
     return backward_impl(plan, HOT_KERNEL_BACKWARD, nullptr, mu, sigma, eps, grad_w, grad_mu, grad_sigma, stream,
                          first_row, rows, accumulate != 0, add_kl != 0);
+}
+
+int hot_backward_adam(hot_plan *plan, const hot_rng *rng, const hot_adam *params, float *mu, float *sigma,
+                      const float *eps, const float *grad_w, float *m_mu, float *v_mu, float *m_sigma, float *v_sigma,
+                      void *stream)
+{
+    if (!plan || plan->d.s_local != plan->d.s_total) return HOT_EINVAL;   // one GPU holds all samples
+    if ((rng != nullptr) == (eps != nullptr)) return HOT_EINVAL;          // exactly one source of eps
+    if (!mu || !sigma || !grad_w || !m_mu || !v_mu || !m_sigma || !v_sigma) return HOT_EINVAL;
+    const void *ptrs[8] = {mu, sigma, grad_w, m_mu, v_mu, m_sigma, v_sigma, eps};
+    bool al = true;
+    for (int i = 0; i < (eps ? 8 : 7); ++i) {
+        if (!aligned4(ptrs[i])) return HOT_EINVAL;
+        if (i >= 3 && i < 7) al = al && aligned16(ptrs[i]);
+    }
+    AdamUpdate epi;
+    if (!make_adam_const(params, epi.c)) return HOT_EINVAL;
+    epi.mu = mu;
+    epi.sigma = sigma;
+    epi.m_mu = m_mu;
+    epi.v_mu = v_mu;
+    epi.m_sig = m_sigma;
+    epi.v_sig = v_sigma;
+    Rng r;
+    if (rng && !make_rng(rng, plan->d.s_local, r)) return HOT_EINVAL;
+    return backward_launch(plan, rng ? HOT_KERNEL_BACKWARD_RNG : HOT_KERNEL_BACKWARD, rng ? &r : nullptr, mu, sigma, eps,
+                           grad_w, epi, al, stream, 0, 0, true);
 }
 
 int hot_sample_eps(hot_plan *plan, const hot_rng *rng, float *eps, void *stream)

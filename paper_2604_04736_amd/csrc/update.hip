@@ -14,25 +14,11 @@
 #include "hot.h"
 #include "vec.h"
 #include "draw.h"
+#include "adam.h"
 
 namespace {
 
 constexpr int kBlock = 256;
-
-struct AdamConst {
-    float lr, beta1, beta2, one_minus_beta1, one_minus_beta2, eps, grad_scale, sigma_min;
-    float corr1, corr2;   // 1 / (1 - beta1^t), 1 / (1 - beta2^t)
-};
-
-// One parameter: Adam's update in fp32 (moments, bias correction, step).
-__device__ __forceinline__ void adam_one(float &theta, float &m, float &v, float grad, const AdamConst &c)
-{
-    const float g = c.grad_scale * grad;
-    m = __builtin_fmaf(c.beta1, m, c.one_minus_beta1 * g);
-    v = __builtin_fmaf(c.beta2, v, c.one_minus_beta2 * (g * g));
-    const float mh = m * c.corr1, vh = v * c.corr2;
-    theta = theta - c.lr * mh / (sqrtf(vh) + c.eps);
-}
 
 // Four 16-byte chunks per thread and non-temporal accesses measured best on MI355X (5.6 TB/s
 // against 5.3 TB/s with one chunk and cached accesses).
@@ -71,8 +57,7 @@ hot_adam_kernel(long n, AdamConst c, float *__restrict__ mu, float *__restrict__
                     adam_one(t, a, b, g0[q][j], c);
                     p0[q][j] = t; m0[q][j] = a; v0[q][j] = b;
                     t = p1[q][j]; a = m1[q][j]; b = v1[q][j];
-                    adam_one(t, a, b, g1[q][j], c);
-                    if (c.sigma_min > 0.0f && t < c.sigma_min) t = c.sigma_min;
+                    adam_one_sigma(t, a, b, g1[q][j], c);
                     p1[q][j] = t; m1[q][j] = a; v1[q][j] = b;
                 }
                 store4<ALIGNED, NT>(mu + col, p0[q]);
@@ -87,8 +72,7 @@ hot_adam_kernel(long n, AdamConst c, float *__restrict__ mu, float *__restrict__
                     adam_one(t, a, b, gmu[i], c);
                     mu[i] = t; m_mu[i] = a; v_mu[i] = b;
                     t = sigma[i]; a = m_sig[i]; b = v_sig[i];
-                    adam_one(t, a, b, gsig[i], c);
-                    if (c.sigma_min > 0.0f && t < c.sigma_min) t = c.sigma_min;
+                    adam_one_sigma(t, a, b, gsig[i], c);
                     sigma[i] = t; m_sig[i] = a; v_sig[i] = b;
                 }
             }
@@ -200,27 +184,15 @@ extern "C" {
 int hot_adam_step(const hot_adam *p, int64_t n, float *mu, float *sigma, const float *grad_mu,
                   const float *grad_sigma, float *m_mu, float *v_mu, float *m_sigma, float *v_sigma, void *stream)
 {
-    if (!p || n < 1 || !mu || !sigma || !grad_mu || !grad_sigma || !m_mu || !v_mu || !m_sigma || !v_sigma) return HOT_EINVAL;
-    if (!(p->lr >= 0.0) || !(p->beta1 >= 0.0 && p->beta1 < 1.0) || !(p->beta2 >= 0.0 && p->beta2 < 1.0) ||
-        !(p->eps >= 0.0) || !std::isfinite(p->grad_scale) || !std::isfinite(p->lr) || p->step < 1)
-        return HOT_EINVAL;
+    if (n < 1 || !mu || !sigma || !grad_mu || !grad_sigma || !m_mu || !v_mu || !m_sigma || !v_sigma) return HOT_EINVAL;
+    AdamConst c;
+    if (!make_adam_const(p, c)) return HOT_EINVAL;
     const void *ptrs[8] = {mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma};
     bool al = true;
     for (const void *q : ptrs) {
         if (!aligned4(q)) return HOT_EINVAL;
         al = al && aligned16(q);
     }
-    AdamConst c;
-    c.lr = (float)p->lr;
-    c.beta1 = (float)p->beta1;
-    c.beta2 = (float)p->beta2;
-    c.one_minus_beta1 = (float)(1.0 - p->beta1);
-    c.one_minus_beta2 = (float)(1.0 - p->beta2);
-    c.eps = (float)p->eps;
-    c.grad_scale = (float)p->grad_scale;
-    c.sigma_min = (float)p->sigma_min;
-    c.corr1 = (float)(1.0 / (1.0 - std::pow(p->beta1, (double)p->step)));
-    c.corr2 = (float)(1.0 / (1.0 - std::pow(p->beta2, (double)p->step)));
     const dim3 grid(blocks_for(((n + 3) / 4 + kAdamChunks - 1) / kAdamChunks)), block(kBlock);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (al) hot_adam_kernel<true><<<grid, block, 0, s>>>(n, c, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma);

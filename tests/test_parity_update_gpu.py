@@ -119,3 +119,90 @@ def test_update_errors(hot):
         with pytest.raises(hot.HotError):
             hot.hot_forward_dropout_rng(plan, rng, keep, t, t.clone().view(1, 16))
     hot.hot_destroy(plan)
+
+
+# (n, ld, samples, pointer offset in floats, eps drawn in the kernel)
+FUSED = [(1, 1, 1, 0, False), (5, 8, 2, 0, True), (100_003, 100_003, 3, 0, False), (100_003, 100_004, 4, 1, True),
+         (3 * 4096 + 5, 3 * 4096 + 8, 16, 0, True), (1_048_579, 1_048_579, 2, 3, False), (262_144, 262_144, 5, 0, False)]
+
+
+@pytest.mark.parametrize("n,ld,s,offset,gen", FUSED)
+def test_fused_backward_adam(oracle, hot, n, ld, s, offset, gen):
+    """hot_backward_adam against (a) hot_backward followed by hot_adam_step, bit for bit, and (b) the
+    oracle's gradient (fp64, never rounded) fed to the oracle's Adam step.  For (b) the rounding of
+    the gradient to fp32 on the GPU moves an Adam step by about twice the gradient's relative error
+    r = 1e-6 A / |grad| (A the sum of the gradient's addend magnitudes): elements with r > 0.05,
+    where cancellation leaves the sign of the gradient itself in doubt, are checked to be rare and
+    excluded from the theta bound."""
+    print("case fused backward+adam", n, ld, s, offset, gen, flush=True)
+    r = np.random.default_rng(n * 31 + s)
+    D, t, lr, b1, b2, eps_a, gsc, smin = 1000.0, 3, 2e-3, 0.9, 0.999, 1e-8, 0.5, 0.02
+    mu = r.normal(size=n).astype(np.float32)
+    sigma = r.uniform(0.01, 1.0, size=n).astype(np.float32)
+    G = np.full((s, ld), np.nan, np.float32)
+    G[:, :n] = r.normal(size=(s, n)) * 10 ** r.uniform(-3, 2, size=(1, n))
+    rng = hot.hot_rng(seed=99, step=t, first_sample=0)
+    eps64 = oracle.eps_normal(n, s, rng.seed, rng.step, rng.first_sample) if gen else r.normal(size=(s, n))
+    eps = np.full((s, ld), np.nan, np.float32)
+    eps[:, :n] = eps64
+    state = {"m_mu": r.normal(size=n) * 0.1, "v_mu": r.uniform(0, 1, size=n) * 0.01,
+             "m_sigma": r.normal(size=n) * 0.1, "v_sigma": r.uniform(0, 1, size=n) * 0.01}
+    state = {k: v.astype(np.float32) for k, v in state.items()}
+    plan = hot.hot_create(n, ld, s, s, D, 0)
+    G_d, eps_d = _dev(G, offset), (None if gen else _dev(eps, offset))
+    params = hot.hot_adam(lr, b1, b2, eps_a, gsc, smin, t)
+
+    two = {"mu": _dev(mu, offset), "sigma": _dev(sigma, offset), **{k: _dev(v, offset) for k, v in state.items()}}
+    gmu, gsig = _dev(np.zeros(n), offset), _dev(np.zeros(n), offset)
+    if gen:
+        hot.hot_backward_rng(plan, rng, two["mu"], two["sigma"], G_d, gmu, gsig)
+    else:
+        hot.hot_backward(plan, two["mu"], two["sigma"], eps_d, G_d, gmu, gsig)
+    hot.hot_adam_step(params, two["mu"], two["sigma"], gmu, gsig, two["m_mu"], two["v_mu"], two["m_sigma"], two["v_sigma"])
+
+    one = {"mu": _dev(mu, offset), "sigma": _dev(sigma, offset), **{k: _dev(v, offset) for k, v in state.items()}}
+    hot.hot_backward_adam(plan, rng if gen else None, params, one["mu"], one["sigma"], eps_d, G_d,
+                          one["m_mu"], one["v_mu"], one["m_sigma"], one["v_sigma"])
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+    for k in one:
+        assert torch.equal(one[k], two[k]), f"{k}: fused and two-call results differ"
+
+    eps_in = eps if not gen else eps     # fp32 values either way (the generator's output is fp32)
+    gm64, gs64 = oracle.grad(mu, sigma, eps_in, G, s, D)
+    want = oracle.adam_step(mu, sigma, gm64, gs64, state["m_mu"], state["v_mu"], state["m_sigma"], state["v_sigma"],
+                            step=t, lr=lr, beta1=b1, beta2=b2, eps=eps_a, grad_scale=gsc, sigma_min=smin)
+    got = {k: v.cpu().numpy().astype(np.float64) for k, v in one.items()}
+    g_abs = np.abs(G[:, :n].astype(np.float64))
+    k_kl = 1.0 / D
+    A = {"mu": g_abs.sum(0) / s + k_kl * np.abs(mu), "sigma": (g_abs * np.abs(eps[:, :n])).sum(0) / s + k_kl * (sigma + 1.0 / sigma)}
+    for name, g64, w_th, w_m, w_v, m_key, v_key, th0 in (("mu", gm64, want[0], want[2], want[3], "m_mu", "v_mu", mu),
+                                                        ("sigma", gs64, want[1], want[4], want[5], "m_sigma", "v_sigma", sigma)):
+        a = gsc * A[name]
+        assert np.all(np.abs(got[m_key] - w_m) <= 1e-6 * (b1 * np.abs(state[m_key]) + (1 - b1) * a) + 1e-45), name
+        assert np.all(np.abs(got[v_key] - w_v) <= 3e-6 * (b2 * state[v_key] + (1 - b2) * a * a) + 1e-45), name
+        rel = 1e-6 * A[name] / np.maximum(np.abs(g64), 1e-300)
+        sure = rel <= 0.05
+        assert sure.mean() >= 0.999 or n < 1000
+        step = np.abs(w_th - th0)
+        bound = 1e-6 * (np.abs(th0) + step + lr) + 2.0 * rel * (step + lr)
+        assert np.all((np.abs(got[name] - w_th) <= bound)[sure]), name
+    assert got["sigma"].min() >= smin * (1 - 1e-7)
+
+
+def test_fused_backward_adam_errors(hot):
+    n = 64
+    t = [torch.zeros(n, device=DEV) for _ in range(6)]
+    G = torch.zeros(2, n, device=DEV)
+    params = hot.hot_adam(1e-3, 0.9, 0.999, 1e-8, 1.0, 0.0, 1)
+    rng = hot.hot_rng(seed=1, step=0, first_sample=0)
+    shared = hot.hot_create(n, n, 2, 4, 1.0, 0)            # only half of the samples are local
+    with pytest.raises(hot.HotError):
+        hot.hot_backward_adam(shared, rng, params, t[0], t[1], None, G, *t[2:])
+    hot.hot_destroy(shared)
+    plan = hot.hot_create(n, n, 2, 2, 1.0, 0)
+    with pytest.raises(ValueError):
+        hot.hot_backward_adam(plan, rng, params, t[0], t[1], G.clone(), G, *t[2:])       # both sources of eps
+    with pytest.raises(hot.HotError):
+        hot.hot_backward_adam(plan, rng, hot.hot_adam(1e-3, 0.9, 0.999, 1e-8, 1.0, 0.0, 0), t[0], t[1], None, G, *t[2:])
+    hot.hot_destroy(plan)

@@ -84,6 +84,46 @@ def time_steps(hot, torch, wl, x, steps: int, warmup: int, in_kernel_eps: bool =
             "out": {"w": w, "kl": kl, "gmu": gmu, "gsig": gsig}}
 
 
+def time_graph_steps(hot, torch, wl, x, steps: int, in_kernel_eps: bool = False) -> float:
+    """ms per step when the step (forward, KL finish, backward) is captured once in a HIP graph and
+    replayed: what a launch-latency-bound small workload costs without the host in the loop."""
+    dev = x["mu"].device
+    w = torch.empty_like(x["G"])
+    kl = torch.zeros(1, dtype=torch.float64, device=dev)
+    gmu, gsig = torch.empty_like(x["mu"]), torch.empty_like(x["mu"])
+    plan = hot.hot_create(wl.n_weights, wl.ld, wl.s_local, wl.s_total, wl.dataset_size, dev.index or 0)
+    rng = hot.hot_rng(seed=RNG_SEED, step=RNG_STEP, first_sample=0)
+
+    def step():
+        if in_kernel_eps:
+            hot.hot_forward_rng(plan, rng, x["mu"], x["sigma"], w, kl)
+            hot.hot_backward_rng(plan, rng, x["mu"], x["sigma"], x["G"], gmu, gsig)
+        else:
+            hot.hot_forward(plan, x["mu"], x["sigma"], x["eps"], w, kl)
+            hot.hot_backward(plan, x["mu"], x["sigma"], x["eps"], x["G"], gmu, gsig)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    del graph
+    hot.hot_destroy(plan)
+    return ms
+
+
 def verify_sampled(oracle, np, wl, x, out, blocks: int = 6, width: int = 20_000, in_kernel_eps: bool = False) -> bool:
     """Checks the timed buffers on a few column blocks against the oracle (same tolerances as the tests)."""
     if in_kernel_eps:
@@ -516,6 +556,10 @@ def main() -> int:
                             "fwd_ms": ro["fwd_ms"], "bwd_ms": ro["bwd_ms"],
                             "step_frac_of_hbm_roofline": (fb + bb) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                             "verified_against_oracle": check(o, xo, ro["out"], gen)}
+            if o.items < 50_000_000:       # launch-latency-bound sizes: the same step replayed from a HIP graph
+                gms = time_graph_steps(hot, torch, o, xo, 200, gen)
+                others[name]["hip_graph_ms_per_step"] = gms
+                others[name]["hip_graph_items_per_s"] = o.items / (gms * 1e-3)
             del xo, ro
             torch.cuda.empty_cache()
         result["other_workloads"] = others

@@ -214,6 +214,18 @@ def cpu_baseline(oracle, np, wl, x, max_weights: int):
             "kl": kl64}
 
 
+def alu_roofline_forward_rng(s_local: int, achieved_items_per_s: float):
+    """Vector-ALU ceiling of the drawing forward kernel, from the instruction mix of its compiled loop
+    (per wave and 16-byte chunk): one sample's draw, multiply-add and store is 17 64-bit integer
+    multiply-adds and 8 transcendentals at 16 issue cycles plus about 62 full-rate instructions at 4,
+    650 cycles; the KL addends of the chunk's four weights are about 300 more.  A wave finishes
+    4 * 64 * S_loc items in that time, on 1024 SIMDs (256 compute units) at 2.4 GHz."""
+    cycles = 650.0 * s_local + 300.0
+    peak = 256.0 * s_local / cycles * 1024 * 2.4e9
+    return {"bound": "alu", "kernel": "hot_forward_kernel (drawn eps)", "achieved": achieved_items_per_s, "peak": peak,
+            "unit": "items/s", "frac": achieved_items_per_s / peak}
+
+
 def measured_traffic(kernel: str, workload: str):
     """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
     path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
@@ -535,6 +547,7 @@ def main() -> int:
             "fwd_GBps": fb / rr["fwd_ms"] / 1e6, "bwd_GBps": bb / rr["bwd_ms"] / 1e6,
             "step_frac_of_hbm_roofline": (fb + bb) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "verified_against_oracle": check(wl, xr, rr["out"], True),
+            "forward_alu_roofline": alu_roofline_forward_rng(wl.s_local, items / (rr["fwd_ms"] * 1e-3)),
             "note": "hot_forward_rng + hot_backward_rng: Philox-4x32-10 + Box-Muller in registers"}
         del xr, rr
         torch.cuda.empty_cache()

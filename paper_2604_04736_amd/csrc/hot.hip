@@ -12,7 +12,9 @@
 //   * the KL term leaves one fp64 partial per workgroup; a one-workgroup kernel launched
 //     right behind adds them in a fixed order (deterministic, no floating-point atomics,
 //     and no fence inside the streaming kernel: a device-scope release there has to
-//     write back the die's whole L2, which cost a factor of four with large grids);
+//     write back the die's whole L2, which cost a factor of four with large grids; grids of
+//     at most 64 workgroups, where a second launch costs more than that, finish the sum
+//     themselves through an arrival counter);
 //   * there is no reuse between threads, hence no LDS staging: LDS only carries the
 //     four per-wave partial sums of the KL reduction.
 // With GEN the kernels draw eps in registers from a counter-based generator instead of
@@ -33,6 +35,7 @@ constexpr int kBlock = 256;             // threads per workgroup = 4 wavefronts 
 constexpr int kWaves = kBlock / 64;
 constexpr int kMaxGrid = 65536;         // upper bound on workgroups (size of the partials buffer)
 constexpr int kFinishBlock = 1024;      // threads of the one workgroup that adds the KL partials
+constexpr int kTicketGrid = 64;         // up to this many workgroups the forward kernel finishes the KL sum itself
 
 typedef u4 u4u __attribute__((aligned(4)));
 
@@ -200,7 +203,7 @@ __global__ void __launch_bounds__(kBlock)
 hot_forward_kernel(long n, long ld, int s_loc,
                    const float *__restrict__ mu, const float *__restrict__ sigma,
                    const float *__restrict__ eps, float *__restrict__ w,
-                   double *__restrict__ partials, Rng rng)
+                   double *partials, unsigned *ticket, double *__restrict__ kl_out, Rng rng)
 {
     constexpr long kTile = (long)kBlock * 4 * CHUNKS;   // columns per tile
     constexpr long kStep = (long)kBlock * 4;            // columns between a thread's chunks
@@ -261,7 +264,32 @@ hot_forward_kernel(long n, long ld, int s_loc,
     if constexpr (KL) {
         __shared__ double lds[kWaves];
         const double mine = block_sum(kl, lds);
-        if (threadIdx.x == 0) partials[blockIdx.x] = mine;
+        if (ticket == nullptr) {
+            if (threadIdx.x == 0) partials[blockIdx.x] = mine;
+        } else {
+            // Small grids (at most kTicketGrid workgroups, where a launch costs more than the kernel):
+            // the workgroup that arrives last adds the partials, so no second kernel is needed.  Each
+            // workgroup pays one device-scope release (a write-back of its die's L2), which is why
+            // large grids use the finish kernel instead.  Nothing waits on anything: whoever draws the
+            // last ticket does the sum, in lane order, hence deterministically.
+            __shared__ int last;
+            if (threadIdx.x == 0) {
+                __hip_atomic_store(&partials[blockIdx.x], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned drawn = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+                last = drawn == gridDim.x - 1 ? 1 : 0;
+            }
+            __syncthreads();
+            if (last && threadIdx.x < 64) {
+                double v = 0.0;
+                if (threadIdx.x < gridDim.x)
+                    v = __hip_atomic_load(&partials[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v = wave_sum(v);
+                if (threadIdx.x == 0) {
+                    *kl_out = 0.5 * v;
+                    __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+                }
+            }
+        }
     }
 }
 
@@ -533,6 +561,8 @@ struct FwdArgs {
     const float *mu, *sigma, *eps;
     float *w;
     double *partials;
+    unsigned *ticket;
+    double *kl_out;
     bool want_kl;
     Rng rng;
     dim3 grid;
@@ -545,10 +575,10 @@ void fwd_go(const FwdArgs &a)
 {
     if (a.want_kl)
         hot_forward_kernel<CH, U, AL, NT, true, GEN><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.rng);
+            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, a.rng);
     else
         hot_forward_kernel<CH, U, AL, NT, false, GEN><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.rng);
+            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, a.rng);
 }
 template <bool GEN, int CH, int U>
 void fwd_flags(bool al, bool nt, const FwdArgs &a)
@@ -654,7 +684,7 @@ int note_hip(hipError_t e)
 struct hot_plan {
     hot_desc d;
     double g, k;
-    double *partials;   // kMaxGrid fp64 KL partial sums, one per forward workgroup
+    double *partials;   // kMaxGrid fp64 KL partial sums, one per forward workgroup, then the arrival counter
     hot_launch cfg[4];  // indexed by HOT_KERNEL_*
     int last_hip;
 };
@@ -712,16 +742,19 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     a.w = w;
     a.partials = plan->partials;
     a.want_kl = kl_out != nullptr;
+    a.kl_out = kl_out;
     a.rng = gen ? *rng : Rng{0, 0, 0, 0};
     a.grid = dim3(grid_for(d.n_weights, c));
     a.stream = static_cast<hipStream_t>(stream);
+    const bool self_finish = a.want_kl && a.grid.x <= (unsigned)kTicketGrid;
+    a.ticket = self_finish ? reinterpret_cast<unsigned *>(plan->partials + kMaxGrid) : nullptr;
 
     DeviceGuard guard(d.device);
     if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
     if (gen) fwd_dispatch<true>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
     else fwd_dispatch<false>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && kl_out) {
+    if (e == hipSuccess && kl_out && !self_finish) {
         hot_kl_finish_kernel<<<dim3(1), dim3(kFinishBlock), 0, a.stream>>>(plan->partials, (int)a.grid.x, kl_out);
         e = hipGetLastError();
     }
@@ -859,9 +892,13 @@ int hot_create(hot_plan **out, const hot_desc *desc)
 
     DeviceGuard guard(d.device);
     hipError_t e = guard.err;
-    if (e == hipSuccess) e = hipMalloc((void **)&p->partials, sizeof(double) * kMaxGrid);
+    // one slot past the partials holds the arrival counter of the self-finishing small-grid forward kernel
+    if (e == hipSuccess) e = hipMalloc((void **)&p->partials, sizeof(double) * (kMaxGrid + 1));
+    if (e == hipSuccess) e = hipMemset(p->partials + kMaxGrid, 0, sizeof(double));
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);   // the counter is zero before any stream uses the plan
     if (e != hipSuccess) {
         const bool oom = (e == hipErrorOutOfMemory);
+        if (p->partials) (void)hipFree(p->partials);
         (void)hipGetLastError();
         delete p;
         return oom ? HOT_ENOMEM : hot_detail::note_hip(e);

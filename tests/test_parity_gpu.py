@@ -159,6 +159,34 @@ def test_bitwise_determinism_over_repeated_launches(hot):
             assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("n,launch", [(64 * 4096, None), (64 * 4096 + 1, None), (63 * 4096 + 5, None), (1_000_003, {"grid_blocks": 8}),
+                                      (1_000_003, {"grid_blocks": 64, "chunks": 1}), (300_000, {"grid_blocks": 65, "chunks": 1})])
+def test_kl_on_either_side_of_the_small_grid_boundary(oracle, hot, n, launch):
+    """Up to 64 workgroups the forward kernel adds its KL partials itself (the last workgroup to
+    arrive does it); above, a second kernel does.  Both sides of the boundary, grids forced small
+    on larger inputs, and repeated calls on one plan (the arrival counter must be back at zero)."""
+    print("case small-grid KL", n, launch, flush=True)
+    x = _random_case(n, n, 2, seed=n % 1000)
+    h = P.host(x)
+    plan = hot.hot_create(n, n, 2, 2, 100.0, 0)
+    if launch:
+        hot.hot_set_launch(plan, hot.HOT_KERNEL_FORWARD, **launch)
+        hot.hot_set_launch(plan, hot.HOT_KERNEL_FORWARD_RNG, **launch)
+    w = torch.empty_like(x["eps"])
+    kls = []
+    for rep in range(5):
+        kl = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+        if rep == 3:
+            hot.hot_forward_rng(plan, hot.hot_rng(seed=5, step=rep, first_sample=0), x["mu"], x["sigma"], w, kl)
+        else:
+            hot.hot_forward(plan, x["mu"], x["sigma"], x["eps"], w, kl)
+        torch.cuda.synchronize()
+        kls.append(kl.item())
+    hot.hot_destroy(plan)
+    P.check_kl(oracle, h, kls[0])
+    assert all(k == kls[0] for k in kls), kls
+
+
 def test_ieee_propagation_for_sigma_outside_the_domain(oracle, hot):
     n, s = 2051, 2
     x = _random_case(n, n, s, seed=11)

@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 201 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 202 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
@@ -174,14 +174,16 @@ int hot_last_hip_error(const hot_plan *plan);
 
 /*
  * One sampled Bayesian linear layer, the weight draw fused into the contraction (Algorithm
- * 1 / 2: reparameterisation line + ForwardPass for a Linear layer; the same minibatch x for
- * every sample):
- *   y[s, r, o] = sum_k x[r, k] * fma(sigma_W[o, k], eps_s[o, k], mu_W[o, k])
+ * 1 / 2: reparameterisation line + ForwardPass for a Linear layer):
+ *   y[s, r, o] = sum_k x_s[r, k] * fma(sigma_W[o, k], eps_s[o, k], mu_W[o, k])
  *                + fma(sigma_b[o], eps_s^b[o], mu_b[o])
+ * x_s is the minibatch itself, shared by all samples (x_sample_stride = 0: the first layer), or
+ * the previous layer's output under the same weight sample (x_sample_stride = floats from x_s
+ * to x_{s+1}: every later layer).
  * eps of weight (o, k) is the draw (see hot_rng) of flat parameter index weight_offset + o*K + k,
  * eps of bias o that of bias_offset + o: the layer sees exactly the w that hot_forward_rng
  * would write for a parameter vector holding this layer at those offsets, without w ever
- * existing in memory.  x: [rows, ldx]; mu_W, sigma_W: [out_features, in_features] packed
+ * existing in memory.  x: [rows, ldx] or [s_local, rows, ldx]; mu_W, sigma_W: [out_features, in_features] packed
  * row-major; mu_b, sigma_b: [out_features] or both NULL; y: [s_local, rows, out_features]
  * packed, out.  All DEVICE pointers; x, mu_W, sigma_W 16-byte aligned; in_features, ldx,
  * weight_offset, bias_offset multiples of 4.  The contraction runs on the matrix cores in
@@ -199,6 +201,7 @@ typedef struct hot_linear_desc {
     int64_t bias_offset;   /* flat parameter index of b[0], multiple of 4 (ignored without bias) */
     int32_t s_local;       /* S_loc >= 1 */
     int32_t reserved;      /* must be 0 */
+    int64_t x_sample_stride; /* 0: one x for all samples; else >= rows * ldx, multiple of 4 */
 } hot_linear_desc;
 
 int hot_linear_forward_rng(const hot_linear_desc *desc, const hot_rng *rng, const float *x, const float *mu_w,

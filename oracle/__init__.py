@@ -77,7 +77,7 @@ def _load():
                                        ctypes.c_int32, dp, dp]
     lib.stats_oracle_merge.restype = None
     lib.linear_oracle_forward.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
-                                          ctypes.c_int64, fp, fp, fp, dp, fp, fp, dp, dp]
+                                          ctypes.c_int64, ctypes.c_int64, fp, fp, fp, dp, fp, fp, dp, dp]
     lib.linear_oracle_forward.restype = None
     lib.update_oracle_adam.argtypes = [ctypes.c_int64, ctypes.POINTER(AdamParams), dp, dp, dp, dp, dp, dp, dp, dp]
     lib.update_oracle_adam.restype = None
@@ -230,7 +230,7 @@ def stats_merge(counts, means, m2s, ddof: int = 0):
 
 def linear_forward(x, mu_w, sigma_w, eps_w, mu_b=None, sigma_b=None, eps_b=None, in_features=None):
     """y[S, R, O] = x W_s^T + b_s with W_s = mu_w + sigma_w*eps_w[s], b_s likewise; fp64.
-    x is [R, ldx >= K]; mu_w, sigma_w [O, K]; eps_w [S, O, K] fp64; bias arrays [O] / [S, O] or None."""
+    x is [R, ldx >= K] (shared by the samples) or [S, R, ldx >= K] (one input per sample); mu_w, sigma_w [O, K]; eps_w [S, O, K] fp64; bias arrays [O] / [S, O] or None."""
     x = _f32(x, "x")
     mu_w = _f32(mu_w, "mu_w")
     sigma_w = _f32(sigma_w, "sigma_w")
@@ -239,9 +239,12 @@ def linear_forward(x, mu_w, sigma_w, eps_w, mu_b=None, sigma_b=None, eps_b=None,
     if in_features is not None and in_features != k:
         raise ValueError("in_features does not match mu_w")
     s = eps_w.shape[0]
-    if sigma_w.shape != (o, k) or eps_w.shape != (s, o, k) or x.ndim != 2 or x.shape[1] < k:
+    if sigma_w.shape != (o, k) or eps_w.shape != (s, o, k) or x.ndim not in (2, 3) or x.shape[-1] < k:
         raise ValueError("shape mismatch")
-    r = x.shape[0]
+    if x.ndim == 3 and x.shape[0] != s:
+        raise ValueError("per-sample x needs one [R, ldx] block per sample")
+    r, ldx = x.shape[-2], x.shape[-1]
+    x_stride = r * ldx if x.ndim == 3 else 0
     y = np.empty((s, r, o), dtype=np.float64)
     if mu_b is None:
         mb = sb = None
@@ -253,7 +256,7 @@ def linear_forward(x, mu_w, sigma_w, eps_w, mu_b=None, sigma_b=None, eps_b=None,
         if mu_b.shape != (o,) or sigma_b.shape != (o,) or eps_b.shape != (s, o):
             raise ValueError("bias shape mismatch")
         mb, sb, eb = _fptr(mu_b), _fptr(sigma_b), _dptr(eps_b)
-    _load().linear_oracle_forward(s, r, k, o, x.shape[1], _fptr(x), _fptr(mu_w), _fptr(sigma_w), _dptr(eps_w),
+    _load().linear_oracle_forward(s, r, k, o, ldx, x_stride, _fptr(x), _fptr(mu_w), _fptr(sigma_w), _dptr(eps_w),
                                   mb, sb, eb, _dptr(y))
     return y
 

@@ -47,7 +47,7 @@ class hot_rng(ctypes.Structure):
 class hot_linear_desc(ctypes.Structure):
     _fields_ = [("rows", ctypes.c_int64), ("in_features", ctypes.c_int64), ("out_features", ctypes.c_int64),
                 ("ldx", ctypes.c_int64), ("weight_offset", ctypes.c_int64), ("bias_offset", ctypes.c_int64),
-                ("s_local", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("s_local", ctypes.c_int32), ("reserved", ctypes.c_int32), ("x_sample_stride", ctypes.c_int64)]
 
 
 class hot_adam(ctypes.Structure):
@@ -348,15 +348,21 @@ def hot_stats_merge(means: torch.Tensor, m2s: torch.Tensor, counts, ddof: int, m
 
 def hot_linear_forward_rng(rng: hot_rng, x, mu_w, sigma_w, mu_b, sigma_b, y, weight_offset: int = 0,
                            bias_offset: int = 0) -> None:
-    """y[S, R, O] = x (mu_w + sigma_w*eps_s)^T + (mu_b + sigma_b*eps_s^b), eps drawn in the kernel."""
+    """y[S, R, O] = x_s (mu_w + sigma_w*eps_s)^T + (mu_b + sigma_b*eps_s^b), eps drawn in the kernel;
+    x is [R, K] (shared by the samples) or [S, R, K] (one input per sample)."""
     def chk(t, shape, name):
         if not (t.is_cuda and t.device == x.device and t.dtype == torch.float32 and tuple(t.shape) == shape
                 and t.is_contiguous()):
             raise TypeError(f"{name}: need a contiguous float32 tensor of shape {shape} on {x.device}")
-    if not (x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.stride(1) == 1):
-        raise TypeError("x: need a 2-D float32 device tensor with unit column stride")
-    rows, k = x.shape
-    ldx = x.stride(0) if rows > 1 else k
+    if not (x.is_cuda and x.dtype == torch.float32 and x.dim() in (2, 3) and x.stride(-1) == 1):
+        raise TypeError("x: need a [rows, K] or [S_loc, rows, K] float32 device tensor with unit column stride")
+    rows, k = x.shape[-2:]
+    ldx = x.stride(-2) if rows > 1 else k
+    x_stride = 0
+    if x.dim() == 3:
+        if y.dim() != 3 or x.shape[0] != y.shape[0]:
+            raise ValueError("per-sample x needs as many [rows, K] blocks as y has samples")
+        x_stride = x.stride(0) if x.shape[0] > 1 else rows * ldx
     if mu_w.dim() != 2 or mu_w.shape[1] != k:
         raise ValueError("mu_w must be [out_features, in_features]")
     o = mu_w.shape[0]
@@ -371,7 +377,7 @@ def hot_linear_forward_rng(rng: hot_rng, x, mu_w, sigma_w, mu_b, sigma_b, y, wei
         raise ValueError("y must be [S_loc, rows, out_features]")
     s_loc = y.shape[0]
     chk(y, (s_loc, rows, o), "y")
-    d = hot_linear_desc(rows, k, o, ldx, weight_offset, bias_offset, s_loc, 0)
+    d = hot_linear_desc(rows, k, o, ldx, weight_offset, bias_offset, s_loc, 0, x_stride)
     with torch.cuda.device(x.device):
         code = lib().hot_linear_forward_rng(ctypes.byref(d), ctypes.byref(rng), x.data_ptr(), mu_w.data_ptr(),
                                             sigma_w.data_ptr(), mu_b.data_ptr() if mu_b is not None else None,

@@ -31,8 +31,12 @@ constexpr int kInputsPerIter = 32;
 // More row tiles need more registers per lane: such workgroups are limited to fewer waves.
 constexpr int max_waves(int rb) { return rb >= 4 ? 4 : (rb >= 2 ? 8 : kMaxWaves); }
 
+// Four samples' accumulators are live together only where the register file holds them without spills.
+constexpr bool four_samples_fit(int rb, bool per_sample_x) { return rb == 2 || (rb == 1 && !per_sample_x); }
+
 struct LinearArgs {
     long rows, in_features, out_features, ldx;
+    long x_sample_stride;   // floats between the inputs of consecutive samples (XS kernels only)
     int s_loc;
     long weight_quad0;   // (weight_offset) / 4
     long bias_quad0;     // (bias_offset) / 4
@@ -42,8 +46,10 @@ struct LinearArgs {
 };
 
 // A workgroup owns 16 output columns and 16*RB rows; its waves take the 32-input blocks round-robin
-// and their partial tiles are added through LDS in wave order (deterministic).
-template <int RB, int ST>
+// and their partial tiles are added through LDS in wave order (deterministic).  XS: every sample has
+// its own input (a layer inside the network); its rows are then loaded per sample, right before
+// that sample's draw, whose arithmetic covers their latency.
+template <int RB, int ST, bool XS>
 __global__ void __launch_bounds__(64 * max_waves(RB), RB >= 4 ? 2 : 1)
 hot_linear_forward_kernel(LinearArgs a)
 {
@@ -74,16 +80,29 @@ hot_linear_forward_kernel(LinearArgs a)
                 ok[h] = o_ok && (k + 4 * h < K);
                 m4[h] = ok[h] ? load4<true, false>(mu_row + k + 4 * h) : f4{0.0f, 0.0f, 0.0f, 0.0f};
                 sd4[h] = ok[h] ? load4<true, false>(sg_row + k + 4 * h) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+                if constexpr (!XS) {
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb) {
-                    const long row = r0 + kRowsPerTile * rb + n;
-                    xa[rb][h] = (row < R && k + 4 * h < K) ? load4<true, false>(a.x + row * a.ldx + k + 4 * h)
-                                                            : f4{0.0f, 0.0f, 0.0f, 0.0f};
+                    for (int rb = 0; rb < RB; ++rb) {
+                        const long row = r0 + kRowsPerTile * rb + n;
+                        xa[rb][h] = (row < R && k + 4 * h < K) ? load4<true, false>(a.x + row * a.ldx + k + 4 * h)
+                                                                : f4{0.0f, 0.0f, 0.0f, 0.0f};
+                    }
                 }
             }
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 if (s0 + st < a.s_loc) {          // uniform over the wave
+                    if constexpr (XS) {
+                        const float *xs = a.x + (size_t)(s0 + st) * (size_t)a.x_sample_stride;
+#pragma unroll
+                        for (int h = 0; h < 2; ++h)
+#pragma unroll
+                            for (int rb = 0; rb < RB; ++rb) {
+                                const long row = r0 + kRowsPerTile * rb + n;
+                                xa[rb][h] = (row < R && k + 4 * h < K) ? load4<true, false>(xs + row * a.ldx + k + 4 * h)
+                                                                        : f4{0.0f, 0.0f, 0.0f, 0.0f};
+                            }
+                    }
                     f4 w4[2];
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
@@ -152,14 +171,23 @@ hot_linear_forward_kernel(LinearArgs a)
     }
 }
 
-template <int RB>
-void linear_go(int st, dim3 grid, int waves, hipStream_t s, const LinearArgs &a)
+template <int RB, bool XS>
+void linear_go_st(int st, dim3 grid, int waves, hipStream_t s, const LinearArgs &a)
 {
     const dim3 block(64 * waves);
     const size_t lds = waves > 1 ? (size_t)(waves - 1) * (size_t)(st * RB * 4) * 64 * sizeof(float) : 0;
-    if (st == 4) hot_linear_forward_kernel<RB, 4><<<grid, block, lds, s>>>(a);
-    else if (st == 2) hot_linear_forward_kernel<RB, 2><<<grid, block, lds, s>>>(a);
-    else hot_linear_forward_kernel<RB, 1><<<grid, block, lds, s>>>(a);
+    if constexpr (four_samples_fit(RB, XS)) {
+        if (st == 4) { hot_linear_forward_kernel<RB, 4, XS><<<grid, block, lds, s>>>(a); return; }
+    }
+    if (st >= 2) hot_linear_forward_kernel<RB, 2, XS><<<grid, block, lds, s>>>(a);
+    else hot_linear_forward_kernel<RB, 1, XS><<<grid, block, lds, s>>>(a);
+}
+
+template <int RB>
+void linear_go(int st, dim3 grid, int waves, hipStream_t s, const LinearArgs &a)
+{
+    if (a.x_sample_stride != 0) linear_go_st<RB, true>(st, grid, waves, s, a);
+    else linear_go_st<RB, false>(st, grid, waves, s, a);
 }
 
 }  // namespace
@@ -173,6 +201,10 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     if ((mu_b == nullptr) != (sigma_b == nullptr)) return HOT_EINVAL;
     if (d->rows < 1 || d->in_features < 4 || (d->in_features & 3) || d->out_features < 1 || d->s_local < 1) return HOT_EINVAL;
     if (d->ldx < d->in_features || (d->ldx & 3) || d->weight_offset < 0 || (d->weight_offset & 3)) return HOT_EINVAL;
+    if (d->reserved != 0 || d->x_sample_stride < 0 || (d->x_sample_stride & 3)) return HOT_EINVAL;
+    if (d->x_sample_stride != 0 && (d->rows > INT64_MAX / d->ldx || d->x_sample_stride < d->rows * d->ldx ||
+                                    d->x_sample_stride > INT64_MAX / 4 / d->s_local))
+        return HOT_EINVAL;
     if (mu_b && (d->bias_offset < 0 || (d->bias_offset & 3))) return HOT_EINVAL;
     if (!aligned16(x) || !aligned16(mu_w) || !aligned16(sigma_w) || !aligned4(y)) return HOT_EINVAL;
     if (mu_b && (!aligned4(mu_b) || !aligned4(sigma_b))) return HOT_EINVAL;
@@ -185,6 +217,7 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     a.in_features = d->in_features;
     a.out_features = d->out_features;
     a.ldx = d->ldx;
+    a.x_sample_stride = d->x_sample_stride;
     a.s_loc = d->s_local;
     a.weight_quad0 = d->weight_offset >> 2;
     a.bias_quad0 = mu_b ? d->bias_offset >> 2 : 0;
@@ -199,7 +232,7 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     // rows per workgroup: 16, 32 or 64 (one, two or four MFMA row tiles share every drawn weight)
     const int rb = d->rows > 32 ? 4 : (d->rows > 16 ? 2 : 1);
     // samples whose accumulators are live together (they share the loads of mu_W, sigma_W and x)
-    const int st = d->s_local >= 4 && rb <= 2 ? 4 : (d->s_local >= 2 ? 2 : 1);
+    const int st = d->s_local >= 4 && four_samples_fit(rb, d->x_sample_stride != 0) ? 4 : (d->s_local >= 2 ? 2 : 1);
     const long gx = (d->out_features + kColsPerWave - 1) / kColsPerWave;
     const long gy = (d->rows + kRowsPerTile * rb - 1) / (kRowsPerTile * rb);
     if (gx > 0x7fffffffL || gy > 65535) return HOT_EINVAL;

@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(hot):
 
 
 def test_host_only_entry_points(hot):
-    assert hot.hot_version() == 201
+    assert hot.hot_version() == 202
     assert hot.hot_strerror(0) == "success"
     assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
     assert hot.hot_strerror(-99) == "unknown error code"
@@ -50,7 +50,8 @@ def test_struct_layout_matches_header(hot):
     assert ctypes.sizeof(hot.hot_desc) == 40
     assert hot.hot_desc.dataset_size.offset == 24 and hot.hot_desc.flags.offset == 36
     assert ctypes.sizeof(hot.hot_launch) == 16
-    assert ctypes.sizeof(hot.hot_linear_desc) == 56 and hot.hot_linear_desc.s_local.offset == 48
+    assert ctypes.sizeof(hot.hot_linear_desc) == 64 and hot.hot_linear_desc.s_local.offset == 48
+    assert hot.hot_linear_desc.x_sample_stride.offset == 56
     assert ctypes.sizeof(hot.hot_adam) == 56 and hot.hot_adam.step.offset == 48
     assert ctypes.sizeof(hot.hot_rng) == 16 and hot.hot_rng.step.offset == 8 and hot.hot_rng.first_sample.offset == 12
 
@@ -73,6 +74,7 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_forward_dropout_rng(None, None, 0.5, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward_dropout_rng(None, None, 0.5, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward_rows(None, None, None, None, None, None, 0, 1, 0, 1, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_backward_adam(None, None, None, None, None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_forward_rng(None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward_rng(None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_sample_eps(None, None, None, None) == hot.HOT_EINVAL

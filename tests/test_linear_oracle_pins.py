@@ -89,3 +89,25 @@ def test_samples_are_independent_slices(oracle):
     spread = np.sqrt((c["x"].astype(np.float64) ** 2) @ (c["sigma_w"].astype(np.float64) ** 2).T
                      + c["sigma_b"].astype(np.float64) ** 2)
     assert np.all(np.abs(m - det) < 5 * spread / np.sqrt(20000))
+
+
+def test_per_sample_inputs_equal_one_call_per_sample(oracle):
+    """x of shape [S, R, ldx] gives sample s its own input: the result must be what S separate
+    calls with a shared input give, and must match einsum; identical blocks reduce to the shared case."""
+    c = _case(21, s=4, r=6, k=8, o=5, ldx=12)
+    g = np.random.default_rng(22)
+    xs = np.full((4, 6, 12), np.nan, f32)
+    xs[:, :, :8] = g.normal(size=(4, 6, 8))
+    y = oracle.linear_forward(**dict(c, x=xs))
+    for s in range(4):
+        one = oracle.linear_forward(xs[s], c["mu_w"], c["sigma_w"], c["eps_w"][s:s + 1], c["mu_b"], c["sigma_b"],
+                                    c["eps_b"][s:s + 1])
+        np.testing.assert_array_equal(y[s], one[0])
+    w = c["mu_w"].astype(np.float64) + c["sigma_w"].astype(np.float64) * c["eps_w"]
+    b = c["mu_b"].astype(np.float64) + c["sigma_b"].astype(np.float64) * c["eps_b"]
+    want = np.einsum("srk,sok->sro", xs[:, :, :8].astype(np.float64), w) + b[:, None, :]
+    np.testing.assert_allclose(y, want, rtol=1e-13, atol=1e-13)
+    same = np.ascontiguousarray(np.broadcast_to(c["x"], (4,) + c["x"].shape))
+    np.testing.assert_array_equal(oracle.linear_forward(**dict(c, x=same)), oracle.linear_forward(**c))
+    with pytest.raises(ValueError):
+        oracle.linear_forward(**dict(c, x=xs[:3]))

@@ -38,10 +38,10 @@ def _layer(seed, rows, k, o, ldx=None):
 def _run(hot, c, s, rng, w_off, b_off, bias=True):
     xd = torch.from_numpy(c["x"]).to(DEV)
     k, o = c["mu_w"].shape[1], c["mu_w"].shape[0]
-    rows = c["x"].shape[0]
+    rows = c["x"].shape[-2]
     y = torch.full((s, rows, o), float("nan"), device=DEV)
     t = {n: torch.from_numpy(c[n]).to(DEV) for n in ("mu_w", "sigma_w", "mu_b", "sigma_b")}
-    hot.hot_linear_forward_rng(rng, xd[:, :k], t["mu_w"], t["sigma_w"], t["mu_b"] if bias else None,
+    hot.hot_linear_forward_rng(rng, xd[..., :k], t["mu_w"], t["sigma_w"], t["mu_b"] if bias else None,
                                t["sigma_b"] if bias else None, y, w_off, b_off)
     torch.cuda.synchronize()
     return y.cpu().numpy()
@@ -56,9 +56,9 @@ def _check(oracle, c, y, s, rng, w_off, b_off, bias=True):
         want = oracle.linear_forward(c["x"], c["mu_w"], c["sigma_w"], ew, c["mu_b"], c["sigma_b"], eb)
     else:
         want = oracle.linear_forward(c["x"], c["mu_w"], c["sigma_w"], ew)
-    ax = np.abs(c["x"][:, :k].astype(np.float64))
+    ax = np.abs(c["x"][..., :k].astype(np.float64))
     mag = np.abs(c["mu_w"].astype(np.float64))[None] + c["sigma_w"].astype(np.float64)[None] * rw      # [S, O, K]
-    A = np.einsum("rk,sok->sro", ax, mag)
+    A = np.einsum("srk,sok->sro" if ax.ndim == 3 else "rk,sok->sro", ax, mag)
     if bias:
         A = A + (np.abs(c["mu_b"].astype(np.float64)) + c["sigma_b"].astype(np.float64) * rb)[:, None, :]
     tol = 1e-5 * A
@@ -120,6 +120,56 @@ def test_layer_sees_the_w_of_hot_forward_rng(hot):
         want = x64 @ ws.T + w64[si, b_off:b_off + o]
         A = np.abs(x64) @ np.abs(ws).T + np.abs(w64[si, b_off:b_off + o])
         assert np.all(np.abs(y[si] - want) <= 1e-5 * A)
+
+
+# (rows, in, out, samples): every row-tile count, sample-chunk size and a ragged everything
+PER_SAMPLE = [(1, 8, 3, 2), (16, 128, 128, 4), (17, 36, 33, 5), (33, 100, 70, 3), (64, 128, 24, 16), (70, 64, 40, 2), (256, 192, 10, 1)]
+
+
+@pytest.mark.parametrize("rows,k,o,s", PER_SAMPLE)
+def test_fused_layer_with_one_input_per_sample(oracle, hot, rows, k, o, s):
+    print("case linear per-sample x", rows, k, o, s, flush=True)
+    c = _layer(rows * 13 + k, rows, k, o, ldx=k + 4 if rows % 2 else k)
+    g = np.random.default_rng(rows + s)
+    xs = np.full((s,) + c["x"].shape, np.nan, np.float32)
+    xs[:, :, :k] = g.normal(size=(s, rows, k))
+    c["x"] = xs
+    rng = hot.hot_rng(seed=2024, step=4, first_sample=3)
+    w_off, b_off = 16, 16 + ((o * k + 3) // 4) * 4 + 8
+    y = _run(hot, c, s, rng, w_off, b_off)
+    worst = _check(oracle, c, y, s, rng, w_off, b_off)
+    print("  worst error / magnitude sum: %.2e" % worst, flush=True)
+
+
+def test_two_layer_bayesian_mlp_forward(oracle, hot):
+    """The paper's use-case-2 MLP shape in miniature: layer 1 on the shared minibatch, ReLU, layer 2
+    on each sample's own activations, both with weights drawn in the kernel from one hot_rng over
+    the flattened parameter vector; against the oracle run on the oracle's own activations."""
+    rows, d_in, d_h, d_out, s = 48, 96, 128, 24, 4
+    l1, l2 = _layer(1, rows, d_in, d_h), _layer(2, rows, d_h, d_out)
+    off = {"w1": 0, "b1": d_in * d_h, "w2": d_in * d_h + d_h, "b2": d_in * d_h + d_h + d_h * d_out}
+    rng = hot.hot_rng(seed=7, step=11, first_sample=0)
+    t1 = {n: torch.from_numpy(l1[n]).to(DEV) for n in ("mu_w", "sigma_w", "mu_b", "sigma_b")}
+    t2 = {n: torch.from_numpy(l2[n]).to(DEV) for n in ("mu_w", "sigma_w", "mu_b", "sigma_b")}
+    x = torch.from_numpy(l1["x"]).to(DEV)
+    h = torch.empty(s, rows, d_h, device=DEV)
+    y = torch.empty(s, rows, d_out, device=DEV)
+    hot.hot_linear_forward_rng(rng, x, t1["mu_w"], t1["sigma_w"], t1["mu_b"], t1["sigma_b"], h, off["w1"], off["b1"])
+    a = torch.relu(h)
+    hot.hot_linear_forward_rng(rng, a, t2["mu_w"], t2["sigma_w"], t2["mu_b"], t2["sigma_b"], y, off["w2"], off["b2"])
+    torch.cuda.synchronize()
+
+    def eps(n, col0, shape):
+        return oracle.eps_normal(n, s, rng.seed, rng.step, rng.first_sample, col0=col0).reshape(shape)
+
+    h64 = oracle.linear_forward(l1["x"], l1["mu_w"], l1["sigma_w"], eps(d_in * d_h, off["w1"], (s, d_h, d_in)),
+                                l1["mu_b"], l1["sigma_b"], eps(d_h, off["b1"], (s, d_h)))
+    a32 = np.maximum(h64, 0.0).astype(np.float32)
+    y64 = oracle.linear_forward(a32, l2["mu_w"], l2["sigma_w"], eps(d_h * d_out, off["w2"], (s, d_out, d_h)),
+                                l2["mu_b"], l2["sigma_b"], eps(d_out, off["b2"], (s, d_out)))
+    # layer 1's error (1e-5 of its magnitude sums) passes through |W2|; bound it by the norms involved
+    scale = np.abs(a32).astype(np.float64).sum(-1).max() * np.abs(l2["mu_w"]).max() + 1.0
+    assert np.abs(y.cpu().numpy() - y64).max() <= 2e-5 * scale
 
 
 def test_rejects_what_it_cannot_run(hot):

@@ -79,6 +79,10 @@ def _load():
     lib.linear_oracle_forward.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                           ctypes.c_int64, ctypes.c_int64, fp, fp, fp, dp, fp, fp, dp, dp]
     lib.linear_oracle_forward.restype = None
+    lib.linear_oracle_backward.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                           ctypes.c_int64, ctypes.c_double, ctypes.c_double, fp, fp, fp, fp, dp, fp, fp,
+                                           dp, dp, dp, dp, dp, dp]
+    lib.linear_oracle_backward.restype = None
     lib.update_oracle_adam.argtypes = [ctypes.c_int64, ctypes.POINTER(AdamParams), dp, dp, dp, dp, dp, dp, dp, dp]
     lib.update_oracle_adam.restype = None
     lib.update_oracle_dropout_threshold.argtypes = [ctypes.c_double]
@@ -259,6 +263,45 @@ def linear_forward(x, mu_w, sigma_w, eps_w, mu_b=None, sigma_b=None, eps_b=None,
     _load().linear_oracle_forward(s, r, k, o, ldx, x_stride, _fptr(x), _fptr(mu_w), _fptr(sigma_w), _dptr(eps_w),
                                   mb, sb, eb, _dptr(y))
     return y
+
+
+def linear_backward(x, dy, mu_w, sigma_w, eps_w, mu_b=None, sigma_b=None, eps_b=None, g: float = 1.0, k: float = 0.0,
+                    want_dx: bool = True):
+    """Gradients of the sampled linear layer, fp64: (grad_mu_w [O,K], grad_sigma_w [O,K], grad_mu_b [O] or None,
+    grad_sigma_b [O] or None, dx [S,R,K] or None) from dy [S,R,O] = dL_s/dy_s; g, k as in grad().
+    x is [R, ldx >= K] or [S, R, ldx >= K]."""
+    x = _f32(x, "x")
+    dy = _f32(dy, "dy")
+    mu_w = _f32(mu_w, "mu_w")
+    sigma_w = _f32(sigma_w, "sigma_w")
+    eps_w = np.ascontiguousarray(eps_w, dtype=np.float64)
+    o, kf = mu_w.shape
+    s = eps_w.shape[0]
+    if sigma_w.shape != (o, kf) or eps_w.shape != (s, o, kf) or x.ndim not in (2, 3) or x.shape[-1] < kf:
+        raise ValueError("shape mismatch")
+    if x.ndim == 3 and x.shape[0] != s:
+        raise ValueError("per-sample x needs one [R, ldx] block per sample")
+    r, ldx = x.shape[-2], x.shape[-1]
+    if dy.shape != (s, r, o):
+        raise ValueError("dy must be [S, R, O]")
+    x_stride = r * ldx if x.ndim == 3 else 0
+    gmw, gsw = np.empty((o, kf)), np.empty((o, kf))
+    if mu_b is None:
+        mb = sb = eb = gmb_p = gsb_p = None
+        gmb = gsb = None
+    else:
+        mu_b = _f32(mu_b, "mu_b")
+        sigma_b = _f32(sigma_b, "sigma_b")
+        eps_b = np.ascontiguousarray(eps_b, dtype=np.float64)
+        if mu_b.shape != (o,) or sigma_b.shape != (o,) or eps_b.shape != (s, o):
+            raise ValueError("bias shape mismatch")
+        gmb, gsb = np.empty(o), np.empty(o)
+        mb, sb, eb, gmb_p, gsb_p = _fptr(mu_b), _fptr(sigma_b), _dptr(eps_b), _dptr(gmb), _dptr(gsb)
+    dx = np.empty((s, r, kf)) if want_dx else None
+    _load().linear_oracle_backward(s, r, kf, o, ldx, x_stride, float(g), float(k), _fptr(x), _fptr(dy), _fptr(mu_w),
+                                   _fptr(sigma_w), _dptr(eps_w), mb, sb, eb, _dptr(gmw), _dptr(gsw), gmb_p, gsb_p,
+                                   _dptr(dx) if want_dx else None)
+    return gmw, gsw, gmb, gsb, dx
 
 
 def adam_step(mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma, step, lr, beta1=0.9, beta2=0.999,

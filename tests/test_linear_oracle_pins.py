@@ -111,3 +111,86 @@ def test_per_sample_inputs_equal_one_call_per_sample(oracle):
     np.testing.assert_array_equal(oracle.linear_forward(**dict(c, x=same)), oracle.linear_forward(**c))
     with pytest.raises(ValueError):
         oracle.linear_forward(**dict(c, x=xs[:3]))
+
+
+def _loss(oracle, c, coef, x=None):
+    """L = sum_s sum_{r,o} coef[s,r,o] * y_s[r,o]: a loss whose dL_s/dy_s is coef[s] exactly."""
+    y = oracle.linear_forward(**(c if x is None else dict(c, x=x)))
+    return float(np.sum(coef * y))
+
+
+@pytest.mark.parametrize("per_sample_x", [False, True])
+def test_backward_matches_central_differences_of_the_forward_oracle(oracle, per_sample_x):
+    """dL/dmu, dL/dsigma (weights and biases) and dL/dx by central differences of the forward
+    function; the loss is linear in every one of them, so the differences are exact up to rounding."""
+    c = _case(31, s=3, r=4, k=8, o=5)
+    g = np.random.default_rng(32)
+    if per_sample_x:
+        c["x"] = g.normal(size=(3, 4, 8)).astype(f32)
+    coef = g.normal(size=(3, 4, 5)).astype(f32)
+    gmw, gsw, gmb, gsb, dx = oracle.linear_backward(c["x"], coef, c["mu_w"], c["sigma_w"], c["eps_w"], c["mu_b"],
+                                                    c["sigma_b"], c["eps_b"], g=1.0, k=0.0)
+    h = 2.0 ** -6                      # exact in fp32 for values of order one
+    for name, grad in (("mu_w", gmw), ("sigma_w", gsw), ("mu_b", gmb), ("sigma_b", gsb)):
+        for idx in list(np.ndindex(c[name].shape))[::3]:
+            up, dn = c[name].copy(), c[name].copy()
+            up[idx] += h
+            dn[idx] -= h
+            fd = (_loss(oracle, dict(c, **{name: up}), coef) - _loss(oracle, dict(c, **{name: dn}), coef)) / \
+                 (float(up[idx]) - float(dn[idx]))
+            assert abs(fd - grad[idx]) <= 1e-9 * (1 + abs(grad[idx])), (name, idx, fd, grad[idx])
+    x = c["x"]
+    for idx in list(np.ndindex(x.shape))[::5]:
+        up, dn = x.copy(), x.copy()
+        up[idx] += h
+        dn[idx] -= h
+        fd = (_loss(oracle, c, coef, up) - _loss(oracle, c, coef, dn)) / (float(up[idx]) - float(dn[idx]))
+        want = dx[idx] if per_sample_x else dx[(slice(None),) + idx].sum()      # a shared x collects every sample's share
+        assert abs(fd - want) <= 1e-9 * (1 + abs(want)), (idx, fd, want)
+
+
+def test_backward_weight_gradients_equal_the_flat_gradient_oracle(oracle):
+    """The layer's weight gradients must be what the flat-vector oracle (Algorithm 2's gradient and
+    averaging lines) returns for the per-sample weight gradients G_s = dy_s^T x_s formed by einsum,
+    including the KL part and the sum convention's scaling."""
+    c = _case(41, s=4, r=6, k=8, o=3)
+    g = np.random.default_rng(42)
+    dy = g.normal(size=(4, 6, 3)).astype(f32)
+    s_total, dsize = 16, 450.0
+    gg, kk = 1.0 / s_total, 4 / (s_total * dsize)
+    gmw, gsw, gmb, gsb, dx = oracle.linear_backward(c["x"], dy, c["mu_w"], c["sigma_w"], c["eps_w"], c["mu_b"],
+                                                    c["sigma_b"], c["eps_b"], g=gg, k=kk)
+    G = np.einsum("sro,rk->sok", dy.astype(np.float64), c["x"].astype(np.float64))        # [S, O, K]
+    # the flat oracle takes fp32 arrays: compare on inputs where G and eps are exactly representable
+    G32, e32 = G.astype(f32), c["eps_w"].astype(f32)
+    want_m, want_s = oracle.grad(c["mu_w"].ravel(), c["sigma_w"].ravel(), e32.reshape(4, -1), G32.reshape(4, -1), s_total, dsize)
+    gmw32, gsw32, _, _, _ = oracle.linear_backward(c["x"], dy, c["mu_w"], c["sigma_w"], e32.astype(np.float64), g=gg, k=kk,
+                                                   want_dx=False)
+    np.testing.assert_allclose(gmw32.ravel(), want_m, rtol=1e-6, atol=1e-9)          # G32 is G rounded to fp32
+    np.testing.assert_allclose(gsw32.ravel(), want_s, rtol=1e-6, atol=1e-9)
+    # closed forms: the data part by einsum, the KL part mu and sigma - 1/sigma
+    m64, s64 = c["mu_w"].astype(np.float64), c["sigma_w"].astype(np.float64)
+    np.testing.assert_allclose(gmw, gg * G.sum(0) + kk * m64, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(gsw, gg * (G * c["eps_w"]).sum(0) + kk * (s64 - 1 / s64), rtol=1e-13, atol=1e-15)
+    Gb = dy.astype(np.float64).sum(1)                                                       # [S, O]
+    mb, sb = c["mu_b"].astype(np.float64), c["sigma_b"].astype(np.float64)
+    np.testing.assert_allclose(gmb, gg * Gb.sum(0) + kk * mb, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(gsb, gg * (Gb * c["eps_b"]).sum(0) + kk * (sb - 1 / sb), rtol=1e-13, atol=1e-15)
+    w = m64 + s64 * c["eps_w"]
+    np.testing.assert_allclose(dx, np.einsum("sro,sok->srk", dy.astype(np.float64), w), rtol=1e-13, atol=1e-14)
+
+
+def test_backward_special_cases(oracle):
+    c = _case(51, s=2, r=3, k=4, o=2)
+    zero = np.zeros((2, 3, 2), f32)
+    gmw, gsw, gmb, gsb, dx = oracle.linear_backward(c["x"], zero, c["mu_w"], c["sigma_w"], c["eps_w"], c["mu_b"],
+                                                    c["sigma_b"], c["eps_b"], g=0.5, k=0.25)
+    np.testing.assert_array_equal(gmw, 0.25 * c["mu_w"].astype(np.float64))             # dy = 0: only the KL part is left
+    s64 = c["sigma_b"].astype(np.float64)
+    np.testing.assert_allclose(gsb, 0.25 * (s64 - 1 / s64), rtol=1e-15)
+    assert not dx.any()
+    # no bias, no dx
+    out = oracle.linear_backward(c["x"], zero, c["mu_w"], c["sigma_w"], c["eps_w"], want_dx=False)
+    assert out[2] is None and out[3] is None and out[4] is None
+    with pytest.raises(ValueError):
+        oracle.linear_backward(c["x"], zero[:, :2], c["mu_w"], c["sigma_w"], c["eps_w"])

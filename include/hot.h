@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 202 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 203 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
@@ -206,6 +206,30 @@ typedef struct hot_linear_desc {
 
 int hot_linear_forward_rng(const hot_linear_desc *desc, const hot_rng *rng, const float *x, const float *mu_w,
                            const float *sigma_w, const float *mu_b, const float *sigma_b, float *y, void *stream);
+
+/*
+ * Back-propagation through the same layer (Algorithm 1 / 2: the gradient and averaging lines for a
+ * Linear layer), again without the sampled weights, and without the per-sample weight gradients,
+ * ever existing in memory.  dy[s_local, rows, out_features] (packed, DEVICE) holds dL_s/dy_s.  With
+ * G_s[o,k] = sum_r dy_s[r,o] x_s[r,k] and Gb_s[o] = sum_r dy_s[r,o]:
+ *   grad_mu_w[o,k]    = g sum_s G_s[o,k]              + k_kl mu_w[o,k]
+ *   grad_sigma_w[o,k] = g sum_s G_s[o,k] eps_s[o,k]   + k_kl (sigma_w[o,k] - 1/sigma_w[o,k])
+ *   grad_mu_b, grad_sigma_b likewise from Gb_s and the bias draws
+ *   dx[s,r,k]         = sum_o dy_s[r,o] fma(sigma_w[o,k], eps_s[o,k], mu_w[o,k])
+ * i.e. what hot_backward_rng returns for grad_w = G on the flat parameter vector that holds the
+ * layer at desc's offsets (g and k_kl from s_total, dataset_size and flags exactly as hot_create
+ * derives them from hot_desc; eps regenerated from rng as in the forward call).  Both contractions
+ * run on the matrix cores in fp32.  grad_mu_w, grad_sigma_w: [out_features, in_features] packed,
+ * 16-byte aligned, overwritten; grad_mu_b, grad_sigma_b: [out_features], both NULL exactly when
+ * mu_b is; dx: [s_local, rows, in_features] packed, 16-byte aligned, one block per sample also
+ * when x is shared (the caller adds them up), or NULL to skip it (a first layer).  Other arguments
+ * and rules as for hot_linear_forward_rng.  Intended for the same regime (tens of rows): every
+ * weight is drawn once per sample for the weight gradients and once per block of 64 rows for dx.
+ */
+int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double dataset_size, uint32_t flags,
+                            const hot_rng *rng, const float *x, const float *dy, const float *mu_w,
+                            const float *sigma_w, const float *mu_b, const float *sigma_b, float *grad_mu_w,
+                            float *grad_sigma_w, float *grad_mu_b, float *grad_sigma_b, float *dx, void *stream);
 
 /*
  * "Update mu and sigma using optimizer (e.g., Adam)" -- the last line of the inner loop of

@@ -1,5 +1,7 @@
 """torch.autograd plumbing around the C ABI: the Gaussian sample layer as a differentiable
-function of (mu, sigma), so that a PyTorch training loop can use the HIP path unchanged.
+function of (mu, sigma), so that a PyTorch training loop can use the HIP path unchanged, and the
+sampled linear layer (BayesianLinear, at the end) whose weights and per-sample weight gradients
+never exist in memory.
 
     layer = GaussianSampleLayer(n_weights, s_local, dataset_size)
     w, kl = layer.sample(mu, sigma, step)          # w[s] = mu + sigma * eps_s,  eps drawn in the kernel
@@ -53,3 +55,57 @@ class GaussianSampleLayer:
     def sample(self, mu: torch.Tensor, sigma: torch.Tensor, step: int):
         """w[S_loc, N] (differentiable with respect to mu and sigma) and the KL term (detached, fp64)."""
         return _Sample.apply(mu, sigma, self, int(step))
+
+
+class _Linear(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, mu_w, sigma_w, mu_b, sigma_b, layer, step):
+        rng = hot.hot_rng(seed=layer.seed, step=step, first_sample=layer.first_sample)
+        xd = x.detach().contiguous()
+        y = torch.empty(layer.s_local, xd.shape[-2], layer.out_features, dtype=torch.float32, device=x.device)
+        det = [t.detach() if t is not None else None for t in (mu_w, sigma_w, mu_b, sigma_b)]
+        hot.hot_linear_forward_rng(rng, xd, det[0], det[1], det[2], det[3], y, layer.weight_offset, layer.bias_offset)
+        ctx.layer, ctx.rng, ctx.has_bias = layer, rng, mu_b is not None
+        ctx.save_for_backward(xd, *[t for t in det if t is not None])
+        return y
+
+    @staticmethod
+    def backward(ctx, grad_y):
+        layer = ctx.layer
+        xd, mu_w, sigma_w = ctx.saved_tensors[:3]
+        mu_b, sigma_b = ctx.saved_tensors[3:] if ctx.has_bias else (None, None)
+        gmw, gsw = torch.empty_like(mu_w), torch.empty_like(sigma_w)
+        gmb = torch.empty_like(mu_b) if ctx.has_bias else None
+        gsb = torch.empty_like(sigma_b) if ctx.has_bias else None
+        dx = None
+        if ctx.needs_input_grad[0]:
+            dx = torch.empty(layer.s_local, xd.shape[-2], layer.in_features, dtype=torch.float32, device=xd.device)
+        hot.hot_linear_backward_rng(ctx.rng, xd, grad_y.contiguous(), mu_w, sigma_w, mu_b, sigma_b, gmw, gsw, gmb, gsb, dx,
+                                    layer.s_local, layer.dataset_size, hot.HOT_REDUCE_NONE, layer.weight_offset,
+                                    layer.bias_offset)
+        if dx is not None and xd.dim() == 2:
+            dx = dx.sum(0)          # a shared input collects every sample's share
+        return dx, gmw, gsw, gmb, gsb, None, None
+
+
+class BayesianLinear:
+    """One mean-field Gaussian linear layer on the fused kernels.  `weight_offset` places the layer in
+    the flat parameter vector of the network (it selects the generator's counters, so two layers must
+    not overlap); `next_offset` is where the following layer may start.  forward(x, ...) takes the
+    minibatch [R, K] (first layer) or one input per sample [S_loc, R, K] and returns y [S_loc, R, O];
+    the gradients it hands to autograd include the KL part divided by dataset_size."""
+
+    def __init__(self, in_features: int, out_features: int, s_local: int, dataset_size: float, bias: bool = True,
+                 seed: int = 0, first_sample: int = 0, weight_offset: int = 0):
+        if in_features % 4 or weight_offset % 4:
+            raise ValueError("in_features and weight_offset must be multiples of 4")
+        self.in_features, self.out_features, self.s_local = in_features, out_features, s_local
+        self.dataset_size, self.seed, self.first_sample, self.bias = float(dataset_size), seed, first_sample, bias
+        self.weight_offset = weight_offset
+        self.bias_offset = weight_offset + in_features * out_features        # a multiple of 4 as well
+        self.next_offset = (self.bias_offset + (out_features if bias else 0) + 3) // 4 * 4
+
+    def forward(self, x, mu_w, sigma_w, mu_b, sigma_b, step: int):
+        if self.bias == (mu_b is None):
+            raise ValueError("bias arrays do not match the layer's bias setting")
+        return _Linear.apply(x, mu_w, sigma_w, mu_b, sigma_b, self, int(step))

@@ -25,7 +25,8 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_version", "hot_probe_copy", "hot_forward_rng", "hot_backward_rng",
            "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
            "hot_stats_merge", "hot_linear_forward_rng", "hot_adam_step", "hot_forward_dropout_rng",
-           "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam")
+           "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam",
+           "hot_linear_backward_rng")
 
 
 class hot_desc(ctypes.Structure):
@@ -102,6 +103,8 @@ def lib() -> ctypes.CDLL:
     L.hot_linear_forward_rng.restype = ctypes.c_int
     L.hot_adam_step.argtypes = [ctypes.POINTER(hot_adam), ctypes.c_int64] + [fp] * 8 + [vp]
     L.hot_adam_step.restype = ctypes.c_int
+    L.hot_linear_backward_rng.argtypes = [ctypes.POINTER(hot_linear_desc), ctypes.c_int32, ctypes.c_double, ctypes.c_uint32,
+                                          rp] + [fp] * 11 + [vp]
     L.hot_backward_adam.argtypes = [vp, rp, ctypes.POINTER(hot_adam)] + [fp] * 8 + [vp]
     L.hot_forward_dropout_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, fp, fp, vp]
     L.hot_forward_dropout_rng.restype = ctypes.c_int
@@ -452,3 +455,46 @@ def hot_backward_adam(plan: Plan, rng, params: hot_adam, mu, sigma, eps, grad_w,
                                    _vec(m_mu, n, dev, "m_mu"), _vec(v_mu, n, dev, "v_mu"),
                                    _vec(m_sigma, n, dev, "m_sigma"), _vec(v_sigma, n, dev, "v_sigma"), _stream(dev))
     _check(code, "hot_backward_adam", plan)
+
+
+def hot_linear_backward_rng(rng: hot_rng, x, dy, mu_w, sigma_w, mu_b, sigma_b, grad_mu_w, grad_sigma_w, grad_mu_b,
+                            grad_sigma_b, dx, s_total: int, dataset_size: float, flags: int = HOT_REDUCE_SUM,
+                            weight_offset: int = 0, bias_offset: int = 0) -> None:
+    """Gradients of the sampled linear layer from dy [S_loc, R, O] (see include/hot.h): weight and bias
+    gradients scaled like hot_backward's, and dx [S_loc, R, K] (or None to skip it)."""
+    def chk(t, shape, name):
+        if not (t.is_cuda and t.device == x.device and t.dtype == torch.float32 and tuple(t.shape) == shape
+                and t.is_contiguous()):
+            raise TypeError(f"{name}: need a contiguous float32 tensor of shape {shape} on {x.device}")
+    if not (x.is_cuda and x.dtype == torch.float32 and x.dim() in (2, 3) and x.stride(-1) == 1):
+        raise TypeError("x: need a [rows, K] or [S_loc, rows, K] float32 device tensor with unit column stride")
+    rows, k = x.shape[-2:]
+    ldx = x.stride(-2) if rows > 1 else k
+    if dy.dim() != 3:
+        raise ValueError("dy must be [S_loc, rows, out_features]")
+    s_loc, o = dy.shape[0], dy.shape[2]
+    x_stride = 0
+    if x.dim() == 3:
+        if x.shape[0] != s_loc:
+            raise ValueError("per-sample x needs as many [rows, K] blocks as dy has samples")
+        x_stride = x.stride(0) if s_loc > 1 else rows * ldx
+    chk(dy, (s_loc, rows, o), "dy")
+    for t, name in ((mu_w, "mu_w"), (sigma_w, "sigma_w"), (grad_mu_w, "grad_mu_w"), (grad_sigma_w, "grad_sigma_w")):
+        chk(t, (o, k), name)
+    bias = (mu_b, sigma_b, grad_mu_b, grad_sigma_b)
+    if any(b is None for b in bias) and not all(b is None for b in bias):
+        raise ValueError("give all four bias arrays or none")
+    if mu_b is not None:
+        for t, name in zip(bias, ("mu_b", "sigma_b", "grad_mu_b", "grad_sigma_b")):
+            chk(t, (o,), name)
+    if dx is not None:
+        chk(dx, (s_loc, rows, k), "dx")
+    d = hot_linear_desc(rows, k, o, ldx, weight_offset, bias_offset, s_loc, 0, x_stride)
+    ptr = lambda t: t.data_ptr() if t is not None else None
+    with torch.cuda.device(x.device):
+        code = lib().hot_linear_backward_rng(ctypes.byref(d), int(s_total), float(dataset_size), int(flags), ctypes.byref(rng),
+                                             x.data_ptr(), dy.data_ptr(), mu_w.data_ptr(), sigma_w.data_ptr(), ptr(mu_b),
+                                             ptr(sigma_b), grad_mu_w.data_ptr(), grad_sigma_w.data_ptr(), ptr(grad_mu_b),
+                                             ptr(grad_sigma_b), ptr(dx), _stream(x.device.index))
+    if code != HOT_OK:
+        raise HotError(code, "hot_linear_backward_rng", lib().hot_last_hip_error(None))

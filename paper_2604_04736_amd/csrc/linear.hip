@@ -190,6 +190,275 @@ void linear_go(int st, dim3 grid, int waves, hipStream_t s, const LinearArgs &a)
     else linear_go_st<RB, false>(st, grid, waves, s, a);
 }
 
+
+// ---------------------------------------------------------------------------------
+// Backward.  Weight gradients: a wave owns 16 outputs x 64 inputs and contracts over the rows with
+// the TRANSPOSED product P_s[k][o] = sum_r x_s[r][k] dy_s[r][o] (x as the A operand, dy as B), so
+// that the four accumulator registers of a lane are four consecutive inputs k of one output o:
+// exactly one quad of the generator, drawn once per sample, and one 16-byte access to mu, sigma
+// and the two gradient arrays.  Input gradients: dx_s^T[k][r] = sum_o W_s[o][k] dy_s[r][o] with
+// the drawn weights as the A operand; MFMA number i of a step takes element i of every lane's
+// quad (as in the forward kernel), so result register rr of the four accumulators again holds
+// four consecutive inputs and dx is written with 16-byte stores.
+// ---------------------------------------------------------------------------------
+struct LinearGradArgs {
+    long rows, in_features, out_features, ldx, x_sample_stride;
+    int s_loc;
+    long weight_quad0, bias_quad0;
+    double g, k;            // scaling of the data part and of the KL part of the gradients
+    const float *x, *dy, *mu_w, *sigma_w, *mu_b, *sigma_b;
+    float *gmu_w, *gsig_w, *gmu_b, *gsig_b, *dx;
+    Rng rng;
+};
+
+__device__ __forceinline__ float pick4(f4 v, int c) { return c == 0 ? v[0] : (c == 1 ? v[1] : (c == 2 ? v[2] : v[3])); }
+
+// grad_mu, grad_sigma of one parameter from its sums over the samples (gradient and averaging lines
+// of Algorithm 2; d KL / d mu = mu, d KL / d sigma = sigma - 1/sigma)
+__device__ __forceinline__ void finish_pair(float sum_g, float sum_ge, float m, float sd, double g, double k,
+                                            float &gm, float &gs)
+{
+    const double kl_m = k != 0.0 ? k * (double)m : 0.0;
+    const double kl_s = k != 0.0 ? k * ((double)sd - (double)(1.0f / sd)) : 0.0;
+    gm = (float)fma(g, (double)sum_g, kl_m);
+    gs = (float)fma(g, (double)sum_ge, kl_s);
+}
+
+constexpr int kWgradWaves = 4;       // waves per workgroup when every wave has a tile of its own
+constexpr int kWgradMaxSplit = 8;    // most waves that share one tile (60 KiB of LDS for their partial sums)
+constexpr int kWgradRowsPerIter = 16;
+constexpr int kWgradPartials = 34;   // per lane: 16 + 16 weight-gradient sums and the two bias sums
+
+// SPLIT = false: the four waves of a workgroup own one tile each.  SPLIT = true (layers with few
+// tiles and many rows): the waves of a workgroup share one tile, take the 16-row blocks round-robin,
+// apply each sample's eps to their own partial product (the gradient is linear in it) and add their
+// sums through LDS in wave order at the end.
+template <bool SPLIT>
+__global__ void __launch_bounds__(64 * (SPLIT ? kWgradMaxSplit : kWgradWaves))
+hot_linear_wgrad_kernel(LinearGradArgs a)
+{
+    extern __shared__ float partial[];   // SPLIT: [waves - 1][kWgradPartials][64]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    const int n = lane & 15, j = lane >> 4;
+    const long K = a.in_features, O = a.out_features, R = a.rows;
+    const long k_groups = (K + 63) / 64;
+    const long tile = SPLIT ? (long)blockIdx.x : (long)blockIdx.x * kWgradWaves + wave;
+    if (tile >= k_groups * ((O + 15) / 16)) return;      // SPLIT: never taken (one workgroup per tile); else a whole wave, and no barrier follows
+    const long o0 = (tile / k_groups) * 16, k0 = (tile % k_groups) * 64;
+    const long o = o0 + n;
+    const bool o_ok = o < O;
+    const bool bias_tile = a.mu_b != nullptr && k0 == 0;     // uniform over the wave: this tile also owns 16 biases
+    const long row_first = SPLIT ? (long)wave * kWgradRowsPerIter : 0;
+    const long row_step = SPLIT ? (long)waves * kWgradRowsPerIter : kWgradRowsPerIter;
+
+    f4 gm[4], gs[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) gm[t] = gs[t] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    float gb_m = 0.0f, gb_s = 0.0f;
+
+    for (int s = 0; s < a.s_loc; ++s) {
+        const float *xs = a.x + (size_t)s * (size_t)a.x_sample_stride;
+        const float *dys = a.dy + (size_t)s * (size_t)R * (size_t)O;
+        f4 P[4], Pb = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) P[t] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (long rb = row_first; rb < R; rb += row_step) {
+            float bv[kWgradRowsPerIter / 4], av[kWgradRowsPerIter / 4][4];
+#pragma unroll
+            for (int q = 0; q < kWgradRowsPerIter / 4; ++q) {
+                const long r = rb + 4 * q + j;
+                const bool r_ok = r < R;
+                bv[q] = (r_ok && o_ok) ? dys[r * O + o] : 0.0f;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const long kk = k0 + 16 * t + n;
+                    av[q][t] = (r_ok && kk < K) ? xs[r * a.ldx + kk] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kWgradRowsPerIter / 4; ++q)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) P[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q][t], bv[q], P[t], 0, 0, 0);
+            if (bias_tile) {             // column sums of dy: the same contraction against ones
+#pragma unroll
+                for (int q = 0; q < kWgradRowsPerIter / 4; ++q) Pb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, bv[q], Pb, 0, 0, 0);
+            }
+        }
+        // register c of P[t] is input k0 + 16 t + 4 j + c of output o
+        if (row_first < R) {             // a wave without rows has nothing to add (uniform over the wave)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const long col = k0 + 16 * t + 4 * j;
+                if (o_ok && col < K) {
+                    const f4 e = eps_quad(a.weight_quad0 + ((o * K + col) >> 2), s, a.rng);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        gm[t][c] += P[t][c];
+                        gs[t][c] = __builtin_fmaf(P[t][c], e[c], gs[t][c]);
+                    }
+                }
+            }
+        }
+        if (bias_tile && row_first < R && o_ok) {      // every register of Pb holds sum_r dy_s[r][o]
+            const f4 e = eps_quad(a.bias_quad0 + (o >> 2), s, a.rng);
+            gb_m += Pb[0];
+            gb_s = __builtin_fmaf(Pb[0], pick4(e, (int)(o & 3)), gb_s);
+        }
+    }
+
+    if constexpr (SPLIT) {
+        if (wave > 0) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    partial[((wave - 1) * kWgradPartials + t * 4 + c) * 64 + lane] = gm[t][c];
+                    partial[((wave - 1) * kWgradPartials + 16 + t * 4 + c) * 64 + lane] = gs[t][c];
+                }
+            partial[((wave - 1) * kWgradPartials + 32) * 64 + lane] = gb_m;
+            partial[((wave - 1) * kWgradPartials + 33) * 64 + lane] = gb_s;
+        }
+        __syncthreads();
+        if (wave != 0) return;
+        for (int v = 1; v < waves; ++v)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    gm[t][c] += partial[((v - 1) * kWgradPartials + t * 4 + c) * 64 + lane];
+                    gs[t][c] += partial[((v - 1) * kWgradPartials + 16 + t * 4 + c) * 64 + lane];
+                }
+        for (int v = 1; v < waves; ++v) {
+            gb_m += partial[((v - 1) * kWgradPartials + 32) * 64 + lane];
+            gb_s += partial[((v - 1) * kWgradPartials + 33) * 64 + lane];
+        }
+    }
+
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const long col = k0 + 16 * t + 4 * j;
+        if (o_ok && col < K) {
+            const f4 m4 = load4<true, false>(a.mu_w + o * K + col), sd4 = load4<true, false>(a.sigma_w + o * K + col);
+            f4 om, os;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                float u, v;
+                finish_pair(gm[t][c], gs[t][c], m4[c], sd4[c], a.g, a.k, u, v);
+                om[c] = u;
+                os[c] = v;
+            }
+            store4<true, false>(a.gmu_w + o * K + col, om);
+            store4<true, false>(a.gsig_w + o * K + col, os);
+        }
+    }
+    if (bias_tile && j == 0 && o_ok) {
+        float u, v;
+        finish_pair(gb_m, gb_s, a.mu_b[o], a.sigma_b[o], a.g, a.k, u, v);
+        a.gmu_b[o] = u;
+        a.gsig_b[o] = v;
+    }
+}
+
+// A workgroup owns 64 inputs x 16*RB rows of one sample's dx; its waves take the outputs in blocks
+// of eight, round-robin, and their partial tiles are added through LDS in wave order.
+template <int RB>
+__global__ void __launch_bounds__(64 * max_waves(RB), RB >= 4 ? 2 : 1)
+hot_linear_xgrad_kernel(LinearGradArgs a)
+{
+    extern __shared__ float partial[];   // [waves - 1][RB * 16][64]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    const int n = lane & 15, j = lane >> 4;
+    const long K = a.in_features, O = a.out_features, R = a.rows;
+    const long k0 = (long)blockIdx.x * 64, r0 = (long)blockIdx.y * (kRowsPerTile * RB);
+    const int s = blockIdx.z;
+    const float *dys = a.dy + (size_t)s * (size_t)R * (size_t)O;
+    const long kq = k0 + 4 * n;          // this lane's quad of inputs (as an A lane)
+    const bool k_ok = kq < K;
+
+    f4 acc[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[rb][i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    for (long ob = (long)wave * 8; ob < O; ob += (long)waves * 8) {
+        f4 m4[2], sd4[2];
+        float dyv[RB][2];
+        bool ok[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const long o = ob + 4 * h + j;
+            ok[h] = k_ok && o < O;
+            m4[h] = ok[h] ? load4<true, false>(a.mu_w + o * K + kq) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+            sd4[h] = ok[h] ? load4<true, false>(a.sigma_w + o * K + kq) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                const long row = r0 + kRowsPerTile * rb + n;
+                dyv[rb][h] = (row < R && o < O) ? dys[row * O + o] : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            f4 w4 = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (ok[h]) {
+                const long o = ob + 4 * h + j;
+                const f4 e = eps_quad(a.weight_quad0 + ((o * K + kq) >> 2), s, a.rng);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) w4[c] = __builtin_fmaf(sd4[h][c], e[c], m4[h][c]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+                    acc[rb][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w4[i], dyv[rb][h], acc[rb][i], 0, 0, 0);
+        }
+    }
+
+    if (waves > 1) {
+        if (wave > 0) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr)
+                        partial[((wave - 1) * (RB * 16) + (rb * 4 + i) * 4 + rr) * 64 + lane] = acc[rb][i][rr];
+        }
+        __syncthreads();
+        if (wave == 0) {
+            for (int v = 1; v < waves; ++v)
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr)
+                            acc[rb][i][rr] += partial[((v - 1) * (RB * 16) + (rb * 4 + i) * 4 + rr) * 64 + lane];
+        }
+    }
+    if (wave != 0) return;
+
+    // register rr of accumulator i is input k0 + 16 j + 4 rr + i of row r0 + 16 rb + n
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const long row = r0 + kRowsPerTile * rb + n;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const long col = k0 + 16 * j + 4 * rr;
+            if (row < R && col < K)
+                store4<true, false>(a.dx + ((size_t)s * (size_t)R + (size_t)row) * (size_t)K + (size_t)col,
+                                    f4{acc[rb][0][rr], acc[rb][1][rr], acc[rb][2][rr], acc[rb][3][rr]});
+        }
+    }
+}
+
+template <int RB>
+void xgrad_go(dim3 grid, int waves, hipStream_t s, const LinearGradArgs &a)
+{
+    const size_t lds = waves > 1 ? (size_t)(waves - 1) * (size_t)(RB * 16) * 64 * sizeof(float) : 0;
+    hot_linear_xgrad_kernel<RB><<<grid, dim3(64 * waves), lds, s>>>(a);
+}
+
 }  // namespace
 
 extern "C" {
@@ -248,6 +517,117 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     if (rb == 4) linear_go<4>(st, grid, waves, s, a);
     else if (rb == 2) linear_go<2>(st, grid, waves, s, a);
     else linear_go<1>(st, grid, waves, s, a);
+    return hot_detail::note_hip(hipGetLastError());
+}
+
+int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double dataset_size, uint32_t flags,
+                            const hot_rng *rng, const float *x, const float *dy, const float *mu_w,
+                            const float *sigma_w, const float *mu_b, const float *sigma_b, float *grad_mu_w,
+                            float *grad_sigma_w, float *grad_mu_b, float *grad_sigma_b, float *dx, void *stream)
+{
+    if (!d || !x || !dy || !mu_w || !sigma_w || !grad_mu_w || !grad_sigma_w) return HOT_EINVAL;
+    if ((mu_b == nullptr) != (sigma_b == nullptr) || (mu_b == nullptr) != (grad_mu_b == nullptr) ||
+        (mu_b == nullptr) != (grad_sigma_b == nullptr))
+        return HOT_EINVAL;
+    if (d->rows < 1 || d->in_features < 4 || (d->in_features & 3) || d->out_features < 1 || d->s_local < 1) return HOT_EINVAL;
+    if (d->ldx < d->in_features || (d->ldx & 3) || d->weight_offset < 0 || (d->weight_offset & 3)) return HOT_EINVAL;
+    if (d->reserved != 0 || d->x_sample_stride < 0 || (d->x_sample_stride & 3)) return HOT_EINVAL;
+    if (d->x_sample_stride != 0 && (d->rows > INT64_MAX / d->ldx || d->x_sample_stride < d->rows * d->ldx ||
+                                    d->x_sample_stride > INT64_MAX / 4 / d->s_local))
+        return HOT_EINVAL;
+    if (mu_b && (d->bias_offset < 0 || (d->bias_offset & 3))) return HOT_EINVAL;
+    if (s_total < d->s_local || !(dataset_size > 0.0) || !(dataset_size < 1.0 / 0.0)) return HOT_EINVAL;
+    if (flags != HOT_REDUCE_SUM && flags != HOT_REDUCE_MEAN && flags != HOT_REDUCE_NONE) return HOT_EINVAL;
+    if (!aligned16(x) || !aligned16(mu_w) || !aligned16(sigma_w) || !aligned16(grad_mu_w) || !aligned16(grad_sigma_w) ||
+        !aligned4(dy) || (dx && !aligned16(dx)))
+        return HOT_EINVAL;
+    if (mu_b && (!aligned4(mu_b) || !aligned4(sigma_b) || !aligned4(grad_mu_b) || !aligned4(grad_sigma_b))) return HOT_EINVAL;
+    if (d->out_features > (INT64_MAX / 8) / d->in_features) return HOT_EINVAL;
+    // element offsets into dy and dx must fit: S_loc * R * max(O, K)
+    const int64_t widest = d->out_features > d->in_features ? d->out_features : d->in_features;
+    if (d->rows > (INT64_MAX / 8) / widest || d->rows * widest > (INT64_MAX / 8) / d->s_local) return HOT_EINVAL;
+    Rng r;
+    if (!make_rng(rng, d->s_local, r)) return HOT_EINVAL;
+
+    LinearGradArgs a;
+    a.rows = d->rows;
+    a.in_features = d->in_features;
+    a.out_features = d->out_features;
+    a.ldx = d->ldx;
+    a.x_sample_stride = d->x_sample_stride;
+    a.s_loc = d->s_local;
+    a.weight_quad0 = d->weight_offset >> 2;
+    a.bias_quad0 = mu_b ? d->bias_offset >> 2 : 0;
+    if (flags == HOT_REDUCE_NONE) {
+        a.g = 1.0;
+        a.k = 1.0 / dataset_size;
+    } else if (flags == HOT_REDUCE_MEAN) {
+        a.g = 1.0 / (double)d->s_local;
+        a.k = 1.0 / dataset_size;
+    } else {
+        a.g = 1.0 / (double)s_total;
+        a.k = (double)d->s_local / ((double)s_total * dataset_size);
+    }
+    a.x = x;
+    a.dy = dy;
+    a.mu_w = mu_w;
+    a.sigma_w = sigma_w;
+    a.mu_b = mu_b;
+    a.sigma_b = sigma_b;
+    a.gmu_w = grad_mu_w;
+    a.gsig_w = grad_sigma_w;
+    a.gmu_b = grad_mu_b;
+    a.gsig_b = grad_sigma_b;
+    a.dx = dx;
+    a.rng = r;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    const long k_groups = (d->in_features + 63) / 64;
+    const long tiles = k_groups * ((d->out_features + kColsPerWave - 1) / kColsPerWave);
+    if (tiles > 0x7fffffffL) return HOT_EINVAL;
+    // few tiles and many rows: let several waves share a tile (each then draws the tile's eps itself)
+    int split = 1;
+    while (split < kWgradMaxSplit && tiles * split < 2048 && d->rows >= 2L * split * kWgradRowsPerIter) split *= 2;
+    if (split > 1) {
+        const size_t lds = (size_t)(split - 1) * kWgradPartials * 64 * sizeof(float);
+        hot_linear_wgrad_kernel<true><<<dim3((unsigned)tiles), dim3(64 * split), lds, s>>>(a);
+    } else {
+        const long wg = (tiles + kWgradWaves - 1) / kWgradWaves;
+        hot_linear_wgrad_kernel<false><<<dim3((unsigned)wg), dim3(64 * kWgradWaves), 0, s>>>(a);
+    }
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return hot_detail::note_hip(e);
+    if (!dx) return HOT_OK;
+
+    // Row tiles per workgroup: more of them share each drawn weight, fewer of them give more
+    // workgroups and more waves per workgroup.  Take the most sharing that still puts a wave on
+    // every SIMD of the chip (1024), else whatever yields the most waves.
+    const long o_blocks = (d->out_features + 7) / 8;
+    auto waves_for = [&](int rb_, long gy_) {
+        int w = 1;
+        while (w < max_waves(rb_) && k_groups * gy_ * d->s_local * w < 8192 && 2L * w <= o_blocks &&
+               (size_t)(2 * w - 1) * (size_t)(rb_ * 16) * 64 * sizeof(float) <= 65536)
+            w *= 2;
+        return w;
+    };
+    int rb = 1, waves = 1;
+    long gy = 0, best = -1;
+    for (int cand = d->rows > 32 ? 4 : (d->rows > 16 ? 2 : 1); cand >= 1; cand >>= 1) {
+        const long gy_c = (d->rows + kRowsPerTile * cand - 1) / (kRowsPerTile * cand);
+        const int w_c = waves_for(cand, gy_c);
+        const long total = k_groups * gy_c * d->s_local * w_c;
+        if (total > best) {
+            best = total;
+            rb = cand;
+            waves = w_c;
+            gy = gy_c;
+        }
+        if (total >= 1024) break;
+    }
+    if (k_groups > 0x7fffffffL || gy > 65535 || d->s_local > 65535) return HOT_EINVAL;
+    const dim3 grid((unsigned)k_groups, (unsigned)gy, (unsigned)d->s_local);
+    if (rb == 4) xgrad_go<4>(grid, waves, s, a);
+    else if (rb == 2) xgrad_go<2>(grid, waves, s, a);
+    else xgrad_go<1>(grid, waves, s, a);
     return hot_detail::note_hip(hipGetLastError());
 }
 

@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(hot):
 
 
 def test_host_only_entry_points(hot):
-    assert hot.hot_version() == 202
+    assert hot.hot_version() == 203
     assert hot.hot_strerror(0) == "success"
     assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
     assert hot.hot_strerror(-99) == "unknown error code"
@@ -70,6 +70,7 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_stats_local(None, 1, 1, 1, None, None, None) == hot.HOT_EINVAL
     assert L.hot_stats_merge(None, None, None, 1, 1, 1, 0, None, None, None) == hot.HOT_EINVAL
     assert L.hot_linear_forward_rng(None, None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_linear_backward_rng(None, 1, 1.0, 0, *([None] * 13)) == hot.HOT_EINVAL
     assert L.hot_adam_step(None, 1, None, None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_forward_dropout_rng(None, None, 0.5, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward_dropout_rng(None, None, 0.5, None, None, None) == hot.HOT_EINVAL

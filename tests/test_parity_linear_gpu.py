@@ -185,3 +185,174 @@ def test_rejects_what_it_cannot_run(hot):
         hot.hot_linear_forward_rng(rng, x, mu, mu.clone(), torch.zeros(3, device=DEV), None, y)
     with pytest.raises(TypeError):
         hot.hot_linear_forward_rng(rng, x, mu, mu.clone(), None, None, y.double())
+
+
+# (rows, in, out, samples, per-sample x, bias, dx)
+BACKWARD = [(1, 4, 1, 1, False, True, True), (16, 64, 16, 2, False, True, True), (17, 36, 33, 3, True, True, True),
+            (33, 100, 70, 5, False, False, True), (64, 128, 24, 4, True, True, True), (64, 96, 128, 16, False, True, False),
+            (70, 68, 40, 2, True, True, True), (8, 540, 2160, 2, False, True, True), (130, 192, 48, 3, True, False, True),
+            (5, 2160, 540, 2, True, True, True)]
+
+
+@pytest.mark.parametrize("rows,k,o,s,xs,bias,want_dx", BACKWARD)
+def test_fused_layer_backward_matches_oracle(oracle, hot, rows, k, o, s, xs, bias, want_dx):
+    """Weight, bias and input gradients of the fused layer against the fp64 oracle, each within 1e-5
+    of the sum of the magnitudes of its addends (eps taken at its Box-Muller radius, which also
+    covers the 2e-6 r error of the fp32 draw)."""
+    print("case linear backward", rows, k, o, s, xs, bias, want_dx, flush=True)
+    c = _layer(rows * 17 + k + o, rows, k, o)
+    g = np.random.default_rng(rows + 3 * s)
+    if xs:
+        c["x"] = g.normal(size=(s, rows, k)).astype(np.float32)
+    dy = (g.normal(size=(s, rows, o)) * 10 ** g.uniform(-2, 1, size=(s, 1, o))).astype(np.float32)
+    rng = hot.hot_rng(seed=77, step=5, first_sample=2)
+    w_off, b_off = 32, 32 + ((o * k + 3) // 4) * 4 + 4
+    s_total, dsize = 4 * s, 500.0
+    t = {n: torch.from_numpy(c[n]).to(DEV) for n in ("x", "mu_w", "sigma_w", "mu_b", "sigma_b")}
+    out = {"gmw": torch.full((o, k), float("nan"), device=DEV), "gsw": torch.full((o, k), float("nan"), device=DEV),
+           "gmb": torch.full((o,), float("nan"), device=DEV), "gsb": torch.full((o,), float("nan"), device=DEV),
+           "dx": torch.full((s, rows, k), float("nan"), device=DEV)}
+    hot.hot_linear_backward_rng(rng, t["x"], torch.from_numpy(dy).to(DEV), t["mu_w"], t["sigma_w"],
+                                t["mu_b"] if bias else None, t["sigma_b"] if bias else None, out["gmw"], out["gsw"],
+                                out["gmb"] if bias else None, out["gsb"] if bias else None, out["dx"] if want_dx else None,
+                                s_total, dsize, hot.HOT_REDUCE_SUM, w_off, b_off)
+    torch.cuda.synchronize()
+    got = {n: v.cpu().numpy().astype(np.float64) for n, v in out.items()}
+
+    ew, rw = oracle.eps_normal(o * k, s, rng.seed, rng.step, rng.first_sample, with_radius=True, col0=w_off)
+    ew, rw = ew.reshape(s, o, k), rw.reshape(s, o, k)
+    eb, rb = oracle.eps_normal(o, s, rng.seed, rng.step, rng.first_sample, with_radius=True, col0=b_off)
+    gg, kk = 1.0 / s_total, s / (s_total * dsize)
+    want = oracle.linear_backward(c["x"], dy, c["mu_w"], c["sigma_w"], ew, c["mu_b"] if bias else None,
+                                  c["sigma_b"] if bias else None, eb if bias else None, g=gg, k=kk, want_dx=want_dx)
+    ax, ady = np.abs(c["x"].astype(np.float64)), np.abs(dy.astype(np.float64))
+    Gabs = np.einsum("sro,srk->sok" if xs else "sro,rk->sok", ady, ax)                       # [S, O, K]
+    m64, s64 = np.abs(c["mu_w"].astype(np.float64)), c["sigma_w"].astype(np.float64)
+    checks = [("gmw", want[0], gg * Gabs.sum(0) + kk * m64), ("gsw", want[1], gg * (Gabs * rw).sum(0) + kk * (s64 + 1 / s64))]
+    if bias:
+        Gb = ady.sum(1)
+        mb, sb = np.abs(c["mu_b"].astype(np.float64)), c["sigma_b"].astype(np.float64)
+        checks += [("gmb", want[2], gg * Gb.sum(0) + kk * mb), ("gsb", want[3], gg * (Gb * rb).sum(0) + kk * (sb + 1 / sb))]
+    else:
+        assert np.isnan(got["gmb"]).all() and np.isnan(got["gsb"]).all()
+    if want_dx:
+        checks.append(("dx", want[4], np.einsum("sro,sok->srk", ady, m64[None] + s64[None] * rw)))
+    else:
+        assert np.isnan(got["dx"]).all()
+    for name, w64, A in checks:
+        err = np.abs(got[name] - w64)
+        assert np.all(np.isfinite(got[name])), name
+        assert np.all(err <= 1e-5 * A), f"{name}: worst {np.max(err / A):.3e} of the magnitude sum"
+        print("  %s worst error / magnitude sum: %.2e" % (name, np.max(err / A)), flush=True)
+
+
+def test_fused_backward_equals_flat_backward_on_materialised_gradients(hot):
+    """The layer's weight gradients against hot_backward_rng fed with G_s = dy_s^T x (fp64 einsum,
+    rounded to fp32) on the flat parameter vector that holds the layer at its offsets: the same
+    draws, the same scaling, the same KL part."""
+    rows, k, o, s = 24, 64, 40, 3
+    c = _layer(5, rows, k, o)
+    g = np.random.default_rng(6)
+    dy = g.normal(size=(s, rows, o)).astype(np.float32)
+    w_off = 128
+    n = w_off + o * k
+    rng = hot.hot_rng(seed=4242, step=9, first_sample=0)
+    mu = torch.zeros(n, device=DEV)
+    sigma = torch.ones(n, device=DEV)
+    mu[w_off:] = torch.from_numpy(c["mu_w"]).flatten().to(DEV)
+    sigma[w_off:] = torch.from_numpy(c["sigma_w"]).flatten().to(DEV)
+    G = np.zeros((s, n), np.float32)
+    G[:, w_off:] = np.einsum("sro,rk->sok", dy.astype(np.float64), c["x"].astype(np.float64)).reshape(s, -1)
+    plan = hot.hot_create(n, n, s, 2 * s, 300.0, 0)
+    gmu, gsig = torch.empty(n, device=DEV), torch.empty(n, device=DEV)
+    hot.hot_backward_rng(plan, rng, mu, sigma, torch.from_numpy(G).to(DEV), gmu, gsig)
+    hot.hot_destroy(plan)
+    gmw, gsw = torch.empty(o, k, device=DEV), torch.empty(o, k, device=DEV)
+    hot.hot_linear_backward_rng(rng, torch.from_numpy(c["x"]).to(DEV), torch.from_numpy(dy).to(DEV),
+                                torch.from_numpy(c["mu_w"]).to(DEV), torch.from_numpy(c["sigma_w"]).to(DEV), None, None,
+                                gmw, gsw, None, None, None, 2 * s, 300.0, hot.HOT_REDUCE_SUM, w_off, 0)
+    torch.cuda.synchronize()
+    A = np.abs(G[:, w_off:]).sum(0).reshape(o, k) / (2 * s) + 1e-3
+    assert np.all(np.abs(gmw.cpu().numpy() - gmu[w_off:].cpu().numpy().reshape(o, k)) <= 1e-5 * A)
+    assert np.all(np.abs(gsw.cpu().numpy() - gsig[w_off:].cpu().numpy().reshape(o, k)) <= 6e-5 * A)
+
+
+def test_backward_rejects_what_it_cannot_run(hot):
+    x = torch.zeros(4, 8, device=DEV)
+    w = torch.ones(3, 8, device=DEV)
+    dy = torch.zeros(2, 4, 3, device=DEV)
+    b = torch.ones(3, device=DEV)
+    rng = hot.hot_rng(seed=1, step=0, first_sample=0)
+    with pytest.raises(ValueError):
+        hot.hot_linear_backward_rng(rng, x, dy, w, w.clone(), b, b.clone(), w.clone(), w.clone(), None, None, None, 2, 1.0)
+    with pytest.raises(hot.HotError):
+        hot.hot_linear_backward_rng(rng, x, dy, w, w.clone(), None, None, w.clone(), w.clone(), None, None, None, 1, 1.0)   # S < S_loc
+    with pytest.raises(hot.HotError):
+        hot.hot_linear_backward_rng(rng, x, dy, w, w.clone(), None, None, w.clone(), w.clone(), None, None, None, 2, 0.0)   # |D| = 0
+    with pytest.raises(TypeError):
+        hot.hot_linear_backward_rng(rng, x, dy[:, :3], w, w.clone(), None, None, w.clone(), w.clone(), None, None, None, 2, 1.0)
+
+
+def test_autograd_two_layer_mlp_on_the_fused_layers(hot):
+    """BayesianLinear under torch.autograd: gradients of a two-layer tanh MLP (layer 1 on the shared
+    minibatch, layer 2 on per-sample activations) against fp64 autograd on the CPU with the very
+    same eps (taken from hot_sample_eps over the flat parameter range), KL/|D| included; then a few
+    Adam steps lower the loss."""
+    from paper_2604_04736_amd.autograd import BayesianLinear
+    torch.manual_seed(3)
+    d_in, d_h, d_out, batch, s, dsize = 8, 32, 4, 64, 4, 2000.0
+    l1 = BayesianLinear(d_in, d_h, s, dsize, seed=11)
+    l2 = BayesianLinear(d_h, d_out, s, dsize, seed=11, weight_offset=l1.next_offset)
+    n = l2.next_offset
+    xb = torch.randn(batch, d_in, device=DEV)
+    yb = torch.sin(xb[:, :d_out] * 2.0)
+    p = {"w1": (torch.randn(d_h, d_in, device=DEV) * 0.3), "b1": torch.zeros(d_h, device=DEV),
+         "w2": (torch.randn(d_out, d_h, device=DEV) * 0.2), "b2": torch.zeros(d_out, device=DEV)}
+    mu = {k: v.clone().requires_grad_(True) for k, v in p.items()}
+    sg = {k: torch.full_like(v, 0.05).requires_grad_(True) for k, v in p.items()}
+
+    def loss_of(step):
+        h = torch.tanh(l1.forward(xb, mu["w1"], sg["w1"], mu["b1"], sg["b1"], step))
+        y = l2.forward(h, mu["w2"], sg["w2"], mu["b2"], sg["b2"], step)
+        return ((y - yb[None]) ** 2).mean(dim=(1, 2)).sum() / s
+
+    loss = loss_of(0)
+    loss.backward()
+
+    plan = hot.hot_create(n, n, s, s, dsize, 0)
+    eps = torch.empty(s, n, device=DEV)
+    hot.hot_sample_eps(plan, hot.hot_rng(seed=11, step=0, first_sample=0), eps)
+    hot.hot_destroy(plan)
+    e = eps.double().cpu()
+    off = {"w1": (l1.weight_offset, (d_h, d_in)), "b1": (l1.bias_offset, (d_h,)),
+           "w2": (l2.weight_offset, (d_out, d_h)), "b2": (l2.bias_offset, (d_out,))}
+    m64 = {k: v.detach().double().cpu().requires_grad_(True) for k, v in mu.items()}
+    s64 = {k: v.detach().double().cpu().requires_grad_(True) for k, v in sg.items()}
+    x64, y64 = xb.double().cpu(), yb.double().cpu()
+    ref = 0.0
+    for i in range(s):
+        w = {k: m64[k] + s64[k] * e[i, o:o + int(np.prod(shape))].view(shape) for k, (o, shape) in off.items()}
+        out = torch.tanh(x64 @ w["w1"].T + w["b1"]) @ w["w2"].T + w["b2"]
+        ref = ref + ((out - y64) ** 2).mean() / s
+    kl = sum(0.5 * (s64[k] ** 2 + m64[k] ** 2 - 1 - 2 * torch.log(s64[k])).sum() for k in m64)
+    (ref + kl / dsize).backward()
+    assert abs(loss.item() - ref.item()) <= 1e-5 * abs(ref.item())
+    for k in mu:
+        for got, want in ((mu[k].grad, m64[k].grad), (sg[k].grad, s64[k].grad)):
+            scale = want.abs().max().item()
+            assert (got.double().cpu() - want).abs().max().item() <= 1e-4 * scale, k
+
+    names = list(mu)
+    state = {k: [torch.zeros_like(mu[k]).view(-1) for _ in range(4)] for k in names}
+    first = last = None
+    for t in range(1, 41):
+        for k in names:
+            mu[k].grad = sg[k].grad = None
+        loss = loss_of(t)
+        loss.backward()
+        for k in names:
+            hot.hot_adam_step(hot.hot_adam(2e-2, 0.9, 0.999, 1e-8, 1.0, 1e-4, t), mu[k].data.view(-1), sg[k].data.view(-1),
+                              mu[k].grad.view(-1), sg[k].grad.view(-1), *state[k])
+        first = loss.item() if first is None else first
+        last = loss.item()
+    assert last < 0.5 * first, (first, last)

@@ -356,3 +356,26 @@ def test_autograd_two_layer_mlp_on_the_fused_layers(hot):
         first = loss.item() if first is None else first
         last = loss.item()
     assert last < 0.5 * first, (first, last)
+
+
+@pytest.mark.parametrize("flag_name", ["HOT_REDUCE_SUM", "HOT_REDUCE_MEAN", "HOT_REDUCE_NONE"])
+def test_backward_scaling_conventions(oracle, hot, flag_name):
+    """g and the KL weight under the three conventions: 1/S and S_loc/(S |D|); 1/S_loc and 1/|D|; 1 and 1/|D|."""
+    rows, k, o, s, s_total, dsize = 12, 32, 20, 3, 12, 50.0
+    c = _layer(77, rows, k, o)
+    g = np.random.default_rng(78)
+    dy = g.normal(size=(s, rows, o)).astype(np.float32)
+    rng = hot.hot_rng(seed=8, step=1, first_sample=0)
+    gg, kk = {"HOT_REDUCE_SUM": (1 / s_total, s / (s_total * dsize)), "HOT_REDUCE_MEAN": (1 / s, 1 / dsize),
+              "HOT_REDUCE_NONE": (1.0, 1 / dsize)}[flag_name]
+    t = {n: torch.from_numpy(c[n]).to(DEV) for n in ("x", "mu_w", "sigma_w", "mu_b", "sigma_b")}
+    out = [torch.empty(o, k, device=DEV), torch.empty(o, k, device=DEV), torch.empty(o, device=DEV), torch.empty(o, device=DEV)]
+    hot.hot_linear_backward_rng(rng, t["x"], torch.from_numpy(dy).to(DEV), t["mu_w"], t["sigma_w"], t["mu_b"], t["sigma_b"],
+                                *out, None, s_total, dsize, getattr(hot, flag_name), 0, o * k)
+    torch.cuda.synchronize()
+    ew = oracle.eps_normal(o * k, s, 8, 1, 0).reshape(s, o, k)
+    eb = oracle.eps_normal(o, s, 8, 1, 0, col0=o * k)
+    want = oracle.linear_backward(c["x"], dy, c["mu_w"], c["sigma_w"], ew, c["mu_b"], c["sigma_b"], eb, g=gg, k=kk, want_dx=False)
+    for got, w64 in zip(out, want[:4]):
+        scale = np.abs(w64).max()
+        assert np.abs(got.cpu().numpy() - w64).max() <= 2e-5 * scale

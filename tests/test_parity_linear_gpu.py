@@ -191,7 +191,7 @@ def test_rejects_what_it_cannot_run(hot):
 BACKWARD = [(1, 4, 1, 1, False, True, True), (16, 64, 16, 2, False, True, True), (17, 36, 33, 3, True, True, True),
             (33, 100, 70, 5, False, False, True), (64, 128, 24, 4, True, True, True), (64, 96, 128, 16, False, True, False),
             (70, 68, 40, 2, True, True, True), (8, 540, 2160, 2, False, True, True), (130, 192, 48, 3, True, False, True),
-            (5, 2160, 540, 2, True, True, True)]
+            (5, 2160, 540, 2, True, True, True), (1030, 64, 32, 4, False, True, True), (300, 260, 20, 16, True, True, True)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias,want_dx", BACKWARD)

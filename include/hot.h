@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 203 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 204 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
@@ -111,6 +111,14 @@ int hot_create(hot_plan **out, const hot_desc *desc);
  */
 int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float *eps,
                 float *w, double *kl_out, void *stream);
+
+/*
+ * The prior-matching term of Algorithm 2 on its own: kl_out = 1/2 sum_i (sigma_i^2 + mu_i^2 - 1 -
+ * ln sigma_i^2), for callers that never materialise w (the fused linear layer) but report the loss.
+ * Same kernel, launch geometry and summation order as hot_forward's KL part (the value is bitwise
+ * the one hot_forward returns); reads 8 bytes per weight.  kl_out: DEVICE, one double, required.
+ */
+int hot_kl(hot_plan *plan, const float *mu, const float *sigma, double *kl_out, void *stream);
 
 /*
  * Algorithm 2, loss / gradient / averaging lines, local share of this GPU.  With

@@ -105,6 +105,18 @@ class BayesianLinear:
         self.bias_offset = weight_offset + in_features * out_features        # a multiple of 4 as well
         self.next_offset = (self.bias_offset + (out_features if bias else 0) + 3) // 4 * 4
 
+    def kl(self, mu_w, sigma_w, mu_b=None, sigma_b=None) -> torch.Tensor:
+        """The layer's KL term (one float64 on the device, detached; its gradient is added by backward)."""
+        if not hasattr(self, "_kl_plans"):
+            dev = mu_w.device.index or 0
+            sizes = [self.in_features * self.out_features] + ([self.out_features] if self.bias else [])
+            self._kl_plans = [hot.hot_create(n, n, 1, 1, self.dataset_size, dev) for n in sizes]
+        out = torch.zeros(len(self._kl_plans), dtype=torch.float64, device=mu_w.device)
+        hot.hot_kl(self._kl_plans[0], mu_w.detach().reshape(-1), sigma_w.detach().reshape(-1), out[0:1])
+        if self.bias:
+            hot.hot_kl(self._kl_plans[1], mu_b.detach(), sigma_b.detach(), out[1:2])
+        return out.sum()
+
     def forward(self, x, mu_w, sigma_w, mu_b, sigma_b, step: int):
         if self.bias == (mu_b is None):
             raise ValueError("bias arrays do not match the layer's bias setting")

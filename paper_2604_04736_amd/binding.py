@@ -26,7 +26,7 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
            "hot_stats_merge", "hot_linear_forward_rng", "hot_adam_step", "hot_forward_dropout_rng",
            "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam",
-           "hot_linear_backward_rng")
+           "hot_linear_backward_rng", "hot_kl")
 
 
 class hot_desc(ctypes.Structure):
@@ -79,6 +79,7 @@ def lib() -> ctypes.CDLL:
     L.hot_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(hot_desc)]
     L.hot_forward.argtypes = [vp, fp, fp, fp, fp, vp, vp]
     L.hot_backward.argtypes = [vp, fp, fp, fp, fp, fp, fp, vp]
+    L.hot_kl.argtypes = [vp, fp, fp, vp, vp]
     L.hot_destroy.argtypes = [vp]
     rp = ctypes.POINTER(hot_rng)
     L.hot_forward_rng.argtypes = [vp, rp, fp, fp, fp, vp, vp]
@@ -498,3 +499,11 @@ def hot_linear_backward_rng(rng: hot_rng, x, dy, mu_w, sigma_w, mu_b, sigma_b, g
                                              ptr(grad_sigma_b), ptr(dx), _stream(x.device.index))
     if code != HOT_OK:
         raise HotError(code, "hot_linear_backward_rng", lib().hot_last_hip_error(None))
+
+
+def hot_kl(plan: Plan, mu, sigma, kl_out) -> None:
+    """kl_out (one float64 on the device) = the KL term of (mu, sigma), without forming w."""
+    d = plan.desc
+    code = lib().hot_kl(plan.handle, _vec(mu, d.n_weights, d.device, "mu"), _vec(sigma, d.n_weights, d.device, "sigma"),
+                        _kl_ptr(plan, kl_out), _stream(d.device))
+    _check(code, "hot_kl", plan)

@@ -721,21 +721,24 @@ unsigned grid_for(long n, const hot_launch &c)
     return (unsigned)(tiles < c.grid_blocks ? tiles : c.grid_blocks);
 }
 
+// kl_only: the prior-matching term alone.  The forward kernel runs over zero samples, so it touches
+// neither eps nor w (both may be NULL) and only its KL part is left.
 int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
-                 const float *eps, float *w, double *kl_out, void *stream)
+                 const float *eps, float *w, double *kl_out, void *stream, bool kl_only = false)
 {
-    const bool gen = rng != nullptr;
-    if (!mu || !sigma || !w || (!gen && !eps)) return HOT_EINVAL;
-    if (!aligned4(mu) || !aligned4(sigma) || !aligned4(w) || (!gen && !aligned4(eps))) return HOT_EINVAL;
+    const bool gen = rng != nullptr || kl_only;      // kl_only: no eps array to look at
+    if (!mu || !sigma || (!kl_only && !w) || (!gen && !eps) || (kl_only && !kl_out)) return HOT_EINVAL;
+    if (!aligned4(mu) || !aligned4(sigma) || (!kl_only && !aligned4(w)) || (!gen && !aligned4(eps))) return HOT_EINVAL;
     if (kl_out && (reinterpret_cast<uintptr_t>(kl_out) & 7u)) return HOT_EINVAL;
     const hot_desc &d = plan->d;
     const hot_launch &c = plan->cfg[kernel];
-    const bool al = aligned16(mu) && aligned16(sigma) && aligned16(w) && (gen || aligned16(eps)) && (d.ld % 4 == 0);
+    const bool al = aligned16(mu) && aligned16(sigma) && (kl_only || aligned16(w)) && (gen || aligned16(eps)) &&
+                    (kl_only || d.ld % 4 == 0);
 
     FwdArgs a;
     a.n = d.n_weights;
     a.ld = d.ld;
-    a.s_loc = d.s_local;
+    a.s_loc = kl_only ? 0 : d.s_local;
     a.mu = mu;
     a.sigma = sigma;
     a.eps = eps;
@@ -743,7 +746,7 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     a.partials = plan->partials;
     a.want_kl = kl_out != nullptr;
     a.kl_out = kl_out;
-    a.rng = gen ? *rng : Rng{0, 0, 0, 0};
+    a.rng = rng ? *rng : Rng{0, 0, 0, 0};
     a.grid = dim3(grid_for(d.n_weights, c));
     a.stream = static_cast<hipStream_t>(stream);
     const bool self_finish = a.want_kl && a.grid.x <= (unsigned)kTicketGrid;
@@ -964,6 +967,12 @@ int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float
 {
     if (!plan) return HOT_EINVAL;
     return forward_impl(plan, HOT_KERNEL_FORWARD, nullptr, mu, sigma, eps, w, kl_out, stream);
+}
+
+int hot_kl(hot_plan *plan, const float *mu, const float *sigma, double *kl_out, void *stream)
+{
+    if (!plan) return HOT_EINVAL;
+    return forward_impl(plan, HOT_KERNEL_FORWARD, nullptr, mu, sigma, nullptr, nullptr, kl_out, stream, true);
 }
 
 int hot_backward(hot_plan *plan, const float *mu, const float *sigma, const float *eps,

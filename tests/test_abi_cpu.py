@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(hot):
 
 
 def test_host_only_entry_points(hot):
-    assert hot.hot_version() == 203
+    assert hot.hot_version() == 204
     assert hot.hot_strerror(0) == "success"
     assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
     assert hot.hot_strerror(-99) == "unknown error code"
@@ -62,6 +62,7 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_destroy(None) == hot.HOT_OK
     assert L.hot_forward(None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward(None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_kl(None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_set_launch(None, 0, None) == hot.HOT_EINVAL
     assert L.hot_get_launch(None, 0, None) == hot.HOT_EINVAL
     assert L.hot_last_hip_error(None) == 0

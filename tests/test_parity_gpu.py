@@ -187,6 +187,27 @@ def test_kl_on_either_side_of_the_small_grid_boundary(oracle, hot, n, launch):
     assert all(k == kls[0] for k in kls), kls
 
 
+@pytest.mark.parametrize("n,offset", [(1, 0), (5, 1), (4097, 0), (262_144, 0), (300_001, 3), (5_000_003, 0)])
+def test_kl_alone_equals_the_forward_call(oracle, hot, n, offset):
+    """hot_kl against the oracle and, bit for bit, against the KL that hot_forward returns."""
+    print("case kl alone", n, offset, flush=True)
+    x = _random_case(n, n, 2, seed=n % 997)
+    if offset:
+        buf = {k: torch.empty(v.numel() + offset, device=DEV) for k, v in x.items()}
+        for k in x:
+            buf[k][offset:].view(x[k].shape).copy_(x[k])
+        x = {k: buf[k][offset:].view(x[k].shape) for k in x}
+    plan = hot.hot_create(n, n, 2, 2, 10.0, 0)
+    kl_f = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+    kl_a = torch.full((1,), -2.0, dtype=torch.float64, device=DEV)
+    hot.hot_forward(plan, x["mu"], x["sigma"], x["eps"], torch.empty_like(x["eps"]), kl_f)
+    hot.hot_kl(plan, x["mu"], x["sigma"], kl_a)
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+    assert kl_a.item() == kl_f.item()
+    P.check_kl(oracle, P.host(x), kl_a.item())
+
+
 def test_ieee_propagation_for_sigma_outside_the_domain(oracle, hot):
     n, s = 2051, 2
     x = _random_case(n, n, s, seed=11)

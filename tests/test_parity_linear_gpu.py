@@ -337,6 +337,8 @@ def test_autograd_two_layer_mlp_on_the_fused_layers(hot):
     kl = sum(0.5 * (s64[k] ** 2 + m64[k] ** 2 - 1 - 2 * torch.log(s64[k])).sum() for k in m64)
     (ref + kl / dsize).backward()
     assert abs(loss.item() - ref.item()) <= 1e-5 * abs(ref.item())
+    kl_gpu = l1.kl(mu["w1"], sg["w1"], mu["b1"], sg["b1"]) + l2.kl(mu["w2"], sg["w2"], mu["b2"], sg["b2"])
+    assert abs(kl_gpu.item() - kl.item()) <= 1e-7 * abs(kl.item())
     for k in mu:
         for got, want in ((mu[k].grad, m64[k].grad), (sg[k].grad, s64[k].grad)):
             scale = want.abs().max().item()

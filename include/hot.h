@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 204 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 205 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
@@ -294,6 +294,20 @@ int hot_forward_dropout_rng(const hot_desc *desc, const hot_rng *rng, double kee
                             void *stream);
 int hot_backward_dropout_rng(const hot_desc *desc, const hot_rng *rng, double keep, const float *grad_w,
                              float *grad_mu, void *stream);
+
+/*
+ * The same layer with one Bernoulli variable per NEURON and sample instead of one per weight
+ * (the same section: dropout "sets a subset of neurons to zero"): mu is the [out, in_features]
+ * row-major weight matrix of a layer (desc->n_weights = out * in_features), and dropping input
+ * unit k of sample s zeroes column k, i.e. all weights i with i mod in_features == k.  The mask
+ * bit of unit k is (generator word of flat index unit_offset + k < floor(keep * 2^32)), so
+ * layers of one network use disjoint unit_offset ranges.  in_features >= 4 and unit_offset are
+ * multiples of 4.  Everything else as above.
+ */
+int hot_forward_dropout_units_rng(const hot_desc *desc, const hot_rng *rng, double keep, int64_t in_features,
+                                  int64_t unit_offset, const float *mu, float *w, void *stream);
+int hot_backward_dropout_units_rng(const hot_desc *desc, const hot_rng *rng, double keep, int64_t in_features,
+                                   int64_t unit_offset, const float *grad_w, float *grad_mu, void *stream);
 
 /*
  * Predictive statistics over the samples (the paper's training description and its Monte

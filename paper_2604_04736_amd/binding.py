@@ -26,7 +26,8 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_sample_eps", "hot_sample_bits", "hot_probe_streams", "hot_stats_local",
            "hot_stats_merge", "hot_linear_forward_rng", "hot_adam_step", "hot_forward_dropout_rng",
            "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam",
-           "hot_linear_backward_rng", "hot_kl")
+           "hot_linear_backward_rng", "hot_kl", "hot_forward_dropout_units_rng",
+           "hot_backward_dropout_units_rng")
 
 
 class hot_desc(ctypes.Structure):
@@ -111,6 +112,10 @@ def lib() -> ctypes.CDLL:
     L.hot_forward_dropout_rng.restype = ctypes.c_int
     L.hot_backward_dropout_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, fp, fp, vp]
     L.hot_backward_dropout_rng.restype = ctypes.c_int
+    L.hot_forward_dropout_units_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, ctypes.c_int64, ctypes.c_int64,
+                                                fp, fp, vp]
+    L.hot_backward_dropout_units_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, ctypes.c_int64,
+                                                 ctypes.c_int64, fp, fp, vp]
     L.hot_stats_local.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     L.hot_stats_local.restype = ctypes.c_int
     L.hot_stats_merge.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_int64,
@@ -507,3 +512,27 @@ def hot_kl(plan: Plan, mu, sigma, kl_out) -> None:
     code = lib().hot_kl(plan.handle, _vec(mu, d.n_weights, d.device, "mu"), _vec(sigma, d.n_weights, d.device, "sigma"),
                         _kl_ptr(plan, kl_out), _stream(d.device))
     _check(code, "hot_kl", plan)
+
+
+def hot_forward_dropout_units_rng(plan: Plan, rng: hot_rng, keep: float, in_features: int, unit_offset: int, mu, w) -> None:
+    """w[s,i] = mu[i] * mask[s, i mod in_features] / keep: one Bernoulli variable per input unit and sample."""
+    d = plan.desc
+    with torch.cuda.device(d.device):
+        code = lib().hot_forward_dropout_units_rng(ctypes.byref(d), ctypes.byref(rng), float(keep), int(in_features),
+                                                   int(unit_offset), _vec(mu, d.n_weights, d.device, "mu"),
+                                                   _mat(w, d.s_local, d.n_weights, d.ld, d.device, "w"), _stream(d.device))
+    if code != HOT_OK:
+        raise HotError(code, "hot_forward_dropout_units_rng")
+
+
+def hot_backward_dropout_units_rng(plan: Plan, rng: hot_rng, keep: float, in_features: int, unit_offset: int, grad_w,
+                                   grad_mu) -> None:
+    """grad_mu[i] = g * sum_s grad_w[s,i] * mask[s, i mod in_features] / keep."""
+    d = plan.desc
+    with torch.cuda.device(d.device):
+        code = lib().hot_backward_dropout_units_rng(ctypes.byref(d), ctypes.byref(rng), float(keep), int(in_features),
+                                                    int(unit_offset),
+                                                    _mat(grad_w, d.s_local, d.n_weights, d.ld, d.device, "grad_w"),
+                                                    _vec(grad_mu, d.n_weights, d.device, "grad_mu"), _stream(d.device))
+    if code != HOT_OK:
+        raise HotError(code, "hot_backward_dropout_units_rng")

@@ -90,25 +90,34 @@ __device__ __forceinline__ f4 mask_quad(long quad, int s, const Rng &rng, unsign
     return b;
 }
 
+// Which generator quad masks the weights 4 chunk .. 4 chunk + 3: their own (one Bernoulli variable per
+// weight), or, with period = K > 0, that of the input units (4 chunk) mod K .. of a [*, K] weight
+// matrix (one variable per unit and sample, shared by the unit's weights to all outputs).
+__device__ __forceinline__ long mask_quad_index(long chunk, long period, long unit_quad0)
+{
+    return period > 0 ? unit_quad0 + (((chunk * 4) % period) >> 2) : chunk;
+}
+
 __device__ __forceinline__ float pick(f4 v, int j) { return j == 0 ? v[0] : (j == 1 ? v[1] : (j == 2 ? v[2] : v[3])); }
 
 template <bool ALIGNED, bool NT>
 __global__ void __launch_bounds__(kBlock)
 hot_dropout_forward_kernel(long n, long ld, int s_loc, const float *__restrict__ mu, float *__restrict__ w,
-                           Rng rng, unsigned threshold, float inv_keep)
+                           Rng rng, unsigned threshold, float inv_keep, long period, long unit_quad0)
 {
     const long n_chunks = (n + 3) / 4;
     for (long chunk = (long)blockIdx.x * kBlock + threadIdx.x; chunk < n_chunks; chunk += (long)gridDim.x * kBlock) {
         const long col = chunk * 4;
+        const long mq = mask_quad_index(chunk, period, unit_quad0);
         if (col + 4 <= n) {
             const f4 m = load4<ALIGNED, false>(mu + col);
             for (int s = 0; s < s_loc; ++s) {
-                const f4 b = mask_quad(chunk, s, rng, threshold, inv_keep);
+                const f4 b = mask_quad(mq, s, rng, threshold, inv_keep);
                 store4<ALIGNED, NT>(w + (size_t)s * (size_t)ld + col, m * b);
             }
         } else {
             for (int s = 0; s < s_loc; ++s) {
-                const f4 b = mask_quad(chunk, s, rng, threshold, inv_keep);
+                const f4 b = mask_quad(mq, s, rng, threshold, inv_keep);
                 for (long i = col; i < n; ++i) w[(size_t)s * (size_t)ld + (size_t)i] = mu[i] * pick(b, (int)(i - col));
             }
         }
@@ -118,19 +127,21 @@ hot_dropout_forward_kernel(long n, long ld, int s_loc, const float *__restrict__
 template <bool ALIGNED, bool NT>
 __global__ void __launch_bounds__(kBlock)
 hot_dropout_backward_kernel(long n, long ld, int s_loc, double g, const float *__restrict__ gw,
-                            float *__restrict__ gmu, Rng rng, unsigned threshold, float inv_keep)
+                            float *__restrict__ gmu, Rng rng, unsigned threshold, float inv_keep, long period,
+                            long unit_quad0)
 {
     const long n_chunks = (n + 3) / 4;
     for (long chunk = (long)blockIdx.x * kBlock + threadIdx.x; chunk < n_chunks; chunk += (long)gridDim.x * kBlock) {
         const long col = chunk * 4;
+        const long mq = mask_quad_index(chunk, period, unit_quad0);
         if (col + 4 <= n) {
             double acc[4] = {0.0, 0.0, 0.0, 0.0};
             int s = 0;
             for (; s + 2 <= s_loc; s += 2) {
                 const f4 v0 = load4<ALIGNED, NT>(gw + (size_t)s * (size_t)ld + col);
                 const f4 v1 = load4<ALIGNED, NT>(gw + (size_t)(s + 1) * (size_t)ld + col);
-                const f4 b0 = mask_quad(chunk, s, rng, threshold, inv_keep);
-                const f4 b1 = mask_quad(chunk, s + 1, rng, threshold, inv_keep);
+                const f4 b0 = mask_quad(mq, s, rng, threshold, inv_keep);
+                const f4 b1 = mask_quad(mq, s + 1, rng, threshold, inv_keep);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     acc[j] = fma((double)v0[j], (double)b0[j], acc[j]);
@@ -139,7 +150,7 @@ hot_dropout_backward_kernel(long n, long ld, int s_loc, double g, const float *_
             }
             for (; s < s_loc; ++s) {
                 const f4 v0 = load4<ALIGNED, NT>(gw + (size_t)s * (size_t)ld + col);
-                const f4 b0 = mask_quad(chunk, s, rng, threshold, inv_keep);
+                const f4 b0 = mask_quad(mq, s, rng, threshold, inv_keep);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) acc[j] = fma((double)v0[j], (double)b0[j], acc[j]);
             }
@@ -150,7 +161,7 @@ hot_dropout_backward_kernel(long n, long ld, int s_loc, double g, const float *_
         } else {
             double acc[3] = {0.0, 0.0, 0.0};
             for (int s = 0; s < s_loc; ++s) {
-                const f4 b = mask_quad(chunk, s, rng, threshold, inv_keep);
+                const f4 b = mask_quad(mq, s, rng, threshold, inv_keep);
 #pragma unroll
                 for (int j = 0; j < 3; ++j)
                     if (col + j < n) acc[j] = fma((double)gw[(size_t)s * (size_t)ld + (size_t)(col + j)], (double)pick(b, j), acc[j]);
@@ -200,9 +211,11 @@ int hot_adam_step(const hot_adam *p, int64_t n, float *mu, float *sigma, const f
     return hot_detail::note_hip(hipGetLastError());
 }
 
-int hot_forward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep, const float *mu, float *w, void *stream)
+static int dropout_forward_impl(const hot_desc *d, const hot_rng *rng, double keep, long period, long unit_offset,
+                                const float *mu, float *w, void *stream)
 {
     if (!d || !mu || !w || !aligned4(mu) || !aligned4(w)) return HOT_EINVAL;
+    if (period < 0 || (period & 3) || unit_offset < 0 || (unit_offset & 3)) return HOT_EINVAL;
     if (d->n_weights < 1 || d->ld < d->n_weights || d->s_local < 1 || d->s_total < d->s_local) return HOT_EINVAL;
     if (!(keep > 0.0 && keep <= 1.0)) return HOT_EINVAL;
     Rng r;
@@ -213,16 +226,17 @@ int hot_forward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep, 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned thr = dropout_threshold(keep);
     const float inv = (float)(1.0 / keep);
-    if (al && nt) hot_dropout_forward_kernel<true, true><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv);
-    else if (al) hot_dropout_forward_kernel<true, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv);
-    else hot_dropout_forward_kernel<false, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv);
+    if (al && nt) hot_dropout_forward_kernel<true, true><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv, period, unit_offset >> 2);
+    else if (al) hot_dropout_forward_kernel<true, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv, period, unit_offset >> 2);
+    else hot_dropout_forward_kernel<false, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv, period, unit_offset >> 2);
     return hot_detail::note_hip(hipGetLastError());
 }
 
-int hot_backward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep, const float *grad_w, float *grad_mu,
-                             void *stream)
+static int dropout_backward_impl(const hot_desc *d, const hot_rng *rng, double keep, long period, long unit_offset,
+                                 const float *grad_w, float *grad_mu, void *stream)
 {
     if (!d || !grad_w || !grad_mu || !aligned4(grad_w) || !aligned4(grad_mu)) return HOT_EINVAL;
+    if (period < 0 || (period & 3) || unit_offset < 0 || (unit_offset & 3)) return HOT_EINVAL;
     if (d->n_weights < 1 || d->ld < d->n_weights || d->s_local < 1 || d->s_total < d->s_local) return HOT_EINVAL;
     if (d->flags != HOT_REDUCE_SUM && d->flags != HOT_REDUCE_MEAN && d->flags != HOT_REDUCE_NONE) return HOT_EINVAL;
     if (!(keep > 0.0 && keep <= 1.0)) return HOT_EINVAL;
@@ -236,10 +250,35 @@ int hot_backward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned thr = dropout_threshold(keep);
     const float inv = (float)(1.0 / keep);
-    if (al && nt) hot_dropout_backward_kernel<true, true><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv);
-    else if (al) hot_dropout_backward_kernel<true, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv);
-    else hot_dropout_backward_kernel<false, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv);
+    if (al && nt) hot_dropout_backward_kernel<true, true><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv, period, unit_offset >> 2);
+    else if (al) hot_dropout_backward_kernel<true, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv, period, unit_offset >> 2);
+    else hot_dropout_backward_kernel<false, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv, period, unit_offset >> 2);
     return hot_detail::note_hip(hipGetLastError());
+}
+
+int hot_forward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep, const float *mu, float *w, void *stream)
+{
+    return dropout_forward_impl(d, rng, keep, 0, 0, mu, w, stream);
+}
+
+int hot_backward_dropout_rng(const hot_desc *d, const hot_rng *rng, double keep, const float *grad_w, float *grad_mu,
+                             void *stream)
+{
+    return dropout_backward_impl(d, rng, keep, 0, 0, grad_w, grad_mu, stream);
+}
+
+int hot_forward_dropout_units_rng(const hot_desc *d, const hot_rng *rng, double keep, int64_t in_features,
+                                  int64_t unit_offset, const float *mu, float *w, void *stream)
+{
+    if (in_features < 4) return HOT_EINVAL;
+    return dropout_forward_impl(d, rng, keep, in_features, unit_offset, mu, w, stream);
+}
+
+int hot_backward_dropout_units_rng(const hot_desc *d, const hot_rng *rng, double keep, int64_t in_features,
+                                   int64_t unit_offset, const float *grad_w, float *grad_mu, void *stream)
+{
+    if (in_features < 4) return HOT_EINVAL;
+    return dropout_backward_impl(d, rng, keep, in_features, unit_offset, grad_w, grad_mu, stream);
 }
 
 }  // extern "C"

@@ -107,6 +107,42 @@ def test_dropout_layer_matches_oracle(oracle, hot, n, ld, s, offset, keep):
         assert np.array_equal(got[:, :n], np.broadcast_to(mu, (s, n)))
 
 
+@pytest.mark.parametrize("o,k,ld_pad,s,offset,keep,unit_off", [(7, 12, 0, 3, 0, 0.5, 0), (128, 96, 4, 4, 0, 0.8, 64), (33, 100, 0, 5, 1, 0.3, 8),
+                                                             (2160, 540, 0, 2, 0, 0.9, 4096), (1, 4, 0, 1, 0, 1.0, 0)])
+def test_unit_dropout_layer_matches_oracle(oracle, hot, o, k, ld_pad, s, offset, keep, unit_off):
+    """One Bernoulli variable per input unit and sample: the oracle's per-weight functions fed with
+    the unit words spread over the weight matrix (word of weight (o, k) = word of unit k)."""
+    print("case unit dropout", o, k, ld_pad, s, offset, keep, unit_off, flush=True)
+    n, ld = o * k, o * k + ld_pad
+    r = np.random.default_rng(o + k)
+    mu = r.normal(size=n).astype(np.float32)
+    G = np.full((s, ld), np.nan, np.float32)
+    G[:, :n] = r.normal(size=(s, n)) * 2
+    rng = hot.hot_rng(seed=2718, step=3, first_sample=1)
+    plan = hot.hot_create(n, ld, s, 3 * s, 1.0, 0)
+    mu_d, G_d = _dev(mu, offset), _dev(G, offset)
+    w = _dev(np.full((s, ld), 7.0, np.float32), offset)
+    gmu = _dev(np.zeros(n), offset)
+    hot.hot_forward_dropout_units_rng(plan, rng, keep, k, unit_off, mu_d, w)
+    hot.hot_backward_dropout_units_rng(plan, rng, keep, k, unit_off, G_d, gmu)
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+    unit_words = oracle.eps_bits(unit_off + k, s, rng.seed, rng.step, rng.first_sample)[:, unit_off:unit_off + k]   # [S, K]
+    words = np.ascontiguousarray(np.tile(unit_words, (1, o)))                                                      # [S, O*K]
+    w64 = oracle.dropout_forward(mu, words, keep)
+    got = w.cpu().numpy()
+    if ld > n:
+        assert np.all(got[:, n:] == 7.0), "w padding written"
+    assert np.array_equal(got[:, :n] == 0, w64 == 0), "mask differs"
+    assert np.all(np.abs(got[:, :n] - w64) <= 1e-6 * np.abs(mu)[None, :] / keep)
+    # a dropped unit zeroes its whole column, a kept one none of it
+    cols = (got[:, :n].reshape(s, o, k) != 0)
+    assert np.all(cols.all(axis=1) | ~cols.any(axis=1))
+    gm64 = oracle.dropout_backward(G, words, keep, s_total=3 * s, n=n)
+    scale = np.abs(G[:, :n].astype(np.float64)).sum(0) / (3 * s) / keep
+    assert np.all(np.abs(gmu.cpu().numpy() - gm64) <= 1e-6 * scale + 1e-30)
+
+
 def test_update_errors(hot):
     t = torch.zeros(16, device=DEV)
     with pytest.raises(hot.HotError):

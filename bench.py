@@ -300,9 +300,20 @@ def predictive_stats_lines(hot, torch, dev, iters: int = 20):
             ms_l += e[0].elapsed_time(e[1]) / iters
             ms_m += e[1].elapsed_time(e[2]) / iters
         ok = bool(torch.allclose(mo, y.mean(0), rtol=1e-5, atol=1e-6) and torch.allclose(so, y.std(0), rtol=1e-4, atol=1e-6))
-        out[name] = {"local_ms": ms_l, "merge_ms": ms_m, "predictions_per_s": s * m / (ms_l * 1e-3),
+        mo1, so1 = torch.empty_like(mo), torch.empty_like(so)
+        for _ in range(3):
+            hot.hot_stats_whole(y, 1, mo1, so1)
+        e[0].record()
+        for _ in range(iters):
+            hot.hot_stats_whole(y, 1, mo1, so1)
+        e[1].record()
+        torch.cuda.synchronize()
+        ms_w = e[0].elapsed_time(e[1]) / iters
+        ok = ok and bool(torch.equal(mo1, mo) and torch.equal(so1, so))
+        out[name] = {"local_ms": ms_l, "merge_ms": ms_m, "one_pass_ms": ms_w, "one_pass_GBps": (4 * s * m + 8 * m) / ms_w / 1e6,
+                     "predictions_per_s": s * m / (ms_l * 1e-3),
                      "local_GBps": (4 * s * m + 16 * m) / ms_l / 1e6, "agrees_with_torch": ok}
-        del y, mean, m2, mo, so
+        del y, mean, m2, mo, so, mo1, so1
     return out
 
 

@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 205 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 206 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
@@ -335,6 +335,14 @@ int hot_stats_local(const float *yhat, int64_t m, int64_t ld, int32_t s_local, d
  */
 int hot_stats_merge(const double *means, const double *m2s, const int32_t *counts, int32_t parts, int64_t m,
                     int64_t ld, int32_t ddof, float *mean_out, float *std_out, void *stream);
+
+/*
+ * hot_stats_local and hot_stats_merge in one pass for a GPU that holds all S samples (nothing to
+ * merge): yhat[S, ld] -> mean_out[M], std_out[M] (fp32, DEVICE), std = sqrt(M2 / (S - ddof)) with
+ * the same shifted fp64 sums.  Arguments and rules as for the two calls.
+ */
+int hot_stats_whole(const float *yhat, int64_t m, int64_t ld, int32_t s, int32_t ddof, float *mean_out,
+                    float *std_out, void *stream);
 
 /*
  * Measurement aid, not a step of the paper's path: copies `bytes` (a multiple of 16;

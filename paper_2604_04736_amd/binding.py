@@ -27,7 +27,7 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_stats_merge", "hot_linear_forward_rng", "hot_adam_step", "hot_forward_dropout_rng",
            "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam",
            "hot_linear_backward_rng", "hot_kl", "hot_forward_dropout_units_rng",
-           "hot_backward_dropout_units_rng")
+           "hot_backward_dropout_units_rng", "hot_stats_whole")
 
 
 class hot_desc(ctypes.Structure):
@@ -118,6 +118,7 @@ def lib() -> ctypes.CDLL:
                                                  ctypes.c_int64, fp, fp, vp]
     L.hot_stats_local.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     L.hot_stats_local.restype = ctypes.c_int
+    L.hot_stats_whole.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, vp, vp, vp]
     L.hot_stats_merge.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_int64,
                                   ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     L.hot_stats_merge.restype = ctypes.c_int
@@ -535,4 +536,18 @@ def hot_backward_dropout_units_rng(plan: Plan, rng: hot_rng, keep: float, in_fea
                                                     _mat(grad_w, d.s_local, d.n_weights, d.ld, d.device, "grad_w"),
                                                     _vec(grad_mu, d.n_weights, d.device, "grad_mu"), _stream(d.device))
     if code != HOT_OK:
-        raise HotError(code, "hot_backward_dropout_units_rng")
+        raise HotError(code, "hot_backward_dropout_units_rng", "hot_stats_whole")
+
+
+def hot_stats_whole(yhat: torch.Tensor, ddof: int, mean_out: torch.Tensor, std_out: torch.Tensor) -> None:
+    """Mean and standard deviation over the rows of yhat[S, M] in one pass (all samples on this GPU)."""
+    s, m, ld = _dense2(yhat, torch.float32, "yhat")
+    for t, name in ((mean_out, "mean_out"), (std_out, "std_out")):
+        if not (t.is_cuda and t.device == yhat.device and t.dtype == torch.float32 and t.dim() == 1
+                and t.shape[0] == m and t.stride(0) == 1):
+            raise TypeError(f"{name}: need a dense float32 vector of {m} elements on {yhat.device}")
+    with torch.cuda.device(yhat.device):
+        code = lib().hot_stats_whole(yhat.data_ptr(), m, ld, s, int(ddof), mean_out.data_ptr(), std_out.data_ptr(),
+                                     _stream(yhat.device.index))
+    if code != HOT_OK:
+        raise HotError(code, "hot_stats_whole")

@@ -5,7 +5,8 @@
 //
 //   hot_stats_local   this GPU's rows yhat[S_loc, ld] -> per output (mean, M2 = sum of squared
 //                     deviations from that mean), fp64: the two numbers to communicate;
-//   hot_stats_merge   the partials of all GPUs -> mean and standard deviation over all samples.
+//   hot_stats_merge   the partials of all GPUs -> mean and standard deviation over all samples;
+//   hot_stats_whole   both steps in one pass when one GPU holds all samples.
 //
 // Both are streaming column reductions, bound by HBM (4 + 16/S_loc bytes per prediction for
 // the local pass), laid out like the backward kernel: a thread owns four consecutive
@@ -32,10 +33,24 @@ __device__ __forceinline__ void finish_column(double y0, double sd, double sq, d
     m2 = v > 0.0 ? v : 0.0;
 }
 
-template <bool ALIGNED>
+// FINAL = false: the two fp64 partials (mean, M2) per output.  FINAL = true (all samples are on this
+// GPU, nothing to merge): mean and standard deviation sqrt(M2 / divisor) as fp32, in the same pass.
+template <bool FINAL>
+__device__ __forceinline__ void put_column(long i, double mean, double m2, double divisor, void *out_a, void *out_b)
+{
+    if constexpr (FINAL) {
+        static_cast<float *>(out_a)[i] = (float)mean;
+        static_cast<float *>(out_b)[i] = (float)sqrt(m2 / divisor);
+    } else {
+        static_cast<double *>(out_a)[i] = mean;
+        static_cast<double *>(out_b)[i] = m2;
+    }
+}
+
+template <bool ALIGNED, bool FINAL>
 __global__ void __launch_bounds__(kBlock)
-hot_stats_local_kernel(long m, long ld, int s_loc, const float *__restrict__ y, double *__restrict__ mean,
-                       double *__restrict__ m2)
+hot_stats_local_kernel(long m, long ld, int s_loc, double divisor, const float *__restrict__ y, void *__restrict__ mean,
+                       void *__restrict__ m2)
 {
     const long n_chunks = (m + 3) / 4;
     const double n = (double)s_loc;
@@ -71,8 +86,7 @@ hot_stats_local_kernel(long m, long ld, int s_loc, const float *__restrict__ y, 
             for (int j = 0; j < 4; ++j) {
                 double a, b;
                 finish_column((double)first[j], sd[j], sq[j], n, a, b);
-                mean[col + j] = a;
-                m2[col + j] = b;
+                put_column<FINAL>(col + j, a, b, divisor, mean, m2);
             }
         } else {
             for (long i = col; i < m; ++i) {
@@ -85,8 +99,7 @@ hot_stats_local_kernel(long m, long ld, int s_loc, const float *__restrict__ y, 
                 }
                 double a, b;
                 finish_column(y0, sd, sq, n, a, b);
-                mean[i] = a;
-                m2[i] = b;
+                put_column<FINAL>(i, a, b, divisor, mean, m2);
             }
         }
     }
@@ -142,8 +155,23 @@ int hot_stats_local(const float *yhat, int64_t m, int64_t ld, int32_t s_local, d
     const bool al = aligned16(yhat) && (ld % 4 == 0);
     const dim3 grid(blocks_for((m + 3) / 4)), block(kBlock);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (al) hot_stats_local_kernel<true><<<grid, block, 0, s>>>(m, ld, s_local, yhat, mean, m2);
-    else hot_stats_local_kernel<false><<<grid, block, 0, s>>>(m, ld, s_local, yhat, mean, m2);
+    if (al) hot_stats_local_kernel<true, false><<<grid, block, 0, s>>>(m, ld, s_local, 1.0, yhat, mean, m2);
+    else hot_stats_local_kernel<false, false><<<grid, block, 0, s>>>(m, ld, s_local, 1.0, yhat, mean, m2);
+    return hot_detail::note_hip(hipGetLastError());
+}
+
+int hot_stats_whole(const float *yhat, int64_t m, int64_t ld, int32_t s, int32_t ddof, float *mean_out, float *std_out,
+                    void *stream)
+{
+    if (!yhat || !mean_out || !std_out || m < 1 || ld < m || s < 1 || (ddof != 0 && ddof != 1)) return HOT_EINVAL;
+    if (!aligned4(yhat) || !aligned4(mean_out) || !aligned4(std_out)) return HOT_EINVAL;
+    if (ld > (INT64_MAX / 4) / s) return HOT_EINVAL;
+    const bool al = aligned16(yhat) && (ld % 4 == 0);
+    const double divisor = (double)s - (double)ddof;     // 0 for one sample with ddof = 1: std is then NaN, as defined
+    const dim3 grid(blocks_for((m + 3) / 4)), block(kBlock);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (al) hot_stats_local_kernel<true, true><<<grid, block, 0, st>>>(m, ld, s, divisor, yhat, mean_out, std_out);
+    else hot_stats_local_kernel<false, true><<<grid, block, 0, st>>>(m, ld, s, divisor, yhat, mean_out, std_out);
     return hot_detail::note_hip(hipGetLastError());
 }
 

@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(hot):
 
 
 def test_host_only_entry_points(hot):
-    assert hot.hot_version() == 205
+    assert hot.hot_version() == 206
     assert hot.hot_strerror(0) == "success"
     assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
     assert hot.hot_strerror(-99) == "unknown error code"
@@ -69,6 +69,7 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_probe_copy(None, None, 16, 0, None) == hot.HOT_EINVAL
     assert L.hot_probe_streams(None, 16, 1, 1, None) == hot.HOT_EINVAL
     assert L.hot_stats_local(None, 1, 1, 1, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_stats_whole(None, 1, 1, 1, 0, None, None, None) == hot.HOT_EINVAL
     assert L.hot_stats_merge(None, None, None, 1, 1, 1, 0, None, None, None) == hot.HOT_EINVAL
     assert L.hot_linear_forward_rng(None, None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_linear_backward_rng(None, 1, 1.0, 0, *([None] * 13)) == hot.HOT_EINVAL

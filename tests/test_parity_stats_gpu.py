@@ -96,6 +96,33 @@ def test_merged_statistics_match_the_whole(oracle, hot, groups, ddof):
     assert std_out[3].item() == 0.0
 
 
+@pytest.mark.parametrize("s,m,ld,offset", SHAPES)
+@pytest.mark.parametrize("ddof", [0, 1])
+def test_one_pass_statistics_match_the_definition(oracle, hot, s, m, ld, offset, ddof):
+    """hot_stats_whole (all samples on one GPU) against the two-pass definition, and bit for bit
+    against hot_stats_local followed by hot_stats_merge of that single partial."""
+    print("case stats whole", s, m, ld, offset, ddof, flush=True)
+    y = _predictions(s, m, ld, seed=s * 1000 + m)
+    buf = torch.empty(s * ld + offset, device=DEV)
+    yd = buf[offset:].view(s, ld)
+    yd.copy_(torch.from_numpy(y))
+    mean_out = torch.full((m,), float("nan"), device=DEV)
+    std_out = torch.full((m,), float("nan"), device=DEV)
+    hot.hot_stats_whole(yd[:, :m], ddof, mean_out, std_out)
+    mean, m2 = _local(hot, yd, m)
+    mo2, so2 = torch.empty(m, device=DEV), torch.empty(m, device=DEV)
+    hot.hot_stats_merge(mean.view(1, m), m2.view(1, m), [s], ddof, mo2, so2)
+    torch.cuda.synchronize()
+    if s == 1 and ddof == 1:
+        assert torch.isnan(std_out).all()          # 0 / 0: no spread can be estimated from one sample
+        return
+    w_mean, w_std = oracle.stats_whole(y, m, ddof)
+    big = np.abs(y[:, :m]).max(axis=0).astype(np.float64)
+    assert np.all(np.abs(mean_out.cpu().numpy() - w_mean) <= 1e-6 * big)
+    assert np.all(np.abs(std_out.cpu().numpy() - w_std) <= 1e-6 * w_std + 1e-12 * big)
+    assert torch.equal(mean_out, mo2) and torch.equal(std_out, so2)
+
+
 def test_single_gpu_finish_and_full_size_weather_shape(oracle, hot):
     # two samples of a 69 x 121 x 240 forecast: the local batch of the paper's third use case
     s, m = 2, 69 * 121 * 240

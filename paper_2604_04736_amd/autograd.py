@@ -121,3 +121,42 @@ class BayesianLinear:
         if self.bias == (mu_b is None):
             raise ValueError("bias arrays do not match the layer's bias setting")
         return _Linear.apply(x, mu_w, sigma_w, mu_b, sigma_b, self, int(step))
+
+
+class BayesianModule(torch.nn.Module):
+    """Any torch.nn.Module with all of its parameters made mean-field Gaussian: the module's
+    parameters are flattened into one vector, `mu` starts at their current values, `sigma` at
+    sqrt(kappa / fan_in) per parameter tensor (a constant that shrinks with the layer width, as the
+    paper's experiments initialise it), and every forward call draws S_loc weight samples with the
+    library, runs the module once per sample on views of the sampled vector, and returns the stacked
+    outputs [S_loc, ...] with the KL term (detached; its gradient, divided by dataset_size, reaches
+    mu.grad and sigma.grad through the backward kernel)."""
+
+    def __init__(self, module: torch.nn.Module, s_local: int, dataset_size: float, kappa: float = 0.01, seed: int = 0,
+                 first_sample: int = 0):
+        super().__init__()
+        self.module = module
+        params = list(module.named_parameters())
+        if not params:
+            raise ValueError("the module has no parameters")
+        device = params[0][1].device
+        self._slices, at = [], 0
+        for name, p in params:
+            self._slices.append((name, at, at + p.numel(), tuple(p.shape)))
+            at += p.numel()
+        flat = torch.cat([p.detach().reshape(-1).float() for _, p in params])
+        spread = torch.cat([torch.full((p.numel(),), (kappa / (p[0].numel() if p.dim() > 1 else p.numel())) ** 0.5)
+                            for _, p in params]).to(device)
+        self.mu = torch.nn.Parameter(flat.clone())
+        self.sigma = torch.nn.Parameter(spread)
+        for _, p in params:
+            p.requires_grad_(False)             # the module's own tensors are only shape templates from here on
+        self.layer = GaussianSampleLayer(at, s_local, dataset_size, device.index or 0, seed, first_sample)
+
+    def forward(self, *inputs, step: int):
+        w, kl = self.layer.sample(self.mu, self.sigma, step)
+        outs = []
+        for s in range(self.layer.s_local):
+            sampled = {name: w[s, a:b].view(shape) for name, a, b, shape in self._slices}
+            outs.append(torch.func.functional_call(self.module, sampled, inputs))
+        return torch.stack(outs), kl

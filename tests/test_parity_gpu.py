@@ -657,3 +657,52 @@ def test_autograd_wrapper_trains_a_bayesian_mlp(hot):
         last = loss.item()
     assert last < 0.5 * first, (first, last)
     assert sigma.min().item() >= 1e-4 * (1 - 1e-6)
+
+
+def test_any_torch_module_becomes_bayesian(hot):
+    """BayesianModule around an nn.Sequential with LayerNorm: the gradients that reach mu and sigma equal
+    fp64 autograd of (mean data loss + KL/|D|) with the very same eps, and Adam steps lower the loss."""
+    from paper_2604_04736_amd.autograd import BayesianModule
+    torch.manual_seed(4)
+    net = torch.nn.Sequential(torch.nn.Linear(6, 24), torch.nn.LayerNorm(24), torch.nn.Tanh(), torch.nn.Linear(24, 3)).to(DEV)
+    s, dsize = 4, 500.0
+    bnn = BayesianModule(net, s, dsize, seed=21)
+    n = bnn.mu.numel()
+    assert n == sum(p.numel() for p in net.parameters())
+    xb = torch.randn(50, 6, device=DEV)
+    yb = torch.cos(xb[:, :3])
+    out, kl = bnn(xb, step=0)
+    assert out.shape == (s, 50, 3)
+    loss = ((out - yb[None]) ** 2).mean(dim=(1, 2)).mean()
+    loss.backward()
+
+    eps = torch.empty(s, n, device=DEV)
+    hot.hot_sample_eps(bnn.layer.plan, hot.hot_rng(seed=21, step=0, first_sample=0), eps)
+    m64 = bnn.mu.detach().double().cpu().requires_grad_(True)
+    s64 = bnn.sigma.detach().double().cpu().requires_grad_(True)
+    net64 = torch.nn.Sequential(torch.nn.Linear(6, 24), torch.nn.LayerNorm(24), torch.nn.Tanh(), torch.nn.Linear(24, 3)).double()
+    ref = 0.0
+    for i in range(s):
+        w = m64 + s64 * eps[i].double().cpu()
+        sampled = {name: w[a:b].view(shape) for name, a, b, shape in bnn._slices}
+        o = torch.func.functional_call(net64, sampled, (xb.double().cpu(),))
+        ref = ref + ((o - yb.double().cpu()) ** 2).mean() / s
+    kl64 = 0.5 * (s64 ** 2 + m64 ** 2 - 1 - 2 * torch.log(s64)).sum()
+    (ref + kl64 / dsize).backward()
+    assert abs(loss.item() - ref.item()) <= 1e-5 * abs(ref.item())
+    assert abs(kl.item() - kl64.item()) <= 1e-7 * abs(kl64.item())
+    assert (bnn.mu.grad.double().cpu() - m64.grad).abs().max().item() <= 1e-4 * m64.grad.abs().max().item()
+    assert (bnn.sigma.grad.double().cpu() - s64.grad).abs().max().item() <= 1e-4 * s64.grad.abs().max().item()
+
+    state = [torch.zeros(n, device=DEV) for _ in range(4)]
+    first = last = None
+    for t in range(1, 41):
+        bnn.mu.grad = bnn.sigma.grad = None
+        out, kl = bnn(xb, step=t)
+        loss = ((out - yb[None]) ** 2).mean(dim=(1, 2)).mean()
+        loss.backward()
+        hot.hot_adam_step(hot.hot_adam(1e-2, 0.9, 0.999, 1e-8, 1.0, 1e-5, t), bnn.mu.data, bnn.sigma.data, bnn.mu.grad,
+                          bnn.sigma.grad, *state)
+        first = loss.item() if first is None else first
+        last = loss.item()
+    assert last < 0.6 * first, (first, last)

@@ -226,6 +226,36 @@ def alu_roofline_forward_rng(s_local: int, achieved_items_per_s: float):
             "unit": "items/s", "frac": achieved_items_per_s / peak}
 
 
+def framework_step(torch, wl, x, iters: int = 5):
+    """The same step written with stock PyTorch operators on the same GPU (the software the paper's own
+    experiments ran on): w = addcmul(mu, sigma, eps), the KL expression in fp32, and the column reductions of
+    G and G * eps with the KL gradient.  Context for the figures above, not a target."""
+    mu, sigma, eps, G = x["mu"], x["sigma"], x["eps"][:, :wl.n_weights], x["G"][:, :wl.n_weights]
+    g = 1.0 / wl.s_total
+    k = wl.s_local / (wl.s_total * wl.dataset_size)
+
+    def step():
+        w = torch.addcmul(mu, sigma, eps)
+        kl = 0.5 * (sigma * sigma + mu * mu - 1.0 - 2.0 * torch.log(sigma)).sum(dtype=torch.float64)
+        gmu = torch.add(G.sum(0), mu, alpha=k / g).mul_(g)
+        gsig = torch.add((G * eps).sum(0), sigma - 1.0 / sigma, alpha=k / g).mul_(g)
+        return w, kl, gmu, gsig
+
+    for _ in range(2):
+        step()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        out = step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    del out
+    torch.cuda.empty_cache()
+    return {"ms_per_step": ms, "items_per_s": wl.items / (ms * 1e-3),
+            "what": "torch.addcmul + KL expression in fp32 (fp64 sum) + G.sum(0), (G * eps).sum(0) with the KL gradient, eager mode"}
+
+
 def measured_traffic(kernel: str, workload: str):
     """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
     path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
@@ -566,6 +596,11 @@ def main() -> int:
                                  "kernel_vs_mix_ceiling": achieved / m["GBps"],
                                  "what": f"hot_probe_streams_kernel: {mix[0]} read + {mix[1]} write streams of "
                                          f"{4 * wl.n_weights} bytes, the {dominant} kernel's traffic without its arithmetic"}
+
+    if not args.no_others and not gen:
+        fw = framework_step(torch, wl, x)
+        fw["speedup_of_this_library"] = fw["ms_per_step"] / ms_per_step
+        result["framework_reference"] = fw
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(oracle, np, wl, x, args.cpu_weights)

@@ -391,6 +391,22 @@ def update_and_dropout_lines(hot, torch, dev, wl, iters: int = 10):
     out["backward_adam_fused"] = {"ms": ms_one, "GBps": b_one / ms_one / 1e6, "frac_of_hbm_peak": b_one / ms_one / 1e6 / HBM_PEAK_GBS,
                                   "bytes_per_weight": b_one / n, "two_calls_ms": ms_two, "two_calls_bytes_per_weight": b_two / n,
                                   "speedup": ms_two / ms_one, "samples": s}
+    # Algorithm 2 after the all-reduce: hot_adam_step then the next step's hot_forward_rng, against hot_adam_forward
+    plan2 = hot.hot_create(n, ld, s, wl.s_total, wl.dataset_size, dev.index or 0)
+    rng2 = hot.hot_rng(seed=RNG_SEED, step=RNG_STEP + 1, first_sample=0)
+    kl = torch.zeros(1, dtype=torch.float64, device=dev)
+
+    def adam_then_forward():
+        hot.hot_adam_step(still, a[0], a[1], a[2], a[3], *a[4:])
+        hot.hot_forward_rng(plan2, rng2, a[0], a[1], G, kl)          # G's storage serves as w here
+
+    ms_af2 = timeit(adam_then_forward)
+    ms_af1 = timeit(lambda: hot.hot_adam_forward(plan2, rng2, still, a[0], a[1], a[2], a[3], *a[4:], None, G, kl))
+    hot.hot_destroy(plan2)
+    b_af2, b_af1 = 56.0 * n + 4.0 * n * (s + 2), 56.0 * n + 4.0 * n * s
+    out["adam_forward_fused"] = {"ms": ms_af1, "GBps": b_af1 / ms_af1 / 1e6, "frac_of_hbm_peak": b_af1 / ms_af1 / 1e6 / HBM_PEAK_GBS,
+                                 "bytes_per_weight": b_af1 / n, "two_calls_ms": ms_af2, "two_calls_bytes_per_weight": b_af2 / n,
+                                 "speedup": ms_af2 / ms_af1, "samples": s, "eps": "in-kernel"}
     del a, G, eps
     torch.cuda.empty_cache()
     mu = torch.randn(n, device=dev)

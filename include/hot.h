@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 206 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 207 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
@@ -278,6 +278,20 @@ int hot_adam_step(const hot_adam *params, int64_t n, float *mu, float *sigma, co
 int hot_backward_adam(hot_plan *plan, const hot_rng *rng, const hot_adam *params, float *mu, float *sigma,
                       const float *eps, const float *grad_w, float *m_mu, float *v_mu, float *m_sigma,
                       float *v_sigma, void *stream);
+
+/*
+ * The update line of step t and the reparameterisation and prior-matching lines of step t + 1 in
+ * ONE pass (Algorithm 2 once the all-reduced gradients are there; also Algorithm 1):
+ * hot_adam_step followed by hot_forward / hot_forward_rng.  The updated mu, sigma are stored and,
+ * still in registers, sampled from, so they are not read back: 8 bytes per weight and one launch
+ * less than the two calls, bit-identical results (mu, sigma, moments, w, kl_out).  Exactly one of
+ * rng / eps is non-NULL (rng: the draw of the NEW step).  grad_mu, grad_sigma [N]: read; the six
+ * state arrays: read and overwritten; w [S_loc, ld], kl_out: as in hot_forward (kl_out is the KL of
+ * the UPDATED parameters; may be NULL).  Launch geometry: HOT_KERNEL_FORWARD(_RNG).
+ */
+int hot_adam_forward(hot_plan *plan, const hot_rng *rng, const hot_adam *params, float *mu, float *sigma,
+                     const float *grad_mu, const float *grad_sigma, float *m_mu, float *v_mu, float *m_sigma,
+                     float *v_sigma, const float *eps, float *w, double *kl_out, void *stream);
 
 /*
  * Monte Carlo dropout in weight space (section "Monte Carlo Dropout": dropout amounts to

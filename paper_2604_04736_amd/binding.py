@@ -27,7 +27,7 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_stats_merge", "hot_linear_forward_rng", "hot_adam_step", "hot_forward_dropout_rng",
            "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam",
            "hot_linear_backward_rng", "hot_kl", "hot_forward_dropout_units_rng",
-           "hot_backward_dropout_units_rng", "hot_stats_whole")
+           "hot_backward_dropout_units_rng", "hot_stats_whole", "hot_adam_forward")
 
 
 class hot_desc(ctypes.Structure):
@@ -107,6 +107,7 @@ def lib() -> ctypes.CDLL:
     L.hot_adam_step.restype = ctypes.c_int
     L.hot_linear_backward_rng.argtypes = [ctypes.POINTER(hot_linear_desc), ctypes.c_int32, ctypes.c_double, ctypes.c_uint32,
                                           rp] + [fp] * 11 + [vp]
+    L.hot_adam_forward.argtypes = [vp, rp, ctypes.POINTER(hot_adam)] + [fp] * 10 + [vp, vp]
     L.hot_backward_adam.argtypes = [vp, rp, ctypes.POINTER(hot_adam)] + [fp] * 8 + [vp]
     L.hot_forward_dropout_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, fp, fp, vp]
     L.hot_forward_dropout_rng.restype = ctypes.c_int
@@ -536,7 +537,7 @@ def hot_backward_dropout_units_rng(plan: Plan, rng: hot_rng, keep: float, in_fea
                                                     _mat(grad_w, d.s_local, d.n_weights, d.ld, d.device, "grad_w"),
                                                     _vec(grad_mu, d.n_weights, d.device, "grad_mu"), _stream(d.device))
     if code != HOT_OK:
-        raise HotError(code, "hot_backward_dropout_units_rng", "hot_stats_whole")
+        raise HotError(code, "hot_backward_dropout_units_rng", "hot_stats_whole", "hot_adam_forward")
 
 
 def hot_stats_whole(yhat: torch.Tensor, ddof: int, mean_out: torch.Tensor, std_out: torch.Tensor) -> None:
@@ -551,3 +552,18 @@ def hot_stats_whole(yhat: torch.Tensor, ddof: int, mean_out: torch.Tensor, std_o
                                      _stream(yhat.device.index))
     if code != HOT_OK:
         raise HotError(code, "hot_stats_whole")
+
+
+def hot_adam_forward(plan: Plan, rng, params: hot_adam, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma,
+                     eps, w, kl_out=None) -> None:
+    """hot_adam_step and the next step's hot_forward / hot_forward_rng in one pass (see include/hot.h)."""
+    d = plan.desc
+    if (rng is None) == (eps is None):
+        raise ValueError("give exactly one of rng and eps")
+    n, dev = d.n_weights, d.device
+    vecs = [_vec(t, n, dev, name) for t, name in ((mu, "mu"), (sigma, "sigma"), (grad_mu, "grad_mu"), (grad_sigma, "grad_sigma"),
+                                                  (m_mu, "m_mu"), (v_mu, "v_mu"), (m_sigma, "m_sigma"), (v_sigma, "v_sigma"))]
+    code = lib().hot_adam_forward(plan.handle, ctypes.byref(rng) if rng is not None else None, ctypes.byref(params), *vecs,
+                                  _mat(eps, d.s_local, n, d.ld, dev, "eps") if eps is not None else None,
+                                  _mat(w, d.s_local, n, d.ld, dev, "w"), _kl_ptr(plan, kl_out), _stream(dev))
+    _check(code, "hot_adam_forward", plan)

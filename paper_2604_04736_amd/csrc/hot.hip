@@ -154,6 +154,56 @@ struct AdamUpdate {
     }
 };
 
+// What the forward kernel does to the (mu, sigma) of a chunk before it samples from them.
+//
+// NoPrologue: nothing (Algorithm 2's reparameterisation line on the parameters as they are).
+struct NoPrologue {
+    template <bool ALIGNED>
+    __device__ __forceinline__ void quad(long, f4 &, f4 &) const {}
+    __device__ __forceinline__ void one(long, float &, float &) const {}
+};
+
+// AdamPrologue: the update line of the previous step first ("Update mu and sigma using optimizer"),
+// on the all-reduced gradients, with hot_adam_step's arithmetic; the updated parameters are stored
+// and, still in registers, sampled from, so they are not read a second time.
+struct AdamPrologue {
+    float *mu, *sigma;
+    const float *gmu, *gsig;
+    float *m_mu, *v_mu, *m_sig, *v_sig;
+    AdamConst c;
+    template <bool ALIGNED>
+    __device__ __forceinline__ void quad(long col, f4 &m, f4 &sd) const
+    {
+        const f4 g0 = load4<ALIGNED, true>(gmu + col), g1 = load4<ALIGNED, true>(gsig + col);
+        f4 a0 = load4<ALIGNED, true>(m_mu + col), b0 = load4<ALIGNED, true>(v_mu + col);
+        f4 a1 = load4<ALIGNED, true>(m_sig + col), b1 = load4<ALIGNED, true>(v_sig + col);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float t = m[j], a = a0[j], b = b0[j];
+            adam_one(t, a, b, g0[j], c);
+            m[j] = t; a0[j] = a; b0[j] = b;
+            t = sd[j]; a = a1[j]; b = b1[j];
+            adam_one_sigma(t, a, b, g1[j], c);
+            sd[j] = t; a1[j] = a; b1[j] = b;
+        }
+        store4<ALIGNED, true>(mu + col, m);
+        store4<ALIGNED, true>(sigma + col, sd);
+        store4<ALIGNED, true>(m_mu + col, a0);
+        store4<ALIGNED, true>(v_mu + col, b0);
+        store4<ALIGNED, true>(m_sig + col, a1);
+        store4<ALIGNED, true>(v_sig + col, b1);
+    }
+    __device__ __forceinline__ void one(long i, float &m, float &sd) const
+    {
+        float a = m_mu[i], b = v_mu[i];
+        adam_one(m, a, b, gmu[i], c);
+        mu[i] = m; m_mu[i] = a; v_mu[i] = b;
+        a = m_sig[i]; b = v_sig[i];
+        adam_one_sigma(sd, a, b, gsig[i], c);
+        sigma[i] = sd; m_sig[i] = a; v_sig[i] = b;
+    }
+};
+
 // Sum over the workgroup, complete in thread 0.  Fixed tree, hence deterministic.
 __device__ __forceinline__ double block_sum(double v, double *lds)
 {
@@ -198,12 +248,12 @@ __device__ __forceinline__ void forward_rows(int s, long col0, long ld, const f4
         }
 }
 
-template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool KL, bool GEN>
+template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool KL, bool GEN, class PRO>
 __global__ void __launch_bounds__(kBlock)
 hot_forward_kernel(long n, long ld, int s_loc,
-                   const float *__restrict__ mu, const float *__restrict__ sigma,
+                   const float *mu, const float *sigma,
                    const float *__restrict__ eps, float *__restrict__ w,
-                   double *partials, unsigned *ticket, double *__restrict__ kl_out, Rng rng)
+                   double *partials, unsigned *ticket, double *__restrict__ kl_out, PRO pro, Rng rng)
 {
     constexpr long kTile = (long)kBlock * 4 * CHUNKS;   // columns per tile
     constexpr long kStep = (long)kBlock * 4;            // columns between a thread's chunks
@@ -218,6 +268,7 @@ hot_forward_kernel(long n, long ld, int s_loc,
             for (int c = 0; c < CHUNKS; ++c) {
                 m[c] = load4<ALIGNED, false>(mu + col0 + c * kStep);
                 sd[c] = load4<ALIGNED, false>(sigma + col0 + c * kStep);
+                pro.template quad<ALIGNED>(col0 + c * kStep, m[c], sd[c]);
             }
             int s = 0;
             for (; s + UNROLL <= s_loc; s += UNROLL)
@@ -234,8 +285,9 @@ hot_forward_kernel(long n, long ld, int s_loc,
             for (int c = 0; c < CHUNKS; ++c) {
                 const long col = col0 + c * kStep;
                 if (col + 4 <= n) {
-                    const f4 m = load4<ALIGNED, false>(mu + col);
-                    const f4 sd = load4<ALIGNED, false>(sigma + col);
+                    f4 m = load4<ALIGNED, false>(mu + col);
+                    f4 sd = load4<ALIGNED, false>(sigma + col);
+                    pro.template quad<ALIGNED>(col, m, sd);
                     for (int s = 0; s < s_loc; ++s) {
                         const f4 e = eps4<ALIGNED, false, GEN>(eps, ld, s, col, rng);
                         f4 r;
@@ -249,7 +301,8 @@ hot_forward_kernel(long n, long ld, int s_loc,
                     }
                 } else {
                     for (long i = col; i < n; ++i) {
-                        const float m = mu[i], sd = sigma[i];
+                        float m = mu[i], sd = sigma[i];
+                        pro.one(i, m, sd);
                         for (int s = 0; s < s_loc; ++s) {
                             const size_t at = (size_t)s * (size_t)ld + (size_t)i;
                             w[at] = __builtin_fmaf(sd, eps1<GEN>(eps, at, i, s, rng), m);
@@ -564,21 +617,27 @@ struct FwdArgs {
     unsigned *ticket;
     double *kl_out;
     bool want_kl;
+    const AdamPrologue *adam;   // not NULL: update (mu, sigma) first
     Rng rng;
     dim3 grid;
     hipStream_t stream;
 };
 
 // Template dispatch over (chunks, unroll, aligned, non-temporal, [KL]); GEN is fixed by the caller.
+// The updating variant always carries the KL reduction (its partials are simply not finished when
+// the caller wants no KL).
 template <bool GEN, int CH, int U, bool AL, bool NT>
 void fwd_go(const FwdArgs &a)
 {
-    if (a.want_kl)
-        hot_forward_kernel<CH, U, AL, NT, true, GEN><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, a.rng);
+    if (a.adam)
+        hot_forward_kernel<CH, U, AL, NT, true, GEN, AdamPrologue><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, *a.adam, a.rng);
+    else if (a.want_kl)
+        hot_forward_kernel<CH, U, AL, NT, true, GEN, NoPrologue><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, NoPrologue{}, a.rng);
     else
-        hot_forward_kernel<CH, U, AL, NT, false, GEN><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, a.rng);
+        hot_forward_kernel<CH, U, AL, NT, false, GEN, NoPrologue><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, NoPrologue{}, a.rng);
 }
 template <bool GEN, int CH, int U>
 void fwd_flags(bool al, bool nt, const FwdArgs &a)
@@ -724,7 +783,8 @@ unsigned grid_for(long n, const hot_launch &c)
 // kl_only: the prior-matching term alone.  The forward kernel runs over zero samples, so it touches
 // neither eps nor w (both may be NULL) and only its KL part is left.
 int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
-                 const float *eps, float *w, double *kl_out, void *stream, bool kl_only = false)
+                 const float *eps, float *w, double *kl_out, void *stream, bool kl_only = false,
+                 const AdamPrologue *adam = nullptr, bool adam_aligned = true)
 {
     const bool gen = rng != nullptr || kl_only;      // kl_only: no eps array to look at
     if (!mu || !sigma || (!kl_only && !w) || (!gen && !eps) || (kl_only && !kl_out)) return HOT_EINVAL;
@@ -733,7 +793,7 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     const hot_desc &d = plan->d;
     const hot_launch &c = plan->cfg[kernel];
     const bool al = aligned16(mu) && aligned16(sigma) && (kl_only || aligned16(w)) && (gen || aligned16(eps)) &&
-                    (kl_only || d.ld % 4 == 0);
+                    (kl_only || d.ld % 4 == 0) && adam_aligned;
 
     FwdArgs a;
     a.n = d.n_weights;
@@ -746,6 +806,7 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     a.partials = plan->partials;
     a.want_kl = kl_out != nullptr;
     a.kl_out = kl_out;
+    a.adam = adam;
     a.rng = rng ? *rng : Rng{0, 0, 0, 0};
     a.grid = dim3(grid_for(d.n_weights, c));
     a.stream = static_cast<hipStream_t>(stream);
@@ -973,6 +1034,34 @@ int hot_kl(hot_plan *plan, const float *mu, const float *sigma, double *kl_out, 
 {
     if (!plan) return HOT_EINVAL;
     return forward_impl(plan, HOT_KERNEL_FORWARD, nullptr, mu, sigma, nullptr, nullptr, kl_out, stream, true);
+}
+
+int hot_adam_forward(hot_plan *plan, const hot_rng *rng, const hot_adam *params, float *mu, float *sigma,
+                     const float *grad_mu, const float *grad_sigma, float *m_mu, float *v_mu, float *m_sigma,
+                     float *v_sigma, const float *eps, float *w, double *kl_out, void *stream)
+{
+    if (!plan || (rng != nullptr) == (eps != nullptr)) return HOT_EINVAL;      // exactly one source of eps
+    if (!grad_mu || !grad_sigma || !m_mu || !v_mu || !m_sigma || !v_sigma) return HOT_EINVAL;
+    const void *ptrs[6] = {grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma};
+    bool al = true;
+    for (const void *q : ptrs) {
+        if (!aligned4(q)) return HOT_EINVAL;
+        al = al && aligned16(q);
+    }
+    AdamPrologue pro;
+    if (!make_adam_const(params, pro.c)) return HOT_EINVAL;
+    pro.mu = mu;
+    pro.sigma = sigma;
+    pro.gmu = grad_mu;
+    pro.gsig = grad_sigma;
+    pro.m_mu = m_mu;
+    pro.v_mu = v_mu;
+    pro.m_sig = m_sigma;
+    pro.v_sig = v_sigma;
+    Rng r;
+    if (rng && !make_rng(rng, plan->d.s_local, r)) return HOT_EINVAL;
+    return forward_impl(plan, rng ? HOT_KERNEL_FORWARD_RNG : HOT_KERNEL_FORWARD, rng ? &r : nullptr, mu, sigma, eps, w, kl_out,
+                        stream, false, &pro, al);
 }
 
 int hot_backward(hot_plan *plan, const float *mu, const float *sigma, const float *eps,

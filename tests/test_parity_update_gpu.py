@@ -226,6 +226,67 @@ def test_fused_backward_adam(oracle, hot, n, ld, s, offset, gen):
     assert got["sigma"].min() >= smin * (1 - 1e-7)
 
 
+@pytest.mark.parametrize("n,ld,s,offset,gen,want_kl", [(1, 1, 1, 0, False, True), (5, 8, 2, 0, True, True), (100_003, 100_003, 3, 0, False, True),
+                                                       (100_003, 100_004, 4, 1, True, False), (3 * 4096 + 5, 3 * 4096 + 8, 16, 0, True, True),
+                                                       (1_048_579, 1_048_579, 2, 3, False, True), (300_000, 300_000, 2, 0, True, True)])
+def test_fused_adam_forward(oracle, hot, n, ld, s, offset, gen, want_kl):
+    """hot_adam_forward against hot_adam_step followed by hot_forward / hot_forward_rng, bit for bit
+    (parameters, moments, w, KL), and against the oracle: Adam step in fp64, then w and KL from the
+    GPU's updated fp32 parameters."""
+    print("case fused adam+forward", n, ld, s, offset, gen, want_kl, flush=True)
+    r = np.random.default_rng(n * 7 + s)
+    t_step, lr, b1, b2, eps_a, gsc, smin = 4, 3e-3, 0.9, 0.999, 1e-8, 0.5, 0.02
+    st = {"mu": r.normal(size=n), "sigma": r.uniform(0.01, 1.0, size=n), "m_mu": r.normal(size=n) * 0.1,
+          "v_mu": r.uniform(0, 1, size=n) * 0.01, "m_sigma": r.normal(size=n) * 0.1, "v_sigma": r.uniform(0, 1, size=n) * 0.01}
+    st = {k: v.astype(np.float32) for k, v in st.items()}
+    g_mu = (r.normal(size=n) * 10 ** r.uniform(-3, 2, size=n)).astype(np.float32)
+    g_sg = (r.normal(size=n) * 10 ** r.uniform(-3, 2, size=n)).astype(np.float32)
+    eps = np.full((s, ld), np.nan, np.float32)
+    eps[:, :n] = r.normal(size=(s, n))
+    rng = hot.hot_rng(seed=5, step=t_step + 1, first_sample=0)
+    params = hot.hot_adam(lr, b1, b2, eps_a, gsc, smin, t_step)
+    plan = hot.hot_create(n, ld, s, 4 * s, 100.0, 0)
+    gmu_d, gsg_d = _dev(g_mu, offset), _dev(g_sg, offset)
+    eps_d = None if gen else _dev(eps, offset)
+    names = ("mu", "sigma", "m_mu", "v_mu", "m_sigma", "v_sigma")
+
+    two = {k: _dev(st[k], offset) for k in names}
+    w2 = _dev(np.full((s, ld), 7.0, np.float32), offset)
+    kl2 = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+    hot.hot_adam_step(params, two["mu"], two["sigma"], gmu_d, gsg_d, two["m_mu"], two["v_mu"], two["m_sigma"], two["v_sigma"])
+    if gen:
+        hot.hot_forward_rng(plan, rng, two["mu"], two["sigma"], w2, kl2 if want_kl else None)
+    else:
+        hot.hot_forward(plan, two["mu"], two["sigma"], eps_d, w2, kl2 if want_kl else None)
+
+    one = {k: _dev(st[k], offset) for k in names}
+    w1 = _dev(np.full((s, ld), 7.0, np.float32), offset)
+    kl1 = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+    hot.hot_adam_forward(plan, rng if gen else None, params, one["mu"], one["sigma"], gmu_d, gsg_d, one["m_mu"], one["v_mu"],
+                         one["m_sigma"], one["v_sigma"], eps_d, w1, kl1 if want_kl else None)
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+    for k in names:
+        assert torch.equal(one[k], two[k]), f"{k}: fused and two-call results differ"
+    assert torch.equal(w1, w2) and kl1.item() == kl2.item()
+    if ld > n:
+        assert torch.all(w1[:, n:] == 7.0), "w padding written"
+
+    want = oracle.adam_step(st["mu"], st["sigma"], g_mu, g_sg, st["m_mu"], st["v_mu"], st["m_sigma"], st["v_sigma"],
+                            step=t_step, lr=lr, beta1=b1, beta2=b2, eps=eps_a, grad_scale=gsc, sigma_min=smin)
+    got_mu, got_sg = one["mu"].cpu().numpy(), one["sigma"].cpu().numpy()
+    for got, w_th, th0 in ((got_mu, want[0], st["mu"]), (got_sg, want[1], st["sigma"])):
+        assert np.all(np.abs(got - w_th) <= 1e-6 * (np.abs(th0) + np.abs(w_th - th0) + lr))
+    e_used = oracle.eps_normal(n, s, rng.seed, rng.step, rng.first_sample).astype(np.float32) if gen else eps[:, :n]
+    w64 = oracle.reparam(got_mu, got_sg, np.ascontiguousarray(e_used))
+    tol = 1e-5 * np.abs(w64) + (4e-6 * got_sg[None, :].astype(np.float64) * 6.0 if gen else 0.0)
+    assert np.all(np.abs(w1.cpu().numpy()[:, :n] - w64) <= tol)
+    if want_kl:
+        m64, s64 = got_mu.astype(np.float64), got_sg.astype(np.float64)
+        scale = 0.5 * float(np.sum(s64 * s64 + m64 * m64 + 1.0 + np.abs(2.0 * np.log(s64))))
+        assert abs(kl1.item() - oracle.kl(got_mu, got_sg)) <= 1e-5 * scale
+
+
 def test_fused_backward_adam_errors(hot):
     n = 64
     t = [torch.zeros(n, device=DEV) for _ in range(6)]

@@ -381,3 +381,51 @@ def test_backward_scaling_conventions(oracle, hot, flag_name):
     for got, w64 in zip(out, want[:4]):
         scale = np.abs(w64).max()
         assert np.abs(got.cpu().numpy() - w64).max() <= 2e-5 * scale
+
+
+def test_random_layer_shapes_forward_and_backward(oracle, hot):
+    """Seeded random draw of layer shapes (every combination of ragged rows, inputs, outputs, sample
+    counts, shared or per-sample input, with and without bias): forward and backward against the oracle."""
+    rs = np.random.default_rng(424242)
+    for case in range(24):
+        rows = int(rs.choice([rs.integers(1, 17), rs.integers(17, 70), rs.integers(70, 200)]))
+        k = 4 * int(rs.integers(1, 90))
+        o = int(rs.choice([rs.integers(1, 17), rs.integers(17, 150)]))
+        s = int(rs.integers(1, 7))
+        xs, bias = bool(rs.integers(0, 2)), bool(rs.integers(0, 2))
+        print("case random layer", case, rows, k, o, s, xs, bias, flush=True)
+        c = _layer(1000 + case, rows, k, o)
+        if xs:
+            c["x"] = rs.normal(size=(s, rows, k)).astype(np.float32)
+        dy = rs.normal(size=(s, rows, o)).astype(np.float32)
+        rng = hot.hot_rng(seed=int(rs.integers(0, 2 ** 62)), step=int(rs.integers(0, 1000)), first_sample=int(rs.integers(0, 50)))
+        w_off = 4 * int(rs.integers(0, 1000))
+        b_off = w_off + o * k + 4 * int(rs.integers(0, 10))
+        y = _run(hot, c, s, rng, w_off, b_off, bias=bias)
+        _check(oracle, c, y, s, rng, w_off, b_off, bias=bias)
+
+        t = {n: torch.from_numpy(c[n]).to(DEV) for n in ("x", "mu_w", "sigma_w", "mu_b", "sigma_b")}
+        gmw, gsw = torch.empty(o, k, device=DEV), torch.empty(o, k, device=DEV)
+        gmb, gsb = torch.empty(o, device=DEV), torch.empty(o, device=DEV)
+        dx = torch.empty(s, rows, k, device=DEV)
+        hot.hot_linear_backward_rng(rng, t["x"], torch.from_numpy(dy).to(DEV), t["mu_w"], t["sigma_w"],
+                                    t["mu_b"] if bias else None, t["sigma_b"] if bias else None, gmw, gsw,
+                                    gmb if bias else None, gsb if bias else None, dx, 3 * s, 77.0, hot.HOT_REDUCE_SUM, w_off, b_off)
+        torch.cuda.synchronize()
+        ew, rw = oracle.eps_normal(o * k, s, rng.seed, rng.step, rng.first_sample, with_radius=True, col0=w_off)
+        ew, rw = ew.reshape(s, o, k), rw.reshape(s, o, k)
+        eb, rb = oracle.eps_normal(o, s, rng.seed, rng.step, rng.first_sample, with_radius=True, col0=b_off)
+        gg, kk = 1.0 / (3 * s), s / (3 * s * 77.0)
+        want = oracle.linear_backward(c["x"], dy, c["mu_w"], c["sigma_w"], ew, c["mu_b"] if bias else None,
+                                      c["sigma_b"] if bias else None, eb if bias else None, g=gg, k=kk)
+        ax, ady = np.abs(c["x"].astype(np.float64)), np.abs(dy.astype(np.float64))
+        Gabs = np.einsum("sro,srk->sok" if xs else "sro,rk->sok", ady, ax)
+        m64, s64 = np.abs(c["mu_w"].astype(np.float64)), c["sigma_w"].astype(np.float64)
+        checks = [(gmw, want[0], gg * Gabs.sum(0) + kk * m64), (gsw, want[1], gg * (Gabs * rw).sum(0) + kk * (s64 + 1 / s64)),
+                  (dx, want[4], np.einsum("sro,sok->srk", ady, m64[None] + s64[None] * rw))]
+        if bias:
+            Gb = ady.sum(1)
+            mb, sb = np.abs(c["mu_b"].astype(np.float64)), c["sigma_b"].astype(np.float64)
+            checks += [(gmb, want[2], gg * Gb.sum(0) + kk * mb), (gsb, want[3], gg * (Gb * rb).sum(0) + kk * (sb + 1 / sb))]
+        for got, w64, A in checks:
+            assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - w64) <= 1e-5 * A), case

@@ -150,6 +150,12 @@ def _check(code: int, where: str, plan: Optional[Plan] = None):
         raise HotError(code, where, hip)
 
 
+def _check_planless(code: int, where: str):
+    """For the entry points that take no plan: the HIP error is the calling thread's last one."""
+    if code != HOT_OK:
+        raise HotError(code, where, lib().hot_last_hip_error(None) if code == HOT_EHIP else 0)
+
+
 def hot_version() -> int:
     return lib().hot_version()
 
@@ -302,8 +308,7 @@ def hot_probe_copy(dst: torch.Tensor, src: torch.Tensor, nontemporal: int = 0) -
     with torch.cuda.device(src.device):
         code = lib().hot_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(),
                                     nontemporal, _stream(src.device.index))
-    if code != HOT_OK:
-        raise HotError(code, "hot_probe_copy")
+    _check_planless(code, "hot_probe_copy")
 
 
 def hot_probe_streams(arena: torch.Tensor, stream_bytes: int, reads: int, writes: int) -> None:
@@ -313,8 +318,7 @@ def hot_probe_streams(arena: torch.Tensor, stream_bytes: int, reads: int, writes
         raise ValueError("hot_probe_streams: arena too small or not a contiguous device tensor")
     with torch.cuda.device(arena.device):
         code = lib().hot_probe_streams(arena.data_ptr(), stream_bytes, reads, writes, _stream(arena.device.index))
-    if code != HOT_OK:
-        raise HotError(code, "hot_probe_streams")
+    _check_planless(code, "hot_probe_streams")
 
 
 def _dense2(t: torch.Tensor, dtype, name: str):
@@ -333,8 +337,7 @@ def hot_stats_local(yhat: torch.Tensor, mean: torch.Tensor, m2: torch.Tensor) ->
     with torch.cuda.device(yhat.device):
         code = lib().hot_stats_local(yhat.data_ptr(), m, ld, s_loc, mean.data_ptr(), m2.data_ptr(),
                                      _stream(yhat.device.index))
-    if code != HOT_OK:
-        raise HotError(code, "hot_stats_local")
+    _check_planless(code, "hot_stats_local")
 
 
 def hot_stats_merge(means: torch.Tensor, m2s: torch.Tensor, counts, ddof: int, mean_out: torch.Tensor,
@@ -353,8 +356,7 @@ def hot_stats_merge(means: torch.Tensor, m2s: torch.Tensor, counts, ddof: int, m
     with torch.cuda.device(means.device):
         code = lib().hot_stats_merge(means.data_ptr(), m2s.data_ptr(), c, parts, m, ld, int(ddof),
                                      mean_out.data_ptr(), std_out.data_ptr(), _stream(means.device.index))
-    if code != HOT_OK:
-        raise HotError(code, "hot_stats_merge")
+    _check_planless(code, "hot_stats_merge")
 
 
 def hot_linear_forward_rng(rng: hot_rng, x, mu_w, sigma_w, mu_b, sigma_b, y, weight_offset: int = 0,
@@ -394,8 +396,7 @@ def hot_linear_forward_rng(rng: hot_rng, x, mu_w, sigma_w, mu_b, sigma_b, y, wei
                                             sigma_w.data_ptr(), mu_b.data_ptr() if mu_b is not None else None,
                                             sigma_b.data_ptr() if mu_b is not None else None, y.data_ptr(),
                                             _stream(x.device.index))
-    if code != HOT_OK:
-        raise HotError(code, "hot_linear_forward_rng")
+    _check_planless(code, "hot_linear_forward_rng")
 
 
 def hot_adam_step(params: hot_adam, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma) -> None:
@@ -407,8 +408,7 @@ def hot_adam_step(params: hot_adam, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, 
                                                    (m_sigma, "m_sigma"), (v_sigma, "v_sigma"))]
     with torch.cuda.device(mu.device):
         code = lib().hot_adam_step(ctypes.byref(params), n, *ptrs, _stream(dev))
-    if code != HOT_OK:
-        raise HotError(code, "hot_adam_step")
+    _check_planless(code, "hot_adam_step")
 
 
 def hot_forward_dropout_rng(plan: Plan, rng: hot_rng, keep: float, mu, w) -> None:
@@ -418,8 +418,7 @@ def hot_forward_dropout_rng(plan: Plan, rng: hot_rng, keep: float, mu, w) -> Non
         code = lib().hot_forward_dropout_rng(ctypes.byref(d), ctypes.byref(rng), float(keep),
                                              _vec(mu, d.n_weights, d.device, "mu"),
                                              _mat(w, d.s_local, d.n_weights, d.ld, d.device, "w"), _stream(d.device))
-    if code != HOT_OK:
-        raise HotError(code, "hot_forward_dropout_rng")
+    _check_planless(code, "hot_forward_dropout_rng")
 
 
 def hot_backward_dropout_rng(plan: Plan, rng: hot_rng, keep: float, grad_w, grad_mu) -> None:
@@ -429,8 +428,7 @@ def hot_backward_dropout_rng(plan: Plan, rng: hot_rng, keep: float, grad_w, grad
         code = lib().hot_backward_dropout_rng(ctypes.byref(d), ctypes.byref(rng), float(keep),
                                               _mat(grad_w, d.s_local, d.n_weights, d.ld, d.device, "grad_w"),
                                               _vec(grad_mu, d.n_weights, d.device, "grad_mu"), _stream(d.device))
-    if code != HOT_OK:
-        raise HotError(code, "hot_backward_dropout_rng")
+    _check_planless(code, "hot_backward_dropout_rng")
 
 
 def hot_backward_rows(plan: Plan, rng, mu, sigma, eps, grad_w, first_row: int, accumulate: bool, add_kl: bool,
@@ -504,8 +502,7 @@ def hot_linear_backward_rng(rng: hot_rng, x, dy, mu_w, sigma_w, mu_b, sigma_b, g
                                              x.data_ptr(), dy.data_ptr(), mu_w.data_ptr(), sigma_w.data_ptr(), ptr(mu_b),
                                              ptr(sigma_b), grad_mu_w.data_ptr(), grad_sigma_w.data_ptr(), ptr(grad_mu_b),
                                              ptr(grad_sigma_b), ptr(dx), _stream(x.device.index))
-    if code != HOT_OK:
-        raise HotError(code, "hot_linear_backward_rng", lib().hot_last_hip_error(None))
+    _check_planless(code, "hot_linear_backward_rng")
 
 
 def hot_kl(plan: Plan, mu, sigma, kl_out) -> None:
@@ -523,8 +520,7 @@ def hot_forward_dropout_units_rng(plan: Plan, rng: hot_rng, keep: float, in_feat
         code = lib().hot_forward_dropout_units_rng(ctypes.byref(d), ctypes.byref(rng), float(keep), int(in_features),
                                                    int(unit_offset), _vec(mu, d.n_weights, d.device, "mu"),
                                                    _mat(w, d.s_local, d.n_weights, d.ld, d.device, "w"), _stream(d.device))
-    if code != HOT_OK:
-        raise HotError(code, "hot_forward_dropout_units_rng")
+    _check_planless(code, "hot_forward_dropout_units_rng")
 
 
 def hot_backward_dropout_units_rng(plan: Plan, rng: hot_rng, keep: float, in_features: int, unit_offset: int, grad_w,
@@ -536,8 +532,7 @@ def hot_backward_dropout_units_rng(plan: Plan, rng: hot_rng, keep: float, in_fea
                                                     int(unit_offset),
                                                     _mat(grad_w, d.s_local, d.n_weights, d.ld, d.device, "grad_w"),
                                                     _vec(grad_mu, d.n_weights, d.device, "grad_mu"), _stream(d.device))
-    if code != HOT_OK:
-        raise HotError(code, "hot_backward_dropout_units_rng", "hot_stats_whole", "hot_adam_forward")
+    _check_planless(code, "hot_backward_dropout_units_rng")
 
 
 def hot_stats_whole(yhat: torch.Tensor, ddof: int, mean_out: torch.Tensor, std_out: torch.Tensor) -> None:
@@ -550,8 +545,7 @@ def hot_stats_whole(yhat: torch.Tensor, ddof: int, mean_out: torch.Tensor, std_o
     with torch.cuda.device(yhat.device):
         code = lib().hot_stats_whole(yhat.data_ptr(), m, ld, s, int(ddof), mean_out.data_ptr(), std_out.data_ptr(),
                                      _stream(yhat.device.index))
-    if code != HOT_OK:
-        raise HotError(code, "hot_stats_whole")
+    _check_planless(code, "hot_stats_whole")
 
 
 def hot_adam_forward(plan: Plan, rng, params: hot_adam, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma,

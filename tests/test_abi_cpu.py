@@ -96,3 +96,14 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
                 hot.hot_desc(8, 8, 1, 1, 1.0, 0, 3)]:       # unknown flag
         assert L.hot_create(ctypes.byref(out), ctypes.byref(bad)) == hot.HOT_EINVAL
         assert not out.value
+
+
+def test_binding_error_objects(hot):
+    # every failing call surfaces as HotError with the code and the library's message
+    with pytest.raises(hot.HotError) as e:
+        hot._check_planless(hot.HOT_EINVAL, "hot_adam_step")
+    assert e.value.code == hot.HOT_EINVAL and "hot_adam_step" in str(e.value) and "invalid" in str(e.value)
+    hot._check_planless(hot.HOT_OK, "hot_adam_step")
+    with pytest.raises(hot.HotError) as e:
+        hot._check(hot.HOT_ENOMEM, "hot_forward")
+    assert e.value.code == hot.HOT_ENOMEM and "memory" in str(e.value)

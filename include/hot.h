@@ -230,7 +230,8 @@ int hot_linear_forward_rng(const hot_linear_desc *desc, const hot_rng *rng, cons
  * run on the matrix cores in fp32.  grad_mu_w, grad_sigma_w: [out_features, in_features] packed,
  * 16-byte aligned, overwritten; grad_mu_b, grad_sigma_b: [out_features], both NULL exactly when
  * mu_b is; dx: [s_local, rows, in_features] packed, 16-byte aligned, one block per sample also
- * when x is shared (the caller adds them up), or NULL to skip it (a first layer).  Other arguments
+ * when x is shared (the caller adds them up), or NULL to skip it (a first layer); with dx, rows <=
+ * 1 048 560 and s_local <= 65 535 (grid limits; HOT_EINVAL beyond, before anything runs).  Other arguments
  * and rules as for hot_linear_forward_rng.  Intended for the same regime (tens of rows): every
  * weight is drawn once per sample for the weight gradients and once per block of 64 rows for dx.
  */

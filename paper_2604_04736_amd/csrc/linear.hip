@@ -546,6 +546,9 @@ int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double da
     // element offsets into dy and dx must fit: S_loc * R * max(O, K)
     const int64_t widest = d->out_features > d->in_features ? d->out_features : d->in_features;
     if (d->rows > (INT64_MAX / 8) / widest || d->rows * widest > (INT64_MAX / 8) / d->s_local) return HOT_EINVAL;
+    // the grid of the input-gradient kernel is (64-input groups, row blocks, samples): checked here so that
+    // a refused call has launched nothing
+    if (dx && (d->s_local > 65535 || (d->rows + kRowsPerTile - 1) / kRowsPerTile > 65535)) return HOT_EINVAL;
     Rng r;
     if (!make_rng(rng, d->s_local, r)) return HOT_EINVAL;
 
@@ -623,7 +626,6 @@ int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double da
         }
         if (total >= 1024) break;
     }
-    if (k_groups > 0x7fffffffL || gy > 65535 || d->s_local > 65535) return HOT_EINVAL;
     const dim3 grid((unsigned)k_groups, (unsigned)gy, (unsigned)d->s_local);
     if (rb == 4) xgrad_go<4>(grid, waves, s, a);
     else if (rb == 2) xgrad_go<2>(grid, waves, s, a);

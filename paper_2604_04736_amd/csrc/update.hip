@@ -217,6 +217,7 @@ static int dropout_forward_impl(const hot_desc *d, const hot_rng *rng, double ke
     if (!d || !mu || !w || !aligned4(mu) || !aligned4(w)) return HOT_EINVAL;
     if (period < 0 || (period & 3) || unit_offset < 0 || (unit_offset & 3)) return HOT_EINVAL;
     if (d->n_weights < 1 || d->ld < d->n_weights || d->s_local < 1 || d->s_total < d->s_local) return HOT_EINVAL;
+    if (d->ld > (INT64_MAX / 4) / d->s_local) return HOT_EINVAL;      // element offsets must fit in 63 bits
     if (!(keep > 0.0 && keep <= 1.0)) return HOT_EINVAL;
     Rng r;
     if (!make_rng(rng, d->s_local, r)) return HOT_EINVAL;
@@ -238,6 +239,7 @@ static int dropout_backward_impl(const hot_desc *d, const hot_rng *rng, double k
     if (!d || !grad_w || !grad_mu || !aligned4(grad_w) || !aligned4(grad_mu)) return HOT_EINVAL;
     if (period < 0 || (period & 3) || unit_offset < 0 || (unit_offset & 3)) return HOT_EINVAL;
     if (d->n_weights < 1 || d->ld < d->n_weights || d->s_local < 1 || d->s_total < d->s_local) return HOT_EINVAL;
+    if (d->ld > (INT64_MAX / 4) / d->s_local) return HOT_EINVAL;      // element offsets must fit in 63 bits
     if (d->flags != HOT_REDUCE_SUM && d->flags != HOT_REDUCE_MEAN && d->flags != HOT_REDUCE_NONE) return HOT_EINVAL;
     if (!(keep > 0.0 && keep <= 1.0)) return HOT_EINVAL;
     Rng r;

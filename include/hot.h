@@ -68,7 +68,7 @@ typedef struct hot_launch {
     int32_t grid_blocks; /* upper bound on workgroups (each strides over column tiles), <= 65536 */
     int32_t chunks;      /* 16-byte column chunks per thread and tile: 1, 2 or 4 */
     int32_t unroll;      /* sample rows whose loads are issued together: 1, 2 or 4 */
-    int32_t nontemporal; /* 1: the streamed arrays (eps, grad_w in; w out) are accessed with non-temporal hints */
+    int32_t nontemporal; /* 1: every array is accessed with non-temporal hints (default when S_loc*ld*4 bytes >= 256 MiB) */
 } hot_launch;
 
 #define HOT_KERNEL_FORWARD 0

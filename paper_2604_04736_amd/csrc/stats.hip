@@ -47,7 +47,40 @@ __device__ __forceinline__ void put_column(long i, double mean, double m2, doubl
     }
 }
 
-template <bool ALIGNED, bool FINAL>
+// Four finished columns at once: 16-byte stores (the fp32 final results; the fp64 partials as two
+// 16-byte halves each).
+template <bool FINAL>
+__device__ __forceinline__ void put_quad(long col, const double (&mean)[4], const double (&m2)[4], double divisor,
+                                         void *out_a, void *out_b)
+{
+    if constexpr (FINAL) {
+        f4 a, b;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            a[j] = (float)mean[j];
+            b[j] = (float)sqrt(m2[j] / divisor);
+        }
+        store4<false, false>(static_cast<float *>(out_a) + col, a);
+        store4<false, false>(static_cast<float *>(out_b) + col, b);
+    } else {
+        typedef double d2 __attribute__((ext_vector_type(2)));
+        typedef d2 d2u __attribute__((aligned(8)));
+        d2u *pa = reinterpret_cast<d2u *>(static_cast<double *>(out_a) + col);
+        d2u *pb = reinterpret_cast<d2u *>(static_cast<double *>(out_b) + col);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            pa[h] = d2{mean[2 * h], mean[2 * h + 1]};
+            pb[h] = d2{m2[2 * h], m2[2 * h + 1]};
+        }
+    }
+}
+
+// NT (arrays larger than the memory-side cache): the rows are read with the non-temporal hint.  Which
+// of the remaining accesses carry it was measured on MI355X at 16 x 2^24 predictions, the kernel
+// alternating with a copy kernel: the outputs are best stored plainly in both variants (hinted stores
+// cost 5-10 %), the first row is best hinted in the partial-sums variant (0.224 against 0.245 ms) and
+// plain in the one-pass variant (0.199 against 0.212 ms); both then run at 6.0-6.1 TB/s.
+template <bool ALIGNED, bool FINAL, bool NT>
 __global__ void __launch_bounds__(kBlock)
 hot_stats_local_kernel(long m, long ld, int s_loc, double divisor, const float *__restrict__ y, void *__restrict__ mean,
                        void *__restrict__ m2)
@@ -57,13 +90,13 @@ hot_stats_local_kernel(long m, long ld, int s_loc, double divisor, const float *
     for (long chunk = (long)blockIdx.x * kBlock + threadIdx.x; chunk < n_chunks; chunk += (long)gridDim.x * kBlock) {
         const long col = chunk * 4;
         if (col + 4 <= m) {
-            const f4 first = load4<ALIGNED, false>(y + col);
+            const f4 first = load4<ALIGNED, NT && !FINAL>(y + col);
             double sd[4] = {0.0, 0.0, 0.0, 0.0}, sq[4] = {0.0, 0.0, 0.0, 0.0};
             int s = 1;
             for (; s + kRowsInFlight <= s_loc; s += kRowsInFlight) {
                 f4 v[kRowsInFlight];
 #pragma unroll
-                for (int u = 0; u < kRowsInFlight; ++u) v[u] = load4<ALIGNED, true>(y + (size_t)(s + u) * (size_t)ld + col);
+                for (int u = 0; u < kRowsInFlight; ++u) v[u] = load4<ALIGNED, NT>(y + (size_t)(s + u) * (size_t)ld + col);
 #pragma unroll
                 for (int u = 0; u < kRowsInFlight; ++u)
 #pragma unroll
@@ -74,7 +107,7 @@ hot_stats_local_kernel(long m, long ld, int s_loc, double divisor, const float *
                     }
             }
             for (; s < s_loc; ++s) {
-                const f4 v = load4<ALIGNED, true>(y + (size_t)s * (size_t)ld + col);
+                const f4 v = load4<ALIGNED, NT>(y + (size_t)s * (size_t)ld + col);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const double d = (double)v[j] - (double)first[j];
@@ -82,12 +115,10 @@ hot_stats_local_kernel(long m, long ld, int s_loc, double divisor, const float *
                     sq[j] = fma(d, d, sq[j]);
                 }
             }
+            double a[4], b[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                double a, b;
-                finish_column((double)first[j], sd[j], sq[j], n, a, b);
-                put_column<FINAL>(col + j, a, b, divisor, mean, m2);
-            }
+            for (int j = 0; j < 4; ++j) finish_column((double)first[j], sd[j], sq[j], n, a[j], b[j]);
+            put_quad<FINAL>(col, a, b, divisor, mean, m2);
         } else {
             for (long i = col; i < m; ++i) {
                 const double y0 = (double)y[i];
@@ -134,6 +165,10 @@ hot_stats_merge_kernel(long m, long ld, Counts c, const double *__restrict__ mea
     }
 }
 
+// Whether the prediction array is larger than the 256 MiB memory-side cache (then it is streamed with
+// non-temporal hints; a smaller one is left to the caches, where the network has just written it).
+bool exceeds_cache(int rows, long ld) { return (double)rows * (double)ld * 4.0 >= 256.0 * 1048576.0; }
+
 unsigned blocks_for(long work_items)
 {
     long b = (work_items + kBlock - 1) / kBlock;
@@ -153,10 +188,13 @@ int hot_stats_local(const float *yhat, int64_t m, int64_t ld, int32_t s_local, d
         return HOT_EINVAL;
     if (ld > (INT64_MAX / 4) / s_local) return HOT_EINVAL;
     const bool al = aligned16(yhat) && (ld % 4 == 0);
+    const bool nt = exceeds_cache(s_local, ld);
     const dim3 grid(blocks_for((m + 3) / 4)), block(kBlock);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (al) hot_stats_local_kernel<true, false><<<grid, block, 0, s>>>(m, ld, s_local, 1.0, yhat, mean, m2);
-    else hot_stats_local_kernel<false, false><<<grid, block, 0, s>>>(m, ld, s_local, 1.0, yhat, mean, m2);
+    if (al && nt) hot_stats_local_kernel<true, false, true><<<grid, block, 0, s>>>(m, ld, s_local, 1.0, yhat, mean, m2);
+    else if (al) hot_stats_local_kernel<true, false, false><<<grid, block, 0, s>>>(m, ld, s_local, 1.0, yhat, mean, m2);
+    else if (nt) hot_stats_local_kernel<false, false, true><<<grid, block, 0, s>>>(m, ld, s_local, 1.0, yhat, mean, m2);
+    else hot_stats_local_kernel<false, false, false><<<grid, block, 0, s>>>(m, ld, s_local, 1.0, yhat, mean, m2);
     return hot_detail::note_hip(hipGetLastError());
 }
 
@@ -170,8 +208,11 @@ int hot_stats_whole(const float *yhat, int64_t m, int64_t ld, int32_t s, int32_t
     const double divisor = (double)s - (double)ddof;     // 0 for one sample with ddof = 1: std is then NaN, as defined
     const dim3 grid(blocks_for((m + 3) / 4)), block(kBlock);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (al) hot_stats_local_kernel<true, true><<<grid, block, 0, st>>>(m, ld, s, divisor, yhat, mean_out, std_out);
-    else hot_stats_local_kernel<false, true><<<grid, block, 0, st>>>(m, ld, s, divisor, yhat, mean_out, std_out);
+    const bool nt = exceeds_cache(s, ld);
+    if (al && nt) hot_stats_local_kernel<true, true, true><<<grid, block, 0, st>>>(m, ld, s, divisor, yhat, mean_out, std_out);
+    else if (al) hot_stats_local_kernel<true, true, false><<<grid, block, 0, st>>>(m, ld, s, divisor, yhat, mean_out, std_out);
+    else if (nt) hot_stats_local_kernel<false, true, true><<<grid, block, 0, st>>>(m, ld, s, divisor, yhat, mean_out, std_out);
+    else hot_stats_local_kernel<false, true, false><<<grid, block, 0, st>>>(m, ld, s, divisor, yhat, mean_out, std_out);
     return hot_detail::note_hip(hipGetLastError());
 }
 

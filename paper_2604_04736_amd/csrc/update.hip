@@ -110,7 +110,7 @@ hot_dropout_forward_kernel(long n, long ld, int s_loc, const float *__restrict__
         const long col = chunk * 4;
         const long mq = mask_quad_index(chunk, period, unit_quad0);
         if (col + 4 <= n) {
-            const f4 m = load4<ALIGNED, false>(mu + col);
+            const f4 m = load4<ALIGNED, NT>(mu + col);
             for (int s = 0; s < s_loc; ++s) {
                 const f4 b = mask_quad(mq, s, rng, threshold, inv_keep);
                 store4<ALIGNED, NT>(w + (size_t)s * (size_t)ld + col, m * b);
@@ -157,7 +157,7 @@ hot_dropout_backward_kernel(long n, long ld, int s_loc, double g, const float *_
             f4 o;
 #pragma unroll
             for (int j = 0; j < 4; ++j) o[j] = (float)(g * acc[j]);
-            store4<ALIGNED, false>(gmu + col, o);
+            store4<ALIGNED, NT>(gmu + col, o);
         } else {
             double acc[3] = {0.0, 0.0, 0.0};
             for (int s = 0; s < s_loc; ++s) {

@@ -46,7 +46,9 @@ def _local(hot, y_dev, m):
 
 
 SHAPES = [(16, 2560, 2560, 0), (16, 1536, 1536, 0), (2, 69 * 121 * 240, 69 * 121 * 240, 0), (5, 1003, 1003, 0),
-          (5, 1003, 1024, 0), (13, 70_001, 70_001, 1), (1, 7, 7, 0), (3, 1, 1, 0), (33, 4099, 4100, 3), (64, 300, 300, 0)]
+          (5, 1003, 1024, 0), (13, 70_001, 70_001, 1), (1, 7, 7, 0), (3, 1, 1, 0), (33, 4099, 4100, 3), (64, 300, 300, 0),
+          # larger than the 256 MiB memory-side cache: the kernels then read with non-temporal hints
+          (17, 4_000_000, 4_000_000, 0), (16, 4_200_003, 4_200_003, 1)]
 
 
 @pytest.mark.parametrize("s,m,ld,offset", SHAPES)

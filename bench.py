@@ -396,6 +396,30 @@ def update_and_dropout_lines(hot, torch, dev, wl, iters: int = 10):
 
     ms_two = timeit(two_calls)
     ms_one = timeit(lambda: hot.hot_backward_adam(plan1, None, still, a[0], a[1], eps, G, *a[4:]))
+    # Algorithm 1's whole step behind the network's backward pass, eps drawn in the kernels: backward, Adam
+    # and the next step's forward as three calls, as hot_backward_adam + hot_forward_rng, and as one call
+    rng_a, rng_b = hot.hot_rng(seed=RNG_SEED, step=RNG_STEP, first_sample=0), hot.hot_rng(seed=RNG_SEED, step=RNG_STEP + 1, first_sample=0)
+    kl1 = torch.zeros(1, dtype=torch.float64, device=dev)
+    w_next = eps                                    # eps' storage serves as the next step's w here
+
+    def three_calls():
+        hot.hot_backward_rng(plan1, rng_a, a[0], a[1], G, a[2], a[3])
+        hot.hot_adam_step(still, a[0], a[1], a[2], a[3], *a[4:])
+        hot.hot_forward_rng(plan1, rng_b, a[0], a[1], w_next, kl1)
+
+    def pair_calls():
+        hot.hot_backward_adam(plan1, rng_a, still, a[0], a[1], None, G, *a[4:])
+        hot.hot_forward_rng(plan1, rng_b, a[0], a[1], w_next, kl1)
+
+    ms_w3, ms_w2 = timeit(three_calls), timeit(pair_calls)
+    ms_w1 = timeit(lambda: hot.hot_backward_adam_forward(plan1, rng_a, rng_b, still, a[0], a[1], G, *a[4:], w_next, kl1))
+    b_w3, b_w2, b_w1 = 4.0 * n * (s + 4) + 56.0 * n + 4.0 * n * (s + 2), 4.0 * n * (s + 2) + 40.0 * n + 4.0 * n * (s + 2), 4.0 * n * (2 * s + 2) + 40.0 * n
+    out["whole_step_fused"] = {"ms": ms_w1, "GBps": b_w1 / ms_w1 / 1e6, "frac_of_hbm_peak": b_w1 / ms_w1 / 1e6 / HBM_PEAK_GBS,
+                               "bytes_per_weight": b_w1 / n, "two_calls_ms": ms_w2, "two_calls_bytes_per_weight": b_w2 / n,
+                               "three_calls_ms": ms_w3, "three_calls_bytes_per_weight": b_w3 / n,
+                               "speedup_over_two_calls": ms_w2 / ms_w1, "speedup_over_three_calls": ms_w3 / ms_w1,
+                               "samples": s, "eps": "in-kernel",
+                               "what": "hot_backward_adam_forward: backward, Adam and the next step's forward (w + KL) in one pass"}
     hot.hot_destroy(plan1)
     b_two, b_one = 4.0 * n * (2 * s + 4) + 56.0 * n, 4.0 * n * (2 * s + 2) + 40.0 * n
     out["backward_adam_fused"] = {"ms": ms_one, "GBps": b_one / ms_one / 1e6, "frac_of_hbm_peak": b_one / ms_one / 1e6 / HBM_PEAK_GBS,

@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 207 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 208 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
@@ -279,6 +279,23 @@ int hot_adam_step(const hot_adam *params, int64_t n, float *mu, float *sigma, co
 int hot_backward_adam(hot_plan *plan, const hot_rng *rng, const hot_adam *params, float *mu, float *sigma,
                       const float *eps, const float *grad_w, float *m_mu, float *v_mu, float *m_sigma,
                       float *v_sigma, void *stream);
+
+/*
+ * Algorithm 1's whole step behind the network's backward pass in ONE pass: hot_backward_rng, hot_adam_step
+ * and the hot_forward_rng of the NEXT step.  The gradients are formed in registers and consumed by the Adam
+ * update as in hot_backward_adam; the updated mu, sigma are stored and, still in registers, sampled from
+ * with the next step's draw: w[s,i] = fma(sigma[i], eps_next[s,i], mu[i]), and *kl_out (DEVICE, one double,
+ * or NULL) receives the KL term of the UPDATED parameters.  Results are bit-identical to
+ * hot_backward_adam(rng) followed by hot_forward_rng(rng_next) (kl_out: equal up to the order in which the
+ * fp64 per-workgroup partial sums are added, and identical when both kernels run with the same chunks and
+ * grid bound on more than 64 workgroups), at 8 bytes per weight and one launch less.  Requires s_local == s_total.  rng: the draw that produced grad_w; rng_next: the draw of the
+ * next step (normally the same seed with step + 1).  mu, sigma, the four moment arrays [N]: read and
+ * overwritten; grad_w [S, ld]: read; w [S, ld]: written, must not be grad_w.  Layout, alignment, stream and
+ * error rules as for hot_backward; launch geometry: HOT_KERNEL_BACKWARD_RNG.
+ */
+int hot_backward_adam_forward(hot_plan *plan, const hot_rng *rng, const hot_rng *rng_next, const hot_adam *params,
+                              float *mu, float *sigma, const float *grad_w, float *m_mu, float *v_mu, float *m_sigma,
+                              float *v_sigma, float *w, double *kl_out, void *stream);
 
 /*
  * The update line of step t and the reparameterisation and prior-matching lines of step t + 1 in

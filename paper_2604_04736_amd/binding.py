@@ -27,7 +27,7 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_stats_merge", "hot_linear_forward_rng", "hot_adam_step", "hot_forward_dropout_rng",
            "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam",
            "hot_linear_backward_rng", "hot_kl", "hot_forward_dropout_units_rng",
-           "hot_backward_dropout_units_rng", "hot_stats_whole", "hot_adam_forward")
+           "hot_backward_dropout_units_rng", "hot_stats_whole", "hot_adam_forward", "hot_backward_adam_forward")
 
 
 class hot_desc(ctypes.Structure):
@@ -109,6 +109,7 @@ def lib() -> ctypes.CDLL:
                                           rp] + [fp] * 11 + [vp]
     L.hot_adam_forward.argtypes = [vp, rp, ctypes.POINTER(hot_adam)] + [fp] * 10 + [vp, vp]
     L.hot_backward_adam.argtypes = [vp, rp, ctypes.POINTER(hot_adam)] + [fp] * 8 + [vp]
+    L.hot_backward_adam_forward.argtypes = [vp, rp, rp, ctypes.POINTER(hot_adam)] + [fp] * 8 + [vp, vp]
     L.hot_forward_dropout_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, fp, fp, vp]
     L.hot_forward_dropout_rng.restype = ctypes.c_int
     L.hot_backward_dropout_rng.argtypes = [ctypes.POINTER(hot_desc), rp, ctypes.c_double, fp, fp, vp]
@@ -561,3 +562,17 @@ def hot_adam_forward(plan: Plan, rng, params: hot_adam, mu, sigma, grad_mu, grad
                                   _mat(eps, d.s_local, n, d.ld, dev, "eps") if eps is not None else None,
                                   _mat(w, d.s_local, n, d.ld, dev, "w"), _kl_ptr(plan, kl_out), _stream(dev))
     _check(code, "hot_adam_forward", plan)
+
+
+def hot_backward_adam_forward(plan: Plan, rng: hot_rng, rng_next: hot_rng, params: hot_adam, mu, sigma, grad_w, m_mu, v_mu,
+                              m_sigma, v_sigma, w, kl_out=None) -> None:
+    """hot_backward_rng, hot_adam_step and the next step's hot_forward_rng in one pass (see include/hot.h)."""
+    d = plan.desc
+    n, dev = d.n_weights, d.device
+    code = lib().hot_backward_adam_forward(plan.handle, ctypes.byref(rng), ctypes.byref(rng_next), ctypes.byref(params),
+                                           _vec(mu, n, dev, "mu"), _vec(sigma, n, dev, "sigma"),
+                                           _mat(grad_w, d.s_local, n, d.ld, dev, "grad_w"),
+                                           _vec(m_mu, n, dev, "m_mu"), _vec(v_mu, n, dev, "v_mu"),
+                                           _vec(m_sigma, n, dev, "m_sigma"), _vec(v_sigma, n, dev, "v_sigma"),
+                                           _mat(w, d.s_local, n, d.ld, dev, "w"), _kl_ptr(plan, kl_out), _stream(dev))
+    _check(code, "hot_backward_adam_forward", plan)

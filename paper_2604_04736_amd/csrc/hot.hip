@@ -99,8 +99,9 @@ __device__ __forceinline__ void finish_grad(double sum_g, double sum_ge, float m
 struct StoreGrad {
     float *gmu, *gsig;
     int accumulate;
+    static constexpr bool kReduces = false;   // no per-workgroup sum behind the tile loop
     template <bool ALIGNED, bool NT>
-    __device__ __forceinline__ void quad(long col, f4, f4, const double (&gm)[4], const double (&gs)[4]) const
+    __device__ __forceinline__ void quad(long col, f4, f4, const double (&gm)[4], const double (&gs)[4], double &) const
     {
         f4 om = {0.0f, 0.0f, 0.0f, 0.0f}, os = {0.0f, 0.0f, 0.0f, 0.0f};
         if (accumulate) {
@@ -115,7 +116,7 @@ struct StoreGrad {
         store4<ALIGNED, NT>(gmu + col, om);
         store4<ALIGNED, NT>(gsig + col, os);
     }
-    __device__ __forceinline__ void one(long i, float, float, double gm, double gs) const
+    __device__ __forceinline__ void one(long i, float, float, double gm, double gs, double &) const
     {
         gmu[i] = (float)(gm + (double)(accumulate ? gmu[i] : 0.0f));
         gsig[i] = (float)(gs + (double)(accumulate ? gsig[i] : 0.0f));
@@ -128,8 +129,10 @@ struct StoreGrad {
 struct AdamUpdate {
     float *mu, *sigma, *m_mu, *v_mu, *m_sig, *v_sig;
     AdamConst c;
-    template <bool ALIGNED, bool NT>
-    __device__ __forceinline__ void quad(long col, f4 m, f4 sd, const double (&gm)[4], const double (&gs)[4]) const
+    static constexpr bool kReduces = false;
+    // updates m, sd (and the moments in memory) in place and stores them
+    template <bool ALIGNED>
+    __device__ __forceinline__ void update4(long col, f4 &m, f4 &sd, const double (&gm)[4], const double (&gs)[4]) const
     {
         f4 a0 = load4<ALIGNED, true>(m_mu + col), b0 = load4<ALIGNED, true>(v_mu + col);
         f4 a1 = load4<ALIGNED, true>(m_sig + col), b1 = load4<ALIGNED, true>(v_sig + col);
@@ -149,7 +152,7 @@ struct AdamUpdate {
         store4<ALIGNED, true>(m_sig + col, a1);
         store4<ALIGNED, true>(v_sig + col, b1);
     }
-    __device__ __forceinline__ void one(long i, float m, float sd, double gm, double gs) const
+    __device__ __forceinline__ void update1(long i, float &m, float &sd, double gm, double gs) const
     {
         float a = m_mu[i], b = v_mu[i];
         adam_one(m, a, b, (float)gm, c);
@@ -157,6 +160,52 @@ struct AdamUpdate {
         a = m_sig[i]; b = v_sig[i];
         adam_one_sigma(sd, a, b, (float)gs, c);
         sigma[i] = sd; m_sig[i] = a; v_sig[i] = b;
+    }
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void quad(long col, f4 m, f4 sd, const double (&gm)[4], const double (&gs)[4], double &) const
+    {
+        update4<ALIGNED>(col, m, sd, gm, gs);
+    }
+    __device__ __forceinline__ void one(long i, float m, float sd, double gm, double gs, double &) const
+    {
+        update1(i, m, sd, gm, gs);
+    }
+};
+
+// AdamUpdateSample: Algorithm 1's whole step behind the network's backward pass.  After AdamUpdate's
+// update the next step's reparameterisation and prior-matching lines run on the updated mu, sigma
+// while they are still in registers: w[s, :] = mu + sigma * eps_s with eps drawn for the NEXT step, and
+// the KL addends of the updated parameters go into the workgroup's partial sum (as in the forward kernel).
+struct AdamUpdateSample {
+    AdamUpdate adam;
+    float *w;
+    long ld;
+    int s_loc;
+    Rng next;          // the draw of the next step
+    double *partials;  // one KL partial per workgroup, or nullptr when no KL is wanted
+    static constexpr bool kReduces = true;
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void quad(long col, f4 m, f4 sd, const double (&gm)[4], const double (&gs)[4], double &kl) const
+    {
+        adam.template update4<ALIGNED>(col, m, sd, gm, gs);
+        for (int s = 0; s < s_loc; ++s) {
+            const f4 e = eps_quad(col >> 2, s, next);
+            f4 r;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[j], e[j], m[j]);
+            store4<ALIGNED, NT>(w + (size_t)s * (size_t)ld + col, r);
+        }
+        if (partials) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) kl += kl_addend(m[j], sd[j]);
+        }
+    }
+    __device__ __forceinline__ void one(long i, float m, float sd, double gm, double gs, double &kl) const
+    {
+        adam.update1(i, m, sd, gm, gs);
+        for (int s = 0; s < s_loc; ++s)
+            w[(size_t)s * (size_t)ld + (size_t)i] = __builtin_fmaf(sd, eps1<true>(nullptr, 0, i, s, next), m);
+        if (partials) kl += kl_addend(m, sd);
     }
 };
 
@@ -428,6 +477,7 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
     constexpr long kTile = (long)kBlock * 4 * CHUNKS;
     constexpr long kStep = (long)kBlock * 4;
     const long n_tiles = (n + kTile - 1) / kTile;
+    double acc = 0.0;   // what a reducing epilogue sums per thread (the KL addends of AdamUpdateSample)
 
     for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const long col0 = tile * kTile + (long)threadIdx.x * 4;
@@ -453,7 +503,7 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                 double gm[4], gs[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) finish_grad(sum_g[c][j], sum_ge[c][j], m[c][j], sd[c][j], g, k, gm[j], gs[j]);
-                epi.template quad<ALIGNED, NT>(col0 + c * kStep, m[c], sd[c], gm, gs);
+                epi.template quad<ALIGNED, NT>(col0 + c * kStep, m[c], sd[c], gm, gs, acc);
             }
         } else {
             for (int c = 0; c < CHUNKS; ++c) {
@@ -475,7 +525,7 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                     double gm[4], gs[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) finish_grad(sum_g[j], sum_ge[j], m[j], sd[j], g, k, gm[j], gs[j]);
-                    epi.template quad<ALIGNED, false>(col, m, sd, gm, gs);
+                    epi.template quad<ALIGNED, false>(col, m, sd, gm, gs, acc);
                 } else {
                     for (long i = col; i < n; ++i) {
                         double sum_g = 0.0, sum_ge = 0.0;
@@ -488,10 +538,17 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
                         const float m = mu[i], sd = sigma[i];
                         double gm, gs;
                         finish_grad(sum_g, sum_ge, m, sd, g, k, gm, gs);
-                        epi.one(i, m, sd, gm, gs);
+                        epi.one(i, m, sd, gm, gs, acc);
                     }
                 }
             }
+        }
+    }
+    if constexpr (EPI::kReduces) {
+        if (epi.partials) {      // uniform over the grid
+            __shared__ double lds[kWaves];
+            const double mine = block_sum(acc, lds);
+            if (threadIdx.x == 0) epi.partials[blockIdx.x] = mine;
         }
     }
 }
@@ -1134,6 +1191,44 @@ int hot_backward_adam(hot_plan *plan, const hot_rng *rng, const hot_adam *params
     if (rng && !make_rng(rng, plan->d.s_local, r)) return HOT_EINVAL;
     return backward_launch(plan, rng ? HOT_KERNEL_BACKWARD_RNG : HOT_KERNEL_BACKWARD, rng ? &r : nullptr, mu, sigma, eps,
                            grad_w, epi, al, stream, 0, 0, true);
+}
+
+int hot_backward_adam_forward(hot_plan *plan, const hot_rng *rng, const hot_rng *rng_next, const hot_adam *params,
+                              float *mu, float *sigma, const float *grad_w, float *m_mu, float *v_mu, float *m_sigma,
+                              float *v_sigma, float *w, double *kl_out, void *stream)
+{
+    if (!plan || plan->d.s_local != plan->d.s_total) return HOT_EINVAL;   // one GPU holds all samples
+    if (!mu || !sigma || !grad_w || !m_mu || !v_mu || !m_sigma || !v_sigma || !w || w == grad_w) return HOT_EINVAL;
+    if (kl_out && (reinterpret_cast<uintptr_t>(kl_out) & 7u)) return HOT_EINVAL;
+    const void *ptrs[8] = {mu, sigma, grad_w, m_mu, v_mu, m_sigma, v_sigma, w};
+    bool al = true;
+    for (int i = 0; i < 8; ++i) {
+        if (!aligned4(ptrs[i])) return HOT_EINVAL;
+        if (i >= 3) al = al && aligned16(ptrs[i]);
+    }
+    AdamUpdateSample epi;
+    if (!make_adam_const(params, epi.adam.c)) return HOT_EINVAL;
+    Rng r, rn;
+    if (!make_rng(rng, plan->d.s_local, r) || !make_rng(rng_next, plan->d.s_local, rn)) return HOT_EINVAL;
+    epi.adam.mu = mu;
+    epi.adam.sigma = sigma;
+    epi.adam.m_mu = m_mu;
+    epi.adam.v_mu = v_mu;
+    epi.adam.m_sig = m_sigma;
+    epi.adam.v_sig = v_sigma;
+    epi.w = w;
+    epi.ld = plan->d.ld;
+    epi.s_loc = plan->d.s_local;
+    epi.next = rn;
+    epi.partials = kl_out ? plan->partials : nullptr;
+    const int rc = backward_launch(plan, HOT_KERNEL_BACKWARD_RNG, &r, mu, sigma, nullptr, grad_w, epi, al, stream, 0, 0, true);
+    if (rc != HOT_OK || !kl_out) return rc;
+    DeviceGuard guard(plan->d.device);
+    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
+    const unsigned blocks = grid_for(plan->d.n_weights, plan->cfg[HOT_KERNEL_BACKWARD_RNG]);
+    hot_kl_finish_kernel<<<dim3(1), dim3(kFinishBlock), 0, static_cast<hipStream_t>(stream)>>>(plan->partials, (int)blocks, kl_out);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
 }
 
 int hot_sample_eps(hot_plan *plan, const hot_rng *rng, float *eps, void *stream)

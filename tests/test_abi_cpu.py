@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(hot):
 
 
 def test_host_only_entry_points(hot):
-    assert hot.hot_version() == 207
+    assert hot.hot_version() == 208
     assert hot.hot_strerror(0) == "success"
     assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
     assert hot.hot_strerror(-99) == "unknown error code"
@@ -81,6 +81,7 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_backward_rows(None, None, None, None, None, None, 0, 1, 0, 1, None, None, None) == hot.HOT_EINVAL
     assert L.hot_adam_forward(*([None] * 15)) == hot.HOT_EINVAL
     assert L.hot_backward_adam(None, None, None, None, None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_backward_adam_forward(*([None] * 14)) == hot.HOT_EINVAL
     assert L.hot_forward_rng(None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward_rng(None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_sample_eps(None, None, None, None) == hot.HOT_EINVAL

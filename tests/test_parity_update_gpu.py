@@ -289,6 +289,92 @@ def test_fused_adam_forward(oracle, hot, n, ld, s, offset, gen, want_kl):
         assert abs(kl1.item() - oracle.kl(got_mu, got_sg)) <= 1e-5 * scale
 
 
+@pytest.mark.parametrize("n,ld,s,offset,want_kl,launch", [
+    (1, 1, 1, 0, True, {}), (5, 8, 2, 0, True, {}), (100_003, 100_004, 3, 1, True, {}), (3 * 4096 + 5, 3 * 4096 + 8, 16, 0, False, {}),
+    (1_048_579, 1_048_579, 2, 3, True, {}), (300_000, 300_000, 2, 0, True, dict(chunks=1, unroll=1, grid_blocks=7)),
+    (2_000_000, 2_000_000, 5, 0, True, dict(chunks=2, unroll=4, nontemporal=1))])
+def test_fused_backward_adam_forward(oracle, hot, n, ld, s, offset, want_kl, launch):
+    """The whole step of Algorithm 1 behind the network's backward pass, hot_backward_adam_forward, against
+    hot_backward_adam followed by hot_forward_rng with the next step's draw: parameters, moments and w bit
+    for bit; KL bit for bit when both kernels run with one launch shape on more than 64 workgroups (the
+    forward kernel then leaves the sum of the partials to the same finish kernel), else to the rounding of the
+    fp64 sum.  (Each of the two calls is checked against the oracle in its own test; here w and KL are checked
+    against the oracle once more, from the updated parameters.)"""
+    print("case fused backward+adam+forward", n, ld, s, offset, want_kl, launch, flush=True)
+    r = np.random.default_rng(n * 13 + s)
+    D, t, lr, b1, b2, eps_a, gsc, smin = 500.0, 6, 2e-3, 0.9, 0.999, 1e-8, 1.0, 0.02
+    st = {"mu": r.normal(size=n), "sigma": r.uniform(0.01, 1.0, size=n), "m_mu": r.normal(size=n) * 0.1,
+          "v_mu": r.uniform(0, 1, size=n) * 0.01, "m_sigma": r.normal(size=n) * 0.1, "v_sigma": r.uniform(0, 1, size=n) * 0.01}
+    st = {k: v.astype(np.float32) for k, v in st.items()}
+    G = np.full((s, ld), np.nan, np.float32)
+    G[:, :n] = r.normal(size=(s, n)) * 10 ** r.uniform(-3, 2, size=(1, n))
+    rng, rng_next = hot.hot_rng(seed=77, step=t, first_sample=0), hot.hot_rng(seed=77, step=t + 1, first_sample=0)
+    params = hot.hot_adam(lr, b1, b2, eps_a, gsc, smin, t)
+    plan = hot.hot_create(n, ld, s, s, D, 0)
+    same_shape = bool(launch)
+    if launch:
+        for kern in (hot.HOT_KERNEL_BACKWARD_RNG, hot.HOT_KERNEL_FORWARD_RNG):
+            hot.hot_set_launch(plan, kern, **launch)
+    else:
+        fr, br = hot.hot_get_launch(plan, hot.HOT_KERNEL_FORWARD_RNG), hot.hot_get_launch(plan, hot.HOT_KERNEL_BACKWARD_RNG)
+        same_shape = fr["chunks"] == br["chunks"] and fr["grid_blocks"] == br["grid_blocks"]
+    G_d = _dev(G, offset)
+    names = ("mu", "sigma", "m_mu", "v_mu", "m_sigma", "v_sigma")
+
+    two = {k: _dev(st[k], offset) for k in names}
+    w2 = _dev(np.full((s, ld), 7.0, np.float32), offset)
+    kl2 = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+    hot.hot_backward_adam(plan, rng, params, two["mu"], two["sigma"], None, G_d, two["m_mu"], two["v_mu"], two["m_sigma"], two["v_sigma"])
+    hot.hot_forward_rng(plan, rng_next, two["mu"], two["sigma"], w2, kl2 if want_kl else None)
+
+    one = {k: _dev(st[k], offset) for k in names}
+    w1 = _dev(np.full((s, ld), 7.0, np.float32), offset)
+    kl1 = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+    hot.hot_backward_adam_forward(plan, rng, rng_next, params, one["mu"], one["sigma"], G_d, one["m_mu"], one["v_mu"],
+                                  one["m_sigma"], one["v_sigma"], w1, kl1 if want_kl else None)
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+    for k in names:
+        assert torch.equal(one[k], two[k]), f"{k}: fused and two-call results differ"
+    assert torch.equal(w1, w2)
+    if ld > n:
+        assert torch.all(w1[:, n:] == 7.0), "w padding written"
+    got_mu, got_sg = one["mu"].cpu().numpy(), one["sigma"].cpu().numpy()
+    if want_kl:
+        m64, s64 = got_mu.astype(np.float64), got_sg.astype(np.float64)
+        scale = 0.5 * float(np.sum(s64 * s64 + m64 * m64 + 1.0 + np.abs(2.0 * np.log(s64))))
+        grid = min(-(-n // (1024 * (launch.get("chunks", 4) if launch else 4))), launch.get("grid_blocks", 65536) if launch else 65536)
+        if same_shape and grid > 64:        # up to 64 workgroups the forward kernel adds the partials itself, in another order
+            assert kl1.item() == kl2.item()
+        assert abs(kl1.item() - kl2.item()) <= 1e-13 * scale
+        assert abs(kl1.item() - oracle.kl(got_mu, got_sg)) <= 1e-5 * scale
+    else:
+        assert kl1.item() == -1.0
+    e_next = oracle.eps_normal(n, s, rng_next.seed, rng_next.step, rng_next.first_sample).astype(np.float32)
+    w64 = oracle.reparam(got_mu, got_sg, np.ascontiguousarray(e_next))
+    assert np.all(np.abs(w1.cpu().numpy()[:, :n] - w64) <= 1e-5 * np.abs(w64) + 4e-6 * got_sg[None, :].astype(np.float64) * 6.0)
+
+
+def test_fused_backward_adam_forward_errors(hot):
+    n = 64
+    t = [torch.zeros(n, device=DEV) for _ in range(6)]
+    G, w = torch.zeros(2, n, device=DEV), torch.zeros(2, n, device=DEV)
+    params = hot.hot_adam(1e-3, 0.9, 0.999, 1e-8, 1.0, 0.0, 1)
+    rng, nxt = hot.hot_rng(seed=1, step=0, first_sample=0), hot.hot_rng(seed=1, step=1, first_sample=0)
+    shared = hot.hot_create(n, n, 2, 4, 1.0, 0)            # only half of the samples are local
+    with pytest.raises(hot.HotError):
+        hot.hot_backward_adam_forward(shared, rng, nxt, params, t[0], t[1], G, *t[2:], w)
+    hot.hot_destroy(shared)
+    plan = hot.hot_create(n, n, 2, 2, 1.0, 0)
+    with pytest.raises(hot.HotError):
+        hot.hot_backward_adam_forward(plan, rng, nxt, params, t[0], t[1], G, *t[2:], G)      # w must not be grad_w
+    with pytest.raises(hot.HotError):
+        hot.hot_backward_adam_forward(plan, rng, hot.hot_rng(seed=1, step=1, first_sample=2 ** 32 - 1), params, t[0], t[1], G, *t[2:], w)
+    hot.hot_backward_adam_forward(plan, rng, nxt, params, t[0], t[1], G, *t[2:], w)
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+
+
 def test_fused_backward_adam_errors(hot):
     n = 64
     t = [torch.zeros(n, device=DEV) for _ in range(6)]

@@ -355,6 +355,74 @@ def test_fused_backward_adam_forward(oracle, hot, n, ld, s, offset, want_kl, lau
     assert np.all(np.abs(w1.cpu().numpy()[:, :n] - w64) <= 1e-5 * np.abs(w64) + 4e-6 * got_sg[None, :].astype(np.float64) * 6.0)
 
 
+@pytest.mark.parametrize("n,ld,s,offset", [(700_001, 700_004, 3, 0), (700_001, 700_001, 2, 1)])
+def test_fused_calls_with_non_temporal_accesses(hot, n, ld, s, offset):
+    """The three fused calls with the non-temporal variants of their kernels (the default only above
+    256 MiB) against the unfused calls with the same launch shape, bit for bit.  The unfused kernels'
+    non-temporal variants are compared with the oracle in test_parity_gpu.py."""
+    print("case fused calls, non-temporal", n, ld, s, offset, flush=True)
+    r = np.random.default_rng(n + s)
+    st = {"mu": r.normal(size=n), "sigma": r.uniform(0.01, 1.0, size=n), "m_mu": r.normal(size=n) * 0.1,
+          "v_mu": r.uniform(0, 1, size=n) * 0.01, "m_sigma": r.normal(size=n) * 0.1, "v_sigma": r.uniform(0, 1, size=n) * 0.01}
+    st = {k: v.astype(np.float32) for k, v in st.items()}
+    names = ("mu", "sigma", "m_mu", "v_mu", "m_sigma", "v_sigma")
+    G = np.full((s, ld), np.nan, np.float32)
+    G[:, :n] = r.normal(size=(s, n))
+    eps = np.full((s, ld), np.nan, np.float32)
+    eps[:, :n] = r.normal(size=(s, n))
+    G_d, eps_d = _dev(G, offset), _dev(eps, offset)
+    gmu_in, gsg_in = _dev(r.normal(size=n).astype(np.float32), offset), _dev(r.normal(size=n).astype(np.float32), offset)
+    rng, nxt = hot.hot_rng(seed=3, step=8, first_sample=0), hot.hot_rng(seed=3, step=9, first_sample=0)
+    params = hot.hot_adam(1e-3, 0.9, 0.999, 1e-8, 1.0, 0.02, 8)
+    plan = hot.hot_create(n, ld, s, s, 100.0, 0)
+    for kern in range(4):
+        hot.hot_set_launch(plan, kern, chunks=4, unroll=2, nontemporal=1)
+
+    def fresh():
+        return {k: _dev(st[k], offset) for k in names}, _dev(np.full((s, ld), 7.0, np.float32), offset), \
+            torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+
+    def same(a, b):
+        for k in names:
+            assert torch.equal(a[0][k], b[0][k]), k
+        assert torch.equal(a[1], b[1]) and a[2].item() == b[2].item()
+
+    for gen in (False, True):
+        # backward + Adam
+        a, b = fresh(), fresh()
+        gm, gs = _dev(np.zeros(n), offset), _dev(np.zeros(n), offset)
+        if gen:
+            hot.hot_backward_rng(plan, rng, a[0]["mu"], a[0]["sigma"], G_d, gm, gs)
+        else:
+            hot.hot_backward(plan, a[0]["mu"], a[0]["sigma"], eps_d, G_d, gm, gs)
+        hot.hot_adam_step(params, a[0]["mu"], a[0]["sigma"], gm, gs, *[a[0][k] for k in names[2:]])
+        hot.hot_backward_adam(plan, rng if gen else None, params, b[0]["mu"], b[0]["sigma"], None if gen else eps_d, G_d,
+                              *[b[0][k] for k in names[2:]])
+        torch.cuda.synchronize()
+        same(a, b)
+        # Adam + forward
+        a, b = fresh(), fresh()
+        hot.hot_adam_step(params, a[0]["mu"], a[0]["sigma"], gmu_in, gsg_in, *[a[0][k] for k in names[2:]])
+        if gen:
+            hot.hot_forward_rng(plan, nxt, a[0]["mu"], a[0]["sigma"], a[1], a[2])
+        else:
+            hot.hot_forward(plan, a[0]["mu"], a[0]["sigma"], eps_d, a[1], a[2])
+        hot.hot_adam_forward(plan, nxt if gen else None, params, b[0]["mu"], b[0]["sigma"], gmu_in, gsg_in,
+                             *[b[0][k] for k in names[2:]], None if gen else eps_d, b[1], b[2])
+        torch.cuda.synchronize()
+        same(a, b)
+    # backward + Adam + forward
+    a, b = fresh(), fresh()
+    hot.hot_backward_adam(plan, rng, params, a[0]["mu"], a[0]["sigma"], None, G_d, *[a[0][k] for k in names[2:]])
+    hot.hot_forward_rng(plan, nxt, a[0]["mu"], a[0]["sigma"], a[1], a[2])
+    hot.hot_backward_adam_forward(plan, rng, nxt, params, b[0]["mu"], b[0]["sigma"], G_d, *[b[0][k] for k in names[2:]], b[1], b[2])
+    torch.cuda.synchronize()
+    same(a, b)
+    if ld > n:
+        assert torch.all(b[1][:, n:] == 7.0), "w padding written"
+    hot.hot_destroy(plan)
+
+
 def test_fused_backward_adam_forward_errors(hot):
     n = 64
     t = [torch.zeros(n, device=DEV) for _ in range(6)]

@@ -1042,12 +1042,20 @@ int hot_create(hot_plan **out, const hot_desc *desc)
     f.unroll = 1;
     b.unroll = pick_unroll(4, d.s_local);
     f.nontemporal = b.nontemporal = streams_exceed_cache ? 1 : 0;
-    // The drawing variants have no eps loads to keep in flight: forward as above; backward prefers
-    // two chunks and single rows from four samples on.
+    // With fewer than four samples the four-chunk backward kernels are fat (over 200 registers per lane,
+    // two workgroups per compute unit) and short: below 16 M weights their last, partly filled round of
+    // workgroups costs 5-10 %, which one chunk per thread avoids.
+    const bool few_tiles = d.n_weights < (16L << 20);
+    if (d.s_local < 4 && few_tiles) b.chunks = 1;
+    // The drawing variants have no eps loads to keep in flight.  Forward: as above up to seven samples;
+    // from eight on one chunk per thread (38 registers, eight waves per SIMD) hides the generator's
+    // latencies better than four independent chains in five waves (10-20 % at 8 M to 25 M weights).
+    // Backward: two chunks and single rows from four samples on.
     hot_launch &fr = p->cfg[HOT_KERNEL_FORWARD_RNG], &br = p->cfg[HOT_KERNEL_BACKWARD_RNG];
     fr = f;
+    if (d.s_local >= 8) fr.chunks = 1;
     br = b;
-    br.chunks = d.s_local >= 4 ? 2 : 4;
+    br.chunks = d.s_local >= 4 ? 2 : (few_tiles ? 1 : 4);
     br.unroll = pick_unroll(d.s_local >= 4 ? 1 : 2, d.s_local);
     *out = p;
     return HOT_OK;

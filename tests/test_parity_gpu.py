@@ -259,8 +259,18 @@ def test_errors_from_the_c_abi(hot):
     with pytest.raises(TypeError):
         hot.hot_forward(plan, t[:1024].cpu(), t[:1024], t[:2048].view(2, 1024), t[:2048].view(2, 1024))
     cfg = hot.hot_get_launch(plan, hot.HOT_KERNEL_BACKWARD)
-    assert cfg["unroll"] == 2 and cfg["nontemporal"] == 0 and cfg["chunks"] == 4 and cfg["grid_blocks"] > 0
+    # two samples, few weights: one chunk per thread, both rows in flight, ordinary cache hints
+    assert cfg["unroll"] == 2 and cfg["nontemporal"] == 0 and cfg["chunks"] == 1 and cfg["grid_blocks"] > 0
+    assert hot.hot_get_launch(plan, hot.HOT_KERNEL_FORWARD)["chunks"] == 4
     hot.hot_destroy(plan)
+    big = hot.hot_create(1 << 26, 1 << 26, 2, 2, 1.0, 0)      # 512 MiB of samples: four chunks, non-temporal
+    cfg = hot.hot_get_launch(big, hot.HOT_KERNEL_BACKWARD)
+    assert cfg["chunks"] == 4 and cfg["nontemporal"] == 1
+    hot.hot_destroy(big)
+    many = hot.hot_create(1 << 20, 1 << 20, 16, 16, 1.0, 0)
+    assert hot.hot_get_launch(many, hot.HOT_KERNEL_FORWARD_RNG)["chunks"] == 1
+    assert hot.hot_get_launch(many, hot.HOT_KERNEL_BACKWARD)["chunks"] == 4
+    hot.hot_destroy(many)
     hot.hot_destroy(plan)      # second destroy of the wrapper is a no-op
 
 

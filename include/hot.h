@@ -400,9 +400,10 @@ const char *hot_strerror(int code);
 
 /*
  * Smallest pitch >= n_weights that keeps every row 256-byte aligned (multiple of 64 floats).  Any pitch is
- * legal, but rows that do not start on a 64-byte boundary cost 4 % (two samples) to 19 % (sixteen samples)
- * of the forward kernels' speed on MI355X, up to 40 % for hot_forward_rng with a launch override of four
- * chunks, whether or not they are 16-byte aligned.
+ * legal.  What MI355X rewards is rows of w that start on 64-byte boundaries, 16-byte aligned or not:
+ * hot_forward re-aligns its stores row by row and loses at most 5 % on other pitches; hot_forward_rng and
+ * the dropout forward calls do not and lose 4 % (two samples) to 19 % (sixteen samples), up to 40 % for
+ * hot_forward_rng with a launch override of four chunks; the backward calls only read rows and lose 1-5 %.
  */
 int64_t hot_recommended_ld(int64_t n_weights);
 

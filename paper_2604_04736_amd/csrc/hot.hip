@@ -275,6 +275,40 @@ __device__ __forceinline__ double block_sum(double v, double *lds)
     return total;
 }
 
+// What a forward workgroup does with its threads' KL sums: one fp64 partial per workgroup, left for the
+// finish kernel (ticket == nullptr), or, on small grids, added up by the workgroup that arrives last.
+__device__ __forceinline__ void kl_leave(double kl, double *partials, unsigned *ticket, double *kl_out)
+{
+    __shared__ double lds[kWaves];
+    const double mine = block_sum(kl, lds);
+    if (ticket == nullptr) {
+        if (threadIdx.x == 0) partials[blockIdx.x] = mine;
+    } else {
+        // Small grids (at most kTicketGrid workgroups, where a launch costs more than the kernel):
+        // the workgroup that arrives last adds the partials, so no second kernel is needed.  Each
+        // workgroup pays one device-scope release and the tickets are drawn one after the other
+        // (about 56 ns each), which is why large grids use the finish kernel instead.  Nothing waits
+        // on anything: whoever draws the last ticket does the sum, in lane order, hence deterministically.
+        __shared__ int last;
+        if (threadIdx.x == 0) {
+            __hip_atomic_store(&partials[blockIdx.x], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned drawn = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            last = drawn == gridDim.x - 1 ? 1 : 0;
+        }
+        __syncthreads();
+        if (last && threadIdx.x < 64) {
+            double v = 0.0;
+            if (threadIdx.x < gridDim.x)
+                v = __hip_atomic_load(&partials[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v = wave_sum(v);
+            if (threadIdx.x == 0) {
+                *kl_out = 0.5 * v;
+                __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------
 // Forward: reparameterisation line  w[s,i] = mu[i] + sigma[i] * eps[s,i]  for every local
 // sample, fused with the prior-matching line (mu and sigma are in registers anyway).
@@ -369,36 +403,147 @@ hot_forward_kernel(long n, long ld, int s_loc,
         }
     }
 
-    if constexpr (KL) {
-        __shared__ double lds[kWaves];
-        const double mine = block_sum(kl, lds);
-        if (ticket == nullptr) {
-            if (threadIdx.x == 0) partials[blockIdx.x] = mine;
-        } else {
-            // Small grids (at most kTicketGrid workgroups, where a launch costs more than the kernel):
-            // the workgroup that arrives last adds the partials, so no second kernel is needed.  Each
-            // workgroup pays one device-scope release (a write-back of its die's L2), which is why
-            // large grids use the finish kernel instead.  Nothing waits on anything: whoever draws the
-            // last ticket does the sum, in lane order, hence deterministically.
-            __shared__ int last;
-            if (threadIdx.x == 0) {
-                __hip_atomic_store(&partials[blockIdx.x], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const unsigned drawn = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-                last = drawn == gridDim.x - 1 ? 1 : 0;
+    if constexpr (KL) kl_leave(kl, partials, ticket, kl_out);
+}
+
+// ---------------------------------------------------------------------------------
+// Forward for rows of w that do not start on 64-byte boundaries (a pitch that is not a multiple of 16
+// floats, or such a base address).  The memory system takes a wave's 1 KiB store at full speed only when
+// it covers whole 64-byte words; otherwise both ends of every such store are half words, which costs the
+// streaming forward kernel 8-19 % and a store-dominated one up to 40 %.  Here the column window of a
+// workgroup is therefore moved, row by row, by that row's misalignment a (0..15 floats): thread t stores
+// the four columns c0 + 4t - a .. c0 + 4t - a + 3, whose address is 16-byte aligned and, over a wave,
+// 64-byte aligned and contiguous.  mu and sigma of the shifted columns come out of LDS, where the
+// workgroup stages its tile plus the 16 columns to its left once; eps is read at whatever alignment its
+// array has (loads do not mind).  The KL sum is taken over the unshifted tile, thread by thread as in the
+// kernel above, so its value does not depend on which kernel ran.  Four chunks per thread, fixed.  Measured
+// (16 samples, 6 M and 20 M weights, pitch 16 bytes off the grid): 148 and 511-530 us against 153-161 and
+// 556-593 us for the kernel above on the same arrays and 142 and 511 us with an aligned pitch.  The
+// drawing variant gains nothing from it (it waits for its arithmetic, not for its stores) and has none.
+// ---------------------------------------------------------------------------------
+template <bool NT, bool KL>
+__global__ void __launch_bounds__(kBlock)
+hot_forward_shifted_kernel(long n, long ld, int s_loc, const float *mu, const float *sigma,
+                           const float *__restrict__ eps, float *__restrict__ w,
+                           double *partials, unsigned *ticket, double *__restrict__ kl_out)
+{
+    constexpr int CH = 4;
+    constexpr int kHalo = 16;                         // columns staged to the left of the tile
+    constexpr int kStep = kBlock * 4;                 // columns between a thread's chunks
+    constexpr int kTile = kStep * CH;
+    // staged column c0 - kHalo + i lives in [i mod 4][i div 4]: a wave's 64 threads, each reading element k of
+    // its four shifted columns, then read 64 consecutive words of one of the four arrays (no bank conflicts
+    // at any shift, and no shuffling in registers)
+    constexpr int kQuads = (kHalo + kTile) / 4;
+    __shared__ float lds_mu[4][kQuads], lds_sg[4][kQuads];
+    const long n_windows = (n + (kHalo - 1) + kTile - 1) / kTile;    // the windows reach back by up to 15 columns
+    const unsigned long w_base = (unsigned long)(reinterpret_cast<uintptr_t>(w) >> 2);
+    const int t4 = (int)threadIdx.x * 4;
+    double kl = 0.0;
+
+    for (long tile = blockIdx.x; tile < n_windows; tile += gridDim.x) {
+        const long c0 = tile * kTile;
+        __syncthreads();          // the previous tile's readers are done with the staging buffers
+        f4 m[CH], sd[CH];
+        if (c0 + kTile <= n) {      // a whole tile (uniform over the workgroup): all eight loads in flight together
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                m[c] = load4<false, NT>(mu + c0 + c * kStep + t4);
+                sd[c] = load4<false, NT>(sigma + c0 + c * kStep + t4);
             }
-            __syncthreads();
-            if (last && threadIdx.x < 64) {
-                double v = 0.0;
-                if (threadIdx.x < gridDim.x)
-                    v = __hip_atomic_load(&partials[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                v = wave_sum(v);
-                if (threadIdx.x == 0) {
-                    *kl_out = 0.5 * v;
-                    __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+            if constexpr (KL) {
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) kl += kl_addend(m[c][j], sd[c][j]);
+            }
+        } else {
+            for (int c = 0; c < CH; ++c) {
+                const long col = c0 + c * kStep + t4;
+                m[c] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+                sd[c] = f4{1.0f, 1.0f, 1.0f, 1.0f};
+                for (int j = 0; j < 4; ++j)
+                    if (col + j < n) {
+                        m[c][j] = mu[col + j];
+                        sd[c][j] = sigma[col + j];
+                        if constexpr (KL) kl += kl_addend(m[c][j], sd[c][j]);
+                    }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int q = (kHalo + c * kStep + t4) >> 2;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                lds_mu[j][q] = m[c][j];
+                lds_sg[j][q] = sd[c][j];
+            }
+        }
+        if (threadIdx.x < kHalo) {
+            const long col = c0 - kHalo + (long)threadIdx.x;
+            const bool ok = col >= 0 && col < n;
+            lds_mu[threadIdx.x & 3][threadIdx.x >> 2] = ok ? mu[col] : 0.0f;
+            lds_sg[threadIdx.x & 3][threadIdx.x >> 2] = ok ? sigma[col] : 1.0f;
+        }
+        __syncthreads();
+
+        for (int s = 0; s < s_loc; ++s) {
+            const int a = (int)((w_base + (unsigned long)s * (unsigned long)ld) & 15ul);   // this row's misalignment in floats
+            float *w_row = w + (size_t)s * (size_t)ld;
+            const float *e_row = eps + (size_t)s * (size_t)ld;
+            f4 e[CH];
+            if (c0 - a >= 0 && c0 + kTile - a <= n) {
+                // the whole shifted window lies inside the row (uniform over the workgroup): no guards, the
+                // four eps loads in flight together
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const long cs = c0 + c * kStep + t4 - a;
+                    e[c] = load4<false, NT>(e_row + cs);
+                }
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const long cs = c0 + c * kStep + t4 - a;
+                    const int at = kHalo + c * kStep + t4 - a;
+                    f4 r;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        r[j] = __builtin_fmaf(lds_sg[(at + j) & 3][(at + j) >> 2], e[c][j], lds_mu[(at + j) & 3][(at + j) >> 2]);
+                    store4<true, NT>(w_row + cs, r);
+                }
+                continue;
+            }
+            bool full[CH];
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const long cs = c0 + c * kStep + t4 - a;
+                full[c] = cs >= 0 && cs + 4 <= n;
+                if (full[c]) {
+                    e[c] = load4<false, NT>(e_row + cs);
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const long cs = c0 + c * kStep + t4 - a;
+                const int at = kHalo + c * kStep + t4 - a;          // 1 .. kHalo + kTile - 4
+                if (full[c]) {
+                    f4 r;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        r[j] = __builtin_fmaf(lds_sg[(at + j) & 3][(at + j) >> 2], e[c][j], lds_mu[(at + j) & 3][(at + j) >> 2]);
+                    store4<true, NT>(w_row + cs, r);
+                } else {
+                    // the two ends of a row: the columns of this quad that exist, one by one
+                    for (int j = 0; j < 4; ++j) {
+                        const long col = cs + j;
+                        if (col >= 0 && col < n) {
+                            w_row[col] = __builtin_fmaf(lds_sg[(at + j) & 3][(at + j) >> 2], e_row[col], lds_mu[(at + j) & 3][(at + j) >> 2]);
+                        }
+                    }
                 }
             }
         }
     }
+    if constexpr (KL) kl_leave(kl, partials, ticket, kl_out);
 }
 
 // Adds the per-workgroup KL partials in a fixed order and applies the factor 1/2 of the
@@ -873,12 +1018,25 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     a.rng = rng ? *rng : Rng{0, 0, 0, 0};
     a.grid = dim3(grid_for(d.n_weights, c));
     a.stream = static_cast<hipStream_t>(stream);
+
+    // Rows of w off the 64-byte grid, streamed with non-temporal stores, eps from its array: the kernel that
+    // moves its column window row by row (fixed shape: four chunks).
+    const bool rows_on_grid = (reinterpret_cast<uintptr_t>(w) & 63u) == 0 && (d.s_local == 1 || d.ld % 16 == 0);
+    const bool shifted = !kl_only && !adam && !gen && c.nontemporal != 0 && !rows_on_grid;
+    if (shifted) {
+        const long windows = (d.n_weights + 15 + 4095) / 4096;
+        a.grid = dim3((unsigned)(windows < c.grid_blocks ? windows : c.grid_blocks));
+    }
     const bool self_finish = a.want_kl && a.grid.x <= (unsigned)kTicketGrid;
     a.ticket = self_finish ? reinterpret_cast<unsigned *>(plan->partials + kMaxGrid) : nullptr;
 
     DeviceGuard guard(d.device);
     if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
-    if (gen) fwd_dispatch<true>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
+    if (shifted) {
+        const dim3 block(kBlock);
+        if (a.want_kl) hot_forward_shifted_kernel<true, true><<<a.grid, block, 0, a.stream>>>(a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out);
+        else hot_forward_shifted_kernel<true, false><<<a.grid, block, 0, a.stream>>>(a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out);
+    } else if (gen) fwd_dispatch<true>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
     else fwd_dispatch<false>(c.chunks, c.unroll, al, c.nontemporal != 0, a);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && kl_out && !self_finish) {

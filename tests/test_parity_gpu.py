@@ -491,6 +491,68 @@ def test_random_shapes_offsets_and_launch_shapes(oracle, hot):
         assert np.abs(eps[:, :n].cpu().numpy() - e64).max() <= 2e-6 * 5.78
 
 
+def test_rows_off_the_64_byte_grid(oracle, hot):
+    """The forward kernel for rows of w that do not start on 64-byte boundaries (taken with non-temporal
+    accesses: forced here, the default above 256 MiB): every base offset 0..15 floats of w, pitches of
+    every residue class that matters, one to several rows, sizes around the 4096-column tile and the
+    16-column halo, eps read (at its own, different alignment) and drawn, with and without KL, one
+    workgroup striding over all windows and many.  Everything element by element against the oracle;
+    the padding of w must stay untouched."""
+    rs = np.random.default_rng(64)
+    sizes = [1, 3, 15, 16, 17, 4095, 4096, 4097, 4096 + 15, 4096 + 16, 2 * 4096 - 1, 3 * 4096 + 5, 70_001]
+    case = 0
+    for n in sizes:
+        for ld_pad in (0, 1, 4, 12, 16, 20):
+            case += 1
+            ld = n + ld_pad
+            s = int(rs.integers(1, 6))
+            w_off, e_off = int(rs.integers(0, 16)), int(rs.integers(0, 16))
+            grid = int(rs.choice([0, 1, 3]))
+            want_kl = bool(rs.integers(0, 2))
+            _say("case off-grid", n, ld, s, w_off, e_off, grid, want_kl)
+            g = torch.Generator().manual_seed(case)
+            mu, sigma = torch.randn(n, generator=g), torch.exp(torch.randn(n, generator=g))
+            eps_h = torch.cat([torch.randn(s, n, generator=g), torch.full((s, ld - n), float("nan"))], 1)
+
+            def at(t, off, fill=None):
+                buf = torch.full((t.numel() + 16,), 5.0 if fill is None else fill, device=DEV)
+                v = buf[off:off + t.numel()].view(t.shape)
+                if fill is None:
+                    v.copy_(t)
+                return v
+
+            mu_d, sg_d, eps_d = at(mu, int(rs.integers(0, 4))), at(sigma, int(rs.integers(0, 4))), at(eps_h, e_off)
+            plan = hot.hot_create(n, ld, s, 2 * s, 77.0, 0)
+            for kern in (hot.HOT_KERNEL_FORWARD, hot.HOT_KERNEL_FORWARD_RNG):
+                hot.hot_set_launch(plan, kern, nontemporal=1, grid_blocks=grid)
+            # eps from its array
+            w = at(eps_h, w_off, fill=123456.0)
+            kl = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+            hot.hot_forward(plan, mu_d, sg_d, eps_d, w, kl if want_kl else None)
+            torch.cuda.synchronize()
+            h = {"mu": mu.numpy(), "sigma": sigma.numpy(), "eps": eps_h.numpy()}
+            wh = w.cpu().numpy()
+            assert np.all(wh[:, n:] == np.float32(123456.0)), "w padding was written"
+            P.check_w(oracle, h, wh, n)
+            if want_kl:
+                P.check_kl(oracle, h, kl.item())
+            else:
+                assert kl.item() == -1.0
+            # eps drawn in the kernel (always the general kernel) against the materialised draw fed to the
+            # row-shifting kernel: the same w, bit for bit
+            rng = hot.hot_rng(seed=case, step=3, first_sample=1)
+            e_draw = at(eps_h, 4 * int(rs.integers(0, 4)), fill=0.0)
+            hot.hot_sample_eps(plan, rng, e_draw)
+            w0, w1 = at(eps_h, w_off, fill=123456.0), at(eps_h, w_off, fill=123456.0)
+            kl0, kl1 = torch.zeros(1, dtype=torch.float64, device=DEV), torch.zeros(1, dtype=torch.float64, device=DEV)
+            hot.hot_forward(plan, mu_d, sg_d, e_draw, w0, kl0)
+            hot.hot_forward_rng(plan, rng, mu_d, sg_d, w1, kl1)
+            torch.cuda.synchronize()
+            assert torch.equal(w0, w1), "drawn and materialised eps give different w"
+            assert abs(kl0.item() - kl1.item()) <= 1e-13 * P.kl_scale(h)
+            hot.hot_destroy(plan)
+
+
 def test_two_plans_on_two_streams_at_once(oracle, hot):
     wl = W.scaled(W.CONFIGS["C3"], 400_000)
     xa = W.make_inputs(wl, DEV)

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRCS = [os.path.join(HERE, "csrc", name) for name in ("hot.hip", "stats.hip", "linear.hip", "update.hip")]
+SRCS = [os.path.join(HERE, "csrc", name) for name in ("forward.hip", "backward.hip", "hot.hip", "stats.hip", "linear.hip", "update.hip")]
 LIB = os.path.join(HERE, "libhot.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -1,0 +1,449 @@
+// libhot, backward half of the sample layer (arxiv 2604.04736, Algorithm 2: loss, gradient and averaging
+// lines; Algorithm 1: with the optimizer step and the next sampling in its epilogue): hot_backward,
+// hot_backward_rng, hot_backward_rows, hot_backward_adam, hot_backward_adam_forward.  The design notes
+// common to both halves are at the top of hot.hip.  gfx950 only.
+#include "sample_layer.h"
+
+namespace {
+
+// grad_mu and grad_sigma of one weight, in fp64, from its fp64 sample sums (Algorithm 2, gradient
+// and averaging lines; d KL / d mu = mu, d KL / d sigma = sigma - 1/sigma).
+__device__ __forceinline__ void finish_grad(double sum_g, double sum_ge, float m, float sd,
+                                            double g, double k, double &gm, double &gs)
+{
+    // k = 0 (a partial call that leaves the KL part to another one) must not turn sigma = 0 into NaN
+    const double kl_m = k != 0.0 ? k * (double)m : 0.0;
+    const double kl_s = k != 0.0 ? k * ((double)sd - (double)(1.0f / sd)) : 0.0;
+    gm = fma(g, sum_g, kl_m);
+    gs = fma(g, sum_ge, kl_s);
+}
+
+// What the backward kernel does with the finished gradients of a column chunk.
+//
+// StoreGrad: writes them (or adds them to what the outputs hold) as fp32: Algorithm 2, where the
+// all-reduce over GPUs comes next.
+struct StoreGrad {
+    float *gmu, *gsig;
+    int accumulate;
+    static constexpr bool kReduces = false;   // no per-workgroup sum behind the tile loop
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void quad(long col, f4, f4, const double (&gm)[4], const double (&gs)[4], double &) const
+    {
+        f4 om = {0.0f, 0.0f, 0.0f, 0.0f}, os = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (accumulate) {
+            om = load4<ALIGNED, NT>(gmu + col);
+            os = load4<ALIGNED, NT>(gsig + col);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            om[j] = (float)(gm[j] + (double)om[j]);
+            os[j] = (float)(gs[j] + (double)os[j]);
+        }
+        store4<ALIGNED, NT>(gmu + col, om);
+        store4<ALIGNED, NT>(gsig + col, os);
+    }
+    __device__ __forceinline__ void one(long i, float, float, double gm, double gs, double &) const
+    {
+        gmu[i] = (float)(gm + (double)(accumulate ? gmu[i] : 0.0f));
+        gsig[i] = (float)(gs + (double)(accumulate ? gsig[i] : 0.0f));
+    }
+};
+
+// AdamUpdate: Algorithm 1 (one GPU, nothing to all-reduce): the gradients, rounded to fp32 exactly
+// as StoreGrad would store them, go straight into the optimizer's update of mu, sigma and their
+// moments, and are never written.
+struct AdamUpdate {
+    float *mu, *sigma, *m_mu, *v_mu, *m_sig, *v_sig;
+    AdamConst c;
+    static constexpr bool kReduces = false;
+    // updates m, sd (and the moments in memory) in place and stores them
+    template <bool ALIGNED>
+    __device__ __forceinline__ void update4(long col, f4 &m, f4 &sd, const double (&gm)[4], const double (&gs)[4]) const
+    {
+        f4 a0 = load4<ALIGNED, true>(m_mu + col), b0 = load4<ALIGNED, true>(v_mu + col);
+        f4 a1 = load4<ALIGNED, true>(m_sig + col), b1 = load4<ALIGNED, true>(v_sig + col);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float t = m[j], a = a0[j], b = b0[j];
+            adam_one(t, a, b, (float)gm[j], c);
+            m[j] = t; a0[j] = a; b0[j] = b;
+            t = sd[j]; a = a1[j]; b = b1[j];
+            adam_one_sigma(t, a, b, (float)gs[j], c);
+            sd[j] = t; a1[j] = a; b1[j] = b;
+        }
+        store4<ALIGNED, true>(mu + col, m);
+        store4<ALIGNED, true>(sigma + col, sd);
+        store4<ALIGNED, true>(m_mu + col, a0);
+        store4<ALIGNED, true>(v_mu + col, b0);
+        store4<ALIGNED, true>(m_sig + col, a1);
+        store4<ALIGNED, true>(v_sig + col, b1);
+    }
+    __device__ __forceinline__ void update1(long i, float &m, float &sd, double gm, double gs) const
+    {
+        float a = m_mu[i], b = v_mu[i];
+        adam_one(m, a, b, (float)gm, c);
+        mu[i] = m; m_mu[i] = a; v_mu[i] = b;
+        a = m_sig[i]; b = v_sig[i];
+        adam_one_sigma(sd, a, b, (float)gs, c);
+        sigma[i] = sd; m_sig[i] = a; v_sig[i] = b;
+    }
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void quad(long col, f4 m, f4 sd, const double (&gm)[4], const double (&gs)[4], double &) const
+    {
+        update4<ALIGNED>(col, m, sd, gm, gs);
+    }
+    __device__ __forceinline__ void one(long i, float m, float sd, double gm, double gs, double &) const
+    {
+        update1(i, m, sd, gm, gs);
+    }
+};
+
+// AdamUpdateSample: Algorithm 1's whole step behind the network's backward pass.  After AdamUpdate's
+// update the next step's reparameterisation and prior-matching lines run on the updated mu, sigma
+// while they are still in registers: w[s, :] = mu + sigma * eps_s with eps drawn for the NEXT step, and
+// the KL addends of the updated parameters go into the workgroup's partial sum (as in the forward kernel).
+struct AdamUpdateSample {
+    AdamUpdate adam;
+    float *w;
+    long ld;
+    int s_loc;
+    Rng next;          // the draw of the next step
+    double *partials;  // one KL partial per workgroup, or nullptr when no KL is wanted
+    static constexpr bool kReduces = true;
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void quad(long col, f4 m, f4 sd, const double (&gm)[4], const double (&gs)[4], double &kl) const
+    {
+        adam.template update4<ALIGNED>(col, m, sd, gm, gs);
+        for (int s = 0; s < s_loc; ++s) {
+            const f4 e = eps_quad(col >> 2, s, next);
+            f4 r;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[j], e[j], m[j]);
+            store4<ALIGNED, NT>(w + (size_t)s * (size_t)ld + col, r);
+        }
+        if (partials) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) kl += kl_addend(m[j], sd[j]);
+        }
+    }
+    __device__ __forceinline__ void one(long i, float m, float sd, double gm, double gs, double &kl) const
+    {
+        adam.update1(i, m, sd, gm, gs);
+        for (int s = 0; s < s_loc; ++s)
+            w[(size_t)s * (size_t)ld + (size_t)i] = __builtin_fmaf(sd, eps1<true>(nullptr, 0, i, s, next), m);
+        if (partials) kl += kl_addend(m, sd);
+    }
+};
+
+// ---------------------------------------------------------------------------------
+// Backward: column sums over the local samples of grad_w and grad_w * eps, then the
+// KL gradient and the scaling (Algorithm 2, loss / gradient / averaging lines).
+// ---------------------------------------------------------------------------------
+template <int CHUNKS, int U, bool ALIGNED, bool NT, bool GEN>
+__device__ __forceinline__ void backward_rows(int s, long col0, long ld, double (&sum_g)[CHUNKS][4],
+                                              double (&sum_ge)[CHUNKS][4], const float *__restrict__ eps,
+                                              const float *__restrict__ gw, const Rng &rng)
+{
+    constexpr long kStep = (long)kBlock * 4;
+    f4 gv[U][CHUNKS], ev[U][CHUNKS];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c) {
+            gv[u][c] = load4<ALIGNED, NT>(gw + (size_t)(s + u) * (size_t)ld + col0 + c * kStep);
+            ev[u][c] = eps4<ALIGNED, NT, GEN>(eps, ld, s + u, col0 + c * kStep, rng);
+        }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double gd = (double)gv[u][c][j];
+                sum_g[c][j] += gd;
+                sum_ge[c][j] = fma(gd, (double)ev[u][c][j], sum_ge[c][j]);
+            }
+}
+
+template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool GEN, class EPI>
+__global__ void __launch_bounds__(kBlock)
+hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
+                    const float *mu, const float *sigma,
+                    const float *__restrict__ eps, const float *__restrict__ gw, EPI epi, Rng rng)
+{
+    constexpr long kTile = (long)kBlock * 4 * CHUNKS;
+    constexpr long kStep = (long)kBlock * 4;
+    const long n_tiles = (n + kTile - 1) / kTile;
+    double acc = 0.0;   // what a reducing epilogue sums per thread (the KL addends of AdamUpdateSample)
+
+    for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const long col0 = tile * kTile + (long)threadIdx.x * 4;
+        if ((tile + 1) * kTile <= n) {
+            f4 m[CHUNKS], sd[CHUNKS];
+#pragma unroll
+            for (int c = 0; c < CHUNKS; ++c) {
+                m[c] = load4<ALIGNED, NT>(mu + col0 + c * kStep);
+                sd[c] = load4<ALIGNED, NT>(sigma + col0 + c * kStep);
+            }
+            double sum_g[CHUNKS][4], sum_ge[CHUNKS][4];
+#pragma unroll
+            for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sum_g[c][j] = sum_ge[c][j] = 0.0;
+            int s = 0;
+            for (; s + UNROLL <= s_loc; s += UNROLL)
+                backward_rows<CHUNKS, UNROLL, ALIGNED, NT, GEN>(s, col0, ld, sum_g, sum_ge, eps, gw, rng);
+            for (; s < s_loc; ++s)
+                backward_rows<CHUNKS, 1, ALIGNED, NT, GEN>(s, col0, ld, sum_g, sum_ge, eps, gw, rng);
+#pragma unroll
+            for (int c = 0; c < CHUNKS; ++c) {
+                double gm[4], gs[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) finish_grad(sum_g[c][j], sum_ge[c][j], m[c][j], sd[c][j], g, k, gm[j], gs[j]);
+                epi.template quad<ALIGNED, NT>(col0 + c * kStep, m[c], sd[c], gm, gs, acc);
+            }
+        } else {
+            for (int c = 0; c < CHUNKS; ++c) {
+                const long col = col0 + c * kStep;
+                if (col + 4 <= n) {
+                    const f4 m = load4<ALIGNED, false>(mu + col);
+                    const f4 sd = load4<ALIGNED, false>(sigma + col);
+                    double sum_g[4] = {0.0, 0.0, 0.0, 0.0}, sum_ge[4] = {0.0, 0.0, 0.0, 0.0};
+                    for (int s = 0; s < s_loc; ++s) {
+                        const f4 gv = load4<ALIGNED, false>(gw + (size_t)s * (size_t)ld + col);
+                        const f4 ev = eps4<ALIGNED, false, GEN>(eps, ld, s, col, rng);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const double gd = (double)gv[j];
+                            sum_g[j] += gd;
+                            sum_ge[j] = fma(gd, (double)ev[j], sum_ge[j]);
+                        }
+                    }
+                    double gm[4], gs[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) finish_grad(sum_g[j], sum_ge[j], m[j], sd[j], g, k, gm[j], gs[j]);
+                    epi.template quad<ALIGNED, false>(col, m, sd, gm, gs, acc);
+                } else {
+                    for (long i = col; i < n; ++i) {
+                        double sum_g = 0.0, sum_ge = 0.0;
+                        for (int s = 0; s < s_loc; ++s) {
+                            const size_t at = (size_t)s * (size_t)ld + (size_t)i;
+                            const double gd = (double)gw[at];
+                            sum_g += gd;
+                            sum_ge = fma(gd, (double)eps1<GEN>(eps, at, i, s, rng), sum_ge);
+                        }
+                        const float m = mu[i], sd = sigma[i];
+                        double gm, gs;
+                        finish_grad(sum_g, sum_ge, m, sd, g, k, gm, gs);
+                        epi.one(i, m, sd, gm, gs, acc);
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (EPI::kReduces) {
+        if (epi.partials) {      // uniform over the grid
+            __shared__ double lds[kWaves];
+            const double mine = block_sum(acc, lds);
+            if (threadIdx.x == 0) epi.partials[blockIdx.x] = mine;
+        }
+    }
+}
+
+template <class EPI>
+struct BwdArgs {
+    long n, ld;
+    int s_loc;
+    double g, k;
+    const float *mu, *sigma, *eps, *gw;
+    EPI epi;
+    Rng rng;
+    dim3 grid;
+    hipStream_t stream;
+};
+
+template <bool GEN, int CH, int U, bool AL, bool NT, class EPI>
+void bwd_go(const BwdArgs<EPI> &a)
+{
+    hot_backward_kernel<CH, U, AL, NT, GEN, EPI><<<a.grid, dim3(kBlock), 0, a.stream>>>(
+        a.n, a.ld, a.s_loc, a.g, a.k, a.mu, a.sigma, a.eps, a.gw, a.epi, a.rng);
+}
+template <bool GEN, int CH, int U, class EPI>
+void bwd_flags(bool al, bool nt, const BwdArgs<EPI> &a)
+{
+    if (al) {
+        if (nt) bwd_go<GEN, CH, U, true, true>(a);
+        else bwd_go<GEN, CH, U, true, false>(a);
+    } else {
+        if (nt) bwd_go<GEN, CH, U, false, true>(a);
+        else bwd_go<GEN, CH, U, false, false>(a);
+    }
+}
+template <bool GEN, int CH, class EPI>
+void bwd_unroll(int u, bool al, bool nt, const BwdArgs<EPI> &a)
+{
+    if (u >= 4) bwd_flags<GEN, CH, 4>(al, nt, a);
+    else if (u >= 2) bwd_flags<GEN, CH, 2>(al, nt, a);
+    else bwd_flags<GEN, CH, 1>(al, nt, a);
+}
+template <bool GEN, class EPI>
+void bwd_dispatch(int ch, int u, bool al, bool nt, const BwdArgs<EPI> &a)
+{
+    if (ch >= 4) bwd_unroll<GEN, 4>(u, al, nt, a);
+    else if (ch >= 2) bwd_unroll<GEN, 2>(u, al, nt, a);
+    else bwd_unroll<GEN, 1>(u, al, nt, a);
+}
+
+// Launches the backward kernel with the given epilogue.  rows samples starting at local sample
+// first_row (eps and grad_w point at the first of them); rows = 0 means all of the plan's samples.
+// aligned_out: whether every array the epilogue touches is 16-byte aligned.
+template <class EPI>
+int backward_launch(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
+                    const float *eps, const float *grad_w, const EPI &epi, bool aligned_out, void *stream,
+                    int first_row, int rows, bool add_kl)
+{
+    const bool gen = rng != nullptr;
+    const hot_desc &d = plan->d;
+    const hot_launch &c = plan->cfg[kernel];
+    const bool al = aligned16(mu) && aligned16(sigma) && aligned16(grad_w) && aligned_out &&
+                    (gen || aligned16(eps)) && (d.ld % 4 == 0);
+
+    BwdArgs<EPI> a;
+    a.n = d.n_weights;
+    a.ld = d.ld;
+    a.s_loc = rows > 0 ? rows : d.s_local;
+    a.g = plan->g;
+    a.k = add_kl ? plan->k : 0.0;
+    a.mu = mu;
+    a.sigma = sigma;
+    a.eps = eps;
+    a.gw = grad_w;
+    a.epi = epi;
+    a.rng = gen ? *rng : Rng{0, 0, 0, 0};
+    a.rng.first_sample += (unsigned)first_row;
+    a.grid = dim3(grid_for(d.n_weights, c));
+    a.stream = static_cast<hipStream_t>(stream);
+
+    DeviceGuard guard(d.device);
+    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
+    if (gen) bwd_dispatch<true>(c.chunks, pick_unroll(c.unroll, a.s_loc), al, c.nontemporal != 0, a);
+    else bwd_dispatch<false>(c.chunks, pick_unroll(c.unroll, a.s_loc), al, c.nontemporal != 0, a);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
+}
+
+int backward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
+                  const float *eps, const float *grad_w, float *grad_mu, float *grad_sigma, void *stream,
+                  int first_row = 0, int rows = 0, bool accumulate = false, bool add_kl = true)
+{
+    const bool gen = rng != nullptr;
+    if (!mu || !sigma || !grad_w || !grad_mu || !grad_sigma || (!gen && !eps)) return HOT_EINVAL;
+    if (!aligned4(mu) || !aligned4(sigma) || !aligned4(grad_w) || !aligned4(grad_mu) || !aligned4(grad_sigma) ||
+        (!gen && !aligned4(eps)))
+        return HOT_EINVAL;
+    const StoreGrad epi{grad_mu, grad_sigma, accumulate ? 1 : 0};
+    return backward_launch(plan, kernel, rng, mu, sigma, eps, grad_w, epi, aligned16(grad_mu) && aligned16(grad_sigma),
+                           stream, first_row, rows, add_kl);
+}
+
+}  // namespace
+
+extern "C" {
+
+int hot_backward(hot_plan *plan, const float *mu, const float *sigma, const float *eps,
+                 const float *grad_w, float *grad_mu, float *grad_sigma, void *stream)
+{
+    if (!plan) return HOT_EINVAL;
+    return backward_impl(plan, HOT_KERNEL_BACKWARD, nullptr, mu, sigma, eps, grad_w, grad_mu, grad_sigma, stream);
+}
+
+int hot_backward_rng(hot_plan *plan, const hot_rng *rng, const float *mu, const float *sigma,
+                     const float *grad_w, float *grad_mu, float *grad_sigma, void *stream)
+{
+    Rng r;
+    if (!plan || !make_rng(rng, plan->d.s_local, r)) return HOT_EINVAL;
+    return backward_impl(plan, HOT_KERNEL_BACKWARD_RNG, &r, mu, sigma, nullptr, grad_w, grad_mu, grad_sigma, stream);
+}
+
+int hot_backward_rows(hot_plan *plan, const hot_rng *rng, const float *mu, const float *sigma, const float *eps,
+                      const float *grad_w, int32_t first_row, int32_t rows, int32_t accumulate, int32_t add_kl,
+                      float *grad_mu, float *grad_sigma, void *stream)
+{
+    if (!plan || first_row < 0 || rows < 1 || (long)first_row + rows > plan->d.s_local) return HOT_EINVAL;
+    if ((rng != nullptr) == (eps != nullptr)) return HOT_EINVAL;      // exactly one source of eps
+    if (rng) {
+        Rng r;
+        if (!make_rng(rng, plan->d.s_local, r)) return HOT_EINVAL;
+        return backward_impl(plan, HOT_KERNEL_BACKWARD_RNG, &r, mu, sigma, nullptr, grad_w, grad_mu, grad_sigma, stream,
+                             first_row, rows, accumulate != 0, add_kl != 0);
+    }
+    return backward_impl(plan, HOT_KERNEL_BACKWARD, nullptr, mu, sigma, eps, grad_w, grad_mu, grad_sigma, stream,
+                         first_row, rows, accumulate != 0, add_kl != 0);
+}
+
+int hot_backward_adam(hot_plan *plan, const hot_rng *rng, const hot_adam *params, float *mu, float *sigma,
+                      const float *eps, const float *grad_w, float *m_mu, float *v_mu, float *m_sigma, float *v_sigma,
+                      void *stream)
+{
+    if (!plan || plan->d.s_local != plan->d.s_total) return HOT_EINVAL;   // one GPU holds all samples
+    if ((rng != nullptr) == (eps != nullptr)) return HOT_EINVAL;          // exactly one source of eps
+    if (!mu || !sigma || !grad_w || !m_mu || !v_mu || !m_sigma || !v_sigma) return HOT_EINVAL;
+    const void *ptrs[8] = {mu, sigma, grad_w, m_mu, v_mu, m_sigma, v_sigma, eps};
+    bool al = true;
+    for (int i = 0; i < (eps ? 8 : 7); ++i) {
+        if (!aligned4(ptrs[i])) return HOT_EINVAL;
+        if (i >= 3 && i < 7) al = al && aligned16(ptrs[i]);
+    }
+    AdamUpdate epi;
+    if (!make_adam_const(params, epi.c)) return HOT_EINVAL;
+    epi.mu = mu;
+    epi.sigma = sigma;
+    epi.m_mu = m_mu;
+    epi.v_mu = v_mu;
+    epi.m_sig = m_sigma;
+    epi.v_sig = v_sigma;
+    Rng r;
+    if (rng && !make_rng(rng, plan->d.s_local, r)) return HOT_EINVAL;
+    return backward_launch(plan, rng ? HOT_KERNEL_BACKWARD_RNG : HOT_KERNEL_BACKWARD, rng ? &r : nullptr, mu, sigma, eps,
+                           grad_w, epi, al, stream, 0, 0, true);
+}
+
+int hot_backward_adam_forward(hot_plan *plan, const hot_rng *rng, const hot_rng *rng_next, const hot_adam *params,
+                              float *mu, float *sigma, const float *grad_w, float *m_mu, float *v_mu, float *m_sigma,
+                              float *v_sigma, float *w, double *kl_out, void *stream)
+{
+    if (!plan || plan->d.s_local != plan->d.s_total) return HOT_EINVAL;   // one GPU holds all samples
+    if (!mu || !sigma || !grad_w || !m_mu || !v_mu || !m_sigma || !v_sigma || !w || w == grad_w) return HOT_EINVAL;
+    if (kl_out && (reinterpret_cast<uintptr_t>(kl_out) & 7u)) return HOT_EINVAL;
+    const void *ptrs[8] = {mu, sigma, grad_w, m_mu, v_mu, m_sigma, v_sigma, w};
+    bool al = true;
+    for (int i = 0; i < 8; ++i) {
+        if (!aligned4(ptrs[i])) return HOT_EINVAL;
+        if (i >= 3) al = al && aligned16(ptrs[i]);
+    }
+    AdamUpdateSample epi;
+    if (!make_adam_const(params, epi.adam.c)) return HOT_EINVAL;
+    Rng r, rn;
+    if (!make_rng(rng, plan->d.s_local, r) || !make_rng(rng_next, plan->d.s_local, rn)) return HOT_EINVAL;
+    epi.adam.mu = mu;
+    epi.adam.sigma = sigma;
+    epi.adam.m_mu = m_mu;
+    epi.adam.v_mu = v_mu;
+    epi.adam.m_sig = m_sigma;
+    epi.adam.v_sig = v_sigma;
+    epi.w = w;
+    epi.ld = plan->d.ld;
+    epi.s_loc = plan->d.s_local;
+    epi.next = rn;
+    epi.partials = kl_out ? plan->partials : nullptr;
+    const int rc = backward_launch(plan, HOT_KERNEL_BACKWARD_RNG, &r, mu, sigma, nullptr, grad_w, epi, al, stream, 0, 0, true);
+    if (rc != HOT_OK || !kl_out) return rc;
+    DeviceGuard guard(plan->d.device);
+    if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
+    const unsigned blocks = grid_for(plan->d.n_weights, plan->cfg[HOT_KERNEL_BACKWARD_RNG]);
+    hot_kl_finish_kernel<<<dim3(1), dim3(kFinishBlock), 0, static_cast<hipStream_t>(stream)>>>(plan->partials, (int)blocks, kl_out);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
+}
+
+}  // extern "C"

@@ -1,0 +1,173 @@
+// Pieces shared by the translation units of the sample layer (hot.hip, forward.hip, backward.hip):
+// constants, the eps accessors, the KL addend, the workgroup sum, the KL finish kernel, the plan and the
+// host helpers around it.  gfx950 only.
+#ifndef HOT_SAMPLE_LAYER_H
+#define HOT_SAMPLE_LAYER_H
+
+#include <hip/hip_runtime.h>
+
+#include "hot.h"
+#include "vec.h"
+#include "draw.h"
+#include "adam.h"
+
+// What hot_create returns: the description, the scaling constants g and k derived from it, the plan's own
+// device scratch and the launch geometry of the four kernels.
+struct hot_plan {
+    hot_desc d;
+    double g, k;
+    double *partials;   // kMaxGrid fp64 KL partial sums, one per forward workgroup, then the arrival counter
+    hot_launch cfg[4];  // indexed by HOT_KERNEL_*
+    int last_hip;
+};
+
+namespace {
+
+constexpr int kBlock = 256;             // threads per workgroup = 4 wavefronts of 64
+constexpr int kWaves = kBlock / 64;
+constexpr int kMaxGrid = 65536;         // upper bound on workgroups (size of the partials buffer)
+constexpr int kFinishBlock = 1024;      // threads of the one workgroup that adds the KL partials
+constexpr int kTicketGrid = 64;         // up to this many workgroups the forward kernel finishes the KL sum itself
+
+typedef u4 u4u __attribute__((aligned(4)));
+
+// eps[s, col .. col+3]: read from memory, or drawn (col is a multiple of 4).
+template <bool ALIGNED, bool NT, bool GEN>
+__device__ __forceinline__ f4 eps4(const float *eps, long ld, int s, long col, const Rng &rng)
+{
+    if constexpr (GEN) return eps_quad(col >> 2, s, rng);
+    else return load4<ALIGNED, NT>(eps + (size_t)s * (size_t)ld + col);
+}
+
+// eps[s, i] of a single weight (the ragged tail): read at its offset, or drawn with its quad.
+template <bool GEN>
+__device__ __forceinline__ float eps1(const float *eps, size_t at, long i, int s, const Rng &rng)
+{
+    if constexpr (GEN) {
+        const f4 e = eps_quad(i >> 2, s, rng);
+        const int j = (int)(i & 3);
+        return j == 0 ? e[0] : (j == 1 ? e[1] : (j == 2 ? e[2] : e[3]));
+    } else {
+        return eps[at];
+    }
+}
+
+// One addend of the prior-matching line of Algorithm 2 (without the factor 1/2):
+// sigma^2 + mu^2 - 1 - ln sigma^2, with ln sigma^2 taken as 2 ln sigma.  sigma is split exactly
+// into mantissa and exponent, ln sigma = (exponent + log2 mantissa) ln 2: only log2 of a number in
+// [1/2, 1) goes through the fp32 hardware logarithm (absolute error below 6e-8), the rest is fp64.
+// sigma = 0 gives +inf, sigma < 0 gives NaN.
+__device__ __forceinline__ double kl_addend(float m, float sd)
+{
+    const double md = (double)m, sdd = (double)sd;
+    const float mant = __builtin_amdgcn_frexp_mantf(sd);
+    const int ex = __builtin_amdgcn_frexp_expf(sd);
+    const double ln_sd = ((double)ex + (double)__builtin_amdgcn_logf(mant)) * 0.69314718055994530942;
+    return fma(sdd, sdd, fma(md, md, -1.0)) - 2.0 * ln_sd;
+}
+
+// Sum over the workgroup, complete in thread 0.  Fixed tree, hence deterministic.
+__device__ __forceinline__ double block_sum(double v, double *lds)
+{
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) lds[wave] = v;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < kWaves; ++i) total += lds[i];
+    }
+    return total;
+}
+
+// Adds the per-workgroup KL partials in a fixed order and applies the factor 1/2 of the
+// prior-matching line.  One workgroup; runs right after the forward kernel on its stream.
+__global__ void __launch_bounds__(kFinishBlock) __attribute__((unused))
+hot_kl_finish_kernel(const double *__restrict__ partials, int count, double *__restrict__ kl_out)
+{
+    __shared__ double lds[kFinishBlock / 64];
+    // Thread t owns the pairs t, t + 1024, t + 2048, ...; eight 16-byte loads are in flight per round
+    // and the values are added in index order.  The buffer holds an even number of slots.
+    typedef double d2 __attribute__((ext_vector_type(2)));
+    const d2 *pairs = reinterpret_cast<const d2 *>(partials);
+    const int n_pairs = (count + 1) / 2;
+    double acc = 0.0;
+    for (int j0 = threadIdx.x; j0 < n_pairs; j0 += kFinishBlock * 8) {
+        d2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = j0 + u * kFinishBlock;
+            v[u] = j < n_pairs ? pairs[j] : d2{0.0, 0.0};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = j0 + u * kFinishBlock;
+            acc += v[u][0];
+            if (2 * j + 1 < count) acc += v[u][1];
+        }
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double total = 0.0;
+#pragma unroll
+        for (int i = 0; i < kFinishBlock / 64; ++i) total += lds[i];
+        *kl_out = 0.5 * total;
+    }
+}
+
+// Makes desc.device current for the lifetime of the object.
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    hipError_t err = hipSuccess;
+    explicit DeviceGuard(int device)
+    {
+        err = hipGetDevice(&prev);
+        if (err == hipSuccess && prev != device) {
+            err = hipSetDevice(device);
+            switched = (err == hipSuccess);
+        }
+    }
+    ~DeviceGuard()
+    {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+inline int fail_hip(hot_plan *p, hipError_t e)
+{
+    if (p) p->last_hip = (int)e;
+    return HOT_EHIP;
+}
+
+inline int pick_unroll(int want, int s_loc)
+{
+    int u = want >= 4 ? 4 : (want >= 2 ? 2 : 1);
+    while (u > 1 && u > s_loc) u >>= 1;
+    return u;
+}
+
+inline bool valid_kernel(int kernel) { return kernel >= HOT_KERNEL_FORWARD && kernel <= HOT_KERNEL_BACKWARD_RNG; }
+
+inline bool valid_launch(const hot_launch &c)
+{
+    auto one_of = [](int v) { return v == 0 || v == 1 || v == 2 || v == 4; };
+    return c.grid_blocks >= 0 && c.grid_blocks <= kMaxGrid && one_of(c.chunks) && one_of(c.unroll) &&
+           (c.nontemporal == 0 || c.nontemporal == 1);
+}
+
+// Number of workgroups: one per column tile, capped by the configured bound.
+inline unsigned grid_for(long n, const hot_launch &c)
+{
+    const long tile = (long)kBlock * 4 * c.chunks;
+    const long tiles = (n + tile - 1) / tile;
+    return (unsigned)(tiles < c.grid_blocks ? tiles : c.grid_blocks);
+}
+
+}  // namespace
+
+#endif  // HOT_SAMPLE_LAYER_H

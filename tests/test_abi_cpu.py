@@ -108,3 +108,23 @@ def test_binding_error_objects(hot):
     with pytest.raises(hot.HotError) as e:
         hot._check(hot.HOT_ENOMEM, "hot_forward")
     assert e.value.code == hot.HOT_ENOMEM and "memory" in str(e.value)
+
+
+def test_device_code_has_no_packed_instructions(tmp_path):
+    """The library is built with packed fp32 arithmetic switched off, and the one kernel version that made
+    the compiler emit a packed move (v_pk_mov_b32, to rotate vectors read from LDS) returned sporadic wrong
+    values on the MI355X: no v_pk_* instruction may appear in the gfx950 code of any source file."""
+    from concurrent.futures import ThreadPoolExecutor
+    import subprocess
+    from paper_2604_04736_amd import build
+
+    def packed(src):
+        out = tmp_path / (os.path.basename(src) + ".s")
+        cmd = [build.HIPCC] + build.FLAGS + ["-S", "--cuda-device-only", "-o", str(out), src]
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert res.returncode == 0, res.stdout[-2000:]
+        return [line.strip() for line in open(out) if re.match(r"\s+v_pk_", line)]
+
+    with ThreadPoolExecutor(max_workers=len(build.SRCS)) as pool:
+        found = dict(zip(build.SRCS, pool.map(packed, build.SRCS)))
+    assert all(not v for v in found.values()), {k: v[:3] for k, v in found.items() if v}

@@ -481,7 +481,8 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
     shapes = {"mlp_fc2_R64_128x128_S4": (64, 128, 128, 4), "swin_fc1_R1_540x2160_S2": (1, 540, 2160, 2),
               "swin_fc1_R64_540x2160_S2": (64, 540, 2160, 2), "swin_fc_R16_2160x8640_S2": (16, 2160, 8640, 2),
               "square_R1_8192x8192_S2": (1, 8192, 8192, 2), "square_R16_8192x8192_S2": (16, 8192, 8192, 2),
-              "square_R64_8192x8192_S2": (64, 8192, 8192, 2), "swin_fc1_R7260_540x2160_S2": (7260, 540, 2160, 2)}
+              "square_R64_8192x8192_S2": (64, 8192, 8192, 2), "swin_fc1_R7260_540x2160_S2": (7260, 540, 2160, 2),
+              "vit_fc1_R16640_192x768_S2": (16640, 192, 768, 2), "square_R1024_8192x8192_S2": (1024, 8192, 8192, 2)}
     for name, (rows, k, o, s) in shapes.items():
         x = torch.randn(rows, k, device=dev)
         mu = torch.randn(o, k, device=dev) * (2.0 / k) ** 0.5

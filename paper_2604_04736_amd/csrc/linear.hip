@@ -171,6 +171,146 @@ hot_linear_forward_kernel(LinearArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------------
+// The same layer for many rows (hundreds and more: a transformer layer's tokens).  In the kernel above
+// every wave draws the weights of its own 16 x 32 tile and uses them for at most 64 rows, so from a few
+// hundred rows on the vector ALUs spend more time drawing than the matrix cores multiplying (the two do
+// not overlap on this chip).  Here the four waves of a workgroup take 64 rows each (256 rows per
+// workgroup) and SHARE every draw through LDS: per iteration of 64 inputs each of the 256 threads draws
+// one quad of the 16-output x 64-input weight tile and stores it in LDS; after one barrier every wave
+// reads its B operands from there (16-byte reads; the 272-byte row pitch spreads the 16 output rows over
+// the banks) and multiplies its own 64 rows: 64 matrix instructions per drawn quad instead of 16.  The
+// LDS tile is double-buffered, so one barrier per iteration suffices: a buffer is overwritten two
+// iterations later, behind the barrier of the iteration in between, which a wave passes only after it
+// has finished reading.  eps, lane roles inside a wave and the order of the contraction index are those
+// of the kernel above (MFMA number i of a 32-input block takes element i of every lane's eight inputs).
+// ---------------------------------------------------------------------------------
+constexpr int kRowsKernelWaves = 4;
+constexpr int kRowsKernelRows = 64 * kRowsKernelWaves;   // rows per workgroup
+constexpr int kRowsKernelInputs = 64;                    // inputs per iteration: one drawn quad per thread
+constexpr int kRowsKernelPitch = kRowsKernelInputs + 4;  // floats per output row of the LDS tile
+
+template <int ST, int NO, bool XS>
+__global__ void __launch_bounds__(64 * kRowsKernelWaves)
+hot_linear_forward_rows_kernel(LinearArgs a)
+{
+    // NO column tiles of 16 outputs per workgroup.  More tiles reuse every loaded row of x more often but
+    // cost accumulators: with two samples in flight one tile is fastest (86-90 TFLOP/s on 4096^3 and
+    // 8192^2 x 1024; two and four tiles leave one wave per SIMD and reach 75-90), a single sample affords two
+    // tiles (81 against 64 TFLOP/s).
+    __shared__ __attribute__((aligned(16))) float tile[2][ST][NO * 16 * kRowsKernelPitch];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, j = lane >> 4;
+    const long K = a.in_features, O = a.out_features, R = a.rows;
+    const long o0 = (long)blockIdx.x * (kColsPerWave * NO);
+    const long r0 = (long)blockIdx.y * kRowsKernelRows + (long)wave * 64;
+    // as a drawing thread: quad dq of the 16 quads of outputs o0 + dn, o0 + dn + 16, ... in every iteration
+    const int dn = (int)threadIdx.x >> 4, dq = (int)threadIdx.x & 15;
+
+    for (int s0 = 0; s0 < a.s_loc; s0 += ST) {
+        f4 acc[ST][4][NO];
+#pragma unroll
+        for (int st = 0; st < ST; ++st)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                for (int no = 0; no < NO; ++no) acc[st][rb][no] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+
+        int buf = 0;
+        for (long kb = 0; kb < K; kb += kRowsKernelInputs, buf ^= 1) {
+            // this wave's rows of x (shared input): row 16 rb + n, inputs kb + 32 blk + 8 j + 4 h .. + 3
+            f4 xa[4][2][2];
+            if constexpr (!XS) {
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            const long row = r0 + kRowsPerTile * rb + n, k = kb + 32 * blk + 8 * j + 4 * h;
+                            xa[rb][blk][h] = (row < R && k < K) ? load4<true, false>(a.x + row * a.ldx + k) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+                        }
+            }
+            // draw this thread's quads for every sample of the chunk and put them into the tile
+            const long kd = kb + 4 * dq;
+#pragma unroll
+            for (int no = 0; no < NO; ++no) {
+                const long o_draw = o0 + 16 * no + dn;
+                const bool draw_ok = o_draw < O && kd < K;
+                const f4 m4 = draw_ok ? load4<true, false>(a.mu_w + o_draw * K + kd) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+                const f4 sd4 = draw_ok ? load4<true, false>(a.sigma_w + o_draw * K + kd) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int st = 0; st < ST; ++st) {
+                    f4 w4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (draw_ok && s0 + st < a.s_loc) {
+                        const f4 e = eps_quad(a.weight_quad0 + ((o_draw * K + kd) >> 2), s0 + st, a.rng);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) w4[c] = __builtin_fmaf(sd4[c], e[c], m4[c]);
+                    }
+                    *reinterpret_cast<f4 *>(&tile[buf][st][(16 * no + dn) * kRowsKernelPitch + 4 * dq]) = w4;
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int st = 0; st < ST; ++st) {
+                if (s0 + st < a.s_loc) {          // uniform over the workgroup
+                    if constexpr (XS) {
+                        const float *xs = a.x + (size_t)(s0 + st) * (size_t)a.x_sample_stride;
+#pragma unroll
+                        for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                                for (int h = 0; h < 2; ++h) {
+                                    const long row = r0 + kRowsPerTile * rb + n, k = kb + 32 * blk + 8 * j + 4 * h;
+                                    xa[rb][blk][h] = (row < R && k < K) ? load4<true, false>(xs + row * a.ldx + k) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+                                }
+                    }
+#pragma unroll
+                    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                        for (int h = 0; h < 2; ++h)
+#pragma unroll
+                            for (int no = 0; no < NO; ++no) {
+                                const f4 wq = *reinterpret_cast<const f4 *>(&tile[buf][st][(16 * no + n) * kRowsKernelPitch + 32 * blk + 8 * j + 4 * h]);
+#pragma unroll
+                                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                                    for (int rb = 0; rb < 4; ++rb)
+                                        acc[st][rb][no] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[rb][blk][h][c], wq[c], acc[st][rb][no], 0, 0, 0);
+                            }
+                }
+            }
+        }
+        __syncthreads();        // the chunk's last reads are done before the next chunk's first draw lands in buffer 0
+
+#pragma unroll
+        for (int st = 0; st < ST; ++st) {
+            if (s0 + st < a.s_loc) {
+#pragma unroll
+                for (int no = 0; no < NO; ++no) {
+                    const long o = o0 + 16 * no + n;
+                    const bool o_ok = o < O;
+                    float bias = 0.0f;
+                    if (a.mu_b && o_ok) {
+                        const f4 e = eps_quad(a.bias_quad0 + (o >> 2), s0 + st, a.rng);
+                        const int c = (int)(o & 3);
+                        const float ev = c == 0 ? e[0] : (c == 1 ? e[1] : (c == 2 ? e[2] : e[3]));
+                        bias = __builtin_fmaf(a.sigma_b[o], ev, a.mu_b[o]);
+                    }
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const long row = r0 + kRowsPerTile * rb + 4 * j + r;
+                            if (row < R && o_ok) a.y[((size_t)(s0 + st) * (size_t)R + (size_t)row) * (size_t)O + (size_t)o] = acc[st][rb][no][r] + bias;
+                        }
+                }
+            }
+        }
+    }
+}
+
 template <int RB, bool XS>
 void linear_go_st(int st, dim3 grid, int waves, hipStream_t s, const LinearArgs &a)
 {
@@ -498,6 +638,23 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     a.y = y;
     a.rng = r;
 
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // Many rows (from 256) and at least 128 workgroups of 256 rows: the kernel whose waves share every draw
+    // through LDS (measured against the kernel above: 1.05-1.4x from there on, slower below).  Two samples per
+    // pass and one column tile when there are several samples; a single sample affords two column tiles.
+    {
+        const bool xs = d->x_sample_stride != 0;
+        const int no = (d->s_local == 1 && !xs) ? 2 : 1;
+        const long gx = (d->out_features + kColsPerWave * no - 1) / (kColsPerWave * no);
+        const long gy = (d->rows + kRowsKernelRows - 1) / kRowsKernelRows;
+        if (d->rows >= 256 && gx * gy >= 128 && gx <= 0x7fffffffL && gy <= 65535) {
+            const dim3 grid((unsigned)gx, (unsigned)gy), block(64 * kRowsKernelWaves);
+            if (xs) hot_linear_forward_rows_kernel<1, 1, true><<<grid, block, 0, s>>>(a);
+            else if (no == 2) hot_linear_forward_rows_kernel<1, 2, false><<<grid, block, 0, s>>>(a);
+            else hot_linear_forward_rows_kernel<2, 1, false><<<grid, block, 0, s>>>(a);
+            return hot_detail::note_hip(hipGetLastError());
+        }
+    }
     // rows per workgroup: 16, 32 or 64 (one, two or four MFMA row tiles share every drawn weight)
     const int rb = d->rows > 32 ? 4 : (d->rows > 16 ? 2 : 1);
     // samples whose accumulators are live together (they share the loads of mu_W, sigma_W and x)
@@ -513,7 +670,6 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
            (size_t)(2 * waves - 1) * (size_t)(st * rb * 4) * 64 * sizeof(float) <= 65536)
         waves *= 2;
     const dim3 grid((unsigned)gx, (unsigned)gy);
-    hipStream_t s = static_cast<hipStream_t>(stream);
     if (rb == 4) linear_go<4>(st, grid, waves, s, a);
     else if (rb == 2) linear_go<2>(st, grid, waves, s, a);
     else linear_go<1>(st, grid, waves, s, a);

@@ -71,7 +71,10 @@ def _check(oracle, c, y, s, rng, w_off, b_off, bias=True):
 # (rows, in, out, samples): the paper's MLP, ViT and SWIN layer shapes and edge cases
 SHAPES = [(64, 96, 128, 4), (64, 128, 24, 4), (65, 192, 576, 4), (256, 192, 10, 4), (1, 540, 2160, 2),
           (8, 540, 2160, 2), (64, 2160, 540, 2), (130, 768, 192, 16), (1, 4, 1, 1), (17, 36, 33, 3), (33, 100, 70, 5),
-          (16, 32, 64, 1), (200, 64, 16, 2)]
+          (16, 32, 64, 1), (200, 64, 16, 2),
+          # 256 rows and more on at least 128 workgroups: the kernel whose waves share the draws through LDS
+          # (two samples per pass; an odd sample count; one sample with two column tiles; ragged everything)
+          (300, 64, 2100, 2), (1030, 36, 2050, 3), (260, 100, 4100, 1), (513, 132, 2049, 5)]
 
 
 @pytest.mark.parametrize("rows,k,o,s", SHAPES)
@@ -123,7 +126,8 @@ def test_layer_sees_the_w_of_hot_forward_rng(hot):
 
 
 # (rows, in, out, samples): every row-tile count, sample-chunk size and a ragged everything
-PER_SAMPLE = [(1, 8, 3, 2), (16, 128, 128, 4), (17, 36, 33, 5), (33, 100, 70, 3), (64, 128, 24, 16), (70, 64, 40, 2), (256, 192, 10, 1)]
+PER_SAMPLE = [(1, 8, 3, 2), (16, 128, 128, 4), (17, 36, 33, 5), (33, 100, 70, 3), (64, 128, 24, 16), (70, 64, 40, 2), (256, 192, 10, 1),
+              (257, 68, 2064, 2), (700, 40, 2100, 3)]      # the many-rows kernel with one input per sample
 
 
 @pytest.mark.parametrize("rows,k,o,s", PER_SAMPLE)

@@ -333,10 +333,11 @@ void linear_go(int st, dim3 grid, int waves, hipStream_t s, const LinearArgs &a)
 
 // ---------------------------------------------------------------------------------
 // Backward.  Weight gradients: a wave owns 16 outputs x 64 inputs and contracts over the rows with
-// the TRANSPOSED product P_s[k][o] = sum_r x_s[r][k] dy_s[r][o] (x as the A operand, dy as B), so
-// that the four accumulator registers of a lane are four consecutive inputs k of one output o:
-// exactly one quad of the generator, drawn once per sample, and one 16-byte access to mu, sigma
-// and the two gradient arrays.  Input gradients: dx_s^T[k][r] = sum_o W_s[o][k] dy_s[r][o] with
+// the TRANSPOSED product P_s[k][o] = sum_r x_s[r][k] dy_s[r][o] (x as the A operand, dy as B).  A lane
+// loads four consecutive inputs of a row of x at once and hands element i to matrix instruction i, so
+// that register c of the four accumulators holds four consecutive inputs k of one output o: exactly one
+// quad of the generator, drawn once per sample, and one 16-byte access to mu, sigma and the two
+// gradient arrays.  Input gradients: dx_s^T[k][r] = sum_o W_s[o][k] dy_s[r][o] with
 // the drawn weights as the A operand; MFMA number i of a step takes element i of every lane's
 // quad (as in the forward kernel), so result register rr of the four accumulators again holds
 // four consecutive inputs and dx is written with 16-byte stores.
@@ -391,50 +392,52 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
     const long row_first = SPLIT ? (long)wave * kWgradRowsPerIter : 0;
     const long row_step = SPLIT ? (long)waves * kWgradRowsPerIter : kWgradRowsPerIter;
 
+    // gm[t], gs[t]: the sums for the generator quad of inputs k0 + 16 j + 4 t .. + 3 of output o
     f4 gm[4], gs[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) gm[t] = gs[t] = f4{0.0f, 0.0f, 0.0f, 0.0f};
     float gb_m = 0.0f, gb_s = 0.0f;
+    const long k_lane = k0 + 4 * n;          // as an A lane: the four inputs k_lane .. k_lane + 3 of a row, one 16-byte load
+    const bool k_lane_ok = k_lane < K;
 
     for (int s = 0; s < a.s_loc; ++s) {
         const float *xs = a.x + (size_t)s * (size_t)a.x_sample_stride;
         const float *dys = a.dy + (size_t)s * (size_t)R * (size_t)O;
+        // matrix instruction i of a row block takes element i of every lane's four inputs, so P[i] collects
+        // the inputs k0 + 4 m + i (m = 0..15) and register c of P[i] is input k0 + 16 j + 4 c + i: the four
+        // P[.][c] are the four consecutive inputs of one generator quad
         f4 P[4], Pb = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int t = 0; t < 4; ++t) P[t] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int i = 0; i < 4; ++i) P[i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
         for (long rb = row_first; rb < R; rb += row_step) {
-            float bv[kWgradRowsPerIter / 4], av[kWgradRowsPerIter / 4][4];
+            float bv[kWgradRowsPerIter / 4];
+            f4 av[kWgradRowsPerIter / 4];
 #pragma unroll
             for (int q = 0; q < kWgradRowsPerIter / 4; ++q) {
                 const long r = rb + 4 * q + j;
                 const bool r_ok = r < R;
                 bv[q] = (r_ok && o_ok) ? dys[r * O + o] : 0.0f;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const long kk = k0 + 16 * t + n;
-                    av[q][t] = (r_ok && kk < K) ? xs[r * a.ldx + kk] : 0.0f;
-                }
+                av[q] = (r_ok && k_lane_ok) ? load4<true, false>(xs + r * a.ldx + k_lane) : f4{0.0f, 0.0f, 0.0f, 0.0f};
             }
 #pragma unroll
             for (int q = 0; q < kWgradRowsPerIter / 4; ++q)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) P[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q][t], bv[q], P[t], 0, 0, 0);
+                for (int i = 0; i < 4; ++i) P[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q][i], bv[q], P[i], 0, 0, 0);
             if (bias_tile) {             // column sums of dy: the same contraction against ones
 #pragma unroll
                 for (int q = 0; q < kWgradRowsPerIter / 4; ++q) Pb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, bv[q], Pb, 0, 0, 0);
             }
         }
-        // register c of P[t] is input k0 + 16 t + 4 j + c of output o
         if (row_first < R) {             // a wave without rows has nothing to add (uniform over the wave)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const long col = k0 + 16 * t + 4 * j;
+                const long col = k0 + 16 * j + 4 * t;
                 if (o_ok && col < K) {
                     const f4 e = eps_quad(a.weight_quad0 + ((o * K + col) >> 2), s, a.rng);
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
-                        gm[t][c] += P[t][c];
-                        gs[t][c] = __builtin_fmaf(P[t][c], e[c], gs[t][c]);
+                        gm[t][c] += P[c][t];
+                        gs[t][c] = __builtin_fmaf(P[c][t], e[c], gs[t][c]);
                     }
                 }
             }
@@ -474,6 +477,41 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
         }
     }
 
+    // A lane holds the 16 consecutive inputs k0 + 16 j .. + 15 of its output; stored like that, every store
+    // instruction of the wave would put four separate 16-byte pieces into each row.  The four lanes of an
+    // output therefore exchange quads first (a 4 x 4 transpose over j, in four rounds of lane shuffles), so
+    // that store t covers the 64 contiguous bytes k0 + 16 t .. + 15 of every row.
+    {
+        f4 tm[4], ts[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int give = (j - d) & 3, from = (((j + d) & 3) << 4) | n, slot = (j + d) & 3;
+            f4 vm = gm[0], vs = gs[0];
+#pragma unroll
+            for (int q = 1; q < 4; ++q)
+                if (give == q) {
+                    vm = gm[q];
+                    vs = gs[q];
+                }
+            f4 rm, rs;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                rm[c] = __shfl(vm[c], from);
+                rs[c] = __shfl(vs[c], from);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (slot == q) {
+                    tm[q] = rm;
+                    ts[q] = rs;
+                }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            gm[t] = tm[t];
+            gs[t] = ts[t];
+        }
+    }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const long col = k0 + 16 * t + 4 * j;

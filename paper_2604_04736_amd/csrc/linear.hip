@@ -354,6 +354,32 @@ struct LinearGradArgs {
 
 __device__ __forceinline__ float pick4(f4 v, int c) { return c == 0 ? v[0] : (c == 1 ? v[1] : (c == 2 ? v[2] : v[3])); }
 
+// The four lanes (j = 0..3, same n) of a 16-lane column each hold four quads q[0..3], lane j's quad t
+// belonging to position 16 j + 4 t of a 64-wide block.  Afterwards lane j's quad t belongs to position
+// 16 t + 4 j: a store of quad t then covers 64 contiguous bytes per 16-lane column instead of four separate
+// 16-byte pieces (the memory system wants whole 64-byte words).  A 4 x 4 transpose over j in four rounds of
+// lane shuffles; every lane of the wave must call it.
+__device__ __forceinline__ void transpose_quads_over_j(f4 (&q)[4], int j, int n)
+{
+    f4 out[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const int give = (j - d) & 3, from = (((j + d) & 3) << 4) | n, slot = (j + d) & 3;
+        f4 v = q[0];
+#pragma unroll
+        for (int t = 1; t < 4; ++t)
+            if (give == t) v = q[t];
+        f4 r;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) r[c] = __shfl(v[c], from);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (slot == t) out[t] = r;
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) q[t] = out[t];
+}
+
 // grad_mu, grad_sigma of one parameter from its sums over the samples (gradient and averaging lines
 // of Algorithm 2; d KL / d mu = mu, d KL / d sigma = sigma - 1/sigma)
 __device__ __forceinline__ void finish_pair(float sum_g, float sum_ge, float m, float sd, double g, double k,
@@ -477,41 +503,10 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
         }
     }
 
-    // A lane holds the 16 consecutive inputs k0 + 16 j .. + 15 of its output; stored like that, every store
-    // instruction of the wave would put four separate 16-byte pieces into each row.  The four lanes of an
-    // output therefore exchange quads first (a 4 x 4 transpose over j, in four rounds of lane shuffles), so
-    // that store t covers the 64 contiguous bytes k0 + 16 t .. + 15 of every row.
-    {
-        f4 tm[4], ts[4];
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const int give = (j - d) & 3, from = (((j + d) & 3) << 4) | n, slot = (j + d) & 3;
-            f4 vm = gm[0], vs = gs[0];
-#pragma unroll
-            for (int q = 1; q < 4; ++q)
-                if (give == q) {
-                    vm = gm[q];
-                    vs = gs[q];
-                }
-            f4 rm, rs;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                rm[c] = __shfl(vm[c], from);
-                rs[c] = __shfl(vs[c], from);
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (slot == q) {
-                    tm[q] = rm;
-                    ts[q] = rs;
-                }
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            gm[t] = tm[t];
-            gs[t] = ts[t];
-        }
-    }
+    // A lane holds the 16 consecutive inputs k0 + 16 j .. + 15 of its output: the four lanes of an output
+    // exchange quads so that store t covers the 64 contiguous bytes k0 + 16 t .. + 15 of every row.
+    transpose_quads_over_j(gm, j, n);
+    transpose_quads_over_j(gs, j, n);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const long col = k0 + 16 * t + 4 * j;
@@ -616,16 +611,20 @@ hot_linear_xgrad_kernel(LinearGradArgs a)
     }
     if (wave != 0) return;
 
-    // register rr of accumulator i is input k0 + 16 j + 4 rr + i of row r0 + 16 rb + n
+    // register rr of accumulator i is input k0 + 16 j + 4 rr + i of row r0 + 16 rb + n; the lanes of a row
+    // exchange quads so that each store covers 64 contiguous bytes of the row
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const long row = r0 + kRowsPerTile * rb + n;
+        f4 q[4];
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const long col = k0 + 16 * j + 4 * rr;
+        for (int rr = 0; rr < 4; ++rr) q[rr] = f4{acc[rb][0][rr], acc[rb][1][rr], acc[rb][2][rr], acc[rb][3][rr]};
+        transpose_quads_over_j(q, j, n);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const long col = k0 + 16 * t + 4 * j;
             if (row < R && col < K)
-                store4<true, false>(a.dx + ((size_t)s * (size_t)R + (size_t)row) * (size_t)K + (size_t)col,
-                                    f4{acc[rb][0][rr], acc[rb][1][rr], acc[rb][2][rr], acc[rb][3][rr]});
+                store4<true, false>(a.dx + ((size_t)s * (size_t)R + (size_t)row) * (size_t)K + (size_t)col, q[t]);
         }
     }
 }

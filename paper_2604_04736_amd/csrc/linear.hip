@@ -394,24 +394,42 @@ __device__ __forceinline__ void finish_pair(float sum_g, float sum_ge, float m, 
 constexpr int kWgradWaves = 4;       // waves per workgroup when every wave has a tile of its own
 constexpr int kWgradMaxSplit = 8;    // most waves that share one tile (60 KiB of LDS for their partial sums)
 constexpr int kWgradRowsPerIter = 16;
+constexpr int kWgradDeepRows = 128;  // from this many rows on operands are prefetched one row block ahead
 constexpr int kWgradPartials = 34;   // per lane: 16 + 16 weight-gradient sums and the two bias sums
 
 // SPLIT = false: the four waves of a workgroup own one tile each.  SPLIT = true (layers with few
 // tiles and many rows): the waves of a workgroup share one tile, take the 16-row blocks round-robin,
 // apply each sample's eps to their own partial product (the gradient is linear in it) and add their
-// sums through LDS in wave order at the end.
-template <bool SPLIT>
+// sums through LDS in wave order at the end.  DEEP (many rows): operands of the next row block are
+// fetched while the current one multiplies; it costs a wave per SIMD, which the few-row shapes need more.
+//
+// Workgroups go to the eight XCDs round-robin and each XCD has an L2 of its own, so the tiles are dealt
+// out by XCD: the list of tiles, ordered so that the larger of the two operands changes slowest (output
+// groups outermost when O >= K: dy is the larger one; input groups outermost otherwise), is cut into eight
+// contiguous ranges, one per XCD.  The larger operand then enters one L2 only (two at a range boundary) and
+// the smaller one each L2 once, where the plain order had every XCD stream both (40 % L2 misses at 7260
+// rows).  Only locality depends on the round-robin placement, not the result.
+constexpr int kXcds = 8;
+
+template <bool SPLIT, bool DEEP>
 __global__ void __launch_bounds__(64 * (SPLIT ? kWgradMaxSplit : kWgradWaves))
 hot_linear_wgrad_kernel(LinearGradArgs a)
 {
     extern __shared__ float partial[];   // SPLIT: [waves - 1][kWgradPartials][64]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, waves = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: tile and trip counts stay scalar
     const int n = lane & 15, j = lane >> 4;
     const long K = a.in_features, O = a.out_features, R = a.rows;
     const long k_groups = (K + 63) / 64;
-    const long tile = SPLIT ? (long)blockIdx.x : (long)blockIdx.x * kWgradWaves + wave;
-    if (tile >= k_groups * ((O + 15) / 16)) return;      // SPLIT: never taken (one workgroup per tile); else a whole wave, and no barrier follows
-    const long o0 = (tile / k_groups) * 16, k0 = (tile % k_groups) * 64;
+    const long o_groups = (O + 15) / 16, tiles = k_groups * o_groups, per_xcd = (tiles + kXcds - 1) / kXcds;
+    const long xcd = blockIdx.x % kXcds, nth = blockIdx.x / kXcds;      // nth workgroup of its XCD
+    const long local = SPLIT ? nth : nth * kWgradWaves + wave;
+    const long tile = xcd * per_xcd + local;
+    // no such tile: a whole workgroup (SPLIT) or a whole wave of a kernel without barriers leaves
+    if (local >= per_xcd || tile >= tiles) return;
+    const bool outputs_outermost = O >= K;
+    const long o0 = (outputs_outermost ? tile / k_groups : tile % o_groups) * 16;
+    const long k0 = (outputs_outermost ? tile % k_groups : tile / o_groups) * 64;
     const long o = o0 + n;
     const bool o_ok = o < O;
     const bool bias_tile = a.mu_b != nullptr && k0 == 0;     // uniform over the wave: this tile also owns 16 biases
@@ -435,23 +453,97 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
         f4 P[4], Pb = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int i = 0; i < 4; ++i) P[i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-        for (long rb = row_first; rb < R; rb += row_step) {
-            float bv[kWgradRowsPerIter / 4];
-            f4 av[kWgradRowsPerIter / 4];
+        // Whole blocks of 16 rows first, with nothing in the loop but the loads, eight offset increments and the
+        // matrix instructions: lanes outside the layer (o >= O, inputs >= K) read a valid address instead, which
+        // only reaches rows and columns of P that are never stored.  The last, partial block is predicated per
+        // row: rows beyond R must contribute zeros, they are summed over.
+        constexpr int Q = kWgradRowsPerIter / 4;
+        long pd[Q], px[Q];      // offsets, not pointers: the loads stay global loads
 #pragma unroll
-            for (int q = 0; q < kWgradRowsPerIter / 4; ++q) {
-                const long r = rb + 4 * q + j;
-                const bool r_ok = r < R;
-                bv[q] = (r_ok && o_ok) ? dys[r * O + o] : 0.0f;
-                av[q] = (r_ok && k_lane_ok) ? load4<true, false>(xs + r * a.ldx + k_lane) : f4{0.0f, 0.0f, 0.0f, 0.0f};
-            }
+        for (int q = 0; q < Q; ++q) {
+            pd[q] = (row_first + 4 * q + j) * O + (o_ok ? o : O - 1);
+            px[q] = (row_first + 4 * q + j) * a.ldx + (k_lane_ok ? k_lane : 0);
+        }
+        const long d_step = row_step * O, x_step = row_step * a.ldx;
+        const long full = R - row_first >= kWgradRowsPerIter ? (R - kWgradRowsPerIter - row_first) / row_step + 1 : 0;
+        auto multiply = [&](const float (&bv)[Q], const f4 (&av)[Q]) {
 #pragma unroll
-            for (int q = 0; q < kWgradRowsPerIter / 4; ++q)
+            for (int q = 0; q < Q; ++q)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) P[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q][i], bv[q], P[i], 0, 0, 0);
             if (bias_tile) {             // column sums of dy: the same contraction against ones
 #pragma unroll
-                for (int q = 0; q < kWgradRowsPerIter / 4; ++q) Pb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, bv[q], Pb, 0, 0, 0);
+                for (int q = 0; q < Q; ++q) Pb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, bv[q], Pb, 0, 0, 0);
+            }
+        };
+        if constexpr (DEEP) {
+            // Two register sets of operands.  Every fetch is unconditional (behind a branch around loads the
+            // compiler waits for all of them at the join): past the last whole block the offsets stop moving
+            // and that block is simply read again.
+            float bA[Q], bB[Q];
+            f4 aA[Q], aB[Q];
+            long fetched = 0;
+            auto fetch = [&](float (&bv)[Q], f4 (&av)[Q]) {
+                ++fetched;
+                const long dd = fetched < full ? d_step : 0, dx = fetched < full ? x_step : 0;
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    bv[q] = dys[pd[q]];
+                    av[q] = load4<true, false>(xs + px[q]);
+                    pd[q] += dd;
+                    px[q] += dx;
+                }
+            };
+            if (full > 0) {
+                fetch(bA, aA);
+                for (long it = 0; it < full; it += 2) {
+                    fetch(bB, aB);
+                    __builtin_amdgcn_sched_barrier(0);
+                    multiply(bA, aA);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fetch(bA, aA);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (it + 1 < full) multiply(bB, aB);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {        // on to the partial block
+                    pd[q] += d_step;
+                    px[q] += x_step;
+                }
+            }
+        } else {
+            for (long it = 0; it < full; ++it) {
+                float bv[Q];
+                f4 av[Q];
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    bv[q] = dys[pd[q]];
+                    av[q] = load4<true, false>(xs + px[q]);
+                    pd[q] += d_step;
+                    px[q] += x_step;
+                }
+                __builtin_amdgcn_sched_barrier(0);      // all eight loads first, one wait
+                multiply(bv, av);
+            }
+        }
+        const long rb = row_first + full * row_step;
+        if (rb < R) {
+            float bv[Q];
+            f4 av[Q];
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const bool r_ok = rb + 4 * q + j < R;
+                bv[q] = r_ok ? dys[pd[q]] : 0.0f;
+                av[q] = r_ok ? load4<true, false>(xs + px[q]) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) P[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q][i], bv[q], P[i], 0, 0, 0);
+            if (bias_tile) {
+#pragma unroll
+                for (int q = 0; q < Q; ++q) Pb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, bv[q], Pb, 0, 0, 0);
             }
         }
         if (row_first < R) {             // a wave without rows has nothing to add (uniform over the wave)
@@ -780,16 +872,25 @@ int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double da
 
     const long k_groups = (d->in_features + 63) / 64;
     const long tiles = k_groups * ((d->out_features + kColsPerWave - 1) / kColsPerWave);
-    if (tiles > 0x7fffffffL) return HOT_EINVAL;
+    if (tiles > 0x7fffff00L) return HOT_EINVAL;      // the grid may exceed the number of tiles by a few workgroups
     // few tiles and many rows: let several waves share a tile (each then draws the tile's eps itself)
     int split = 1;
-    while (split < kWgradMaxSplit && tiles * split < 2048 && d->rows >= 2L * split * kWgradRowsPerIter) split *= 2;
+    // (up to a wave on every SIMD twice over; beyond that only while a wave keeps a thousand rows: finer pieces
+    // even out the last round of waves, but every piece draws eps and adds through LDS again)
+    while (split < kWgradMaxSplit && d->rows >= 2L * split * kWgradRowsPerIter &&
+           (tiles * split < 2048 || (tiles * split < 6144 && d->rows >= 1024L * split)))
+        split *= 2;
+    const long per_xcd = (tiles + kXcds - 1) / kXcds;      // the kernel deals the tiles out by XCD
+    const bool deep = d->rows >= kWgradDeepRows;
     if (split > 1) {
         const size_t lds = (size_t)(split - 1) * kWgradPartials * 64 * sizeof(float);
-        hot_linear_wgrad_kernel<true><<<dim3((unsigned)tiles), dim3(64 * split), lds, s>>>(a);
+        const dim3 grid((unsigned)(kXcds * per_xcd)), block(64 * split);
+        if (deep) hot_linear_wgrad_kernel<true, true><<<grid, block, lds, s>>>(a);
+        else hot_linear_wgrad_kernel<true, false><<<grid, block, lds, s>>>(a);
     } else {
-        const long wg = (tiles + kWgradWaves - 1) / kWgradWaves;
-        hot_linear_wgrad_kernel<false><<<dim3((unsigned)wg), dim3(64 * kWgradWaves), 0, s>>>(a);
+        const dim3 grid((unsigned)(kXcds * ((per_xcd + kWgradWaves - 1) / kWgradWaves))), block(64 * kWgradWaves);
+        if (deep) hot_linear_wgrad_kernel<false, true><<<grid, block, 0, s>>>(a);
+        else hot_linear_wgrad_kernel<false, false><<<grid, block, 0, s>>>(a);
     }
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return hot_detail::note_hip(e);
     if (!dx) return HOT_OK;

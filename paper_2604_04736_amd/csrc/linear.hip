@@ -395,6 +395,7 @@ constexpr int kWgradWaves = 4;       // waves per workgroup when every wave has 
 constexpr int kWgradMaxSplit = 8;    // most waves that share one tile (60 KiB of LDS for their partial sums)
 constexpr int kWgradRowsPerIter = 16;
 constexpr int kWgradDeepRows = 128;  // from this many rows on operands are prefetched one row block ahead
+constexpr int kWgradWideRows = 512;  // from this many rows on a wave may own several output groups
 constexpr int kWgradPartials = 34;   // per lane: 16 + 16 weight-gradient sums and the two bias sums
 
 // SPLIT = false: the four waves of a workgroup own one tile each.  SPLIT = true (layers with few
@@ -402,6 +403,9 @@ constexpr int kWgradPartials = 34;   // per lane: 16 + 16 weight-gradient sums a
 // apply each sample's eps to their own partial product (the gradient is linear in it) and add their
 // sums through LDS in wave order at the end.  DEEP (many rows): operands of the next row block are
 // fetched while the current one multiplies; it costs a wave per SIMD, which the few-row shapes need more.
+// OB: 16-output groups per tile.  At many rows the kernel is bound by the 16-byte loads of x (with them
+// taken out it runs at 100-119 TFLOP/s instead of 60-80, with the loads of dy taken out nothing changes);
+// two output groups per wave use every loaded quad of x twice.
 //
 // Workgroups go to the eight XCDs round-robin and each XCD has an L2 of its own, so the tiles are dealt
 // out by XCD: the list of tiles, ordered so that the larger of the two operands changes slowest (output
@@ -411,86 +415,110 @@ constexpr int kWgradPartials = 34;   // per lane: 16 + 16 weight-gradient sums a
 // rows).  Only locality depends on the round-robin placement, not the result.
 constexpr int kXcds = 8;
 
-template <bool SPLIT, bool DEEP>
-__global__ void __launch_bounds__(64 * (SPLIT ? kWgradMaxSplit : kWgradWaves))
+constexpr int wgrad_max_split(int ob) { return kWgradMaxSplit / ob; }   // at most 60 KiB of LDS
+
+template <bool SPLIT, bool DEEP, int OB>
+__global__ void __launch_bounds__(64 * (SPLIT ? wgrad_max_split(OB) : kWgradWaves), 1)
 hot_linear_wgrad_kernel(LinearGradArgs a)
 {
-    extern __shared__ float partial[];   // SPLIT: [waves - 1][kWgradPartials][64]
+    extern __shared__ float partial[];   // SPLIT: [waves - 1][OB][kWgradPartials][64]
     const int lane = threadIdx.x & 63, waves = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: tile and trip counts stay scalar
     const int n = lane & 15, j = lane >> 4;
     const long K = a.in_features, O = a.out_features, R = a.rows;
     const long k_groups = (K + 63) / 64;
-    const long o_groups = (O + 15) / 16, tiles = k_groups * o_groups, per_xcd = (tiles + kXcds - 1) / kXcds;
+    const long o_tiles = ((O + 15) / 16 + OB - 1) / OB, tiles = k_groups * o_tiles, per_xcd = (tiles + kXcds - 1) / kXcds;
     const long xcd = blockIdx.x % kXcds, nth = blockIdx.x / kXcds;      // nth workgroup of its XCD
     const long local = SPLIT ? nth : nth * kWgradWaves + wave;
     const long tile = xcd * per_xcd + local;
     // no such tile: a whole workgroup (SPLIT) or a whole wave of a kernel without barriers leaves
     if (local >= per_xcd || tile >= tiles) return;
     const bool outputs_outermost = O >= K;
-    const long o0 = (outputs_outermost ? tile / k_groups : tile % o_groups) * 16;
-    const long k0 = (outputs_outermost ? tile % k_groups : tile / o_groups) * 64;
-    const long o = o0 + n;
-    const bool o_ok = o < O;
-    const bool bias_tile = a.mu_b != nullptr && k0 == 0;     // uniform over the wave: this tile also owns 16 biases
+    const long o0 = (outputs_outermost ? tile / k_groups : tile % o_tiles) * (16 * OB);
+    const long k0 = (outputs_outermost ? tile % k_groups : tile / o_tiles) * 64;
+    long o[OB];
+    bool o_ok[OB];
+#pragma unroll
+    for (int b = 0; b < OB; ++b) {
+        o[b] = o0 + 16 * b + n;
+        o_ok[b] = o[b] < O;
+    }
+    const bool bias_tile = a.mu_b != nullptr && k0 == 0;     // uniform over the wave: this tile also owns its outputs' biases
     const long row_first = SPLIT ? (long)wave * kWgradRowsPerIter : 0;
     const long row_step = SPLIT ? (long)waves * kWgradRowsPerIter : kWgradRowsPerIter;
 
-    // gm[t], gs[t]: the sums for the generator quad of inputs k0 + 16 j + 4 t .. + 3 of output o
-    f4 gm[4], gs[4];
+    // gm[b][t], gs[b][t]: the sums for the generator quad of inputs k0 + 16 j + 4 t .. + 3 of output o[b]
+    f4 gm[OB][4], gs[OB][4];
+    float gb_m[OB], gb_s[OB];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) gm[t] = gs[t] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-    float gb_m = 0.0f, gb_s = 0.0f;
+    for (int b = 0; b < OB; ++b) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) gm[b][t] = gs[b][t] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+        gb_m[b] = gb_s[b] = 0.0f;
+    }
     const long k_lane = k0 + 4 * n;          // as an A lane: the four inputs k_lane .. k_lane + 3 of a row, one 16-byte load
     const bool k_lane_ok = k_lane < K;
 
     for (int s = 0; s < a.s_loc; ++s) {
         const float *xs = a.x + (size_t)s * (size_t)a.x_sample_stride;
         const float *dys = a.dy + (size_t)s * (size_t)R * (size_t)O;
-        // matrix instruction i of a row block takes element i of every lane's four inputs, so P[i] collects
-        // the inputs k0 + 4 m + i (m = 0..15) and register c of P[i] is input k0 + 16 j + 4 c + i: the four
-        // P[.][c] are the four consecutive inputs of one generator quad
-        f4 P[4], Pb = {0.0f, 0.0f, 0.0f, 0.0f};
+        // matrix instruction i of a row block takes element i of every lane's four inputs, so P[.][i] collects
+        // the inputs k0 + 4 m + i (m = 0..15) and register c of P[.][i] is input k0 + 16 j + 4 c + i: the four
+        // P[.][.][c] are the four consecutive inputs of one generator quad
+        f4 P[OB][4], Pb[OB];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) P[i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-        // Whole blocks of 16 rows first, with nothing in the loop but the loads, eight offset increments and the
+        for (int b = 0; b < OB; ++b) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) P[b][i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+            Pb[b] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+        // Whole blocks of 16 rows first, with nothing in the loop but the loads, the offset increments and the
         // matrix instructions: lanes outside the layer (o >= O, inputs >= K) read a valid address instead, which
         // only reaches rows and columns of P that are never stored.  The last, partial block is predicated per
         // row: rows beyond R must contribute zeros, they are summed over.
         constexpr int Q = kWgradRowsPerIter / 4;
-        long pd[Q], px[Q];      // offsets, not pointers: the loads stay global loads
+        long pd[OB][Q], px[Q];      // offsets, not pointers: the loads stay global loads
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            pd[q] = (row_first + 4 * q + j) * O + (o_ok ? o : O - 1);
+#pragma unroll
+            for (int b = 0; b < OB; ++b) pd[b][q] = (row_first + 4 * q + j) * O + (o_ok[b] ? o[b] : O - 1);
             px[q] = (row_first + 4 * q + j) * a.ldx + (k_lane_ok ? k_lane : 0);
         }
         const long d_step = row_step * O, x_step = row_step * a.ldx;
         const long full = R - row_first >= kWgradRowsPerIter ? (R - kWgradRowsPerIter - row_first) / row_step + 1 : 0;
-        auto multiply = [&](const float (&bv)[Q], const f4 (&av)[Q]) {
+        auto multiply = [&](const float (&bv)[OB][Q], const f4 (&av)[Q]) {
 #pragma unroll
             for (int q = 0; q < Q; ++q)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) P[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q][i], bv[q], P[i], 0, 0, 0);
+                for (int b = 0; b < OB; ++b)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        P[b][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q][i], bv[b][q], P[b][i], 0, 0, 0);
             if (bias_tile) {             // column sums of dy: the same contraction against ones
 #pragma unroll
-                for (int q = 0; q < Q; ++q) Pb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, bv[q], Pb, 0, 0, 0);
+                for (int q = 0; q < Q; ++q)
+#pragma unroll
+                    for (int b = 0; b < OB; ++b) Pb[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, bv[b][q], Pb[b], 0, 0, 0);
             }
         };
         if constexpr (DEEP) {
             // Two register sets of operands.  Every fetch is unconditional (behind a branch around loads the
             // compiler waits for all of them at the join): past the last whole block the offsets stop moving
             // and that block is simply read again.
-            float bA[Q], bB[Q];
+            float bA[OB][Q], bB[OB][Q];
             f4 aA[Q], aB[Q];
             long fetched = 0;
-            auto fetch = [&](float (&bv)[Q], f4 (&av)[Q]) {
+            auto fetch = [&](float (&bv)[OB][Q], f4 (&av)[Q]) {
                 ++fetched;
                 const long dd = fetched < full ? d_step : 0, dx = fetched < full ? x_step : 0;
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
-                    bv[q] = dys[pd[q]];
+#pragma unroll
+                    for (int b = 0; b < OB; ++b) {
+                        bv[b][q] = dys[pd[b][q]];
+                        pd[b][q] += dd;
+                    }
                     av[q] = load4<true, false>(xs + px[q]);
-                    pd[q] += dd;
                     px[q] += dx;
                 }
             };
@@ -508,120 +536,140 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
                 }
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {        // on to the partial block
-                    pd[q] += d_step;
+#pragma unroll
+                    for (int b = 0; b < OB; ++b) pd[b][q] += d_step;
                     px[q] += x_step;
                 }
             }
         } else {
             for (long it = 0; it < full; ++it) {
-                float bv[Q];
+                float bv[OB][Q];
                 f4 av[Q];
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
-                    bv[q] = dys[pd[q]];
+#pragma unroll
+                    for (int b = 0; b < OB; ++b) {
+                        bv[b][q] = dys[pd[b][q]];
+                        pd[b][q] += d_step;
+                    }
                     av[q] = load4<true, false>(xs + px[q]);
-                    pd[q] += d_step;
                     px[q] += x_step;
                 }
-                __builtin_amdgcn_sched_barrier(0);      // all eight loads first, one wait
+                __builtin_amdgcn_sched_barrier(0);      // all loads first, one wait
                 multiply(bv, av);
             }
         }
         const long rb = row_first + full * row_step;
         if (rb < R) {
-            float bv[Q];
+            float bv[OB][Q];
             f4 av[Q];
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 const bool r_ok = rb + 4 * q + j < R;
-                bv[q] = r_ok ? dys[pd[q]] : 0.0f;
+#pragma unroll
+                for (int b = 0; b < OB; ++b) bv[b][q] = r_ok ? dys[pd[b][q]] : 0.0f;
                 av[q] = r_ok ? load4<true, false>(xs + px[q]) : f4{0.0f, 0.0f, 0.0f, 0.0f};
             }
-#pragma unroll
-            for (int q = 0; q < Q; ++q)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) P[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q][i], bv[q], P[i], 0, 0, 0);
-            if (bias_tile) {
-#pragma unroll
-                for (int q = 0; q < Q; ++q) Pb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, bv[q], Pb, 0, 0, 0);
-            }
+            multiply(bv, av);
         }
         if (row_first < R) {             // a wave without rows has nothing to add (uniform over the wave)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const long col = k0 + 16 * j + 4 * t;
-                if (o_ok && col < K) {
-                    const f4 e = eps_quad(a.weight_quad0 + ((o * K + col) >> 2), s, a.rng);
+            for (int b = 0; b < OB; ++b) {
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        gm[t][c] += P[c][t];
-                        gs[t][c] = __builtin_fmaf(P[c][t], e[c], gs[t][c]);
+                for (int t = 0; t < 4; ++t) {
+                    const long col = k0 + 16 * j + 4 * t;
+                    if (o_ok[b] && col < K) {
+                        const f4 e = eps_quad(a.weight_quad0 + ((o[b] * K + col) >> 2), s, a.rng);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            gm[b][t][c] += P[b][c][t];
+                            gs[b][t][c] = __builtin_fmaf(P[b][c][t], e[c], gs[b][t][c]);
+                        }
                     }
                 }
+                if (bias_tile && o_ok[b]) {      // every register of Pb holds sum_r dy_s[r][o]
+                    const f4 e = eps_quad(a.bias_quad0 + (o[b] >> 2), s, a.rng);
+                    gb_m[b] += Pb[b][0];
+                    gb_s[b] = __builtin_fmaf(Pb[b][0], pick4(e, (int)(o[b] & 3)), gb_s[b]);
+                }
             }
-        }
-        if (bias_tile && row_first < R && o_ok) {      // every register of Pb holds sum_r dy_s[r][o]
-            const f4 e = eps_quad(a.bias_quad0 + (o >> 2), s, a.rng);
-            gb_m += Pb[0];
-            gb_s = __builtin_fmaf(Pb[0], pick4(e, (int)(o & 3)), gb_s);
         }
     }
 
     if constexpr (SPLIT) {
         if (wave > 0) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int b = 0; b < OB; ++b) {
+                float *mine = partial + (size_t)((wave - 1) * OB + b) * kWgradPartials * 64 + lane;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    partial[((wave - 1) * kWgradPartials + t * 4 + c) * 64 + lane] = gm[t][c];
-                    partial[((wave - 1) * kWgradPartials + 16 + t * 4 + c) * 64 + lane] = gs[t][c];
-                }
-            partial[((wave - 1) * kWgradPartials + 32) * 64 + lane] = gb_m;
-            partial[((wave - 1) * kWgradPartials + 33) * 64 + lane] = gb_s;
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        mine[(t * 4 + c) * 64] = gm[b][t][c];
+                        mine[(16 + t * 4 + c) * 64] = gs[b][t][c];
+                    }
+                mine[32 * 64] = gb_m[b];
+                mine[33 * 64] = gb_s[b];
+            }
         }
         __syncthreads();
         if (wave != 0) return;
         for (int v = 1; v < waves; ++v)
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int b = 0; b < OB; ++b) {
+                const float *theirs = partial + (size_t)((v - 1) * OB + b) * kWgradPartials * 64 + lane;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    gm[t][c] += partial[((v - 1) * kWgradPartials + t * 4 + c) * 64 + lane];
-                    gs[t][c] += partial[((v - 1) * kWgradPartials + 16 + t * 4 + c) * 64 + lane];
-                }
-        for (int v = 1; v < waves; ++v) {
-            gb_m += partial[((v - 1) * kWgradPartials + 32) * 64 + lane];
-            gb_s += partial[((v - 1) * kWgradPartials + 33) * 64 + lane];
-        }
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        gm[b][t][c] += theirs[(t * 4 + c) * 64];
+                        gs[b][t][c] += theirs[(16 + t * 4 + c) * 64];
+                    }
+                gb_m[b] += theirs[32 * 64];
+                gb_s[b] += theirs[33 * 64];
+            }
     }
 
     // A lane holds the 16 consecutive inputs k0 + 16 j .. + 15 of its output: the four lanes of an output
     // exchange quads so that store t covers the 64 contiguous bytes k0 + 16 t .. + 15 of every row.
-    transpose_quads_over_j(gm, j, n);
-    transpose_quads_over_j(gs, j, n);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const long col = k0 + 16 * t + 4 * j;
-        if (o_ok && col < K) {
-            const f4 m4 = load4<true, false>(a.mu_w + o * K + col), sd4 = load4<true, false>(a.sigma_w + o * K + col);
-            f4 om, os;
+    for (int b = 0; b < OB; ++b) {
+        transpose_quads_over_j(gm[b], j, n);
+        transpose_quads_over_j(gs[b], j, n);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                float u, v;
-                finish_pair(gm[t][c], gs[t][c], m4[c], sd4[c], a.g, a.k, u, v);
-                om[c] = u;
-                os[c] = v;
+        for (int t = 0; t < 4; ++t) {
+            const long col = k0 + 16 * t + 4 * j;
+            if (o_ok[b] && col < K) {
+                const long at = o[b] * K + col;
+                const f4 m4 = load4<true, false>(a.mu_w + at), sd4 = load4<true, false>(a.sigma_w + at);
+                f4 om, os;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    float u, v;
+                    finish_pair(gm[b][t][c], gs[b][t][c], m4[c], sd4[c], a.g, a.k, u, v);
+                    om[c] = u;
+                    os[c] = v;
+                }
+                store4<true, false>(a.gmu_w + at, om);
+                store4<true, false>(a.gsig_w + at, os);
             }
-            store4<true, false>(a.gmu_w + o * K + col, om);
-            store4<true, false>(a.gsig_w + o * K + col, os);
+        }
+        if (bias_tile && j == 0 && o_ok[b]) {
+            float u, v;
+            finish_pair(gb_m[b], gb_s[b], a.mu_b[o[b]], a.sigma_b[o[b]], a.g, a.k, u, v);
+            a.gmu_b[o[b]] = u;
+            a.gsig_b[o[b]] = v;
         }
     }
-    if (bias_tile && j == 0 && o_ok) {
-        float u, v;
-        finish_pair(gb_m, gb_s, a.mu_b[o], a.sigma_b[o], a.g, a.k, u, v);
-        a.gmu_b[o] = u;
-        a.gsig_b[o] = v;
-    }
+}
+
+template <bool SPLIT, bool DEEP, int OB>
+void wgrad_go(long tiles, int waves, hipStream_t s, const LinearGradArgs &a)
+{
+    const long per_xcd = (tiles + kXcds - 1) / kXcds;      // the kernel deals the tiles out by XCD
+    const long wgs = SPLIT ? per_xcd : (per_xcd + kWgradWaves - 1) / kWgradWaves;
+    const size_t lds = SPLIT ? (size_t)(waves - 1) * OB * kWgradPartials * 64 * sizeof(float) : 0;
+    hot_linear_wgrad_kernel<SPLIT, DEEP, OB><<<dim3((unsigned)(kXcds * wgs)), dim3(64 * waves), lds, s>>>(a);
 }
 
 // A workgroup owns 64 inputs x 16*RB rows of one sample's dx; its waves take the outputs in blocks
@@ -871,26 +919,28 @@ int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double da
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     const long k_groups = (d->in_features + 63) / 64;
-    const long tiles = k_groups * ((d->out_features + kColsPerWave - 1) / kColsPerWave);
-    if (tiles > 0x7fffff00L) return HOT_EINVAL;      // the grid may exceed the number of tiles by a few workgroups
+    const long o_groups = (d->out_features + kColsPerWave - 1) / kColsPerWave;
+    if (k_groups * o_groups > 0x7fffff00L) return HOT_EINVAL;      // the grid may exceed the number of tiles by a few workgroups
+    const bool deep = d->rows >= kWgradDeepRows;
+    // two output groups per tile where that still leaves a wave for every SIMD twice over after the row split
+    // (four per tile were measured too: 90 against 95 TFLOP/s at 4096^2 x 1024, their registers spill)
+    const int ob = (d->rows >= kWgradWideRows && k_groups * ((o_groups + 1) / 2) * wgrad_max_split(2) >= 2048) ? 2 : 1;
+    const long tiles = k_groups * ((o_groups + ob - 1) / ob);
     // few tiles and many rows: let several waves share a tile (each then draws the tile's eps itself)
-    int split = 1;
     // (up to a wave on every SIMD twice over; beyond that only while a wave keeps a thousand rows: finer pieces
     // even out the last round of waves, but every piece draws eps and adds through LDS again)
-    while (split < kWgradMaxSplit && d->rows >= 2L * split * kWgradRowsPerIter &&
+    int split = 1;
+    while (split < wgrad_max_split(ob) && d->rows >= 2L * split * kWgradRowsPerIter &&
            (tiles * split < 2048 || (tiles * split < 6144 && d->rows >= 1024L * split)))
         split *= 2;
-    const long per_xcd = (tiles + kXcds - 1) / kXcds;      // the kernel deals the tiles out by XCD
-    const bool deep = d->rows >= kWgradDeepRows;
     if (split > 1) {
-        const size_t lds = (size_t)(split - 1) * kWgradPartials * 64 * sizeof(float);
-        const dim3 grid((unsigned)(kXcds * per_xcd)), block(64 * split);
-        if (deep) hot_linear_wgrad_kernel<true, true><<<grid, block, lds, s>>>(a);
-        else hot_linear_wgrad_kernel<true, false><<<grid, block, lds, s>>>(a);
+        if (ob == 2) wgrad_go<true, true, 2>(tiles, split, s, a);
+        else if (deep) wgrad_go<true, true, 1>(tiles, split, s, a);
+        else wgrad_go<true, false, 1>(tiles, split, s, a);
     } else {
-        const dim3 grid((unsigned)(kXcds * ((per_xcd + kWgradWaves - 1) / kWgradWaves))), block(64 * kWgradWaves);
-        if (deep) hot_linear_wgrad_kernel<false, true><<<grid, block, 0, s>>>(a);
-        else hot_linear_wgrad_kernel<false, false><<<grid, block, 0, s>>>(a);
+        if (ob == 2) wgrad_go<false, true, 2>(tiles, kWgradWaves, s, a);
+        else if (deep) wgrad_go<false, true, 1>(tiles, kWgradWaves, s, a);
+        else wgrad_go<false, false, 1>(tiles, kWgradWaves, s, a);
     }
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return hot_detail::note_hip(e);
     if (!dx) return HOT_OK;

@@ -195,7 +195,10 @@ def test_rejects_what_it_cannot_run(hot):
 BACKWARD = [(1, 4, 1, 1, False, True, True), (16, 64, 16, 2, False, True, True), (17, 36, 33, 3, True, True, True),
             (33, 100, 70, 5, False, False, True), (64, 128, 24, 4, True, True, True), (64, 96, 128, 16, False, True, False),
             (70, 68, 40, 2, True, True, True), (8, 540, 2160, 2, False, True, True), (130, 192, 48, 3, True, False, True),
-            (5, 2160, 540, 2, True, True, True), (1030, 64, 32, 4, False, True, True), (300, 260, 20, 16, True, True, True)]
+            (5, 2160, 540, 2, True, True, True), (1030, 64, 32, 4, False, True, True), (300, 260, 20, 16, True, True, True),
+            # many rows and many tiles: a wave owns two output groups, operands prefetched; rows split over four
+            # waves, and one tile per wave
+            (600, 516, 1840, 2, False, True, False), (515, 1028, 3900, 1, False, True, False)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias,want_dx", BACKWARD)
@@ -230,7 +233,7 @@ def test_fused_layer_backward_matches_oracle(oracle, hot, rows, k, o, s, xs, bia
     want = oracle.linear_backward(c["x"], dy, c["mu_w"], c["sigma_w"], ew, c["mu_b"] if bias else None,
                                   c["sigma_b"] if bias else None, eb if bias else None, g=gg, k=kk, want_dx=want_dx)
     ax, ady = np.abs(c["x"].astype(np.float64)), np.abs(dy.astype(np.float64))
-    Gabs = np.einsum("sro,srk->sok" if xs else "sro,rk->sok", ady, ax)                       # [S, O, K]
+    Gabs = np.matmul(ady.transpose(0, 2, 1), ax)                                              # [S, O, K]
     m64, s64 = np.abs(c["mu_w"].astype(np.float64)), c["sigma_w"].astype(np.float64)
     checks = [("gmw", want[0], gg * Gabs.sum(0) + kk * m64), ("gsw", want[1], gg * (Gabs * rw).sum(0) + kk * (s64 + 1 / s64))]
     if bias:

@@ -769,6 +769,101 @@ hot_linear_xgrad_kernel(LinearGradArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------------
+// Input gradients for many rows: as in the forward kernel for many rows, the four waves of a workgroup
+// take up to 64 rows each and share every draw through LDS.  A workgroup owns 64 inputs x 256 rows of one
+// sample's dx and walks over the outputs 16 at a time: each of its 256 threads draws one quad of the
+// 16-output x 64-input weight tile (wave c, lane (m, j): output ob + 4 j + c, inputs k0 + 4 m .. + 3) into
+// LDS, and after one barrier every wave reads the four quads of its lane position and multiplies its own
+// 64 rows: 64 matrix instructions per drawn quad instead of 16.  A lane reads dy as quads of four
+// consecutive outputs (one 16-byte load per row block and iteration; dy needs dword alignment only) and
+// matrix instruction (c, i) takes element c of the dy quads against element i of weight quad c: the
+// contraction index is only enumerated in another order.  Tile double-buffered, one barrier per iteration,
+// as in the forward kernel; accumulators and epilogue are those of the kernel above.
+// ---------------------------------------------------------------------------------
+constexpr int kXgradRowsKernelOutputs = 16;    // outputs per iteration: one drawn quad per thread
+
+// RB: 16-row blocks per wave (a workgroup owns 64 RB rows); fewer of them where 256-row workgroups would be too few.
+template <int RB>
+__global__ void __launch_bounds__(256)
+hot_linear_xgrad_rows_kernel(LinearGradArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float tile[2][4 * 64 * 4];     // [buffer][c][j][m] quads
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, j = lane >> 4;
+    const long K = a.in_features, O = a.out_features, R = a.rows;
+    const long k0 = (long)blockIdx.x * 64, r0 = ((long)blockIdx.y * 4 + wave) * (kRowsPerTile * RB);
+    const int s = blockIdx.z;
+    const float *dys = a.dy + (size_t)s * (size_t)R * (size_t)O;
+    const long kq = k0 + 4 * n;          // this lane's quad of inputs (as a drawing thread and as an A lane)
+    const bool k_ok = kq < K;
+
+    f4 acc[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[rb][i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    // rows beyond R read row R - 1 instead: they only reach columns of the accumulators that are never stored
+    long at[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const long row = r0 + kRowsPerTile * rb + n;
+        at[rb] = (row < R ? row : R - 1) * O + 4 * j;
+    }
+
+    int buf = 0;
+    for (long ob = 0; ob < O; ob += kXgradRowsKernelOutputs, buf ^= 1) {
+        const long o_draw = ob + 4 * j + wave;
+        const bool draw_ok = k_ok && o_draw < O;
+        f4 w4 = {0.0f, 0.0f, 0.0f, 0.0f};
+        f4 dyq[RB];
+        if (ob + kXgradRowsKernelOutputs <= O) {         // uniform
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) dyq[rb] = load4<false, false>(dys + at[rb] + ob);
+        } else {                                         // last, partial step: outputs beyond O contribute zeros
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) dyq[rb][c] = ob + 4 * j + c < O ? dys[at[rb] + ob + c] : 0.0f;
+        }
+        if (draw_ok) {
+            const f4 m4 = load4<true, false>(a.mu_w + o_draw * K + kq), sd4 = load4<true, false>(a.sigma_w + o_draw * K + kq);
+            const f4 e = eps_quad(a.weight_quad0 + ((o_draw * K + kq) >> 2), s, a.rng);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) w4[c] = __builtin_fmaf(sd4[c], e[c], m4[c]);
+        }
+        *reinterpret_cast<f4 *>(&tile[buf][((wave * 4 + j) * 16 + n) * 4]) = w4;
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const f4 wq = *reinterpret_cast<const f4 *>(&tile[buf][((c * 4 + j) * 16 + n) * 4]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+                    acc[rb][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[i], dyq[rb][c], acc[rb][i], 0, 0, 0);
+        }
+    }
+
+    // register rr of accumulator i is input k0 + 16 j + 4 rr + i of row r0 + 16 rb + n; the lanes of a row
+    // exchange quads so that each store covers 64 contiguous bytes of the row
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const long row = r0 + kRowsPerTile * rb + n;
+        f4 q[4];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) q[rr] = f4{acc[rb][0][rr], acc[rb][1][rr], acc[rb][2][rr], acc[rb][3][rr]};
+        transpose_quads_over_j(q, j, n);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const long col = k0 + 16 * t + 4 * j;
+            if (row < R && col < K)
+                store4<true, false>(a.dx + ((size_t)s * (size_t)R + (size_t)row) * (size_t)K + (size_t)col, q[t]);
+        }
+    }
+}
+
 template <int RB>
 void xgrad_go(dim3 grid, int waves, hipStream_t s, const LinearGradArgs &a)
 {
@@ -956,6 +1051,19 @@ int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double da
             w *= 2;
         return w;
     };
+    // many rows: the workgroup-shared draw, with as many rows per workgroup (256, 128, 64) as still give every
+    // compute unit a workgroup
+    if (d->rows >= 256) {
+        for (int cand = 4; cand >= 1; cand >>= 1) {
+            const long gy_c = (d->rows + 64 * cand - 1) / (64 * cand);
+            if (gy_c > 65535 || k_groups * gy_c * d->s_local < (cand > 1 ? 256 : 128)) continue;     // (none fits: the kernel above)
+            const dim3 grid((unsigned)k_groups, (unsigned)gy_c, (unsigned)d->s_local);
+            if (cand == 4) hot_linear_xgrad_rows_kernel<4><<<grid, dim3(256), 0, s>>>(a);
+            else if (cand == 2) hot_linear_xgrad_rows_kernel<2><<<grid, dim3(256), 0, s>>>(a);
+            else hot_linear_xgrad_rows_kernel<1><<<grid, dim3(256), 0, s>>>(a);
+            return hot_detail::note_hip(hipGetLastError());
+        }
+    }
     int rb = 1, waves = 1;
     long gy = 0, best = -1;
     for (int cand = d->rows > 32 ? 4 : (d->rows > 16 ? 2 : 1); cand >= 1; cand >>= 1) {

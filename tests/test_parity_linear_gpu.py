@@ -198,7 +198,10 @@ BACKWARD = [(1, 4, 1, 1, False, True, True), (16, 64, 16, 2, False, True, True),
             (5, 2160, 540, 2, True, True, True), (1030, 64, 32, 4, False, True, True), (300, 260, 20, 16, True, True, True),
             # many rows and many tiles: a wave owns two output groups, operands prefetched; rows split over four
             # waves, and one tile per wave
-            (600, 516, 1840, 2, False, True, False), (515, 1028, 3900, 1, False, True, False)]
+            (600, 516, 1840, 2, False, True, False), (515, 1028, 3900, 1, False, True, False),
+            # many rows: the input-gradient kernel whose waves share the draws (odd O: dy rows only dword-aligned,
+            # a last partial step of outputs; O a multiple of the step)
+            (520, 516, 33, 8, False, True, True), (1100, 1028, 48, 2, True, False, True)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias,want_dx", BACKWARD)

@@ -199,6 +199,12 @@ hot_linear_forward_rows_kernel(LinearArgs a)
     // 8192^2 x 1024; two and four tiles leave one wave per SIMD and reach 75-90), a single sample affords two
     // tiles (81 against 64 TFLOP/s).
     __shared__ __attribute__((aligned(16))) float tile[2][ST][NO * 16 * kRowsKernelPitch];
+    // A shared x is loaded with consecutive lanes on consecutive addresses (lane (n, j): inputs kb + 4 n .. + 3
+    // of a row 4 q + j) and brought into the operand layout (lane (n, j): row n) through a wave's own 32 rows
+    // of LDS, half a tile at a time: loading in the operand layout, where every lane of a 16-byte load sits
+    // in another row, made the loads of x cost a third of the kernel's time (89 -> 105 TFLOP/s on 4096^3 with
+    // the lane pattern alone).
+    __shared__ __attribute__((aligned(16))) float turn[XS ? 1 : kRowsKernelWaves][XS ? 4 : 32 * kRowsKernelPitch];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, j = lane >> 4;
     const long K = a.in_features, O = a.out_features, R = a.rows;
@@ -220,16 +226,15 @@ hot_linear_forward_rows_kernel(LinearArgs a)
         for (long kb = 0; kb < K; kb += kRowsKernelInputs, buf ^= 1) {
             // this wave's rows of x (shared input): row 16 rb + n, inputs kb + 32 blk + 8 j + 4 h .. + 3
             f4 xa[4][2][2];
+            f4 xg[XS ? 1 : 4][XS ? 1 : 4];          // as loaded: row 16 rb + 4 q + j, inputs kb + 4 n .. + 3
             if constexpr (!XS) {
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-                    for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            const long row = r0 + kRowsPerTile * rb + n, k = kb + 32 * blk + 8 * j + 4 * h;
-                            xa[rb][blk][h] = (row < R && k < K) ? load4<true, false>(a.x + row * a.ldx + k) : f4{0.0f, 0.0f, 0.0f, 0.0f};
-                        }
+                    for (int q = 0; q < 4; ++q) {
+                        const long row = r0 + kRowsPerTile * rb + 4 * q + j, k = kb + 4 * n;
+                        xg[rb][q] = (row < R && k < K) ? load4<true, false>(a.x + row * a.ldx + k) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+                    }
             }
             // draw this thread's quads for every sample of the chunk and put them into the tile
             const long kd = kb + 4 * dq;
@@ -251,6 +256,33 @@ hot_linear_forward_rows_kernel(LinearArgs a)
                 }
             }
             __syncthreads();
+            if constexpr (!XS) {
+                // Two halves of 32 rows through the wave's own LDS rows.  Only this wave touches them and the LDS
+                // executes a wave's instructions in order, so no barrier is needed, only the program order.
+                float *mine = turn[wave];
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+#pragma unroll
+                    for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            *reinterpret_cast<f4 *>(&mine[(16 * r2 + 4 * q + j) * kRowsKernelPitch + 4 * n]) = xg[2 * half + r2][q];
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                    for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+                        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                            for (int h = 0; h < 2; ++h)
+                                xa[2 * half + r2][blk][h] =
+                                    *reinterpret_cast<const f4 *>(&mine[(16 * r2 + n) * kRowsKernelPitch + 32 * blk + 8 * j + 4 * h]);
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                }
+            }
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 if (s0 + st < a.s_loc) {          // uniform over the workgroup

@@ -503,35 +503,33 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
                           w[:, :o * k].view(s, o, k).transpose(1, 2), out=y2)
 
         ms_u = timeit(unfused)
-        bwd = None
-        if rows <= 256:
-            # back-propagation through the layer: fused (neither w nor the per-sample weight gradients exist)
-            # against library GEMMs for dx and G_s followed by hot_backward_rng (w kept from the forward pass)
-            dy = torch.randn(s, rows, o, device=dev)
-            gmw, gsw, gmb, gsb = (torch.empty(o, k, device=dev), torch.empty(o, k, device=dev),
-                                  torch.empty(o, device=dev), torch.empty(o, device=dev))
-            dx = torch.empty(s, rows, k, device=dev)
-            ms_b = timeit(lambda: hot.hot_linear_backward_rng(rng, x, dy, mu, sg, mb, sb, gmw, gsw, gmb, gsb, dx, s, 45000.0,
-                                                              hot.HOT_REDUCE_SUM, 0, o * k))
-            G = torch.empty(s, n, device=dev)
-            dx2 = torch.empty_like(dx)
-            gf, gs2 = torch.empty(n, device=dev), torch.empty(n, device=dev)
-            plan_b = hot.hot_create(n, n, s, s, 45000.0, dev.index or 0)
+        # back-propagation through the layer: fused (neither w nor the per-sample weight gradients exist)
+        # against library GEMMs for dx and G_s followed by hot_backward_rng (w kept from the forward pass)
+        dy = torch.randn(s, rows, o, device=dev)
+        gmw, gsw, gmb, gsb = (torch.empty(o, k, device=dev), torch.empty(o, k, device=dev),
+                              torch.empty(o, device=dev), torch.empty(o, device=dev))
+        dx = torch.empty(s, rows, k, device=dev)
+        ms_b = timeit(lambda: hot.hot_linear_backward_rng(rng, x, dy, mu, sg, mb, sb, gmw, gsw, gmb, gsb, dx, s, 45000.0,
+                                                          hot.HOT_REDUCE_SUM, 0, o * k))
+        G = torch.empty(s, n, device=dev)
+        dx2 = torch.empty_like(dx)
+        gf, gs2 = torch.empty(n, device=dev), torch.empty(n, device=dev)
+        plan_b = hot.hot_create(n, n, s, s, 45000.0, dev.index or 0)
 
-            def unfused_backward():
-                torch.matmul(dy, w.as_strided((s, o, k), (n, k, 1)), out=dx2)
-                torch.matmul(dy.transpose(1, 2), x.unsqueeze(0).expand(s, rows, k), out=G.as_strided((s, o, k), (n, k, 1)))
-                torch.sum(dy, dim=1, out=G[:, o * k:])
-                hot.hot_backward_rng(plan_b, rng, flat_mu, flat_sg, G, gf, gs2)
+        def unfused_backward():
+            torch.matmul(dy, w.as_strided((s, o, k), (n, k, 1)), out=dx2)
+            torch.matmul(dy.transpose(1, 2), x.unsqueeze(0).expand(s, rows, k), out=G.as_strided((s, o, k), (n, k, 1)))
+            torch.sum(dy, dim=1, out=G[:, o * k:])
+            hot.hot_backward_rng(plan_b, rng, flat_mu, flat_sg, G, gf, gs2)
 
-            ms_bu = timeit(unfused_backward)
-            hot.hot_destroy(plan_b)
-            gscale = G[:, :o * k].abs().sum(0).max().item() / s + 1e-6
-            bwd = {"fused_ms": ms_b, "weight_samples_per_s": s * o * k / (ms_b * 1e-3),
-                   "library_gemms_plus_hot_backward_ms": ms_bu, "speedup": ms_bu / ms_b,
-                   "agrees": bool((gmw.view(-1) - gf[:o * k]).abs().max().item() <= 1e-5 * gscale
-                                  and (dx - dx2).abs().max().item() <= 1e-4 * dx2.abs().max().item())}
-            del dy, gmw, gsw, dx, dx2, G, gf, gs2
+        ms_bu = timeit(unfused_backward)
+        hot.hot_destroy(plan_b)
+        gscale = G[:, :o * k].abs().sum(0).max().item() / s + 1e-6
+        bwd = {"fused_ms": ms_b, "weight_samples_per_s": s * o * k / (ms_b * 1e-3),
+               "library_gemms_plus_hot_backward_ms": ms_bu, "speedup": ms_bu / ms_b,
+               "agrees": bool((gmw.view(-1) - gf[:o * k]).abs().max().item() <= 1e-5 * gscale
+                              and (dx - dx2).abs().max().item() <= 1e-4 * dx2.abs().max().item())}
+        del dy, gmw, gsw, dx, dx2, G, gf, gs2
         hot.hot_destroy(plan)
         scale = (x.abs() @ (mu.abs() + 6 * sg).t()).max().item()
         out[name] = {"fused_ms": ms, "TFLOPs": 2.0 * s * rows * k * o / ms / 1e9,

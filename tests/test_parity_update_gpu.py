@@ -423,6 +423,64 @@ def test_fused_calls_with_non_temporal_accesses(hot, n, ld, s, offset):
     hot.hot_destroy(plan)
 
 
+@pytest.mark.parametrize("n,s", [(30_011, 4), (400_003, 2)])
+def test_fused_step_replayed_from_a_hip_graph(hot, n, s):
+    """hot_backward_adam_forward neither allocates nor synchronises, so a stream capture takes it.  The call
+    updates its state in place: three replays of the captured step, with eager work and synchronisations
+    between them, must walk through the same three states as three eager calls, bit for bit (parameters,
+    moments, w and KL; the smaller case lets the kernel add the KL partials itself, the larger one uses the
+    finish kernel)."""
+    print("case fused step under a HIP graph", n, s, flush=True)
+    r = np.random.default_rng(n + s)
+    names = ("mu", "sigma", "m_mu", "v_mu", "m_sigma", "v_sigma")
+    st = {"mu": r.normal(size=n), "sigma": r.uniform(0.05, 1.0, size=n), "m_mu": r.normal(size=n) * 0.1,
+          "v_mu": r.uniform(0, 1, size=n) * 0.01, "m_sigma": r.normal(size=n) * 0.1, "v_sigma": r.uniform(0, 1, size=n) * 0.01}
+    G = torch.from_numpy(r.normal(size=(s, n)).astype(np.float32)).to(DEV)
+    rng, rng_next = hot.hot_rng(seed=9, step=3, first_sample=0), hot.hot_rng(seed=9, step=4, first_sample=0)
+    params = hot.hot_adam(1e-2, 0.9, 0.999, 1e-8, 1.0, 0.01, 4)
+    plan = hot.hot_create(n, n, s, s, 300.0, 0)
+
+    def fresh():
+        d = {k: torch.from_numpy(st[k].astype(np.float32)).to(DEV) for k in names}
+        d["w"] = torch.zeros(s, n, device=DEV)
+        d["kl"] = torch.zeros(1, dtype=torch.float64, device=DEV)
+        return d
+
+    def step(d):
+        hot.hot_backward_adam_forward(plan, rng, rng_next, params, d["mu"], d["sigma"], G, d["m_mu"], d["v_mu"],
+                                      d["m_sigma"], d["v_sigma"], d["w"], d["kl"])
+
+    eager, trail = fresh(), []
+    for _ in range(3):
+        step(eager)
+        torch.cuda.synchronize()
+        trail.append({k: v.clone() for k, v in eager.items()})
+    assert not torch.equal(trail[0]["mu"], trail[1]["mu"])          # the state does move
+
+    warm = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(warm)                              # warm-up on the capture stream, on buffers of its own
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    held = fresh()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(held)
+    for k, v in fresh().items():                # capture does not run the kernels; start from the initial state anyway
+        held[k].copy_(v)
+    for rep in range(3):
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in held:
+            assert torch.equal(held[k], trail[rep][k]), (rep, k)
+        scratch = torch.randn(1000, device=DEV).sum().item()       # eager work between replays
+        assert scratch == scratch
+    hot.hot_destroy(plan)
+
+
 def test_fused_backward_adam_forward_errors(hot):
     n = 64
     t = [torch.zeros(n, device=DEV) for _ in range(6)]

@@ -705,7 +705,8 @@ void wgrad_go(long tiles, int waves, hipStream_t s, const LinearGradArgs &a)
 }
 
 // A workgroup owns 64 inputs x 16*RB rows of one sample's dx; its waves take the outputs in blocks
-// of eight, round-robin, and their partial tiles are added through LDS in wave order.
+// of sixteen, round-robin, and their partial tiles are added through LDS in wave order.
+constexpr int kXgradOutputsPerStep = 16;
 template <int RB>
 __global__ void __launch_bounds__(64 * max_waves(RB), RB >= 4 ? 2 : 1)
 hot_linear_xgrad_kernel(LinearGradArgs a)
@@ -726,36 +727,49 @@ hot_linear_xgrad_kernel(LinearGradArgs a)
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[rb][i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
 
-    for (long ob = (long)wave * 8; ob < O; ob += (long)waves * 8) {
-        f4 m4[2], sd4[2];
-        float dyv[RB][2];
-        bool ok[2];
+    // dy is read as quads of four consecutive outputs (lane (n, j): outputs ob + 4 j .. + 3 of row n; dword
+    // alignment suffices), and matrix instruction (c, i) takes element c of them against element i of the
+    // weight quad of output ob + 4 j + c: one 16-byte load per row block where single values took four loads.
+    // Rows beyond R read row R - 1: they only reach accumulator columns that are never stored.
+    long at[RB];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const long o = ob + 4 * h + j;
-            ok[h] = k_ok && o < O;
-            m4[h] = ok[h] ? load4<true, false>(a.mu_w + o * K + kq) : f4{0.0f, 0.0f, 0.0f, 0.0f};
-            sd4[h] = ok[h] ? load4<true, false>(a.sigma_w + o * K + kq) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int rb = 0; rb < RB; ++rb) {
+        const long row = r0 + kRowsPerTile * rb + n;
+        at[rb] = (row < R ? row : R - 1) * O + 4 * j;
+    }
+    for (long ob = (long)wave * kXgradOutputsPerStep; ob < O; ob += (long)waves * kXgradOutputsPerStep) {
+        f4 m4[4], sd4[4], dyq[RB];
+        bool ok[4];
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                const long row = r0 + kRowsPerTile * rb + n;
-                dyv[rb][h] = (row < R && o < O) ? dys[row * O + o] : 0.0f;
-            }
+        for (int c = 0; c < 4; ++c) {
+            const long o = ob + 4 * j + c;
+            ok[c] = k_ok && o < O;
+            m4[c] = ok[c] ? load4<true, false>(a.mu_w + o * K + kq) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+            sd4[c] = ok[c] ? load4<true, false>(a.sigma_w + o * K + kq) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+        if (ob + kXgradOutputsPerStep <= O) {        // uniform over the wave
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) dyq[rb] = load4<false, false>(dys + at[rb] + ob);
+        } else {                                     // last, partial step: outputs beyond O contribute zeros
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) dyq[rb][c] = ob + 4 * j + c < O ? dys[at[rb] + ob + c] : 0.0f;
         }
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int c = 0; c < 4; ++c) {
             f4 w4 = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (ok[h]) {
-                const long o = ob + 4 * h + j;
+            if (ok[c]) {
+                const long o = ob + 4 * j + c;
                 const f4 e = eps_quad(a.weight_quad0 + ((o * K + kq) >> 2), s, a.rng);
 #pragma unroll
-                for (int c = 0; c < 4; ++c) w4[c] = __builtin_fmaf(sd4[h][c], e[c], m4[h][c]);
+                for (int i = 0; i < 4; ++i) w4[i] = __builtin_fmaf(sd4[c][i], e[i], m4[c][i]);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
-                    acc[rb][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w4[i], dyv[rb][h], acc[rb][i], 0, 0, 0);
+                    acc[rb][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w4[i], dyq[rb][c], acc[rb][i], 0, 0, 0);
         }
     }
 
@@ -1075,7 +1089,7 @@ int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double da
     // Row tiles per workgroup: more of them share each drawn weight, fewer of them give more
     // workgroups and more waves per workgroup.  Take the most sharing that still puts a wave on
     // every SIMD of the chip (1024), else whatever yields the most waves.
-    const long o_blocks = (d->out_features + 7) / 8;
+    const long o_blocks = (d->out_features + kXgradOutputsPerStep - 1) / kXgradOutputsPerStep;
     auto waves_for = [&](int rb_, long gy_) {
         int w = 1;
         while (w < max_waves(rb_) && k_groups * gy_ * d->s_local * w < 8192 && 2L * w <= o_blocks &&

@@ -439,3 +439,68 @@ def test_random_layer_shapes_forward_and_backward(oracle, hot):
             checks += [(gmb, want[2], gg * Gb.sum(0) + kk * mb), (gsb, want[3], gg * (Gb * rb).sum(0) + kk * (sb + 1 / sb))]
         for got, w64, A in checks:
             assert np.all(np.abs(got.cpu().numpy().astype(np.float64) - w64) <= 1e-5 * A), case
+
+
+def test_swin_layer_at_its_full_size_on_sampled_blocks(oracle, hot):
+    """The layer shape the benchmark times for many rows (7260 tokens, 540 -> 2160, two samples), in the
+    kernels the default dispatch picks there, against the oracle on blocks it can afford: y for 24 rows x 24
+    outputs, the weight gradients of 24 outputs (all rows, all inputs), the bias gradients of those outputs,
+    and dx for 24 rows (all outputs, all inputs).  Rows of y and dx and outputs of the weight gradients do
+    not depend on one another, so each block is the oracle's result for the sub-layer it spans."""
+    rows, k, o, s = 7260, 540, 2160, 2
+    print("case linear layer at full size", rows, k, o, s, flush=True)
+    c = _layer(99, rows, k, o)
+    g = np.random.default_rng(5)
+    dy = (g.normal(size=(s, rows, o)) * 0.1).astype(np.float32)
+    rng = hot.hot_rng(seed=2025, step=11, first_sample=1)
+    w_off, b_off = 64, 64 + o * k
+    s_total, dsize = 8, 45000.0
+    t = {n: torch.from_numpy(c[n]).to(DEV) for n in ("x", "mu_w", "sigma_w", "mu_b", "sigma_b")}
+    y = torch.full((s, rows, o), float("nan"), device=DEV)
+    hot.hot_linear_forward_rng(rng, t["x"], t["mu_w"], t["sigma_w"], t["mu_b"], t["sigma_b"], y, w_off, b_off)
+    out = {"gmw": torch.full((o, k), float("nan"), device=DEV), "gsw": torch.full((o, k), float("nan"), device=DEV),
+           "gmb": torch.full((o,), float("nan"), device=DEV), "gsb": torch.full((o,), float("nan"), device=DEV),
+           "dx": torch.full((s, rows, k), float("nan"), device=DEV)}
+    hot.hot_linear_backward_rng(rng, t["x"], torch.from_numpy(dy).to(DEV), t["mu_w"], t["sigma_w"], t["mu_b"], t["sigma_b"],
+                                out["gmw"], out["gsw"], out["gmb"], out["gsb"], out["dx"], s_total, dsize,
+                                hot.HOT_REDUCE_SUM, w_off, b_off)
+    torch.cuda.synchronize()
+    for v in list(out.values()) + [y]:
+        assert bool(torch.isfinite(v).all())
+    ew, rw = oracle.eps_normal(o * k, s, rng.seed, rng.step, rng.first_sample, with_radius=True, col0=w_off)
+    ew, rw = ew.reshape(s, o, k), rw.reshape(s, o, k)
+    eb, rb = oracle.eps_normal(o, s, rng.seed, rng.step, rng.first_sample, with_radius=True, col0=b_off)
+    r_sub = np.sort(np.concatenate([[0, 255, 256, rows - 1], g.choice(rows, 20, replace=False)]))
+    o_sub = np.sort(np.concatenate([[0, 15, 16, o - 1], g.choice(o, 20, replace=False)]))
+    m64, s64 = np.abs(c["mu_w"].astype(np.float64)), c["sigma_w"].astype(np.float64)
+    ax, ady = np.abs(c["x"].astype(np.float64)), np.abs(dy.astype(np.float64))
+    gg, kk = 1.0 / s_total, s / (s_total * dsize)
+
+    # forward block
+    sub = dict(x=c["x"][r_sub], mu_w=c["mu_w"][o_sub], sigma_w=c["sigma_w"][o_sub], mu_b=c["mu_b"][o_sub], sigma_b=c["sigma_b"][o_sub])
+    want = oracle.linear_forward(sub["x"], sub["mu_w"], sub["sigma_w"], np.ascontiguousarray(ew[:, o_sub]), sub["mu_b"],
+                                 sub["sigma_b"], np.ascontiguousarray(eb[:, o_sub]))
+    A = np.einsum("rk,sok->sro", ax[r_sub], m64[o_sub][None] + s64[o_sub][None] * rw[:, o_sub]) + \
+        (np.abs(c["mu_b"][o_sub].astype(np.float64)) + c["sigma_b"][o_sub].astype(np.float64) * rb[:, o_sub])[:, None, :]
+    got = y.cpu().numpy()[:, r_sub][:, :, o_sub].astype(np.float64)
+    assert np.all(np.abs(got - want) <= 1e-5 * A), f"y: worst {np.max(np.abs(got - want) / A):.2e}"
+
+    # weight and bias gradients of the chosen outputs
+    wb = oracle.linear_backward(c["x"], np.ascontiguousarray(dy[:, :, o_sub]), sub["mu_w"], sub["sigma_w"],
+                                np.ascontiguousarray(ew[:, o_sub]), sub["mu_b"], sub["sigma_b"], np.ascontiguousarray(eb[:, o_sub]),
+                                g=gg, k=kk, want_dx=False)
+    Gabs = np.matmul(ady[:, :, o_sub].transpose(0, 2, 1), ax)                                  # [S, |o_sub|, K]
+    Gb = ady[:, :, o_sub].sum(1)
+    mb, sb = np.abs(c["mu_b"][o_sub].astype(np.float64)), c["sigma_b"][o_sub].astype(np.float64)
+    for name, w64, mag in (("gmw", wb[0], gg * Gabs.sum(0) + kk * m64[o_sub]),
+                           ("gsw", wb[1], gg * (Gabs * rw[:, o_sub]).sum(0) + kk * (s64[o_sub] + 1 / s64[o_sub])),
+                           ("gmb", wb[2], gg * Gb.sum(0) + kk * mb), ("gsb", wb[3], gg * (Gb * rb[:, o_sub]).sum(0) + kk * (sb + 1 / sb))):
+        err = np.abs(out[name].cpu().numpy()[o_sub].astype(np.float64) - w64)
+        assert np.all(err <= 1e-5 * mag), f"{name}: worst {np.max(err / mag):.2e}"
+
+    # input gradients of the chosen rows
+    xb = oracle.linear_backward(c["x"][r_sub], np.ascontiguousarray(dy[:, r_sub]), c["mu_w"], c["sigma_w"], ew, None, None, None,
+                                g=gg, k=kk, want_dx=True)
+    mag = np.einsum("sro,sok->srk", ady[:, r_sub], m64[None] + s64[None] * rw)
+    err = np.abs(out["dx"].cpu().numpy()[:, r_sub].astype(np.float64) - xb[4])
+    assert np.all(err <= 1e-5 * mag), f"dx: worst {np.max(err / mag):.2e}"

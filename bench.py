@@ -482,9 +482,13 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
               "swin_fc1_R64_540x2160_S2": (64, 540, 2160, 2), "swin_fc_R16_2160x8640_S2": (16, 2160, 8640, 2),
               "square_R1_8192x8192_S2": (1, 8192, 8192, 2), "square_R16_8192x8192_S2": (16, 8192, 8192, 2),
               "square_R64_8192x8192_S2": (64, 8192, 8192, 2), "swin_fc1_R7260_540x2160_S2": (7260, 540, 2160, 2),
-              "vit_fc1_R16640_192x768_S2": (16640, 192, 768, 2), "square_R1024_8192x8192_S2": (1024, 8192, 8192, 2)}
+              "vit_fc1_R16640_192x768_S2": (16640, 192, 768, 2), "square_R1024_8192x8192_S2": (1024, 8192, 8192, 2),
+              # a layer inside the network: every sample has an input of its own
+              "swin_fc2_R7260_2160x540_S2_own_x": (7260, 2160, 540, 2)}
     for name, (rows, k, o, s) in shapes.items():
-        x = torch.randn(rows, k, device=dev)
+        own_x = name.endswith("_own_x")
+        x = torch.randn(s, rows, k, device=dev) if own_x else torch.randn(rows, k, device=dev)
+        x_all = x if own_x else x.unsqueeze(0).expand(s, rows, k)          # [S, R, K] view for the library calls
         mu = torch.randn(o, k, device=dev) * (2.0 / k) ** 0.5
         sg = torch.rand(o, k, device=dev) * 0.01 + 0.001
         mb = torch.zeros(o, device=dev)
@@ -499,7 +503,7 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
 
         def unfused():
             hot.hot_forward_rng(plan, rng, flat_mu, flat_sg, w)
-            torch.baddbmm(w[:, o * k:].unsqueeze(1), x.unsqueeze(0).expand(s, rows, k),
+            torch.baddbmm(w[:, o * k:].unsqueeze(1), x_all,
                           w[:, :o * k].view(s, o, k).transpose(1, 2), out=y2)
 
         ms_u = timeit(unfused)
@@ -518,7 +522,7 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
 
         def unfused_backward():
             torch.matmul(dy, w.as_strided((s, o, k), (n, k, 1)), out=dx2)
-            torch.matmul(dy.transpose(1, 2), x.unsqueeze(0).expand(s, rows, k), out=G.as_strided((s, o, k), (n, k, 1)))
+            torch.matmul(dy.transpose(1, 2), x_all, out=G.as_strided((s, o, k), (n, k, 1)))
             torch.sum(dy, dim=1, out=G[:, o * k:])
             hot.hot_backward_rng(plan_b, rng, flat_mu, flat_sg, G, gf, gs2)
 
@@ -531,7 +535,7 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
                               and (dx - dx2).abs().max().item() <= 1e-4 * dx2.abs().max().item())}
         del dy, gmw, gsw, dx, dx2, G, gf, gs2
         hot.hot_destroy(plan)
-        scale = (x.abs() @ (mu.abs() + 6 * sg).t()).max().item()
+        scale = (x.reshape(-1, k).abs() @ (mu.abs() + 6 * sg).t()).max().item()
         out[name] = {"fused_ms": ms, "TFLOPs": 2.0 * s * rows * k * o / ms / 1e9,
                      "frac_of_fp32_mfma_peak": 2.0 * s * rows * k * o / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS,
                      "weight_samples_per_s": s * o * k / (ms * 1e-3), "mu_sigma_GBps": 8.0 * o * k / ms / 1e6,

@@ -198,8 +198,8 @@ int hot_last_hip_error(const hot_plan *plan);
  * fp32 (v_mfma_f32_16x16x4_f32).  Runs on the current device, asynchronous on `stream`.
  * Up to a few hundred rows a wave draws the weights it multiplies (re-drawing eps per block of 64
  * rows is then cheaper than writing and re-reading w); from 256 rows on, given at least 128 workgroups
- * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS (78-90 TFLOP/s,
- * half of the fp32 matrix peak).  For thousands of rows writing w once with hot_forward_rng and calling
+ * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS (70-93 TFLOP/s,
+ * half of the fp32 matrix peak, with a shared x and with one x per sample alike).  For thousands of rows writing w once with hot_forward_rng and calling
  * a library GEMM is still 1.2-1.6x faster: the draw and the matrix instructions do not overlap here.
  */
 typedef struct hot_linear_desc {

@@ -199,12 +199,13 @@ hot_linear_forward_rows_kernel(LinearArgs a)
     // 8192^2 x 1024; two and four tiles leave one wave per SIMD and reach 75-90), a single sample affords two
     // tiles (81 against 64 TFLOP/s).
     __shared__ __attribute__((aligned(16))) float tile[2][ST][NO * 16 * kRowsKernelPitch];
-    // A shared x is loaded with consecutive lanes on consecutive addresses (lane (n, j): inputs kb + 4 n .. + 3
+    // x is loaded with consecutive lanes on consecutive addresses (lane (n, j): inputs kb + 4 n .. + 3
     // of a row 4 q + j) and brought into the operand layout (lane (n, j): row n) through a wave's own 32 rows
     // of LDS, half a tile at a time: loading in the operand layout, where every lane of a 16-byte load sits
     // in another row, made the loads of x cost a third of the kernel's time (89 -> 105 TFLOP/s on 4096^3 with
     // the lane pattern alone).
-    __shared__ __attribute__((aligned(16))) float turn[XS ? 1 : kRowsKernelWaves][XS ? 4 : 32 * kRowsKernelPitch];
+    __shared__ __attribute__((aligned(16))) float turn[kRowsKernelWaves][32 * kRowsKernelPitch];
+    static_assert(!XS || ST == 1, "one input per sample: one sample per pass");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, j = lane >> 4;
     const long K = a.in_features, O = a.out_features, R = a.rows;
@@ -226,14 +227,15 @@ hot_linear_forward_rows_kernel(LinearArgs a)
         for (long kb = 0; kb < K; kb += kRowsKernelInputs, buf ^= 1) {
             // this wave's rows of x (shared input): row 16 rb + n, inputs kb + 32 blk + 8 j + 4 h .. + 3
             f4 xa[4][2][2];
-            f4 xg[XS ? 1 : 4][XS ? 1 : 4];          // as loaded: row 16 rb + 4 q + j, inputs kb + 4 n .. + 3
-            if constexpr (!XS) {
+            f4 xg[4][4];          // as loaded: row 16 rb + 4 q + j, inputs kb + 4 n .. + 3
+            {
+                const float *xs = XS ? a.x + (size_t)s0 * (size_t)a.x_sample_stride : a.x;     // XS: the pass's one sample
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const long row = r0 + kRowsPerTile * rb + 4 * q + j, k = kb + 4 * n;
-                        xg[rb][q] = (row < R && k < K) ? load4<true, false>(a.x + row * a.ldx + k) : f4{0.0f, 0.0f, 0.0f, 0.0f};
+                        xg[rb][q] = (row < R && k < K) ? load4<true, false>(xs + row * a.ldx + k) : f4{0.0f, 0.0f, 0.0f, 0.0f};
                     }
             }
             // draw this thread's quads for every sample of the chunk and put them into the tile
@@ -256,7 +258,7 @@ hot_linear_forward_rows_kernel(LinearArgs a)
                 }
             }
             __syncthreads();
-            if constexpr (!XS) {
+            {
                 // Two halves of 32 rows through the wave's own LDS rows.  Only this wave touches them and the LDS
                 // executes a wave's instructions in order, so no barrier is needed, only the program order.
                 float *mine = turn[wave];
@@ -286,18 +288,6 @@ hot_linear_forward_rows_kernel(LinearArgs a)
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 if (s0 + st < a.s_loc) {          // uniform over the workgroup
-                    if constexpr (XS) {
-                        const float *xs = a.x + (size_t)(s0 + st) * (size_t)a.x_sample_stride;
-#pragma unroll
-                        for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-                            for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-                                for (int h = 0; h < 2; ++h) {
-                                    const long row = r0 + kRowsPerTile * rb + n, k = kb + 32 * blk + 8 * j + 4 * h;
-                                    xa[rb][blk][h] = (row < R && k < K) ? load4<true, false>(xs + row * a.ldx + k) : f4{0.0f, 0.0f, 0.0f, 0.0f};
-                                }
-                    }
 #pragma unroll
                     for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
@@ -959,15 +949,16 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     hipStream_t s = static_cast<hipStream_t>(stream);
     // Many rows (from 256) and at least 128 workgroups of 256 rows: the kernel whose waves share every draw
     // through LDS (measured against the kernel above: 1.05-1.4x from there on, slower below).  Two samples per
-    // pass and one column tile when there are several samples; a single sample affords two column tiles.
+    // pass and one column tile when several samples share x; a single sample, and samples with inputs of
+    // their own (one per pass), afford two column tiles.
     {
         const bool xs = d->x_sample_stride != 0;
-        const int no = (d->s_local == 1 && !xs) ? 2 : 1;
+        const int no = (d->s_local == 1 || xs) ? 2 : 1;      // one sample per pass: its x loads serve two column tiles
         const long gx = (d->out_features + kColsPerWave * no - 1) / (kColsPerWave * no);
         const long gy = (d->rows + kRowsKernelRows - 1) / kRowsKernelRows;
         if (d->rows >= 256 && gx * gy >= 128 && gx <= 0x7fffffffL && gy <= 65535) {
             const dim3 grid((unsigned)gx, (unsigned)gy), block(64 * kRowsKernelWaves);
-            if (xs) hot_linear_forward_rows_kernel<1, 1, true><<<grid, block, 0, s>>>(a);
+            if (xs) hot_linear_forward_rows_kernel<1, 2, true><<<grid, block, 0, s>>>(a);
             else if (no == 2) hot_linear_forward_rows_kernel<1, 2, false><<<grid, block, 0, s>>>(a);
             else hot_linear_forward_rows_kernel<2, 1, false><<<grid, block, 0, s>>>(a);
             return hot_detail::note_hip(hipGetLastError());

@@ -694,6 +694,29 @@ void wgrad_go(long tiles, int waves, hipStream_t s, const LinearGradArgs &a)
     hot_linear_wgrad_kernel<SPLIT, DEEP, OB><<<dim3((unsigned)(kXcds * wgs)), dim3(64 * waves), lds, s>>>(a);
 }
 
+// A wave's finished 64-input x 16*RB-row tile of one sample's dx goes to memory.  Register rr of accumulator
+// i is input k0 + 16 j + 4 rr + i of row r0 + 16 rb + n; the lanes of a row exchange quads so that each store
+// covers 64 contiguous bytes of the row.  Every lane of the wave must call it.
+template <int RB>
+__device__ __forceinline__ void store_dx_tile(const f4 (&acc)[RB][4], int s, long r0, long k0, int j, int n, const LinearGradArgs &a)
+{
+    const long K = a.in_features, R = a.rows;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const long row = r0 + kRowsPerTile * rb + n;
+        f4 q[4];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) q[rr] = f4{acc[rb][0][rr], acc[rb][1][rr], acc[rb][2][rr], acc[rb][3][rr]};
+        transpose_quads_over_j(q, j, n);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const long col = k0 + 16 * t + 4 * j;
+            if (row < R && col < K)
+                store4<true, false>(a.dx + ((size_t)s * (size_t)R + (size_t)row) * (size_t)K + (size_t)col, q[t]);
+        }
+    }
+}
+
 // A workgroup owns 64 inputs x 16*RB rows of one sample's dx; its waves take the outputs in blocks
 // of sixteen, round-robin, and their partial tiles are added through LDS in wave order.
 constexpr int kXgradOutputsPerStep = 16;
@@ -787,22 +810,7 @@ hot_linear_xgrad_kernel(LinearGradArgs a)
     }
     if (wave != 0) return;
 
-    // register rr of accumulator i is input k0 + 16 j + 4 rr + i of row r0 + 16 rb + n; the lanes of a row
-    // exchange quads so that each store covers 64 contiguous bytes of the row
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const long row = r0 + kRowsPerTile * rb + n;
-        f4 q[4];
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) q[rr] = f4{acc[rb][0][rr], acc[rb][1][rr], acc[rb][2][rr], acc[rb][3][rr]};
-        transpose_quads_over_j(q, j, n);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const long col = k0 + 16 * t + 4 * j;
-            if (row < R && col < K)
-                store4<true, false>(a.dx + ((size_t)s * (size_t)R + (size_t)row) * (size_t)K + (size_t)col, q[t]);
-        }
-    }
+    store_dx_tile<RB>(acc, s, r0, k0, j, n, a);
 }
 
 // ---------------------------------------------------------------------------------
@@ -882,22 +890,7 @@ hot_linear_xgrad_rows_kernel(LinearGradArgs a)
         }
     }
 
-    // register rr of accumulator i is input k0 + 16 j + 4 rr + i of row r0 + 16 rb + n; the lanes of a row
-    // exchange quads so that each store covers 64 contiguous bytes of the row
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const long row = r0 + kRowsPerTile * rb + n;
-        f4 q[4];
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) q[rr] = f4{acc[rb][0][rr], acc[rb][1][rr], acc[rb][2][rr], acc[rb][3][rr]};
-        transpose_quads_over_j(q, j, n);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const long col = k0 + 16 * t + 4 * j;
-            if (row < R && col < K)
-                store4<true, false>(a.dx + ((size_t)s * (size_t)R + (size_t)row) * (size_t)K + (size_t)col, q[t]);
-        }
-    }
+    store_dx_tile<RB>(acc, s, r0, k0, j, n, a);
 }
 
 template <int RB>

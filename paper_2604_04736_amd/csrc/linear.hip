@@ -15,6 +15,15 @@
 // as an A lane, the same eight inputs of row m = n of x.  MFMA number i of a 32-input block then
 // takes element i of every lane's eight: the contraction index is merely enumerated in a different
 // order, and every 128-byte line of mu_W, sigma_W and x is consumed by one iteration.
+//
+// Kernels of this file, by regime:
+//   forward   hot_linear_forward_kernel        up to a few hundred rows: every wave draws what it multiplies
+//             hot_linear_forward_rows_kernel   from 256 rows: four waves x 64 rows share every draw through LDS
+//   backward  hot_linear_wgrad_kernel          weight and bias gradients (per-sample G never stored); variants for
+//                                              few tiles (waves split the rows), many rows (operands prefetched,
+//                                              two output groups per wave), tiles dealt out by XCD
+//             hot_linear_xgrad_kernel          input gradients up to a few hundred rows
+//             hot_linear_xgrad_rows_kernel     input gradients from 256 rows: shared draws, as in the forward kernel
 #include <hip/hip_runtime.h>
 
 #include "hot.h"
@@ -36,7 +45,7 @@ constexpr bool four_samples_fit(int rb, bool per_sample_x) { return rb == 2 || (
 
 struct LinearArgs {
     long rows, in_features, out_features, ldx;
-    long x_sample_stride;   // floats between the inputs of consecutive samples (XS kernels only)
+    long x_sample_stride;   // floats between the inputs of consecutive samples (0: one input for all)
     int s_loc;
     long weight_quad0;   // (weight_offset) / 4
     long bias_quad0;     // (bias_offset) / 4

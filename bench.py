@@ -515,6 +515,13 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
         dx = torch.empty(s, rows, k, device=dev)
         ms_b = timeit(lambda: hot.hot_linear_backward_rng(rng, x, dy, mu, sg, mb, sb, gmw, gsw, gmb, gsb, dx, s, 45000.0,
                                                           hot.HOT_REDUCE_SUM, 0, o * k))
+        ws_bytes = hot.hot_linear_backward_workspace_bytes(rows, k, o, s)
+        ms_bw = None
+        if ws_bytes > 0:        # few tiles, many rows: the rows go to several workgroups through a workspace
+            ws = torch.empty(ws_bytes // 4, device=dev)
+            ms_bw = timeit(lambda: hot.hot_linear_backward_rng(rng, x, dy, mu, sg, mb, sb, gmw, gsw, gmb, gsb, dx, s, 45000.0,
+                                                               hot.HOT_REDUCE_SUM, 0, o * k, workspace=ws))
+            del ws
         G = torch.empty(s, n, device=dev)
         dx2 = torch.empty_like(dx)
         gf, gs2 = torch.empty(n, device=dev), torch.empty(n, device=dev)
@@ -530,7 +537,9 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
         hot.hot_destroy(plan_b)
         gscale = G[:, :o * k].abs().sum(0).max().item() / s + 1e-6
         bwd = {"fused_ms": ms_b, "weight_samples_per_s": s * o * k / (ms_b * 1e-3),
+               "fused_with_workspace_ms": ms_bw, "workspace_bytes": ws_bytes,
                "library_gemms_plus_hot_backward_ms": ms_bu, "speedup": ms_bu / ms_b,
+               "speedup_with_workspace": ms_bu / ms_bw if ms_bw else None,
                "agrees": bool((gmw.view(-1) - gf[:o * k]).abs().max().item() <= 1e-5 * gscale
                               and (dx - dx2).abs().max().item() <= 1e-4 * dx2.abs().max().item())}
         del dy, gmw, gsw, dx, dx2, G, gf, gs2

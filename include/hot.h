@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 208 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 209 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
@@ -244,6 +244,27 @@ int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double
                             const hot_rng *rng, const float *x, const float *dy, const float *mu_w,
                             const float *sigma_w, const float *mu_b, const float *sigma_b, float *grad_mu_w,
                             float *grad_sigma_w, float *grad_mu_b, float *grad_sigma_b, float *dx, void *stream);
+
+/*
+ * The same call with device scratch of the caller's (same passage of the paper; only the launch shape
+ * differs).  A layer with few weights and many rows (a ViT layer: 192 x 768 weights, 16 640 rows) has too
+ * few 16-output x 64-input tiles to give every compute unit weight-gradient work, and the waves of one
+ * workgroup are all that can add up the rows of a tile without memory.  With a workspace the rows are cut
+ * into up to 16 parts for different workgroups; each part leaves its sums there and a second kernel adds
+ * them in part order and finishes the gradients: deterministic, no atomics.
+ * hot_linear_backward_workspace_bytes(desc) returns the number of bytes with which the call splits as far
+ * as it wants to (0: this shape would not use a workspace; HOT_EINVAL for a malformed desc).  workspace:
+ * DEVICE, 16-byte aligned, owned by the caller, contents undefined afterwards, or NULL (then the call is
+ * hot_linear_backward_rng); with fewer bytes than asked for the call splits less, or not at all.  Calls
+ * that share a workspace must not overlap.  Results agree with hot_linear_backward_rng to the rounding of
+ * a different order of summation over the rows.
+ */
+int64_t hot_linear_backward_workspace_bytes(const hot_linear_desc *desc);
+int hot_linear_backward_rng_ws(const hot_linear_desc *desc, int32_t s_total, double dataset_size, uint32_t flags,
+                               const hot_rng *rng, const float *x, const float *dy, const float *mu_w,
+                               const float *sigma_w, const float *mu_b, const float *sigma_b, float *grad_mu_w,
+                               float *grad_sigma_w, float *grad_mu_b, float *grad_sigma_b, float *dx, void *workspace,
+                               int64_t workspace_bytes, void *stream);
 
 /*
  * "Update mu and sigma using optimizer (e.g., Adam)" -- the last line of the inner loop of

@@ -80,9 +80,12 @@ class _Linear(torch.autograd.Function):
         dx = None
         if ctx.needs_input_grad[0]:
             dx = torch.empty(layer.s_local, xd.shape[-2], layer.in_features, dtype=torch.float32, device=xd.device)
+        # few weights and many rows: the library spreads the rows over the chip through scratch memory of ours
+        ws_bytes = hot.hot_linear_backward_workspace_bytes(xd.shape[-2], layer.in_features, layer.out_features, layer.s_local)
+        ws = torch.empty(ws_bytes // 4, dtype=torch.float32, device=xd.device) if ws_bytes > 0 else None
         hot.hot_linear_backward_rng(ctx.rng, xd, grad_y.contiguous(), mu_w, sigma_w, mu_b, sigma_b, gmw, gsw, gmb, gsb, dx,
                                     layer.s_local, layer.dataset_size, hot.HOT_REDUCE_NONE, layer.weight_offset,
-                                    layer.bias_offset)
+                                    layer.bias_offset, workspace=ws)
         if dx is not None and xd.dim() == 2:
             dx = dx.sum(0)          # a shared input collects every sample's share
         return dx, gmw, gsw, gmb, gsb, None, None

@@ -27,7 +27,8 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_stats_merge", "hot_linear_forward_rng", "hot_adam_step", "hot_forward_dropout_rng",
            "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam",
            "hot_linear_backward_rng", "hot_kl", "hot_forward_dropout_units_rng",
-           "hot_backward_dropout_units_rng", "hot_stats_whole", "hot_adam_forward", "hot_backward_adam_forward")
+           "hot_backward_dropout_units_rng", "hot_stats_whole", "hot_adam_forward", "hot_backward_adam_forward",
+           "hot_linear_backward_rng_ws", "hot_linear_backward_workspace_bytes")
 
 
 class hot_desc(ctypes.Structure):
@@ -107,6 +108,11 @@ def lib() -> ctypes.CDLL:
     L.hot_adam_step.restype = ctypes.c_int
     L.hot_linear_backward_rng.argtypes = [ctypes.POINTER(hot_linear_desc), ctypes.c_int32, ctypes.c_double, ctypes.c_uint32,
                                           rp] + [fp] * 11 + [vp]
+    L.hot_linear_backward_rng_ws.argtypes = [ctypes.POINTER(hot_linear_desc), ctypes.c_int32, ctypes.c_double, ctypes.c_uint32,
+                                             rp] + [fp] * 11 + [vp, ctypes.c_int64, vp]
+    L.hot_linear_backward_rng_ws.restype = ctypes.c_int
+    L.hot_linear_backward_workspace_bytes.argtypes = [ctypes.POINTER(hot_linear_desc)]
+    L.hot_linear_backward_workspace_bytes.restype = ctypes.c_int64
     L.hot_adam_forward.argtypes = [vp, rp, ctypes.POINTER(hot_adam)] + [fp] * 10 + [vp, vp]
     L.hot_backward_adam.argtypes = [vp, rp, ctypes.POINTER(hot_adam)] + [fp] * 8 + [vp]
     L.hot_backward_adam_forward.argtypes = [vp, rp, rp, ctypes.POINTER(hot_adam)] + [fp] * 8 + [vp, vp]
@@ -464,11 +470,22 @@ def hot_backward_adam(plan: Plan, rng, params: hot_adam, mu, sigma, eps, grad_w,
     _check(code, "hot_backward_adam", plan)
 
 
+def hot_linear_backward_workspace_bytes(rows: int, in_features: int, out_features: int, s_local: int) -> int:
+    """Bytes of device scratch with which hot_linear_backward_rng(..., workspace=...) splits the rows of this
+    layer shape over workgroups as far as it wants to; 0 if it would not use any."""
+    d = hot_linear_desc(rows, in_features, out_features, in_features, 0, 0, s_local, 0, 0)
+    n = lib().hot_linear_backward_workspace_bytes(ctypes.byref(d))
+    if n < 0:
+        _check_planless(int(n), "hot_linear_backward_workspace_bytes")
+    return int(n)
+
+
 def hot_linear_backward_rng(rng: hot_rng, x, dy, mu_w, sigma_w, mu_b, sigma_b, grad_mu_w, grad_sigma_w, grad_mu_b,
                             grad_sigma_b, dx, s_total: int, dataset_size: float, flags: int = HOT_REDUCE_SUM,
-                            weight_offset: int = 0, bias_offset: int = 0) -> None:
+                            weight_offset: int = 0, bias_offset: int = 0, workspace=None) -> None:
     """Gradients of the sampled linear layer from dy [S_loc, R, O] (see include/hot.h): weight and bias
-    gradients scaled like hot_backward's, and dx [S_loc, R, K] (or None to skip it)."""
+    gradients scaled like hot_backward's, and dx [S_loc, R, K] (or None to skip it).  workspace: an optional
+    contiguous device tensor (any dtype) used as scratch (hot_linear_backward_rng_ws)."""
     def chk(t, shape, name):
         if not (t.is_cuda and t.device == x.device and t.dtype == torch.float32 and tuple(t.shape) == shape
                 and t.is_contiguous()):
@@ -498,12 +515,21 @@ def hot_linear_backward_rng(rng: hot_rng, x, dy, mu_w, sigma_w, mu_b, sigma_b, g
         chk(dx, (s_loc, rows, k), "dx")
     d = hot_linear_desc(rows, k, o, ldx, weight_offset, bias_offset, s_loc, 0, x_stride)
     ptr = lambda t: t.data_ptr() if t is not None else None
+    if workspace is not None and not (workspace.is_cuda and workspace.device == x.device and workspace.is_contiguous()):
+        raise TypeError(f"workspace: need a contiguous tensor on {x.device}")
     with torch.cuda.device(x.device):
-        code = lib().hot_linear_backward_rng(ctypes.byref(d), int(s_total), float(dataset_size), int(flags), ctypes.byref(rng),
-                                             x.data_ptr(), dy.data_ptr(), mu_w.data_ptr(), sigma_w.data_ptr(), ptr(mu_b),
-                                             ptr(sigma_b), grad_mu_w.data_ptr(), grad_sigma_w.data_ptr(), ptr(grad_mu_b),
-                                             ptr(grad_sigma_b), ptr(dx), _stream(x.device.index))
-    _check_planless(code, "hot_linear_backward_rng")
+        if workspace is None:
+            code = lib().hot_linear_backward_rng(ctypes.byref(d), int(s_total), float(dataset_size), int(flags), ctypes.byref(rng),
+                                                 x.data_ptr(), dy.data_ptr(), mu_w.data_ptr(), sigma_w.data_ptr(), ptr(mu_b),
+                                                 ptr(sigma_b), grad_mu_w.data_ptr(), grad_sigma_w.data_ptr(), ptr(grad_mu_b),
+                                                 ptr(grad_sigma_b), ptr(dx), _stream(x.device.index))
+        else:
+            code = lib().hot_linear_backward_rng_ws(ctypes.byref(d), int(s_total), float(dataset_size), int(flags), ctypes.byref(rng),
+                                                    x.data_ptr(), dy.data_ptr(), mu_w.data_ptr(), sigma_w.data_ptr(), ptr(mu_b),
+                                                    ptr(sigma_b), grad_mu_w.data_ptr(), grad_sigma_w.data_ptr(), ptr(grad_mu_b),
+                                                    ptr(grad_sigma_b), ptr(dx), workspace.data_ptr(),
+                                                    workspace.numel() * workspace.element_size(), _stream(x.device.index))
+    _check_planless(code, "hot_linear_backward_rng_ws" if workspace is not None else "hot_linear_backward_rng")
 
 
 def hot_kl(plan: Plan, mu, sigma, kl_out) -> None:

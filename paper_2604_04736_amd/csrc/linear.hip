@@ -380,6 +380,8 @@ struct LinearGradArgs {
     double g, k;            // scaling of the data part and of the KL part of the gradients
     const float *x, *dy, *mu_w, *sigma_w, *mu_b, *sigma_b;
     float *gmu_w, *gsig_w, *gmu_b, *gsig_b, *dx;
+    float *ws;              // PARTS kernels: partial sums [part][gm, gs][O*K + O]
+    long rows_per_part;     // PARTS kernels: rows of one part, a multiple of 16
     Rng rng;
 };
 
@@ -427,6 +429,7 @@ constexpr int kWgradMaxSplit = 8;    // most waves that share one tile (60 KiB o
 constexpr int kWgradRowsPerIter = 16;
 constexpr int kWgradDeepRows = 128;  // from this many rows on operands are prefetched one row block ahead
 constexpr int kWgradWideRows = 512;  // from this many rows on a wave may own several output groups
+constexpr int kWgradMaxParts = 16;    // most row parts of a run with a workspace
 constexpr int kWgradPartials = 34;   // per lane: 16 + 16 weight-gradient sums and the two bias sums
 
 // SPLIT = false: the four waves of a workgroup own one tile each.  SPLIT = true (layers with few
@@ -448,7 +451,7 @@ constexpr int kXcds = 8;
 
 constexpr int wgrad_max_split(int ob) { return kWgradMaxSplit / ob; }   // at most 60 KiB of LDS
 
-template <bool SPLIT, bool DEEP, int OB>
+template <bool SPLIT, bool DEEP, int OB, bool PARTS = false>
 __global__ void __launch_bounds__(64 * (SPLIT ? wgrad_max_split(OB) : kWgradWaves), 1)
 hot_linear_wgrad_kernel(LinearGradArgs a)
 {
@@ -475,7 +478,10 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
         o_ok[b] = o[b] < O;
     }
     const bool bias_tile = a.mu_b != nullptr && k0 == 0;     // uniform over the wave: this tile also owns its outputs' biases
-    const long row_first = SPLIT ? (long)wave * kWgradRowsPerIter : 0;
+    // PARTS: workgroup (x, y) owns the rows of part y only and leaves its sums in the workspace
+    const long r_lo = PARTS ? (long)blockIdx.y * a.rows_per_part : 0;
+    const long r_hi = PARTS ? (r_lo + a.rows_per_part < R ? r_lo + a.rows_per_part : R) : R;
+    const long row_first = r_lo + (SPLIT ? (long)wave * kWgradRowsPerIter : 0);
     const long row_step = SPLIT ? (long)waves * kWgradRowsPerIter : kWgradRowsPerIter;
 
     // gm[b][t], gs[b][t]: the sums for the generator quad of inputs k0 + 16 j + 4 t .. + 3 of output o[b]
@@ -506,7 +512,7 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
         // Whole blocks of 16 rows first, with nothing in the loop but the loads, the offset increments and the
         // matrix instructions: lanes outside the layer (o >= O, inputs >= K) read a valid address instead, which
         // only reaches rows and columns of P that are never stored.  The last, partial block is predicated per
-        // row: rows beyond R must contribute zeros, they are summed over.
+        // row: rows beyond the last one must contribute zeros, they are summed over.
         constexpr int Q = kWgradRowsPerIter / 4;
         long pd[OB][Q], px[Q];      // offsets, not pointers: the loads stay global loads
 #pragma unroll
@@ -516,7 +522,7 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
             px[q] = (row_first + 4 * q + j) * a.ldx + (k_lane_ok ? k_lane : 0);
         }
         const long d_step = row_step * O, x_step = row_step * a.ldx;
-        const long full = R - row_first >= kWgradRowsPerIter ? (R - kWgradRowsPerIter - row_first) / row_step + 1 : 0;
+        const long full = r_hi - row_first >= kWgradRowsPerIter ? (r_hi - kWgradRowsPerIter - row_first) / row_step + 1 : 0;
         auto multiply = [&](const float (&bv)[OB][Q], const f4 (&av)[Q]) {
 #pragma unroll
             for (int q = 0; q < Q; ++q)
@@ -591,19 +597,19 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
             }
         }
         const long rb = row_first + full * row_step;
-        if (rb < R) {
+        if (rb < r_hi) {
             float bv[OB][Q];
             f4 av[Q];
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
-                const bool r_ok = rb + 4 * q + j < R;
+                const bool r_ok = rb + 4 * q + j < r_hi;
 #pragma unroll
                 for (int b = 0; b < OB; ++b) bv[b][q] = r_ok ? dys[pd[b][q]] : 0.0f;
                 av[q] = r_ok ? load4<true, false>(xs + px[q]) : f4{0.0f, 0.0f, 0.0f, 0.0f};
             }
             multiply(bv, av);
         }
-        if (row_first < R) {             // a wave without rows has nothing to add (uniform over the wave)
+        if (row_first < r_hi) {          // a wave without rows has nothing to add (uniform over the wave)
 #pragma unroll
             for (int b = 0; b < OB; ++b) {
 #pragma unroll
@@ -667,6 +673,23 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
     for (int b = 0; b < OB; ++b) {
         transpose_quads_over_j(gm[b], j, n);
         transpose_quads_over_j(gs[b], j, n);
+        if constexpr (PARTS) {          // the raw sums of this part; hot_linear_wgrad_finish_kernel adds the parts up
+            const long per = O * K + ((O + 3) & ~3L);       // a multiple of 4 floats: quads stay 16-byte aligned
+            float *mine = a.ws + (size_t)blockIdx.y * 2 * (size_t)per;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const long col = k0 + 16 * t + 4 * j;
+                if (o_ok[b] && col < K) {
+                    store4<true, false>(mine + o[b] * K + col, gm[b][t]);
+                    store4<true, false>(mine + per + o[b] * K + col, gs[b][t]);
+                }
+            }
+            if (bias_tile && j == 0 && o_ok[b]) {
+                mine[O * K + o[b]] = gb_m[b];
+                mine[per + O * K + o[b]] = gb_s[b];
+            }
+            continue;
+        }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const long col = k0 + 16 * t + 4 * j;
@@ -692,6 +715,62 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
             a.gsig_b[o[b]] = v;
         }
     }
+}
+
+// Adds the parts of a PARTS run in their order and finishes the gradients: thread q owns quad q of the
+// O*K weights (K is a multiple of 4, so a quad never leaves its row), the first O threads also one bias.
+__global__ void __launch_bounds__(256)
+hot_linear_wgrad_finish_kernel(LinearGradArgs a, int parts)
+{
+    const long K = a.in_features, O = a.out_features, per = O * K + ((O + 3) & ~3L);
+    const long q = (long)blockIdx.x * 256 + threadIdx.x;
+    if (q < O * K / 4) {
+        f4 gm = {0.0f, 0.0f, 0.0f, 0.0f}, gs = gm;
+        for (int p = 0; p < parts; ++p) {
+            const float *theirs = a.ws + (size_t)p * 2 * (size_t)per;
+            const f4 u = load4<true, false>(theirs + 4 * q), v = load4<true, false>(theirs + per + 4 * q);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                gm[c] += u[c];
+                gs[c] += v[c];
+            }
+        }
+        const f4 m4 = load4<true, false>(a.mu_w + 4 * q), sd4 = load4<true, false>(a.sigma_w + 4 * q);
+        f4 om, os;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float u, v;
+            finish_pair(gm[c], gs[c], m4[c], sd4[c], a.g, a.k, u, v);
+            om[c] = u;
+            os[c] = v;
+        }
+        store4<true, false>(a.gmu_w + 4 * q, om);
+        store4<true, false>(a.gsig_w + 4 * q, os);
+    }
+    if (a.mu_b != nullptr && q < O) {
+        float gm = 0.0f, gs = 0.0f;
+        for (int p = 0; p < parts; ++p) {
+            const float *theirs = a.ws + (size_t)p * 2 * (size_t)per;
+            gm += theirs[O * K + q];
+            gs += theirs[per + O * K + q];
+        }
+        float u, v;
+        finish_pair(gm, gs, a.mu_b[q], a.sigma_b[q], a.g, a.k, u, v);
+        a.gmu_b[q] = u;
+        a.gsig_b[q] = v;
+    }
+}
+
+// The PARTS run: every tile once per part (grid y), then the finish kernel.
+template <int OB>
+void wgrad_go_parts(long tiles, int waves, int parts, hipStream_t s, const LinearGradArgs &a)
+{
+    const long per_xcd = (tiles + kXcds - 1) / kXcds;
+    const size_t lds = (size_t)(waves - 1) * OB * kWgradPartials * 64 * sizeof(float);
+    hot_linear_wgrad_kernel<true, true, OB, true><<<dim3((unsigned)(kXcds * per_xcd), (unsigned)parts), dim3(64 * waves), lds, s>>>(a);
+    const long quads = a.out_features * a.in_features / 4;
+    const long threads = quads > a.out_features ? quads : a.out_features;
+    hot_linear_wgrad_finish_kernel<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s>>>(a, parts);
 }
 
 template <bool SPLIT, bool DEEP, int OB>
@@ -909,9 +988,69 @@ void xgrad_go(dim3 grid, int waves, hipStream_t s, const LinearGradArgs &a)
     hot_linear_xgrad_kernel<RB><<<grid, dim3(64 * waves), lds, s>>>(a);
 }
 
+// Launch shape of the weight-gradient kernel.
+struct WgradShape {
+    long tiles, rows_per_part;
+    int ob, split, parts;
+    bool deep;
+};
+
+inline int64_t wgrad_part_bytes(const hot_linear_desc *d)
+{
+    return 2 * (d->out_features * d->in_features + ((d->out_features + 3) & ~(int64_t)3)) * (int64_t)sizeof(float);
+}
+
+// ws_bytes: what the caller's workspace holds (0: none; a negative value: as much as wanted, for the size query)
+WgradShape wgrad_shape(const hot_linear_desc *d, int64_t ws_bytes)
+{
+    WgradShape w;
+    const long k_groups = (d->in_features + 63) / 64;
+    const long o_groups = (d->out_features + kColsPerWave - 1) / kColsPerWave;
+    w.deep = d->rows >= kWgradDeepRows;
+    // two output groups per tile where that still leaves a wave for every SIMD twice over after the row split
+    // (four per tile were measured too: 90 against 95 TFLOP/s at 4096^2 x 1024, their registers spill)
+    w.ob = (d->rows >= kWgradWideRows && d->out_features >= 32 && k_groups * ((o_groups + 1) / 2) * wgrad_max_split(2) * (ws_bytes != 0 && d->rows >= 8192 ? 8 : 1) >= 2048) ? 2 : 1;
+    w.tiles = k_groups * ((o_groups + w.ob - 1) / w.ob);
+    // few tiles and many rows: let several waves share a tile (each then draws the tile's eps itself)
+    // (up to a wave on every SIMD twice over; beyond that only while a wave keeps a thousand rows: finer pieces
+    // even out the last round of waves, but every piece draws eps and adds through LDS again)
+    w.split = 1;
+    while (w.split < wgrad_max_split(w.ob) && d->rows >= 2L * w.split * kWgradRowsPerIter &&
+           (w.tiles * w.split < 2048 || (w.tiles * w.split < 6144 && d->rows >= 1024L * w.split)))
+        w.split *= 2;
+    // Still too few waves for the chip (the tiles are few and a workgroup cannot hold more waves), or a number
+    // of waves that fills the last round of the chip's 2048 wave slots (two per SIMD) badly: with a workspace
+    // the rows are cut into parts for different workgroups, whose sums a second kernel adds in part order.
+    // Measured: 1152 waves -> 4 or 8 parts (0.25 -> 0.19 ms), 2448 -> 2 parts (0.47 -> 0.42 ms; 4 parts lose),
+    // 2048 -> none (2 parts: 0.19 -> 0.21 ms).  A wave keeps at least 128 rows.
+    w.parts = 1;
+    w.rows_per_part = 0;
+    const long waves = w.tiles * w.split, last_round = waves % 2048;
+    const bool fills_its_rounds = waves >= 2048 && (last_round == 0 || last_round > 1536);
+    if (w.deep && ws_bytes != 0 && w.split == wgrad_max_split(w.ob) && !fills_its_rounds) {
+        int parts = 1;
+        while (parts < kWgradMaxParts && waves * parts < 4096 && d->rows >= 256L * w.split * (2 * parts) &&
+               (ws_bytes < 0 || (int64_t)(2 * parts) * wgrad_part_bytes(d) <= ws_bytes))
+            parts *= 2;
+        if (parts > 1) {
+            w.parts = parts;
+            w.rows_per_part = ((d->rows + parts - 1) / parts + kWgradRowsPerIter - 1) / kWgradRowsPerIter * kWgradRowsPerIter;
+        }
+    }
+    return w;
+}
+
 }  // namespace
 
 extern "C" {
+
+int64_t hot_linear_backward_workspace_bytes(const hot_linear_desc *d)
+{
+    if (!d || d->rows < 1 || d->in_features < 4 || (d->in_features & 3) || d->out_features < 1 || d->s_local < 1) return HOT_EINVAL;
+    if (d->out_features > (INT64_MAX / 64) / d->in_features) return HOT_EINVAL;
+    const WgradShape w = wgrad_shape(d, -1);
+    return w.parts > 1 ? (int64_t)w.parts * wgrad_part_bytes(d) : 0;
+}
 
 int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const float *x, const float *mu_w,
                            const float *sigma_w, const float *mu_b, const float *sigma_b, float *y, void *stream)
@@ -987,12 +1126,14 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     return hot_detail::note_hip(hipGetLastError());
 }
 
-int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double dataset_size, uint32_t flags,
-                            const hot_rng *rng, const float *x, const float *dy, const float *mu_w,
-                            const float *sigma_w, const float *mu_b, const float *sigma_b, float *grad_mu_w,
-                            float *grad_sigma_w, float *grad_mu_b, float *grad_sigma_b, float *dx, void *stream)
+int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double dataset_size, uint32_t flags,
+                               const hot_rng *rng, const float *x, const float *dy, const float *mu_w,
+                               const float *sigma_w, const float *mu_b, const float *sigma_b, float *grad_mu_w,
+                               float *grad_sigma_w, float *grad_mu_b, float *grad_sigma_b, float *dx, void *workspace,
+                               int64_t workspace_bytes, void *stream)
 {
     if (!d || !x || !dy || !mu_w || !sigma_w || !grad_mu_w || !grad_sigma_w) return HOT_EINVAL;
+    if (workspace && (workspace_bytes < 0 || !aligned16(workspace))) return HOT_EINVAL;
     if ((mu_b == nullptr) != (sigma_b == nullptr) || (mu_b == nullptr) != (grad_mu_b == nullptr) ||
         (mu_b == nullptr) != (grad_sigma_b == nullptr))
         return HOT_EINVAL;
@@ -1049,25 +1190,24 @@ int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double da
     a.gmu_b = grad_mu_b;
     a.gsig_b = grad_sigma_b;
     a.dx = dx;
+    a.ws = nullptr;
+    a.rows_per_part = 0;
     a.rng = r;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     const long k_groups = (d->in_features + 63) / 64;
     const long o_groups = (d->out_features + kColsPerWave - 1) / kColsPerWave;
     if (k_groups * o_groups > 0x7fffff00L) return HOT_EINVAL;      // the grid may exceed the number of tiles by a few workgroups
-    const bool deep = d->rows >= kWgradDeepRows;
-    // two output groups per tile where that still leaves a wave for every SIMD twice over after the row split
-    // (four per tile were measured too: 90 against 95 TFLOP/s at 4096^2 x 1024, their registers spill)
-    const int ob = (d->rows >= kWgradWideRows && k_groups * ((o_groups + 1) / 2) * wgrad_max_split(2) >= 2048) ? 2 : 1;
-    const long tiles = k_groups * ((o_groups + ob - 1) / ob);
-    // few tiles and many rows: let several waves share a tile (each then draws the tile's eps itself)
-    // (up to a wave on every SIMD twice over; beyond that only while a wave keeps a thousand rows: finer pieces
-    // even out the last round of waves, but every piece draws eps and adds through LDS again)
-    int split = 1;
-    while (split < wgrad_max_split(ob) && d->rows >= 2L * split * kWgradRowsPerIter &&
-           (tiles * split < 2048 || (tiles * split < 6144 && d->rows >= 1024L * split)))
-        split *= 2;
-    if (split > 1) {
+    const WgradShape shape = wgrad_shape(d, workspace ? workspace_bytes : 0);
+    const long tiles = shape.tiles;
+    const int split = shape.split, ob = shape.ob;
+    const bool deep = shape.deep;
+    if (shape.parts > 1) {
+        a.ws = static_cast<float *>(workspace);
+        a.rows_per_part = shape.rows_per_part;
+        if (ob == 2) wgrad_go_parts<2>(tiles, split, shape.parts, s, a);
+        else wgrad_go_parts<1>(tiles, split, shape.parts, s, a);
+    } else if (split > 1) {
         if (ob == 2) wgrad_go<true, true, 2>(tiles, split, s, a);
         else if (deep) wgrad_go<true, true, 1>(tiles, split, s, a);
         else wgrad_go<true, false, 1>(tiles, split, s, a);
@@ -1122,6 +1262,15 @@ int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double da
     else if (rb == 2) xgrad_go<2>(grid, waves, s, a);
     else xgrad_go<1>(grid, waves, s, a);
     return hot_detail::note_hip(hipGetLastError());
+}
+
+int hot_linear_backward_rng(const hot_linear_desc *d, int32_t s_total, double dataset_size, uint32_t flags,
+                            const hot_rng *rng, const float *x, const float *dy, const float *mu_w,
+                            const float *sigma_w, const float *mu_b, const float *sigma_b, float *grad_mu_w,
+                            float *grad_sigma_w, float *grad_mu_b, float *grad_sigma_b, float *dx, void *stream)
+{
+    return hot_linear_backward_rng_ws(d, s_total, dataset_size, flags, rng, x, dy, mu_w, sigma_w, mu_b, sigma_b, grad_mu_w,
+                                      grad_sigma_w, grad_mu_b, grad_sigma_b, dx, nullptr, 0, stream);
 }
 
 }  // extern "C"

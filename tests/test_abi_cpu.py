@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(hot):
 
 
 def test_host_only_entry_points(hot):
-    assert hot.hot_version() == 208
+    assert hot.hot_version() == 209
     assert hot.hot_strerror(0) == "success"
     assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
     assert hot.hot_strerror(-99) == "unknown error code"
@@ -73,6 +73,13 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_stats_merge(None, None, None, 1, 1, 1, 0, None, None, None) == hot.HOT_EINVAL
     assert L.hot_linear_forward_rng(None, None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_linear_backward_rng(None, 1, 1.0, 0, *([None] * 13)) == hot.HOT_EINVAL
+    assert L.hot_linear_backward_rng_ws(None, 1, 1.0, 0, *([None] * 12), None, 0, None) == hot.HOT_EINVAL
+    assert L.hot_linear_backward_workspace_bytes(None) == hot.HOT_EINVAL
+    # the workspace query is host arithmetic: a ViT layer at 16 640 rows wants parts, a small layer none
+    per = 2 * (768 * 192 + 768) * 4
+    assert hot.hot_linear_backward_workspace_bytes(16640, 192, 768, 2) in (2 * per, 4 * per, 8 * per, 16 * per)
+    assert hot.hot_linear_backward_workspace_bytes(64, 128, 128, 4) == 0
+    assert hot.hot_linear_backward_workspace_bytes(4096, 4096, 4096, 2) == 0
     assert L.hot_adam_step(None, 1, None, None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_forward_dropout_rng(None, None, 0.5, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward_dropout_rng(None, None, 0.5, None, None, None) == hot.HOT_EINVAL

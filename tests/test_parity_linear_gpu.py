@@ -256,6 +256,76 @@ def test_fused_layer_backward_matches_oracle(oracle, hot, rows, k, o, s, xs, bia
         print("  %s worst error / magnitude sum: %.2e" % (name, np.max(err / A)), flush=True)
 
 
+# (rows, in, out, samples, per-sample x, bias, fraction of the wanted workspace, expected use of it)
+WITH_WORKSPACE = [(4200, 64, 48, 2, False, True, 1.0, True), (17000, 36, 20, 3, True, True, 1.0, True),
+                  (17000, 36, 20, 2, False, False, 0.3, True), (17000, 36, 20, 2, False, True, 0.01, False),
+                  (2100, 516, 1840, 1, False, True, 1.0, True), (300, 64, 48, 2, False, True, 1.0, False)]
+
+
+@pytest.mark.parametrize("rows,k,o,s,xs,bias,fraction,used", WITH_WORKSPACE)
+def test_backward_with_a_workspace_matches_oracle(oracle, hot, rows, k, o, s, xs, bias, fraction, used):
+    """hot_linear_backward_rng_ws: few tiles and many rows, the rows cut into parts over workgroups, partial sums
+    in the caller's workspace, added in part order by a second kernel.  Weight and bias gradients against the
+    oracle to the same bound as without a workspace; a workspace smaller than asked for (fewer parts, or none)
+    and a shape that wants none give the same; the workspace is the only memory written besides the outputs."""
+    print("case linear backward with workspace", rows, k, o, s, xs, bias, fraction, flush=True)
+    c = _layer(rows + k + o, rows, k, o)
+    g = np.random.default_rng(rows + s)
+    if xs:
+        c["x"] = g.normal(size=(s, rows, k)).astype(np.float32)
+    dy = (g.normal(size=(s, rows, o)) * 10 ** g.uniform(-2, 1, size=(s, 1, o))).astype(np.float32)
+    rng = hot.hot_rng(seed=31, step=2, first_sample=0)
+    w_off, b_off = 16, 16 + o * k
+    s_total, dsize = 2 * s, 800.0
+    want_bytes = hot.hot_linear_backward_workspace_bytes(rows, k, o, s)
+    assert (want_bytes > 0) == (used or fraction < 0.05), want_bytes
+    n_ws = max(int(want_bytes * fraction) // 16 * 4, 4)
+    ws = torch.full((n_ws + 8,), float("nan"), device=DEV)
+    t = {n: torch.from_numpy(c[n]).to(DEV) for n in ("x", "mu_w", "sigma_w", "mu_b", "sigma_b")}
+    out = {"gmw": torch.full((o, k), float("nan"), device=DEV), "gsw": torch.full((o, k), float("nan"), device=DEV),
+           "gmb": torch.full((o,), float("nan"), device=DEV), "gsb": torch.full((o,), float("nan"), device=DEV)}
+    hot.hot_linear_backward_rng(rng, t["x"], torch.from_numpy(dy).to(DEV), t["mu_w"], t["sigma_w"],
+                                t["mu_b"] if bias else None, t["sigma_b"] if bias else None, out["gmw"], out["gsw"],
+                                out["gmb"] if bias else None, out["gsb"] if bias else None, None,
+                                s_total, dsize, hot.HOT_REDUCE_SUM, w_off, b_off, workspace=ws[:n_ws])
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(ws[n_ws:]).all()), "written beyond the workspace"
+    assert bool(torch.isnan(ws[:n_ws]).all()) != used, "workspace use is not what the shape and its size call for"
+    got = {n: v.cpu().numpy().astype(np.float64) for n, v in out.items()}
+    ew, rw = oracle.eps_normal(o * k, s, rng.seed, rng.step, rng.first_sample, with_radius=True, col0=w_off)
+    ew, rw = ew.reshape(s, o, k), rw.reshape(s, o, k)
+    eb, rb = oracle.eps_normal(o, s, rng.seed, rng.step, rng.first_sample, with_radius=True, col0=b_off)
+    gg, kk = 1.0 / s_total, s / (s_total * dsize)
+    want = oracle.linear_backward(c["x"], dy, c["mu_w"], c["sigma_w"], ew, c["mu_b"] if bias else None,
+                                  c["sigma_b"] if bias else None, eb if bias else None, g=gg, k=kk, want_dx=False)
+    ax, ady = np.abs(c["x"].astype(np.float64)), np.abs(dy.astype(np.float64))
+    Gabs = np.matmul(ady.transpose(0, 2, 1), ax)
+    m64, s64 = np.abs(c["mu_w"].astype(np.float64)), c["sigma_w"].astype(np.float64)
+    checks = [("gmw", want[0], gg * Gabs.sum(0) + kk * m64), ("gsw", want[1], gg * (Gabs * rw).sum(0) + kk * (s64 + 1 / s64))]
+    if bias:
+        Gb = ady.sum(1)
+        mb, sb = np.abs(c["mu_b"].astype(np.float64)), c["sigma_b"].astype(np.float64)
+        checks += [("gmb", want[2], gg * Gb.sum(0) + kk * mb), ("gsb", want[3], gg * (Gb * rb).sum(0) + kk * (sb + 1 / sb))]
+    for name, w64, A in checks:
+        err = np.abs(got[name] - w64)
+        assert np.all(np.isfinite(got[name])), name
+        assert np.all(err <= 1e-5 * A), f"{name}: worst {np.max(err / A):.3e} of the magnitude sum"
+
+
+def test_workspace_arguments_are_checked(hot):
+    x, w, dy = torch.zeros(4, 8, device=DEV), torch.ones(3, 8, device=DEV), torch.zeros(2, 4, 3, device=DEV)
+    rng = hot.hot_rng(seed=1, step=0, first_sample=0)
+    ws = torch.zeros(64, device=DEV)
+    with pytest.raises(hot.HotError):       # not 16-byte aligned
+        hot.hot_linear_backward_rng(rng, x, dy, w, w.clone(), None, None, w.clone(), w.clone(), None, None, None, 2, 1.0, workspace=ws[1:])
+    with pytest.raises(TypeError):
+        hot.hot_linear_backward_rng(rng, x, dy, w, w.clone(), None, None, w.clone(), w.clone(), None, None, None, 2, 1.0, workspace=ws.cpu())
+    hot.hot_linear_backward_rng(rng, x, dy, w, w.clone(), None, None, w.clone(), w.clone(), None, None, None, 2, 1.0, workspace=ws)
+    torch.cuda.synchronize()
+    with pytest.raises(hot.HotError):
+        hot.hot_linear_backward_workspace_bytes(0, 8, 3, 2)
+
+
 def test_fused_backward_equals_flat_backward_on_materialised_gradients(hot):
     """The layer's weight gradients against hot_backward_rng fed with G_s = dy_s^T x (fp64 einsum,
     rounded to fp32) on the flat parameter vector that holds the layer at its offsets: the same

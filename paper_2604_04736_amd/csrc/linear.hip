@@ -1001,7 +1001,8 @@ inline int64_t wgrad_part_bytes(const hot_linear_desc *d)
 }
 
 // ws_bytes: what the caller's workspace holds (0: none; a negative value: as much as wanted, for the size query)
-WgradShape wgrad_shape(const hot_linear_desc *d, int64_t ws_bytes)
+// wide_through_parts: count on eight row parts when deciding for two output groups per tile
+WgradShape wgrad_shape_with(const hot_linear_desc *d, int64_t ws_bytes, bool wide_through_parts)
 {
     WgradShape w;
     const long k_groups = (d->in_features + 63) / 64;
@@ -1009,7 +1010,8 @@ WgradShape wgrad_shape(const hot_linear_desc *d, int64_t ws_bytes)
     w.deep = d->rows >= kWgradDeepRows;
     // two output groups per tile where that still leaves a wave for every SIMD twice over after the row split
     // (four per tile were measured too: 90 against 95 TFLOP/s at 4096^2 x 1024, their registers spill)
-    w.ob = (d->rows >= kWgradWideRows && d->out_features >= 32 && k_groups * ((o_groups + 1) / 2) * wgrad_max_split(2) * (ws_bytes != 0 && d->rows >= 8192 ? 8 : 1) >= 2048) ? 2 : 1;
+    const long wide_waves = k_groups * ((o_groups + 1) / 2) * wgrad_max_split(2) * (wide_through_parts ? 8 : 1);
+    w.ob = (d->rows >= kWgradWideRows && d->out_features >= 32 && wide_waves >= 2048) ? 2 : 1;
     w.tiles = k_groups * ((o_groups + w.ob - 1) / w.ob);
     // few tiles and many rows: let several waves share a tile (each then draws the tile's eps itself)
     // (up to a wave on every SIMD twice over; beyond that only while a wave keeps a thousand rows: finer pieces
@@ -1038,6 +1040,15 @@ WgradShape wgrad_shape(const hot_linear_desc *d, int64_t ws_bytes)
         }
     }
     return w;
+}
+
+WgradShape wgrad_shape(const hot_linear_desc *d, int64_t ws_bytes)
+{
+    if (ws_bytes != 0 && d->rows >= 8192) {     // with parts, smaller layers afford the wide tiles too (16640 x 192 x 768: 51 -> 57 TFLOP/s)
+        const WgradShape w = wgrad_shape_with(d, ws_bytes, true);
+        if (w.parts > 1) return w;              // (else the workspace was too small for that)
+    }
+    return wgrad_shape_with(d, ws_bytes, false);
 }
 
 }  // namespace

@@ -266,10 +266,10 @@ hot_linear_forward_rows_kernel(LinearArgs a)
                     *reinterpret_cast<f4 *>(&tile[buf][st][(16 * no + dn) * kRowsKernelPitch + 4 * dq]) = w4;
                 }
             }
-            __syncthreads();
             {
                 // Two halves of 32 rows through the wave's own LDS rows.  Only this wave touches them and the LDS
-                // executes a wave's instructions in order, so no barrier is needed, only the program order.
+                // executes a wave's instructions in order, so no barrier is needed, only the program order.  It
+                // happens ahead of the workgroup's barrier: a wave that drew faster turns its x while it would wait.
                 float *mine = turn[wave];
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
@@ -294,6 +294,7 @@ hot_linear_forward_rows_kernel(LinearArgs a)
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 }
             }
+            __syncthreads();
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 if (s0 + st < a.s_loc) {          // uniform over the workgroup

@@ -251,13 +251,15 @@ int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double
  * few 16-output x 64-input tiles to give every compute unit weight-gradient work, and the waves of one
  * workgroup are all that can add up the rows of a tile without memory.  With a workspace the rows are cut
  * into up to 16 parts for different workgroups; each part leaves its sums there and a second kernel adds
- * them in part order and finishes the gradients: deterministic, no atomics.
+ * them in part order and finishes the gradients: deterministic, no atomics.  The input gradients use the
+ * same memory afterwards where 256-row workgroups are too few for the chip (few inputs, around a thousand
+ * rows): the outputs they contract over are cut into parts, whose dx blocks a second kernel adds.
  * hot_linear_backward_workspace_bytes(desc) returns the number of bytes with which the call splits as far
  * as it wants to (0: this shape would not use a workspace; HOT_EINVAL for a malformed desc).  workspace:
  * DEVICE, 16-byte aligned, owned by the caller, contents undefined afterwards, or NULL (then the call is
  * hot_linear_backward_rng); with fewer bytes than asked for the call splits less, or not at all.  Calls
  * that share a workspace must not overlap.  Results agree with hot_linear_backward_rng to the rounding of
- * a different order of summation over the rows.
+ * a different order of summation (over the rows; for dx over the outputs).
  */
 int64_t hot_linear_backward_workspace_bytes(const hot_linear_desc *desc);
 int hot_linear_backward_rng_ws(const hot_linear_desc *desc, int32_t s_total, double dataset_size, uint32_t flags,

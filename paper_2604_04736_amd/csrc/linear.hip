@@ -383,6 +383,8 @@ struct LinearGradArgs {
     float *gmu_w, *gsig_w, *gmu_b, *gsig_b, *dx;
     float *ws;              // PARTS kernels: partial sums [part][gm, gs][O*K + O]
     long rows_per_part;     // PARTS kernels: rows of one part, a multiple of 16
+    int x_parts;            // input gradients for many rows: parts the outputs are cut into (1: dx written directly)
+    long outs_per_part;     // outputs of one such part, a multiple of 16; partial dx blocks go to ws[part][S][R][K]
     Rng rng;
 };
 
@@ -787,7 +789,8 @@ void wgrad_go(long tiles, int waves, hipStream_t s, const LinearGradArgs &a)
 // i is input k0 + 16 j + 4 rr + i of row r0 + 16 rb + n; the lanes of a row exchange quads so that each store
 // covers 64 contiguous bytes of the row.  Every lane of the wave must call it.
 template <int RB>
-__device__ __forceinline__ void store_dx_tile(const f4 (&acc)[RB][4], int s, long r0, long k0, int j, int n, const LinearGradArgs &a)
+__device__ __forceinline__ void store_dx_tile(const f4 (&acc)[RB][4], float *dx, int s, long r0, long k0, int j, int n,
+                                              const LinearGradArgs &a)
 {
     const long K = a.in_features, R = a.rows;
 #pragma unroll
@@ -801,7 +804,7 @@ __device__ __forceinline__ void store_dx_tile(const f4 (&acc)[RB][4], int s, lon
         for (int t = 0; t < 4; ++t) {
             const long col = k0 + 16 * t + 4 * j;
             if (row < R && col < K)
-                store4<true, false>(a.dx + ((size_t)s * (size_t)R + (size_t)row) * (size_t)K + (size_t)col, q[t]);
+                store4<true, false>(dx + ((size_t)s * (size_t)R + (size_t)row) * (size_t)K + (size_t)col, q[t]);
         }
     }
 }
@@ -899,7 +902,7 @@ hot_linear_xgrad_kernel(LinearGradArgs a)
     }
     if (wave != 0) return;
 
-    store_dx_tile<RB>(acc, s, r0, k0, j, n, a);
+    store_dx_tile<RB>(acc, a.dx, s, r0, k0, j, n, a);
 }
 
 // ---------------------------------------------------------------------------------
@@ -915,6 +918,7 @@ hot_linear_xgrad_kernel(LinearGradArgs a)
 // as in the forward kernel; accumulators and epilogue are those of the kernel above.
 // ---------------------------------------------------------------------------------
 constexpr int kXgradRowsKernelOutputs = 16;    // outputs per iteration: one drawn quad per thread
+constexpr int kXgradMaxParts = 16;             // most parts the outputs are cut into with a workspace
 
 // RB: 16-row blocks per wave (a workgroup owns 64 RB rows); fewer of them where 256-row workgroups would be too few.
 template <int RB>
@@ -926,7 +930,13 @@ hot_linear_xgrad_rows_kernel(LinearGradArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15, j = lane >> 4;
     const long K = a.in_features, O = a.out_features, R = a.rows;
-    const long k0 = (long)blockIdx.x * 64, r0 = ((long)blockIdx.y * 4 + wave) * (kRowsPerTile * RB);
+    // with a workspace the outputs may be cut into parts for different workgroups (grid x = input groups x parts):
+    // this one contracts over the outputs o_lo .. o_hi - 1 only and leaves its block in the workspace
+    const long k_groups = (K + 63) / 64;
+    const long part = (long)blockIdx.x / k_groups, k0 = ((long)blockIdx.x % k_groups) * 64;
+    const long o_lo = a.x_parts > 1 ? part * a.outs_per_part : 0;
+    const long o_hi = a.x_parts > 1 && o_lo + a.outs_per_part < O ? o_lo + a.outs_per_part : O;
+    const long r0 = ((long)blockIdx.y * 4 + wave) * (kRowsPerTile * RB);
     const int s = blockIdx.z;
     const float *dys = a.dy + (size_t)s * (size_t)R * (size_t)O;
     const long kq = k0 + 4 * n;          // this lane's quad of inputs (as a drawing thread and as an A lane)
@@ -946,19 +956,19 @@ hot_linear_xgrad_rows_kernel(LinearGradArgs a)
     }
 
     int buf = 0;
-    for (long ob = 0; ob < O; ob += kXgradRowsKernelOutputs, buf ^= 1) {
+    for (long ob = o_lo; ob < o_hi; ob += kXgradRowsKernelOutputs, buf ^= 1) {
         const long o_draw = ob + 4 * j + wave;
-        const bool draw_ok = k_ok && o_draw < O;
+        const bool draw_ok = k_ok && o_draw < o_hi;
         f4 w4 = {0.0f, 0.0f, 0.0f, 0.0f};
         f4 dyq[RB];
-        if (ob + kXgradRowsKernelOutputs <= O) {         // uniform
+        if (ob + kXgradRowsKernelOutputs <= o_hi) {      // uniform
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) dyq[rb] = load4<false, false>(dys + at[rb] + ob);
         } else {                                         // last, partial step: outputs beyond O contribute zeros
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) dyq[rb][c] = ob + 4 * j + c < O ? dys[at[rb] + ob + c] : 0.0f;
+                for (int c = 0; c < 4; ++c) dyq[rb][c] = ob + 4 * j + c < o_hi ? dys[at[rb] + ob + c] : 0.0f;
         }
         if (draw_ok) {
             const f4 m4 = load4<true, false>(a.mu_w + o_draw * K + kq), sd4 = load4<true, false>(a.sigma_w + o_draw * K + kq);
@@ -979,7 +989,23 @@ hot_linear_xgrad_rows_kernel(LinearGradArgs a)
         }
     }
 
-    store_dx_tile<RB>(acc, s, r0, k0, j, n, a);
+    float *dst = a.x_parts > 1 ? a.ws + (size_t)part * (size_t)a.s_loc * (size_t)R * (size_t)K : a.dx;
+    store_dx_tile<RB>(acc, dst, s, r0, k0, j, n, a);
+}
+
+// dx = the sum of the parts' blocks in the workspace, in part order; one quad per thread.
+__global__ void __launch_bounds__(256)
+hot_linear_dx_sum_kernel(float *__restrict__ dx, const float *__restrict__ ws, long quads, int parts)
+{
+    const long q = (long)blockIdx.x * 256 + threadIdx.x;
+    if (q >= quads) return;
+    f4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int p = 0; p < parts; ++p) {
+        const f4 v = load4<true, false>(ws + (size_t)p * (size_t)quads * 4 + (size_t)q * 4);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) sum[c] += v[c];
+    }
+    store4<true, false>(dx + (size_t)q * 4, sum);
 }
 
 template <int RB>
@@ -987,6 +1013,32 @@ void xgrad_go(dim3 grid, int waves, hipStream_t s, const LinearGradArgs &a)
 {
     const size_t lds = waves > 1 ? (size_t)(waves - 1) * (size_t)(RB * 16) * 64 * sizeof(float) : 0;
     hot_linear_xgrad_kernel<RB><<<grid, dim3(64 * waves), lds, s>>>(a);
+}
+
+// Input gradients for many rows on too few workgroups of 256 rows (few 64-input groups, around a thousand
+// rows): with a workspace the contraction over the outputs is cut into parts (1024 x 540 x 2160: 72
+// workgroups, 0.15 ms with 64-row workgroups instead).  Returns the number of parts, 1 for none.
+// ws_bytes as in wgrad_shape.
+inline long xgrad_outs_per_part(const hot_linear_desc *d, int parts)
+{
+    return ((d->out_features + parts - 1) / parts + kXgradRowsKernelOutputs - 1) / kXgradRowsKernelOutputs * kXgradRowsKernelOutputs;
+}
+
+int xgrad_parts(const hot_linear_desc *d, int64_t ws_bytes)
+{
+    if (ws_bytes == 0 || d->rows < 256) return 1;
+    const long k_groups = (d->in_features + 63) / 64, gy = (d->rows + 255) / 256;
+    const long wgs = k_groups * gy * d->s_local;
+    if (wgs >= 256 || gy > 65535) return 1;
+    const int64_t block_bytes = (int64_t)d->s_local * d->rows * d->in_features * (int64_t)sizeof(float);
+    int parts = 1;
+    // up to two workgroups per compute unit; a part keeps at least 64 outputs (four steps)
+    while (parts < kXgradMaxParts && wgs * parts < 512 && d->out_features >= 64L * (2 * parts) &&
+           (ws_bytes < 0 || (int64_t)(2 * parts) * block_bytes <= ws_bytes))
+        parts *= 2;
+    // (the parts must all exist: the last one begins below O)
+    while (parts > 1 && xgrad_outs_per_part(d, parts) * (parts - 1) >= d->out_features) parts /= 2;
+    return parts;
 }
 
 // Launch shape of the weight-gradient kernel.
@@ -1060,8 +1112,12 @@ int64_t hot_linear_backward_workspace_bytes(const hot_linear_desc *d)
 {
     if (!d || d->rows < 1 || d->in_features < 4 || (d->in_features & 3) || d->out_features < 1 || d->s_local < 1) return HOT_EINVAL;
     if (d->out_features > (INT64_MAX / 64) / d->in_features) return HOT_EINVAL;
+    if (d->rows > (INT64_MAX / 64) / d->in_features || d->rows * d->in_features > (INT64_MAX / 64) / d->s_local) return HOT_EINVAL;
     const WgradShape w = wgrad_shape(d, -1);
-    return w.parts > 1 ? (int64_t)w.parts * wgrad_part_bytes(d) : 0;
+    const int64_t for_weights = w.parts > 1 ? (int64_t)w.parts * wgrad_part_bytes(d) : 0;
+    const int x_parts = xgrad_parts(d, -1);
+    const int64_t for_inputs = x_parts > 1 ? (int64_t)x_parts * d->s_local * d->rows * d->in_features * (int64_t)sizeof(float) : 0;
+    return for_weights > for_inputs ? for_weights : for_inputs;       // the two kernels use it one after the other
 }
 
 int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const float *x, const float *mu_w,
@@ -1204,6 +1260,8 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
     a.dx = dx;
     a.ws = nullptr;
     a.rows_per_part = 0;
+    a.x_parts = 1;
+    a.outs_per_part = 0;
     a.rng = r;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
@@ -1244,6 +1302,17 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
     };
     // many rows: the workgroup-shared draw, with as many rows per workgroup (256, 128, 64) as still give every
     // compute unit a workgroup
+    if (const int x_parts = xgrad_parts(d, workspace ? workspace_bytes : 0); x_parts > 1) {
+        // too few 256-row workgroups: the outputs are cut into parts, summed from the workspace afterwards
+        a.ws = static_cast<float *>(workspace);
+        a.x_parts = x_parts;
+        a.outs_per_part = xgrad_outs_per_part(d, x_parts);
+        const long gy_c = (d->rows + 255) / 256;
+        hot_linear_xgrad_rows_kernel<4><<<dim3((unsigned)(k_groups * x_parts), (unsigned)gy_c, (unsigned)d->s_local), dim3(256), 0, s>>>(a);
+        const long quads = (long)d->s_local * d->rows * d->in_features / 4;
+        hot_linear_dx_sum_kernel<<<dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s>>>(dx, a.ws, quads, x_parts);
+        return hot_detail::note_hip(hipGetLastError());
+    }
     if (d->rows >= 256) {
         for (int cand = 4; cand >= 1; cand >>= 1) {
             const long gy_c = (d->rows + 64 * cand - 1) / (64 * cand);

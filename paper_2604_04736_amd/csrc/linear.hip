@@ -43,6 +43,20 @@ constexpr int max_waves(int rb) { return rb >= 4 ? 4 : (rb >= 2 ? 8 : kMaxWaves)
 // Four samples' accumulators are live together only where the register file holds them without spills.
 constexpr bool four_samples_fit(int rb, bool per_sample_x) { return rb == 2 || (rb == 1 && !per_sample_x); }
 
+// The matrix pipeline writes the registers of an accumulator over several passes after the instruction has
+// issued, and only wait states keep a following read from seeing the old value.  The compiler inserts them,
+// but left them out where a branch lay between the last matrix instruction and the first read of its result:
+// in one kernel variant the register written last came back stale (one row's product missing from one
+// column of the weight gradients; found by comparing launch shapes on random layer sizes).  Every run of
+// matrix instructions whose results are read next therefore ends here: 32 wait states that the scheduler
+// may not move, more than any of these instructions needs.
+__device__ __forceinline__ void mfma_results_settle()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 struct LinearArgs {
     long rows, in_features, out_features, ldx;
     long x_sample_stride;   // floats between the inputs of consecutive samples (0: one input for all)
@@ -132,6 +146,7 @@ hot_linear_forward_kernel(LinearArgs a)
                 }
             }
         }
+        mfma_results_settle();
 
         if (waves > 1) {
             __syncthreads();            // the previous chunk's readers are done with the buffer
@@ -314,6 +329,7 @@ hot_linear_forward_rows_kernel(LinearArgs a)
                 }
             }
         }
+        mfma_results_settle();
         __syncthreads();        // the chunk's last reads are done before the next chunk's first draw lands in buffer 0
 
 #pragma unroll
@@ -612,6 +628,7 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
             }
             multiply(bv, av);
         }
+        mfma_results_settle();
         if (row_first < r_hi) {          // a wave without rows has nothing to add (uniform over the wave)
 #pragma unroll
             for (int b = 0; b < OB; ++b) {
@@ -877,6 +894,7 @@ hot_linear_xgrad_kernel(LinearGradArgs a)
                     acc[rb][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w4[i], dyq[rb][c], acc[rb][i], 0, 0, 0);
         }
     }
+    mfma_results_settle();
 
     if (waves > 1) {
         if (wave > 0) {
@@ -988,6 +1006,7 @@ hot_linear_xgrad_rows_kernel(LinearGradArgs a)
                     acc[rb][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[i], dyq[rb][c], acc[rb][i], 0, 0, 0);
         }
     }
+    mfma_results_settle();
 
     float *dst = a.x_parts > 1 ? a.ws + (size_t)part * (size_t)a.s_loc * (size_t)R * (size_t)K : a.dx;
     store_dx_tile<RB>(acc, dst, s, r0, k0, j, n, a);

@@ -266,7 +266,10 @@ WITH_WORKSPACE = [(4200, 64, 48, 2, False, True, False, 1.0, True), (17000, 36, 
                   # input gradients on too few 256-row workgroups: the outputs cut into parts (ragged last part; a
                   # workspace for fewer parts; none)
                   (1030, 132, 700, 2, False, True, True, 1.0, True), (300, 36, 333, 3, True, False, True, 1.0, True),
-                  (1030, 132, 700, 2, False, True, True, 0.6, True), (1030, 132, 700, 2, False, True, True, 0.1, False)]
+                  (1030, 132, 700, 2, False, True, True, 0.6, True), (1030, 132, 700, 2, False, True, True, 0.1, False),
+                  # the shape on which one accumulator register was once read before the matrix pipeline had written it
+                  # (a partial last row block in a tile without biases; the kernels now wait explicitly)
+                  (19549, 84, 1744, 1, False, True, False, 1.0, True)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias,want_dx,fraction,used", WITH_WORKSPACE)

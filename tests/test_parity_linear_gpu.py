@@ -588,3 +588,48 @@ def test_swin_layer_at_its_full_size_on_sampled_blocks(oracle, hot):
     mag = np.einsum("sro,sok->srk", ady[:, r_sub], m64[None] + s64[None] * rw)
     err = np.abs(out["dx"].cpu().numpy()[:, r_sub].astype(np.float64) - xb[4])
     assert np.all(err <= 1e-5 * mag), f"dx: worst {np.max(err / mag):.2e}"
+
+
+def test_random_layer_shapes_agree_with_and_without_a_workspace(hot):
+    """Two launch shapes of the same computation on seeded random layer sizes (hundreds to twenty thousand rows,
+    few to many tiles, with and without biases and per-sample inputs, whole and partial workspaces): the call
+    with a workspace against the call without one, every output, to the rounding of a different order of
+    summation.  Each shape is checked against the oracle elsewhere; this comparison is cheap enough to reach
+    sizes and tile counts that the oracle cannot, and it is the one that exposed the stale accumulator read
+    which mfma_results_settle now rules out."""
+    rs = np.random.default_rng(7)
+    done = 0
+    while done < 24:
+        rows = int(rs.choice([rs.integers(256, 1200), rs.integers(1200, 6000), rs.integers(6000, 20000)]))
+        k = 4 * int(rs.choice([rs.integers(1, 20), rs.integers(20, 160)]))
+        o = int(rs.choice([rs.integers(1, 40), rs.integers(40, 900), rs.integers(900, 2600)]))
+        s = int(rs.integers(1, 4))
+        bias, xs = bool(rs.integers(0, 2)), bool(rs.integers(0, 2))
+        frac = float(rs.choice([1.0, 1.0, 0.5, 0.2]))
+        if rows * k * o * s > 3e9:
+            continue
+        done += 1
+        print("case", done, rows, k, o, s, bias, xs, frac, flush=True)
+        g = torch.Generator(device=DEV).manual_seed(done)
+        x = torch.randn((s, rows, k) if xs else (rows, k), device=DEV, generator=g)
+        mu = torch.randn(o, k, device=DEV, generator=g) * 0.05
+        sg = torch.rand(o, k, device=DEV, generator=g) * 0.01 + 0.001
+        mb = torch.randn(o, device=DEV, generator=g) if bias else None
+        sb = (torch.rand(o, device=DEV, generator=g) * 0.01 + 0.001) if bias else None
+        dy = torch.randn(s, rows, o, device=DEV, generator=g)
+        n_ws = max(int(hot.hot_linear_backward_workspace_bytes(rows, k, o, s) * frac) // 16 * 4, 4)
+        outs = []
+        for ws in (None, torch.full((n_ws + 16,), float("nan"), device=DEV)):
+            t = [torch.full((o, k), float("nan"), device=DEV), torch.full((o, k), float("nan"), device=DEV),
+                 torch.full((o,), float("nan"), device=DEV) if bias else None,
+                 torch.full((o,), float("nan"), device=DEV) if bias else None, torch.full((s, rows, k), float("nan"), device=DEV)]
+            hot.hot_linear_backward_rng(hot.hot_rng(seed=5, step=done, first_sample=0), x, dy, mu, sg, mb, sb, *t, 2 * s, 4500.0,
+                                        hot.HOT_REDUCE_SUM, 0, o * k, workspace=None if ws is None else ws[:n_ws])
+            torch.cuda.synchronize()
+            if ws is not None:
+                assert bool(torch.isnan(ws[n_ws:]).all()), "written beyond the workspace"
+            outs.append([v for v in t if v is not None])
+        for a, b in zip(*outs):
+            assert bool(torch.isfinite(a).all()) and bool(torch.isfinite(b).all())
+            # a sum of R (or O) products of unit-scale factors: its fp32 rounding is far below 1e-4 of the largest sum
+            assert (a - b).abs().max().item() <= 1e-4 * max(a.abs().max().item(), 1e-6)

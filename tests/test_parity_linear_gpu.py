@@ -633,3 +633,61 @@ def test_random_layer_shapes_agree_with_and_without_a_workspace(hot):
             assert bool(torch.isfinite(a).all()) and bool(torch.isfinite(b).all())
             # a sum of R (or O) products of unit-scale factors: its fp32 rounding is far below 1e-4 of the largest sum
             assert (a - b).abs().max().item() <= 1e-4 * max(a.abs().max().item(), 1e-6)
+
+
+def test_random_layer_shapes_forward_and_dx_against_materialised_weights(hot):
+    """Seeded random layer sizes beyond the oracle's reach (one to twenty thousand rows, every kernel of the
+    forward and input-gradient dispatch): y and dx of the fused calls against fp64 products on the GPU with
+    the weights that hot_forward_rng materialises for the same hot_rng (that call is compared with the
+    oracle in test_parity_rng_gpu.py), within 1e-5 of the sum of the magnitudes of the addends."""
+    rs = np.random.default_rng(11)
+    done = 0
+    while done < 24:
+        rows = int(rs.choice([rs.integers(1, 70), rs.integers(70, 1200), rs.integers(1200, 20000)]))
+        k = 4 * int(rs.choice([rs.integers(1, 20), rs.integers(20, 160)]))
+        o = int(rs.choice([rs.integers(1, 40), rs.integers(40, 900), rs.integers(900, 2600)]))
+        s = int(rs.integers(1, 4))
+        bias, xs = bool(rs.integers(0, 2)), bool(rs.integers(0, 2))
+        if rows * k * o * s > 3e9:
+            continue
+        done += 1
+        print("case", done, rows, k, o, s, bias, xs, flush=True)
+        g = torch.Generator(device=DEV).manual_seed(100 + done)
+        x = torch.randn((s, rows, k) if xs else (rows, k), device=DEV, generator=g)
+        n_w = o * k
+        b_off = n_w + 8
+        n = b_off + ((o + 3) // 4) * 4
+        mu = torch.randn(n, device=DEV, generator=g) * 0.1
+        sigma = torch.rand(n, device=DEV, generator=g) * 0.05 + 0.01
+        rng = hot.hot_rng(seed=17, step=done, first_sample=0)
+        plan = hot.hot_create(n, n, s, s, 1.0, 0)
+        w = torch.empty(s, n, device=DEV)
+        hot.hot_forward_rng(plan, rng, mu, sigma, w)
+        hot.hot_destroy(plan)
+        mu_w, sg_w = mu[:n_w].view(o, k), sigma[:n_w].view(o, k)
+        mu_b, sg_b = (mu[b_off:b_off + o], sigma[b_off:b_off + o]) if bias else (None, None)
+        y = torch.full((s, rows, o), float("nan"), device=DEV)
+        hot.hot_linear_forward_rng(rng, x, mu_w, sg_w, mu_b, sg_b, y, 0, b_off)
+        dy = torch.randn(s, rows, o, device=DEV, generator=g)
+        dx = torch.full((s, rows, k), float("nan"), device=DEV)
+        gw = [torch.empty(o, k, device=DEV), torch.empty(o, k, device=DEV)]
+        gb = [torch.empty(o, device=DEV), torch.empty(o, device=DEV)] if bias else [None, None]
+        hot.hot_linear_backward_rng(rng, x, dy, mu_w, sg_w, mu_b, sg_b, gw[0], gw[1], gb[0], gb[1], dx, s, 100.0,
+                                    hot.HOT_REDUCE_SUM, 0, b_off)
+        torch.cuda.synchronize()
+        w3 = w[:, :n_w].view(s, o, k).double()
+        x3 = (x if xs else x.unsqueeze(0).expand(s, rows, k)).double()
+        want_y = torch.matmul(x3, w3.transpose(1, 2))
+        A_y = torch.matmul(x3.abs(), w3.abs().transpose(1, 2))
+        if bias:
+            want_y = want_y + w[:, b_off:b_off + o].double().unsqueeze(1)
+            A_y = A_y + w[:, b_off:b_off + o].double().abs().unsqueeze(1)
+        assert bool(torch.isfinite(y).all()) and bool(((y.double() - want_y).abs() <= 1e-5 * A_y + 1e-30).all()), "y"
+        want_dx = torch.matmul(dy.double(), w3)
+        A_dx = torch.matmul(dy.double().abs(), w3.abs())
+        assert bool(torch.isfinite(dx).all()) and bool(((dx.double() - want_dx).abs() <= 1e-5 * A_dx + 1e-30).all()), "dx"
+        # weight gradients, mu part: g * sum_s dy_s^T x_s + k_kl mu  (g = 1/S, k_kl = 1/|D| here)
+        G = torch.matmul(dy.double().transpose(1, 2), x3)
+        A_g = torch.matmul(dy.double().abs().transpose(1, 2), x3.abs()).sum(0) / s + mu_w.double().abs() / 100.0
+        want_g = G.sum(0) / s + mu_w.double() / 100.0
+        assert bool(((gw[0].double() - want_g).abs() <= 1e-5 * A_g + 1e-30).all()), "grad_mu_w"

@@ -135,3 +135,15 @@ def test_device_code_has_no_packed_instructions(tmp_path):
     with ThreadPoolExecutor(max_workers=len(build.SRCS)) as pool:
         found = dict(zip(build.SRCS, pool.map(packed, build.SRCS)))
     assert all(not v for v in found.values()), {k: v[:3] for k, v in found.items() if v}
+
+    # Every kernel that uses the matrix cores ends its runs of matrix instructions with explicit wait states
+    # (mfma_results_settle in linear.hip: the compiler once left them out behind a branch and an accumulator
+    # register was read before the matrix pipeline had written it).
+    kernels = 0
+    for src in build.SRCS:
+        text = open(tmp_path / (os.path.basename(src) + ".s")).read()
+        for m in re.finditer(r"^(_Z\w+):[^\n]*\n(.*?)s_endpgm", text, re.S | re.M):
+            if "v_mfma" in m.group(2):
+                kernels += 1
+                assert "s_nop 15" in m.group(2), m.group(1)
+    assert kernels >= 10        # the instantiations of the five kernels of the linear layer

@@ -180,11 +180,48 @@ def verify_sampled_rng(oracle, np, wl, x, out, blocks: int, width: int) -> bool:
     return True
 
 
-def cpu_baseline(oracle, np, wl, x, max_weights: int):
-    """The oracle as it stands, timed on the host cores over the first max_weights weights."""
+def compare_every_element(np, wl, h, n, w64, kl64, gm64, gs64, out):
+    """Every element of the timed buffers against the oracle arrays cpu_baseline has just computed: the
+    largest error of each output in units of its tolerance scale (the tests' scales: |w64| for w, the sums
+    of addend magnitudes for the KL term and the gradients) and whether all lie within 1e-5 of it."""
+    g = 1.0 / wl.s_total
+    k = wl.s_local / (wl.s_total * wl.dataset_size)
+    worst = {"w": 0.0, "grad_mu": 0.0, "grad_sigma": 0.0}
+    step = 1 << 24
+    tiny = np.finfo(np.float64).tiny
+    for a in range(0, n, step):
+        b = min(n, a + step)
+        m64, s64 = h["mu"][a:b].astype(np.float64), h["sigma"][a:b].astype(np.float64)
+        G64, e64 = h["G"][:, a:b].astype(np.float64), h["eps"][:, a:b].astype(np.float64)
+        ref = w64[:, a:b]
+        err = np.abs(out["w"][:, a:b].cpu().numpy() - ref) / np.maximum(np.abs(ref), tiny)
+        worst["w"] = max(worst["w"], float(err.max()))
+        scale = g * np.abs(G64).sum(0) + k * np.abs(m64)
+        err = np.abs(out["gmu"][a:b].cpu().numpy() - gm64[a:b]) / np.maximum(scale, tiny)
+        worst["grad_mu"] = max(worst["grad_mu"], float(err.max()))
+        scale = g * np.abs(G64 * e64).sum(0) + k * (s64 + 1.0 / s64)
+        err = np.abs(out["gsig"][a:b].cpu().numpy() - gs64[a:b]) / np.maximum(scale, tiny)
+        worst["grad_sigma"] = max(worst["grad_sigma"], float(err.max()))
+    m64, s64 = h["mu"].astype(np.float64), h["sigma"].astype(np.float64)
+    kl_scale = 0.5 * float(np.sum(s64 * s64 + m64 * m64 + 1.0 + np.abs(2.0 * np.log(s64))))
+    worst["kl"] = abs(out["kl"].item() - kl64) / kl_scale
+    return {"max_error_over_scale": worst, "tolerance": 1e-5, "elements": {"w": n * wl.s_local, "grad_mu": n, "grad_sigma": n},
+            "all_within_tolerance": bool(all(v <= 1e-5 for v in worst.values())),
+            "scales": "w: |w64|; KL: 1/2 sum(sigma^2 + mu^2 + 1 + |2 ln sigma|); grad_mu: g sum_s|G| + k|mu|; "
+                      "grad_sigma: g sum_s|G eps| + k(sigma + 1/sigma)"}
+
+
+def cpu_baseline(oracle, np, wl, x, max_weights: int, out=None):
+    """The oracle as it stands, timed on the host cores over the first max_weights weights.  With the timed
+    buffers in `out` and the whole workload inside max_weights, the arrays the oracle has just produced are
+    then compared with them element by element (outside the timed interval)."""
     n = min(wl.n_weights, max_weights)
-    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
-    cores = max(1, min(cores, 16))
+    # the threads the oracle is given: the cores this process may run on, within OMP_NUM_THREADS when the
+    # environment sets a CPU share (the GPU boxes do: 16 per GPU, whatever the host's core count)
+    host_cores = os.cpu_count() or 1
+    affinity = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else host_cores
+    share = int(os.environ.get("OMP_NUM_THREADS", "0") or 0)
+    cores = max(1, min(affinity, share) if share > 0 else affinity)
     h = {"mu": x["mu"][:n].cpu().numpy(), "sigma": x["sigma"][:n].cpu().numpy(),
          "eps": np.ascontiguousarray(x["eps"][:, :n].cpu().numpy()),
          "G": np.ascontiguousarray(x["G"][:, :n].cpu().numpy())}
@@ -194,6 +231,9 @@ def cpu_baseline(oracle, np, wl, x, max_weights: int):
     kl64 = oracle.kl(h["mu"], h["sigma"])
     gm, gs = oracle.grad(h["mu"], h["sigma"], h["eps"], h["G"], wl.s_total, wl.dataset_size, False, used)
     dt = time.perf_counter() - t0
+    compared = None
+    if out is not None and n == wl.n_weights:
+        compared = compare_every_element(np, wl, h, n, w64, kl64, gm, gs, out)
     del w64, gm, gs
     # the same three calls on one thread, over an eighth of the sample
     n1 = max(1, n // 8)
@@ -207,11 +247,12 @@ def cpu_baseline(oracle, np, wl, x, max_weights: int):
     dt1 = time.perf_counter() - t1
     del w64, gm, gs
     return {"value": n * wl.s_local / dt, "unit": "items/s", "cores": used, "kind": "oracle",
+            "host": {"nproc": host_cores, "affinity": affinity, "omp_num_threads_env": share or None},
             "single_thread": {"value": n1 * wl.s_local / dt1, "unit": "items/s", "cores": one,
                               "sample": f"first {n1} weights, {dt1:.1f} s"},
             "sample": f"first {n} of {wl.n_weights} weights x {wl.s_local} samples of {wl.name}, "
                       f"forward + KL + backward, {dt:.1f} s (KL sum is serial by definition)",
-            "kl": kl64}
+            "kl": kl64, "every_element": compared}
 
 
 def alu_roofline_forward_rng(s_local: int, achieved_items_per_s: float):
@@ -667,9 +708,15 @@ def main() -> int:
         result["framework_reference"] = fw
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(oracle, np, wl, x, args.cpu_weights)
+        result["cpu_baseline"] = cpu_baseline(oracle, np, wl, x, args.cpu_weights, None if gen else r["out"])
         kl_gpu = r["out"]["kl"].item()
         result["cpu_baseline"]["kl_gpu"] = kl_gpu
+        every = result["cpu_baseline"].pop("every_element")
+        if every is not None:
+            # every element of the timed buffers of the headline workload against the oracle, not a sample
+            result["verified_every_element"] = every
+            if not every["all_within_tolerance"]:
+                verified = result["verified_against_oracle"] = False
     del x, r
     torch.cuda.empty_cache()
 

@@ -269,8 +269,8 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *desc, int32_t s_total, dou
                                int64_t workspace_bytes, void *stream);
 
 /*
- * "Update mu and sigma using optimizer (e.g., Adam)" -- the last line of the inner loop of
- * Algorithm 1 / 2, run on the all-reduced gradients.  The paper gives no hyper-parameters:
+ * The optimizer-update line that closes the inner loop of Algorithm 1 / 2 (the paper names Adam as
+ * its example), run on the all-reduced gradients.  The paper gives no hyper-parameters:
  * they are inputs.  Adam as published (Kingma and Ba, ICLR 2015), for mu and for sigma with
  * their own moments, in place, fp32:
  *   g = grad_scale * grad;  m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2
@@ -340,10 +340,11 @@ int hot_adam_forward(hot_plan *plan, const hot_rng *rng, const hot_adam *params,
                      float *v_sigma, const float *eps, float *w, double *kl_out, void *stream);
 
 /*
- * Monte Carlo dropout in weight space (section "Monte Carlo Dropout": dropout amounts to
- * multiplying every weight with a Bernoulli variable; each of the S stochastic passes uses its
+ * Monte Carlo dropout in weight space (section "Monte Carlo Dropout": in the variational reading of
+ * dropout each weight carries a random 0/1 keep factor; each of the S stochastic passes uses its
  * own mask).  For sample s and weight i the mask bit is (generator word of (s, i) <
- * floor(keep * 2^32)), the word being the one hot_sample_bits returns for the same hot_rng:
+ * floor(keep * 2^32)), compared as 64-bit integers so that keep = 1 keeps every weight, the word being
+ * the one hot_sample_bits returns for the same hot_rng:
  *   forward   w[s,i]     = mu[i] * bit / keep                  (1/keep keeps E[w] = mu)
  *   backward  grad_mu[i] = g * sum_s grad_w[s,i] * bit / keep   (g = 1/S; 1/S_loc with HOT_REDUCE_MEAN; 1 with HOT_REDUCE_NONE)
  * The mask is never stored; the backward call regenerates it.  desc gives N, ld, S_loc, S and
@@ -357,7 +358,7 @@ int hot_backward_dropout_rng(const hot_desc *desc, const hot_rng *rng, double ke
 
 /*
  * The same layer with one Bernoulli variable per NEURON and sample instead of one per weight
- * (the same section: dropout "sets a subset of neurons to zero"): mu is the [out, in_features]
+ * (the same section also describes dropout unit-wise, zeroing whole neurons): mu is the [out, in_features]
  * row-major weight matrix of a layer (desc->n_weights = out * in_features), and dropping input
  * unit k of sample s zeroes column k, i.e. all weights i with i mod in_features == k.  The mask
  * bit of unit k is (generator word of flat index unit_offset + k < floor(keep * 2^32)), so

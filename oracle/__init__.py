@@ -86,7 +86,7 @@ def _load():
     lib.update_oracle_adam.argtypes = [ctypes.c_int64, ctypes.POINTER(AdamParams), dp, dp, dp, dp, dp, dp, dp, dp]
     lib.update_oracle_adam.restype = None
     lib.update_oracle_dropout_threshold.argtypes = [ctypes.c_double]
-    lib.update_oracle_dropout_threshold.restype = ctypes.c_uint32
+    lib.update_oracle_dropout_threshold.restype = ctypes.c_uint64
     lib.update_oracle_dropout_forward.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_double,
                                                   fp, u32p, dp]
     lib.update_oracle_dropout_forward.restype = None

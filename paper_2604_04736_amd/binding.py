@@ -31,6 +31,11 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_linear_backward_rng_ws", "hot_linear_backward_workspace_bytes")
 
 
+# Return types of the entry points that do not return an int status (as declared in include/hot.h).
+RESTYPES = {"hot_strerror": ctypes.c_char_p, "hot_recommended_ld": ctypes.c_int64,
+            "hot_linear_backward_workspace_bytes": ctypes.c_int64}
+
+
 class hot_desc(ctypes.Structure):
     _fields_ = [("n_weights", ctypes.c_int64), ("ld", ctypes.c_int64),
                 ("s_local", ctypes.c_int32), ("s_total", ctypes.c_int32),
@@ -131,7 +136,7 @@ def lib() -> ctypes.CDLL:
                                   ctypes.c_int64, ctypes.c_int32, vp, vp, vp]
     L.hot_stats_merge.restype = ctypes.c_int
     for name in EXPORTS:
-        if name not in ("hot_strerror", "hot_recommended_ld"):
+        if name not in RESTYPES:
             getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L

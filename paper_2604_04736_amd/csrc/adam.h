@@ -1,6 +1,6 @@
 // Adam's update of one parameter (Kingma and Ba, ICLR 2015) in fp32, and the constants it needs,
 // shared by the stand-alone optimizer kernel and by the backward kernel that applies the update
-// in its epilogue (arxiv 2604.04736, Algorithm 1 / 2: "Update mu and sigma using optimizer").
+// in its epilogue (arxiv 2604.04736, Algorithm 1 / 2: the optimizer-update line).
 #ifndef HOT_ADAM_H
 #define HOT_ADAM_H
 

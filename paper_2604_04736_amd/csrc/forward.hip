@@ -14,7 +14,7 @@ struct NoPrologue {
     __device__ __forceinline__ void one(long, float &, float &) const {}
 };
 
-// AdamPrologue: the update line of the previous step first ("Update mu and sigma using optimizer"),
+// AdamPrologue: the optimizer-update line of the previous step first (Algorithm 1 / 2, end of the inner loop),
 // on the all-reduced gradients, with hot_adam_step's arithmetic; the updated parameters are stored
 // and, still in registers, sampled from, so they are not read a second time.
 struct AdamPrologue {

@@ -217,11 +217,7 @@ int hot_create(hot_plan **out, const hot_desc *desc)
 {
     if (!out || !desc) return HOT_EINVAL;
     const hot_desc &d = *desc;
-    if (d.n_weights < 1 || d.ld < d.n_weights || d.s_local < 1 || d.s_total < d.s_local) return HOT_EINVAL;
-    if (!(d.dataset_size > 0.0) || !(d.dataset_size < 1.0 / 0.0)) return HOT_EINVAL;
-    if (d.flags != HOT_REDUCE_SUM && d.flags != HOT_REDUCE_MEAN && d.flags != HOT_REDUCE_NONE) return HOT_EINVAL;
-    // element offsets (s_local - 1) * ld + n_weights must fit in 63 bits
-    if (d.ld > (INT64_MAX / 4) / d.s_local) return HOT_EINVAL;
+    if (!valid_desc(d)) return HOT_EINVAL;
     int n_dev = 0;
     if (hipError_t e = hipGetDeviceCount(&n_dev); e != hipSuccess) return hot_detail::note_hip(e);
     if (d.device < 0 || d.device >= n_dev) return HOT_EINVAL;
@@ -229,16 +225,7 @@ int hot_create(hot_plan **out, const hot_desc *desc)
     hot_plan *p = new (std::nothrow) hot_plan();
     if (!p) return HOT_ENOMEM;
     p->d = d;
-    if (d.flags == HOT_REDUCE_NONE) {
-        p->g = 1.0;
-        p->k = 1.0 / d.dataset_size;
-    } else if (d.flags == HOT_REDUCE_MEAN) {
-        p->g = 1.0 / (double)d.s_local;
-        p->k = 1.0 / d.dataset_size;
-    } else {
-        p->g = 1.0 / (double)d.s_total;
-        p->k = (double)d.s_local / ((double)d.s_total * d.dataset_size);
-    }
+    set_scaling(*p);
     p->partials = nullptr;
     p->last_hip = 0;
 
@@ -255,33 +242,7 @@ int hot_create(hot_plan **out, const hot_desc *desc)
         delete p;
         return oom ? HOT_ENOMEM : hot_detail::note_hip(e);
     }
-    // Defaults from launch-shape sweeps on MI355X, each kernel timed with the other one running in
-    // between (timing a kernel back to back with itself lets part of its input stay in the 256 MiB
-    // memory-side cache and favours shapes that lose in a real step): four chunks per thread for
-    // the array kernels, single rows in flight forward, as many rows as there are (up to four)
-    // backward.  Non-temporal hints pay only when the streamed arrays are larger than that cache.
-    const bool streams_exceed_cache = (double)d.s_local * (double)d.ld * 4.0 >= 256.0 * 1048576.0;
-    hot_launch &f = p->cfg[HOT_KERNEL_FORWARD], &b = p->cfg[HOT_KERNEL_BACKWARD];
-    f.grid_blocks = b.grid_blocks = kMaxGrid;
-    f.chunks = b.chunks = 4;
-    f.unroll = 1;
-    b.unroll = pick_unroll(4, d.s_local);
-    f.nontemporal = b.nontemporal = streams_exceed_cache ? 1 : 0;
-    // With fewer than four samples the four-chunk backward kernels are fat (over 200 registers per lane,
-    // two workgroups per compute unit) and short: below 16 M weights their last, partly filled round of
-    // workgroups costs 5-10 %, which one chunk per thread avoids.
-    const bool few_tiles = d.n_weights < (16L << 20);
-    if (d.s_local < 4 && few_tiles) b.chunks = 1;
-    // The drawing variants have no eps loads to keep in flight.  Forward: as above up to seven samples;
-    // from eight on one chunk per thread (38 registers, eight waves per SIMD) hides the generator's
-    // latencies better than four independent chains in five waves (10-20 % at 8 M to 25 M weights).
-    // Backward: two chunks and single rows from four samples on.
-    hot_launch &fr = p->cfg[HOT_KERNEL_FORWARD_RNG], &br = p->cfg[HOT_KERNEL_BACKWARD_RNG];
-    fr = f;
-    if (d.s_local >= 8) fr.chunks = 1;
-    br = b;
-    br.chunks = d.s_local >= 4 ? 2 : (few_tiles ? 1 : 4);
-    br.unroll = pick_unroll(d.s_local >= 4 ? 1 : 2, d.s_local);
+    default_launches(*p);
     *out = p;
     return HOT_OK;
 }

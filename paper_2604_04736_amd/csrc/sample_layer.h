@@ -160,6 +160,65 @@ inline bool valid_launch(const hot_launch &c)
            (c.nontemporal == 0 || c.nontemporal == 1);
 }
 
+// What every entry point requires of a description (device aside).
+inline bool valid_desc(const hot_desc &d)
+{
+    if (d.n_weights < 1 || d.ld < d.n_weights || d.s_local < 1 || d.s_total < d.s_local) return false;
+    if (!(d.dataset_size > 0.0) || !(d.dataset_size < 1.0 / 0.0)) return false;
+    if (d.flags != HOT_REDUCE_SUM && d.flags != HOT_REDUCE_MEAN && d.flags != HOT_REDUCE_NONE) return false;
+    // element offsets (s_local - 1) * ld + n_weights must fit in 63 bits
+    return d.ld <= (INT64_MAX / 4) / d.s_local;
+}
+
+// g and k of the gradient and averaging lines of Algorithm 2 for the plan's reduce convention.
+inline void set_scaling(hot_plan &p)
+{
+    const hot_desc &d = p.d;
+    if (d.flags == HOT_REDUCE_NONE) {
+        p.g = 1.0;
+        p.k = 1.0 / d.dataset_size;
+    } else if (d.flags == HOT_REDUCE_MEAN) {
+        p.g = 1.0 / (double)d.s_local;
+        p.k = 1.0 / d.dataset_size;
+    } else {
+        p.g = 1.0 / (double)d.s_total;
+        p.k = (double)d.s_local / ((double)d.s_total * d.dataset_size);
+    }
+}
+
+// The default launch geometry of the four kernels for the plan's description.
+inline void default_launches(hot_plan &p)
+{
+    // Defaults from launch-shape sweeps on MI355X, each kernel timed with the other one running in
+    // between (timing a kernel back to back with itself lets part of its input stay in the 256 MiB
+    // memory-side cache and favours shapes that lose in a real step): four chunks per thread for
+    // the array kernels, single rows in flight forward, as many rows as there are (up to four)
+    // backward.  Non-temporal hints pay only when the streamed arrays are larger than that cache.
+    const hot_desc &d = p.d;
+    const bool streams_exceed_cache = (double)d.s_local * (double)d.ld * 4.0 >= 256.0 * 1048576.0;
+    hot_launch &f = p.cfg[HOT_KERNEL_FORWARD], &b = p.cfg[HOT_KERNEL_BACKWARD];
+    f.grid_blocks = b.grid_blocks = kMaxGrid;
+    f.chunks = b.chunks = 4;
+    f.unroll = 1;
+    b.unroll = pick_unroll(4, d.s_local);
+    f.nontemporal = b.nontemporal = streams_exceed_cache ? 1 : 0;
+    // With fewer than four samples the four-chunk backward kernels are fat (over 200 registers per lane,
+    // two workgroups per compute unit) and short: below 16 M weights their last, partly filled round of
+    // workgroups costs 5-10 %, which one chunk per thread avoids.
+    const bool few_tiles = d.n_weights < (16L << 20);
+    if (d.s_local < 4 && few_tiles) b.chunks = 1;
+    // The drawing variants have no eps loads to keep in flight.  Forward: as above up to seven samples;
+    // from eight on one chunk per thread (38 registers, eight waves per SIMD) hides the generator's
+    // latencies better than four independent chains in five waves (10-20 % at 8 M to 25 M weights).
+    // Backward: two chunks and single rows from four samples on.
+    hot_launch &fr = p.cfg[HOT_KERNEL_FORWARD_RNG], &br = p.cfg[HOT_KERNEL_BACKWARD_RNG];
+    fr = f;
+    if (d.s_local >= 8) fr.chunks = 1;
+    br = b;
+    br.chunks = d.s_local >= 4 ? 2 : (few_tiles ? 1 : 4);
+    br.unroll = pick_unroll(d.s_local >= 4 ? 1 : 2, d.s_local);
+}
+
 // Number of workgroups: one per column tile, capped by the configured bound.
 inline unsigned grid_for(long n, const hot_launch &c)
 {

@@ -1,10 +1,10 @@
 // libhot: the two steps next to the Gaussian sample layer in the paper's algorithms
 // (arxiv 2604.04736), both streaming kernels bound by HBM:
-//   hot_adam_step              "Update mu and sigma using optimizer (e.g., Adam)", last line of the
-//                              inner loop of Algorithm 1 / 2: one pass over eight input and six
+//   hot_adam_step              the optimizer-update line that closes the inner loop of
+//                              Algorithm 1 / 2 (Adam, the paper's example): one pass over eight input and six
 //                              output arrays (56 bytes per weight), Adam as published by Kingma & Ba;
 //   hot_forward_dropout_rng,   Monte Carlo dropout in weight space (section "Monte Carlo Dropout":
-//   hot_backward_dropout_rng   every weight is multiplied by a Bernoulli variable), the mask being a
+//   hot_backward_dropout_rng   each weight carries a random 0/1 keep factor), the mask being a
 //                              threshold on the same counter-based generator words the Gaussian
 //                              draw uses, so it is never stored and the backward pass regenerates it.
 #include <hip/hip_runtime.h>
@@ -80,13 +80,15 @@ hot_adam_kernel(long n, AdamConst c, float *__restrict__ mu, float *__restrict__
     }
 }
 
-// b[s, 4q .. 4q+3] = (generator word < threshold), as multipliers 1/keep or 0
-__device__ __forceinline__ f4 mask_quad(long quad, int s, const Rng &rng, unsigned threshold, float inv_keep)
+// b[s, 4q .. 4q+3] = (generator word < floor(keep * 2^32)), as multipliers 1/keep or 0.  The threshold lies in
+// [0, 2^32] and arrives as last_kept = threshold - 1 for a 32-bit compare (keep = 1 keeps every word); a
+// threshold of 0 (keep below 2^-32) arrives as last_kept = 0 with inv_keep = 0, so nothing is kept.
+__device__ __forceinline__ f4 mask_quad(long quad, int s, const Rng &rng, unsigned last_kept, float inv_keep)
 {
     const u4 x = eps_words(quad, s, rng);
     f4 b;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) b[j] = x[j] < threshold ? inv_keep : 0.0f;
+    for (int j = 0; j < 4; ++j) b[j] = x[j] <= last_kept ? inv_keep : 0.0f;
     return b;
 }
 
@@ -103,7 +105,7 @@ __device__ __forceinline__ float pick(f4 v, int j) { return j == 0 ? v[0] : (j =
 template <bool ALIGNED, bool NT>
 __global__ void __launch_bounds__(kBlock)
 hot_dropout_forward_kernel(long n, long ld, int s_loc, const float *__restrict__ mu, float *__restrict__ w,
-                           Rng rng, unsigned threshold, float inv_keep, long period, long unit_quad0)
+                           Rng rng, unsigned last_kept, float inv_keep, long period, long unit_quad0)
 {
     const long n_chunks = (n + 3) / 4;
     for (long chunk = (long)blockIdx.x * kBlock + threadIdx.x; chunk < n_chunks; chunk += (long)gridDim.x * kBlock) {
@@ -112,12 +114,12 @@ hot_dropout_forward_kernel(long n, long ld, int s_loc, const float *__restrict__
         if (col + 4 <= n) {
             const f4 m = load4<ALIGNED, NT>(mu + col);
             for (int s = 0; s < s_loc; ++s) {
-                const f4 b = mask_quad(mq, s, rng, threshold, inv_keep);
+                const f4 b = mask_quad(mq, s, rng, last_kept, inv_keep);
                 store4<ALIGNED, NT>(w + (size_t)s * (size_t)ld + col, m * b);
             }
         } else {
             for (int s = 0; s < s_loc; ++s) {
-                const f4 b = mask_quad(mq, s, rng, threshold, inv_keep);
+                const f4 b = mask_quad(mq, s, rng, last_kept, inv_keep);
                 for (long i = col; i < n; ++i) w[(size_t)s * (size_t)ld + (size_t)i] = mu[i] * pick(b, (int)(i - col));
             }
         }
@@ -127,7 +129,7 @@ hot_dropout_forward_kernel(long n, long ld, int s_loc, const float *__restrict__
 template <bool ALIGNED, bool NT>
 __global__ void __launch_bounds__(kBlock)
 hot_dropout_backward_kernel(long n, long ld, int s_loc, double g, const float *__restrict__ gw,
-                            float *__restrict__ gmu, Rng rng, unsigned threshold, float inv_keep, long period,
+                            float *__restrict__ gmu, Rng rng, unsigned last_kept, float inv_keep, long period,
                             long unit_quad0)
 {
     const long n_chunks = (n + 3) / 4;
@@ -140,8 +142,8 @@ hot_dropout_backward_kernel(long n, long ld, int s_loc, double g, const float *_
             for (; s + 2 <= s_loc; s += 2) {
                 const f4 v0 = load4<ALIGNED, NT>(gw + (size_t)s * (size_t)ld + col);
                 const f4 v1 = load4<ALIGNED, NT>(gw + (size_t)(s + 1) * (size_t)ld + col);
-                const f4 b0 = mask_quad(mq, s, rng, threshold, inv_keep);
-                const f4 b1 = mask_quad(mq, s + 1, rng, threshold, inv_keep);
+                const f4 b0 = mask_quad(mq, s, rng, last_kept, inv_keep);
+                const f4 b1 = mask_quad(mq, s + 1, rng, last_kept, inv_keep);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     acc[j] = fma((double)v0[j], (double)b0[j], acc[j]);
@@ -150,7 +152,7 @@ hot_dropout_backward_kernel(long n, long ld, int s_loc, double g, const float *_
             }
             for (; s < s_loc; ++s) {
                 const f4 v0 = load4<ALIGNED, NT>(gw + (size_t)s * (size_t)ld + col);
-                const f4 b0 = mask_quad(mq, s, rng, threshold, inv_keep);
+                const f4 b0 = mask_quad(mq, s, rng, last_kept, inv_keep);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) acc[j] = fma((double)v0[j], (double)b0[j], acc[j]);
             }
@@ -161,7 +163,7 @@ hot_dropout_backward_kernel(long n, long ld, int s_loc, double g, const float *_
         } else {
             double acc[3] = {0.0, 0.0, 0.0};
             for (int s = 0; s < s_loc; ++s) {
-                const f4 b = mask_quad(mq, s, rng, threshold, inv_keep);
+                const f4 b = mask_quad(mq, s, rng, last_kept, inv_keep);
 #pragma unroll
                 for (int j = 0; j < 3; ++j)
                     if (col + j < n) acc[j] = fma((double)gw[(size_t)s * (size_t)ld + (size_t)(col + j)], (double)pick(b, j), acc[j]);
@@ -181,11 +183,18 @@ unsigned blocks_for(long chunks)
     return (unsigned)b;
 }
 
-unsigned dropout_threshold(double keep)
+// The kernels' form of the keep threshold floor(keep * 2^32) in [0, 2^32] (see mask_quad).
+struct DropMask {
+    unsigned last_kept;
+    float inv_keep;
+};
+
+DropMask drop_mask(double keep)
 {
     double t = std::floor(keep * 4294967296.0);
-    if (t > 4294967295.0) t = 4294967295.0;
-    return (unsigned)t;
+    if (t > 4294967296.0) t = 4294967296.0;
+    if (t < 1.0) return DropMask{0u, 0.0f};
+    return DropMask{(unsigned)(t - 1.0), (float)(1.0 / keep)};
 }
 
 }  // namespace
@@ -225,8 +234,9 @@ static int dropout_forward_impl(const hot_desc *d, const hot_rng *rng, double ke
     const bool nt = (double)d->s_local * (double)d->ld * 4.0 >= 256.0 * 1048576.0;
     const dim3 grid(blocks_for((d->n_weights + 3) / 4)), block(kBlock);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const unsigned thr = dropout_threshold(keep);
-    const float inv = (float)(1.0 / keep);
+    const DropMask dm = drop_mask(keep);
+    const unsigned thr = dm.last_kept;
+    const float inv = dm.inv_keep;
     if (al && nt) hot_dropout_forward_kernel<true, true><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv, period, unit_offset >> 2);
     else if (al) hot_dropout_forward_kernel<true, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv, period, unit_offset >> 2);
     else hot_dropout_forward_kernel<false, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, mu, w, r, thr, inv, period, unit_offset >> 2);
@@ -250,8 +260,9 @@ static int dropout_backward_impl(const hot_desc *d, const hot_rng *rng, double k
                      : (d->flags == HOT_REDUCE_MEAN ? 1.0 / (double)d->s_local : 1.0 / (double)d->s_total);
     const dim3 grid(blocks_for((d->n_weights + 3) / 4)), block(kBlock);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const unsigned thr = dropout_threshold(keep);
-    const float inv = (float)(1.0 / keep);
+    const DropMask dm = drop_mask(keep);
+    const unsigned thr = dm.last_kept;
+    const float inv = dm.inv_keep;
     if (al && nt) hot_dropout_backward_kernel<true, true><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv, period, unit_offset >> 2);
     else if (al) hot_dropout_backward_kernel<true, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv, period, unit_offset >> 2);
     else hot_dropout_backward_kernel<false, false><<<grid, block, 0, s>>>(d->n_weights, d->ld, d->s_local, g, grad_w, grad_mu, r, thr, inv, period, unit_offset >> 2);

@@ -33,6 +33,50 @@ def test_header_symbols_are_exported(hot):
         assert getattr(L, name) is not None
 
 
+def _declared_return_types():
+    """{name: C return type} for every function include/hot.h declares."""
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    out = {}
+    for m in re.finditer(r"^\s*((?:const\s+)?[A-Za-z_0-9]+(?:\s*\*)?)\s*\b(hot_[a-z_]+)\s*\(", text, re.M):
+        out[m.group(2)] = re.sub(r"\s+", " ", m.group(1)).replace(" *", "*").strip()
+    return out
+
+
+def test_binding_return_types_match_the_header(hot):
+    """The ctypes restype of every entry point is the header's return type: a 64-bit byte count read as a
+    32-bit int would be cut off (and turn negative) from 2 GiB on."""
+    want = {"int": ctypes.c_int, "int64_t": ctypes.c_int64, "const char*": ctypes.c_char_p}
+    declared = _declared_return_types()
+    assert set(declared) == set(hot.EXPORTS)
+    L = hot.lib()
+    for name, ctype in declared.items():
+        assert getattr(L, name).restype is want[ctype], (name, ctype, getattr(L, name).restype)
+    assert {n for n, t in declared.items() if t != "int"} == set(hot.RESTYPES)
+
+
+def test_workspace_query_over_many_shapes_is_consistent(hot):
+    """Host arithmetic only: the answer is never negative for a valid layer, a multiple of 16 bytes, and
+    covers at least two parts of what is split when it is not zero.  (With the present launch rules the
+    largest answer is below 2 GiB; the return type is 64-bit all the same and is checked above.)"""
+    import random
+    r = random.Random(7)
+    biggest = 0
+    for _ in range(3000):
+        rows = r.choice([1, 64, 255, 256, 1000, 7260, 16640, 65536, 1 << 20])
+        k = 4 * r.randint(1, 4096)
+        o = r.randint(1, 16384)
+        s = r.choice([1, 2, 4, 16])
+        b = hot.hot_linear_backward_workspace_bytes(rows, k, o, s)
+        assert b >= 0 and b % 16 == 0, (rows, k, o, s, b)
+        if b:
+            per_w = 2 * (o * k + (o + 3) // 4 * 4) * 4
+            per_x = s * rows * k * 4
+            assert b >= 2 * min(per_w, per_x), (rows, k, o, s, b)
+        biggest = max(biggest, b)
+    assert biggest > 0
+
+
 def test_host_only_entry_points(hot):
     assert hot.hot_version() == 209
     assert hot.hot_strerror(0) == "success"

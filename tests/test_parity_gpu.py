@@ -93,6 +93,7 @@ def test_edge_sizes_packed_and_padded(oracle, hot, n):
             wl = _WL(n, ld, s, s_total, 321.0)
             P.check_all(oracle, hot, x, wl)
             P.check_all(oracle, hot, x, wl, launch=dict(chunks=1, unroll=1, grid_blocks=1), flags=hot.HOT_REDUCE_MEAN)
+            P.check_all(oracle, hot, x, wl, launch=dict(chunks=2, unroll=2), flags=hot.HOT_REDUCE_NONE)
 
 
 def test_mean_convention_and_sharding_over_plans(oracle, hot):
@@ -353,12 +354,17 @@ def test_full_size_sampled_blocks_and_whole_kl(oracle, hot, name):
     assert torch.isfinite(w).all() and torch.isfinite(gmu).all() and torch.isfinite(gsig).all()
 
 
-@pytest.mark.parametrize("name", ["C3", "C5"])
+@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
 def test_full_size_every_element(oracle, hot, name):
+    """Every element of w, grad_mu and grad_sigma and the whole KL term at the benchmark's sizes and default
+    launch shape (C4, the workload the metric is quoted on, block by block to bound host memory)."""
     wl = W.CONFIGS[name]
     _say("case every element", name)
     x = W.make_inputs(wl, DEV)
-    _say(P.check_all(oracle, hot, x, wl))
+    if wl.items > 200_000_000:
+        _say(P.check_all_chunked(oracle, hot, x, wl, say=_say))
+    else:
+        _say(P.check_all(oracle, hot, x, wl))
 
 
 def test_indices_beyond_32_bits(oracle, hot):
@@ -388,14 +394,17 @@ def test_indices_beyond_32_bits(oracle, hot):
              "eps": np.ascontiguousarray(eps[:, a:b].cpu().numpy()), "G": np.ascontiguousarray(G[:, a:b].cpu().numpy())}
         P.check_w(oracle, h, w[:, a:b].cpu().numpy(), width)
         P.check_grads(oracle, h, gmu[a:b].cpu().numpy(), gsig[a:b].cpu().numpy(), width, 16, 45000.0)
-    # the KL term of 1.2e9 weights against a chunked fp64 evaluation of the same formula on the GPU's values
-    acc = 0.0
-    for c0 in range(0, n, 1 << 26):
-        m64, s64 = mu[c0:c0 + (1 << 26)].double(), sigma[c0:c0 + (1 << 26)].double()
-        acc += float((s64 * s64 + m64 * m64 - 1.0 - 2.0 * torch.log(s64)).sum())
-    _say("KL", kl.item(), "reference", 0.5 * acc, "relative difference", abs(kl.item() - 0.5 * acc) / abs(0.5 * acc))
-    assert abs(kl.item() - 0.5 * acc) <= 1e-7 * abs(0.5 * acc)
     del eps, G, w
+    # the KL term of all 1.2e9 weights against the oracle, which takes them in blocks of 2^26 (the term is
+    # additive over any partition of the weights; the oracle's pins include that)
+    want = scale = 0.0
+    for c0 in range(0, n, 1 << 26):
+        hb = {"mu": mu[c0:c0 + (1 << 26)].cpu().numpy(), "sigma": sigma[c0:c0 + (1 << 26)].cpu().numpy()}
+        want += oracle.kl(hb["mu"], hb["sigma"])
+        scale += P.kl_scale(hb)
+    _say("KL", kl.item(), "oracle", want, "difference over the sum of addend magnitudes", abs(kl.item() - want) / scale)
+    assert abs(kl.item() - want) <= P.RTOL * scale
+    assert abs(kl.item() - want) <= 1e-7 * abs(want)        # (far inside the tolerance: every addend is positive here)
 
 
 def test_hip_graph_replays_equal_eager(hot):
@@ -457,7 +466,7 @@ def test_random_shapes_offsets_and_launch_shapes(oracle, hot):
         offset = int(rs.choice([0, 0, 1, 2, 3]))
         launch = dict(chunks=int(rs.choice([1, 2, 4])), unroll=int(rs.choice([1, 2, 4])),
                       nontemporal=int(rs.integers(0, 2)), grid_blocks=int(rs.choice([0, 1, 3, 64])))
-        flags = int(rs.integers(0, 2))
+        flags = int(rs.integers(0, 3))        # sum, mean and unscaled reduce conventions
         _say("case random", case, n, ld, s, s_total, offset, launch, flags)
         g = torch.Generator().manual_seed(case)
         def place(t):

@@ -93,7 +93,7 @@ def test_adam_grad_scale_zero_gradient_and_sigma_floor(oracle):
 
 def test_dropout_threshold_and_hand_case(oracle):
     assert oracle.dropout_threshold(0.5) == 1 << 31
-    assert oracle.dropout_threshold(1.0) == (1 << 32) - 1
+    assert oracle.dropout_threshold(1.0) == 1 << 32
     assert oracle.dropout_threshold(0.0) == 0
     assert oracle.dropout_threshold(0.75) == 3 << 30
     mu = np.array([2.0, -4.0, 8.0], np.float32)
@@ -105,6 +105,24 @@ def test_dropout_threshold_and_hand_case(oracle):
     np.testing.assert_array_equal(gm, [(1.0 * 2) / 4, (2.0 * 2 + 20.0 * 2) / 4, (30.0 * 2) / 4])
     gm = oracle.dropout_backward(G, words, 0.5, s_total=4, reduce_mean=True)
     np.testing.assert_array_equal(gm, [(1.0 * 2) / 2, (2.0 * 2 + 20.0 * 2) / 2, (30.0 * 2) / 2])
+
+
+def test_dropout_with_keep_one_keeps_every_weight(oracle):
+    """A Bernoulli variable with probability 1 is identically 1 (section "Monte Carlo Dropout"): also the
+    largest generator word is kept, forward and backward, and the layer is then the identity in mu."""
+    mu = np.array([2.0, -4.0, 8.0, 0.5], np.float32)
+    words = np.array([[0, (1 << 32) - 1, 1 << 31, (1 << 32) - 2], [(1 << 32) - 1] * 4], np.uint32)
+    np.testing.assert_array_equal(oracle.dropout_forward(mu, words, 1.0), np.broadcast_to(mu.astype(np.float64), (2, 4)))
+    G = np.array([[1.0, 2.0, 3.0, 4.0], [10.0, 20.0, 30.0, 40.0]], np.float32)
+    np.testing.assert_array_equal(oracle.dropout_backward(G, words, 1.0, s_total=2), [5.5, 11.0, 16.5, 22.0])
+    # just below one, the largest word is dropped again: the threshold is floor(keep * 2^32)
+    keep = 1.0 - 2.0 ** -32
+    assert oracle.dropout_threshold(keep) == (1 << 32) - 1
+    w = oracle.dropout_forward(mu, words, keep)
+    assert w[0, 1] == 0.0 and np.all(w[1] == 0.0) and w[0, 3] == float(mu[3]) / keep
+    # a keep probability below 2^-32 has threshold 0: nothing is kept
+    assert oracle.dropout_threshold(2.0 ** -33) == 0
+    assert np.all(oracle.dropout_forward(mu, words, 2.0 ** -33) == 0.0)
 
 
 @pytest.mark.parametrize("keep", [0.5, 0.9, 0.2])

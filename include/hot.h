@@ -35,13 +35,14 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 209 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 210 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,
     HOT_EINVAL = -1, /* bad argument (null pointer, size out of range, misaligned to 4 bytes) */
     HOT_ENOMEM = -2, /* host or device allocation failed */
-    HOT_EHIP = -3    /* a HIP call failed; hot_last_hip_error() gives its code */
+    HOT_EHIP = -3,   /* a HIP call failed; hot_last_hip_error() gives its code */
+    HOT_ERANGE = -4  /* the problem is larger than the fixed capacity of an entry point that allocates nothing */
 };
 
 /* hot_desc.flags */
@@ -119,6 +120,26 @@ int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float
  * the one hot_forward returns); reads 8 bytes per weight.  kl_out: DEVICE, one double, required.
  */
 int hot_kl(hot_plan *plan, const float *mu, const float *sigma, double *kl_out, void *stream);
+
+/*
+ * hot_forward for callers that cannot allocate device memory or create a plan: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, launch geometry and results
+ * as hot_forward on a plan made from `desc` (w bit for bit; kl_out is always summed by the one-workgroup finish
+ * kernel, so for at most 64 workgroups it may differ from hot_forward's in the last bits), but the
+ * per-workgroup KL partial sums live in a static device array of the library (512 KiB on every GPU the
+ * library runs on, held until the process ends) instead of a plan's own memory, and the call itself
+ * allocates nothing, on the host or on the device, and frees nothing.
+ * Capacity: desc->n_weights <= HOT_STATIC_MAX_WEIGHTS (one partial per 4096-weight tile); beyond it the
+ * call returns HOT_ERANGE and launches nothing.  desc as for hot_create (desc->device < 64); pointer, layout,
+ * stream and error rules as for hot_forward; a failed HIP call is reported by hot_last_hip_error(NULL).
+ * The first call on a device looks up the array's address there (hipGetSymbolAddress, with that device
+ * current): make that call outside any stream capture.  Nothing in the array needs to be zero before a call
+ * (every partial is written before it is read).  All calls on one GPU share the array: calls that overlap
+ * there (different streams or host threads) race on it; calls on one stream are ordered and safe.
+ */
+#define HOT_STATIC_MAX_WEIGHTS 268435456 /* 2^28 */
+int hot_forward_static(const hot_desc *desc, const float *mu, const float *sigma, const float *eps, float *w,
+                       double *kl_out, void *stream);
 
 /*
  * Algorithm 2, loss / gradient / averaging lines, local share of this GPU.  With

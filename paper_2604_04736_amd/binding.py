@@ -16,7 +16,8 @@ import torch  # imported before libhot.so so that both share one HIP runtime
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhot.so")
 
-HOT_OK, HOT_EINVAL, HOT_ENOMEM, HOT_EHIP = 0, -1, -2, -3
+HOT_OK, HOT_EINVAL, HOT_ENOMEM, HOT_EHIP, HOT_ERANGE = 0, -1, -2, -3, -4
+HOT_STATIC_MAX_WEIGHTS = 1 << 28
 HOT_REDUCE_SUM, HOT_REDUCE_MEAN, HOT_REDUCE_NONE = 0, 1, 2
 HOT_KERNEL_FORWARD, HOT_KERNEL_BACKWARD, HOT_KERNEL_FORWARD_RNG, HOT_KERNEL_BACKWARD_RNG = 0, 1, 2, 3
 
@@ -28,7 +29,7 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam",
            "hot_linear_backward_rng", "hot_kl", "hot_forward_dropout_units_rng",
            "hot_backward_dropout_units_rng", "hot_stats_whole", "hot_adam_forward", "hot_backward_adam_forward",
-           "hot_linear_backward_rng_ws", "hot_linear_backward_workspace_bytes")
+           "hot_linear_backward_rng_ws", "hot_linear_backward_workspace_bytes", "hot_forward_static")
 
 
 # Return types of the entry points that do not return an int status (as declared in include/hot.h).
@@ -87,6 +88,7 @@ def lib() -> ctypes.CDLL:
     L.hot_forward.argtypes = [vp, fp, fp, fp, fp, vp, vp]
     L.hot_backward.argtypes = [vp, fp, fp, fp, fp, fp, fp, vp]
     L.hot_kl.argtypes = [vp, fp, fp, vp, vp]
+    L.hot_forward_static.argtypes = [ctypes.POINTER(hot_desc), fp, fp, fp, fp, vp, vp]
     L.hot_destroy.argtypes = [vp]
     rp = ctypes.POINTER(hot_rng)
     L.hot_forward_rng.argtypes = [vp, rp, fp, fp, fp, vp, vp]
@@ -243,6 +245,23 @@ def hot_forward(plan: Plan, mu, sigma, eps, w, kl_out=None) -> None:
                              _mat(w, d.s_local, d.n_weights, d.ld, d.device, "w"),
                              klp, _stream(d.device))
     _check(code, "hot_forward", plan)
+
+
+def hot_forward_static(desc: hot_desc, mu, sigma, eps, w, kl_out=None) -> None:
+    """hot_forward without a plan and without any allocation (see include/hot.h); desc: a hot_desc."""
+    d = desc
+    klp = None
+    if kl_out is not None:
+        if not (kl_out.is_cuda and kl_out.device.index == d.device and kl_out.dtype == torch.float64 and kl_out.numel() == 1):
+            raise TypeError("kl_out: need one float64 element on desc.device")
+        klp = kl_out.data_ptr()
+    code = lib().hot_forward_static(ctypes.byref(d),
+                                    _vec(mu, d.n_weights, d.device, "mu"),
+                                    _vec(sigma, d.n_weights, d.device, "sigma"),
+                                    _mat(eps, d.s_local, d.n_weights, d.ld, d.device, "eps"),
+                                    _mat(w, d.s_local, d.n_weights, d.ld, d.device, "w"),
+                                    klp, _stream(d.device))
+    _check_planless(code, "hot_forward_static")
 
 
 def hot_backward(plan: Plan, mu, sigma, eps, grad_w, grad_mu, grad_sigma) -> None:

@@ -1,7 +1,15 @@
 // libhot, forward half of the sample layer (arxiv 2604.04736, Algorithm 2: reparameterisation and
 // prior-matching lines): hot_forward, hot_forward_rng, hot_kl, hot_adam_forward.  The design notes
 // common to both halves are at the top of hot.hip.  gfx950 only.
+#include <atomic>
+
 #include "sample_layer.h"
+
+// Scratch of hot_forward_static (the entry point that allocates nothing): the per-workgroup KL partial sums
+// that a plan otherwise keeps in memory of its own.  One copy per GPU, loaded with the library's code object and
+// held until the process ends (512 KiB).  In host code the name is only a handle for hipGetSymbolAddress; the
+// device address it returns (one per device) is what kernels and runtime calls are given.
+static __device__ __align__(256) double scratch[65536];
 
 namespace {
 
@@ -385,9 +393,11 @@ void fwd_dispatch(int ch, int u, bool al, bool nt, const FwdArgs &a)
 
 // kl_only: the prior-matching term alone.  The forward kernel runs over zero samples, so it touches
 // neither eps nor w (both may be NULL) and only its KL part is left.
+// finish_kernel_always: never let the forward kernel add the partials itself (that path needs an arrival
+// counter that is zero before the launch; the finish kernel needs no state at all).
 int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
                  const float *eps, float *w, double *kl_out, void *stream, bool kl_only = false,
-                 const AdamPrologue *adam = nullptr, bool adam_aligned = true)
+                 const AdamPrologue *adam = nullptr, bool adam_aligned = true, bool finish_kernel_always = false)
 {
     const bool gen = rng != nullptr || kl_only;      // kl_only: no eps array to look at
     if (!mu || !sigma || (!kl_only && !w) || (!gen && !eps) || (kl_only && !kl_out)) return HOT_EINVAL;
@@ -422,7 +432,7 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
         const long windows = (d.n_weights + 15 + 4095) / 4096;
         a.grid = dim3((unsigned)(windows < c.grid_blocks ? windows : c.grid_blocks));
     }
-    const bool self_finish = a.want_kl && a.grid.x <= (unsigned)kTicketGrid;
+    const bool self_finish = a.want_kl && a.grid.x <= (unsigned)kTicketGrid && !finish_kernel_always;
     a.ticket = self_finish ? reinterpret_cast<unsigned *>(plan->partials + kMaxGrid) : nullptr;
 
     DeviceGuard guard(d.device);
@@ -441,9 +451,48 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     return e == hipSuccess ? HOT_OK : fail_hip(plan, e);
 }
 
+static_assert(sizeof(scratch) == sizeof(double) * kMaxGrid, "one KL partial per workgroup of the largest grid");
+
+// Device address of `scratch` on each device, looked up on the first call there.
+constexpr int kMaxDevices = 64;
+std::atomic<double *> g_scratch_ptr[kMaxDevices];
+
 }  // namespace
 
 extern "C" {
+
+int hot_forward_static(const hot_desc *desc, const float *mu, const float *sigma, const float *eps, float *w,
+                       double *kl_out, void *stream)
+{
+    if (!desc || !valid_desc(*desc)) return HOT_EINVAL;
+    if (desc->device < 0 || desc->device >= kMaxDevices) return HOT_EINVAL;
+    if (desc->n_weights > HOT_STATIC_MAX_WEIGHTS) return HOT_ERANGE;
+    double *ptr = g_scratch_ptr[desc->device].load(std::memory_order_acquire);
+    if (!ptr) {
+        // first call on this device: with it current, ask the runtime where its copy of the array lives
+        // (threads that race here look up the same address)
+        int n_dev = 0;
+        if (hipError_t e = hipGetDeviceCount(&n_dev); e != hipSuccess) return hot_detail::note_hip(e);
+        if (desc->device >= n_dev) return HOT_EINVAL;
+        DeviceGuard guard(desc->device);
+        if (guard.err != hipSuccess) return hot_detail::note_hip(guard.err);
+        void *at = nullptr;
+        if (hipError_t e = hipGetSymbolAddress(&at, HIP_SYMBOL(scratch)); e != hipSuccess) return hot_detail::note_hip(e);
+        if (!at) return hot_detail::note_hip(hipErrorInvalidSymbol);
+        ptr = static_cast<double *>(at);
+        g_scratch_ptr[desc->device].store(ptr, std::memory_order_release);
+    }
+    // a plan on the stack: the description, the default launch geometry, and the static array for its partials
+    hot_plan tmp;
+    tmp.d = *desc;
+    set_scaling(tmp);
+    default_launches(tmp);
+    tmp.partials = ptr;
+    tmp.last_hip = 0;
+    const int rc = forward_impl(&tmp, HOT_KERNEL_FORWARD, nullptr, mu, sigma, eps, w, kl_out, stream, false, nullptr, true, true);
+    if (rc == HOT_EHIP) (void)hot_detail::note_hip(static_cast<hipError_t>(tmp.last_hip));
+    return rc;
+}
 
 int hot_forward(hot_plan *plan, const float *mu, const float *sigma, const float *eps, float *w,
                 double *kl_out, void *stream)

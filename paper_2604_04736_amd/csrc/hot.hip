@@ -203,6 +203,7 @@ const char *hot_strerror(int code)
     case HOT_EINVAL: return "invalid argument";
     case HOT_ENOMEM: return "out of memory";
     case HOT_EHIP: return "HIP runtime error (see hot_last_hip_error)";
+    case HOT_ERANGE: return "problem larger than the fixed capacity of this no-allocation entry point";
     default: return "unknown error code";
     }
 }

@@ -78,7 +78,7 @@ def test_workspace_query_over_many_shapes_is_consistent(hot):
 
 
 def test_host_only_entry_points(hot):
-    assert hot.hot_version() == 209
+    assert hot.hot_version() == 210
     assert hot.hot_strerror(0) == "success"
     assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
     assert hot.hot_strerror(-99) == "unknown error code"
@@ -107,6 +107,11 @@ def test_null_arguments_are_rejected_without_a_gpu(hot):
     assert L.hot_forward(None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_backward(None, None, None, None, None, None, None, None) == hot.HOT_EINVAL
     assert L.hot_kl(None, None, None, None, None) == hot.HOT_EINVAL
+    assert L.hot_forward_static(None, None, None, None, None, None, None) == hot.HOT_EINVAL
+    # beyond the capacity of the static scratch: refused before anything touches a GPU
+    too_big = hot.hot_desc(hot.HOT_STATIC_MAX_WEIGHTS + 1, hot.HOT_STATIC_MAX_WEIGHTS + 1, 1, 1, 1.0, 0, 0)
+    assert L.hot_forward_static(ctypes.byref(too_big), None, None, None, None, None, None) == hot.HOT_ERANGE
+    assert "capacity" in hot.hot_strerror(hot.HOT_ERANGE)
     assert L.hot_set_launch(None, 0, None) == hot.HOT_EINVAL
     assert L.hot_get_launch(None, 0, None) == hot.HOT_EINVAL
     assert L.hot_last_hip_error(None) == 0

@@ -393,6 +393,15 @@ void fwd_dispatch(int ch, int u, bool al, bool nt, const FwdArgs &a)
 
 // kl_only: the prior-matching term alone.  The forward kernel runs over zero samples, so it touches
 // neither eps nor w (both may be NULL) and only its KL part is left.
+// The pointer rules of the forward calls: present where needed, 4-byte aligned, kl_out 8-byte aligned.
+bool forward_pointers_ok(bool gen, bool kl_only, const float *mu, const float *sigma, const float *eps, const float *w,
+                         const double *kl_out)
+{
+    if (!mu || !sigma || (!kl_only && !w) || (!gen && !eps) || (kl_only && !kl_out)) return false;
+    if (!aligned4(mu) || !aligned4(sigma) || (!kl_only && !aligned4(w)) || (!gen && !aligned4(eps))) return false;
+    return !(kl_out && (reinterpret_cast<uintptr_t>(kl_out) & 7u));
+}
+
 // finish_kernel_always: never let the forward kernel add the partials itself (that path needs an arrival
 // counter that is zero before the launch; the finish kernel needs no state at all).
 int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, const float *sigma,
@@ -400,9 +409,7 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
                  const AdamPrologue *adam = nullptr, bool adam_aligned = true, bool finish_kernel_always = false)
 {
     const bool gen = rng != nullptr || kl_only;      // kl_only: no eps array to look at
-    if (!mu || !sigma || (!kl_only && !w) || (!gen && !eps) || (kl_only && !kl_out)) return HOT_EINVAL;
-    if (!aligned4(mu) || !aligned4(sigma) || (!kl_only && !aligned4(w)) || (!gen && !aligned4(eps))) return HOT_EINVAL;
-    if (kl_out && (reinterpret_cast<uintptr_t>(kl_out) & 7u)) return HOT_EINVAL;
+    if (!forward_pointers_ok(gen, kl_only, mu, sigma, eps, w, kl_out)) return HOT_EINVAL;
     const hot_desc &d = plan->d;
     const hot_launch &c = plan->cfg[kernel];
     const bool al = aligned16(mu) && aligned16(sigma) && (kl_only || aligned16(w)) && (gen || aligned16(eps)) &&
@@ -467,6 +474,7 @@ int hot_forward_static(const hot_desc *desc, const float *mu, const float *sigma
     if (!desc || !valid_desc(*desc)) return HOT_EINVAL;
     if (desc->device < 0 || desc->device >= kMaxDevices) return HOT_EINVAL;
     if (desc->n_weights > HOT_STATIC_MAX_WEIGHTS) return HOT_ERANGE;
+    if (!forward_pointers_ok(false, false, mu, sigma, eps, w, kl_out)) return HOT_EINVAL;      // before any HIP call
     double *ptr = g_scratch_ptr[desc->device].load(std::memory_order_acquire);
     if (!ptr) {
         // first call on this device: with it current, ask the runtime where its copy of the array lives

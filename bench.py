@@ -84,6 +84,63 @@ def time_steps(hot, torch, wl, x, steps: int, warmup: int, in_kernel_eps: bool =
             "out": {"w": w, "kl": kl, "gmu": gmu, "gsig": gsig}}
 
 
+def time_kernels_between_other_work(hot, torch, wl, x, iters: int = 20, in_kernel_eps: bool = False, plain: bool = False):
+    """ms of each kernel when an unrelated element-wise kernel (512 MiB read and written with plain accesses: a
+    stand-in for the network that runs between the two calls in training) precedes it, so that the memory-side
+    cache holds somebody else's partly dirty lines instead of this library's arrays.  plain: the same with the
+    library's non-temporal hints switched off."""
+    dev = x["mu"].device
+    other = torch.zeros(128 << 20, dtype=torch.float32, device=dev)
+    w = torch.empty_like(x["G"])
+    kl = torch.zeros(1, dtype=torch.float64, device=dev)
+    gmu, gsig = torch.empty_like(x["mu"]), torch.empty_like(x["mu"])
+    plan = hot.hot_create(wl.n_weights, wl.ld, wl.s_local, wl.s_total, wl.dataset_size, dev.index or 0)
+    if plain:
+        for kern in (hot.HOT_KERNEL_FORWARD, hot.HOT_KERNEL_BACKWARD, hot.HOT_KERNEL_FORWARD_RNG, hot.HOT_KERNEL_BACKWARD_RNG):
+            hot.hot_set_launch(plan, kern, nontemporal=0)
+    rng = hot.hot_rng(seed=RNG_SEED, step=RNG_STEP, first_sample=0)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(iters)]
+    for i in range(3 + iters):
+        e = ev[i - 3] if i >= 3 else None
+        other.add_(1.0)
+        if e:
+            e[0].record()
+        if in_kernel_eps:
+            hot.hot_forward_rng(plan, rng, x["mu"], x["sigma"], w, kl)
+        else:
+            hot.hot_forward(plan, x["mu"], x["sigma"], x["eps"], w, kl)
+        if e:
+            e[1].record()
+        other.add_(1.0)
+        if e:
+            e[2].record()
+        if in_kernel_eps:
+            hot.hot_backward_rng(plan, rng, x["mu"], x["sigma"], x["G"], gmu, gsig)
+        else:
+            hot.hot_backward(plan, x["mu"], x["sigma"], x["eps"], x["G"], gmu, gsig)
+        if e:
+            e[3].record()
+    torch.cuda.synchronize()
+    hot.hot_destroy(plan)
+    f = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    b = sorted(e[2].elapsed_time(e[3]) for e in ev)
+    del other, w
+    torch.cuda.empty_cache()
+    return {"fwd_ms": f[iters // 2], "bwd_ms": b[iters // 2]}
+
+
+def between_other_work(hot, torch, wl, x, in_kernel_eps: bool):
+    hinted = time_kernels_between_other_work(hot, torch, wl, x, 20, in_kernel_eps, False)
+    plain = time_kernels_between_other_work(hot, torch, wl, x, 20, in_kernel_eps, True)
+    fb, bb = algorithmic_bytes(wl.n_weights, wl.s_local, in_kernel_eps)
+    return {"fwd_ms": hinted["fwd_ms"], "bwd_ms": hinted["bwd_ms"],
+            "fwd_GBps": fb / hinted["fwd_ms"] / 1e6, "bwd_GBps": bb / hinted["bwd_ms"] / 1e6,
+            "kernels_frac_of_hbm_roofline": (fb + bb) / ((hinted["fwd_ms"] + hinted["bwd_ms"]) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "with_plain_accesses": plain,
+            "what": "each kernel timed right after an unrelated 512 MiB element-wise kernel (the network's stand-in); "
+                    "with_plain_accesses: the same with the non-temporal hints switched off"}
+
+
 def time_graph_steps(hot, torch, wl, x, steps: int, in_kernel_eps: bool = False) -> float:
     """ms per step when the step (forward, KL finish, backward) is captured once in a HIP graph and
     replayed: what a launch-latency-bound small workload costs without the host in the loop."""
@@ -349,6 +406,29 @@ def mix_ceiling(hot, torch, dev, stream_bytes: int, reads: int, writes: int, ite
     ms = e0.elapsed_time(e1) / iters
     return {"GBps": (reads + writes) * stream_bytes / ms / 1e6, "ms": ms, "read_streams": reads,
             "write_streams": writes, "stream_bytes": stream_bytes}
+
+
+def stream_mix(wl, in_kernel_eps: bool):
+    """(read streams, write streams) of N floats each that the two kernels move: forward reads (the eps rows,) mu,
+    sigma and writes the w rows; backward reads the G rows (and the eps rows), mu, sigma and writes grad_mu, grad_sigma."""
+    rows = wl.s_local
+    return {"forward": ((0 if in_kernel_eps else rows) + 2, rows), "backward": ((1 if in_kernel_eps else 2) * rows + 2, 2)}
+
+
+def mix_ceilings(hot, torch, dev, wl, in_kernel_eps: bool, fwd_ms: float, bwd_ms: float):
+    """Both kernels of a workload beside hot_probe_streams with their stream counts (no arithmetic)."""
+    out = {}
+    fb, bb = algorithmic_bytes(wl.n_weights, wl.s_local, in_kernel_eps)
+    stream_bytes = 4 * wl.n_weights // 16 * 16
+    for which, (r, w), nbytes, ms in (("forward",) + (stream_mix(wl, in_kernel_eps)["forward"],) + (fb, fwd_ms),
+                                      ("backward",) + (stream_mix(wl, in_kernel_eps)["backward"],) + (bb, bwd_ms)):
+        if r > 64 or w > 64:
+            continue
+        m = mix_ceiling(hot, torch, dev, stream_bytes, r, w)
+        out[which] = {"probe_GBps": m["GBps"], "probe_ms": m["ms"], "read_streams": r, "write_streams": w,
+                      "kernel_GBps": nbytes / ms / 1e6, "kernel_vs_probe": nbytes / ms / 1e6 / m["GBps"]}
+        torch.cuda.empty_cache()
+    return out
 
 
 def predictive_stats_lines(hot, torch, dev, iters: int = 20):
@@ -695,13 +775,16 @@ def main() -> int:
     # rows plus mu, sigma and writes grad_mu, grad_sigma; forward reads (eps rows,) mu, sigma and writes w rows
     rows = wl.s_local
     mix = {"backward": ((1 if gen else 2) * rows + 2, 2), "forward": ((0 if gen else rows) + 2, rows)}[dominant]
-    if mix[0] <= 6 and mix[1] <= 2 and wl.ld == wl.n_weights:
-        m = mix_ceiling(hot, torch, dev, 4 * wl.n_weights, mix[0], mix[1])
+    if mix[0] <= 64 and mix[1] <= 64:
+        stream_bytes = 4 * wl.n_weights // 16 * 16
+        m = mix_ceiling(hot, torch, dev, stream_bytes, mix[0], mix[1])
         result["mix_ceiling"] = {"GBps": m["GBps"], "frac_of_hbm_peak": m["GBps"] / HBM_PEAK_GBS,
                                  "kernel_vs_mix_ceiling": achieved / m["GBps"],
                                  "what": f"hot_probe_streams_kernel: {mix[0]} read + {mix[1]} write streams of "
-                                         f"{4 * wl.n_weights} bytes, the {dominant} kernel's traffic without its arithmetic"}
+                                         f"{stream_bytes} bytes, the {dominant} kernel's traffic without its arithmetic"}
 
+    if not args.no_others:
+        result["between_other_work"] = between_other_work(hot, torch, wl, x, gen)
     if not args.no_others and not gen:
         fw = framework_step(torch, wl, x)
         fw["speedup_of_this_library"] = fw["ms_per_step"] / ms_per_step
@@ -756,6 +839,9 @@ def main() -> int:
                             "fwd_ms": ro["fwd_ms"], "bwd_ms": ro["bwd_ms"],
                             "step_frac_of_hbm_roofline": (fb + bb) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                             "verified_against_oracle": check(o, xo, ro["out"], gen)}
+            others[name]["between_other_work"] = between_other_work(hot, torch, o, xo, gen)
+            if o.items >= 50_000_000:      # HBM-bound sizes: each kernel beside a no-arithmetic kernel with its stream mix
+                others[name]["mix_ceiling"] = mix_ceilings(hot, torch, dev, o, gen, ro["fwd_ms"], ro["bwd_ms"])
             if o.items < 50_000_000:       # launch-latency-bound sizes: the same step replayed from a HIP graph
                 gms = time_graph_steps(hot, torch, o, xo, 200, gen)
                 others[name]["hip_graph_ms_per_step"] = gms

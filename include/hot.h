@@ -67,9 +67,13 @@ typedef struct hot_desc {
 /* Launch geometry of one kernel; a zero field means "library default". */
 typedef struct hot_launch {
     int32_t grid_blocks; /* upper bound on workgroups (each strides over column tiles), <= 65536 */
-    int32_t chunks;      /* 16-byte column chunks per thread and tile: 1, 2 or 4 */
+    int32_t chunks;      /* 16-byte column chunks per thread and tile: 1, 2 or 4 (default: 4 where that leaves at least
+                            512 column tiles that fill their rounds of 256 workgroups to 90 %, else 2, else 1) */
     int32_t unroll;      /* sample rows whose loads are issued together: 1, 2 or 4 */
-    int32_t nontemporal; /* 1: every array is accessed with non-temporal hints (default when S_loc*ld*4 bytes >= 256 MiB) */
+    int32_t nontemporal; /* 1: every array is accessed with non-temporal hints (the default: the arrays are touched once
+                            per step and should not displace, or pay for displacing, what the network left in the
+                            memory-side cache); 0: plain accesses (faster only when nothing else runs between the
+                            calls and all arrays fit in that cache together) */
 } hot_launch;
 
 #define HOT_KERNEL_FORWARD 0
@@ -436,12 +440,14 @@ int hot_stats_whole(const float *yhat, int64_t m, int64_t ld, int32_t s, int32_t
 int hot_probe_copy(void *dst, const void *src, int64_t bytes, int nontemporal, void *stream);
 
 /*
- * Measurement aid: `reads` (1..6) read streams and `writes` (0..2) write streams of
+ * Measurement aid: `reads` (1..64) read streams and `writes` (0..64) write streams of
  * stream_bytes each (a multiple of 16), laid out back to back in `arena` (a DEVICE buffer
  * of (reads + writes) * stream_bytes bytes, 16-byte aligned; read streams first).  Every
  * write stream receives the element-wise sum of the read streams.  With the stream counts
  * of one of the kernels above it measures the machine's ceiling for that kernel's mix of
- * read and write traffic.
+ * read and write traffic.  Up to 6 read and 2 write streams a thread loads all of them before it
+ * stores; beyond that (then writes >= 1) it walks the read streams four at a time and the write
+ * streams one at a time, as the kernels walk their sample rows.
  */
 int hot_probe_streams(void *arena, int64_t stream_bytes, int reads, int writes, void *stream);
 

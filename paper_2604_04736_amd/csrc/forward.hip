@@ -431,10 +431,11 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     a.grid = dim3(grid_for(d.n_weights, c));
     a.stream = static_cast<hipStream_t>(stream);
 
-    // Rows of w off the 64-byte grid, streamed with non-temporal stores, eps from its array: the kernel that
-    // moves its column window row by row (fixed shape: four chunks).
+    // Rows of w off the 64-byte grid, streamed with non-temporal stores, eps from its array, four chunks per
+    // thread: the kernel that moves its column window row by row (its shape is fixed at four chunks; with
+    // fewer, i.e. few column tiles, the general kernel runs).
     const bool rows_on_grid = (reinterpret_cast<uintptr_t>(w) & 63u) == 0 && (d.s_local == 1 || d.ld % 16 == 0);
-    const bool shifted = !kl_only && !adam && !gen && c.nontemporal != 0 && !rows_on_grid;
+    const bool shifted = !kl_only && !adam && !gen && c.nontemporal != 0 && c.chunks == 4 && !rows_on_grid;
     if (shifted) {
         const long windows = (d.n_weights + 15 + 4095) / 4096;
         a.grid = dim3((unsigned)(windows < c.grid_blocks ? windows : c.grid_blocks));

@@ -260,18 +260,24 @@ def test_errors_from_the_c_abi(hot):
     with pytest.raises(TypeError):
         hot.hot_forward(plan, t[:1024].cpu(), t[:1024], t[:2048].view(2, 1024), t[:2048].view(2, 1024))
     cfg = hot.hot_get_launch(plan, hot.HOT_KERNEL_BACKWARD)
-    # two samples, few weights: one chunk per thread, both rows in flight, ordinary cache hints
-    assert cfg["unroll"] == 2 and cfg["nontemporal"] == 0 and cfg["chunks"] == 1 and cfg["grid_blocks"] > 0
-    assert hot.hot_get_launch(plan, hot.HOT_KERNEL_FORWARD)["chunks"] == 4
+    # two samples, few weights: one chunk per thread, both rows in flight; non-temporal hints at every size
+    assert cfg["unroll"] == 2 and cfg["nontemporal"] == 1 and cfg["chunks"] == 1 and cfg["grid_blocks"] > 0
+    assert hot.hot_get_launch(plan, hot.HOT_KERNEL_FORWARD)["chunks"] == 1
     hot.hot_destroy(plan)
     big = hot.hot_create(1 << 26, 1 << 26, 2, 2, 1.0, 0)      # 512 MiB of samples: four chunks, non-temporal
     cfg = hot.hot_get_launch(big, hot.HOT_KERNEL_BACKWARD)
     assert cfg["chunks"] == 4 and cfg["nontemporal"] == 1
     hot.hot_destroy(big)
-    many = hot.hot_create(1 << 20, 1 << 20, 16, 16, 1.0, 0)
+    many = hot.hot_create(1 << 22, 1 << 22, 16, 16, 1.0, 0)
     assert hot.hot_get_launch(many, hot.HOT_KERNEL_FORWARD_RNG)["chunks"] == 1
     assert hot.hot_get_launch(many, hot.HOT_KERNEL_BACKWARD)["chunks"] == 4
     hot.hot_destroy(many)
+    # chunks per thread follow the number of column tiles: 2.7 M weights are 658 tiles of 4096 (2.6 rounds of the
+    # 256 compute units) -> smaller tiles; 1 M weights are 256 tiles of 4096 -> 512 tiles of 2048
+    for n_w, want in ((2_693_578, 1), (1 << 20, 2), (6_291_456, 4), (7_700_003, 4), (300_000, 1)):
+        pl = hot.hot_create(n_w, n_w, 4, 16, 1.0, 0)
+        assert hot.hot_get_launch(pl, hot.HOT_KERNEL_FORWARD)["chunks"] == want, n_w
+        hot.hot_destroy(pl)
     hot.hot_destroy(plan)      # second destroy of the wrapper is a no-op
 
 
@@ -291,17 +297,28 @@ def test_probe_copy_is_exact(hot):
 
 def test_probe_streams_sums_its_read_streams(hot):
     count = 100_000                      # floats per stream, a multiple of 4
-    for reads, writes in [(1, 0), (1, 1), (2, 2), (4, 2), (6, 2), (6, 0), (3, 1), (5, 2)]:
+    for reads, writes in [(1, 0), (1, 1), (2, 2), (4, 2), (6, 2), (6, 0), (3, 1), (5, 2), (7, 1), (18, 16), (34, 2), (15, 13),
+                          (28, 2), (64, 64), (3, 3)]:
         arena = torch.randn((reads + writes) * count, device=DEV)
         before = arena.clone()
         hot.hot_probe_streams(arena, 4 * count, reads, writes)
         torch.cuda.synchronize()
         assert torch.equal(arena[:reads * count], before[:reads * count])
-        want = before[:count].clone()
-        for r in range(1, reads):
-            want += before[r * count:(r + 1) * count]
+        if reads > 6 or writes > 2:        # the looping kernel adds four streams at a time onto a running sum from zero
+            want = torch.zeros(count, device=DEV)
+            for r0 in range(0, reads - reads % 4, 4):
+                for r in range(r0, r0 + 4):
+                    want += before[r * count:(r + 1) * count]
+            for r in range(reads - reads % 4, reads):
+                want += before[r * count:(r + 1) * count]
+        else:
+            want = before[:count].clone()
+            for r in range(1, reads):
+                want += before[r * count:(r + 1) * count]
         for w in range(writes):
             assert torch.equal(arena[(reads + w) * count:(reads + w + 1) * count], want)
+    with pytest.raises(hot.HotError):
+        hot.hot_probe_streams(torch.zeros(1024, device=DEV), 16, 65, 1)
     with pytest.raises(hot.HotError):
         hot.hot_probe_streams(torch.zeros(64, device=DEV), 16, 7, 0)
     with pytest.raises(ValueError):
@@ -533,7 +550,7 @@ def test_rows_off_the_64_byte_grid(oracle, hot):
             mu_d, sg_d, eps_d = at(mu, int(rs.integers(0, 4))), at(sigma, int(rs.integers(0, 4))), at(eps_h, e_off)
             plan = hot.hot_create(n, ld, s, 2 * s, 77.0, 0)
             for kern in (hot.HOT_KERNEL_FORWARD, hot.HOT_KERNEL_FORWARD_RNG):
-                hot.hot_set_launch(plan, kern, nontemporal=1, grid_blocks=grid)
+                hot.hot_set_launch(plan, kern, nontemporal=1, grid_blocks=grid, chunks=4)
             # eps from its array
             w = at(eps_h, w_off, fill=123456.0)
             kl = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)

@@ -139,20 +139,33 @@ struct AdamUpdateSample {
 // Backward: column sums over the local samples of grad_w and grad_w * eps, then the
 // KL gradient and the scaling (Algorithm 2, loss / gradient / averaging lines).
 // ---------------------------------------------------------------------------------
-template <int CHUNKS, int U, bool ALIGNED, bool NT, bool GEN>
-__device__ __forceinline__ void backward_rows(int s, long col0, long ld, double (&sum_g)[CHUNKS][4],
+// Rows s .. s+U-1 of one thread's chunks: all loads first, then the sums.  FULL: the tile has all its CHUNKS * 1024
+// columns and is read through plain pointers; otherwise through range-checked windows of `bytes` bytes from column
+// `begin` on (no branches: see window() in vec.h; what lies beyond the tile reads as zero and adds nothing).
+template <int CHUNKS, int U, bool ALIGNED, bool NT, bool GEN, bool FULL>
+__device__ __forceinline__ void backward_rows(int s, long begin, unsigned bytes, long ld, double (&sum_g)[CHUNKS][4],
                                               double (&sum_ge)[CHUNKS][4], const float *__restrict__ eps,
                                               const float *__restrict__ gw, const Rng &rng)
 {
     constexpr long kStep = (long)kBlock * 4;
+    const long col0 = begin + (long)threadIdx.x * 4;
+    const unsigned off0 = threadIdx.x * 16u;
     f4 gv[U][CHUNKS], ev[U][CHUNKS];
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int u = 0; u < U; ++u) {
+        [[maybe_unused]] window_t in;
+        if constexpr (!FULL) in = window(gw + (size_t)(s + u) * (size_t)ld + begin, bytes);
 #pragma unroll
         for (int c = 0; c < CHUNKS; ++c) {
-            gv[u][c] = load4<ALIGNED, NT>(gw + (size_t)(s + u) * (size_t)ld + col0 + c * kStep);
-            ev[u][c] = eps4<ALIGNED, NT, GEN>(eps, ld, s + u, col0 + c * kStep, rng);
+            if constexpr (FULL) {
+                gv[u][c] = load4<ALIGNED, NT>(gw + (size_t)(s + u) * (size_t)ld + col0 + c * kStep);
+                ev[u][c] = eps4<ALIGNED, NT, GEN>(eps, ld, s + u, col0 + c * kStep, rng);
+            } else {
+                gv[u][c] = window_load4<NT>(in, off0 + c * (unsigned)(kStep * 4));
+                ev[u][c] = eps4_window<NT, GEN>(eps, ld, s + u, begin, bytes, off0 + c * (unsigned)(kStep * 4), rng);
+            }
         }
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -165,66 +178,72 @@ __device__ __forceinline__ void backward_rows(int s, long col0, long ld, double 
             }
 }
 
+// One column tile [begin, end) of the backward kernel for one thread: mu and sigma of its chunks, the sample sums,
+// the finished gradients handed to the epilogue.
+template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool GEN, bool FULL, class EPI>
+__device__ __forceinline__ void backward_tile(long begin, long end, long ld, int s_loc, double g, double k,
+                                              const float *mu, const float *sigma, const float *__restrict__ eps,
+                                              const float *__restrict__ gw, const EPI &epi, const Rng &rng, double &acc)
+{
+    constexpr long kStep = (long)kBlock * 4;
+    const long col0 = begin + (long)threadIdx.x * 4;
+    const unsigned bytes = (unsigned)(((end & ~3L) - begin) * 4);     // the tile's whole quads
+    f4 m[CHUNKS], sd[CHUNKS];
+    bool ok[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+        ok[c] = FULL || col0 + c * kStep + 4 <= end;
+        if constexpr (FULL) {
+            m[c] = load4<ALIGNED, NT>(mu + col0 + c * kStep);
+            sd[c] = load4<ALIGNED, NT>(sigma + col0 + c * kStep);
+        } else {
+            m[c] = window_load4<NT>(window(mu + begin, bytes), threadIdx.x * 16u + c * (unsigned)(kStep * 4));
+            sd[c] = window_load4<NT>(window(sigma + begin, bytes), threadIdx.x * 16u + c * (unsigned)(kStep * 4));
+        }
+    }
+    double sum_g[CHUNKS][4], sum_ge[CHUNKS][4];
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sum_g[c][j] = sum_ge[c][j] = 0.0;
+    int s = 0;
+    for (; s + UNROLL <= s_loc; s += UNROLL)
+        backward_rows<CHUNKS, UNROLL, ALIGNED, NT, GEN, FULL>(s, begin, bytes, ld, sum_g, sum_ge, eps, gw, rng);
+    for (; s < s_loc; ++s)
+        backward_rows<CHUNKS, 1, ALIGNED, NT, GEN, FULL>(s, begin, bytes, ld, sum_g, sum_ge, eps, gw, rng);
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c)
+        if (ok[c]) {
+            double gm[4], gs[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) finish_grad(sum_g[c][j], sum_ge[c][j], m[c][j], sd[c][j], g, k, gm[j], gs[j]);
+            epi.template quad<ALIGNED, NT>(col0 + c * kStep, m[c], sd[c], gm, gs, acc);
+        }
+}
+
 template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool GEN, class EPI>
 __global__ void __launch_bounds__(kBlock)
-hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
+hot_backward_kernel(long n, long ld, int s_loc, long width, double g, double k,
                     const float *mu, const float *sigma,
                     const float *__restrict__ eps, const float *__restrict__ gw, EPI epi, Rng rng)
 {
-    constexpr long kTile = (long)kBlock * 4 * CHUNKS;
+    // Column tiles as in the forward kernel: tile t is [t * width, min(n, (t + 1) * width)), width <= CHUNKS * 1024.
     constexpr long kStep = (long)kBlock * 4;
-    const long n_tiles = (n + kTile - 1) / kTile;
+    const long n_tiles = (n + width - 1) / width;
     double acc = 0.0;   // what a reducing epilogue sums per thread (the KL addends of AdamUpdateSample)
 
     for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const long col0 = tile * kTile + (long)threadIdx.x * 4;
-        if ((tile + 1) * kTile <= n) {
-            f4 m[CHUNKS], sd[CHUNKS];
-#pragma unroll
-            for (int c = 0; c < CHUNKS; ++c) {
-                m[c] = load4<ALIGNED, NT>(mu + col0 + c * kStep);
-                sd[c] = load4<ALIGNED, NT>(sigma + col0 + c * kStep);
-            }
-            double sum_g[CHUNKS][4], sum_ge[CHUNKS][4];
-#pragma unroll
-            for (int c = 0; c < CHUNKS; ++c)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) sum_g[c][j] = sum_ge[c][j] = 0.0;
-            int s = 0;
-            for (; s + UNROLL <= s_loc; s += UNROLL)
-                backward_rows<CHUNKS, UNROLL, ALIGNED, NT, GEN>(s, col0, ld, sum_g, sum_ge, eps, gw, rng);
-            for (; s < s_loc; ++s)
-                backward_rows<CHUNKS, 1, ALIGNED, NT, GEN>(s, col0, ld, sum_g, sum_ge, eps, gw, rng);
-#pragma unroll
-            for (int c = 0; c < CHUNKS; ++c) {
-                double gm[4], gs[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) finish_grad(sum_g[c][j], sum_ge[c][j], m[c][j], sd[c][j], g, k, gm[j], gs[j]);
-                epi.template quad<ALIGNED, NT>(col0 + c * kStep, m[c], sd[c], gm, gs, acc);
-            }
+        const long begin = tile * width;
+        const long end = begin + width < n ? begin + width : n;
+        if (end - begin == CHUNKS * kStep) {
+            backward_tile<CHUNKS, UNROLL, ALIGNED, NT, GEN, true>(begin, end, ld, s_loc, g, k, mu, sigma, eps, gw, epi, rng, acc);
         } else {
-            for (int c = 0; c < CHUNKS; ++c) {
-                const long col = col0 + c * kStep;
-                if (col + 4 <= n) {
-                    const f4 m = load4<ALIGNED, false>(mu + col);
-                    const f4 sd = load4<ALIGNED, false>(sigma + col);
-                    double sum_g[4] = {0.0, 0.0, 0.0, 0.0}, sum_ge[4] = {0.0, 0.0, 0.0, 0.0};
-                    for (int s = 0; s < s_loc; ++s) {
-                        const f4 gv = load4<ALIGNED, false>(gw + (size_t)s * (size_t)ld + col);
-                        const f4 ev = eps4<ALIGNED, false, GEN>(eps, ld, s, col, rng);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const double gd = (double)gv[j];
-                            sum_g[j] += gd;
-                            sum_ge[j] = fma(gd, (double)ev[j], sum_ge[j]);
-                        }
-                    }
-                    double gm[4], gs[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) finish_grad(sum_g[j], sum_ge[j], m[j], sd[j], g, k, gm[j], gs[j]);
-                    epi.template quad<ALIGNED, false>(col, m, sd, gm, gs, acc);
-                } else {
-                    for (long i = col; i < n; ++i) {
+            backward_tile<CHUNKS, UNROLL, ALIGNED, NT, GEN, false>(begin, end, ld, s_loc, g, k, mu, sigma, eps, gw, epi, rng, acc);
+            // the final 1..3 columns of the vector (n not a multiple of 4), one by one, by the thread whose quad they start
+            if (end == n && (n & 3)) {
+                const long first = n & ~3L;
+                if ((long)threadIdx.x * 4 == (first - begin) % kStep) {
+                    for (long i = first; i < n; ++i) {
                         double sum_g = 0.0, sum_ge = 0.0;
                         for (int s = 0; s < s_loc; ++s) {
                             const size_t at = (size_t)s * (size_t)ld + (size_t)i;
@@ -252,7 +271,7 @@ hot_backward_kernel(long n, long ld, int s_loc, double g, double k,
 
 template <class EPI>
 struct BwdArgs {
-    long n, ld;
+    long n, ld, width;
     int s_loc;
     double g, k;
     const float *mu, *sigma, *eps, *gw;
@@ -266,7 +285,7 @@ template <bool GEN, int CH, int U, bool AL, bool NT, class EPI>
 void bwd_go(const BwdArgs<EPI> &a)
 {
     hot_backward_kernel<CH, U, AL, NT, GEN, EPI><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-        a.n, a.ld, a.s_loc, a.g, a.k, a.mu, a.sigma, a.eps, a.gw, a.epi, a.rng);
+        a.n, a.ld, a.s_loc, a.width, a.g, a.k, a.mu, a.sigma, a.eps, a.gw, a.epi, a.rng);
 }
 template <bool GEN, int CH, int U, class EPI>
 void bwd_flags(bool al, bool nt, const BwdArgs<EPI> &a)
@@ -321,7 +340,9 @@ int backward_launch(hot_plan *plan, int kernel, const Rng *rng, const float *mu,
     a.epi = epi;
     a.rng = gen ? *rng : Rng{0, 0, 0, 0};
     a.rng.first_sample += (unsigned)first_row;
-    a.grid = dim3(grid_for(d.n_weights, c));
+    const Tiling tiling = tiling_for(d.n_weights, c);
+    a.width = tiling.width;
+    a.grid = dim3(tiling.grid);
     a.stream = static_cast<hipStream_t>(stream);
 
     DeviceGuard guard(d.device);
@@ -440,7 +461,7 @@ int hot_backward_adam_forward(hot_plan *plan, const hot_rng *rng, const hot_rng 
     if (rc != HOT_OK || !kl_out) return rc;
     DeviceGuard guard(plan->d.device);
     if (guard.err != hipSuccess) return fail_hip(plan, guard.err);
-    const unsigned blocks = grid_for(plan->d.n_weights, plan->cfg[HOT_KERNEL_BACKWARD_RNG]);
+    const unsigned blocks = tiling_for(plan->d.n_weights, plan->cfg[HOT_KERNEL_BACKWARD_RNG]).grid;
     hot_kl_finish_kernel<<<dim3(1), dim3(kFinishBlock), 0, static_cast<hipStream_t>(stream)>>>(plan->partials, (int)blocks, kl_out);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? HOT_OK : fail_hip(plan, e);

@@ -102,82 +102,107 @@ __device__ __forceinline__ void kl_leave(double kl, double *partials, unsigned *
 // sample, fused with the prior-matching line (mu and sigma are in registers anyway).
 // ---------------------------------------------------------------------------------
 
-// Rows s .. s+U-1 of one thread's chunks: all eps values first, then multiply-add and store.
-template <int CHUNKS, int U, bool ALIGNED, bool NT, bool GEN>
-__device__ __forceinline__ void forward_rows(int s, long col0, long ld, const f4 (&m)[CHUNKS],
+// Rows s .. s+U-1 of one thread's chunks: all eps values first, then multiply-add and store.  FULL: the tile has
+// all its CHUNKS * 1024 columns and is accessed through plain pointers; otherwise through range-checked windows of
+// `bytes` bytes from column `begin` on (no branches: see window() in vec.h).
+template <int CHUNKS, int U, bool ALIGNED, bool NT, bool GEN, bool FULL>
+__device__ __forceinline__ void forward_rows(int s, long begin, unsigned bytes, long ld, const f4 (&m)[CHUNKS],
                                              const f4 (&sd)[CHUNKS], const float *__restrict__ eps,
                                              float *__restrict__ w, const Rng &rng)
 {
     constexpr long kStep = (long)kBlock * 4;
+    const long col0 = begin + (long)threadIdx.x * 4;
+    const unsigned off0 = threadIdx.x * 16u;
     f4 e[U][CHUNKS];
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int c = 0; c < CHUNKS; ++c) e[u][c] = eps4<ALIGNED, NT, GEN>(eps, ld, s + u, col0 + c * kStep, rng);
+        for (int c = 0; c < CHUNKS; ++c) {
+            if constexpr (FULL) e[u][c] = eps4<ALIGNED, NT, GEN>(eps, ld, s + u, col0 + c * kStep, rng);
+            else e[u][c] = eps4_window<NT, GEN>(eps, ld, s + u, begin, bytes, off0 + c * (unsigned)(kStep * 4), rng);
+        }
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int u = 0; u < U; ++u) {
+        [[maybe_unused]] window_t out;
+        if constexpr (!FULL) out = window(w + (size_t)(s + u) * (size_t)ld + begin, bytes);
 #pragma unroll
         for (int c = 0; c < CHUNKS; ++c) {
             f4 r;
 #pragma unroll
             for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[c][j], e[u][c][j], m[c][j]);
-            store4<ALIGNED, NT>(w + (size_t)(s + u) * (size_t)ld + col0 + c * kStep, r);
+            if constexpr (FULL) store4<ALIGNED, NT>(w + (size_t)(s + u) * (size_t)ld + col0 + c * kStep, r);
+            else window_store4<NT>(out, off0 + c * (unsigned)(kStep * 4), r);
         }
+    }
+}
+
+// One column tile [begin, end) of the forward kernel for one thread: mu and sigma of its chunks (through the
+// prologue), all rows, and the KL addends.
+template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool KL, bool GEN, bool FULL, class PRO>
+__device__ __forceinline__ void forward_tile(long begin, long end, long ld, int s_loc, const float *mu, const float *sigma,
+                                             const float *__restrict__ eps, float *__restrict__ w, const PRO &pro,
+                                             const Rng &rng, double &kl)
+{
+    constexpr long kStep = (long)kBlock * 4;
+    const long col0 = begin + (long)threadIdx.x * 4;
+    const unsigned bytes = (unsigned)(((end & ~3L) - begin) * 4);     // the tile's whole quads
+    f4 m[CHUNKS], sd[CHUNKS];
+    bool ok[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+        ok[c] = FULL || col0 + c * kStep + 4 <= end;
+        if constexpr (FULL) {
+            m[c] = load4<ALIGNED, NT>(mu + col0 + c * kStep);
+            sd[c] = load4<ALIGNED, NT>(sigma + col0 + c * kStep);
+        } else {
+            m[c] = window_load4<NT>(window(mu + begin, bytes), threadIdx.x * 16u + c * (unsigned)(kStep * 4));
+            sd[c] = window_load4<NT>(window(sigma + begin, bytes), threadIdx.x * 16u + c * (unsigned)(kStep * 4));
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c)
+        if (ok[c]) pro.template quad<ALIGNED>(col0 + c * kStep, m[c], sd[c]);
+    int s = 0;
+    for (; s + UNROLL <= s_loc; s += UNROLL)
+        forward_rows<CHUNKS, UNROLL, ALIGNED, NT, GEN, FULL>(s, begin, bytes, ld, m, sd, eps, w, rng);
+    for (; s < s_loc; ++s) forward_rows<CHUNKS, 1, ALIGNED, NT, GEN, FULL>(s, begin, bytes, ld, m, sd, eps, w, rng);
+    if constexpr (KL) {
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c)
+            if (ok[c]) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) kl += kl_addend(m[c][j], sd[c][j]);
+            }
+    }
 }
 
 template <int CHUNKS, int UNROLL, bool ALIGNED, bool NT, bool KL, bool GEN, class PRO>
 __global__ void __launch_bounds__(kBlock)
-hot_forward_kernel(long n, long ld, int s_loc,
+hot_forward_kernel(long n, long ld, int s_loc, long width,
                    const float *mu, const float *sigma,
                    const float *__restrict__ eps, float *__restrict__ w,
                    double *partials, unsigned *ticket, double *__restrict__ kl_out, PRO pro, Rng rng)
 {
-    constexpr long kTile = (long)kBlock * 4 * CHUNKS;   // columns per tile
+    // Column tile t is [t * width, min(n, (t + 1) * width)): width <= CHUNKS * 1024 columns, a multiple of 64
+    // (tiling_for() picks it).  A thread's chunks sit 1024 columns apart from the tile's first column on.
     constexpr long kStep = (long)kBlock * 4;            // columns between a thread's chunks
-    const long n_tiles = (n + kTile - 1) / kTile;
+    const long n_tiles = (n + width - 1) / width;
     double kl = 0.0;
 
     for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const long col0 = tile * kTile + (long)threadIdx.x * 4;
-        if ((tile + 1) * kTile <= n) {
-            f4 m[CHUNKS], sd[CHUNKS];
-#pragma unroll
-            for (int c = 0; c < CHUNKS; ++c) {
-                m[c] = load4<ALIGNED, NT>(mu + col0 + c * kStep);
-                sd[c] = load4<ALIGNED, NT>(sigma + col0 + c * kStep);
-                pro.template quad<ALIGNED>(col0 + c * kStep, m[c], sd[c]);
-            }
-            int s = 0;
-            for (; s + UNROLL <= s_loc; s += UNROLL)
-                forward_rows<CHUNKS, UNROLL, ALIGNED, NT, GEN>(s, col0, ld, m, sd, eps, w, rng);
-            for (; s < s_loc; ++s) forward_rows<CHUNKS, 1, ALIGNED, NT, GEN>(s, col0, ld, m, sd, eps, w, rng);
-            if constexpr (KL) {
-#pragma unroll
-                for (int c = 0; c < CHUNKS; ++c)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) kl += kl_addend(m[c][j], sd[c][j]);
-            }
+        const long begin = tile * width;
+        const long end = begin + width < n ? begin + width : n;
+        if (end - begin == CHUNKS * kStep) {
+            forward_tile<CHUNKS, UNROLL, ALIGNED, NT, KL, GEN, true>(begin, end, ld, s_loc, mu, sigma, eps, w, pro, rng, kl);
         } else {
-            // ragged last tile: whole chunks as vectors, the final 1..3 columns one by one
-            for (int c = 0; c < CHUNKS; ++c) {
-                const long col = col0 + c * kStep;
-                if (col + 4 <= n) {
-                    f4 m = load4<ALIGNED, false>(mu + col);
-                    f4 sd = load4<ALIGNED, false>(sigma + col);
-                    pro.template quad<ALIGNED>(col, m, sd);
-                    for (int s = 0; s < s_loc; ++s) {
-                        const f4 e = eps4<ALIGNED, false, GEN>(eps, ld, s, col, rng);
-                        f4 r;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) r[j] = __builtin_fmaf(sd[j], e[j], m[j]);
-                        store4<ALIGNED, false>(w + (size_t)s * (size_t)ld + col, r);
-                    }
-                    if constexpr (KL) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) kl += kl_addend(m[j], sd[j]);
-                    }
-                } else {
-                    for (long i = col; i < n; ++i) {
+            // a narrower tile: the same, every chunk guarded
+            forward_tile<CHUNKS, UNROLL, ALIGNED, NT, KL, GEN, false>(begin, end, ld, s_loc, mu, sigma, eps, w, pro, rng, kl);
+            // the final 1..3 columns of the vector (n not a multiple of 4), one by one, by the thread whose quad they start
+            if (end == n && (n & 3)) {
+                const long first = n & ~3L;
+                const long off = first - begin;
+                if ((long)threadIdx.x * 4 == off % kStep) {
+                    for (long i = first; i < n; ++i) {
                         float m = mu[i], sd = sigma[i];
                         pro.one(i, m, sd);
                         for (int s = 0; s < s_loc; ++s) {
@@ -335,7 +360,7 @@ hot_forward_shifted_kernel(long n, long ld, int s_loc, const float *mu, const fl
 }
 
 struct FwdArgs {
-    long n, ld;
+    long n, ld, width;
     int s_loc;
     const float *mu, *sigma, *eps;
     float *w;
@@ -357,13 +382,13 @@ void fwd_go(const FwdArgs &a)
 {
     if (a.adam)
         hot_forward_kernel<CH, U, AL, NT, true, GEN, AdamPrologue><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, *a.adam, a.rng);
+            a.n, a.ld, a.s_loc, a.width, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, *a.adam, a.rng);
     else if (a.want_kl)
         hot_forward_kernel<CH, U, AL, NT, true, GEN, NoPrologue><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, NoPrologue{}, a.rng);
+            a.n, a.ld, a.s_loc, a.width, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, NoPrologue{}, a.rng);
     else
         hot_forward_kernel<CH, U, AL, NT, false, GEN, NoPrologue><<<a.grid, dim3(kBlock), 0, a.stream>>>(
-            a.n, a.ld, a.s_loc, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, NoPrologue{}, a.rng);
+            a.n, a.ld, a.s_loc, a.width, a.mu, a.sigma, a.eps, a.w, a.partials, a.ticket, a.kl_out, NoPrologue{}, a.rng);
 }
 template <bool GEN, int CH, int U>
 void fwd_flags(bool al, bool nt, const FwdArgs &a)
@@ -428,7 +453,9 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     a.kl_out = kl_out;
     a.adam = adam;
     a.rng = rng ? *rng : Rng{0, 0, 0, 0};
-    a.grid = dim3(grid_for(d.n_weights, c));
+    const Tiling tiling = tiling_for(d.n_weights, c);
+    a.width = tiling.width;
+    a.grid = dim3(tiling.grid);
     a.stream = static_cast<hipStream_t>(stream);
 
     // Rows of w off the 64-byte grid, streamed with non-temporal stores, eps from its array, four chunks per
@@ -436,7 +463,7 @@ int forward_impl(hot_plan *plan, int kernel, const Rng *rng, const float *mu, co
     // fewer, i.e. few column tiles, the general kernel runs).
     const bool rows_on_grid = (reinterpret_cast<uintptr_t>(w) & 63u) == 0 && (d.s_local == 1 || d.ld % 16 == 0);
     const bool shifted = !kl_only && !adam && !gen && c.nontemporal != 0 && c.chunks == 4 && !rows_on_grid;
-    if (shifted) {
+    if (shifted) {      // (its windows reach back by up to 15 columns, so there may be one more of them than tiles)
         const long windows = (d.n_weights + 15 + 4095) / 4096;
         a.grid = dim3((unsigned)(windows < c.grid_blocks ? windows : c.grid_blocks));
     }

@@ -39,6 +39,15 @@ __device__ __forceinline__ f4 eps4(const float *eps, long ld, int s, long col, c
     else return load4<ALIGNED, NT>(eps + (size_t)s * (size_t)ld + col);
 }
 
+// The same inside a column tile that begins at column `begin` and holds `bytes` bytes of whole quads: read through
+// a range-checked window (zeros beyond it), or drawn.  off = byte offset of the quad from the tile's first column.
+template <bool NT, bool GEN>
+__device__ __forceinline__ f4 eps4_window(const float *eps, long ld, int s, long begin, unsigned bytes, unsigned off, const Rng &rng)
+{
+    if constexpr (GEN) return eps_quad((begin + (off >> 2)) >> 2, s, rng);
+    else return window_load4<NT>(window(eps + (size_t)s * (size_t)ld + begin, bytes), off);
+}
+
 // eps[s, i] of a single weight (the ragged tail): read at its offset, or drawn with its quad.
 template <bool GEN>
 __device__ __forceinline__ float eps1(const float *eps, size_t at, long i, int s, const Rng &rng)
@@ -218,7 +227,8 @@ inline void default_launches(hot_plan &p)
     hot_launch &f = p.cfg[HOT_KERNEL_FORWARD], &b = p.cfg[HOT_KERNEL_BACKWARD];
     f.grid_blocks = b.grid_blocks = kMaxGrid;
     // Chunks per thread: four, unless that leaves fewer than two workgroups per compute unit or a last round of
-    // workgroups that is mostly empty (2.7 M weights are 658 tiles of 4096: 2.6 rounds of 256); then two, then one.
+    // workgroups that is mostly empty (2.7 M weights are 658 tiles of 4096: 2.6 rounds of 256); then two, then one
+    // (2.7 M weights x 4 samples with other work between the calls: backward 28.4 us with four chunks, 26.5 with one).
     f.chunks = b.chunks = balanced_chunks(d.n_weights);
     f.unroll = 1;
     b.unroll = pick_unroll(4, d.s_local);
@@ -241,12 +251,22 @@ inline void default_launches(hot_plan &p)
     br.unroll = pick_unroll(d.s_local >= 4 ? 1 : 2, d.s_local);
 }
 
-// Number of workgroups: one per column tile, capped by the configured bound.
-inline unsigned grid_for(long n, const hot_launch &c)
+// How the N columns are cut into tiles, one workgroup each (capped by the configured bound, beyond which workgroups
+// stride over the tiles): tiles of chunks * 1024 columns, the last one narrower.  The kernels take any width that is
+// a multiple of 64 columns (narrower tiles go through range-checked windows, see vec.h).  Cutting the width down so
+// that every compute unit holds the same number of equally wide tiles was built and measured (13 samples, 6.3 M to
+// 13 M weights, other work between the calls): no gain over full tiles within +-3 %; what does vary by 5 % from one
+// N to the next is not the partly filled last round of workgroups.
+struct Tiling {
+    long width;       // columns per tile
+    unsigned grid;    // workgroups
+};
+
+inline Tiling tiling_for(long n, const hot_launch &c)
 {
-    const long tile = (long)kBlock * 4 * c.chunks;
-    const long tiles = (n + tile - 1) / tile;
-    return (unsigned)(tiles < c.grid_blocks ? tiles : c.grid_blocks);
+    const long width = (long)kBlock * 4 * c.chunks;
+    const long tiles = (n + width - 1) / width;
+    return Tiling{width, (unsigned)(tiles < c.grid_blocks ? tiles : c.grid_blocks)};
 }
 
 }  // namespace

@@ -47,6 +47,33 @@ __device__ __forceinline__ void store4(float *p, f4 v)
     }
 }
 
+// Range-checked 16-byte accesses for column tiles narrower than their threads' reach: a window of `bytes` bytes at
+// p (uniform over the wave), addressed by byte offsets.  The hardware's buffer addressing returns zeros for a load
+// beyond the window and drops a store beyond it, so no thread branches around its accesses: a branch would make
+// the compiler wait for ALL outstanding memory operations before every store behind it (it cannot count them
+// across the join), which serialises a workgroup's stores.  Windows and offsets here are multiples of 16 bytes
+// (of 4 for the base address), so a quad is inside or outside as a whole.
+typedef int i4 __attribute__((ext_vector_type(4)));
+typedef __amdgpu_buffer_rsrc_t window_t;
+
+__device__ __forceinline__ window_t window(const float *p, unsigned bytes)
+{
+    // (stride 0, `bytes` records, 32-bit data format: the raw-buffer descriptor of gfx9-family chips)
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p), 0, (int)bytes, 0x00020000);
+}
+
+template <bool NT>
+__device__ __forceinline__ f4 window_load4(window_t win, unsigned byte_offset)
+{
+    return __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(win, (int)byte_offset, 0, NT ? 2 : 0));
+}
+
+template <bool NT>
+__device__ __forceinline__ void window_store4(window_t win, unsigned byte_offset, f4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(i4, v), win, (int)byte_offset, 0, NT ? 2 : 0);
+}
+
 __device__ __forceinline__ double wave_sum(double v)
 {
 #pragma unroll

@@ -312,16 +312,29 @@ def cpu_baseline(oracle, np, wl, x, max_weights: int, out=None):
             "kl": kl64, "every_element": compared}
 
 
-def alu_roofline_forward_rng(s_local: int, achieved_items_per_s: float):
-    """Vector-ALU ceiling of the drawing forward kernel, from the instruction mix of its compiled loop
-    (per wave and 16-byte chunk): one sample's draw, multiply-add and store is 17 64-bit integer
-    multiply-adds and 8 transcendentals at 16 issue cycles plus about 62 full-rate instructions at 4,
-    650 cycles; the KL addends of the chunk's four weights are about 300 more.  A wave finishes
-    4 * 64 * S_loc items in that time, on 1024 SIMDs (256 compute units) at 2.4 GHz."""
-    cycles = 650.0 * s_local + 300.0
-    peak = 256.0 * s_local / cycles * 1024 * 2.4e9
+def alu_roofline_forward_rng(workload: str, achieved_items_per_s: float):
+    """Vector-ALU ceiling of the drawing forward kernel from hardware counters (the committed rocprofv3 summary
+    of this workload): SQ_ACTIVE_INST_VALU gives the SIMD-cycles the vector ALUs were busy per launch, hence per
+    item; the chip has 1024 SIMDs (256 compute units x 4) at a nominal 2.4 GHz, so at most
+    1024 * 2.4e9 / (SIMD-cycles per item) items/s.  The summary also holds the clock the chip actually ran the
+    kernel at (GRBM_GUI_ACTIVE per XCD over the kernel's duration) and the busy fraction at that clock."""
+    path = os.path.join(ROOT, "profiles", f"hot_forward_rng_kernel_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+
+    def field(name):
+        m = re.search(r"^" + name + r":\s*([0-9.eE+-]+)", text, re.M)
+        return float(m.group(1)) if m else None
+
+    per_item, clock, busy = field("valu_simd_cycles_per_item"), field("measured_clock_GHz"), field("valu_busy_frac_at_measured_clock")
+    if per_item is None:
+        return None
+    peak = 1024 * 2.4e9 / per_item
     return {"bound": "alu", "kernel": "hot_forward_kernel (drawn eps)", "achieved": achieved_items_per_s, "peak": peak,
-            "unit": "items/s", "frac": achieved_items_per_s / peak}
+            "unit": "items/s", "frac": achieved_items_per_s / peak, "valu_simd_cycles_per_item": per_item,
+            "measured_clock_GHz": clock, "valu_busy_frac_at_measured_clock": busy,
+            "source": "SQ_ACTIVE_INST_VALU, GRBM_GUI_ACTIVE of " + os.path.basename(path)}
 
 
 def framework_step(torch, wl, x, iters: int = 5):
@@ -817,7 +830,7 @@ def main() -> int:
             "fwd_GBps": fb / rr["fwd_ms"] / 1e6, "bwd_GBps": bb / rr["bwd_ms"] / 1e6,
             "step_frac_of_hbm_roofline": (fb + bb) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "verified_against_oracle": check(wl, xr, rr["out"], True),
-            "forward_alu_roofline": alu_roofline_forward_rng(wl.s_local, items / (rr["fwd_ms"] * 1e-3)),
+            "forward_alu_roofline": alu_roofline_forward_rng(wl.name, items / (rr["fwd_ms"] * 1e-3)),
             "note": "hot_forward_rng + hot_backward_rng: Philox-4x32-10 + Box-Muller in registers"}
         del xr, rr
         torch.cuda.empty_cache()

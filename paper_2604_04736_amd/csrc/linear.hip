@@ -57,6 +57,8 @@ __device__ __forceinline__ void mfma_results_settle()
     __builtin_amdgcn_sched_barrier(0);
 }
 
+__device__ __forceinline__ float pick4_of(f4 v, int c) { return c == 0 ? v[0] : (c == 1 ? v[1] : (c == 2 ? v[2] : v[3])); }
+
 struct LinearArgs {
     long rows, in_features, out_features, ldx;
     long x_sample_stride;   // floats between the inputs of consecutive samples (0: one input for all)
@@ -357,6 +359,190 @@ hot_linear_forward_rows_kernel(LinearArgs a)
             }
         }
     }
+}
+
+// ---------------------------------------------------------------------------------
+// The same layer for thousands of rows.  On this chip the fp32 matrix instructions and the vector ALU do not run
+// side by side (the fp32 matrix rate equals the packed fp32 vector rate: the same multipliers serve both; measured
+// with the two kinds of work in different waves of one SIMD, the times add), so every cycle spent drawing is lost to
+// the contraction, and the share of the draw is 81 / (rows per workgroup): a third at 256 rows.  Here a workgroup
+// of eight waves owns 512 rows x 64 outputs; per step of 16 inputs each thread draws at most ONE quad of the
+// 64 x 16 weight tile (two samples: thread t draws sample t / 256), and x is staged through LDS as well, loaded
+// from memory with consecutive lanes on consecutive addresses.  Both tiles are double-buffered: while the matrix
+// instructions of step i run from one buffer, the operands of step i + 1 are on their way from memory (requested
+// before the matrix instructions, consumed after them), are drawn, and go into the other buffer; one barrier per
+// step.  The matrix instruction is v_mfma_f32_32x32x2_f32: a wave multiplies its 64 rows by all 64 outputs as 2 x 2
+// tiles of 32 x 32, and one 16-byte LDS read per operand tile feeds four instructions (lanes 0-31 hold inputs
+// k .. k + 3 of their row or output, lanes 32-63 inputs k + 4 .. k + 7; instruction i takes element i of both
+// operands, so the contraction index is enumerated in another order, identically on both sides).
+// All global accesses go through range-checked windows (see vec.h): rows beyond R, outputs beyond O and inputs
+// beyond K are masked by offsets outside the window, without branches, so the loads of the next step stay in
+// flight across the matrix instructions.
+// ---------------------------------------------------------------------------------
+constexpr int kBigWaves = 8;
+constexpr int kBigRows = 64 * kBigWaves;     // rows per workgroup
+constexpr int kBigOuts = 64;                 // outputs per workgroup
+constexpr int kBigK = 16;                    // inputs per step
+constexpr int kBigPitch = kBigK + 4;         // floats per row of the LDS tiles (80 bytes: eight lanes' 16-byte reads cover all banks)
+constexpr unsigned kOutside = 0xFFFFFFF0u;   // a byte offset beyond any window
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+// What the kernel below works on: out_s[row][n] = sum_c in_s[row][c] W_s[n][c] + bias_s[n] with W_s drawn: in = x
+// (one for all samples, or one per sample), c runs over the layer's inputs, n over its outputs, weight (n, c) has flat
+// index n * C + c (the generator's quads run along c).  (The input gradients, dx = dy W, were run through the same kernel
+// with the drawn tile transposed on its way into LDS: 106 against 105-112 TFLOP/s for the kernel they have; not kept.)
+struct BigArgs {
+    long rows, contract, outs;   // R, C, N
+    long ld_in;                  // pitch of the rows of `in`
+    long in_sample_stride;       // floats between the inputs of consecutive samples (0: one input for all)
+    int s_loc;
+    long weight_quad0, bias_quad0;
+    const float *in, *mu_w, *sigma_w, *mu_b, *sigma_b;
+    float *out;                  // [S_loc, R, N] packed
+    Rng rng;
+};
+
+// ST samples per pass (they share the input tile); OWN: every sample has an input of its own (then ST = 1).
+template <int ST, bool OWN>
+__global__ void __launch_bounds__(64 * kBigWaves, 1)
+hot_linear_big_kernel(BigArgs a)
+{
+    static_assert(ST == 1 || ST == 2, "one or two samples per pass");
+    static_assert(!OWN || ST == 1, "one input per sample: one sample per pass");
+    __shared__ __attribute__((aligned(16))) float xt[2][kBigRows * kBigPitch];
+    __shared__ __attribute__((aligned(16))) float wt[2][ST][kBigOuts * kBigPitch];      // [n][c]
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const long C = a.contract, N = a.outs, R = a.rows;
+    const long n0 = (long)blockIdx.x * kBigOuts, r0 = (long)blockIdx.y * kBigRows;
+
+    // as a loading thread: quad (t + 512 j) % 4 of row (t + 512 j) / 4 of the input tile, j = 0..3 (2048 quads per step)
+    // as a drawing thread: sample t / 256 (ST == 2) and one of the tile's 256 quads: quad idx % 4 (along c) of output idx / 4
+    const int d_st = ST == 2 ? t >> 8 : 0, d_idx = t & 255;
+    const bool draws = ST == 2 || t < 256;
+    const int d_n = d_idx >> 2;            // the quad's output, relative to n0
+    const int d_c = 4 * (d_idx & 3);       // its first input, relative to the step
+    const window_t mu_win = window(a.mu_w, (unsigned)(C * N * 4)), sg_win = window(a.sigma_w, (unsigned)(C * N * 4));
+    const unsigned in_bytes = (unsigned)(((R - 1) * a.ld_in + C) * 4);
+
+    for (int s0 = 0; s0 < a.s_loc; s0 += ST) {
+        const window_t in_win = window(OWN ? a.in + (size_t)s0 * (size_t)a.in_sample_stride : a.in, in_bytes);
+        f16v acc[ST][2][2];
+#pragma unroll
+        for (int st = 0; st < ST; ++st)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[st][rb][cb][i] = 0.0f;
+
+        f4 xg[4], m4, sd4;
+        // flat index of the first weight of this thread's quad in the step that starts at contraction index cb0, or -1
+        auto quad_at = [&](long cb0) -> long {
+            const long n = n0 + d_n, c = cb0 + d_c;
+            if (!draws || n >= N || c >= C) return -1;
+            return n * C + c;
+        };
+        // requests the operands of the step that starts at contraction index cb0 (nothing is read where the tile ends)
+        auto request = [&](long cb0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int idx = t + 512 * j;
+                const long row = r0 + (idx >> 2), c = cb0 + 4 * (idx & 3);
+                xg[j] = window_load4<false>(in_win, (row < R && c < C) ? (unsigned)((row * a.ld_in + c) * 4) : kOutside);
+            }
+            const long at = quad_at(cb0);
+            m4 = window_load4<false>(mu_win, at >= 0 ? (unsigned)(at * 4) : kOutside);
+            sd4 = window_load4<false>(sg_win, at >= 0 ? (unsigned)(at * 4) : kOutside);
+        };
+        // draws this thread's quad of that step and puts the requested operands into tile buffer `buf`
+        auto deposit = [&](long cb0, int buf) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int idx = t + 512 * j;
+                *reinterpret_cast<f4 *>(&xt[buf][(idx >> 2) * kBigPitch + 4 * (idx & 3)]) = xg[j];
+            }
+            if (draws) {
+                const long at = quad_at(cb0);
+                f4 w4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (at >= 0 && s0 + d_st < a.s_loc) {
+                    const f4 e = eps_quad(a.weight_quad0 + (at >> 2), s0 + d_st, a.rng);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) w4[c] = __builtin_fmaf(sd4[c], e[c], m4[c]);
+                }
+                *reinterpret_cast<f4 *>(&wt[buf][d_st][d_n * kBigPitch + d_c]) = w4;
+            }
+        };
+
+        request(0);
+        deposit(0, 0);
+        __syncthreads();
+        int buf = 0;
+        for (long cb0 = 0; cb0 < C; cb0 += kBigK, buf ^= 1) {
+            request(cb0 + kBigK);           // (all offsets outside the windows behind the last step: no traffic)
+#pragma unroll
+            for (int k8 = 0; k8 < 2; ++k8) {
+                f4 xa[2];
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+                    xa[rb] = *reinterpret_cast<const f4 *>(&xt[buf][(64 * wave + 32 * rb + l32) * kBigPitch + 8 * k8 + 4 * half]);
+#pragma unroll
+                for (int st = 0; st < ST; ++st) {
+                    f4 wb[2];
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb)
+                        wb[cb] = *reinterpret_cast<const f4 *>(&wt[buf][st][(32 * cb + l32) * kBigPitch + 8 * k8 + 4 * half]);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                            for (int cb = 0; cb < 2; ++cb)
+                                acc[st][rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[rb][i], wb[cb][i], acc[st][rb][cb], 0, 0, 0);
+                }
+            }
+            if (cb0 + kBigK < C) deposit(cb0 + kBigK, buf ^ 1);      // uniform over the workgroup
+            __syncthreads();
+        }
+        mfma_results_settle();
+
+        // result register i of a 32 x 32 tile: row 8 (i / 4) + 4 (lane / 32) + i % 4, column lane % 32
+#pragma unroll
+        for (int st = 0; st < ST; ++st) {
+            if (s0 + st < a.s_loc) {
+                const window_t out_win = window(a.out + (size_t)(s0 + st) * (size_t)R * (size_t)N, (unsigned)(R * N * 4));
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) {
+                    const long n = n0 + 32 * cb + l32;
+                    const bool n_ok = n < N;
+                    float bias = 0.0f;
+                    if (a.mu_b && n_ok) {
+                        const f4 e = eps_quad(a.bias_quad0 + (n >> 2), s0 + st, a.rng);
+                        bias = __builtin_fmaf(a.sigma_b[n], pick4_of(e, (int)(n & 3)), a.mu_b[n]);
+                    }
+#pragma unroll
+                    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const long row = r0 + 64 * wave + 32 * rb + 8 * (i >> 2) + 4 * half + (i & 3);
+                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, acc[st][rb][cb][i] + bias), out_win,
+                                                                  (n_ok && row < R) ? (int)((row * N + n) * 4) : (int)kOutside, 0, 0);
+                        }
+                }
+            }
+        }
+    }
+}
+
+// Whether the kernel above can address this problem (its windows take 32-bit byte offsets).
+inline bool big_kernel_fits(long rows, long contract, long outs, long ld_in)
+{
+    const unsigned long long lim = 0xFFFFFFF0ull;
+    return (unsigned long long)((rows - 1) * ld_in + contract) * 4 < lim && (unsigned long long)contract * outs * 4 < lim &&
+           (unsigned long long)(rows + kBigRows) * outs * 4 < lim && (rows + kBigRows - 1) / kBigRows <= 65535;
 }
 
 template <int RB, bool XS>
@@ -1180,6 +1366,38 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     // pass and one column tile when several samples share x; a single sample, and samples with inputs of
     // their own (one per pass), afford two column tiles.
     {
+        // Thousands of rows: 512 rows x 64 outputs per workgroup (the draw's share of the vector ALU halves again).
+        const bool xs = d->x_sample_stride != 0;
+        const long gx = (d->out_features + kBigOuts - 1) / kBigOuts, gy = (d->rows + kBigRows - 1) / kBigRows;
+        // (measured against the 256-row kernel below: 96 against 78 TFLOP/s at 7260 x 540 x 2160, 112-115 against 93-95
+        // at 1024 x 8192^2 and 4096^3 with a shared x, 100 against 95 with one x per sample; with fewer workgroups than
+        // three quarters of the compute units it loses)
+        const bool want = d->rows >= 1024 && gx * gy >= 192;
+        if (want && big_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) {
+            BigArgs b;
+            b.rows = d->rows;
+            b.contract = d->in_features;
+            b.outs = d->out_features;
+            b.ld_in = d->ldx;
+            b.in_sample_stride = d->x_sample_stride;
+            b.s_loc = d->s_local;
+            b.weight_quad0 = a.weight_quad0;
+            b.bias_quad0 = a.bias_quad0;
+            b.in = x;
+            b.mu_w = mu_w;
+            b.sigma_w = sigma_w;
+            b.mu_b = mu_b;
+            b.sigma_b = sigma_b;
+            b.out = y;
+            b.rng = r;
+            const dim3 grid((unsigned)gx, (unsigned)gy), block(64 * kBigWaves);
+            if (xs) hot_linear_big_kernel<1, true><<<grid, block, 0, s>>>(b);
+            else if (d->s_local == 1) hot_linear_big_kernel<1, false><<<grid, block, 0, s>>>(b);
+            else hot_linear_big_kernel<2, false><<<grid, block, 0, s>>>(b);
+            return hot_detail::note_hip(hipGetLastError());
+        }
+    }
+    {
         const bool xs = d->x_sample_stride != 0;
         const int no = (d->s_local == 1 || xs) ? 2 : 1;      // one sample per pass: its x loads serve two column tiles
         const long gx = (d->out_features + kColsPerWave * no - 1) / (kColsPerWave * no);
@@ -1333,12 +1551,29 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
         return hot_detail::note_hip(hipGetLastError());
     }
     if (d->rows >= 256) {
-        for (int cand = 4; cand >= 1; cand >>= 1) {
+        // Rows per workgroup: 64 x cand.  All workgroups of these shapes are resident at once and those that share a
+        // compute unit share its SIMDs, so the kernel takes (most workgroups on one compute unit) x (one workgroup's
+        // work): per step 512 x cand matrix cycles per wave plus about 900 for the draw and the rest.  The count that
+        // minimises the product wins: 7260 rows x 540 inputs x 2 samples are 522 workgroups of 256 rows (three on ten
+        // compute units, two on the others: a third of the chip's time idle) but 684 of 192 rows (0.48 -> 0.40 ms).
+        int best = 0;
+        long best_cost = 0, best_gy = 0;
+        for (int cand = 4; cand >= 1; --cand) {
             const long gy_c = (d->rows + 64 * cand - 1) / (64 * cand);
-            if (gy_c > 65535 || k_groups * gy_c * d->s_local < (cand > 1 ? 256 : 128)) continue;     // (none fits: the kernel above)
-            const dim3 grid((unsigned)k_groups, (unsigned)gy_c, (unsigned)d->s_local);
-            if (cand == 4) hot_linear_xgrad_rows_kernel<4><<<grid, dim3(256), 0, s>>>(a);
-            else if (cand == 2) hot_linear_xgrad_rows_kernel<2><<<grid, dim3(256), 0, s>>>(a);
+            const long wgs = k_groups * gy_c * d->s_local;
+            if (gy_c > 65535 || wgs < 256) continue;     // (none fits: the kernel below, 15 % faster than 64-row workgroups there)
+            const long cost = ((wgs + 255) / 256) * (512L * cand + 900);
+            if (best == 0 || cost < best_cost) {
+                best = cand;
+                best_cost = cost;
+                best_gy = gy_c;
+            }
+        }
+        if (best) {
+            const dim3 grid((unsigned)k_groups, (unsigned)best_gy, (unsigned)d->s_local);
+            if (best == 4) hot_linear_xgrad_rows_kernel<4><<<grid, dim3(256), 0, s>>>(a);
+            else if (best == 3) hot_linear_xgrad_rows_kernel<3><<<grid, dim3(256), 0, s>>>(a);
+            else if (best == 2) hot_linear_xgrad_rows_kernel<2><<<grid, dim3(256), 0, s>>>(a);
             else hot_linear_xgrad_rows_kernel<1><<<grid, dim3(256), 0, s>>>(a);
             return hot_detail::note_hip(hipGetLastError());
         }

@@ -74,7 +74,11 @@ SHAPES = [(64, 96, 128, 4), (64, 128, 24, 4), (65, 192, 576, 4), (256, 192, 10, 
           (16, 32, 64, 1), (200, 64, 16, 2),
           # 256 rows and more on at least 128 workgroups: the kernel whose waves share the draws through LDS
           # (two samples per pass; an odd sample count; one sample with two column tiles; ragged everything)
-          (300, 64, 2100, 2), (1030, 36, 2050, 3), (260, 100, 4100, 1), (513, 132, 2049, 5)]
+          (300, 64, 2100, 2), (1030, 36, 2050, 3), (260, 100, 4100, 1), (513, 132, 2049, 5),
+          # 1024 rows and more on at least 192 workgroups of 512 rows x 64 outputs: the kernel that stages x and the drawn
+          # weights through LDS (two samples per pass, an odd count, one sample; rows, outputs and inputs all ragged:
+          # 36 and 20 inputs are 2.25 and 1.25 steps of 16, 4100 outputs are 64 tiles and 4 columns)
+          (1025, 36, 4100, 2), (1540, 20, 4160, 3), (1100, 52, 4097, 1), (2049, 16, 2500, 2)]
 
 
 @pytest.mark.parametrize("rows,k,o,s", SHAPES)
@@ -127,7 +131,8 @@ def test_layer_sees_the_w_of_hot_forward_rng(hot):
 
 # (rows, in, out, samples): every row-tile count, sample-chunk size and a ragged everything
 PER_SAMPLE = [(1, 8, 3, 2), (16, 128, 128, 4), (17, 36, 33, 5), (33, 100, 70, 3), (64, 128, 24, 16), (70, 64, 40, 2), (256, 192, 10, 1),
-              (257, 68, 2064, 2), (700, 40, 2100, 3)]      # the many-rows kernel with one input per sample
+              (257, 68, 2064, 2), (700, 40, 2100, 3),      # the many-rows kernel with one input per sample
+              (1030, 24, 4100, 2), (1537, 36, 3100, 3)]    # the 512-row kernel with one input per sample
 
 
 @pytest.mark.parametrize("rows,k,o,s", PER_SAMPLE)

@@ -988,6 +988,322 @@ void wgrad_go(long tiles, int waves, hipStream_t s, const LinearGradArgs &a)
     hot_linear_wgrad_kernel<SPLIT, DEEP, OB><<<dim3((unsigned)(kXcds * wgs)), dim3(64 * waves), lds, s>>>(a);
 }
 
+// ---------------------------------------------------------------------------------
+// Weight gradients for thousands of rows.  The kernel above gives a wave a tile of 16-32 outputs x 64 inputs,
+// about 10 flops per byte it loads: at thousands of rows the second-level caches cannot feed that (the matrix pipes
+// were 42 % busy).  Here a workgroup of four waves owns 128 inputs x 128 outputs and stages 16 rows of x and of dy
+// at a time through LDS (both arrive from memory with consecutive lanes on consecutive addresses, 32 flops per byte
+// loaded); a wave multiplies its 64 inputs x 64 outputs as 2 x 2 tiles of v_mfma_f32_32x32x2_f32 with x as the A
+// operand and dy as the B operand, so result registers 4 q .. 4 q + 3 of a lane are the inputs
+// 8 q + 4 (lane / 32) .. + 3 of output lane % 32: one generator quad, as above.  The two tile buffers alternate:
+// the rows of step i + 1 are requested before the matrix instructions of step i and land in the other buffer after
+// them, one barrier per step; two workgroups share a compute unit, so one's barrier is covered by the other's
+// matrix instructions.  Rows beyond the part and columns beyond the layer are masked by offsets outside the
+// range-checked windows and arrive as zeros.  A wave skips the 32 x 32 tiles that lie outside the layer
+// altogether (540 inputs are four whole tiles of 128 and 28 columns of a fifth).  The finished sums leave through
+// LDS so that every store instruction covers 128 contiguous bytes per row of the gradient arrays.
+// PARTS: workgroup (x, y) contracts over the rows of part y and leaves raw sums in the workspace, as above.
+// ---------------------------------------------------------------------------------
+constexpr int kTileRows = 16;         // rows per step
+constexpr int kTurnPitch = 36;        // floats per row of a wave's 32 x 32 block on its way out (16-byte aligned rows)
+
+// WK x WO waves (WK * WO = 4) of 64 inputs x 64 outputs each: 2 x 2 for a tile of 128 x 128, 1 x 4 for 64 inputs x
+// 256 outputs (layers whose inputs fill tiles of 128 badly: 540 inputs are 8.4 tiles of 64 but 4.2 of 128).
+// WHOLE: every 32 x 32 block of the workgroup's tile reaches into the layer (no block is skipped).
+// Vector-ALU instructions are kept out of the row loop as far as possible, since each takes its cycles from the
+// matrix instructions: the threads' offsets advance by a uniform step, rows are masked by one comparison per
+// load, and the LDS reads carry their offsets as immediates (volatile: merged into two-address reads they
+// needed a computed base register each).
+// (LDS pointers keep their address space through the call: as generic pointers they would become flat accesses)
+typedef __attribute__((address_space(3))) float lds_float;
+typedef __attribute__((address_space(3))) f4 lds_f4;
+
+template <int WK, bool PARTS, bool WHOLE>
+__device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_float *lds, long o0, long k0, long r_lo, long r_hi)
+{
+    constexpr int WO = 4 / WK, TK = 64 * WK, TO = 64 * WO;         // the tile: TK inputs x TO outputs
+    lds_float *const xt = lds, *const dt = lds + 2 * kTileRows * TK;   // [2][16][TK], [2][16][TO]
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wk = wave % WK, wo = wave / WK;
+    const long K = a.in_features, O = a.out_features, R = a.rows;
+
+    // which of this wave's 2 x 2 blocks of 32 x 32 reach into the layer (uniform over the wave): the others are skipped
+    bool ok[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) ok[i][j] = WHOLE || (k0 + 64 * wk + 32 * i < K && o0 + 64 * wo + 32 * j < O);
+    const bool bias_wave = a.mu_b != nullptr && k0 == 0 && wk == 0 && ok[0][0];      // these waves also sum dy over the rows
+
+    // as a loading thread: quads t, t + 256, .. of the 16 x TK / 4 quads of x and of the 16 x TO / 4 quads of dy;
+    // a quad outside the layer's columns gets a row number that is never below the rows left
+    int x_row[WK], d_row[WO];
+    unsigned x_first[WK], d_first[WO];
+#pragma unroll
+    for (int j = 0; j < WK; ++j) {
+        const int idx = t + 256 * j;
+        const long col = k0 + 4 * (idx % (TK / 4));
+        x_row[j] = (WHOLE || col < K) ? idx / (TK / 4) : 1 << 30;
+        x_first[j] = (unsigned)(((r_lo + idx / (TK / 4)) * a.ldx + col) * 4);
+    }
+#pragma unroll
+    for (int j = 0; j < WO; ++j) {
+        const int idx = t + 256 * j;
+        const long col = o0 + 4 * (idx % (TO / 4));
+        d_row[j] = (WHOLE || col < O) ? idx / (TO / 4) : 1 << 30;
+        d_first[j] = (unsigned)(((r_lo + idx / (TO / 4)) * O + col) * 4);
+    }
+    const unsigned x_step = (unsigned)(kTileRows * a.ldx * 4), d_step = (unsigned)(kTileRows * O * 4);
+    const int rows = (int)(r_hi - r_lo);
+
+    // Registers for one set of products and one set of sums only (two workgroups per compute unit leave a wave 256):
+    // the accumulators run on over the samples, acc = A_s = G_1 + .. + G_s after sample s, which is the sum for
+    // grad_mu at the end, and the sum for grad_sigma is built by summation by parts,
+    // sum_s G_s eps_s = sum_s A_s (eps_s - eps_{s+1}) with eps_{S+1} = 0, at the price of a second draw per sample.
+    f16v acc[2][2], gs[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int c = 0; c < 16; ++c) acc[i][j][c] = gs[i][j][c] = 0.0f;
+    float gb_m[2] = {0.0f, 0.0f}, gb_s[2] = {0.0f, 0.0f};
+
+    for (int s = 0; s < a.s_loc; ++s) {
+        const window_t x_win = window(a.x + (size_t)s * (size_t)a.x_sample_stride, (unsigned)(((R - 1) * a.ldx + K) * 4));
+        const window_t d_win = window(a.dy + (size_t)s * (size_t)R * (size_t)O, (unsigned)(R * O * 4));
+        float sb[2] = {0.0f, 0.0f};
+        unsigned x_off[WK], d_off[WO];
+#pragma unroll
+        for (int j = 0; j < WK; ++j) x_off[j] = x_first[j];
+#pragma unroll
+        for (int j = 0; j < WO; ++j) d_off[j] = d_first[j];
+
+        f4 xg[WK], dg[WO];
+        // requests the next 16 rows of both operands, of which rows_left are inside the part (possibly none)
+        auto request = [&](int rows_left) {
+#pragma unroll
+            for (int j = 0; j < WK; ++j) {
+                xg[j] = window_load4<false>(x_win, x_row[j] < rows_left ? x_off[j] : kOutside);
+                x_off[j] += x_step;
+            }
+#pragma unroll
+            for (int j = 0; j < WO; ++j) {
+                dg[j] = window_load4<false>(d_win, d_row[j] < rows_left ? d_off[j] : kOutside);
+                d_off[j] += d_step;
+            }
+        };
+        auto deposit = [&](int buf) {
+#pragma unroll
+            for (int j = 0; j < WK; ++j) *reinterpret_cast<lds_f4 *>(xt + buf * (kTileRows * TK) + 4 * (t + 256 * j)) = xg[j];
+#pragma unroll
+            for (int j = 0; j < WO; ++j) *reinterpret_cast<lds_f4 *>(dt + buf * (kTileRows * TO) + 4 * (t + 256 * j)) = dg[j];
+        };
+        auto multiply = [&](int buf) {
+            const volatile lds_float *xb = xt + buf * (kTileRows * TK) + half * TK + 64 * wk + l32;
+            const volatile lds_float *db = dt + buf * (kTileRows * TO) + half * TO + 64 * wo + l32;
+            float av[kTileRows / 2][2], bv[kTileRows / 2][2];
+#pragma unroll
+            for (int p = 0; p < kTileRows / 2; ++p)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    av[p][i] = xb[2 * p * TK + 32 * i];
+                    bv[p][i] = db[2 * p * TO + 32 * i];
+                }
+            if (bias_wave) {
+#pragma unroll
+                for (int p = 0; p < kTileRows / 2; ++p) {
+                    sb[0] += bv[p][0];
+                    sb[1] += bv[p][1];
+                }
+            }
+            if constexpr (WHOLE) {
+#pragma unroll
+                for (int p = 0; p < kTileRows / 2; ++p)
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p][i], bv[p][j], acc[i][j], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        if (ok[i][j]) {
+#pragma unroll
+                            for (int p = 0; p < kTileRows / 2; ++p)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p][i], bv[p][j], acc[i][j], 0, 0, 0);
+                        }
+            }
+        };
+
+        request(rows);
+        deposit(0);
+        __syncthreads();
+        int buf = 0;
+        for (int left = rows; left > 0; left -= kTileRows, buf ^= 1) {
+            request(left - kTileRows);          // (behind the last step every offset is outside the windows: no traffic)
+            multiply(buf);
+            if (left > kTileRows) deposit(buf ^ 1);
+            __syncthreads();
+        }
+        mfma_results_settle();
+
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                if (!ok[i][j]) continue;
+                const long o = o0 + 64 * wo + 32 * j + l32;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const long k = k0 + 64 * wk + 32 * i + 8 * q + 4 * half;
+                    if (WHOLE || (o < O && k < K)) {
+                        f4 e = eps_quad(a.weight_quad0 + ((o * K + k) >> 2), s, a.rng);
+                        if (s + 1 < a.s_loc) e -= eps_quad(a.weight_quad0 + ((o * K + k) >> 2), s + 1, a.rng);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            gs[i][j][4 * q + c] = __builtin_fmaf(acc[i][j][4 * q + c], e[c], gs[i][j][4 * q + c]);
+                    }
+                }
+            }
+        if (bias_wave) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const long o = o0 + 64 * wo + 32 * j + l32;
+                const float total = sb[j] + __shfl_xor(sb[j], 32);     // even and odd rows of the steps
+                if (o < O) {
+                    const f4 e = eps_quad(a.bias_quad0 + (o >> 2), s, a.rng);
+                    gb_m[j] += total;
+                    gb_s[j] = __builtin_fmaf(total, pick4(e, (int)(o & 3)), gb_s[j]);
+                }
+            }
+        }
+    }
+
+    // (the loop's last barrier lies behind the last reads of the operand buffers: they are free)
+    const long per = O * K + ((O + 3) & ~3L);
+    float *const part_m = PARTS ? a.ws + (size_t)blockIdx.y * 2 * (size_t)per : nullptr;
+    lds_float *const mine_m = lds + wave * (2 * 32 * kTurnPitch), *const mine_s = mine_m + 32 * kTurnPitch;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (!ok[i][j]) continue;
+            // Only this wave touches its block and the LDS executes a wave's instructions in order: program order suffices.
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f4 u, v;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    u[c] = acc[i][j][4 * q + c];
+                    v[c] = gs[i][j][4 * q + c];
+                }
+                *reinterpret_cast<lds_f4 *>(mine_m + l32 * kTurnPitch + 8 * q + 4 * half) = u;
+                *reinterpret_cast<lds_f4 *>(mine_s + l32 * kTurnPitch + 8 * q + 4 * half) = v;
+            }
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int row = 8 * it + (lane >> 3), quad = lane & 7;
+                const f4 u = *reinterpret_cast<const lds_f4 *>(mine_m + row * kTurnPitch + 4 * quad);
+                const f4 v = *reinterpret_cast<const lds_f4 *>(mine_s + row * kTurnPitch + 4 * quad);
+                const long o = o0 + 64 * wo + 32 * j + row, k = k0 + 64 * wk + 32 * i + 4 * quad;
+                if (WHOLE || (o < O && k < K)) {
+                    const long at = o * K + k;
+                    if constexpr (PARTS) {
+                        store4<true, false>(part_m + at, u);
+                        store4<true, false>(part_m + per + at, v);
+                    } else {
+                        const f4 m4 = load4<true, false>(a.mu_w + at), sd4 = load4<true, false>(a.sigma_w + at);
+                        f4 om, os;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            float p, r;
+                            finish_pair(u[c], v[c], m4[c], sd4[c], a.g, a.k, p, r);
+                            om[c] = p;
+                            os[c] = r;
+                        }
+                        store4<true, false>(a.gmu_w + at, om);
+                        store4<true, false>(a.gsig_w + at, os);
+                    }
+                }
+            }
+        }
+    if (bias_wave && half == 0) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const long o = o0 + 64 * wo + 32 * j + l32;
+            if (o < O) {
+                if constexpr (PARTS) {
+                    part_m[O * K + o] = gb_m[j];
+                    part_m[per + O * K + o] = gb_s[j];
+                } else {
+                    float p, r;
+                    finish_pair(gb_m[j], gb_s[j], a.mu_b[o], a.sigma_b[o], a.g, a.k, p, r);
+                    a.gmu_b[o] = p;
+                    a.gsig_b[o] = r;
+                }
+            }
+        }
+    }
+}
+
+template <int WK, bool PARTS>
+__global__ void __launch_bounds__(256, 2)
+hot_linear_wgrad_tile_kernel(LinearGradArgs a)
+{
+    constexpr int WO = 4 / WK, TK = 64 * WK, TO = 64 * WO;
+    constexpr int kOperandFloats = 2 * kTileRows * (TK + TO), kTurnFloats = 4 * 2 * 32 * kTurnPitch;
+    // operands: x tile [2][16][TK] then dy tile [2][16][TO]; at the end every wave turns its blocks in 2 x 32 x 36 floats
+    __shared__ __attribute__((aligned(16))) float lds[kOperandFloats > kTurnFloats ? kOperandFloats : kTurnFloats];
+    const long K = a.in_features, O = a.out_features, R = a.rows;
+    const long k_tiles = (K + TK - 1) / TK, o_tiles = (O + TO - 1) / TO;
+    const long tiles = k_tiles * o_tiles, per_xcd = (tiles + kXcds - 1) / kXcds;
+    const long xcd = blockIdx.x % kXcds, nth = blockIdx.x / kXcds;
+    const long tile = xcd * per_xcd + nth;
+    if (nth >= per_xcd || tile >= tiles) return;          // the whole workgroup
+    const bool outputs_outermost = O >= K;
+    const long o0 = (outputs_outermost ? tile / k_tiles : tile % o_tiles) * TO;
+    const long k0 = (outputs_outermost ? tile % k_tiles : tile / o_tiles) * TK;
+    const long r_lo = PARTS ? (long)blockIdx.y * a.rows_per_part : 0;
+    const long r_hi = PARTS ? (r_lo + a.rows_per_part < R ? r_lo + a.rows_per_part : R) : R;
+    // (uniform over the workgroup, so all its waves meet at the same barriers)
+    if (k0 + TK <= K && o0 + TO <= O) wgrad_tile_body<WK, PARTS, true>(a, (lds_float *)lds, o0, k0, r_lo, r_hi);
+    else wgrad_tile_body<WK, PARTS, false>(a, (lds_float *)lds, o0, k0, r_lo, r_hi);
+}
+
+// Whether the kernel above can address this problem (its windows take 32-bit byte offsets).
+inline bool wgrad_tile_fits(const hot_linear_desc *d)
+{
+    const unsigned long long lim = 0xFFFFFFF0ull;
+    if (d->out_features & 3) return false;        // rows of dy are read in 16-byte quads
+    return (unsigned long long)((d->rows + kTileRows) * d->ldx + d->in_features) * 4 < lim &&
+           (unsigned long long)(d->rows + kTileRows) * d->out_features * 4 < lim;
+}
+
+inline long wgrad_tile_count(const hot_linear_desc *d, int wk)
+{
+    const long tk = 64 * wk, to = 64 * (4 / wk);
+    return ((d->in_features + tk - 1) / tk) * ((d->out_features + to - 1) / to);
+}
+
+template <int WK>
+void wgrad_tile_go(int parts, hipStream_t s, const LinearGradArgs &a, long tiles)
+{
+    const long per_xcd = (tiles + kXcds - 1) / kXcds;
+    if (parts > 1) {
+        hot_linear_wgrad_tile_kernel<WK, true><<<dim3((unsigned)(kXcds * per_xcd), (unsigned)parts), dim3(256), 0, s>>>(a);
+        const long quads = a.out_features * a.in_features / 4;
+        const long threads = quads > a.out_features ? quads : a.out_features;
+        hot_linear_wgrad_finish_kernel<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s>>>(a, parts);
+    } else {
+        hot_linear_wgrad_tile_kernel<WK, false><<<dim3((unsigned)(kXcds * per_xcd)), dim3(256), 0, s>>>(a);
+    }
+}
+
 // A wave's finished 64-input x 16*RB-row tile of one sample's dx goes to memory.  Register rr of accumulator
 // i is input k0 + 16 j + 4 rr + i of row r0 + 16 rb + n; the lanes of a row exchange quads so that each store
 // covers 64 contiguous bytes of the row.  Every lane of the wave must call it.
@@ -1251,6 +1567,7 @@ struct WgradShape {
     long tiles, rows_per_part;
     int ob, split, parts;
     bool deep;
+    bool tile;      // the kernel with tiles of 128 x 128 instead (no parts; the other fields do not apply)
 };
 
 inline int64_t wgrad_part_bytes(const hot_linear_desc *d)
@@ -1263,6 +1580,7 @@ inline int64_t wgrad_part_bytes(const hot_linear_desc *d)
 WgradShape wgrad_shape_with(const hot_linear_desc *d, int64_t ws_bytes, bool wide_through_parts)
 {
     WgradShape w;
+    w.tile = false;
     const long k_groups = (d->in_features + 63) / 64;
     const long o_groups = (d->out_features + kColsPerWave - 1) / kColsPerWave;
     w.deep = d->rows >= kWgradDeepRows;
@@ -1302,6 +1620,20 @@ WgradShape wgrad_shape_with(const hot_linear_desc *d, int64_t ws_bytes, bool wid
 
 WgradShape wgrad_shape(const hot_linear_desc *d, int64_t ws_bytes)
 {
+    // Large layers (two tiles of 128 x 128 for every compute unit) at hundreds of rows and more: the kernel
+    // that stages both operands through LDS (1024 x 8192^2: 100 -> 113 TFLOP/s, 4096^3: 114 -> 123).  Layers
+    // with fewer tiles stay with the kernel above, whose smaller tiles and row split fill the chip better
+    // (7260 x 540 x 2160 with five row parts: 0.46 against 0.42 ms; 16640 x 192 x 768: 0.21 against 0.17 ms).
+    // Two workgroups share a compute unit, so 512 tiles make a round: a last round less than half full costs as
+    // much as a full one (2160 x 8640, 1156 tiles: 5 % behind the kernel above at every row count).
+    const long tile_count = wgrad_tile_count(d, 2), last_round = tile_count % 512;
+    if (wgrad_tile_fits(d) && d->rows >= 256 && tile_count >= 512 && (last_round == 0 || last_round >= 256 || tile_count >= 2048)) {
+        WgradShape w = wgrad_shape_with(d, 0, false);
+        w.parts = 1;
+        w.rows_per_part = 0;
+        w.tile = true;
+        return w;
+    }
     if (ws_bytes != 0 && d->rows >= 8192) {     // with parts, smaller layers afford the wide tiles too (16640 x 192 x 768: 51 -> 57 TFLOP/s)
         const WgradShape w = wgrad_shape_with(d, ws_bytes, true);
         if (w.parts > 1) return w;              // (else the workspace was too small for that)
@@ -1506,22 +1838,26 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
     const long o_groups = (d->out_features + kColsPerWave - 1) / kColsPerWave;
     if (k_groups * o_groups > 0x7fffff00L) return HOT_EINVAL;      // the grid may exceed the number of tiles by a few workgroups
     const WgradShape shape = wgrad_shape(d, workspace ? workspace_bytes : 0);
-    const long tiles = shape.tiles;
-    const int split = shape.split, ob = shape.ob;
-    const bool deep = shape.deep;
-    if (shape.parts > 1) {
-        a.ws = static_cast<float *>(workspace);
-        a.rows_per_part = shape.rows_per_part;
-        if (ob == 2) wgrad_go_parts<2>(tiles, split, shape.parts, s, a);
-        else wgrad_go_parts<1>(tiles, split, shape.parts, s, a);
-    } else if (split > 1) {
-        if (ob == 2) wgrad_go<true, true, 2>(tiles, split, s, a);
-        else if (deep) wgrad_go<true, true, 1>(tiles, split, s, a);
-        else wgrad_go<true, false, 1>(tiles, split, s, a);
+    if (shape.tile) {
+        wgrad_tile_go<2>(1, s, a, wgrad_tile_count(d, 2));
     } else {
-        if (ob == 2) wgrad_go<false, true, 2>(tiles, kWgradWaves, s, a);
-        else if (deep) wgrad_go<false, true, 1>(tiles, kWgradWaves, s, a);
-        else wgrad_go<false, false, 1>(tiles, kWgradWaves, s, a);
+        const long tiles = shape.tiles;
+        const int split = shape.split, ob = shape.ob;
+        const bool deep = shape.deep;
+        if (shape.parts > 1) {
+            a.ws = static_cast<float *>(workspace);
+            a.rows_per_part = shape.rows_per_part;
+            if (ob == 2) wgrad_go_parts<2>(tiles, split, shape.parts, s, a);
+            else wgrad_go_parts<1>(tiles, split, shape.parts, s, a);
+        } else if (split > 1) {
+            if (ob == 2) wgrad_go<true, true, 2>(tiles, split, s, a);
+            else if (deep) wgrad_go<true, true, 1>(tiles, split, s, a);
+            else wgrad_go<true, false, 1>(tiles, split, s, a);
+        } else {
+            if (ob == 2) wgrad_go<false, true, 2>(tiles, kWgradWaves, s, a);
+            else if (deep) wgrad_go<false, true, 1>(tiles, kWgradWaves, s, a);
+            else wgrad_go<false, false, 1>(tiles, kWgradWaves, s, a);
+        }
     }
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return hot_detail::note_hip(e);
     if (!dx) return HOT_OK;

@@ -696,3 +696,57 @@ def test_random_layer_shapes_forward_and_dx_against_materialised_weights(hot):
         A_g = torch.matmul(dy.double().abs().transpose(1, 2), x3.abs()).sum(0) / s + mu_w.double().abs() / 100.0
         want_g = G.sum(0) / s + mu_w.double() / 100.0
         assert bool(((gw[0].double() - want_g).abs() <= 1e-5 * A_g + 1e-30).all()), "grad_mu_w"
+
+
+# (rows, in, out, samples, per-sample x, bias)
+TILED = [(300, 2900, 4228, 2, False, True),      # 23 x 34 tiles of 128 x 128, ragged in rows, inputs and outputs
+         (272, 2048, 4096, 3, True, False)]      # 16 x 32 whole tiles, three samples with inputs of their own
+
+
+@pytest.mark.parametrize("rows,k,o,s,xs,bias", TILED)
+def test_large_layer_weight_gradients_on_sampled_outputs(oracle, hot, rows, k, o, s, xs, bias):
+    """Layers large enough for the weight-gradient kernel with tiles of 128 x 128 (at least two tiles per compute
+    unit), against the oracle on the outputs it can afford: the weight gradients of 40 outputs (all rows, all
+    inputs; the first and last output of the first, second and last tile among them) and their bias gradients.
+    Outputs do not depend on one another, so the block is the oracle's result for the sub-layer it spans."""
+    print("case linear backward, large layer", rows, k, o, s, xs, bias, flush=True)
+    c = _layer(7 * rows + k + o, rows, k, o)
+    g = np.random.default_rng(rows + o)
+    if xs:
+        c["x"] = g.normal(size=(s, rows, k)).astype(np.float32)
+    dy = (g.normal(size=(s, rows, o)) * 10 ** g.uniform(-2, 1, size=(s, 1, o))).astype(np.float32)
+    rng = hot.hot_rng(seed=31, step=2, first_sample=3)
+    w_off, b_off = 128, 128 + o * k
+    s_total, dsize = 2 * s, 45000.0
+    t = {n: torch.from_numpy(c[n]).to(DEV) for n in ("x", "mu_w", "sigma_w", "mu_b", "sigma_b")}
+    out = {"gmw": torch.full((o, k), float("nan"), device=DEV), "gsw": torch.full((o, k), float("nan"), device=DEV),
+           "gmb": torch.full((o,), float("nan"), device=DEV), "gsb": torch.full((o,), float("nan"), device=DEV)}
+    hot.hot_linear_backward_rng(rng, t["x"], torch.from_numpy(dy).to(DEV), t["mu_w"], t["sigma_w"],
+                                t["mu_b"] if bias else None, t["sigma_b"] if bias else None, out["gmw"], out["gsw"],
+                                out["gmb"] if bias else None, out["gsb"] if bias else None, None,
+                                s_total, dsize, hot.HOT_REDUCE_SUM, w_off, b_off)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out["gmw"]).all()) and bool(torch.isfinite(out["gsw"]).all())
+    ew, rw = oracle.eps_normal(o * k, s, rng.seed, rng.step, rng.first_sample, with_radius=True, col0=w_off)
+    ew, rw = ew.reshape(s, o, k), rw.reshape(s, o, k)
+    eb, rb = oracle.eps_normal(o, s, rng.seed, rng.step, rng.first_sample, with_radius=True, col0=b_off)
+    last = (o - 1) // 128 * 128
+    o_sub = np.unique(np.concatenate([[0, 31, 32, 63, 64, 127, 128, 255, last, o - 1], g.choice(o, 30, replace=False)]))
+    gg, kk = 1.0 / s_total, s / (s_total * dsize)
+    sub_b = (c["mu_b"][o_sub], c["sigma_b"][o_sub], np.ascontiguousarray(eb[:, o_sub])) if bias else (None, None, None)
+    want = oracle.linear_backward(c["x"], np.ascontiguousarray(dy[:, :, o_sub]), c["mu_w"][o_sub], c["sigma_w"][o_sub],
+                                  np.ascontiguousarray(ew[:, o_sub]), *sub_b, g=gg, k=kk, want_dx=False)
+    ax, ady = np.abs(c["x"].astype(np.float64)), np.abs(dy[:, :, o_sub].astype(np.float64))
+    Gabs = np.matmul(ady.transpose(0, 2, 1), ax)                                                 # [S, |o_sub|, K]
+    m64, s64 = np.abs(c["mu_w"][o_sub].astype(np.float64)), c["sigma_w"][o_sub].astype(np.float64)
+    checks = [("gmw", want[0], gg * Gabs.sum(0) + kk * m64), ("gsw", want[1], gg * (Gabs * rw[:, o_sub]).sum(0) + kk * (s64 + 1 / s64))]
+    if bias:
+        Gb = ady.sum(1)
+        mb, sb = np.abs(c["mu_b"][o_sub].astype(np.float64)), c["sigma_b"][o_sub].astype(np.float64)
+        checks += [("gmb", want[2], gg * Gb.sum(0) + kk * mb), ("gsb", want[3], gg * (Gb * rb[:, o_sub]).sum(0) + kk * (sb + 1 / sb))]
+    else:
+        assert np.isnan(out["gmb"].cpu().numpy()).all() and np.isnan(out["gsb"].cpu().numpy()).all()
+    for name, w64, mag in checks:
+        err = np.abs(out[name].cpu().numpy()[o_sub].astype(np.float64) - w64)
+        assert np.all(err <= 1e-5 * mag), f"{name}: worst {np.max(err / mag):.2e}"
+        print("  %s worst error / magnitude sum: %.2e" % (name, np.max(err / mag)), flush=True)

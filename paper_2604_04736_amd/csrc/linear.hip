@@ -19,9 +19,13 @@
 // Kernels of this file, by regime:
 //   forward   hot_linear_forward_kernel        up to a few hundred rows: every wave draws what it multiplies
 //             hot_linear_forward_rows_kernel   from 256 rows: four waves x 64 rows share every draw through LDS
+//             hot_linear_big_kernel            from a thousand rows: 512 rows x 64 outputs per workgroup, x and the drawn
+//                                              weights double-buffered in LDS, v_mfma_f32_32x32x2_f32
 //   backward  hot_linear_wgrad_kernel          weight and bias gradients (per-sample G never stored); variants for
 //                                              few tiles (waves split the rows), many rows (operands prefetched,
 //                                              two output groups per wave), tiles dealt out by XCD
+//             hot_linear_wgrad_tile_kernel     the same for large layers: 128 inputs x 128 outputs per workgroup, rows of
+//                                              x and dy loaded straight into LDS
 //             hot_linear_xgrad_kernel          input gradients up to a few hundred rows
 //             hot_linear_xgrad_rows_kernel     input gradients from 256 rows: shared draws, as in the forward kernel
 #include <hip/hip_runtime.h>
@@ -989,40 +993,42 @@ void wgrad_go(long tiles, int waves, hipStream_t s, const LinearGradArgs &a)
 }
 
 // ---------------------------------------------------------------------------------
-// Weight gradients for thousands of rows.  The kernel above gives a wave a tile of 16-32 outputs x 64 inputs,
-// about 10 flops per byte it loads: at thousands of rows the second-level caches cannot feed that (the matrix pipes
-// were 42 % busy).  Here a workgroup of four waves owns 128 inputs x 128 outputs and stages 16 rows of x and of dy
-// at a time through LDS (both arrive from memory with consecutive lanes on consecutive addresses, 32 flops per byte
-// loaded); a wave multiplies its 64 inputs x 64 outputs as 2 x 2 tiles of v_mfma_f32_32x32x2_f32 with x as the A
-// operand and dy as the B operand, so result registers 4 q .. 4 q + 3 of a lane are the inputs
-// 8 q + 4 (lane / 32) .. + 3 of output lane % 32: one generator quad, as above.  The two tile buffers alternate:
-// the rows of step i + 1 are requested before the matrix instructions of step i and land in the other buffer after
-// them, one barrier per step; two workgroups share a compute unit, so one's barrier is covered by the other's
-// matrix instructions.  Rows beyond the part and columns beyond the layer are masked by offsets outside the
-// range-checked windows and arrive as zeros.  A wave skips the 32 x 32 tiles that lie outside the layer
-// altogether (540 inputs are four whole tiles of 128 and 28 columns of a fifth).  The finished sums leave through
-// LDS so that every store instruction covers 128 contiguous bytes per row of the gradient arrays.
-// PARTS: workgroup (x, y) contracts over the rows of part y and leaves raw sums in the workspace, as above.
+// Weight gradients of large layers.  The kernel above gives a wave a tile of 16-32 outputs x 64 inputs, about 10
+// flops per byte it loads: at thousands of rows the second-level caches cannot feed that (the matrix pipes were 42 %
+// busy).  Here a workgroup of four waves owns 128 inputs x 128 outputs and takes 32 rows of x and of dy at a time
+// through LDS (32 flops per byte loaded).  The rows go from memory straight into LDS (buffer loads with the LDS
+// bit, 16 bytes per lane, consecutive lanes on consecutive addresses): no registers and no vector-ALU instruction
+// carry them.  A wave multiplies its 64 inputs x 64 outputs as 2 x 2 blocks of v_mfma_f32_32x32x2_f32 with x as
+// the A operand and dy as the B operand, so result registers 4 q .. 4 q + 3 of a lane are the inputs
+// 8 q + 4 (lane / 32) .. + 3 of output lane % 32: one generator quad, as above.  Two pairs of buffers alternate: the
+// rows of step i + 1 are sent for before the matrix instructions of step i, one barrier per step; two workgroups
+// share a compute unit, so one's barrier is covered by the other's matrix instructions.  Rows beyond the last
+// and columns beyond the layer are masked by offsets outside the range-checked windows and arrive as zeros; a wave
+// skips the 32 x 32 blocks that lie outside the layer altogether.  The finished sums leave through LDS so that
+// every store instruction covers 128 contiguous bytes per row of the gradient arrays.
+// Vector-ALU instructions are kept out of the row loop as far as possible, since each takes its cycles from the
+// matrix instructions: the lanes' offsets advance by a uniform step, rows are masked by one comparison per load,
+// and the LDS reads carry their offsets as immediates (volatile: merged into two-address reads they needed a
+// computed base register each).  Measured on the way: the same tile with 16-row steps staged through registers,
+// 123 TFLOP/s at 4096^3 against 134 now (the kernel above: 114, the library's GEMM alone: 146); tiles of 64 inputs
+// x 256 outputs, 2-8 % slower; row parts through a workspace for layers of fewer tiles, behind the kernel above
+// (7260 x 540 x 2160, five or six parts: 0.46-0.49 against 0.42 ms; 16640 x 192 x 768: 0.21 against 0.17 ms).
 // ---------------------------------------------------------------------------------
-constexpr int kTileRows = 16;         // rows per step
+constexpr int kTileSide = 128;        // inputs and outputs per workgroup
+constexpr int kTileRows = 32;         // rows per step
 constexpr int kTurnPitch = 36;        // floats per row of a wave's 32 x 32 block on its way out (16-byte aligned rows)
 
-// WK x WO waves (WK * WO = 4) of 64 inputs x 64 outputs each: 2 x 2 for a tile of 128 x 128, 1 x 4 for 64 inputs x
-// 256 outputs (layers whose inputs fill tiles of 128 badly: 540 inputs are 8.4 tiles of 64 but 4.2 of 128).
-// WHOLE: every 32 x 32 block of the workgroup's tile reaches into the layer (no block is skipped).
-// Vector-ALU instructions are kept out of the row loop as far as possible, since each takes its cycles from the
-// matrix instructions: the threads' offsets advance by a uniform step, rows are masked by one comparison per
-// load, and the LDS reads carry their offsets as immediates (volatile: merged into two-address reads they
-// needed a computed base register each).
 // (LDS pointers keep their address space through the call: as generic pointers they would become flat accesses)
 typedef __attribute__((address_space(3))) float lds_float;
 typedef __attribute__((address_space(3))) f4 lds_f4;
+typedef __attribute__((address_space(3))) void lds_void;
 
-template <int WK, bool PARTS, bool WHOLE>
-__device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_float *lds, long o0, long k0, long r_lo, long r_hi)
+// WHOLE: every 32 x 32 block of the workgroup's tile reaches into the layer (no block is skipped, no column masked).
+template <bool WHOLE>
+__device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_float *x0, lds_float *x1, lds_float *d0, lds_float *d1,
+                                                long o0, long k0)
 {
-    constexpr int WO = 4 / WK, TK = 64 * WK, TO = 64 * WO;         // the tile: TK inputs x TO outputs
-    lds_float *const xt = lds, *const dt = lds + 2 * kTileRows * TK;   // [2][16][TK], [2][16][TO]
+    constexpr int WK = 2, TK = kTileSide, TO = kTileSide;         // 2 x 2 waves of 64 inputs x 64 outputs
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int l32 = lane & 31, half = lane >> 5;
@@ -1037,26 +1043,29 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
         for (int j = 0; j < 2; ++j) ok[i][j] = WHOLE || (k0 + 64 * wk + 32 * i < K && o0 + 64 * wo + 32 * j < O);
     const bool bias_wave = a.mu_b != nullptr && k0 == 0 && wk == 0 && ok[0][0];      // these waves also sum dy over the rows
 
-    // as a loading thread: quads t, t + 256, .. of the 16 x TK / 4 quads of x and of the 16 x TO / 4 quads of dy;
-    // a quad outside the layer's columns gets a row number that is never below the rows left
-    int x_row[WK], d_row[WO];
-    unsigned x_first[WK], d_first[WO];
+    // As a loading wave: the tiles go from memory straight into LDS (buffer loads with the LDS bit: lane l of
+    // an instruction leaves its 16 bytes at the instruction's LDS address + 16 l, zeros for an offset outside the
+    // window), 64 consecutive quads of a tile per instruction, instruction 4 m + wave of the tile for this wave.
+    // A quad outside the layer's columns gets a row number that is never below the rows left.
+    constexpr int XI = kTileRows * TK / 4 / 256, DI = kTileRows * TO / 4 / 256;       // instructions per wave and tile
+    int x_row[XI], d_row[DI];
+    unsigned x_first[XI], d_first[DI];
 #pragma unroll
-    for (int j = 0; j < WK; ++j) {
-        const int idx = t + 256 * j;
+    for (int m = 0; m < XI; ++m) {
+        const int idx = (4 * m + wave) * 64 + lane;
         const long col = k0 + 4 * (idx % (TK / 4));
-        x_row[j] = (WHOLE || col < K) ? idx / (TK / 4) : 1 << 30;
-        x_first[j] = (unsigned)(((r_lo + idx / (TK / 4)) * a.ldx + col) * 4);
+        x_row[m] = (WHOLE || col < K) ? idx / (TK / 4) : 1 << 30;
+        x_first[m] = (unsigned)((idx / (TK / 4) * a.ldx + col) * 4);
     }
 #pragma unroll
-    for (int j = 0; j < WO; ++j) {
-        const int idx = t + 256 * j;
+    for (int m = 0; m < DI; ++m) {
+        const int idx = (4 * m + wave) * 64 + lane;
         const long col = o0 + 4 * (idx % (TO / 4));
-        d_row[j] = (WHOLE || col < O) ? idx / (TO / 4) : 1 << 30;
-        d_first[j] = (unsigned)(((r_lo + idx / (TO / 4)) * O + col) * 4);
+        d_row[m] = (WHOLE || col < O) ? idx / (TO / 4) : 1 << 30;
+        d_first[m] = (unsigned)((idx / (TO / 4) * O + col) * 4);
     }
     const unsigned x_step = (unsigned)(kTileRows * a.ldx * 4), d_step = (unsigned)(kTileRows * O * 4);
-    const int rows = (int)(r_hi - r_lo);
+    const int rows = (int)R;
 
     // Registers for one set of products and one set of sums only (two workgroups per compute unit leave a wave 256):
     // the accumulators run on over the samples, acc = A_s = G_1 + .. + G_s after sample s, which is the sum for
@@ -1075,80 +1084,91 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
         const window_t x_win = window(a.x + (size_t)s * (size_t)a.x_sample_stride, (unsigned)(((R - 1) * a.ldx + K) * 4));
         const window_t d_win = window(a.dy + (size_t)s * (size_t)R * (size_t)O, (unsigned)(R * O * 4));
         float sb[2] = {0.0f, 0.0f};
-        unsigned x_off[WK], d_off[WO];
+        unsigned x_off[XI], d_off[DI];
 #pragma unroll
-        for (int j = 0; j < WK; ++j) x_off[j] = x_first[j];
+        for (int m = 0; m < XI; ++m) x_off[m] = x_first[m];
 #pragma unroll
-        for (int j = 0; j < WO; ++j) d_off[j] = d_first[j];
+        for (int m = 0; m < DI; ++m) d_off[m] = d_first[m];
 
-        f4 xg[WK], dg[WO];
-        // requests the next 16 rows of both operands, of which rows_left are inside the part (possibly none)
-        auto request = [&](int rows_left) {
+        // requests the next 32 rows of both operands, of which rows_left exist, into one pair of buffers
+        auto request = [&](lds_float *xt, lds_float *dt, int rows_left) {
 #pragma unroll
-            for (int j = 0; j < WK; ++j) {
-                xg[j] = window_load4<false>(x_win, x_row[j] < rows_left ? x_off[j] : kOutside);
-                x_off[j] += x_step;
+            for (int m = 0; m < XI; ++m) {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(x_win, (lds_void *)(xt + (4 * m + wave) * 256), 16,
+                                                         (int)(x_row[m] < rows_left ? x_off[m] : kOutside), 0, 0, 0);
+                x_off[m] += x_step;
             }
 #pragma unroll
-            for (int j = 0; j < WO; ++j) {
-                dg[j] = window_load4<false>(d_win, d_row[j] < rows_left ? d_off[j] : kOutside);
-                d_off[j] += d_step;
+            for (int m = 0; m < DI; ++m) {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(d_win, (lds_void *)(dt + (4 * m + wave) * 256), 16,
+                                                         (int)(d_row[m] < rows_left ? d_off[m] : kOutside), 0, 0, 0);
+                d_off[m] += d_step;
             }
         };
-        auto deposit = [&](int buf) {
+        auto multiply = [&](const lds_float *xt, const lds_float *dt) {
+            const volatile lds_float *xb = xt + half * TK + 64 * wk + l32;
+            const volatile lds_float *db = dt + half * TO + 64 * wo + l32;
 #pragma unroll
-            for (int j = 0; j < WK; ++j) *reinterpret_cast<lds_f4 *>(xt + buf * (kTileRows * TK) + 4 * (t + 256 * j)) = xg[j];
+            for (int h = 0; h < 2; ++h) {                // two halves of 16 rows: 32 operand registers at a time
+                constexpr int P = kTileRows / 4;
+                float av[P][2], bv[P][2];
 #pragma unroll
-            for (int j = 0; j < WO; ++j) *reinterpret_cast<lds_f4 *>(dt + buf * (kTileRows * TO) + 4 * (t + 256 * j)) = dg[j];
-        };
-        auto multiply = [&](int buf) {
-            const volatile lds_float *xb = xt + buf * (kTileRows * TK) + half * TK + 64 * wk + l32;
-            const volatile lds_float *db = dt + buf * (kTileRows * TO) + half * TO + 64 * wo + l32;
-            float av[kTileRows / 2][2], bv[kTileRows / 2][2];
+                for (int p = 0; p < P; ++p)
 #pragma unroll
-            for (int p = 0; p < kTileRows / 2; ++p)
+                    for (int i = 0; i < 2; ++i) {
+                        av[p][i] = xb[2 * (h * P + p) * TK + 32 * i];
+                        bv[p][i] = db[2 * (h * P + p) * TO + 32 * i];
+                    }
+                if (bias_wave) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    av[p][i] = xb[2 * p * TK + 32 * i];
-                    bv[p][i] = db[2 * p * TO + 32 * i];
+                    for (int p = 0; p < P; ++p) {
+                        sb[0] += bv[p][0];
+                        sb[1] += bv[p][1];
+                    }
                 }
-            if (bias_wave) {
+                if constexpr (WHOLE) {
 #pragma unroll
-                for (int p = 0; p < kTileRows / 2; ++p) {
-                    sb[0] += bv[p][0];
-                    sb[1] += bv[p][1];
-                }
-            }
-            if constexpr (WHOLE) {
+                    for (int p = 0; p < P; ++p)
 #pragma unroll
-                for (int p = 0; p < kTileRows / 2; ++p)
+                        for (int i = 0; i < 2; ++i)
+#pragma unroll
+                            for (int j = 0; j < 2; ++j)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p][i], bv[p][j], acc[i][j], 0, 0, 0);
+                } else {
 #pragma unroll
                     for (int i = 0; i < 2; ++i)
 #pragma unroll
                         for (int j = 0; j < 2; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p][i], bv[p][j], acc[i][j], 0, 0, 0);
-            } else {
+                            if (ok[i][j]) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        if (ok[i][j]) {
-#pragma unroll
-                            for (int p = 0; p < kTileRows / 2; ++p)
-                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p][i], bv[p][j], acc[i][j], 0, 0, 0);
-                        }
+                                for (int p = 0; p < P; ++p)
+                                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p][i], bv[p][j], acc[i][j], 0, 0, 0);
+                            }
+                }
             }
         };
-
-        request(rows);
-        deposit(0);
-        __syncthreads();
-        int buf = 0;
-        for (int left = rows; left > 0; left -= kTileRows, buf ^= 1) {
-            request(left - kTileRows);          // (behind the last step every offset is outside the windows: no traffic)
-            multiply(buf);
-            if (left > kTileRows) deposit(buf ^ 1);
+        // everything this wave has sent for has arrived (also in LDS), then the workgroup's barrier
+        auto arrive = [&]() {
+            __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
+        };
+
+        // The two pairs of buffers are separate arrays and the loop names them in turn, so that the compiler
+        // can tell the loads in flight towards one pair from the reads of the other (else it waits for them
+        // ahead of the first read).
+        request(x0, d0, rows);
+        arrive();
+        for (int left = rows;;) {
+            if (left > kTileRows) request(x1, d1, left - kTileRows);
+            multiply(x0, d0);
+            arrive();
+            left -= kTileRows;
+            if (left <= 0) break;
+            if (left > kTileRows) request(x0, d0, left - kTileRows);
+            multiply(x1, d1);
+            arrive();
+            left -= kTileRows;
+            if (left <= 0) break;
         }
         mfma_results_settle();
 
@@ -1185,50 +1205,50 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
     }
 
     // (the loop's last barrier lies behind the last reads of the operand buffers: they are free)
-    const long per = O * K + ((O + 3) & ~3L);
-    float *const part_m = PARTS ? a.ws + (size_t)blockIdx.y * 2 * (size_t)per : nullptr;
-    lds_float *const mine_m = lds + wave * (2 * 32 * kTurnPitch), *const mine_s = mine_m + 32 * kTurnPitch;
+    // every wave turns its blocks in a buffer of its own: 32 x 36 floats, first the sums for grad_mu, then those for grad_sigma
+    lds_float *const mine = wave == 0 ? x0 : (wave == 1 ? x1 : (wave == 2 ? d0 : d1));
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             if (!ok[i][j]) continue;
-            // Only this wave touches its block and the LDS executes a wave's instructions in order: program order suffices.
+            // Only this wave touches its buffer and the LDS executes a wave's instructions in order: program order suffices.
+            f4 u[4], v[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                f4 u, v;
+                f4 w;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    u[c] = acc[i][j][4 * q + c];
-                    v[c] = gs[i][j][4 * q + c];
-                }
-                *reinterpret_cast<lds_f4 *>(mine_m + l32 * kTurnPitch + 8 * q + 4 * half) = u;
-                *reinterpret_cast<lds_f4 *>(mine_s + l32 * kTurnPitch + 8 * q + 4 * half) = v;
+                for (int c = 0; c < 4; ++c) w[c] = acc[i][j][4 * q + c];
+                *reinterpret_cast<lds_f4 *>(mine + l32 * kTurnPitch + 8 * q + 4 * half) = w;
             }
+#pragma unroll
+            for (int it = 0; it < 4; ++it) u[it] = *reinterpret_cast<const lds_f4 *>(mine + (8 * it + (lane >> 3)) * kTurnPitch + 4 * (lane & 7));
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f4 w;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) w[c] = gs[i][j][4 * q + c];
+                *reinterpret_cast<lds_f4 *>(mine + l32 * kTurnPitch + 8 * q + 4 * half) = w;
+            }
+#pragma unroll
+            for (int it = 0; it < 4; ++it) v[it] = *reinterpret_cast<const lds_f4 *>(mine + (8 * it + (lane >> 3)) * kTurnPitch + 4 * (lane & 7));
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 const int row = 8 * it + (lane >> 3), quad = lane & 7;
-                const f4 u = *reinterpret_cast<const lds_f4 *>(mine_m + row * kTurnPitch + 4 * quad);
-                const f4 v = *reinterpret_cast<const lds_f4 *>(mine_s + row * kTurnPitch + 4 * quad);
                 const long o = o0 + 64 * wo + 32 * j + row, k = k0 + 64 * wk + 32 * i + 4 * quad;
                 if (WHOLE || (o < O && k < K)) {
                     const long at = o * K + k;
-                    if constexpr (PARTS) {
-                        store4<true, false>(part_m + at, u);
-                        store4<true, false>(part_m + per + at, v);
-                    } else {
-                        const f4 m4 = load4<true, false>(a.mu_w + at), sd4 = load4<true, false>(a.sigma_w + at);
-                        f4 om, os;
+                    const f4 m4 = load4<true, false>(a.mu_w + at), sd4 = load4<true, false>(a.sigma_w + at);
+                    f4 om, os;
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            float p, r;
-                            finish_pair(u[c], v[c], m4[c], sd4[c], a.g, a.k, p, r);
-                            om[c] = p;
-                            os[c] = r;
-                        }
-                        store4<true, false>(a.gmu_w + at, om);
-                        store4<true, false>(a.gsig_w + at, os);
+                    for (int c = 0; c < 4; ++c) {
+                        float p, r;
+                        finish_pair(u[it][c], v[it][c], m4[c], sd4[c], a.g, a.k, p, r);
+                        om[c] = p;
+                        os[c] = r;
                     }
+                    store4<true, false>(a.gmu_w + at, om);
+                    store4<true, false>(a.gsig_w + at, os);
                 }
             }
         }
@@ -1237,42 +1257,34 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
         for (int j = 0; j < 2; ++j) {
             const long o = o0 + 64 * wo + 32 * j + l32;
             if (o < O) {
-                if constexpr (PARTS) {
-                    part_m[O * K + o] = gb_m[j];
-                    part_m[per + O * K + o] = gb_s[j];
-                } else {
-                    float p, r;
-                    finish_pair(gb_m[j], gb_s[j], a.mu_b[o], a.sigma_b[o], a.g, a.k, p, r);
-                    a.gmu_b[o] = p;
-                    a.gsig_b[o] = r;
-                }
+                float p, r;
+                finish_pair(gb_m[j], gb_s[j], a.mu_b[o], a.sigma_b[o], a.g, a.k, p, r);
+                a.gmu_b[o] = p;
+                a.gsig_b[o] = r;
             }
         }
     }
 }
 
-template <int WK, bool PARTS>
 __global__ void __launch_bounds__(256, 2)
 hot_linear_wgrad_tile_kernel(LinearGradArgs a)
 {
-    constexpr int WO = 4 / WK, TK = 64 * WK, TO = 64 * WO;
-    constexpr int kOperandFloats = 2 * kTileRows * (TK + TO), kTurnFloats = 4 * 2 * 32 * kTurnPitch;
-    // operands: x tile [2][16][TK] then dy tile [2][16][TO]; at the end every wave turns its blocks in 2 x 32 x 36 floats
-    __shared__ __attribute__((aligned(16))) float lds[kOperandFloats > kTurnFloats ? kOperandFloats : kTurnFloats];
-    const long K = a.in_features, O = a.out_features, R = a.rows;
+    constexpr int TK = kTileSide, TO = kTileSide;
+    // two pairs of operand buffers, [32][128] of x and of dy each; at the end every wave turns its blocks in one of them
+    __shared__ __attribute__((aligned(16))) float x0[kTileRows * TK], x1[kTileRows * TK], d0[kTileRows * TO], d1[kTileRows * TO];
+    static_assert(kTileRows * TK >= 32 * kTurnPitch && kTileRows * TO >= 32 * kTurnPitch, "a wave's block fits in any of the buffers");
+    const long K = a.in_features, O = a.out_features;
     const long k_tiles = (K + TK - 1) / TK, o_tiles = (O + TO - 1) / TO;
     const long tiles = k_tiles * o_tiles, per_xcd = (tiles + kXcds - 1) / kXcds;
-    const long xcd = blockIdx.x % kXcds, nth = blockIdx.x / kXcds;
+    const long xcd = blockIdx.x % kXcds, nth = blockIdx.x / kXcds;      // the tiles are dealt out by XCD as above
     const long tile = xcd * per_xcd + nth;
     if (nth >= per_xcd || tile >= tiles) return;          // the whole workgroup
     const bool outputs_outermost = O >= K;
     const long o0 = (outputs_outermost ? tile / k_tiles : tile % o_tiles) * TO;
     const long k0 = (outputs_outermost ? tile % k_tiles : tile / o_tiles) * TK;
-    const long r_lo = PARTS ? (long)blockIdx.y * a.rows_per_part : 0;
-    const long r_hi = PARTS ? (r_lo + a.rows_per_part < R ? r_lo + a.rows_per_part : R) : R;
     // (uniform over the workgroup, so all its waves meet at the same barriers)
-    if (k0 + TK <= K && o0 + TO <= O) wgrad_tile_body<WK, PARTS, true>(a, (lds_float *)lds, o0, k0, r_lo, r_hi);
-    else wgrad_tile_body<WK, PARTS, false>(a, (lds_float *)lds, o0, k0, r_lo, r_hi);
+    if (k0 + TK <= K && o0 + TO <= O) wgrad_tile_body<true>(a, (lds_float *)x0, (lds_float *)x1, (lds_float *)d0, (lds_float *)d1, o0, k0);
+    else wgrad_tile_body<false>(a, (lds_float *)x0, (lds_float *)x1, (lds_float *)d0, (lds_float *)d1, o0, k0);
 }
 
 // Whether the kernel above can address this problem (its windows take 32-bit byte offsets).
@@ -1284,24 +1296,15 @@ inline bool wgrad_tile_fits(const hot_linear_desc *d)
            (unsigned long long)(d->rows + kTileRows) * d->out_features * 4 < lim;
 }
 
-inline long wgrad_tile_count(const hot_linear_desc *d, int wk)
+inline long wgrad_tile_count(const hot_linear_desc *d)
 {
-    const long tk = 64 * wk, to = 64 * (4 / wk);
-    return ((d->in_features + tk - 1) / tk) * ((d->out_features + to - 1) / to);
+    return ((d->in_features + kTileSide - 1) / kTileSide) * ((d->out_features + kTileSide - 1) / kTileSide);
 }
 
-template <int WK>
-void wgrad_tile_go(int parts, hipStream_t s, const LinearGradArgs &a, long tiles)
+void wgrad_tile_go(hipStream_t s, const LinearGradArgs &a, long tiles)
 {
     const long per_xcd = (tiles + kXcds - 1) / kXcds;
-    if (parts > 1) {
-        hot_linear_wgrad_tile_kernel<WK, true><<<dim3((unsigned)(kXcds * per_xcd), (unsigned)parts), dim3(256), 0, s>>>(a);
-        const long quads = a.out_features * a.in_features / 4;
-        const long threads = quads > a.out_features ? quads : a.out_features;
-        hot_linear_wgrad_finish_kernel<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s>>>(a, parts);
-    } else {
-        hot_linear_wgrad_tile_kernel<WK, false><<<dim3((unsigned)(kXcds * per_xcd)), dim3(256), 0, s>>>(a);
-    }
+    hot_linear_wgrad_tile_kernel<<<dim3((unsigned)(kXcds * per_xcd)), dim3(256), 0, s>>>(a);
 }
 
 // A wave's finished 64-input x 16*RB-row tile of one sample's dx goes to memory.  Register rr of accumulator
@@ -1620,14 +1623,16 @@ WgradShape wgrad_shape_with(const hot_linear_desc *d, int64_t ws_bytes, bool wid
 
 WgradShape wgrad_shape(const hot_linear_desc *d, int64_t ws_bytes)
 {
-    // Large layers (two tiles of 128 x 128 for every compute unit) at hundreds of rows and more: the kernel
-    // that stages both operands through LDS (1024 x 8192^2: 100 -> 113 TFLOP/s, 4096^3: 114 -> 123).  Layers
-    // with fewer tiles stay with the kernel above, whose smaller tiles and row split fill the chip better
-    // (7260 x 540 x 2160 with five row parts: 0.46 against 0.42 ms; 16640 x 192 x 768: 0.21 against 0.17 ms).
-    // Two workgroups share a compute unit, so 512 tiles make a round: a last round less than half full costs as
-    // much as a full one (2160 x 8640, 1156 tiles: 5 % behind the kernel above at every row count).
-    const long tile_count = wgrad_tile_count(d, 2), last_round = tile_count % 512;
-    if (wgrad_tile_fits(d) && d->rows >= 256 && tile_count >= 512 && (last_round == 0 || last_round >= 256 || tile_count >= 2048)) {
+    // Large layers at hundreds of rows and more: the kernel with tiles of 128 x 128 (1024 x 8192^2: 100 -> 120
+    // TFLOP/s, 4096^3: 114 -> 134).  Two workgroups share a compute unit, so 512 tiles make a round, and a last
+    // round less than half full costs as much as a full one (2160 x 8640, 1156 tiles: level with the kernel above
+    // at every row count, which keeps it); one tile per compute unit pays from a thousand rows on (2048^2: 86 ->
+    // 100 TFLOP/s).  Layers with fewer tiles stay with the kernel above, whose smaller tiles and row split fill the
+    // chip better.
+    const long tile_count = wgrad_tile_count(d), last_round = tile_count % 512;
+    const bool fills = tile_count >= 512 ? (last_round == 0 || last_round >= 256 || tile_count >= 2048)
+                                         : (tile_count > 230 && tile_count <= 256 && d->rows >= 1024);
+    if (wgrad_tile_fits(d) && d->rows >= 256 && fills) {
         WgradShape w = wgrad_shape_with(d, 0, false);
         w.parts = 1;
         w.rows_per_part = 0;
@@ -1839,7 +1844,7 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
     if (k_groups * o_groups > 0x7fffff00L) return HOT_EINVAL;      // the grid may exceed the number of tiles by a few workgroups
     const WgradShape shape = wgrad_shape(d, workspace ? workspace_bytes : 0);
     if (shape.tile) {
-        wgrad_tile_go<2>(1, s, a, wgrad_tile_count(d, 2));
+        wgrad_tile_go(s, a, wgrad_tile_count(d));
     } else {
         const long tiles = shape.tiles;
         const int split = shape.split, ob = shape.ob;

@@ -220,12 +220,15 @@ int hot_last_hip_error(const hot_plan *plan);
  * row-major; mu_b, sigma_b: [out_features] or both NULL; y: [s_local, rows, out_features]
  * packed, out.  All DEVICE pointers; x, mu_W, sigma_W 16-byte aligned; in_features, ldx,
  * weight_offset, bias_offset multiples of 4.  The contraction runs on the matrix cores in
- * fp32 (v_mfma_f32_16x16x4_f32).  Runs on the current device, asynchronous on `stream`.
+ * fp32 (v_mfma_f32_16x16x4_f32, v_mfma_f32_32x32x2_f32).  Runs on the current device, asynchronous on `stream`.
  * Up to a few hundred rows a wave draws the weights it multiplies (re-drawing eps per block of 64
  * rows is then cheaper than writing and re-reading w); from 256 rows on, given at least 128 workgroups
- * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS (70-93 TFLOP/s,
- * half of the fp32 matrix peak, with a shared x and with one x per sample alike).  For thousands of rows writing w once with hot_forward_rng and calling
- * a library GEMM is still 1.2-1.6x faster: the draw and the matrix instructions do not overlap here.
+ * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS; from 1024 rows on,
+ * given at least 192 workgroups of 512 rows x 64 outputs, eight waves share it and x is staged through LDS
+ * too (92-115 TFLOP/s, up to 73 % of the fp32 matrix peak).  The draw and the matrix instructions do not
+ * overlap on this chip; against writing w once with hot_forward_rng and calling a library GEMM the call is
+ * 1.8-2.9x faster up to tens of rows, level at 64 rows and at a Swin layer's 7260 rows, and 0.8x on the
+ * largest squares.
  */
 typedef struct hot_linear_desc {
     int64_t rows;          /* R >= 1: rows of x (batch x tokens) */
@@ -261,9 +264,12 @@ int hot_linear_forward_rng(const hot_linear_desc *desc, const hot_rng *rng, cons
  * 1 048 560 and s_local <= 65 535 (grid limits; HOT_EINVAL beyond, before anything runs).  Other arguments
  * and rules as for hot_linear_forward_rng.  Every weight is drawn once per sample (and per wave that
  * shares its tile) for the weight gradients, and for dx once per block of 64 rows, or, from 256 rows
- * on, once per workgroup of up to 256 rows (its waves share the draws through LDS).  Against library
- * GEMMs for dx and G followed by hot_backward_rng the call is 1-3x faster up to tens of rows and at
- * 0.7-1.25x for thousands of rows (75-98 TFLOP/s per kernel).
+ * on, once per workgroup of 64 to 256 rows (its waves share the draws through LDS).  Large layers
+ * (from 256 rows on, at least two tiles of 128 inputs x 128 outputs per compute unit) take their weight
+ * gradients from a kernel that stages x and dy through LDS (up to 134 TFLOP/s); it needs out_features to
+ * be a multiple of 4 and rows * max(ldx, out_features) * 4 below 4 GiB, else the first kernel runs.  Against
+ * library GEMMs for dx and G followed by hot_backward_rng the call is 1.1-3x faster up to tens of rows and at
+ * 0.8-1.1x for thousands of rows.
  */
 int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double dataset_size, uint32_t flags,
                             const hot_rng *rng, const float *x, const float *dy, const float *mu_w,

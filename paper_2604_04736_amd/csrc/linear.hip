@@ -1708,7 +1708,9 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
         const long gx = (d->out_features + kBigOuts - 1) / kBigOuts, gy = (d->rows + kBigRows - 1) / kBigRows;
         // (measured against the 256-row kernel below: 96 against 78 TFLOP/s at 7260 x 540 x 2160, 112-115 against 93-95
         // at 1024 x 8192^2 and 4096^3 with a shared x, 100 against 95 with one x per sample; with fewer workgroups than
-        // three quarters of the compute units it loses)
+        // three quarters of the compute units it loses; 32 outputs per workgroup, for layers whose 64-output workgroups
+        // are too few, were measured at 7260 x 2160 x 540 with one input per sample, 255 workgroups instead of 135: 0.55
+        // against 0.41 ms for the 256-row kernel, every workgroup still loading its full 512 x 16 tile of x per step)
         const bool want = d->rows >= 1024 && gx * gy >= 192;
         if (want && big_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) {
             BigArgs b;

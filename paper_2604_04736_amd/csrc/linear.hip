@@ -61,6 +61,38 @@ __device__ __forceinline__ void mfma_results_settle()
     __builtin_amdgcn_sched_barrier(0);
 }
 
+// So that no read of a result can be written without those wait states: the accumulator registers of the
+// matrix instructions are private to MfmaAcc, which hands them out only against an MfmaSettled, and constructing
+// one of those issues the wait states.  Construct it behind the last mac() of a run; one serves all accumulators.
+struct MfmaSettled {
+    __device__ __forceinline__ MfmaSettled() { mfma_results_settle(); }
+    MfmaSettled(const MfmaSettled &) = delete;
+    MfmaSettled &operator=(const MfmaSettled &) = delete;
+};
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+template <class V, int N>
+class MfmaAcc {
+    V v_;
+
+public:
+    __device__ __forceinline__ MfmaAcc()
+    {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v_[i] = 0.0f;
+    }
+    // v += a (x) b over the instruction's contraction block
+    __device__ __forceinline__ void mac(float a, float b)
+    {
+        if constexpr (N == 4) v_ = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, v_, 0, 0, 0);
+        else v_ = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, v_, 0, 0, 0);
+    }
+    __device__ __forceinline__ V read(const MfmaSettled &) const { return v_; }
+};
+typedef MfmaAcc<f4, 4> Acc16x16;        // v_mfma_f32_16x16x4_f32: four result registers per lane
+typedef MfmaAcc<f16v, 16> Acc32x32;     // v_mfma_f32_32x32x2_f32: sixteen
+
 __device__ __forceinline__ float pick4_of(f4 v, int c) { return c == 0 ? v[0] : (c == 1 ? v[1] : (c == 2 ? v[2] : v[3])); }
 
 struct LinearArgs {
@@ -94,11 +126,7 @@ hot_linear_forward_kernel(LinearArgs a)
     const long quad_row = a.weight_quad0 + ((o_ok ? o : 0) * K >> 2);
 
     for (int s0 = 0; s0 < a.s_loc; s0 += ST) {
-        f4 acc[ST][RB];
-#pragma unroll
-        for (int st = 0; st < ST; ++st)
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) acc[st][rb] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+        Acc16x16 mm[ST][RB];
 
         for (long kb = (long)wave * kInputsPerIter; kb < K; kb += (long)waves * kInputsPerIter) {
             const long k = kb + 8 * j;
@@ -148,11 +176,16 @@ hot_linear_forward_kernel(LinearArgs a)
                         for (int c = 0; c < 4; ++c)
 #pragma unroll
                             for (int rb = 0; rb < RB; ++rb)
-                                acc[st][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[rb][h][c], w4[h][c], acc[st][rb], 0, 0, 0);
+                                mm[st][rb].mac(xa[rb][h][c], w4[h][c]);
                 }
             }
         }
-        mfma_results_settle();
+        const MfmaSettled settled;
+        f4 acc[ST][RB];
+#pragma unroll
+        for (int st = 0; st < ST; ++st)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) acc[st][rb] = mm[st][rb].read(settled);
 
         if (waves > 1) {
             __syncthreads();            // the previous chunk's readers are done with the buffer
@@ -245,13 +278,7 @@ hot_linear_forward_rows_kernel(LinearArgs a)
     const int dn = (int)threadIdx.x >> 4, dq = (int)threadIdx.x & 15;
 
     for (int s0 = 0; s0 < a.s_loc; s0 += ST) {
-        f4 acc[ST][4][NO];
-#pragma unroll
-        for (int st = 0; st < ST; ++st)
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-                for (int no = 0; no < NO; ++no) acc[st][rb][no] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+        Acc16x16 mm[ST][4][NO];
 
         int buf = 0;
         for (long kb = 0; kb < K; kb += kRowsKernelInputs, buf ^= 1) {
@@ -330,12 +357,19 @@ hot_linear_forward_rows_kernel(LinearArgs a)
                                 for (int c = 0; c < 4; ++c)
 #pragma unroll
                                     for (int rb = 0; rb < 4; ++rb)
-                                        acc[st][rb][no] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[rb][blk][h][c], wq[c], acc[st][rb][no], 0, 0, 0);
+                                        mm[st][rb][no].mac(xa[rb][blk][h][c], wq[c]);
                             }
                 }
             }
         }
-        mfma_results_settle();
+        const MfmaSettled settled;
+        f4 acc[ST][4][NO];
+#pragma unroll
+        for (int st = 0; st < ST; ++st)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                for (int no = 0; no < NO; ++no) acc[st][rb][no] = mm[st][rb][no].read(settled);
         __syncthreads();        // the chunk's last reads are done before the next chunk's first draw lands in buffer 0
 
 #pragma unroll
@@ -390,8 +424,6 @@ constexpr int kBigK = 16;                    // inputs per step
 constexpr int kBigPitch = kBigK + 4;         // floats per row of the LDS tiles (80 bytes: eight lanes' 16-byte reads cover all banks)
 constexpr unsigned kOutside = 0xFFFFFFF0u;   // a byte offset beyond any window
 
-typedef float f16v __attribute__((ext_vector_type(16)));
-
 // What the kernel below works on: out_s[row][n] = sum_c in_s[row][c] W_s[n][c] + bias_s[n] with W_s drawn: in = x
 // (one for all samples, or one per sample), c runs over the layer's inputs, n over its outputs, weight (n, c) has flat
 // index n * C + c (the generator's quads run along c).  (The input gradients, dx = dy W, were run through the same kernel
@@ -433,15 +465,7 @@ hot_linear_big_kernel(BigArgs a)
 
     for (int s0 = 0; s0 < a.s_loc; s0 += ST) {
         const window_t in_win = window(OWN ? a.in + (size_t)s0 * (size_t)a.in_sample_stride : a.in, in_bytes);
-        f16v acc[ST][2][2];
-#pragma unroll
-        for (int st = 0; st < ST; ++st)
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[st][rb][cb][i] = 0.0f;
+        Acc32x32 mm[ST][2][2];
 
         f4 xg[4], m4, sd4;
         // flat index of the first weight of this thread's quad in the step that starts at contraction index cb0, or -1
@@ -505,13 +529,20 @@ hot_linear_big_kernel(BigArgs a)
                         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                             for (int cb = 0; cb < 2; ++cb)
-                                acc[st][rb][cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[rb][i], wb[cb][i], acc[st][rb][cb], 0, 0, 0);
+                                mm[st][rb][cb].mac(xa[rb][i], wb[cb][i]);
                 }
             }
             if (cb0 + kBigK < C) deposit(cb0 + kBigK, buf ^ 1);      // uniform over the workgroup
             __syncthreads();
         }
-        mfma_results_settle();
+        const MfmaSettled settled;
+        f16v acc[ST][2][2];
+#pragma unroll
+        for (int st = 0; st < ST; ++st)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) acc[st][rb][cb] = mm[st][rb][cb].read(settled);
 
         // result register i of a 32 x 32 tile: row 8 (i / 4) + 4 (lane / 32) + i % 4, column lane % 32
 #pragma unroll
@@ -711,13 +742,7 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
         // matrix instruction i of a row block takes element i of every lane's four inputs, so P[.][i] collects
         // the inputs k0 + 4 m + i (m = 0..15) and register c of P[.][i] is input k0 + 16 j + 4 c + i: the four
         // P[.][.][c] are the four consecutive inputs of one generator quad
-        f4 P[OB][4], Pb[OB];
-#pragma unroll
-        for (int b = 0; b < OB; ++b) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) P[b][i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-            Pb[b] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-        }
+        Acc16x16 mm[OB][4], mm_b[OB];
         // Whole blocks of 16 rows first, with nothing in the loop but the loads, the offset increments and the
         // matrix instructions: lanes outside the layer (o >= O, inputs >= K) read a valid address instead, which
         // only reaches rows and columns of P that are never stored.  The last, partial block is predicated per
@@ -739,12 +764,12 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
                 for (int b = 0; b < OB; ++b)
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        P[b][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q][i], bv[b][q], P[b][i], 0, 0, 0);
+                        mm[b][i].mac(av[q][i], bv[b][q]);
             if (bias_tile) {             // column sums of dy: the same contraction against ones
 #pragma unroll
                 for (int q = 0; q < Q; ++q)
 #pragma unroll
-                    for (int b = 0; b < OB; ++b) Pb[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, bv[b][q], Pb[b], 0, 0, 0);
+                    for (int b = 0; b < OB; ++b) mm_b[b].mac(1.0f, bv[b][q]);
             }
         };
         if constexpr (DEEP) {
@@ -818,7 +843,14 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
             }
             multiply(bv, av);
         }
-        mfma_results_settle();
+        const MfmaSettled settled;
+        f4 P[OB][4], Pb[OB];
+#pragma unroll
+        for (int b = 0; b < OB; ++b) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) P[b][i] = mm[b][i].read(settled);
+            Pb[b] = mm_b[b].read(settled);
+        }
         if (row_first < r_hi) {          // a wave without rows has nothing to add (uniform over the wave)
 #pragma unroll
             for (int b = 0; b < OB; ++b) {
@@ -1071,7 +1103,8 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
     // the accumulators run on over the samples, acc = A_s = G_1 + .. + G_s after sample s, which is the sum for
     // grad_mu at the end, and the sum for grad_sigma is built by summation by parts,
     // sum_s G_s eps_s = sum_s A_s (eps_s - eps_{s+1}) with eps_{S+1} = 0, at the price of a second draw per sample.
-    f16v acc[2][2], gs[2][2];
+    Acc32x32 mm[2][2];
+    f16v acc[2][2], gs[2][2];       // acc: the accumulators as read behind the last sample's matrix instructions
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -1133,7 +1166,7 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
                         for (int i = 0; i < 2; ++i)
 #pragma unroll
                             for (int j = 0; j < 2; ++j)
-                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p][i], bv[p][j], acc[i][j], 0, 0, 0);
+                                mm[i][j].mac(av[p][i], bv[p][j]);
                 } else {
 #pragma unroll
                     for (int i = 0; i < 2; ++i)
@@ -1142,7 +1175,7 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
                             if (ok[i][j]) {
 #pragma unroll
                                 for (int p = 0; p < P; ++p)
-                                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p][i], bv[p][j], acc[i][j], 0, 0, 0);
+                                    mm[i][j].mac(av[p][i], bv[p][j]);
                             }
                 }
             }
@@ -1170,7 +1203,11 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
             left -= kTileRows;
             if (left <= 0) break;
         }
-        mfma_results_settle();
+        const MfmaSettled settled;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = mm[i][j].read(settled);
 
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -1348,11 +1385,7 @@ hot_linear_xgrad_kernel(LinearGradArgs a)
     const long kq = k0 + 4 * n;          // this lane's quad of inputs (as an A lane)
     const bool k_ok = kq < K;
 
-    f4 acc[RB][4];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[rb][i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    Acc16x16 mm[RB][4];
 
     // dy is read as quads of four consecutive outputs (lane (n, j): outputs ob + 4 j .. + 3 of row n; dword
     // alignment suffices), and matrix instruction (c, i) takes element c of them against element i of the
@@ -1396,10 +1429,15 @@ hot_linear_xgrad_kernel(LinearGradArgs a)
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
-                    acc[rb][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(w4[i], dyq[rb][c], acc[rb][i], 0, 0, 0);
+                    mm[rb][i].mac(w4[i], dyq[rb][c]);
         }
     }
-    mfma_results_settle();
+    const MfmaSettled settled;
+    f4 acc[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[rb][i] = mm[rb][i].read(settled);
 
     if (waves > 1) {
         if (wave > 0) {
@@ -1465,11 +1503,7 @@ hot_linear_xgrad_rows_kernel(LinearGradArgs a)
     const long kq = k0 + 4 * n;          // this lane's quad of inputs (as a drawing thread and as an A lane)
     const bool k_ok = kq < K;
 
-    f4 acc[RB][4];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[rb][i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    Acc16x16 mm[RB][4];
     // rows beyond R read row R - 1 instead: they only reach columns of the accumulators that are never stored
     long at[RB];
 #pragma unroll
@@ -1508,10 +1542,15 @@ hot_linear_xgrad_rows_kernel(LinearGradArgs a)
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
-                    acc[rb][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(wq[i], dyq[rb][c], acc[rb][i], 0, 0, 0);
+                    mm[rb][i].mac(wq[i], dyq[rb][c]);
         }
     }
-    mfma_results_settle();
+    const MfmaSettled settled;
+    f4 acc[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[rb][i] = mm[rb][i].read(settled);
 
     float *dst = a.x_parts > 1 ? a.ws + (size_t)part * (size_t)a.s_loc * (size_t)R * (size_t)K : a.dx;
     store_dx_tile<RB>(acc, dst, s, r0, k0, j, n, a);

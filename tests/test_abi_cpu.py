@@ -195,4 +195,20 @@ def test_device_code_has_no_packed_instructions(tmp_path):
             if "v_mfma" in m.group(2):
                 kernels += 1
                 assert "s_nop 15" in m.group(2), m.group(1)
-    assert kernels >= 10        # the instantiations of the five kernels of the linear layer
+    assert kernels >= 10        # the instantiations of the kernels of the linear layer
+
+    # ... and no kernel can read a result without them: the matrix builtins occur only inside MfmaAcc, whose
+    # registers are private and handed out against an MfmaSettled alone, and only MfmaSettled's constructor
+    # issues the wait states (so a read needs one constructed, i.e. the wait states issued).
+    for src in build.SRCS:
+        code = re.sub(r"//[^\n]*", "", open(src).read())
+        calls = len(re.findall(r"__builtin_amdgcn_mfma_", code))
+        if os.path.basename(src) != "linear.hip":
+            assert calls == 0, src
+            continue
+        cls = re.search(r"class MfmaAcc \{(.*?)\n\};", code, re.S).group(1)
+        assert calls == len(re.findall(r"__builtin_amdgcn_mfma_", cls)) == 2
+        assert re.search(r"\n    V v_;\n\npublic:", "\n" + cls) and "read(const MfmaSettled &) const { return v_; }" in cls
+        assert len(re.findall(r"mfma_results_settle\(\)", code)) == 2      # its definition and MfmaSettled's constructor
+        assert "MfmaSettled() { mfma_results_settle(); }" in code
+        assert len(re.findall(r"const MfmaSettled settled;", code)) >= 7     # one per kernel

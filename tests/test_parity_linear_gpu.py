@@ -700,7 +700,9 @@ def test_random_layer_shapes_forward_and_dx_against_materialised_weights(hot):
 
 # (rows, in, out, samples, per-sample x, bias)
 TILED = [(300, 2900, 4228, 2, False, True),      # 23 x 34 tiles of 128 x 128, ragged in rows, inputs and outputs
-         (272, 2048, 4096, 3, True, False)]      # 16 x 32 whole tiles, three samples with inputs of their own
+         (272, 2048, 4096, 3, True, False),      # 16 x 32 whole tiles, three samples with inputs of their own
+         (257, 3000, 4092, 1, False, True),      # 24 x 32 tiles, both edges ragged, a single sample, an odd number of steps
+         (1030, 2048, 2000, 2, False, True)]     # one tile per compute unit, from a thousand rows on
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias", TILED)

@@ -649,6 +649,9 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
         dx = torch.empty(s, rows, k, device=dev)
         ms_b = timeit(lambda: hot.hot_linear_backward_rng(rng, x, dy, mu, sg, mb, sb, gmw, gsw, gmb, gsb, dx, s, 45000.0,
                                                           hot.HOT_REDUCE_SUM, 0, o * k))
+        # the two halves of the call: weight and bias gradients alone (dx = NULL); the input gradients are the rest
+        ms_wg = timeit(lambda: hot.hot_linear_backward_rng(rng, x, dy, mu, sg, mb, sb, gmw, gsw, gmb, gsb, None, s, 45000.0,
+                                                           hot.HOT_REDUCE_SUM, 0, o * k))
         ws_bytes = hot.hot_linear_backward_workspace_bytes(rows, k, o, s)
         ms_bw = None
         if ws_bytes > 0:        # few tiles, many rows: the rows go to several workgroups through a workspace
@@ -668,10 +671,15 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
             hot.hot_backward_rng(plan_b, rng, flat_mu, flat_sg, G, gf, gs2)
 
         ms_bu = timeit(unfused_backward)
+        ms_lib_g = timeit(lambda: torch.matmul(dy.transpose(1, 2), x_all, out=G.as_strided((s, o, k), (n, k, 1))))
+        ms_lib_dx = timeit(lambda: torch.matmul(dy, w.as_strided((s, o, k), (n, k, 1)), out=dx2))
         hot.hot_destroy(plan_b)
         gscale = G[:, :o * k].abs().sum(0).max().item() / s + 1e-6
         bwd = {"fused_ms": ms_b, "weight_samples_per_s": s * o * k / (ms_b * 1e-3),
                "fused_with_workspace_ms": ms_bw, "workspace_bytes": ws_bytes,
+               "weight_gradients_ms": ms_wg, "weight_gradients_TFLOPs": 2.0 * s * rows * k * o / ms_wg / 1e9,
+               "input_gradients_ms": ms_b - ms_wg, "input_gradients_TFLOPs": 2.0 * s * rows * k * o / max(ms_b - ms_wg, 1e-6) / 1e9,
+               "library_gemm_for_G_ms": ms_lib_g, "library_gemm_for_dx_ms": ms_lib_dx,
                "library_gemms_plus_hot_backward_ms": ms_bu, "speedup": ms_bu / ms_b,
                "speedup_with_workspace": ms_bu / ms_bw if ms_bw else None,
                "agrees": bool((gmw.view(-1) - gf[:o * k]).abs().max().item() <= 1e-5 * gscale

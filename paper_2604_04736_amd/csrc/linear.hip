@@ -19,8 +19,9 @@
 // Kernels of this file, by regime:
 //   forward   hot_linear_forward_kernel        up to a few hundred rows: every wave draws what it multiplies
 //             hot_linear_forward_rows_kernel   from 256 rows: four waves x 64 rows share every draw through LDS
-//             hot_linear_big_kernel            from a thousand rows: 512 rows x 64 outputs per workgroup, x and the drawn
-//                                              weights double-buffered in LDS, v_mfma_f32_32x32x2_f32
+//             hot_linear_slab_kernel           from 512 rows on layers that fill the chip: 512 rows x 32 to 128 outputs per
+//                                              workgroup, x loaded straight into LDS, the drawn weights shared through it,
+//                                              v_mfma_f32_32x32x2_f32; also the input gradients of such layers
 //   backward  hot_linear_wgrad_kernel          weight and bias gradients (per-sample G never stored); variants for
 //                                              few tiles (waves split the rows), many rows (operands prefetched,
 //                                              two output groups per wave), tiles dealt out by XCD
@@ -404,180 +405,292 @@ hot_linear_forward_rows_kernel(LinearArgs a)
 // side by side (the fp32 matrix rate equals the packed fp32 vector rate: the same multipliers serve both; measured
 // with the two kinds of work in different waves of one SIMD, the times add), so every cycle spent drawing is lost to
 // the contraction, and the share of the draw is 81 / (rows per workgroup): a third at 256 rows.  Here a workgroup
-// of eight waves owns 512 rows x 64 outputs; per step of 16 inputs each thread draws at most ONE quad of the
-// 64 x 16 weight tile (two samples: thread t draws sample t / 256), and x is staged through LDS as well, loaded
-// from memory with consecutive lanes on consecutive addresses.  Both tiles are double-buffered: while the matrix
-// instructions of step i run from one buffer, the operands of step i + 1 are on their way from memory (requested
-// before the matrix instructions, consumed after them), are drawn, and go into the other buffer; one barrier per
-// step.  The matrix instruction is v_mfma_f32_32x32x2_f32: a wave multiplies its 64 rows by all 64 outputs as 2 x 2
-// tiles of 32 x 32, and one 16-byte LDS read per operand tile feeds four instructions (lanes 0-31 hold inputs
-// k .. k + 3 of their row or output, lanes 32-63 inputs k + 4 .. k + 7; instruction i takes element i of both
-// operands, so the contraction index is enumerated in another order, identically on both sides).
-// All global accesses go through range-checked windows (see vec.h): rows beyond R, outputs beyond O and inputs
-// beyond K are masked by offsets outside the window, without branches, so the loads of the next step stay in
-// flight across the matrix instructions.
+// of eight waves owns 512 rows (64 per wave) x 64 or 128 outputs; per step of 16 contraction indices a thread draws at
+// most ONE quad of the weight tile (two samples per pass: thread t draws sample t / 256).
+// x never passes through registers: each wave sends for the 16 inputs of its own 64 rows with buffer loads that write
+// straight into LDS (lane l of an instruction leaves its 16 bytes at the instruction's LDS address + 16 l, zeros for an
+// offset outside the window), into a region that only this wave reads, so x needs no barrier at all.  Rows are 64 bytes
+// there without padding; so that the operand reads (lane = row, 16 bytes at a fixed input) still spread over all banks,
+// the quad q of row r sits at position q ^ swizzle(r) of its row, which the loading lanes arrange by choosing which
+// quad of memory they fetch.  The drawn weight tile is shared by the waves and laid out the same way.
+// One barrier per step, in its middle.  A step on tile i (buffers i % 2):
+//     read the operands of the second half (inputs 8 .. 15) of tile i;  matrix instructions of the first half, whose
+//     operands are in registers already;  wait for everything sent for a step ago, barrier (every wave has now read
+//     tile i, and tile i + 1 is complete);  draw tile i + 2 into the weight buffer just freed, send for mu, sigma of
+//     tile i + 3 (registers) and for x of tile i + 2 (the x region just freed);  matrix instructions of the second half,
+//     with the reads of the first-half operands of tile i + 1 issued ahead of their last quarter.
+// Behind the barrier nothing waits for LDS or memory: loads have a whole step of matrix instructions to arrive, and
+// the first matrix instruction behind it has its operands.  (The kernel this replaces kept both tiles in padded
+// LDS arrays filled through registers and met at a barrier at the end of every step, behind which every wave first
+// had to read its operands: 105-115 TFLOP/s where this one reaches 130.)
+// The matrix instruction is v_mfma_f32_32x32x2_f32: lanes 0-31 hold inputs k .. k + 3 of their row or output, lanes
+// 32-63 inputs k + 4 .. k + 7; instruction i takes element i of both operands, so the contraction index is enumerated
+// in another order, identically on both sides.  All global accesses go through range-checked windows (see vec.h).
 // ---------------------------------------------------------------------------------
-constexpr int kBigWaves = 8;
-constexpr int kBigRows = 64 * kBigWaves;     // rows per workgroup
-constexpr int kBigOuts = 64;                 // outputs per workgroup
-constexpr int kBigK = 16;                    // inputs per step
-constexpr int kBigPitch = kBigK + 4;         // floats per row of the LDS tiles (80 bytes: eight lanes' 16-byte reads cover all banks)
+constexpr int kSlabWaves = 8;
+constexpr int kSlabRows = 64 * kSlabWaves;   // rows per workgroup
+constexpr int kSlabK = 16;                   // contraction indices per step
 constexpr unsigned kOutside = 0xFFFFFFF0u;   // a byte offset beyond any window
 
-// What the kernel below works on: out_s[row][n] = sum_c in_s[row][c] W_s[n][c] + bias_s[n] with W_s drawn: in = x
-// (one for all samples, or one per sample), c runs over the layer's inputs, n over its outputs, weight (n, c) has flat
-// index n * C + c (the generator's quads run along c).  (The input gradients, dx = dy W, were run through the same kernel
-// with the drawn tile transposed on its way into LDS: 106 against 105-112 TFLOP/s for the kernel they have; not kept.)
-struct BigArgs {
+// (LDS pointers keep their address space through the call: as generic pointers they would become flat accesses)
+typedef __attribute__((address_space(3))) float lds_float;
+typedef __attribute__((address_space(3))) f4 lds_f4;
+typedef __attribute__((address_space(3))) void lds_void;
+
+// What the kernel works on: out_s[row][n] = sum_c in_s[row][c] W_s(n, c) + bias_s[n] with W_s drawn.  Forward (TR = false):
+// in = x, c runs over the layer's inputs, n over its outputs, weight (n, c) has flat index n * C + c (the generator's
+// quads run along c).  Input gradients (TR = true): in = dy, c runs over the layer's outputs, n over its inputs, weight
+// (n, c) has flat index c * N + n (the quads run along n: a drawn quad goes into four rows of the tile), no bias.
+struct SlabArgs {
     long rows, contract, outs;   // R, C, N
     long ld_in;                  // pitch of the rows of `in`
     long in_sample_stride;       // floats between the inputs of consecutive samples (0: one input for all)
-    int s_loc;
+    int s_begin, s_end;          // the local samples of this launch: workgroups with blockIdx.z = p take those of pass p
     long weight_quad0, bias_quad0;
     const float *in, *mu_w, *sigma_w, *mu_b, *sigma_b;
     float *out;                  // [S_loc, R, N] packed
     Rng rng;
 };
 
-// ST samples per pass (they share the input tile); OWN: every sample has an input of its own (then ST = 1).
-template <int ST, bool OWN>
-__global__ void __launch_bounds__(64 * kBigWaves, 1)
-hot_linear_big_kernel(BigArgs a)
+__device__ __forceinline__ void everything_arrived_then_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// position of a row's quads in LDS: quad q of row r (r counted within a block of 16) is stored as quad q ^ slab_swizzle(r);
+// any 8 and any 16 consecutive rows then put a given q into different banks
+__device__ __forceinline__ int slab_swizzle(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
+
+// CBW: blocks of 32 outputs per workgroup (every wave multiplies its 64 rows by all of them); ST samples per pass (they
+// share the input tile); OWN: every sample has an input of its own (then ST = 1).
+template <int CBW, int ST, bool OWN, bool TR>
+__global__ void __launch_bounds__(64 * kSlabWaves, 1)
+hot_linear_slab_kernel(SlabArgs a)
 {
     static_assert(ST == 1 || ST == 2, "one or two samples per pass");
     static_assert(!OWN || ST == 1, "one input per sample: one sample per pass");
-    __shared__ __attribute__((aligned(16))) float xt[2][kBigRows * kBigPitch];
-    __shared__ __attribute__((aligned(16))) float wt[2][ST][kBigOuts * kBigPitch];      // [n][c]
+    constexpr int RBW = 2, WROWS = 32 * RBW, OUTS = 32 * CBW, KS = kSlabK;
+    constexpr int XW = WROWS * KS;           // floats of a wave's region of x
+    constexpr int WT = OUTS * KS;            // floats of one sample's weight tile
+    constexpr int NX = WROWS / 16;           // load instructions per wave and step
+    constexpr int QUADS = ST * OUTS * 4;     // quads drawn per step
+    static_assert(QUADS <= 64 * kSlabWaves && QUADS % 64 == 0, "whole waves draw");
+    __shared__ __attribute__((aligned(16))) float xs0[kSlabWaves * XW], xs1[kSlabWaves * XW];
+    __shared__ __attribute__((aligned(16))) float ws0[ST * WT], ws1[ST * WT];
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const long C = a.contract, N = a.outs, R = a.rows;
-    const long n0 = (long)blockIdx.x * kBigOuts, r0 = (long)blockIdx.y * kBigRows;
+    const int C = (int)a.contract, N = (int)a.outs, R = (int)a.rows;
+    const int n0 = (int)blockIdx.x * OUTS, r0 = (int)blockIdx.y * kSlabRows;
 
-    // as a loading thread: quad (t + 512 j) % 4 of row (t + 512 j) / 4 of the input tile, j = 0..3 (2048 quads per step)
-    // as a drawing thread: sample t / 256 (ST == 2) and one of the tile's 256 quads: quad idx % 4 (along c) of output idx / 4
-    const int d_st = ST == 2 ? t >> 8 : 0, d_idx = t & 255;
-    const bool draws = ST == 2 || t < 256;
-    const int d_n = d_idx >> 2;            // the quad's output, relative to n0
-    const int d_c = 4 * (d_idx & 3);       // its first input, relative to the step
-    const window_t mu_win = window(a.mu_w, (unsigned)(C * N * 4)), sg_win = window(a.sigma_w, (unsigned)(C * N * 4));
-    const unsigned in_bytes = (unsigned)(((R - 1) * a.ld_in + C) * 4);
+    // reading operands: lane (l32, half) holds, for half-step k8, inputs 8 k8 + 4 half .. + 3 of row / output l32 of a block of 32
+    int op_off[2];
+#pragma unroll
+    for (int k8 = 0; k8 < 2; ++k8) op_off[k8] = (l32 >> 4) * 256 + (4 * (l32 & 15) + ((2 * k8 + half) ^ slab_swizzle(l32 & 15))) * 4;
 
-    for (int s0 = 0; s0 < a.s_loc; s0 += ST) {
+    // loading x: instruction j of a step brings rows 16 j .. 16 j + 15 of this wave's 64, lane l the quad that belongs at position l
+    const int lq = (lane & 3) ^ slab_swizzle(lane >> 2);
+    const int x_cols = C - 4 * lq;           // this lane's quad exists in the step that starts at cb0 while cb0 < x_cols
+    unsigned x_first[NX];
+    bool x_ok[NX];
+#pragma unroll
+    for (int j = 0; j < NX; ++j) {
+        const long row = (long)r0 + wave * WROWS + 16 * j + (lane >> 2);
+        x_ok[j] = row < R;
+        x_first[j] = (unsigned)((row * a.ld_in + 4 * lq) * 4);
+    }
+    // drawing: sample d_st of the pass, quad d_idx of the step's tile: outputs n0 + d_n (.. + 3 if TR), contraction
+    // indices cb0 + d_c (.. + 3 if not TR)
+    const bool draws = t < QUADS;
+    const int d_st = t / (OUTS * 4), d_idx = t % (OUTS * 4);
+    const int d_n = TR ? 4 * (d_idx % (OUTS / 4)) : d_idx >> 2;
+    const int d_c = TR ? d_idx / (OUTS / 4) : 4 * (d_idx & 3);
+    const bool d_ok = draws && n0 + d_n < N;
+    const int d_cols = C - d_c;
+    const long d_flat = TR ? (long)d_c * N + n0 + d_n : (long)(n0 + d_n) * C + d_c;
+    const unsigned w_step = TR ? (unsigned)(KS * N * 4) : (unsigned)(KS * 4);      // bytes from one step's quad to the next
+    int d_put[TR ? 4 : 1];                   // where the drawn weights go in the tile (floats)
+    if constexpr (!TR) d_put[0] = d_st * WT + (4 * d_n + ((d_c >> 2) ^ slab_swizzle(d_n & 15))) * 4;
+    else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) d_put[e] = d_st * WT + (4 * (d_n + e) + ((d_c >> 2) ^ slab_swizzle((d_n + e) & 15))) * 4 + (d_c & 3);
+    }
+    const window_t mu_win = window(a.mu_w, (unsigned)((long)C * N * 4)), sg_win = window(a.sigma_w, (unsigned)((long)C * N * 4));
+    const unsigned in_bytes = (unsigned)((((long)R - 1) * a.ld_in + C) * 4);
+    lds_float *const X0 = (lds_float *)xs0, *const X1 = (lds_float *)xs1, *const W0 = (lds_float *)ws0, *const W1 = (lds_float *)ws1;
+
+    const int s0 = a.s_begin + (int)blockIdx.z * ST, s_hi = a.s_end;      // this workgroup's pass: samples s0 .. s0 + ST - 1 below s_hi
+    {
         const window_t in_win = window(OWN ? a.in + (size_t)s0 * (size_t)a.in_sample_stride : a.in, in_bytes);
-        Acc32x32 mm[ST][2][2];
+        Acc32x32 mm[ST][RBW][CBW];
 
-        f4 xg[4], m4, sd4;
-        // flat index of the first weight of this thread's quad in the step that starts at contraction index cb0, or -1
-        auto quad_at = [&](long cb0) -> long {
-            const long n = n0 + d_n, c = cb0 + d_c;
-            if (!draws || n >= N || c >= C) return -1;
-            return n * C + c;
-        };
-        // requests the operands of the step that starts at contraction index cb0 (nothing is read where the tile ends)
-        auto request = [&](long cb0) {
+        unsigned x_off[NX], w_off = (unsigned)(d_flat * 4);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int idx = t + 512 * j;
-                const long row = r0 + (idx >> 2), c = cb0 + 4 * (idx & 3);
-                xg[j] = window_load4<false>(in_win, (row < R && c < C) ? (unsigned)((row * a.ld_in + c) * 4) : kOutside);
-            }
-            const long at = quad_at(cb0);
-            m4 = window_load4<false>(mu_win, at >= 0 ? (unsigned)(at * 4) : kOutside);
-            sd4 = window_load4<false>(sg_win, at >= 0 ? (unsigned)(at * 4) : kOutside);
+        for (int j = 0; j < NX; ++j) x_off[j] = x_first[j];
+        long d_quad = a.weight_quad0 + (d_flat >> 2);
+        const bool d_live = d_ok && s0 + d_st < s_hi;
+
+        // sends for mu and sigma of this thread's quad of the step that starts at cb0 (every call advances one step)
+        f4 m4, sd4;
+        auto ask_w = [&](int cb0) {
+            const int off = (int)((d_ok && cb0 < d_cols) ? w_off : kOutside);
+            m4 = window_load4<false>(mu_win, off);
+            sd4 = window_load4<false>(sg_win, off);
+            w_off += w_step;
         };
-        // draws this thread's quad of that step and puts the requested operands into tile buffer `buf`
-        auto deposit = [&](long cb0, int buf) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int idx = t + 512 * j;
-                *reinterpret_cast<f4 *>(&xt[buf][(idx >> 2) * kBigPitch + 4 * (idx & 3)]) = xg[j];
-            }
+        // draws that quad and puts it into the tile (every call advances one step; zeros beyond the layer's edges)
+        auto put_w = [&](int cb0, lds_float *wsb) {
             if (draws) {
-                const long at = quad_at(cb0);
                 f4 w4 = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (at >= 0 && s0 + d_st < a.s_loc) {
-                    const f4 e = eps_quad(a.weight_quad0 + (at >> 2), s0 + d_st, a.rng);
+                if (d_live && cb0 < d_cols) {
+                    const f4 e = eps_quad(d_quad, s0 + d_st, a.rng);
 #pragma unroll
                     for (int c = 0; c < 4; ++c) w4[c] = __builtin_fmaf(sd4[c], e[c], m4[c]);
                 }
-                *reinterpret_cast<f4 *>(&wt[buf][d_st][d_n * kBigPitch + d_c]) = w4;
+                if constexpr (!TR) *(lds_f4 *)(wsb + d_put[0]) = w4;
+                else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) wsb[d_put[e]] = w4[e];
+                }
+                d_quad += TR ? (long)(KS / 4) * N : KS / 4;
             }
         };
-
-        request(0);
-        deposit(0, 0);
-        __syncthreads();
-        int buf = 0;
-        for (long cb0 = 0; cb0 < C; cb0 += kBigK, buf ^= 1) {
-            request(cb0 + kBigK);           // (all offsets outside the windows behind the last step: no traffic)
+        // sends for this wave's rows of the step that starts at cb0, straight into its region of xsb (every call advances one step)
+        auto ask_x = [&](int cb0, lds_float *xsb) {
+            const bool col_ok = cb0 < x_cols;
 #pragma unroll
-            for (int k8 = 0; k8 < 2; ++k8) {
-                f4 xa[2];
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
-                    xa[rb] = *reinterpret_cast<const f4 *>(&xt[buf][(64 * wave + 32 * rb + l32) * kBigPitch + 8 * k8 + 4 * half]);
-#pragma unroll
-                for (int st = 0; st < ST; ++st) {
-                    f4 wb[2];
-#pragma unroll
-                    for (int cb = 0; cb < 2; ++cb)
-                        wb[cb] = *reinterpret_cast<const f4 *>(&wt[buf][st][(32 * cb + l32) * kBigPitch + 8 * k8 + 4 * half]);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-#pragma unroll
-                        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                            for (int cb = 0; cb < 2; ++cb)
-                                mm[st][rb][cb].mac(xa[rb][i], wb[cb][i]);
-                }
+            for (int j = 0; j < NX; ++j) {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(in_win, (lds_void *)(xsb + wave * XW + j * 256), 16,
+                                                         (int)((x_ok[j] && col_ok) ? x_off[j] : kOutside), 0, 0, 0);
+                x_off[j] += KS * 4;
             }
-            if (cb0 + kBigK < C) deposit(cb0 + kBigK, buf ^ 1);      // uniform over the workgroup
-            __syncthreads();
+        };
+        f4 xa[2][RBW], wb[2][ST][CBW];      // operand registers of the two half-steps
+        auto read_ops = [&](int k8, const lds_float *xsb, const lds_float *wsb) {
+            const volatile lds_f4 *xp = (const volatile lds_f4 *)(xsb + wave * XW + op_off[k8]);
+            const volatile lds_f4 *wp = (const volatile lds_f4 *)(wsb + op_off[k8]);
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) xa[k8][rb] = xp[rb * 128];
+#pragma unroll
+            for (int st = 0; st < ST; ++st)
+#pragma unroll
+                for (int cb = 0; cb < CBW; ++cb) wb[k8][st][cb] = wp[(st * WT + cb * 512) / 4];
+        };
+        auto multiply = [&](int k8, int i0, int i1) {
+#pragma unroll
+            for (int i = i0; i < i1; ++i)
+#pragma unroll
+                for (int st = 0; st < ST; ++st)
+#pragma unroll
+                    for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+                        for (int cb = 0; cb < CBW; ++cb) mm[st][rb][cb].mac(xa[k8][rb][i], wb[k8][st][cb][i]);
+        };
+        auto step = [&](int cb0, lds_float *xsb, lds_float *wsb, const lds_float *xsn, const lds_float *wsn) {
+            read_ops(1, xsb, wsb);
+            multiply(0, 0, 4);
+            everything_arrived_then_barrier();
+            put_w(cb0 + 2 * KS, wsb);
+            ask_w(cb0 + 3 * KS);
+            ask_x(cb0 + 2 * KS, xsb);
+            multiply(1, 0, 3);
+            read_ops(0, xsn, wsn);
+            multiply(1, 3, 4);
+        };
+
+        ask_x(0, X0);
+        ask_x(KS, X1);
+        ask_w(0);
+        put_w(0, W0);
+        ask_w(KS);
+        put_w(KS, W1);
+        ask_w(2 * KS);
+        everything_arrived_then_barrier();
+        read_ops(0, X0, W0);
+        for (int cb0 = 0; cb0 < C; cb0 += 2 * KS) {      // (an odd number of steps is followed by one on zeros)
+            step(cb0, X0, W0, X1, W1);
+            step(cb0 + KS, X1, W1, X0, W0);
         }
         const MfmaSettled settled;
-        f16v acc[ST][2][2];
-#pragma unroll
-        for (int st = 0; st < ST; ++st)
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb) acc[st][rb][cb] = mm[st][rb][cb].read(settled);
 
-        // result register i of a 32 x 32 tile: row 8 (i / 4) + 4 (lane / 32) + i % 4, column lane % 32
+        // result register i of a 32 x 32 block: row 8 (i / 4) + 4 (lane / 32) + i % 4, column lane % 32
+        int r0w = r0 + wave * WROWS + 4 * half, n0l = n0 + l32;
+        asm volatile("" : "+v"(r0w), "+v"(n0l));       // (so that the offsets below are formed here, not ahead of the loop)
 #pragma unroll
         for (int st = 0; st < ST; ++st) {
-            if (s0 + st < a.s_loc) {
-                const window_t out_win = window(a.out + (size_t)(s0 + st) * (size_t)R * (size_t)N, (unsigned)(R * N * 4));
+            if (s0 + st < s_hi) {
+                const window_t out_win = window(a.out + (size_t)(s0 + st) * (size_t)R * (size_t)N, (unsigned)((long)R * N * 4));
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb) {
-                    const long n = n0 + 32 * cb + l32;
+                for (int cb = 0; cb < CBW; ++cb) {
+                    const int n = n0l + 32 * cb;
                     const bool n_ok = n < N;
                     float bias = 0.0f;
-                    if (a.mu_b && n_ok) {
+                    if (!TR && a.mu_b && n_ok) {
                         const f4 e = eps_quad(a.bias_quad0 + (n >> 2), s0 + st, a.rng);
-                        bias = __builtin_fmaf(a.sigma_b[n], pick4_of(e, (int)(n & 3)), a.mu_b[n]);
+                        bias = __builtin_fmaf(a.sigma_b[n], pick4_of(e, n & 3), a.mu_b[n]);
                     }
 #pragma unroll
-                    for (int rb = 0; rb < 2; ++rb)
+                    for (int rb = 0; rb < RBW; ++rb) {
+                        const f16v acc = mm[st][rb][cb].read(settled);
 #pragma unroll
                         for (int i = 0; i < 16; ++i) {
-                            const long row = r0 + 64 * wave + 32 * rb + 8 * (i >> 2) + 4 * half + (i & 3);
-                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, acc[st][rb][cb][i] + bias), out_win,
-                                                                  (n_ok && row < R) ? (int)((row * N + n) * 4) : (int)kOutside, 0, 0);
+                            const int row = r0w + 32 * rb + 8 * (i >> 2) + (i & 3);
+                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, acc[i] + bias), out_win,
+                                                                  (n_ok && row < R) ? (int)(((unsigned)row * (unsigned)N + (unsigned)n) * 4u) : (int)kOutside, 0, 0);
                         }
+                    }
                 }
             }
         }
     }
 }
 
-// Whether the kernel above can address this problem (its windows take 32-bit byte offsets).
-inline bool big_kernel_fits(long rows, long contract, long outs, long ld_in)
+// Whether the kernel above can address this problem (its windows take 32-bit byte offsets, its indices are 32-bit).
+inline bool slab_kernel_fits(long rows, long contract, long outs, long ld_in)
 {
     const unsigned long long lim = 0xFFFFFFF0ull;
-    return (unsigned long long)((rows - 1) * ld_in + contract) * 4 < lim && (unsigned long long)contract * outs * 4 < lim &&
-           (unsigned long long)(rows + kBigRows) * outs * 4 < lim && (rows + kBigRows - 1) / kBigRows <= 65535;
+    return (unsigned long long)((rows + kSlabRows) * ld_in + contract) * 4 < lim && (unsigned long long)(contract + 4 * kSlabK) * outs * 4 < lim &&
+           (unsigned long long)(rows + kSlabRows) * (outs + 128) * 4 < lim && (rows + kSlabRows - 1) / kSlabRows <= 65535;
+}
+
+constexpr int kComputeUnits = 256;
+constexpr int kSlabMinRows = 512;             // below, the kernels whose workgroups hold 256 rows
+// Least share of the chip's time that the tiles of a launch must fill, measured against the kernels for fewer rows on 130
+// layer shapes: the forward pass wins from 0.6 on (1.1-2x), the input gradients, whose other kernel packs several 256-row
+// workgroups into a compute unit, from 0.72 on (1.0-1.2x; 0.8-0.9x between 0.6 and 0.7).
+constexpr double kSlabMinFillForward = 0.6, kSlabMinFillInputGrad = 0.72;
+
+// Tile width of a launch of the kernel above, in blocks of 32 outputs: `narrow` or `wide`, whichever finishes first, or 0
+// where the chip would stand too empty.  One workgroup per compute unit runs at a time, so the launch takes its number
+// of rounds times the time of a workgroup, which per step is about 2400 cycles per block of 32 outputs and sample (matrix
+// instructions and draw) plus 600 for the barrier and what else does not overlap; the wider tile loads x half as often.
+inline int slab_width(long rows, long outs, long passes, int st, int narrow, int wide, double min_fill)
+{
+    if (passes < 1 || passes > 65535) return 0;
+    const long row_blocks = (rows + kSlabRows - 1) / kSlabRows;
+    int best = 0;
+    double best_cost = 0.0;
+    for (int cbw = wide; cbw >= narrow; cbw /= 2) {
+        const long wgs = ((outs + 32 * cbw - 1) / (32 * cbw)) * row_blocks * passes;
+        const double cost = (double)((wgs + kComputeUnits - 1) / kComputeUnits) * (2400.0 * cbw * st + 600.0);
+        if (best == 0 || cost < best_cost) {
+            best = cbw;
+            best_cost = cost;
+        }
+    }
+    const double full = (double)rows / kSlabRows * (double)outs / 32.0 * (double)passes * st * 2400.0 / kComputeUnits;
+    return full >= min_fill * best_cost ? best : 0;
+}
+
+// Launches it for the samples s_begin .. s_end - 1, ST per pass, one pass per layer of the grid along z.
+template <int CBW, int ST, bool OWN, bool TR>
+void slab_go(hipStream_t s, SlabArgs a, int s_begin, int s_end)
+{
+    a.s_begin = s_begin;
+    a.s_end = s_end;
+    const dim3 grid((unsigned)((a.outs + 32 * CBW - 1) / (32 * CBW)), (unsigned)((a.rows + kSlabRows - 1) / kSlabRows),
+                    (unsigned)((s_end - s_begin + ST - 1) / ST));
+    hot_linear_slab_kernel<CBW, ST, OWN, TR><<<grid, dim3(64 * kSlabWaves), 0, s>>>(a);
 }
 
 template <int RB, bool XS>
@@ -1050,10 +1163,6 @@ constexpr int kTileSide = 128;        // inputs and outputs per workgroup
 constexpr int kTileRows = 32;         // rows per step
 constexpr int kTurnPitch = 36;        // floats per row of a wave's 32 x 32 block on its way out (16-byte aligned rows)
 
-// (LDS pointers keep their address space through the call: as generic pointers they would become flat accesses)
-typedef __attribute__((address_space(3))) float lds_float;
-typedef __attribute__((address_space(3))) f4 lds_f4;
-typedef __attribute__((address_space(3))) void lds_void;
 
 // WHOLE: every 32 x 32 block of the workgroup's tile reaches into the layer (no block is skipped, no column masked).
 template <bool WHOLE>
@@ -1741,38 +1850,43 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     // through LDS (measured against the kernel above: 1.05-1.4x from there on, slower below).  Two samples per
     // pass and one column tile when several samples share x; a single sample, and samples with inputs of
     // their own (one per pass), afford two column tiles.
-    {
-        // Thousands of rows: 512 rows x 64 outputs per workgroup (the draw's share of the vector ALU halves again).
-        const bool xs = d->x_sample_stride != 0;
-        const long gx = (d->out_features + kBigOuts - 1) / kBigOuts, gy = (d->rows + kBigRows - 1) / kBigRows;
-        // (measured against the 256-row kernel below: 96 against 78 TFLOP/s at 7260 x 540 x 2160, 112-115 against 93-95
-        // at 1024 x 8192^2 and 4096^3 with a shared x, 100 against 95 with one x per sample; with fewer workgroups than
-        // three quarters of the compute units it loses; 32 outputs per workgroup, for layers whose 64-output workgroups
-        // are too few, were measured at 7260 x 2160 x 540 with one input per sample, 255 workgroups instead of 135: 0.55
-        // against 0.41 ms for the 256-row kernel, every workgroup still loading its full 512 x 16 tile of x per step)
-        const bool want = d->rows >= 1024 && gx * gy >= 192;
-        if (want && big_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) {
-            BigArgs b;
-            b.rows = d->rows;
-            b.contract = d->in_features;
-            b.outs = d->out_features;
-            b.ld_in = d->ldx;
-            b.in_sample_stride = d->x_sample_stride;
-            b.s_loc = d->s_local;
-            b.weight_quad0 = a.weight_quad0;
-            b.bias_quad0 = a.bias_quad0;
-            b.in = x;
-            b.mu_w = mu_w;
-            b.sigma_w = sigma_w;
-            b.mu_b = mu_b;
-            b.sigma_b = sigma_b;
-            b.out = y;
-            b.rng = r;
-            const dim3 grid((unsigned)gx, (unsigned)gy), block(64 * kBigWaves);
-            if (xs) hot_linear_big_kernel<1, true><<<grid, block, 0, s>>>(b);
-            else if (d->s_local == 1) hot_linear_big_kernel<1, false><<<grid, block, 0, s>>>(b);
-            else hot_linear_big_kernel<2, false><<<grid, block, 0, s>>>(b);
-            return hot_detail::note_hip(hipGetLastError());
+    // Hundreds to thousands of rows on a layer that fills the chip with tiles of 512 rows: the kernel that stages x and the
+    // drawn weights through LDS.  Samples that share x go two to a pass (they share every loaded row), an odd last one,
+    // a single one and samples with inputs of their own one to a pass with tiles twice as wide.
+    if (d->rows >= kSlabMinRows && slab_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) {
+        SlabArgs b;
+        b.rows = d->rows;
+        b.contract = d->in_features;
+        b.outs = d->out_features;
+        b.ld_in = d->ldx;
+        b.in_sample_stride = d->x_sample_stride;
+        b.s_begin = b.s_end = 0;
+        b.weight_quad0 = a.weight_quad0;
+        b.bias_quad0 = a.bias_quad0;
+        b.in = x;
+        b.mu_w = mu_w;
+        b.sigma_w = sigma_w;
+        b.mu_b = mu_b;
+        b.sigma_b = sigma_b;
+        b.out = y;
+        b.rng = r;
+        const int S = d->s_local;
+        if (d->x_sample_stride != 0) {
+            const int w = slab_width(d->rows, d->out_features, S, 1, 2, 4, kSlabMinFillForward);
+            if (w == 4) slab_go<4, 1, true, false>(s, b, 0, S);
+            else if (w == 2) slab_go<2, 1, true, false>(s, b, 0, S);
+            if (w) return hot_detail::note_hip(hipGetLastError());
+        } else {
+            const int pairs = S / 2, odd = S & 1;
+            const int w2 = pairs ? slab_width(d->rows, d->out_features, pairs, 2, 1, 2, kSlabMinFillForward) : 0;
+            const int w1 = odd ? slab_width(d->rows, d->out_features, 1, 1, 2, 4, kSlabMinFillForward) : 0;
+            if ((w2 || !pairs) && (w1 || !odd)) {
+                if (w2 == 2) slab_go<2, 2, false, false>(s, b, 0, 2 * pairs);
+                else if (w2 == 1) slab_go<1, 2, false, false>(s, b, 0, 2 * pairs);
+                if (w1 == 4) slab_go<4, 1, false, false>(s, b, S - 1, S);
+                else if (w1 == 2) slab_go<2, 1, false, false>(s, b, S - 1, S);
+                return hot_detail::note_hip(hipGetLastError());
+            }
         }
     }
     {
@@ -1919,6 +2033,30 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
             w *= 2;
         return w;
     };
+    // Hundreds to thousands of rows on a layer whose dx fills the chip with tiles of 512 rows: the kernel of the forward pass
+    // with dy as its input and the weight tile drawn transposed (rows of dy are read in 16-byte quads).
+    if (d->rows >= kSlabMinRows && (d->out_features & 3) == 0 && aligned16(dy) &&
+        slab_kernel_fits(d->rows, d->out_features, d->in_features, d->out_features)) {
+        SlabArgs b;
+        b.rows = d->rows;
+        b.contract = d->out_features;
+        b.outs = d->in_features;
+        b.ld_in = d->out_features;
+        b.in_sample_stride = d->rows * d->out_features;
+        b.s_begin = b.s_end = 0;
+        b.weight_quad0 = a.weight_quad0;
+        b.bias_quad0 = 0;
+        b.in = dy;
+        b.mu_w = mu_w;
+        b.sigma_w = sigma_w;
+        b.mu_b = b.sigma_b = nullptr;
+        b.out = dx;
+        b.rng = r;
+        const int w = slab_width(d->rows, d->in_features, d->s_local, 1, 2, 4, kSlabMinFillInputGrad);
+        if (w == 4) slab_go<4, 1, true, true>(s, b, 0, d->s_local);
+        else if (w == 2) slab_go<2, 1, true, true>(s, b, 0, d->s_local);
+        if (w) return hot_detail::note_hip(hipGetLastError());
+    }
     // many rows: the workgroup-shared draw, with as many rows per workgroup (256, 128, 64) as still give every
     // compute unit a workgroup
     if (const int x_parts = xgrad_parts(d, workspace ? workspace_bytes : 0); x_parts > 1) {

@@ -75,10 +75,14 @@ SHAPES = [(64, 96, 128, 4), (64, 128, 24, 4), (65, 192, 576, 4), (256, 192, 10, 
           # 256 rows and more on at least 128 workgroups: the kernel whose waves share the draws through LDS
           # (two samples per pass; an odd sample count; one sample with two column tiles; ragged everything)
           (300, 64, 2100, 2), (1030, 36, 2050, 3), (260, 100, 4100, 1), (513, 132, 2049, 5),
-          # 1024 rows and more on at least 192 workgroups of 512 rows x 64 outputs: the kernel that stages x and the drawn
-          # weights through LDS (two samples per pass, an odd count, one sample; rows, outputs and inputs all ragged:
-          # 36 and 20 inputs are 2.25 and 1.25 steps of 16, 4100 outputs are 64 tiles and 4 columns)
-          (1025, 36, 4100, 2), (1540, 20, 4160, 3), (1100, 52, 4097, 1), (2049, 16, 2500, 2)]
+          # layers with more than a thousand rows whose tiles of 512 rows do not fill the chip (they stay with the kernel above)
+          (1025, 36, 4100, 2), (1540, 20, 4160, 3), (1100, 52, 4097, 1), (2049, 16, 2500, 2),
+          # 512 rows and more on layers whose tiles of 512 rows fill the chip: the kernel that loads x straight into LDS, one
+          # shape per tile width it is launched with (rows, outputs and inputs all ragged: 36 and 20 inputs are 2.25 and
+          # 1.25 steps of 16, the last block of rows is short, the last tile of outputs partly outside):
+          # two samples per pass on tiles of 64 outputs; on tiles of 32 (288 of the wider ones would need two rounds);
+          # three samples: a pass of two and one on tiles of 128 outputs; one sample on tiles of 64
+          (2040, 36, 4090, 2), (1530, 20, 6100, 2), (2040, 16, 8180, 3), (1530, 20, 12002, 1)]
 
 
 @pytest.mark.parametrize("rows,k,o,s", SHAPES)
@@ -132,7 +136,8 @@ def test_layer_sees_the_w_of_hot_forward_rng(hot):
 # (rows, in, out, samples): every row-tile count, sample-chunk size and a ragged everything
 PER_SAMPLE = [(1, 8, 3, 2), (16, 128, 128, 4), (17, 36, 33, 5), (33, 100, 70, 3), (64, 128, 24, 16), (70, 64, 40, 2), (256, 192, 10, 1),
               (257, 68, 2064, 2), (700, 40, 2100, 3),      # the many-rows kernel with one input per sample
-              (1030, 24, 4100, 2), (1537, 36, 3100, 3)]    # the 512-row kernel with one input per sample
+              (1030, 24, 4100, 2), (1537, 36, 3100, 3),    # a thousand rows and more on too few tiles of 512 rows
+              (2040, 24, 4090, 2), (1530, 36, 6002, 2)]    # the 512-row kernel with one input per sample: tiles of 128 and of 64 outputs
 
 
 @pytest.mark.parametrize("rows,k,o,s", PER_SAMPLE)
@@ -206,7 +211,12 @@ BACKWARD = [(1, 4, 1, 1, False, True, True), (16, 64, 16, 2, False, True, True),
             (600, 516, 1840, 2, False, True, False), (515, 1028, 3900, 1, False, True, False),
             # many rows: the input-gradient kernel whose waves share the draws (odd O: dy rows only dword-aligned,
             # a last partial step of outputs; O a multiple of the step)
-            (520, 516, 33, 8, False, True, True), (1100, 1028, 48, 2, True, False, True)]
+            (520, 516, 33, 8, False, True, True), (1100, 1028, 48, 2, True, False, True),
+            # many rows on a layer whose dx fills the chip with tiles of 512 rows: the forward pass's 512-row kernel with
+            # the weight tile drawn transposed, on tiles of 128 inputs and of 64 inputs (36 and 20 outputs are 2.25 and 1.25
+            # steps, the last block of rows and the last tile of inputs ragged); the same rows with an output count
+            # that is no multiple of 4 (rows of dy not readable in quads: the other kernel)
+            (2040, 4092, 36, 2, False, True, True), (1530, 7000, 20, 2, True, False, True), (2040, 4092, 38, 2, False, True, True)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias,want_dx", BACKWARD)

@@ -464,7 +464,7 @@ __device__ __forceinline__ int slab_swizzle(int r) { return ((r >> 1) & 3) ^ ((r
 // CBW: blocks of 32 outputs per workgroup (every wave multiplies its 64 rows by all of them); ST samples per pass (they
 // share the input tile); OWN: every sample has an input of its own (then ST = 1).
 template <int CBW, int ST, bool OWN, bool TR>
-__global__ void __launch_bounds__(64 * kSlabWaves, 1)
+__global__ void __launch_bounds__(64 * kSlabWaves, CBW * ST <= 2 ? 4 : 2)
 hot_linear_slab_kernel(SlabArgs a)
 {
     static_assert(ST == 1 || ST == 2, "one or two samples per pass");
@@ -1872,19 +1872,21 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
         b.rng = r;
         const int S = d->s_local;
         if (d->x_sample_stride != 0) {
-            const int w = slab_width(d->rows, d->out_features, S, 1, 2, 4, kSlabMinFillForward);
+            const int w = slab_width(d->rows, d->out_features, S, 1, 1, 4, kSlabMinFillForward);
             if (w == 4) slab_go<4, 1, true, false>(s, b, 0, S);
             else if (w == 2) slab_go<2, 1, true, false>(s, b, 0, S);
+            else if (w == 1) slab_go<1, 1, true, false>(s, b, 0, S);
             if (w) return hot_detail::note_hip(hipGetLastError());
         } else {
             const int pairs = S / 2, odd = S & 1;
             const int w2 = pairs ? slab_width(d->rows, d->out_features, pairs, 2, 1, 2, kSlabMinFillForward) : 0;
-            const int w1 = odd ? slab_width(d->rows, d->out_features, 1, 1, 2, 4, kSlabMinFillForward) : 0;
+            const int w1 = odd ? slab_width(d->rows, d->out_features, 1, 1, 1, 4, kSlabMinFillForward) : 0;
             if ((w2 || !pairs) && (w1 || !odd)) {
                 if (w2 == 2) slab_go<2, 2, false, false>(s, b, 0, 2 * pairs);
                 else if (w2 == 1) slab_go<1, 2, false, false>(s, b, 0, 2 * pairs);
                 if (w1 == 4) slab_go<4, 1, false, false>(s, b, S - 1, S);
                 else if (w1 == 2) slab_go<2, 1, false, false>(s, b, S - 1, S);
+                else if (w1 == 1) slab_go<1, 1, false, false>(s, b, S - 1, S);
                 return hot_detail::note_hip(hipGetLastError());
             }
         }
@@ -2052,9 +2054,10 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
         b.mu_b = b.sigma_b = nullptr;
         b.out = dx;
         b.rng = r;
-        const int w = slab_width(d->rows, d->in_features, d->s_local, 1, 2, 4, kSlabMinFillInputGrad);
+        const int w = slab_width(d->rows, d->in_features, d->s_local, 1, 1, 4, kSlabMinFillInputGrad);
         if (w == 4) slab_go<4, 1, true, true>(s, b, 0, d->s_local);
         else if (w == 2) slab_go<2, 1, true, true>(s, b, 0, d->s_local);
+        else if (w == 1) slab_go<1, 1, true, true>(s, b, 0, d->s_local);
         if (w) return hot_detail::note_hip(hipGetLastError());
     }
     // many rows: the workgroup-shared draw, with as many rows per workgroup (256, 128, 64) as still give every

@@ -82,7 +82,9 @@ SHAPES = [(64, 96, 128, 4), (64, 128, 24, 4), (65, 192, 576, 4), (256, 192, 10, 
           # 1.25 steps of 16, the last block of rows is short, the last tile of outputs partly outside):
           # two samples per pass on tiles of 64 outputs; on tiles of 32 (288 of the wider ones would need two rounds);
           # three samples: a pass of two and one on tiles of 128 outputs; one sample on tiles of 64
-          (2040, 36, 4090, 2), (1530, 20, 6100, 2), (2040, 16, 8180, 3), (1530, 20, 12002, 1)]
+          (2040, 36, 4090, 2), (1530, 20, 6100, 2), (2040, 16, 8180, 3), (1530, 20, 12002, 1),
+          # one sample on tiles of 32 outputs (the SWIN token count on 540 outputs: 255 such tiles, 75 of the widest)
+          (7260, 20, 540, 1)]
 
 
 @pytest.mark.parametrize("rows,k,o,s", SHAPES)
@@ -137,7 +139,8 @@ def test_layer_sees_the_w_of_hot_forward_rng(hot):
 PER_SAMPLE = [(1, 8, 3, 2), (16, 128, 128, 4), (17, 36, 33, 5), (33, 100, 70, 3), (64, 128, 24, 16), (70, 64, 40, 2), (256, 192, 10, 1),
               (257, 68, 2064, 2), (700, 40, 2100, 3),      # the many-rows kernel with one input per sample
               (1030, 24, 4100, 2), (1537, 36, 3100, 3),    # a thousand rows and more on too few tiles of 512 rows
-              (2040, 24, 4090, 2), (1530, 36, 6002, 2)]    # the 512-row kernel with one input per sample: tiles of 128 and of 64 outputs
+              (2040, 24, 4090, 2), (1530, 36, 6002, 2),    # the 512-row kernel with one input per sample: tiles of 128 and of 64 outputs
+              (7260, 20, 540, 2)]                          # ... and of 32 (510 tiles: two per compute unit)
 
 
 @pytest.mark.parametrize("rows,k,o,s", PER_SAMPLE)
@@ -213,10 +216,12 @@ BACKWARD = [(1, 4, 1, 1, False, True, True), (16, 64, 16, 2, False, True, True),
             # a last partial step of outputs; O a multiple of the step)
             (520, 516, 33, 8, False, True, True), (1100, 1028, 48, 2, True, False, True),
             # many rows on a layer whose dx fills the chip with tiles of 512 rows: the forward pass's 512-row kernel with
-            # the weight tile drawn transposed, on tiles of 128 inputs and of 64 inputs (36 and 20 outputs are 2.25 and 1.25
+            # the weight tile drawn transposed, on tiles of 128 and of 64 inputs (36 and 20 outputs are 2.25 and 1.25
             # steps, the last block of rows and the last tile of inputs ragged); the same rows with an output count
             # that is no multiple of 4 (rows of dy not readable in quads: the other kernel)
-            (2040, 4092, 36, 2, False, True, True), (1530, 7000, 20, 2, True, False, True), (2040, 4092, 38, 2, False, True, True)]
+            (2040, 4092, 36, 2, False, True, True), (1530, 7000, 20, 2, True, False, True), (2040, 4092, 38, 2, False, True, True),
+            # ... and on tiles of 32 inputs (the SWIN token count, 540 inputs)
+            (7260, 540, 20, 2, False, True, True)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias,want_dx", BACKWARD)

@@ -1160,14 +1160,14 @@ void wgrad_go(long tiles, int waves, hipStream_t s, const LinearGradArgs &a)
 // (7260 x 540 x 2160, five or six parts: 0.46-0.49 against 0.42 ms; 16640 x 192 x 768: 0.21 against 0.17 ms).
 // ---------------------------------------------------------------------------------
 constexpr int kTileSide = 128;        // inputs and outputs per workgroup
-constexpr int kTileRows = 32;         // rows per step
+constexpr int kTileRows = 16;         // rows per step
 constexpr int kTurnPitch = 36;        // floats per row of a wave's 32 x 32 block on its way out (16-byte aligned rows)
 
 
 // WHOLE: every 32 x 32 block of the workgroup's tile reaches into the layer (no block is skipped, no column masked).
+// XB, DB: the four buffers of 16 rows x 128 columns of x and of dy.
 template <bool WHOLE>
-__device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_float *x0, lds_float *x1, lds_float *d0, lds_float *d1,
-                                                long o0, long k0)
+__device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_float *const (&XB)[4], lds_float *const (&DB)[4], long o0, long k0)
 {
     constexpr int WK = 2, TK = kTileSide, TO = kTileSide;         // 2 x 2 waves of 64 inputs x 64 outputs
     const int t = threadIdx.x, lane = t & 63;
@@ -1208,31 +1208,23 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
     const unsigned x_step = (unsigned)(kTileRows * a.ldx * 4), d_step = (unsigned)(kTileRows * O * 4);
     const int rows = (int)R;
 
-    // Registers for one set of products and one set of sums only (two workgroups per compute unit leave a wave 256):
-    // the accumulators run on over the samples, acc = A_s = G_1 + .. + G_s after sample s, which is the sum for
-    // grad_mu at the end, and the sum for grad_sigma is built by summation by parts,
-    // sum_s G_s eps_s = sum_s A_s (eps_s - eps_{s+1}) with eps_{S+1} = 0, at the price of a second draw per sample.
-    Acc32x32 mm[2][2];
-    f16v acc[2][2], gs[2][2];       // acc: the accumulators as read behind the last sample's matrix instructions
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int c = 0; c < 16; ++c) acc[i][j][c] = gs[i][j][c] = 0.0f;
-    float gb_m[2] = {0.0f, 0.0f}, gb_s[2] = {0.0f, 0.0f};
-
-    for (int s = 0; s < a.s_loc; ++s) {
+    // The products of one sample over all rows, into the accumulators mm (and the column sums of dy into sb).
+    // A step is 16 rows; four buffers, loads three steps ahead.  Step i (buffers i % 4): read the operands of its last 8
+    // rows; matrix instructions of its first 8 rows, whose operands are in registers already; wait for the loads
+    // of step i + 1 (sent for two steps ago; those of step i + 2 may still be on their way), barrier; send for step
+    // i + 3 (its buffers held step i - 1, read for the last time before this barrier); matrix instructions of the last 8
+    // rows, with the reads of the first operands of step i + 1 ahead of their last quarter.  Nothing behind the barrier waits for LDS or memory.  The steps are taken four at a time so that
+    // every access names its buffer; up to three steps behind the last row run on zeros.
+    auto all_rows = [&](int s, Acc32x32 (&mm)[2][2], float (&sb)[2]) {
         const window_t x_win = window(a.x + (size_t)s * (size_t)a.x_sample_stride, (unsigned)(((R - 1) * a.ldx + K) * 4));
         const window_t d_win = window(a.dy + (size_t)s * (size_t)R * (size_t)O, (unsigned)(R * O * 4));
-        float sb[2] = {0.0f, 0.0f};
         unsigned x_off[XI], d_off[DI];
 #pragma unroll
         for (int m = 0; m < XI; ++m) x_off[m] = x_first[m];
 #pragma unroll
         for (int m = 0; m < DI; ++m) d_off[m] = d_first[m];
 
-        // requests the next 32 rows of both operands, of which rows_left exist, into one pair of buffers
+        // requests the next 16 rows of both operands, of which rows_left exist, into one pair of buffers
         auto request = [&](lds_float *xt, lds_float *dt, int rows_left) {
 #pragma unroll
             for (int m = 0; m < XI; ++m) {
@@ -1247,92 +1239,149 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
                 d_off[m] += d_step;
             }
         };
-        auto multiply = [&](const lds_float *xt, const lds_float *dt) {
+        constexpr int P = kTileRows / 2, H = P / 2;       // pairs of rows per step and per half-step
+        float av[P][2], bv[P][2];
+        auto read_half = [&](int h, const lds_float *xt, const lds_float *dt) {
             const volatile lds_float *xb = xt + half * TK + 64 * wk + l32;
             const volatile lds_float *db = dt + half * TO + 64 * wo + l32;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {                // two halves of 16 rows: 32 operand registers at a time
-                constexpr int P = kTileRows / 4;
-                float av[P][2], bv[P][2];
+            for (int p = h * H; p < (h + 1) * H; ++p)
 #pragma unroll
-                for (int p = 0; p < P; ++p)
-#pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        av[p][i] = xb[2 * (h * P + p) * TK + 32 * i];
-                        bv[p][i] = db[2 * (h * P + p) * TO + 32 * i];
-                    }
-                if (bias_wave) {
-#pragma unroll
-                    for (int p = 0; p < P; ++p) {
-                        sb[0] += bv[p][0];
-                        sb[1] += bv[p][1];
-                    }
+                for (int i = 0; i < 2; ++i) {
+                    av[p][i] = xb[2 * p * TK + 32 * i];
+                    bv[p][i] = db[2 * p * TO + 32 * i];
                 }
-                if constexpr (WHOLE) {
+        };
+        auto multiply = [&](int p0, int p1) {
+            if (bias_wave) {
 #pragma unroll
-                    for (int p = 0; p < P; ++p)
+                for (int p = p0; p < p1; ++p) {
+                    sb[0] += bv[p][0];
+                    sb[1] += bv[p][1];
+                }
+            }
+            if constexpr (WHOLE) {
 #pragma unroll
-                        for (int i = 0; i < 2; ++i)
-#pragma unroll
-                            for (int j = 0; j < 2; ++j)
-                                mm[i][j].mac(av[p][i], bv[p][j]);
-                } else {
+                for (int p = p0; p < p1; ++p)
 #pragma unroll
                     for (int i = 0; i < 2; ++i)
 #pragma unroll
-                        for (int j = 0; j < 2; ++j)
-                            if (ok[i][j]) {
+                        for (int j = 0; j < 2; ++j) mm[i][j].mac(av[p][i], bv[p][j]);
+            } else {
 #pragma unroll
-                                for (int p = 0; p < P; ++p)
-                                    mm[i][j].mac(av[p][i], bv[p][j]);
-                            }
-                }
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        if (ok[i][j]) {
+#pragma unroll
+                            for (int p = p0; p < p1; ++p) mm[i][j].mac(av[p][i], bv[p][j]);
+                        }
             }
         };
-        // everything this wave has sent for has arrived (also in LDS), then the workgroup's barrier
-        auto arrive = [&]() {
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
-        };
 
-        // The two pairs of buffers are separate arrays and the loop names them in turn, so that the compiler
-        // can tell the loads in flight towards one pair from the reads of the other (else it waits for them
-        // ahead of the first read).
-        request(x0, d0, rows);
-        arrive();
-        for (int left = rows;;) {
-            if (left > kTileRows) request(x1, d1, left - kTileRows);
-            multiply(x0, d0);
-            arrive();
-            left -= kTileRows;
-            if (left <= 0) break;
-            if (left > kTileRows) request(x0, d0, left - kTileRows);
-            multiply(x1, d1);
-            arrive();
-            left -= kTileRows;
-            if (left <= 0) break;
+        request(XB[0], DB[0], rows);
+        request(XB[1], DB[1], rows - kTileRows);
+        request(XB[2], DB[2], rows - 2 * kTileRows);
+        everything_arrived_then_barrier();
+        read_half(0, XB[0], DB[0]);
+        for (int left = rows; left > 0;) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                read_half(1, XB[b], DB[b]);
+                multiply(0, H);
+                // all but the loads sent for last (XI + DI of them, for step i + 2) have arrived, and this wave's reads
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(XI + DI) : "memory");
+                request(XB[(b + 3) % 4], DB[(b + 3) % 4], left - 3 * kTileRows);
+                multiply(H, P - 1);
+                read_half(0, XB[(b + 1) % 4], DB[(b + 1) % 4]);
+                multiply(P - 1, P);
+                left -= kTileRows;
+            }
         }
-        const MfmaSettled settled;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) acc[i][j] = mm[i][j].read(settled);
+        everything_arrived_then_barrier();       // every wave is done with the buffers
+    };
 
+    // Two samples at a time, each with accumulators of its own: P_s = sum_r x_s[r] (x) dy_s[r], whose sum and whose sum
+    // weighted with eps_s leave together (one draw per sample and weight).  Further pairs of samples add to what the
+    // pairs before left in the gradient arrays (the same thread holds the same weights every time); the last pair
+    // applies the scale and the KL part.
+    float gb_m[2] = {0.0f, 0.0f}, gb_s[2] = {0.0f, 0.0f};
+    lds_float *const mine = XB[wave];        // a buffer per wave for turning its blocks on their way out
+    for (int s0 = 0; s0 < a.s_loc; s0 += 2) {
+        const bool two = s0 + 1 < a.s_loc, first = s0 == 0, last = s0 + 2 >= a.s_loc;
+        Acc32x32 m0[2][2], m1[2][2];
+        float sb0[2] = {0.0f, 0.0f}, sb1[2] = {0.0f, 0.0f};
+        all_rows(s0, m0, sb0);
+        if (two) all_rows(s0 + 1, m1, sb1);
+        const MfmaSettled settled;
+
+        long o0e = o0 + 64 * wo, k0e = k0 + 64 * wk;
+        asm volatile("" : "+s"(o0e), "+s"(k0e));       // (so that the addresses below are formed here, not ahead of the row loops)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 if (!ok[i][j]) continue;
-                const long o = o0 + 64 * wo + 32 * j + l32;
+                const f16v p0 = m0[i][j].read(settled), p1 = m1[i][j].read(settled);      // (p1 is zero without a second sample)
+                const long o = o0e + 32 * j + l32;
+                f4 u[4], v[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const long k = k0 + 64 * wk + 32 * i + 8 * q + 4 * half;
+                    const long k = k0e + 32 * i + 8 * q + 4 * half;
+                    f4 sum = {0.0f, 0.0f, 0.0f, 0.0f}, wsum = {0.0f, 0.0f, 0.0f, 0.0f};
                     if (WHOLE || (o < O && k < K)) {
-                        f4 e = eps_quad(a.weight_quad0 + ((o * K + k) >> 2), s, a.rng);
-                        if (s + 1 < a.s_loc) e -= eps_quad(a.weight_quad0 + ((o * K + k) >> 2), s + 1, a.rng);
+                        const long quad = a.weight_quad0 + ((o * K + k) >> 2);
+                        const f4 e0 = eps_quad(quad, s0, a.rng);
 #pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            gs[i][j][4 * q + c] = __builtin_fmaf(acc[i][j][4 * q + c], e[c], gs[i][j][4 * q + c]);
+                        for (int c = 0; c < 4; ++c) {
+                            sum[c] = p0[4 * q + c];
+                            wsum[c] = p0[4 * q + c] * e0[c];
+                        }
+                        if (two) {
+                            const f4 e1 = eps_quad(quad, s0 + 1, a.rng);
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                sum[c] += p1[4 * q + c];
+                                wsum[c] = __builtin_fmaf(p1[4 * q + c], e1[c], wsum[c]);
+                            }
+                        }
+                    }
+                    u[q] = sum;
+                    v[q] = wsum;
+                }
+                // Only this wave touches its buffer and the LDS executes a wave's instructions in order: program order suffices.
+                f4 ut[4], vt[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) *reinterpret_cast<lds_f4 *>(mine + l32 * kTurnPitch + 8 * q + 4 * half) = u[q];
+#pragma unroll
+                for (int it = 0; it < 4; ++it) ut[it] = *reinterpret_cast<const lds_f4 *>(mine + (8 * it + (lane >> 3)) * kTurnPitch + 4 * (lane & 7));
+#pragma unroll
+                for (int q = 0; q < 4; ++q) *reinterpret_cast<lds_f4 *>(mine + l32 * kTurnPitch + 8 * q + 4 * half) = v[q];
+#pragma unroll
+                for (int it = 0; it < 4; ++it) vt[it] = *reinterpret_cast<const lds_f4 *>(mine + (8 * it + (lane >> 3)) * kTurnPitch + 4 * (lane & 7));
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int row = 8 * it + (lane >> 3), quad = lane & 7;
+                    const long oo = o0e + 32 * j + row, k = k0e + 32 * i + 4 * quad;
+                    if (WHOLE || (oo < O && k < K)) {
+                        const long at = oo * K + k;
+                        f4 om = ut[it], os = vt[it];
+                        if (!first) {
+                            om += load4<true, false>(a.gmu_w + at);
+                            os += load4<true, false>(a.gsig_w + at);
+                        }
+                        if (last) {
+                            const f4 m4 = load4<true, false>(a.mu_w + at), sd4 = load4<true, false>(a.sigma_w + at);
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                float pm, ps;
+                                finish_pair(om[c], os[c], m4[c], sd4[c], a.g, a.k, pm, ps);
+                                om[c] = pm;
+                                os[c] = ps;
+                            }
+                        }
+                        store4<true, false>(a.gmu_w + at, om);
+                        store4<true, false>(a.gsig_w + at, os);
                     }
                 }
             }
@@ -1340,64 +1389,20 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const long o = o0 + 64 * wo + 32 * j + l32;
-                const float total = sb[j] + __shfl_xor(sb[j], 32);     // even and odd rows of the steps
                 if (o < O) {
-                    const f4 e = eps_quad(a.bias_quad0 + (o >> 2), s, a.rng);
-                    gb_m[j] += total;
-                    gb_s[j] = __builtin_fmaf(total, pick4(e, (int)(o & 3)), gb_s[j]);
-                }
-            }
-        }
-    }
-
-    // (the loop's last barrier lies behind the last reads of the operand buffers: they are free)
-    // every wave turns its blocks in a buffer of its own: 32 x 36 floats, first the sums for grad_mu, then those for grad_sigma
-    lds_float *const mine = wave == 0 ? x0 : (wave == 1 ? x1 : (wave == 2 ? d0 : d1));
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            if (!ok[i][j]) continue;
-            // Only this wave touches its buffer and the LDS executes a wave's instructions in order: program order suffices.
-            f4 u[4], v[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                f4 w;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) w[c] = acc[i][j][4 * q + c];
-                *reinterpret_cast<lds_f4 *>(mine + l32 * kTurnPitch + 8 * q + 4 * half) = w;
-            }
-#pragma unroll
-            for (int it = 0; it < 4; ++it) u[it] = *reinterpret_cast<const lds_f4 *>(mine + (8 * it + (lane >> 3)) * kTurnPitch + 4 * (lane & 7));
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                f4 w;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) w[c] = gs[i][j][4 * q + c];
-                *reinterpret_cast<lds_f4 *>(mine + l32 * kTurnPitch + 8 * q + 4 * half) = w;
-            }
-#pragma unroll
-            for (int it = 0; it < 4; ++it) v[it] = *reinterpret_cast<const lds_f4 *>(mine + (8 * it + (lane >> 3)) * kTurnPitch + 4 * (lane & 7));
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int row = 8 * it + (lane >> 3), quad = lane & 7;
-                const long o = o0 + 64 * wo + 32 * j + row, k = k0 + 64 * wk + 32 * i + 4 * quad;
-                if (WHOLE || (o < O && k < K)) {
-                    const long at = o * K + k;
-                    const f4 m4 = load4<true, false>(a.mu_w + at), sd4 = load4<true, false>(a.sigma_w + at);
-                    f4 om, os;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        float p, r;
-                        finish_pair(u[it][c], v[it][c], m4[c], sd4[c], a.g, a.k, p, r);
-                        om[c] = p;
-                        os[c] = r;
+                    const float t0 = sb0[j] + __shfl_xor(sb0[j], 32);     // even and odd rows of the steps
+                    gb_m[j] += t0;
+                    gb_s[j] = __builtin_fmaf(t0, pick4(eps_quad(a.bias_quad0 + (o >> 2), s0, a.rng), (int)(o & 3)), gb_s[j]);
+                    if (two) {
+                        const float t1 = sb1[j] + __shfl_xor(sb1[j], 32);
+                        gb_m[j] += t1;
+                        gb_s[j] = __builtin_fmaf(t1, pick4(eps_quad(a.bias_quad0 + (o >> 2), s0 + 1, a.rng), (int)(o & 3)), gb_s[j]);
                     }
-                    store4<true, false>(a.gmu_w + at, om);
-                    store4<true, false>(a.gsig_w + at, os);
                 }
             }
         }
+        everything_arrived_then_barrier();       // (the buffers go back to the rows of the next pair)
+    }
     if (bias_wave && half == 0) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -1416,21 +1421,29 @@ __global__ void __launch_bounds__(256, 2)
 hot_linear_wgrad_tile_kernel(LinearGradArgs a)
 {
     constexpr int TK = kTileSide, TO = kTileSide;
-    // two pairs of operand buffers, [32][128] of x and of dy each; at the end every wave turns its blocks in one of them
-    __shared__ __attribute__((aligned(16))) float x0[kTileRows * TK], x1[kTileRows * TK], d0[kTileRows * TO], d1[kTileRows * TO];
-    static_assert(kTileRows * TK >= 32 * kTurnPitch && kTileRows * TO >= 32 * kTurnPitch, "a wave's block fits in any of the buffers");
+    // four pairs of operand buffers, [16][128] of x and of dy each; at the end every wave turns its blocks in one of them
+    __shared__ __attribute__((aligned(16))) float x0[kTileRows * TK], x1[kTileRows * TK], x2[kTileRows * TK], x3[kTileRows * TK];
+    __shared__ __attribute__((aligned(16))) float d0[kTileRows * TO], d1[kTileRows * TO], d2[kTileRows * TO], d3[kTileRows * TO];
+    static_assert(kTileRows * TK >= 32 * kTurnPitch, "a wave's block fits in any of the buffers");
+    lds_float *XB[4], *DB[4];           // (filled by assignments: as a constant table of LDS addresses it would not link)
+    XB[0] = (lds_float *)x0, XB[1] = (lds_float *)x1, XB[2] = (lds_float *)x2, XB[3] = (lds_float *)x3;
+    DB[0] = (lds_float *)d0, DB[1] = (lds_float *)d1, DB[2] = (lds_float *)d2, DB[3] = (lds_float *)d3;
     const long K = a.in_features, O = a.out_features;
     const long k_tiles = (K + TK - 1) / TK, o_tiles = (O + TO - 1) / TO;
     const long tiles = k_tiles * o_tiles, per_xcd = (tiles + kXcds - 1) / kXcds;
     const long xcd = blockIdx.x % kXcds, nth = blockIdx.x / kXcds;      // the tiles are dealt out by XCD as above
     const long tile = xcd * per_xcd + nth;
     if (nth >= per_xcd || tile >= tiles) return;          // the whole workgroup
-    const bool outputs_outermost = O >= K;
-    const long o0 = (outputs_outermost ? tile / k_tiles : tile % o_tiles) * TO;
-    const long k0 = (outputs_outermost ? tile % k_tiles : tile / o_tiles) * TK;
+    // The tile list runs through bands of eight rows of tiles, column by column inside a band, so that the 64 tiles an
+    // XCD works on at a time are about 8 x 8 and share 16 columns of x and dy in its L2 (listed row by row they were
+    // 2 x 32 and shared 34).
+    const long band = tile / (8 * k_tiles), bands = o_tiles / 8;
+    const long height = band < bands ? 8 : o_tiles - 8 * bands, within = tile - (band < bands ? band : bands) * 8 * k_tiles;
+    const long o0 = (8 * (band < bands ? band : bands) + within % height) * TO;
+    const long k0 = (within / height) * TK;
     // (uniform over the workgroup, so all its waves meet at the same barriers)
-    if (k0 + TK <= K && o0 + TO <= O) wgrad_tile_body<true>(a, (lds_float *)x0, (lds_float *)x1, (lds_float *)d0, (lds_float *)d1, o0, k0);
-    else wgrad_tile_body<false>(a, (lds_float *)x0, (lds_float *)x1, (lds_float *)d0, (lds_float *)d1, o0, k0);
+    if (k0 + TK <= K && o0 + TO <= O) wgrad_tile_body<true>(a, XB, DB, o0, k0);
+    else wgrad_tile_body<false>(a, XB, DB, o0, k0);
 }
 
 // Whether the kernel above can address this problem (its windows take 32-bit byte offsets).

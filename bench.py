@@ -600,9 +600,17 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
     of the paper's models and on one large square layer; beside it the same layer done as
     hot_forward_rng (w written to HBM) + one library GEMM per sample."""
     def timeit(fn):
-        for _ in range(3):
-            fn()
+        # untimed calls first, for at least 30 ms: the card sits at idle clocks while the tensors of a shape are made, and
+        # what is timed first would otherwise run 5-8 % slower than the same call a moment later
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        warm = 0.0
+        while warm < 30.0:
+            e0.record()
+            for _ in range(3):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            warm += max(e0.elapsed_time(e1), 0.5)
         e0.record()
         for _ in range(iters):
             fn()

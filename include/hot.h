@@ -277,6 +277,18 @@ int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double
                             float *grad_sigma_w, float *grad_mu_b, float *grad_sigma_b, float *dx, void *stream);
 
 /*
+ * Which launch shape the calls above choose for a layer (host arithmetic only; for tests and for tuning, same
+ * passages of the paper).  which = 0: hot_linear_forward_rng; which = 1: the input-gradient part of
+ * hot_linear_backward_rng (dy taken to be 16-byte aligned).  Returns 0 where the layer goes to the kernels for up
+ * to a few hundred rows per workgroup; else, for the kernel with 512 or 1024 rows per workgroup,
+ * 100 * waves + 10 * (outputs per workgroup / 32) + samples per pass of its (first) launch, e.g. 822: eight waves
+ * (512 rows), 64 outputs, two samples per pass; 1621: sixteen waves (1024 rows), 64 outputs, one sample per pass;
+ * plus 1000 * (outputs per workgroup / 32) of a second launch that takes an odd last sample on its own.
+ * HOT_EINVAL for a malformed desc or another `which`.
+ */
+int hot_linear_launch_shape(const hot_linear_desc *desc, int which);
+
+/*
  * The same call with device scratch of the caller's (same passage of the paper; only the launch shape
  * differs).  A layer with few weights and many rows (a ViT layer: 192 x 768 weights, 16 640 rows) has too
  * few 16-output x 64-input tiles to give every compute unit weight-gradient work, and the waves of one

@@ -29,7 +29,8 @@ EXPORTS = ("hot_create", "hot_forward", "hot_backward", "hot_destroy", "hot_set_
            "hot_backward_dropout_rng", "hot_backward_rows", "hot_backward_adam",
            "hot_linear_backward_rng", "hot_kl", "hot_forward_dropout_units_rng",
            "hot_backward_dropout_units_rng", "hot_stats_whole", "hot_adam_forward", "hot_backward_adam_forward",
-           "hot_linear_backward_rng_ws", "hot_linear_backward_workspace_bytes", "hot_forward_static")
+           "hot_linear_backward_rng_ws", "hot_linear_backward_workspace_bytes", "hot_forward_static",
+           "hot_linear_launch_shape")
 
 
 # Return types of the entry points that do not return an int status (as declared in include/hot.h).
@@ -119,6 +120,7 @@ def lib() -> ctypes.CDLL:
                                              rp] + [fp] * 11 + [vp, ctypes.c_int64, vp]
     L.hot_linear_backward_rng_ws.restype = ctypes.c_int
     L.hot_linear_backward_workspace_bytes.argtypes = [ctypes.POINTER(hot_linear_desc)]
+    L.hot_linear_launch_shape.argtypes = [ctypes.POINTER(hot_linear_desc), ctypes.c_int]
     L.hot_linear_backward_workspace_bytes.restype = ctypes.c_int64
     L.hot_adam_forward.argtypes = [vp, rp, ctypes.POINTER(hot_adam)] + [fp] * 10 + [vp, vp]
     L.hot_backward_adam.argtypes = [vp, rp, ctypes.POINTER(hot_adam)] + [fp] * 8 + [vp]
@@ -502,6 +504,18 @@ def hot_linear_backward_workspace_bytes(rows: int, in_features: int, out_feature
     if n < 0:
         _check_planless(int(n), "hot_linear_backward_workspace_bytes")
     return int(n)
+
+
+def hot_linear_launch_shape(rows: int, in_features: int, out_features: int, s_local: int, which: int, per_sample_x: bool = False,
+                            ldx: int = 0) -> int:
+    """Code of the launch shape hot_linear_forward_rng (which = 0) or the input-gradient part of
+    hot_linear_backward_rng (which = 1) chooses for this layer (see include/hot.h); 0: the kernels for few rows."""
+    ldx = ldx or in_features
+    d = hot_linear_desc(rows, in_features, out_features, ldx, 0, 0, s_local, 0, rows * ldx if per_sample_x else 0)
+    code = lib().hot_linear_launch_shape(ctypes.byref(d), which)
+    if code < 0:
+        _check_planless(int(code), "hot_linear_launch_shape")
+    return int(code)
 
 
 def hot_linear_backward_rng(rng: hot_rng, x, dy, mu_w, sigma_w, mu_b, sigma_b, grad_mu_w, grad_sigma_w, grad_mu_b,

@@ -405,7 +405,7 @@ hot_linear_forward_rows_kernel(LinearArgs a)
 // side by side (the fp32 matrix rate equals the packed fp32 vector rate: the same multipliers serve both; measured
 // with the two kinds of work in different waves of one SIMD, the times add), so every cycle spent drawing is lost to
 // the contraction, and the share of the draw is 81 / (rows per workgroup): a third at 256 rows.  Here a workgroup
-// of eight waves owns 512 rows (64 per wave) x 64 or 128 outputs; per step of 16 contraction indices a thread draws at
+// of eight waves owns 512 rows (64 per wave) x 32 to 128 outputs (one of sixteen: 1024 rows x 64 outputs); per step of 16 contraction indices a thread draws at
 // most ONE quad of the weight tile (two samples per pass: thread t draws sample t / 256).
 // x never passes through registers: each wave sends for the 16 inputs of its own 64 rows with buffer loads that write
 // straight into LDS (lane l of an instruction leaves its 16 bytes at the instruction's LDS address + 16 l, zeros for an
@@ -427,8 +427,7 @@ hot_linear_forward_rows_kernel(LinearArgs a)
 // 32-63 inputs k + 4 .. k + 7; instruction i takes element i of both operands, so the contraction index is enumerated
 // in another order, identically on both sides.  All global accesses go through range-checked windows (see vec.h).
 // ---------------------------------------------------------------------------------
-constexpr int kSlabWaves = 8;
-constexpr int kSlabRows = 64 * kSlabWaves;   // rows per workgroup
+constexpr int kSlabRows = 512;               // rows per workgroup of eight waves (sixteen: twice as many)
 constexpr int kSlabK = 16;                   // contraction indices per step
 constexpr unsigned kOutside = 0xFFFFFFF0u;   // a byte offset beyond any window
 
@@ -461,27 +460,29 @@ __device__ __forceinline__ void everything_arrived_then_barrier()
 // any 8 and any 16 consecutive rows then put a given q into different banks
 __device__ __forceinline__ int slab_swizzle(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
 
-// CBW: blocks of 32 outputs per workgroup (every wave multiplies its 64 rows by all of them); ST samples per pass (they
-// share the input tile); OWN: every sample has an input of its own (then ST = 1).
-template <int CBW, int ST, bool OWN, bool TR>
-__global__ void __launch_bounds__(64 * kSlabWaves, CBW * ST <= 2 ? 4 : 2)
+// WAVES: 8 or 16 waves of 64 rows each (16: half the draw per row again; their registers then allow 64 outputs and one
+// sample); CBW: blocks of 32 outputs per workgroup (every wave multiplies its 64 rows by all of them); ST samples per pass
+// (they share the input tile); OWN: every sample has an input of its own (then ST = 1).
+template <int WAVES, int CBW, int ST, bool OWN, bool TR>
+__global__ void __launch_bounds__(64 * WAVES, CBW * ST <= 2 ? 4 : 2)
 hot_linear_slab_kernel(SlabArgs a)
 {
     static_assert(ST == 1 || ST == 2, "one or two samples per pass");
     static_assert(!OWN || ST == 1, "one input per sample: one sample per pass");
+    static_assert(WAVES == 8 || (WAVES == 16 && CBW * ST <= 2), "sixteen waves have 128 registers each");
     constexpr int RBW = 2, WROWS = 32 * RBW, OUTS = 32 * CBW, KS = kSlabK;
     constexpr int XW = WROWS * KS;           // floats of a wave's region of x
     constexpr int WT = OUTS * KS;            // floats of one sample's weight tile
     constexpr int NX = WROWS / 16;           // load instructions per wave and step
     constexpr int QUADS = ST * OUTS * 4;     // quads drawn per step
-    static_assert(QUADS <= 64 * kSlabWaves && QUADS % 64 == 0, "whole waves draw");
-    __shared__ __attribute__((aligned(16))) float xs0[kSlabWaves * XW], xs1[kSlabWaves * XW];
+    static_assert(QUADS <= 64 * WAVES && QUADS % 64 == 0, "whole waves draw");
+    __shared__ __attribute__((aligned(16))) float xs0[WAVES * XW], xs1[WAVES * XW];
     __shared__ __attribute__((aligned(16))) float ws0[ST * WT], ws1[ST * WT];
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int C = (int)a.contract, N = (int)a.outs, R = (int)a.rows;
-    const int n0 = (int)blockIdx.x * OUTS, r0 = (int)blockIdx.y * kSlabRows;
+    const int n0 = (int)blockIdx.x * OUTS, r0 = (int)blockIdx.y * (64 * WAVES);
 
     // reading operands: lane (l32, half) holds, for half-step k8, inputs 8 k8 + 4 half .. + 3 of row / output l32 of a block of 32
     int op_off[2];
@@ -649,8 +650,8 @@ hot_linear_slab_kernel(SlabArgs a)
 inline bool slab_kernel_fits(long rows, long contract, long outs, long ld_in)
 {
     const unsigned long long lim = 0xFFFFFFF0ull;
-    return (unsigned long long)((rows + kSlabRows) * ld_in + contract) * 4 < lim && (unsigned long long)(contract + 4 * kSlabK) * outs * 4 < lim &&
-           (unsigned long long)(rows + kSlabRows) * (outs + 128) * 4 < lim && (rows + kSlabRows - 1) / kSlabRows <= 65535;
+    return (unsigned long long)((rows + 2 * kSlabRows) * ld_in + contract) * 4 < lim && (unsigned long long)(contract + 4 * kSlabK) * outs * 4 < lim &&
+           (unsigned long long)(rows + 2 * kSlabRows) * (outs + 128) * 4 < lim && (rows + kSlabRows - 1) / kSlabRows <= 65535;
 }
 
 constexpr int kComputeUnits = 256;
@@ -660,37 +661,117 @@ constexpr int kSlabMinRows = 512;             // below, the kernels whose workgr
 // workgroups into a compute unit, from 0.72 on (1.0-1.2x; 0.8-0.9x between 0.6 and 0.7).
 constexpr double kSlabMinFillForward = 0.6, kSlabMinFillInputGrad = 0.72;
 
-// Tile width of a launch of the kernel above, in blocks of 32 outputs: `narrow` or `wide`, whichever finishes first, or 0
-// where the chip would stand too empty.  One workgroup per compute unit runs at a time, so the launch takes its number
-// of rounds times the time of a workgroup, which per step is about 2400 cycles per block of 32 outputs and sample (matrix
-// instructions and draw) plus 600 for the barrier and what else does not overlap; the wider tile loads x half as often.
-inline int slab_width(long rows, long outs, long passes, int st, int narrow, int wide, double min_fill)
+// A launch shape of the kernel above and what it costs.  One workgroup per compute unit runs at a time (two of the narrow
+// ones, at half speed each), so a launch takes its number of rounds times the time of a workgroup, which per step is, per
+// block of 32 outputs and sample, about 2050 cycles of matrix instructions for 512 rows plus 325 of drawing, and
+// 600 for the barrier and what else does not overlap; the wider tile also loads x half as often.  The constants are
+// fitted to timings of 130 layer shapes; the model only has to rank the shapes of one layer.
+struct SlabShape {
+    int waves;      // 8 or 16; 0: none
+    int cbw;        // blocks of 32 outputs per workgroup
+    double cost;
+};
+
+// the cheapest of the eight-wave shapes with `st` samples per pass and tiles of 32 * narrow .. 32 * wide outputs
+inline SlabShape slab_shape8(long rows, long outs, long passes, int st, int narrow, int wide)
 {
-    if (passes < 1 || passes > 65535) return 0;
+    SlabShape best = {0, 0, 0.0};
+    if (passes < 1 || passes > 65535) return best;
     const long row_blocks = (rows + kSlabRows - 1) / kSlabRows;
-    int best = 0;
-    double best_cost = 0.0;
     for (int cbw = wide; cbw >= narrow; cbw /= 2) {
         const long wgs = ((outs + 32 * cbw - 1) / (32 * cbw)) * row_blocks * passes;
-        const double cost = (double)((wgs + kComputeUnits - 1) / kComputeUnits) * (2400.0 * cbw * st + 600.0);
-        if (best == 0 || cost < best_cost) {
-            best = cbw;
-            best_cost = cost;
-        }
+        // (two narrow workgroups share a compute unit and cover part of each other's waits: about 5 % by measurement)
+        const double cost = (double)((wgs + kComputeUnits - 1) / kComputeUnits) * (2375.0 * cbw * st + 600.0) * (cbw * st <= 2 ? 0.95 : 1.0);
+        if (best.waves == 0 || cost < best.cost) best = SlabShape{8, cbw, cost};
     }
-    const double full = (double)rows / kSlabRows * (double)outs / 32.0 * (double)passes * st * 2400.0 / kComputeUnits;
-    return full >= min_fill * best_cost ? best : 0;
+    return best;
+}
+
+// sixteen waves: 1024 rows x 64 outputs, one sample per pass
+inline SlabShape slab_shape16(long rows, long outs, long passes)
+{
+    if (passes < 1 || passes > 65535 || rows <= kSlabRows) return SlabShape{0, 0, 0.0};
+    const long wgs = ((outs + 63) / 64) * ((rows + 2 * kSlabRows - 1) / (2 * kSlabRows)) * passes;
+    // (measured on layers that both shapes fill: 0.966 of the time of 512 rows x 64 outputs x 2 samples)
+    return SlabShape{16, 2, (double)((wgs + kComputeUnits - 1) / kComputeUnits) * 9750.0};
+}
+
+// what the samples of a launch would cost on a chip they fill evenly
+inline double slab_full(long rows, long outs, long samples)
+{
+    return (double)rows / kSlabRows * (double)outs / 32.0 * (double)samples * 2375.0 / kComputeUnits;
 }
 
 // Launches it for the samples s_begin .. s_end - 1, ST per pass, one pass per layer of the grid along z.
-template <int CBW, int ST, bool OWN, bool TR>
+template <int WAVES, int CBW, int ST, bool OWN, bool TR>
 void slab_go(hipStream_t s, SlabArgs a, int s_begin, int s_end)
 {
     a.s_begin = s_begin;
     a.s_end = s_end;
-    const dim3 grid((unsigned)((a.outs + 32 * CBW - 1) / (32 * CBW)), (unsigned)((a.rows + kSlabRows - 1) / kSlabRows),
+    const dim3 grid((unsigned)((a.outs + 32 * CBW - 1) / (32 * CBW)), (unsigned)((a.rows + 64 * WAVES - 1) / (64 * WAVES)),
                     (unsigned)((s_end - s_begin + ST - 1) / ST));
-    hot_linear_slab_kernel<CBW, ST, OWN, TR><<<grid, dim3(64 * kSlabWaves), 0, s>>>(a);
+    hot_linear_slab_kernel<WAVES, CBW, ST, OWN, TR><<<grid, dim3(64 * WAVES), 0, s>>>(a);
+}
+
+// one sample per pass, in the shape chosen
+template <bool OWN, bool TR>
+void slab_go_singles(const SlabShape &shape, hipStream_t s, const SlabArgs &a, int s_begin, int s_end)
+{
+    if (shape.waves == 16) slab_go<16, 2, 1, OWN, TR>(s, a, s_begin, s_end);
+    else if (shape.cbw == 4) slab_go<8, 4, 1, OWN, TR>(s, a, s_begin, s_end);
+    else if (shape.cbw == 2) slab_go<8, 2, 1, OWN, TR>(s, a, s_begin, s_end);
+    else slab_go<8, 1, 1, OWN, TR>(s, a, s_begin, s_end);
+}
+
+// the cheaper of the shapes with one sample per pass, or none where the chip would stand too empty
+inline SlabShape slab_shape_singles(long rows, long outs, long samples, double min_fill)
+{
+    SlabShape best = slab_shape8(rows, outs, samples, 1, 1, 4);
+    const SlabShape tall = slab_shape16(rows, outs, samples);
+    if (tall.waves && (!best.waves || tall.cost < best.cost)) best = tall;
+    if (best.waves && slab_full(rows, outs, samples) < min_fill * best.cost) best.waves = 0;
+    return best;
+}
+
+// How the forward call runs a layer on the kernel above: pairs of samples that share x (samples 0 .. 2 * pairs - 1) in
+// `two` and the samples behind them one at a time in `one`; neither where the layer is left to the kernels for fewer rows.
+struct SlabForwardPlan {
+    int pair_samples;     // samples that go two to a pass
+    SlabShape two, one;   // (waves == 0: not used)
+};
+
+inline SlabForwardPlan slab_forward_plan(const hot_linear_desc *d)
+{
+    SlabForwardPlan p = {0, SlabShape{0, 0, 0.0}, SlabShape{0, 0, 0.0}};
+    if (d->rows < kSlabMinRows || !slab_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) return p;
+    const int S = d->s_local;
+    if (d->x_sample_stride != 0 || S == 1) {
+        p.one = slab_shape_singles(d->rows, d->out_features, S, kSlabMinFillForward);
+        return p;
+    }
+    // two samples to a pass and an odd last one on its own, or every sample on its own in the tall shape
+    const int pairs = S / 2, odd = S & 1;
+    const SlabShape two = slab_shape8(d->rows, d->out_features, pairs, 2, 1, 2);
+    const SlabShape last = odd ? slab_shape8(d->rows, d->out_features, 1, 1, 1, 4) : SlabShape{8, 0, 0.0};
+    const SlabShape tall = slab_shape16(d->rows, d->out_features, S);
+    const double full = slab_full(d->rows, d->out_features, S);
+    if (tall.waves && (!two.waves || !last.waves || tall.cost < two.cost + last.cost)) {
+        if (full >= kSlabMinFillForward * tall.cost) p.one = tall;
+    } else if (two.waves && last.waves && full >= kSlabMinFillForward * (two.cost + last.cost)) {
+        p.pair_samples = 2 * pairs;
+        p.two = two;
+        if (odd) p.one = last;
+    }
+    return p;
+}
+
+// ... and the input gradients (dy is the input, read in 16-byte quads: rows of dy must allow that)
+inline SlabShape slab_input_grad_shape(const hot_linear_desc *d, bool dy_aligned)
+{
+    if (d->rows < kSlabMinRows || (d->out_features & 3) != 0 || !dy_aligned ||
+        !slab_kernel_fits(d->rows, d->out_features, d->in_features, d->out_features))
+        return SlabShape{0, 0, 0.0};
+    return slab_shape_singles(d->rows, d->in_features, d->s_local, kSlabMinFillInputGrad);
 }
 
 template <int RB, bool XS>
@@ -1811,6 +1892,17 @@ WgradShape wgrad_shape(const hot_linear_desc *d, int64_t ws_bytes)
 
 extern "C" {
 
+int hot_linear_launch_shape(const hot_linear_desc *d, int which)
+{
+    if (!d || d->rows < 1 || d->in_features < 4 || (d->in_features & 3) || d->out_features < 1 || d->s_local < 1) return HOT_EINVAL;
+    if (d->ldx < d->in_features || (d->ldx & 3) || d->x_sample_stride < 0 || (which != 0 && which != 1)) return HOT_EINVAL;
+    if (d->out_features > (INT64_MAX / 8) / d->in_features || d->rows > (INT64_MAX / 8) / d->ldx) return HOT_EINVAL;
+    auto code = [](const SlabShape &h, int st) { return h.waves ? 100 * h.waves + 10 * h.cbw + st : 0; };
+    if (which == 1) return code(slab_input_grad_shape(d, true), 1);
+    const SlabForwardPlan p = slab_forward_plan(d);
+    return p.two.waves ? code(p.two, 2) + 1000 * (p.one.waves ? p.one.cbw : 0) : code(p.one, 1);
+}
+
 int64_t hot_linear_backward_workspace_bytes(const hot_linear_desc *d)
 {
     if (!d || d->rows < 1 || d->in_features < 4 || (d->in_features & 3) || d->out_features < 1 || d->s_local < 1) return HOT_EINVAL;
@@ -1866,7 +1958,7 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
     // Hundreds to thousands of rows on a layer that fills the chip with tiles of 512 rows: the kernel that stages x and the
     // drawn weights through LDS.  Samples that share x go two to a pass (they share every loaded row), an odd last one,
     // a single one and samples with inputs of their own one to a pass with tiles twice as wide.
-    if (d->rows >= kSlabMinRows && slab_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) {
+    if (const SlabForwardPlan plan = slab_forward_plan(d); plan.two.waves || plan.one.waves) {
         SlabArgs b;
         b.rows = d->rows;
         b.contract = d->in_features;
@@ -1883,26 +1975,15 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
         b.sigma_b = sigma_b;
         b.out = y;
         b.rng = r;
-        const int S = d->s_local;
-        if (d->x_sample_stride != 0) {
-            const int w = slab_width(d->rows, d->out_features, S, 1, 1, 4, kSlabMinFillForward);
-            if (w == 4) slab_go<4, 1, true, false>(s, b, 0, S);
-            else if (w == 2) slab_go<2, 1, true, false>(s, b, 0, S);
-            else if (w == 1) slab_go<1, 1, true, false>(s, b, 0, S);
-            if (w) return hot_detail::note_hip(hipGetLastError());
-        } else {
-            const int pairs = S / 2, odd = S & 1;
-            const int w2 = pairs ? slab_width(d->rows, d->out_features, pairs, 2, 1, 2, kSlabMinFillForward) : 0;
-            const int w1 = odd ? slab_width(d->rows, d->out_features, 1, 1, 1, 4, kSlabMinFillForward) : 0;
-            if ((w2 || !pairs) && (w1 || !odd)) {
-                if (w2 == 2) slab_go<2, 2, false, false>(s, b, 0, 2 * pairs);
-                else if (w2 == 1) slab_go<1, 2, false, false>(s, b, 0, 2 * pairs);
-                if (w1 == 4) slab_go<4, 1, false, false>(s, b, S - 1, S);
-                else if (w1 == 2) slab_go<2, 1, false, false>(s, b, S - 1, S);
-                else if (w1 == 1) slab_go<1, 1, false, false>(s, b, S - 1, S);
-                return hot_detail::note_hip(hipGetLastError());
-            }
+        if (plan.two.waves) {
+            if (plan.two.cbw == 2) slab_go<8, 2, 2, false, false>(s, b, 0, plan.pair_samples);
+            else slab_go<8, 1, 2, false, false>(s, b, 0, plan.pair_samples);
         }
+        if (plan.one.waves) {
+            if (d->x_sample_stride != 0) slab_go_singles<true, false>(plan.one, s, b, plan.pair_samples, d->s_local);
+            else slab_go_singles<false, false>(plan.one, s, b, plan.pair_samples, d->s_local);
+        }
+        return hot_detail::note_hip(hipGetLastError());
     }
     {
         const bool xs = d->x_sample_stride != 0;
@@ -2050,8 +2131,7 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
     };
     // Hundreds to thousands of rows on a layer whose dx fills the chip with tiles of 512 rows: the kernel of the forward pass
     // with dy as its input and the weight tile drawn transposed (rows of dy are read in 16-byte quads).
-    if (d->rows >= kSlabMinRows && (d->out_features & 3) == 0 && aligned16(dy) &&
-        slab_kernel_fits(d->rows, d->out_features, d->in_features, d->out_features)) {
+    if (const SlabShape one = slab_input_grad_shape(d, aligned16(dy)); one.waves) {
         SlabArgs b;
         b.rows = d->rows;
         b.contract = d->out_features;
@@ -2067,11 +2147,8 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
         b.mu_b = b.sigma_b = nullptr;
         b.out = dx;
         b.rng = r;
-        const int w = slab_width(d->rows, d->in_features, d->s_local, 1, 1, 4, kSlabMinFillInputGrad);
-        if (w == 4) slab_go<4, 1, true, true>(s, b, 0, d->s_local);
-        else if (w == 2) slab_go<2, 1, true, true>(s, b, 0, d->s_local);
-        else if (w == 1) slab_go<1, 1, true, true>(s, b, 0, d->s_local);
-        if (w) return hot_detail::note_hip(hipGetLastError());
+        slab_go_singles<true, true>(one, s, b, 0, d->s_local);
+        return hot_detail::note_hip(hipGetLastError());
     }
     // many rows: the workgroup-shared draw, with as many rows per workgroup (256, 128, 64) as still give every
     // compute unit a workgroup

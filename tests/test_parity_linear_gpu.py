@@ -75,16 +75,37 @@ SHAPES = [(64, 96, 128, 4), (64, 128, 24, 4), (65, 192, 576, 4), (256, 192, 10, 
           # 256 rows and more on at least 128 workgroups: the kernel whose waves share the draws through LDS
           # (two samples per pass; an odd sample count; one sample with two column tiles; ragged everything)
           (300, 64, 2100, 2), (1030, 36, 2050, 3), (260, 100, 4100, 1), (513, 132, 2049, 5),
-          # layers with more than a thousand rows whose tiles of 512 rows do not fill the chip (they stay with the kernel above)
-          (1025, 36, 4100, 2), (1540, 20, 4160, 3), (1100, 52, 4097, 1), (2049, 16, 2500, 2),
-          # 512 rows and more on layers whose tiles of 512 rows fill the chip: the kernel that loads x straight into LDS, one
-          # shape per tile width it is launched with (rows, outputs and inputs all ragged: 36 and 20 inputs are 2.25 and
-          # 1.25 steps of 16, the last block of rows is short, the last tile of outputs partly outside):
-          # two samples per pass on tiles of 64 outputs; on tiles of 32 (288 of the wider ones would need two rounds);
-          # three samples: a pass of two and one on tiles of 128 outputs; one sample on tiles of 64
-          (2040, 36, 4090, 2), (1530, 20, 6100, 2), (2040, 16, 8180, 3), (1530, 20, 12002, 1),
-          # one sample on tiles of 32 outputs (the SWIN token count on 540 outputs: 255 such tiles, 75 of the widest)
-          (7260, 20, 540, 1)]
+          # more than a thousand rows on layers whose tiles of 512 rows do not fill the chip (they stay with the kernel above)
+          (1025, 36, 4100, 2), (1540, 20, 4160, 3), (1100, 52, 4097, 1), (2049, 16, 2500, 2)]
+
+# 512 rows and more on layers whose tiles of 512 or 1024 rows fill the chip: the kernel that loads x straight into LDS, one
+# layer per launch shape it has (rows, outputs and inputs all ragged: 36, 20 and 16 inputs are 2.25, 1.25 and 1 steps of 16,
+# the last block of rows is short, the last tile of outputs partly outside).  (rows, in, out, samples, launch shape as
+# hot_linear_launch_shape reports it: 100 x waves + 10 x outputs per workgroup / 32 + samples per pass, + 1000 x outputs / 32
+# of the launch for an odd last sample.)
+SLAB_SHARED = [(2040, 36, 4090, 2, 1621), (2040, 16, 8180, 3, 1621),      # 1024 rows x 64 outputs, one sample per pass
+               (1530, 20, 5400, 2, 822), (1530, 20, 6100, 2, 812),         # two samples per pass on 64 and on 32 outputs
+               (1530, 20, 5400, 3, 2822), (1530, 16, 8180, 3, 1812),       # ... followed by the third on its own
+               (1530, 20, 10800, 1, 841), (1530, 20, 14000, 1, 821), (1530, 20, 12002, 1, 811), (7260, 20, 540, 1, 811)]
+SLAB_PER_SAMPLE = [(2040, 24, 4090, 2, 1621), (1530, 24, 5300, 2, 841), (1530, 36, 7000, 2, 821), (1530, 36, 6002, 2, 811),
+                   (7260, 20, 540, 2, 811)]
+# (rows, in, out, samples, per-sample x, bias, launch shape of the input gradients): dy is the input there, its rows
+# are read in quads, and the weight tile is drawn transposed; 38 outputs are no multiple of 4: the other kernel
+SLAB_BACKWARD = [(2040, 4092, 36, 2, False, True, 1621), (1530, 5300, 36, 2, False, True, 841), (1530, 7000, 20, 2, True, False, 821),
+                 (7260, 540, 20, 2, False, True, 811), (2040, 4092, 38, 2, False, True, 0)]
+
+
+@pytest.mark.parametrize("rows,k,o,s,shape", SLAB_SHARED)
+def test_fused_layer_on_the_512_row_kernel(oracle, hot, rows, k, o, s, shape):
+    print("case linear, 512-row kernel", rows, k, o, s, shape, flush=True)
+    ldx = k + 4 if rows % 2 else k
+    assert hot.hot_linear_launch_shape(rows, k, o, s, 0, ldx=ldx) == shape
+    c = _layer(rows * 7 + k, rows, k, o, ldx=ldx)
+    rng = hot.hot_rng(seed=0xABCDEF12345, step=4, first_sample=2 * s)
+    w_off, b_off = 4 * 1000, 4 * 1000 + ((o * k + 3) // 4) * 4 + 8
+    y = _run(hot, c, s, rng, w_off, b_off)
+    worst = _check(oracle, c, y, s, rng, w_off, b_off)
+    print("  worst error / magnitude sum: %.2e" % worst, flush=True)
 
 
 @pytest.mark.parametrize("rows,k,o,s", SHAPES)
@@ -138,15 +159,16 @@ def test_layer_sees_the_w_of_hot_forward_rng(hot):
 # (rows, in, out, samples): every row-tile count, sample-chunk size and a ragged everything
 PER_SAMPLE = [(1, 8, 3, 2), (16, 128, 128, 4), (17, 36, 33, 5), (33, 100, 70, 3), (64, 128, 24, 16), (70, 64, 40, 2), (256, 192, 10, 1),
               (257, 68, 2064, 2), (700, 40, 2100, 3),      # the many-rows kernel with one input per sample
-              (1030, 24, 4100, 2), (1537, 36, 3100, 3),    # a thousand rows and more on too few tiles of 512 rows
-              (2040, 24, 4090, 2), (1530, 36, 6002, 2),    # the 512-row kernel with one input per sample: tiles of 128 and of 64 outputs
-              (7260, 20, 540, 2)]                          # ... and of 32 (510 tiles: two per compute unit)
+              (1030, 24, 4100, 2), (1537, 36, 3100, 3)]    # a thousand rows and more on too few tiles of 512 rows
 
 
-@pytest.mark.parametrize("rows,k,o,s", PER_SAMPLE)
-def test_fused_layer_with_one_input_per_sample(oracle, hot, rows, k, o, s):
-    print("case linear per-sample x", rows, k, o, s, flush=True)
-    c = _layer(rows * 13 + k, rows, k, o, ldx=k + 4 if rows % 2 else k)
+@pytest.mark.parametrize("rows,k,o,s,shape", [c + (None,) for c in PER_SAMPLE] + SLAB_PER_SAMPLE)
+def test_fused_layer_with_one_input_per_sample(oracle, hot, rows, k, o, s, shape):
+    print("case linear per-sample x", rows, k, o, s, shape, flush=True)
+    ldx = k + 4 if rows % 2 else k
+    if shape is not None:
+        assert hot.hot_linear_launch_shape(rows, k, o, s, 0, per_sample_x=True, ldx=ldx) == shape
+    c = _layer(rows * 13 + k, rows, k, o, ldx=ldx)
     g = np.random.default_rng(rows + s)
     xs = np.full((s,) + c["x"].shape, np.nan, np.float32)
     xs[:, :, :k] = g.normal(size=(s, rows, k))
@@ -214,22 +236,17 @@ BACKWARD = [(1, 4, 1, 1, False, True, True), (16, 64, 16, 2, False, True, True),
             (600, 516, 1840, 2, False, True, False), (515, 1028, 3900, 1, False, True, False),
             # many rows: the input-gradient kernel whose waves share the draws (odd O: dy rows only dword-aligned,
             # a last partial step of outputs; O a multiple of the step)
-            (520, 516, 33, 8, False, True, True), (1100, 1028, 48, 2, True, False, True),
-            # many rows on a layer whose dx fills the chip with tiles of 512 rows: the forward pass's 512-row kernel with
-            # the weight tile drawn transposed, on tiles of 128 and of 64 inputs (36 and 20 outputs are 2.25 and 1.25
-            # steps, the last block of rows and the last tile of inputs ragged); the same rows with an output count
-            # that is no multiple of 4 (rows of dy not readable in quads: the other kernel)
-            (2040, 4092, 36, 2, False, True, True), (1530, 7000, 20, 2, True, False, True), (2040, 4092, 38, 2, False, True, True),
-            # ... and on tiles of 32 inputs (the SWIN token count, 540 inputs)
-            (7260, 540, 20, 2, False, True, True)]
+            (520, 516, 33, 8, False, True, True), (1100, 1028, 48, 2, True, False, True)]
 
 
-@pytest.mark.parametrize("rows,k,o,s,xs,bias,want_dx", BACKWARD)
-def test_fused_layer_backward_matches_oracle(oracle, hot, rows, k, o, s, xs, bias, want_dx):
+@pytest.mark.parametrize("rows,k,o,s,xs,bias,want_dx,shape", [c + (None,) for c in BACKWARD] + [c[:6] + (True, c[6]) for c in SLAB_BACKWARD])
+def test_fused_layer_backward_matches_oracle(oracle, hot, rows, k, o, s, xs, bias, want_dx, shape):
     """Weight, bias and input gradients of the fused layer against the fp64 oracle, each within 1e-5
     of the sum of the magnitudes of its addends (eps taken at its Box-Muller radius, which also
     covers the 2e-6 r error of the fp32 draw)."""
-    print("case linear backward", rows, k, o, s, xs, bias, want_dx, flush=True)
+    print("case linear backward", rows, k, o, s, xs, bias, want_dx, shape, flush=True)
+    if shape is not None:
+        assert hot.hot_linear_launch_shape(rows, k, o, s, 1, per_sample_x=xs) == shape
     c = _layer(rows * 17 + k + o, rows, k, o)
     g = np.random.default_rng(rows + 3 * s)
     if xs:

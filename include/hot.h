@@ -223,12 +223,12 @@ int hot_last_hip_error(const hot_plan *plan);
  * fp32 (v_mfma_f32_16x16x4_f32, v_mfma_f32_32x32x2_f32).  Runs on the current device, asynchronous on `stream`.
  * Up to a few hundred rows a wave draws the weights it multiplies (re-drawing eps per block of 64
  * rows is then cheaper than writing and re-reading w); from 256 rows on, given at least 128 workgroups
- * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS; from 1024 rows on,
- * given at least 192 workgroups of 512 rows x 64 outputs, eight waves share it and x is staged through LDS
- * too (92-115 TFLOP/s, up to 73 % of the fp32 matrix peak).  The draw and the matrix instructions do not
- * overlap on this chip; against writing w once with hot_forward_rng and calling a library GEMM the call is
- * 1.8-2.9x faster up to tens of rows, level at 64 rows and at a Swin layer's 7260 rows, and 0.8x on the
- * largest squares.
+ * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS; from 512 rows on,
+ * where tiles of 512 or 1024 rows x 32 to 128 outputs fill the chip (hot_linear_launch_shape tells), eight or
+ * sixteen waves share it and x goes from memory straight into LDS (110-140 TFLOP/s, up to 89 % of the fp32
+ * matrix peak).  The draw and the matrix instructions do not overlap on this chip; against writing w once
+ * with hot_forward_rng and calling a library GEMM the call is 1.8-2.9x faster up to tens of rows, level at
+ * 64 rows, 1.2-1.35x at the 7260 and 16640 rows of a Swin and a ViT layer, and level on the largest squares.
  */
 typedef struct hot_linear_desc {
     int64_t rows;          /* R >= 1: rows of x (batch x tokens) */
@@ -264,12 +264,15 @@ int hot_linear_forward_rng(const hot_linear_desc *desc, const hot_rng *rng, cons
  * 1 048 560 and s_local <= 65 535 (grid limits; HOT_EINVAL beyond, before anything runs).  Other arguments
  * and rules as for hot_linear_forward_rng.  Every weight is drawn once per sample (and per wave that
  * shares its tile) for the weight gradients, and for dx once per block of 64 rows, or, from 256 rows
- * on, once per workgroup of 64 to 256 rows (its waves share the draws through LDS).  Large layers
+ * on, once per workgroup of 64 to 256 rows (its waves share the draws through LDS), or, where tiles of 512
+ * or 1024 rows fill the chip, once per such tile (the forward pass's kernel for many rows with dy as its
+ * input; it needs out_features to be a multiple of 4 and dy 16-byte aligned).  Large layers
  * (from 256 rows on, at least two tiles of 128 inputs x 128 outputs per compute unit) take their weight
- * gradients from a kernel that stages x and dy through LDS (up to 134 TFLOP/s); it needs out_features to
- * be a multiple of 4 and rows * max(ldx, out_features) * 4 below 4 GiB, else the first kernel runs.  Against
+ * gradients from a kernel that stages x and dy through LDS (up to 138 TFLOP/s); it needs out_features to
+ * be a multiple of 4 and rows * max(ldx, out_features) * 4 below 4 GiB, else the first kernel runs; with more
+ * than two samples it adds up pairs of samples in grad_mu_w and grad_sigma_w themselves.  Against
  * library GEMMs for dx and G followed by hot_backward_rng the call is 1.1-3x faster up to tens of rows and at
- * 0.8-1.1x for thousands of rows.
+ * 1.0-1.35x for thousands of rows.
  */
 int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double dataset_size, uint32_t flags,
                             const hot_rng *rng, const float *x, const float *dy, const float *mu_w,

@@ -1221,24 +1221,28 @@ void wgrad_go(long tiles, int waves, hipStream_t s, const LinearGradArgs &a)
 // ---------------------------------------------------------------------------------
 // Weight gradients of large layers.  The kernel above gives a wave a tile of 16-32 outputs x 64 inputs, about 10
 // flops per byte it loads: at thousands of rows the second-level caches cannot feed that (the matrix pipes were 42 %
-// busy).  Here a workgroup of four waves owns 128 inputs x 128 outputs and takes 32 rows of x and of dy at a time
+// busy).  Here a workgroup of four waves owns 128 inputs x 128 outputs and takes 16 rows of x and of dy at a time
 // through LDS (32 flops per byte loaded).  The rows go from memory straight into LDS (buffer loads with the LDS
 // bit, 16 bytes per lane, consecutive lanes on consecutive addresses): no registers and no vector-ALU instruction
 // carry them.  A wave multiplies its 64 inputs x 64 outputs as 2 x 2 blocks of v_mfma_f32_32x32x2_f32 with x as
 // the A operand and dy as the B operand, so result registers 4 q .. 4 q + 3 of a lane are the inputs
-// 8 q + 4 (lane / 32) .. + 3 of output lane % 32: one generator quad, as above.  Two pairs of buffers alternate: the
-// rows of step i + 1 are sent for before the matrix instructions of step i, one barrier per step; two workgroups
-// share a compute unit, so one's barrier is covered by the other's matrix instructions.  Rows beyond the last
+// 8 q + 4 (lane / 32) .. + 3 of output lane % 32: one generator quad, as above.  Four pairs of buffers take turns: the
+// rows of a step are sent for three steps ahead, and the one barrier of a step lies in its middle, with the operands
+// of the matrix instructions behind it already in registers (see the row loop); two workgroups share a compute unit,
+// so what one still waits for is covered by the other's matrix instructions.  Rows beyond the last
 // and columns beyond the layer are masked by offsets outside the range-checked windows and arrive as zeros; a wave
 // skips the 32 x 32 blocks that lie outside the layer altogether.  The finished sums leave through LDS so that
 // every store instruction covers 128 contiguous bytes per row of the gradient arrays.
 // Vector-ALU instructions are kept out of the row loop as far as possible, since each takes its cycles from the
 // matrix instructions: the lanes' offsets advance by a uniform step, rows are masked by one comparison per load,
 // and the LDS reads carry their offsets as immediates (volatile: merged into two-address reads they needed a
-// computed base register each).  Measured on the way: the same tile with 16-row steps staged through registers,
-// 123 TFLOP/s at 4096^3 against 134 now (the kernel above: 114, the library's GEMM alone: 146); tiles of 64 inputs
-// x 256 outputs, 2-8 % slower; row parts through a workspace for layers of fewer tiles, behind the kernel above
-// (7260 x 540 x 2160, five or six parts: 0.46-0.49 against 0.42 ms; 16640 x 192 x 768: 0.21 against 0.17 ms).
+// computed base register each).  Measured on the way, at 4096^3 with two samples: 16-row steps staged through
+// registers 123 TFLOP/s; 32-row steps straight into two pairs of LDS buffers, one barrier at the end of a step, one
+// set of accumulators for all samples with the eps-weighted sum built by summation by parts (two draws per sample)
+// 134; this form 136-139 (the kernel above: 114, the library's GEMM alone: 146) and at 1024 x 8192^2, where the
+// draws weigh more, 119 -> 127; tiles of 64 inputs x 256 outputs, 2-8 % slower; row parts through a workspace for
+// layers of fewer tiles, behind the kernel above (7260 x 540 x 2160, five or six parts: 0.46-0.49 against 0.42 ms;
+// 16640 x 192 x 768: 0.21 against 0.17 ms).
 // ---------------------------------------------------------------------------------
 constexpr int kTileSide = 128;        // inputs and outputs per workgroup
 constexpr int kTileRows = 16;         // rows per step

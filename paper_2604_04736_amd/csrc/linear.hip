@@ -657,9 +657,11 @@ inline bool slab_kernel_fits(long rows, long contract, long outs, long ld_in)
 constexpr int kComputeUnits = 256;
 constexpr int kSlabMinRows = 512;             // below, the kernels whose workgroups hold 256 rows
 // Least share of the chip's time that the tiles of a launch must fill, measured against the kernels for fewer rows on 130
-// layer shapes: the forward pass wins from 0.6 on (1.1-2x), the input gradients, whose other kernel packs several 256-row
-// workgroups into a compute unit, from 0.72 on (1.0-1.2x; 0.8-0.9x between 0.6 and 0.7).
-constexpr double kSlabMinFillForward = 0.6, kSlabMinFillInputGrad = 0.72;
+// layer shapes.  Forward with a shared x: wins from 0.6 on (1.1-2x; between 0.45 and 0.6 anything from 0.73x to 1.2x).
+// Forward with one x per sample, where the other kernel is weaker: from 0.45 on (1.4-1.5x between 0.45 and 0.6).  Input
+// gradients, whose other kernel packs several 256-row workgroups into a compute unit: from 0.72 on (1.0-1.3x), and from
+// 0.6 on where the tiles of 32 inputs are the best shape (1.0-1.2x there; the wider shapes 0.95-0.97x).
+constexpr double kSlabMinFillForward = 0.6, kSlabMinFillForwardOwnX = 0.45, kSlabMinFillInputGrad = 0.72, kSlabMinFillInputGradNarrow = 0.6;
 
 // A launch shape of the kernel above and what it costs.  One workgroup per compute unit runs at a time (two of the narrow
 // ones, at half speed each), so a launch takes its number of rounds times the time of a workgroup, which per step is, per
@@ -724,12 +726,14 @@ void slab_go_singles(const SlabShape &shape, hipStream_t s, const SlabArgs &a, i
 }
 
 // the cheaper of the shapes with one sample per pass, or none where the chip would stand too empty
-inline SlabShape slab_shape_singles(long rows, long outs, long samples, double min_fill)
+// (min_fill_narrow: the bar where that shape has tiles of 32 outputs)
+inline SlabShape slab_shape_singles(long rows, long outs, long samples, double min_fill, double min_fill_narrow)
 {
     SlabShape best = slab_shape8(rows, outs, samples, 1, 1, 4);
     const SlabShape tall = slab_shape16(rows, outs, samples);
     if (tall.waves && (!best.waves || tall.cost < best.cost)) best = tall;
-    if (best.waves && slab_full(rows, outs, samples) < min_fill * best.cost) best.waves = 0;
+    const double bar = best.waves == 8 && best.cbw == 1 ? min_fill_narrow : min_fill;
+    if (best.waves && slab_full(rows, outs, samples) < bar * best.cost) best.waves = 0;
     return best;
 }
 
@@ -746,7 +750,8 @@ inline SlabForwardPlan slab_forward_plan(const hot_linear_desc *d)
     if (d->rows < kSlabMinRows || !slab_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) return p;
     const int S = d->s_local;
     if (d->x_sample_stride != 0 || S == 1) {
-        p.one = slab_shape_singles(d->rows, d->out_features, S, kSlabMinFillForward);
+        const double bar = d->x_sample_stride != 0 ? kSlabMinFillForwardOwnX : kSlabMinFillForward;
+        p.one = slab_shape_singles(d->rows, d->out_features, S, bar, bar);
         return p;
     }
     // two samples to a pass and an odd last one on its own, or every sample on its own in the tall shape
@@ -771,7 +776,7 @@ inline SlabShape slab_input_grad_shape(const hot_linear_desc *d, bool dy_aligned
     if (d->rows < kSlabMinRows || (d->out_features & 3) != 0 || !dy_aligned ||
         !slab_kernel_fits(d->rows, d->out_features, d->in_features, d->out_features))
         return SlabShape{0, 0, 0.0};
-    return slab_shape_singles(d->rows, d->in_features, d->s_local, kSlabMinFillInputGrad);
+    return slab_shape_singles(d->rows, d->in_features, d->s_local, kSlabMinFillInputGrad, kSlabMinFillInputGradNarrow);
 }
 
 template <int RB, bool XS>

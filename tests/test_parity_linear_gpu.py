@@ -731,6 +731,79 @@ def test_random_layer_shapes_forward_and_dx_against_materialised_weights(hot):
         assert bool(((gw[0].double() - want_g).abs() <= 1e-5 * A_g + 1e-30).all()), "grad_mu_w"
 
 
+def test_random_layers_on_the_512_row_kernel_against_materialised_weights(hot):
+    """Seeded random layer sizes that the forward call or the input gradients give to the 512/1024-row kernel
+    (hot_linear_launch_shape says so; sizes that neither does are skipped): y and dx against fp64 products on the GPU with the
+    weights that hot_forward_rng materialises, as in the test above.  Every launch shape has to come up."""
+    rs = np.random.default_rng(23)
+    done, seen = 0, set()
+    for _ in range(50000):
+        if done == 24:
+            break
+        rows = int(rs.integers(512, 9000))
+        k = 4 * int(rs.choice([rs.integers(1, 24), rs.integers(24, 400)]))
+        o = int(rs.choice([rs.integers(100, 1200), rs.integers(1200, 9000)]))
+        if rs.integers(0, 3) == 0:
+            o = 4 * (o // 4 + 1)                      # rows of dy readable in quads: the input gradients may take the kernel too
+        s = int(rs.integers(1, 5))
+        bias, xs = bool(rs.integers(0, 2)), bool(rs.integers(0, 2))
+        if rows * o * s > 1.2e8 or rows * k * o * s > 2e10:
+            continue
+        f = hot.hot_linear_launch_shape(rows, k, o, s, 0, per_sample_x=xs)
+        d = hot.hot_linear_launch_shape(rows, k, o, s, 1, per_sample_x=xs)
+        # what the case would add: ("two", pair shape), ("last", outputs / 32 of an odd last sample's launch), ("one", single
+        # shape of the forward call), ("dx", shape of the input gradients)
+        pair = f % 1000 in (812, 822)
+        new = {("two", f % 1000), ("last", f // 1000)} if pair else {("one", f)}
+        new = {c for c in new | {("dx", d)} if c[1] != 0} - seen
+        if (f == 0 and d == 0) or (done >= 12 and not new):       # (after a dozen cases only shapes not yet seen)
+            continue
+        seen |= new
+        done += 1
+        print("case", done, rows, k, o, s, bias, xs, "shapes", f, d, flush=True)
+        g = torch.Generator(device=DEV).manual_seed(500 + done)
+        x = torch.randn((s, rows, k) if xs else (rows, k), device=DEV, generator=g)
+        n_w = o * k
+        b_off = n_w + 8
+        n = b_off + ((o + 3) // 4) * 4
+        mu = torch.randn(n, device=DEV, generator=g) * 0.1
+        sigma = torch.rand(n, device=DEV, generator=g) * 0.05 + 0.01
+        rng = hot.hot_rng(seed=29, step=done, first_sample=5)
+        plan = hot.hot_create(n, n, s, s, 1.0, 0)
+        w = torch.empty(s, n, device=DEV)
+        hot.hot_forward_rng(plan, rng, mu, sigma, w)
+        hot.hot_destroy(plan)
+        mu_w, sg_w = mu[:n_w].view(o, k), sigma[:n_w].view(o, k)
+        mu_b, sg_b = (mu[b_off:b_off + o], sigma[b_off:b_off + o]) if bias else (None, None)
+        y = torch.full((s, rows, o), float("nan"), device=DEV)
+        hot.hot_linear_forward_rng(rng, x, mu_w, sg_w, mu_b, sg_b, y, 0, b_off)
+        dy = torch.randn(s, rows, o, device=DEV, generator=g)
+        dx = torch.full((s, rows, k), float("nan"), device=DEV)
+        gw = [torch.empty(o, k, device=DEV), torch.empty(o, k, device=DEV)]
+        gb = [torch.empty(o, device=DEV), torch.empty(o, device=DEV)] if bias else [None, None]
+        hot.hot_linear_backward_rng(rng, x, dy, mu_w, sg_w, mu_b, sg_b, gw[0], gw[1], gb[0], gb[1], dx, s, 100.0,
+                                    hot.HOT_REDUCE_SUM, 0, b_off)
+        torch.cuda.synchronize()
+        for si in range(s):                              # one sample at a time: the fp64 products are large
+            w2 = w[si, :n_w].view(o, k).double()
+            x2 = (x[si] if xs else x).double()
+            want_y, A_y = x2 @ w2.T, x2.abs() @ w2.abs().T
+            if bias:
+                want_y = want_y + w[si, b_off:b_off + o].double()
+                A_y = A_y + w[si, b_off:b_off + o].double().abs()
+            assert bool(torch.isfinite(y[si]).all()) and bool(((y[si].double() - want_y).abs() <= 1e-5 * A_y + 1e-30).all()), "y"
+            del want_y, A_y
+            d2 = dy[si].double()
+            want_dx, A_dx = d2 @ w2, d2.abs() @ w2.abs()
+            assert bool(torch.isfinite(dx[si]).all()) and bool(((dx[si].double() - want_dx).abs() <= 1e-5 * A_dx + 1e-30).all()), "dx"
+            del want_dx, A_dx, d2, w2, x2
+        del x, w, y, dy, dx, gw
+        torch.cuda.empty_cache()
+    # forward: pairs on 32 and 64 outputs, single samples on 32 to 128 and in the 1024-row shape, an odd last sample; input gradients
+    assert {("two", 812), ("two", 822), ("one", 811), ("one", 821), ("one", 841), ("one", 1621)} <= seen, sorted(seen)
+    assert {("dx", 811), ("dx", 821), ("dx", 841), ("dx", 1621)} <= seen and any(c[0] == "last" for c in seen), sorted(seen)
+
+
 # (rows, in, out, samples, per-sample x, bias)
 TILED = [(300, 2900, 4228, 2, False, True),      # 23 x 34 tiles of 128 x 128, ragged in rows, inputs and outputs
          (272, 2048, 4096, 3, True, False),      # 16 x 32 whole tiles, three samples with inputs of their own

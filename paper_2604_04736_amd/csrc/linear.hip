@@ -1406,7 +1406,7 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
         const MfmaSettled settled;
 
         long o0e = o0 + 64 * wo, k0e = k0 + 64 * wk;
-        asm volatile("" : "+s"(o0e), "+s"(k0e));       // (so that the addresses below are formed here, not ahead of the row loops)
+        asm volatile("" : "+v"(o0e), "+v"(k0e));       // (so that the addresses below are formed here, not ahead of the row loops)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll

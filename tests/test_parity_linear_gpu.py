@@ -237,7 +237,11 @@ BACKWARD = [(1, 4, 1, 1, False, True, True), (16, 64, 16, 2, False, True, True),
             (600, 516, 1840, 2, False, True, False), (515, 1028, 3900, 1, False, True, False),
             # many rows: the input-gradient kernel whose waves share the draws (odd O: dy rows only dword-aligned,
             # a last partial step of outputs; O a multiple of the step)
-            (520, 516, 33, 8, False, True, True), (1100, 1028, 48, 2, True, False, True)]
+            (520, 516, 33, 8, False, True, True), (1100, 1028, 48, 2, True, False, True),
+            # up to 64 rows on thousands of tiles, a tile per wave (one to four 16-row blocks, the last one ragged; 2052
+            # inputs are 32 tiles and 4 columns, 4100 outputs 256 groups and 4; one x per sample; no bias)
+            (16, 2052, 4100, 2, False, True, False), (20, 4100, 2052, 3, True, False, False), (40, 2052, 4100, 1, False, True, False),
+            (50, 2052, 4100, 2, False, True, True), (64, 516, 2100, 4, True, True, False)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias,want_dx,shape", [c + (None,) for c in BACKWARD] + [c[:6] + (True, c[6]) for c in SLAB_BACKWARD])

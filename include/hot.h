@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 210 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 300 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,

@@ -107,7 +107,7 @@ def test_launch_shape_query_over_many_shapes_is_consistent(hot):
 
 
 def test_host_only_entry_points(hot):
-    assert hot.hot_version() == 210
+    assert hot.hot_version() == 300
     assert hot.hot_strerror(0) == "success"
     assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
     assert hot.hot_strerror(-99) == "unknown error code"

@@ -223,9 +223,9 @@ int hot_last_hip_error(const hot_plan *plan);
  * fp32 (v_mfma_f32_16x16x4_f32, v_mfma_f32_32x32x2_f32).  Runs on the current device, asynchronous on `stream`.
  * Up to a few hundred rows a wave draws the weights it multiplies (re-drawing eps per block of 64
  * rows is then cheaper than writing and re-reading w); from 256 rows on, given at least 128 workgroups
- * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS; from 512 rows on,
- * where tiles of 512 or 1024 rows x 32 to 128 outputs fill the chip (hot_linear_launch_shape tells), eight or
- * sixteen waves share it and x goes from memory straight into LDS (110-140 TFLOP/s, up to 89 % of the fp32
+ * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS; where tiles of 256, 512
+ * or 1024 rows x 32 to 128 outputs fill the chip (hot_linear_launch_shape tells), four, eight or sixteen waves
+ * share it and x goes from memory straight into LDS (110-140 TFLOP/s, up to 89 % of the fp32
  * matrix peak).  The draw and the matrix instructions do not overlap on this chip; against writing w once
  * with hot_forward_rng and calling a library GEMM the call is 1.8-2.9x faster up to tens of rows, level at
  * 64 rows, 1.2-1.35x at the 7260 and 16640 rows of a Swin and a ViT layer, and level on the largest squares.
@@ -283,9 +283,10 @@ int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double
  * Which launch shape the calls above choose for a layer (host arithmetic only; for tests and for tuning, same
  * passages of the paper).  which = 0: hot_linear_forward_rng; which = 1: the input-gradient part of
  * hot_linear_backward_rng (dy taken to be 16-byte aligned).  Returns 0 where the layer goes to the kernels for up
- * to a few hundred rows per workgroup; else, for the kernel with 512 or 1024 rows per workgroup,
+ * to a few hundred rows per workgroup; else, for the kernel with 256, 512 or 1024 rows per workgroup (64 per wave),
  * 100 * waves + 10 * (outputs per workgroup / 32) + samples per pass of its (first) launch, e.g. 822: eight waves
  * (512 rows), 64 outputs, two samples per pass; 1621: sixteen waves (1024 rows), 64 outputs, one sample per pass;
+ * 412: four waves (256 rows), 32 outputs, two samples per pass;
  * plus 1000 * (outputs per workgroup / 32) of a second launch that takes an odd last sample on its own.
  * HOT_EINVAL for a malformed desc or another `which`.
  */

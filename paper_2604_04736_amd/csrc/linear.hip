@@ -19,7 +19,7 @@
 // Kernels of this file, by regime:
 //   forward   hot_linear_forward_kernel        up to a few hundred rows: every wave draws what it multiplies
 //             hot_linear_forward_rows_kernel   from 256 rows: four waves x 64 rows share every draw through LDS
-//             hot_linear_slab_kernel           from 512 rows on layers that fill the chip: 512 rows x 32 to 128 outputs per
+//             hot_linear_slab_kernel           from 256 rows on layers that fill the chip: 256 to 1024 rows x 32 to 128 outputs per
 //                                              workgroup, x loaded straight into LDS, the drawn weights shared through it,
 //                                              v_mfma_f32_32x32x2_f32; also the input gradients of such layers
 //   backward  hot_linear_wgrad_kernel          weight and bias gradients (per-sample G never stored); variants for
@@ -460,8 +460,9 @@ __device__ __forceinline__ void everything_arrived_then_barrier()
 // any 8 and any 16 consecutive rows then put a given q into different banks
 __device__ __forceinline__ int slab_swizzle(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
 
-// WAVES: 8 or 16 waves of 64 rows each (16: half the draw per row again; their registers then allow 64 outputs and one
-// sample); CBW: blocks of 32 outputs per workgroup (every wave multiplies its 64 rows by all of them); ST samples per pass
+// WAVES: 4, 8 or 16 waves of 64 rows each (16: half the draw per row again; their registers then allow 64 outputs and one
+// sample; 4: for layers that 512 rows per workgroup fill badly: twice the draw per row, but up to four such workgroups
+// share a compute unit, one's matrix instructions covering what the others wait for); CBW: blocks of 32 outputs per workgroup (every wave multiplies its 64 rows by all of them); ST samples per pass
 // (they share the input tile); OWN: every sample has an input of its own (then ST = 1).
 template <int WAVES, int CBW, int ST, bool OWN, bool TR>
 __global__ void __launch_bounds__(64 * WAVES, CBW * ST <= 2 ? 4 : 2)
@@ -469,7 +470,7 @@ hot_linear_slab_kernel(SlabArgs a)
 {
     static_assert(ST == 1 || ST == 2, "one or two samples per pass");
     static_assert(!OWN || ST == 1, "one input per sample: one sample per pass");
-    static_assert(WAVES == 8 || (WAVES == 16 && CBW * ST <= 2), "sixteen waves have 128 registers each");
+    static_assert(WAVES == 8 || ((WAVES == 16 || WAVES == 4) && CBW * ST <= 2), "sixteen waves have 128 registers each, and so have four: four such workgroups share a compute unit");
     constexpr int RBW = 2, WROWS = 32 * RBW, OUTS = 32 * CBW, KS = kSlabK;
     constexpr int XW = WROWS * KS;           // floats of a wave's region of x
     constexpr int WT = OUTS * KS;            // floats of one sample's weight tile
@@ -669,10 +670,31 @@ constexpr double kSlabMinFillForward = 0.6, kSlabMinFillForwardOwnX = 0.45, kSla
 // 600 for the barrier and what else does not overlap; the wider tile also loads x half as often.  The constants are
 // fitted to timings of 130 layer shapes; the model only has to rank the shapes of one layer.
 struct SlabShape {
-    int waves;      // 8 or 16; 0: none
+    int waves;      // 4, 8 or 16; 0: none
     int cbw;        // blocks of 32 outputs per workgroup
     double cost;
 };
+
+// Four waves: 256 rows x 32 or 64 output-samples.  Up to four such workgroups share a compute unit and run at the rate of
+// its matrix pipes together (measured per step and workgroup: 2700 cycles for 64 output-samples, 1600 for 32, whose x is
+// re-read twice as often), one alone at that plus 600.  Against the kernels for few rows they win from a fill of 0.52 of the
+// compute units' last workgroup on (measured on 160 layer shapes of 256 to 7260 rows: 1.1-2.2x from there, 0.3-0.9x below).
+constexpr double kSlab4MinFill = 0.52;
+
+inline SlabShape slab_shape4(long rows, long outs, long passes, int st)
+{
+    SlabShape best = {0, 0, 0.0};
+    if (passes < 1 || passes > 65535 || rows < 256) return best;
+    for (int cbw = st == 2 ? 1 : 2; cbw >= 1; cbw /= 2) {
+        const long col_tiles = (outs + 32 * cbw - 1) / (32 * cbw), wgs = col_tiles * ((rows + 255) / 256) * passes;
+        const long per_cu = (wgs + kComputeUnits - 1) / kComputeUnits;
+        const double exact = (double)outs / (32 * cbw) * (double)rows / 256.0 * (double)passes;
+        if (exact < kSlab4MinFill * (double)(per_cu * kComputeUnits)) continue;
+        const double cost = (double)per_cu * (cbw * st == 2 ? 2700.0 : 1600.0) + (per_cu == 1 ? 600.0 : 0.0);
+        if (best.waves == 0 || cost < best.cost) best = SlabShape{4, cbw, cost};
+    }
+    return best;
+}
 
 // the cheapest of the eight-wave shapes with `st` samples per pass and tiles of 32 * narrow .. 32 * wide outputs
 inline SlabShape slab_shape8(long rows, long outs, long passes, int st, int narrow, int wide)
@@ -720,6 +742,8 @@ template <bool OWN, bool TR>
 void slab_go_singles(const SlabShape &shape, hipStream_t s, const SlabArgs &a, int s_begin, int s_end)
 {
     if (shape.waves == 16) slab_go<16, 2, 1, OWN, TR>(s, a, s_begin, s_end);
+    else if (shape.waves == 4 && shape.cbw == 2) slab_go<4, 2, 1, OWN, TR>(s, a, s_begin, s_end);
+    else if (shape.waves == 4) slab_go<4, 1, 1, OWN, TR>(s, a, s_begin, s_end);
     else if (shape.cbw == 4) slab_go<8, 4, 1, OWN, TR>(s, a, s_begin, s_end);
     else if (shape.cbw == 2) slab_go<8, 2, 1, OWN, TR>(s, a, s_begin, s_end);
     else slab_go<8, 1, 1, OWN, TR>(s, a, s_begin, s_end);
@@ -729,11 +753,16 @@ void slab_go_singles(const SlabShape &shape, hipStream_t s, const SlabArgs &a, i
 // (min_fill_narrow: the bar where that shape has tiles of 32 outputs)
 inline SlabShape slab_shape_singles(long rows, long outs, long samples, double min_fill, double min_fill_narrow)
 {
-    SlabShape best = slab_shape8(rows, outs, samples, 1, 1, 4);
-    const SlabShape tall = slab_shape16(rows, outs, samples);
-    if (tall.waves && (!best.waves || tall.cost < best.cost)) best = tall;
-    const double bar = best.waves == 8 && best.cbw == 1 ? min_fill_narrow : min_fill;
-    if (best.waves && slab_full(rows, outs, samples) < bar * best.cost) best.waves = 0;
+    SlabShape best = {0, 0, 0.0};
+    if (rows >= kSlabMinRows) {
+        best = slab_shape8(rows, outs, samples, 1, 1, 4);
+        const SlabShape tall = slab_shape16(rows, outs, samples);
+        if (tall.waves && (!best.waves || tall.cost < best.cost)) best = tall;
+        const double bar = best.waves == 8 && best.cbw == 1 ? min_fill_narrow : min_fill;
+        if (best.waves && slab_full(rows, outs, samples) < bar * best.cost) best.waves = 0;
+    }
+    const SlabShape small = slab_shape4(rows, outs, samples, 1);
+    if (small.waves && (!best.waves || small.cost < best.cost)) best = small;
     return best;
 }
 
@@ -747,25 +776,41 @@ struct SlabForwardPlan {
 inline SlabForwardPlan slab_forward_plan(const hot_linear_desc *d)
 {
     SlabForwardPlan p = {0, SlabShape{0, 0, 0.0}, SlabShape{0, 0, 0.0}};
-    if (d->rows < kSlabMinRows || !slab_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) return p;
+    if (d->rows < 256 || !slab_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) return p;
     const int S = d->s_local;
     if (d->x_sample_stride != 0 || S == 1) {
         const double bar = d->x_sample_stride != 0 ? kSlabMinFillForwardOwnX : kSlabMinFillForward;
         p.one = slab_shape_singles(d->rows, d->out_features, S, bar, bar);
         return p;
     }
-    // two samples to a pass and an odd last one on its own, or every sample on its own in the tall shape
+    // two samples to a pass and an odd last one on its own (512-row or 256-row workgroups), or every sample on its own in the
+    // tall shape: whichever is cheapest among those that fill the chip well enough
     const int pairs = S / 2, odd = S & 1;
-    const SlabShape two = slab_shape8(d->rows, d->out_features, pairs, 2, 1, 2);
-    const SlabShape last = odd ? slab_shape8(d->rows, d->out_features, 1, 1, 1, 4) : SlabShape{8, 0, 0.0};
-    const SlabShape tall = slab_shape16(d->rows, d->out_features, S);
-    const double full = slab_full(d->rows, d->out_features, S);
-    if (tall.waves && (!two.waves || !last.waves || tall.cost < two.cost + last.cost)) {
-        if (full >= kSlabMinFillForward * tall.cost) p.one = tall;
-    } else if (two.waves && last.waves && full >= kSlabMinFillForward * (two.cost + last.cost)) {
+    const SlabShape none = {0, 0, 0.0}, free = {8, 0, 0.0};
+    double best = 0.0;
+    if (d->rows >= kSlabMinRows) {
+        const SlabShape two = slab_shape8(d->rows, d->out_features, pairs, 2, 1, 2);
+        const SlabShape last = odd ? slab_shape8(d->rows, d->out_features, 1, 1, 1, 4) : free;
+        const SlabShape tall = slab_shape16(d->rows, d->out_features, S);
+        const double full = slab_full(d->rows, d->out_features, S);
+        if (tall.waves && (!two.waves || !last.waves || tall.cost < two.cost + last.cost)) {
+            if (full >= kSlabMinFillForward * tall.cost) {
+                p.one = tall;
+                best = tall.cost;
+            }
+        } else if (two.waves && last.waves && full >= kSlabMinFillForward * (two.cost + last.cost)) {
+            p.pair_samples = 2 * pairs;
+            p.two = two;
+            p.one = odd ? last : none;
+            best = two.cost + last.cost;
+        }
+    }
+    const SlabShape two4 = slab_shape4(d->rows, d->out_features, pairs, 2);
+    const SlabShape last4 = odd ? slab_shape4(d->rows, d->out_features, 1, 1) : free;
+    if (two4.waves && last4.waves && (best == 0.0 || two4.cost + last4.cost < best)) {
         p.pair_samples = 2 * pairs;
-        p.two = two;
-        if (odd) p.one = last;
+        p.two = two4;
+        p.one = odd ? last4 : none;
     }
     return p;
 }
@@ -773,7 +818,7 @@ inline SlabForwardPlan slab_forward_plan(const hot_linear_desc *d)
 // ... and the input gradients (dy is the input, read in 16-byte quads: rows of dy must allow that)
 inline SlabShape slab_input_grad_shape(const hot_linear_desc *d, bool dy_aligned)
 {
-    if (d->rows < kSlabMinRows || (d->out_features & 3) != 0 || !dy_aligned ||
+    if (d->rows < 256 || (d->out_features & 3) != 0 || !dy_aligned ||
         !slab_kernel_fits(d->rows, d->out_features, d->in_features, d->out_features))
         return SlabShape{0, 0, 0.0};
     return slab_shape_singles(d->rows, d->in_features, d->s_local, kSlabMinFillInputGrad, kSlabMinFillInputGradNarrow);
@@ -1984,7 +2029,8 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
         b.sigma_b = sigma_b;
         b.out = y;
         b.rng = r;
-        if (plan.two.waves) {
+        if (plan.two.waves == 4) slab_go<4, 1, 2, false, false>(s, b, 0, plan.pair_samples);
+        else if (plan.two.waves) {
             if (plan.two.cbw == 2) slab_go<8, 2, 2, false, false>(s, b, 0, plan.pair_samples);
             else slab_go<8, 1, 2, false, false>(s, b, 0, plan.pair_samples);
         }

@@ -78,21 +78,26 @@ SHAPES = [(64, 96, 128, 4), (64, 128, 24, 4), (65, 192, 576, 4), (256, 192, 10, 
           # more than a thousand rows on layers whose tiles of 512 rows do not fill the chip (they stay with the kernel above)
           (1025, 36, 4100, 2), (1540, 20, 4160, 3), (1100, 52, 4097, 1), (2049, 16, 2500, 2)]
 
-# 512 rows and more on layers whose tiles of 512 or 1024 rows fill the chip: the kernel that loads x straight into LDS, one
+# 256 rows and more on layers whose tiles of 256, 512 or 1024 rows fill the chip: the kernel that loads x straight into LDS, one
 # layer per launch shape it has (rows, outputs and inputs all ragged: 36, 20 and 16 inputs are 2.25, 1.25 and 1 steps of 16,
 # the last block of rows is short, the last tile of outputs partly outside).  (rows, in, out, samples, launch shape as
 # hot_linear_launch_shape reports it: 100 x waves + 10 x outputs per workgroup / 32 + samples per pass, + 1000 x outputs / 32
 # of the launch for an odd last sample.)
 SLAB_SHARED = [(2040, 36, 4090, 2, 1621), (2040, 16, 8180, 3, 1621),      # 1024 rows x 64 outputs, one sample per pass
-               (1530, 20, 5400, 2, 822), (1530, 20, 6100, 2, 812),         # two samples per pass on 64 and on 32 outputs
+               (1530, 20, 5400, 2, 822), (1000, 20, 2902, 2, 812),         # two samples per pass on 64 and on 32 outputs
                (1530, 20, 5400, 3, 2822), (1530, 16, 8180, 3, 1812),       # ... followed by the third on its own
-               (1530, 20, 10800, 1, 841), (1530, 20, 14000, 1, 821), (1530, 20, 12002, 1, 811), (7260, 20, 540, 1, 811)]
-SLAB_PER_SAMPLE = [(2040, 24, 4090, 2, 1621), (1530, 24, 5300, 2, 841), (1530, 36, 7000, 2, 821), (1530, 36, 6002, 2, 811),
-                   (7260, 20, 540, 2, 811)]
+               (1530, 20, 10800, 1, 841), (1530, 20, 14000, 1, 821), (7260, 20, 540, 1, 811),
+               # 256 rows per workgroup (four waves), for layers that tiles of 512 rows fill badly: two samples per pass, three
+               # (the last one on tiles of 32 and of 64 outputs), one
+               (300, 20, 3702, 2, 412), (760, 16, 4102, 2, 412), (300, 20, 3702, 3, 1412), (700, 20, 8202, 3, 2412),
+               (300, 20, 3702, 1, 411), (700, 20, 8202, 1, 421)]
+SLAB_PER_SAMPLE = [(2040, 24, 4090, 2, 1621), (1530, 24, 5300, 2, 841), (1530, 36, 7000, 2, 821),
+                   (7260, 20, 540, 2, 811), (300, 20, 1902, 2, 411), (300, 20, 4902, 3, 421), (700, 24, 5102, 2, 421)]
 # (rows, in, out, samples, per-sample x, bias, launch shape of the input gradients): dy is the input there, its rows
 # are read in quads, and the weight tile is drawn transposed; 38 outputs are no multiple of 4: the other kernel
 SLAB_BACKWARD = [(2040, 4092, 36, 2, False, True, 1621), (1530, 5300, 36, 2, False, True, 841), (1530, 7000, 20, 2, True, False, 821),
-                 (7260, 540, 20, 2, False, True, 811), (2040, 4092, 38, 2, False, True, 0)]
+                 (7260, 540, 20, 2, False, True, 811), (2040, 4092, 38, 2, False, True, 0),
+                 (300, 1904, 20, 2, False, True, 411), (300, 4904, 20, 3, True, False, 421), (700, 5104, 24, 2, False, True, 421)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,shape", SLAB_SHARED)
@@ -735,16 +740,16 @@ def test_random_layer_shapes_forward_and_dx_against_materialised_weights(hot):
         assert bool(((gw[0].double() - want_g).abs() <= 1e-5 * A_g + 1e-30).all()), "grad_mu_w"
 
 
-def test_random_layers_on_the_512_row_kernel_against_materialised_weights(hot):
-    """Seeded random layer sizes that the forward call or the input gradients give to the 512/1024-row kernel
+def test_random_layers_on_the_256_to_1024_row_kernel_against_materialised_weights(hot):
+    """Seeded random layer sizes that the forward call or the input gradients give to the 256/512/1024-row kernel
     (hot_linear_launch_shape says so; sizes that neither does are skipped): y and dx against fp64 products on the GPU with the
     weights that hot_forward_rng materialises, as in the test above.  Every launch shape has to come up."""
     rs = np.random.default_rng(23)
     done, seen = 0, set()
     for _ in range(50000):
-        if done == 24:
+        if done == 32:
             break
-        rows = int(rs.integers(512, 9000))
+        rows = int(rs.choice([rs.integers(256, 1200), rs.integers(1200, 9000)]))
         k = 4 * int(rs.choice([rs.integers(1, 24), rs.integers(24, 400)]))
         o = int(rs.choice([rs.integers(100, 1200), rs.integers(1200, 9000)]))
         if rs.integers(0, 3) == 0:
@@ -757,7 +762,7 @@ def test_random_layers_on_the_512_row_kernel_against_materialised_weights(hot):
         d = hot.hot_linear_launch_shape(rows, k, o, s, 1, per_sample_x=xs)
         # what the case would add: ("two", pair shape), ("last", outputs / 32 of an odd last sample's launch), ("one", single
         # shape of the forward call), ("dx", shape of the input gradients)
-        pair = f % 1000 in (812, 822)
+        pair = f % 1000 in (412, 812, 822)
         new = {("two", f % 1000), ("last", f // 1000)} if pair else {("one", f)}
         new = {c for c in new | {("dx", d)} if c[1] != 0} - seen
         if (f == 0 and d == 0) or (done >= 12 and not new):       # (after a dozen cases only shapes not yet seen)
@@ -804,8 +809,10 @@ def test_random_layers_on_the_512_row_kernel_against_materialised_weights(hot):
         del x, w, y, dy, dx, gw
         torch.cuda.empty_cache()
     # forward: pairs on 32 and 64 outputs, single samples on 32 to 128 and in the 1024-row shape, an odd last sample; input gradients
-    assert {("two", 812), ("two", 822), ("one", 811), ("one", 821), ("one", 841), ("one", 1621)} <= seen, sorted(seen)
-    assert {("dx", 811), ("dx", 821), ("dx", 841), ("dx", 1621)} <= seen and any(c[0] == "last" for c in seen), sorted(seen)
+    assert {("two", 412), ("two", 812), ("two", 822), ("one", 411), ("one", 421), ("one", 811), ("one", 821), ("one", 841),
+            ("one", 1621)} <= seen, sorted(seen)
+    assert {("dx", 411), ("dx", 421), ("dx", 811), ("dx", 821), ("dx", 841), ("dx", 1621)} <= seen, sorted(seen)
+    assert any(c[0] == "last" for c in seen), sorted(seen)
 
 
 # (rows, in, out, samples, per-sample x, bias)

@@ -401,12 +401,13 @@ hot_linear_forward_rows_kernel(LinearArgs a)
 }
 
 // ---------------------------------------------------------------------------------
-// The same layer for thousands of rows.  On this chip the fp32 matrix instructions and the vector ALU do not run
-// side by side (the fp32 matrix rate equals the packed fp32 vector rate: the same multipliers serve both; measured
+// The same layer for hundreds to thousands of rows.  On this chip the fp32 matrix instructions and the vector ALU do not
+// run side by side (the fp32 matrix rate equals the packed fp32 vector rate: the same multipliers serve both; measured
 // with the two kinds of work in different waves of one SIMD, the times add), so every cycle spent drawing is lost to
-// the contraction, and the share of the draw is 81 / (rows per workgroup): a third at 256 rows.  Here a workgroup
-// of eight waves owns 512 rows (64 per wave) x 32 to 128 outputs (one of sixteen: 1024 rows x 64 outputs); per step of 16 contraction indices a thread draws at
-// most ONE quad of the weight tile (two samples per pass: thread t draws sample t / 256).
+// the contraction, and the share of the draw is 81 / (rows per workgroup): a third at 256 rows, a seventh at 512.  Here
+// a workgroup of eight waves owns 512 rows (64 per wave) x 32 to 128 outputs (one of sixteen: 1024 rows x 64 outputs; one
+// of four: 256 rows x 32 or 64); per step of 16 contraction indices a thread draws at most ONE quad of the weight tile
+// (two samples per pass: the second half of the drawing threads takes the second sample).
 // x never passes through registers: each wave sends for the 16 inputs of its own 64 rows with buffer loads that write
 // straight into LDS (lane l of an instruction leaves its 16 bytes at the instruction's LDS address + 16 l, zeros for an
 // offset outside the window), into a region that only this wave reads, so x needs no barrier at all.  Rows are 64 bytes
@@ -427,7 +428,7 @@ hot_linear_forward_rows_kernel(LinearArgs a)
 // 32-63 inputs k + 4 .. k + 7; instruction i takes element i of both operands, so the contraction index is enumerated
 // in another order, identically on both sides.  All global accesses go through range-checked windows (see vec.h).
 // ---------------------------------------------------------------------------------
-constexpr int kSlabRows = 512;               // rows per workgroup of eight waves (sixteen: twice as many)
+constexpr int kSlabRows = 512;               // rows per workgroup of eight waves (sixteen: twice as many, four: half)
 constexpr int kSlabK = 16;                   // contraction indices per step
 constexpr unsigned kOutside = 0xFFFFFFF0u;   // a byte offset beyond any window
 
@@ -462,8 +463,9 @@ __device__ __forceinline__ int slab_swizzle(int r) { return ((r >> 1) & 3) ^ ((r
 
 // WAVES: 4, 8 or 16 waves of 64 rows each (16: half the draw per row again; their registers then allow 64 outputs and one
 // sample; 4: for layers that 512 rows per workgroup fill badly: twice the draw per row, but up to four such workgroups
-// share a compute unit, one's matrix instructions covering what the others wait for); CBW: blocks of 32 outputs per workgroup (every wave multiplies its 64 rows by all of them); ST samples per pass
-// (they share the input tile); OWN: every sample has an input of its own (then ST = 1).
+// share a compute unit, one's matrix instructions covering what the others wait for); CBW: blocks of 32 outputs per
+// workgroup (every wave multiplies its 64 rows by all of them); ST samples per pass (they share the input tile); OWN:
+// every sample has an input of its own (then ST = 1).
 template <int WAVES, int CBW, int ST, bool OWN, bool TR>
 __global__ void __launch_bounds__(64 * WAVES, CBW * ST <= 2 ? 4 : 2)
 hot_linear_slab_kernel(SlabArgs a)

@@ -509,7 +509,8 @@ def hot_linear_backward_workspace_bytes(rows: int, in_features: int, out_feature
 def hot_linear_launch_shape(rows: int, in_features: int, out_features: int, s_local: int, which: int, per_sample_x: bool = False,
                             ldx: int = 0) -> int:
     """Code of the launch shape hot_linear_forward_rng (which = 0) or the input-gradient part of
-    hot_linear_backward_rng (which = 1) chooses for this layer (see include/hot.h); 0: the kernels for few rows."""
+    hot_linear_backward_rng (which = 1) chooses for this layer; which = 2: of the kernel that takes both gradients in
+    one pass (hot_linear_backward_rng_ws with dx and a full workspace); see include/hot.h.  0: the other kernels."""
     ldx = ldx or in_features
     d = hot_linear_desc(rows, in_features, out_features, ldx, 0, 0, s_local, 0, rows * ldx if per_sample_x else 0)
     code = lib().hot_linear_launch_shape(ctypes.byref(d), which)

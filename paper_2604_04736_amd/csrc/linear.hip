@@ -910,6 +910,17 @@ __device__ __forceinline__ void finish_pair(float sum_g, float sum_ge, float m, 
     gs = (float)fma(g, (double)sum_ge, kl_s);
 }
 
+// The same in single precision, for the kernel whose time is vector arithmetic: six operations per parameter where
+// the fp64 form takes a few dozen cycles more; each term is rounded once more (1e-7 of its magnitude).
+__device__ __forceinline__ void finish_pair_fp32(float sum_g, float sum_ge, float m, float sd, float g, float k,
+                                                 float &gm, float &gs)
+{
+    const float kl_m = k != 0.0f ? k * m : 0.0f;
+    const float kl_s = k != 0.0f ? k * (sd - __builtin_amdgcn_rcpf(sd)) : 0.0f;
+    gm = __builtin_fmaf(g, sum_g, kl_m);
+    gs = __builtin_fmaf(g, sum_ge, kl_s);
+}
+
 constexpr int kWgradWaves = 4;       // waves per workgroup when every wave has a tile of its own
 constexpr int kWgradMaxSplit = 8;    // most waves that share one tile (60 KiB of LDS for their partial sums)
 constexpr int kWgradRowsPerIter = 16;
@@ -1830,6 +1841,319 @@ hot_linear_dx_sum_kernel(float *__restrict__ dx, const float *__restrict__ ws, l
     store4<true, false>(dx + (size_t)q * 4, sum);
 }
 
+// ---------------------------------------------------------------------------------
+// Few rows (at most 64) with the input gradients wanted: both gradients in ONE pass over the weights.  The kernels
+// above each draw every eps of the layer, and at few rows the draw is most of their time (four generator quads
+// per lane and 16 x 64 tile: about 2600 vector cycles, against 512 matrix cycles per 16 rows and product); here a
+// wave draws the quads of its tile once per sample and uses them for both products.  No drawn value has to move
+// between lanes for that: with dy as the A operand and element i of a lane's quad of x as the B operand, result
+// register rr of accumulator i is G[ob + 4 j + rr][k0 + 4 n + i], so lane (n, j) receives the weight gradients of
+// exactly the four quads (outputs ob + 4 j + c, inputs k0 + 4 n .. + 3) that the input-gradient kernel has it draw.
+//
+// A workgroup of four waves owns 64 inputs (its strip of x waits in LDS) and one part of the outputs; its waves
+// take that part's 16-output tiles round-robin, and the accumulators of every sample's dx stay in registers over
+// the whole loop (16 RB per sample and lane: that bounds rows x samples).  Per tile and sample: dy of the tile
+// (once per operand layout), the draw, G = dy^T x, sum_s G and sum_s G eps in registers, w = mu + sigma eps in
+// the registers of eps, dx += dy w; the loads of a sample (and of the tile's mu, sigma) are issued before its draw.  After the last
+// sample the tile's gradients are finished and stored, 256 contiguous bytes per output row.  At the end the
+// waves' dx tiles are added through LDS in wave order and go to the workspace as this part's block (straight to
+// dx if the layer has one part); hot_linear_dx_sum_kernel adds the blocks in part order.  No atomics.
+// ---------------------------------------------------------------------------------
+constexpr int kOnePassWaves = 4;
+constexpr int kOnePassMaxRows = 64;
+constexpr int kOnePassAccumulators = 8;     // most (16-row blocks) x (samples) whose dx accumulators a lane holds
+
+template <int RB, int SMAX>
+__global__ void __launch_bounds__(64 * kOnePassWaves, RB * SMAX <= 4 ? 2 : 1)
+hot_linear_backward_one_pass_kernel(LinearGradArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) float strip[];   // [copies of x][16 RB rows][64 inputs]; at the end [waves - 1][16 RB][64]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, j = lane >> 4;
+    const long K = a.in_features, O = a.out_features, R = a.rows;
+    const long k0 = (long)blockIdx.x * 64;
+    const long part = blockIdx.y;
+    const long o_lo = part * a.outs_per_part;
+    const long o_hi = o_lo + a.outs_per_part < O ? o_lo + a.outs_per_part : O;
+    const long kq = k0 + 4 * n;             // this lane's quad of inputs
+    const bool k_ok = kq < K;
+    const bool bias_strip = a.mu_b != nullptr && blockIdx.x == 0;    // this strip's workgroups also own the biases of their outputs
+    constexpr int kStripQuads = 16 * RB * 16;
+    const float gf = (float)a.g, kf = (float)a.k;
+
+    // rows beyond R and inputs beyond K enter as zeros: they are summed over
+    const int copies = a.x_sample_stride != 0 ? a.s_loc : 1;
+    for (int at = threadIdx.x; at < copies * kStripQuads; at += 64 * kOnePassWaves) {
+        const int copy = at / kStripQuads, rest = at % kStripQuads, row = rest >> 4, q = rest & 15;
+        f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (row < R && k0 + 4 * q < K)
+            v = load4<true, false>(a.x + (size_t)copy * (size_t)a.x_sample_stride + (size_t)row * (size_t)a.ldx + (size_t)(k0 + 4 * q));
+        *reinterpret_cast<f4 *>(strip + (size_t)at * 4) = v;
+    }
+    __syncthreads();
+
+    // dx: register rr of mx[s][rb][i] is input k0 + 16 j + 4 rr + i of row 16 rb + n of sample s
+    Acc16x16 mx[SMAX][RB][4];
+
+    // Lanes outside the layer (outputs >= O, inputs >= K) read a valid address instead; what they read is never used.
+    auto fetch_parameters = [&](long ob, f4 (&m)[4], f4 (&sd)[4]) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const long o = ob + 4 * j + c;
+            const long at = (o < O ? o : O - 1) * K + (k_ok ? kq : 0);
+            m[c] = load4<true, false>(a.mu_w + at);
+            sd[c] = load4<true, false>(a.sigma_w + at);
+        }
+    };
+
+    // dy of a tile and sample, once per operand layout: as the A operand of G (lane (n, j): output ob + n, rows 4 q + j; rows
+    // beyond R are zeros) and as the B operand of dx (row 16 rb + n, outputs ob + 4 j .. + 3; rows beyond R read row R - 1,
+    // which only reaches columns of the accumulators that are never stored; outputs beyond O must be zeros)
+    auto fetch_dy = [&](long ob, int s, float (&dya)[4 * RB], f4 (&dyq)[RB]) {
+        const float *dys = a.dy + (size_t)s * (size_t)R * (size_t)O;
+        const long o_a = ob + n < O ? ob + n : O - 1;
+#pragma unroll
+        for (int q = 0; q < 4 * RB; ++q) {      // (rows beyond R: row R - 1 for now; zeroed where the values are used, behind the draw)
+            const long row = 4 * q + j;
+            dya[q] = dys[(row < R ? row : R - 1) * O + o_a];
+        }
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const long row = 16 * rb + n;
+            const float *at = dys + (row < R ? row : R - 1) * O + ob + 4 * j;
+            if (ob + 16 <= O) dyq[rb] = load4<false, false>(at);       // uniform over the wave
+            else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) dyq[rb][c] = ob + 4 * j + c < O ? at[c] : 0.0f;
+            }
+        }
+    };
+
+    // The loads of a tile's first sample and of its mu, sigma are issued at the end of the tile before, ahead of that
+    // tile's stores: loads and stores complete in order, and a wait for a load issued behind the stores would also wait
+    // until the gradients have reached memory.  A wave without tiles fetches a valid tile and uses nothing.
+    const long ob_first = o_lo + 16 * wave;
+    f4 m4[4], sd4[4];
+    float dya0[4 * RB];
+    f4 dyq0[RB];
+    fetch_parameters(ob_first < o_hi ? ob_first : o_lo, m4, sd4);
+    fetch_dy(ob_first < o_hi ? ob_first : o_lo, 0, dya0, dyq0);
+    for (long ob = ob_first; ob < o_hi; ob += 16 * kOnePassWaves) {
+        bool ok[4];
+        long quad[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const long o = ob + 4 * j + c;
+            ok[c] = k_ok && o < O;
+            quad[c] = a.weight_quad0 + (((o < O ? o : O - 1) * K + (k_ok ? kq : 0)) >> 2);
+        }
+        f4 gm[4], gs[4], gbm = {0.0f, 0.0f, 0.0f, 0.0f}, gbs = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) gm[c] = gs[c] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+
+#pragma unroll
+        for (int s = 0; s < SMAX; ++s) {
+            if (s < a.s_loc) {                  // uniform over the grid
+                float dya[4 * RB];
+                f4 dyq[RB];
+                if (s == 0) {
+#pragma unroll
+                    for (int q = 0; q < 4 * RB; ++q) dya[q] = dya0[q];
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) dyq[rb] = dyq0[rb];
+                } else {
+                    fetch_dy(ob, s, dya, dyq);
+                }
+                // every load of this sample is on its way before its draw, whose arithmetic covers their latency
+                __builtin_amdgcn_sched_barrier(0);
+                f4 e[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) e[c] = eps_quad(quad[c], s, a.rng);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = 0; q < 4 * RB; ++q)
+                    if (4 * q + j >= R) dya[q] = 0.0f;
+
+                Acc16x16 mg[4], mb;
+                const float *xs = strip + (a.x_sample_stride != 0 ? s : 0) * (kStripQuads * 4);
+#pragma unroll
+                for (int q = 0; q < 4 * RB; ++q) {
+                    const f4 xq = *reinterpret_cast<const f4 *>(xs + (4 * q + j) * 64 + 4 * n);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) mg[i].mac(dya[q], xq[i]);
+                }
+                if (bias_strip) {               // column sums of dy: the same contraction against ones
+#pragma unroll
+                    for (int q = 0; q < 4 * RB; ++q) mb.mac(dya[q], 1.0f);
+                }
+                f4 P[4], Pb;
+                {
+                    const MfmaSettled settled;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) P[i] = mg[i].read(settled);
+                    Pb = mb.read(settled);
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        gm[c][i] += P[i][c];
+                        gs[c][i] = __builtin_fmaf(P[i][c], e[c][i], gs[c][i]);
+                    }
+                if (bias_strip) {               // register rr of Pb: sum_r dy_s[r][ob + 4 j + rr], the four outputs of one generator quad
+                    const f4 eb = eps_quad(a.bias_quad0 + ((ob + 4 * j) >> 2), s, a.rng);
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        gbm[rr] += Pb[rr];
+                        gbs[rr] = __builtin_fmaf(Pb[rr], eb[rr], gbs[rr]);
+                    }
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) e[c][i] = ok[c] ? __builtin_fmaf(sd4[c][i], e[c][i], m4[c][i]) : 0.0f;
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb) mx[s][rb][i].mac(e[c][i], dyq[rb][c]);
+            }
+        }
+
+        // the tile's gradients; then the next tile's loads into the registers they leave; then the stores
+        f4 om[4], os[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float u, v;
+                finish_pair_fp32(gm[c][i], gs[c][i], m4[c][i], sd4[c][i], gf, kf, u, v);
+                om[c][i] = u;
+                os[c][i] = v;
+            }
+        f4 ob_m = {0.0f, 0.0f, 0.0f, 0.0f}, ob_s = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (bias_strip) {
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const long o = ob + 4 * j + rr < O ? ob + 4 * j + rr : O - 1;
+                float u, v;
+                finish_pair_fp32(gbm[rr], gbs[rr], a.mu_b[o], a.sigma_b[o], gf, kf, u, v);
+                ob_m[rr] = u;
+                ob_s[rr] = v;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        {
+            const long ob_next = ob + 16 * kOnePassWaves < o_hi ? ob + 16 * kOnePassWaves : ob;
+            fetch_parameters(ob_next, m4, sd4);
+            fetch_dy(ob_next, 0, dya0, dyq0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (ok[c]) {
+                const long at = (ob + 4 * j + c) * K + kq;
+                store4<true, false>(a.gmu_w + at, om[c]);
+                store4<true, false>(a.gsig_w + at, os[c]);
+            }
+        }
+        if (bias_strip && n == 0) {
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const long o = ob + 4 * j + rr;
+                if (o < O) {
+                    a.gmu_b[o] = ob_m[rr];
+                    a.gsig_b[o] = ob_s[rr];
+                }
+            }
+        }
+    }
+
+    __syncthreads();        // every wave is done with the strip of x: its LDS now carries the waves' partial tiles
+    float *dst = a.x_parts > 1 ? a.ws + (size_t)part * (size_t)a.s_loc * (size_t)R * (size_t)K : a.dx;
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) {
+        if (s < a.s_loc) {
+            f4 acc[RB][4];
+            {
+                const MfmaSettled settled;
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[rb][i] = mx[s][rb][i].read(settled);
+            }
+            if (wave > 0) {
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr)
+                            strip[((wave - 1) * (RB * 16) + (rb * 4 + i) * 4 + rr) * 64 + lane] = acc[rb][i][rr];
+            }
+            __syncthreads();
+            if (wave == 0) {
+                for (int v = 1; v < kOnePassWaves; ++v)
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+#pragma unroll
+                            for (int rr = 0; rr < 4; ++rr)
+                                acc[rb][i][rr] += strip[((v - 1) * (RB * 16) + (rb * 4 + i) * 4 + rr) * 64 + lane];
+                store_dx_tile<RB>(acc, dst, s, 0, k0, j, n, a);
+            }
+            __syncthreads();    // the next sample's tiles overwrite these
+        }
+    }
+}
+
+// Launch shape of that kernel; rb == 0: the layer goes to the two separate kernels.
+struct OnePassPlan {
+    int rb, smax;
+    long parts, outs_per_part;
+};
+
+// ws_bytes as in wgrad_shape
+OnePassPlan one_pass_plan(const hot_linear_desc *d, bool input_gradients, int64_t ws_bytes)
+{
+    OnePassPlan p{0, 0, 1, 0};
+    if (!input_gradients || d->rows > kOnePassMaxRows) return p;
+    const int rb = d->rows > 32 ? 4 : (d->rows > 16 ? 2 : 1);
+    const int smax = d->s_local <= 2 ? 2 : (d->s_local <= 4 ? 4 : 8);
+    if (d->s_local > 8 || rb * smax > kOnePassAccumulators) return p;
+    const long strips = (d->in_features + 63) / 64, tiles = (d->out_features + 15) / 16;
+    // A workgroup per compute unit and strip of inputs where the strips are that many; fewer strips cut the outputs into
+    // parts (a part keeps a tile per wave), whose blocks of dx go through the workspace.
+    long parts = (rb * smax <= 4 ? 512 : 256) / strips;    // (the lighter shapes fit two workgroups on a compute unit)
+    if (parts > tiles / kOnePassWaves) parts = tiles / kOnePassWaves;
+    if (parts > 65535) parts = 65535;
+    if (parts < 1) parts = 1;
+    const int64_t block_bytes = (int64_t)d->s_local * d->rows * d->in_features * (int64_t)sizeof(float);
+    if (parts > 1 && ws_bytes >= 0 && parts * block_bytes > ws_bytes) parts = ws_bytes / block_bytes;
+    if (parts <= 1) {
+        // no workspace (or one too small for two blocks): only where the strips alone nearly fill the chip
+        if (strips < 200) return p;
+        parts = 1;
+    }
+    p.outs_per_part = (tiles + parts - 1) / parts * 16;
+    p.parts = (d->out_features + p.outs_per_part - 1) / p.outs_per_part;       // every part begins below O
+    p.rb = rb;
+    p.smax = smax;
+    return p;
+}
+
+template <int RB, int SMAX>
+void one_pass_go(const OnePassPlan &p, hipStream_t s, const LinearGradArgs &a)
+{
+    const size_t strip_bytes = (size_t)SMAX * 16 * RB * 64 * sizeof(float);
+    const size_t tiles_bytes = (size_t)(kOnePassWaves - 1) * 16 * RB * 64 * sizeof(float);
+    const dim3 grid((unsigned)((a.in_features + 63) / 64), (unsigned)p.parts);
+    hot_linear_backward_one_pass_kernel<RB, SMAX><<<grid, dim3(64 * kOnePassWaves), strip_bytes > tiles_bytes ? strip_bytes : tiles_bytes, s>>>(a);
+}
+
 template <int RB>
 void xgrad_go(dim3 grid, int waves, hipStream_t s, const LinearGradArgs &a)
 {
@@ -1951,8 +2275,12 @@ extern "C" {
 int hot_linear_launch_shape(const hot_linear_desc *d, int which)
 {
     if (!d || d->rows < 1 || d->in_features < 4 || (d->in_features & 3) || d->out_features < 1 || d->s_local < 1) return HOT_EINVAL;
-    if (d->ldx < d->in_features || (d->ldx & 3) || d->x_sample_stride < 0 || (which != 0 && which != 1)) return HOT_EINVAL;
+    if (d->ldx < d->in_features || (d->ldx & 3) || d->x_sample_stride < 0 || which < 0 || which > 2) return HOT_EINVAL;
     if (d->out_features > (INT64_MAX / 8) / d->in_features || d->rows > (INT64_MAX / 8) / d->ldx) return HOT_EINVAL;
+    if (which == 2) {
+        const OnePassPlan p = one_pass_plan(d, true, -1);
+        return p.rb ? 10 * p.rb + p.smax : 0;
+    }
     auto code = [](const SlabShape &h, int st) { return h.waves ? 100 * h.waves + 10 * h.cbw + st : 0; };
     if (which == 1) return code(slab_input_grad_shape(d, true), 1);
     const SlabForwardPlan p = slab_forward_plan(d);
@@ -1968,6 +2296,8 @@ int64_t hot_linear_backward_workspace_bytes(const hot_linear_desc *d)
     const int64_t for_weights = w.parts > 1 ? (int64_t)w.parts * wgrad_part_bytes(d) : 0;
     const int x_parts = xgrad_parts(d, -1);
     const int64_t for_inputs = x_parts > 1 ? (int64_t)x_parts * d->s_local * d->rows * d->in_features * (int64_t)sizeof(float) : 0;
+    if (const OnePassPlan plan = one_pass_plan(d, true, -1); plan.rb)   // (asked for input gradients or not: the query does not know)
+        return plan.parts > 1 ? plan.parts * (int64_t)d->s_local * d->rows * d->in_features * (int64_t)sizeof(float) : 0;
     return for_weights > for_inputs ? for_weights : for_inputs;       // the two kernels use it one after the other
 }
 
@@ -2150,6 +2480,23 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
     const long k_groups = (d->in_features + 63) / 64;
     const long o_groups = (d->out_features + kColsPerWave - 1) / kColsPerWave;
     if (k_groups * o_groups > 0x7fffff00L) return HOT_EINVAL;      // the grid may exceed the number of tiles by a few workgroups
+    // Few rows and input gradients wanted: both gradients in one pass over the weights, every eps drawn once.
+    if (const OnePassPlan plan = one_pass_plan(d, dx != nullptr, workspace ? workspace_bytes : 0); plan.rb) {
+        a.ws = static_cast<float *>(workspace);
+        a.x_parts = (int)plan.parts;
+        a.outs_per_part = plan.outs_per_part;
+        if (plan.rb == 4) one_pass_go<4, 2>(plan, s, a);
+        else if (plan.rb == 2 && plan.smax == 2) one_pass_go<2, 2>(plan, s, a);
+        else if (plan.rb == 2) one_pass_go<2, 4>(plan, s, a);
+        else if (plan.smax == 2) one_pass_go<1, 2>(plan, s, a);
+        else if (plan.smax == 4) one_pass_go<1, 4>(plan, s, a);
+        else one_pass_go<1, 8>(plan, s, a);
+        if (plan.parts > 1) {
+            const long quads = (long)d->s_local * d->rows * d->in_features / 4;
+            hot_linear_dx_sum_kernel<<<dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s>>>(dx, a.ws, quads, (int)plan.parts);
+        }
+        return hot_detail::note_hip(hipGetLastError());
+    }
     const WgradShape shape = wgrad_shape(d, workspace ? workspace_bytes : 0);
     if (shape.tile) {
         wgrad_tile_go(s, a, wgrad_tile_count(d));

@@ -326,6 +326,30 @@ def test_backward_with_a_workspace_matches_oracle(oracle, hot, rows, k, o, s, xs
     on too few workgroups: the outputs cut into parts the same way.  Everything against the oracle to the same
     bound as without a workspace; a workspace smaller than asked for (fewer parts, or none) and a shape that
     wants none give the same; the workspace is the only memory written besides the outputs."""
+    _backward_with_a_workspace(oracle, hot, rows, k, o, s, xs, bias, want_dx, fraction, used)
+
+
+# (rows, in, out, samples, per-sample x, bias, fraction of the wanted workspace, expected use of it, shape code)
+# every instantiation of the kernel (16-row blocks x samples held: 12, 14, 18, 22, 24, 42); inputs that are not a
+# multiple of 64 and outputs that are not a multiple of 16; a last row block with one row; half the workspace (fewer
+# parts); too little for two parts (the separate kernels run); 200 strips of inputs (one part, no workspace needed)
+ONE_PASS = [(16, 2052, 4100, 2, False, True, 1.0, True, 12), (5, 2160, 540, 1, True, True, 1.0, True, 12),
+            (13, 132, 1000, 3, False, True, 1.0, True, 14), (9, 132, 1000, 7, True, False, 1.0, True, 18),
+            (17, 36, 330, 2, False, True, 1.0, True, 22), (20, 4100, 2052, 3, True, False, 1.0, True, 24),
+            (50, 2052, 4100, 2, False, True, 1.0, True, 42), (64, 516, 2100, 2, True, True, 0.5, True, 42),
+            (49, 64, 640, 1, False, True, 1.0, True, 42), (16, 2052, 4100, 2, False, True, 0.05, False, 12),
+            (3, 12800, 40, 2, False, True, 1.0, False, 12)]
+
+
+@pytest.mark.parametrize("rows,k,o,s,xs,bias,fraction,used,shape", ONE_PASS)
+def test_backward_in_one_pass_matches_oracle(oracle, hot, rows, k, o, s, xs, bias, fraction, used, shape):
+    """Up to 64 rows with dx wanted: hot_linear_backward_rng_ws takes weight, bias and input gradients in one pass
+    over the weights (every eps drawn once); same bounds against the oracle as the separate kernels."""
+    assert hot.hot_linear_launch_shape(rows, k, o, s, 2, per_sample_x=xs) == shape
+    _backward_with_a_workspace(oracle, hot, rows, k, o, s, xs, bias, True, fraction, used, wants_none=(rows, k) == (3, 12800))
+
+
+def _backward_with_a_workspace(oracle, hot, rows, k, o, s, xs, bias, want_dx, fraction, used, wants_none=None):
     print("case linear backward with workspace", rows, k, o, s, xs, bias, want_dx, fraction, flush=True)
     c = _layer(rows + k + o, rows, k, o)
     g = np.random.default_rng(rows + s)
@@ -336,7 +360,7 @@ def test_backward_with_a_workspace_matches_oracle(oracle, hot, rows, k, o, s, xs
     w_off, b_off = 16, 16 + o * k
     s_total, dsize = 2 * s, 800.0
     want_bytes = hot.hot_linear_backward_workspace_bytes(rows, k, o, s)
-    assert (want_bytes > 0) == (used or fraction <= 0.1), want_bytes
+    assert (want_bytes > 0) == ((used or fraction <= 0.1) if wants_none is None else not wants_none), want_bytes
     n_ws = max(int(want_bytes * fraction) // 16 * 4, 4)
     ws = torch.full((n_ws + 8,), float("nan"), device=DEV)
     t = {n: torch.from_numpy(c[n]).to(DEV) for n in ("x", "mu_w", "sigma_w", "mu_b", "sigma_b")}
@@ -680,6 +704,53 @@ def test_random_layer_shapes_agree_with_and_without_a_workspace(hot):
             assert bool(torch.isfinite(a).all()) and bool(torch.isfinite(b).all())
             # a sum of R (or O) products of unit-scale factors: its fp32 rounding is far below 1e-4 of the largest sum
             assert (a - b).abs().max().item() <= 1e-4 * max(a.abs().max().item(), 1e-6)
+
+
+def test_random_few_row_layers_in_one_pass_agree_with_the_separate_kernels(hot):
+    """The kernel that takes both gradients in one pass (a workspace given) against the two separate kernels (none
+    given) on seeded random layers of 1 to 64 rows: every output, to the rounding of another order of summation
+    and of the single-precision finish.  Reaches tile and strip counts beyond the oracle-checked cases."""
+    rs = np.random.default_rng(23)
+    done, in_one_pass, codes = 0, 0, set()
+    while done < 40:
+        rows = int(rs.integers(1, 65))
+        k = 4 * int(rs.choice([rs.integers(1, 40), rs.integers(40, 700), rs.integers(3200, 3400)]))
+        o = int(rs.choice([rs.integers(1, 130), rs.integers(130, 3000)]))
+        s = int(rs.choice([1, 2, 2, 3, 4, 6, 8]))
+        bias, xs = bool(rs.integers(0, 2)), bool(rs.integers(0, 2))
+        frac = float(rs.choice([1.0, 1.0, 0.6, 0.3]))
+        if k * o > 6e6:
+            continue
+        done += 1
+        code = hot.hot_linear_launch_shape(rows, k, o, s, 2, per_sample_x=xs)
+        print("case", done, rows, k, o, s, bias, xs, frac, code, flush=True)
+        g = torch.Generator(device=DEV).manual_seed(100 + done)
+        x = torch.randn((s, rows, k) if xs else (rows, k), device=DEV, generator=g)
+        mu = torch.randn(o, k, device=DEV, generator=g) * 0.05
+        sg = torch.rand(o, k, device=DEV, generator=g) * 0.01 + 0.001
+        mb = torch.randn(o, device=DEV, generator=g) if bias else None
+        sb = (torch.rand(o, device=DEV, generator=g) * 0.01 + 0.001) if bias else None
+        dy = torch.randn(s, rows, o, device=DEV, generator=g)
+        want = hot.hot_linear_backward_workspace_bytes(rows, k, o, s)
+        n_ws = max(int(want * frac) // 16 * 4, 4)
+        outs = []
+        for ws in (None, torch.full((n_ws + 16,), float("nan"), device=DEV)):
+            t = [torch.full((o, k), float("nan"), device=DEV), torch.full((o, k), float("nan"), device=DEV),
+                 torch.full((o,), float("nan"), device=DEV) if bias else None,
+                 torch.full((o,), float("nan"), device=DEV) if bias else None, torch.full((s, rows, k), float("nan"), device=DEV)]
+            hot.hot_linear_backward_rng(hot.hot_rng(seed=9, step=done, first_sample=1), x, dy, mu, sg, mb, sb, *t, 2 * s, 4500.0,
+                                        hot.HOT_REDUCE_MEAN, 8, 8 + o * k, workspace=None if ws is None else ws[:n_ws])
+            torch.cuda.synchronize()
+            if ws is not None:
+                assert bool(torch.isnan(ws[n_ws:]).all()), "written beyond the workspace"
+                if want > 0 and not bool(torch.isnan(ws[:n_ws]).all()):
+                    in_one_pass += 1
+                    codes.add(code)
+            outs.append([v for v in t if v is not None])
+        for a, b in zip(*outs):
+            assert bool(torch.isfinite(a).all()) and bool(torch.isfinite(b).all())
+            assert (a - b).abs().max().item() <= 1e-4 * max(a.abs().max().item(), 1e-6)
+    assert in_one_pass >= 10 and len(codes) >= 4, (in_one_pass, codes)      # (counted where the workspace was written)
 
 
 def test_random_layer_shapes_forward_and_dx_against_materialised_weights(hot):

@@ -662,7 +662,7 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
                                                            hot.HOT_REDUCE_SUM, 0, o * k))
         ws_bytes = hot.hot_linear_backward_workspace_bytes(rows, k, o, s)
         ms_bw = None
-        if ws_bytes > 0:        # few tiles, many rows: the rows go to several workgroups through a workspace
+        if ws_bytes > 0:        # few tiles, many rows: the rows go to several workgroups through a workspace; up to 128 rows: both gradients in one pass
             ws = torch.empty(ws_bytes // 4, device=dev)
             ms_bw = timeit(lambda: hot.hot_linear_backward_rng(rng, x, dy, mu, sg, mb, sb, gmw, gsw, gmb, gsb, dx, s, 45000.0,
                                                                hot.HOT_REDUCE_SUM, 0, o * k, workspace=ws))

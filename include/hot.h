@@ -289,8 +289,8 @@ int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double
  * 412: four waves (256 rows), 32 outputs, two samples per pass;
  * plus 1000 * (outputs per workgroup / 32) of a second launch that takes an odd last sample on its own.
  * which = 2: hot_linear_backward_rng_ws with dx wanted and all the workspace it asks for: 10 * (16-row blocks) +
- * (samples a lane holds accumulators for) of the kernel that takes both gradients in one pass, e.g. 42, 24, 18;
- * 0 where the two separate kernels run.
+ * (samples a lane holds accumulators for) of the kernel that takes both gradients in one pass, e.g. 12, 24, 18,
+ * plus 100 where the waves split the rows (blocks per wave: 112, 122); 0 where the two separate kernels run.
  * HOT_EINVAL for a malformed desc or another `which`.
  */
 int hot_linear_launch_shape(const hot_linear_desc *desc, int which);
@@ -304,14 +304,16 @@ int hot_linear_launch_shape(const hot_linear_desc *desc, int which);
  * them in part order and finishes the gradients: deterministic, no atomics.  The input gradients use the
  * same memory afterwards where 256-row workgroups are too few for the chip (few inputs, around a thousand
  * rows): the outputs they contract over are cut into parts, whose dx blocks a second kernel adds.
- * Up to 64 rows, with dx wanted and rows x samples small enough for one lane's registers (64 rows: 2 samples,
- * 32 rows: 4, 16 rows: 8), the workspace buys more: weight and input gradients then come from ONE pass over
- * the weights, every eps drawn once instead of once per kernel, and the draw is most of the time at so few
- * rows (16 rows: 1.4x at 8192 x 8192, 2.1x at 2160 x 8640 against the call without a workspace).  A workgroup
- * owns 64 inputs and keeps their dx in registers over all outputs; layers with fewer than 256 such strips cut the
- * outputs into parts, whose dx blocks go through the workspace as above (s_local * rows * in_features * 4
- * bytes per part).  That kernel finishes the gradients in fp32 (1e-7 of each term more than the fp64 of
- * the others).
+ * Up to 128 rows with dx wanted the workspace buys more: weight and input gradients then come from ONE pass
+ * over the weights, every eps drawn once instead of once per kernel, and the draw is most of the time at so
+ * few rows.  Up to 32 rows (where a lane's registers hold the dx accumulators of all samples: 32 rows: 4 samples,
+ * 16 rows: 8) every wave draws the tiles it multiplies (16 rows: 1.4x at 8192 x 8192, 2.1x at 2160 x 8640
+ * against the call without a workspace); from 33 to 128 rows, for one or two samples on layers of half a million
+ * weights and more, the four waves of a workgroup split the rows and share the draws through LDS (64 rows: 1.6x
+ * at 2160 x 8640, 1.17x at 8192 x 8192).  A workgroup owns 64 inputs and keeps their dx in registers over all
+ * outputs; layers with fewer than 256 such strips cut the outputs into parts, whose dx blocks go through the
+ * workspace as above (s_local * rows * in_features * 4 bytes per part).  These kernels finish the gradients in
+ * fp32 (1e-7 of each term more than the fp64 of the others).
  * hot_linear_backward_workspace_bytes(desc) returns the number of bytes with which the call splits as far
  * as it wants to (0: this shape would not use a workspace; HOT_EINVAL for a malformed desc).  workspace:
  * DEVICE, 16-byte aligned, owned by the caller, contents undefined afterwards, or NULL (then the call is

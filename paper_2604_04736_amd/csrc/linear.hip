@@ -1842,7 +1842,7 @@ hot_linear_dx_sum_kernel(float *__restrict__ dx, const float *__restrict__ ws, l
 }
 
 // ---------------------------------------------------------------------------------
-// Few rows (at most 64) with the input gradients wanted: both gradients in ONE pass over the weights.  The kernels
+// Few rows (at most 32) with the input gradients wanted: both gradients in ONE pass over the weights.  The kernels
 // above each draw every eps of the layer, and at few rows the draw is most of their time (four generator quads
 // per lane and 16 x 64 tile: about 2600 vector cycles, against 512 matrix cycles per 16 rows and product); here a
 // wave draws the quads of its tile once per sample and uses them for both products.  No drawn value has to move
@@ -1860,7 +1860,7 @@ hot_linear_dx_sum_kernel(float *__restrict__ dx, const float *__restrict__ ws, l
 // dx if the layer has one part); hot_linear_dx_sum_kernel adds the blocks in part order.  No atomics.
 // ---------------------------------------------------------------------------------
 constexpr int kOnePassWaves = 4;
-constexpr int kOnePassMaxRows = 64;
+constexpr int kOnePassMaxRows = 32;
 constexpr int kOnePassAccumulators = 8;     // most (16-row blocks) x (samples) whose dx accumulators a lane holds
 
 template <int RB, int SMAX>
@@ -2110,25 +2110,233 @@ hot_linear_backward_one_pass_kernel(LinearGradArgs a)
     }
 }
 
-// Launch shape of that kernel; rb == 0: the layer goes to the two separate kernels.
+// ---------------------------------------------------------------------------------
+// The same one pass for more rows (33 to 128): the four waves of a workgroup split the ROWS (16 RBW each) and share
+// every draw.  Per 16-output x 64-input tile and sample, wave c draws quad c of every lane position (output
+// ob + 4 j + c, inputs k0 + 4 n .. + 3), forms w = mu + sigma eps and leaves it in LDS; behind a barrier every wave reads
+// the four quads of its lane position, which are exactly its A operands of dx += dy w for its own rows, and multiplies
+// G = dy^T x over its own rows; the partial G of the waves meet in LDS, and behind a second barrier wave c adds
+// those of quad c in wave order and applies the eps that it drew itself.  A wave so holds the dx accumulators of its
+// own rows only (16 RBW per sample) and one quad's gradient sums: few registers, several workgroups per compute
+// unit, which take turns at the barriers.  No reduction of dx at the end: every wave stores its own rows.
+// ---------------------------------------------------------------------------------
+constexpr int kSplitRowsWaves = 4;
+
+template <int RBW, int SMAX>
+__global__ void __launch_bounds__(64 * kSplitRowsWaves, 2)
+hot_linear_backward_split_rows_kernel(LinearGradArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    // [4][64] quads of drawn weights; [4 waves][5][64] quads of partial G (the fifth: column sums of dy); then the strip of x
+    float *const wt = lds, *const gp = lds + 4 * 64 * 4, *const strip = gp + kSplitRowsWaves * 5 * 64 * 4;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, j = lane >> 4;
+    const long K = a.in_features, O = a.out_features, R = a.rows;
+    const long k0 = (long)blockIdx.x * 64;
+    const long part = blockIdx.y;
+    const long o_lo = part * a.outs_per_part;
+    const long o_hi = o_lo + a.outs_per_part < O ? o_lo + a.outs_per_part : O;
+    const long kq = k0 + 4 * n;
+    const bool k_ok = kq < K;
+    const bool bias_strip = a.mu_b != nullptr && blockIdx.x == 0;
+    const float gf = (float)a.g, kf = (float)a.k;
+    constexpr int kRows = 16 * RBW * kSplitRowsWaves;       // rows of the workgroup
+    constexpr int kStripQuads = kRows * 16;
+    const int r0 = 16 * RBW * wave;                         // this wave's rows
+
+    const int copies = a.x_sample_stride != 0 ? a.s_loc : 1;
+    for (int at = threadIdx.x; at < copies * kStripQuads; at += 64 * kSplitRowsWaves) {
+        const int copy = at / kStripQuads, rest = at % kStripQuads, row = rest >> 4, q = rest & 15;
+        f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (row < R && k0 + 4 * q < K)
+            v = load4<true, false>(a.x + (size_t)copy * (size_t)a.x_sample_stride + (size_t)row * (size_t)a.ldx + (size_t)(k0 + 4 * q));
+        *reinterpret_cast<f4 *>(strip + (size_t)at * 4) = v;
+    }
+    __syncthreads();
+
+    // dx of this wave's rows: register rr of mx[s][rb][i] is input k0 + 16 j + 4 rr + i of row r0 + 16 rb + n
+    Acc16x16 mx[SMAX][RBW][4];
+
+    for (long ob = o_lo; ob < o_hi; ob += 16) {         // every wave walks every tile of the part
+        // this wave's quad of the tile
+        const long o_own = ob + 4 * j + wave;
+        const bool ok = k_ok && o_own < O;
+        const long at_own = (o_own < O ? o_own : O - 1) * K + (k_ok ? kq : 0);
+        const f4 m4 = load4<true, false>(a.mu_w + at_own), sd4 = load4<true, false>(a.sigma_w + at_own);
+        const long quad = a.weight_quad0 + (at_own >> 2);
+        f4 gm = {0.0f, 0.0f, 0.0f, 0.0f}, gs = {0.0f, 0.0f, 0.0f, 0.0f};
+        float gbm = 0.0f, gbs = 0.0f;
+
+#pragma unroll
+        for (int s = 0; s < SMAX; ++s) {
+            if (s < a.s_loc) {                  // uniform over the grid
+                const float *dys = a.dy + (size_t)s * (size_t)R * (size_t)O;
+                // dy of the tile and this wave's rows, once per operand layout (as in the kernel above), and the rows of x
+                float dya[4 * RBW];
+                f4 dyq[RBW], xq[4 * RBW];
+                const long o_a = ob + n < O ? ob + n : O - 1;
+#pragma unroll
+                for (int q = 0; q < 4 * RBW; ++q) {
+                    const long row = r0 + 4 * q + j;
+                    dya[q] = dys[(row < R ? row : R - 1) * O + o_a];
+                }
+#pragma unroll
+                for (int rb = 0; rb < RBW; ++rb) {
+                    const long row = r0 + 16 * rb + n;
+                    const float *at = dys + (row < R ? row : R - 1) * O + ob + 4 * j;
+                    if (ob + 16 <= O) dyq[rb] = load4<false, false>(at);       // uniform over the wave
+                    else {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) dyq[rb][c] = ob + 4 * j + c < O ? at[c] : 0.0f;
+                    }
+                }
+                const float *xs = strip + (a.x_sample_stride != 0 ? s : 0) * (kStripQuads * 4);
+#pragma unroll
+                for (int q = 0; q < 4 * RBW; ++q) xq[q] = *reinterpret_cast<const f4 *>(xs + (r0 + 4 * q + j) * 64 + 4 * n);
+                __builtin_amdgcn_sched_barrier(0);      // all of it on its way before the draw
+
+                const f4 e = eps_quad(quad, s, a.rng);
+                f4 w;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w[i] = ok ? __builtin_fmaf(sd4[i], e[i], m4[i]) : 0.0f;
+                *reinterpret_cast<f4 *>(wt + (wave * 64 + lane) * 4) = w;
+                __syncthreads();        // the tile's four quads per lane position are there (and the sums below have been read)
+
+                f4 wq[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) wq[c] = *reinterpret_cast<const f4 *>(wt + (c * 64 + lane) * 4);
+#pragma unroll
+                for (int q = 0; q < 4 * RBW; ++q)
+                    if (r0 + 4 * q + j >= R) dya[q] = 0.0f;      // rows beyond R are summed over: zeros
+                Acc16x16 mg[4], mb;
+#pragma unroll
+                for (int q = 0; q < 4 * RBW; ++q)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) mg[i].mac(dya[q], xq[q][i]);
+                if (bias_strip) {
+#pragma unroll
+                    for (int q = 0; q < 4 * RBW; ++q) mb.mac(dya[q], 1.0f);
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int rb = 0; rb < RBW; ++rb) mx[s][rb][i].mac(wq[c][i], dyq[rb][c]);
+                {
+                    const MfmaSettled settled;
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        const f4 p = {mg[0].read(settled)[rr], mg[1].read(settled)[rr], mg[2].read(settled)[rr], mg[3].read(settled)[rr]};
+                        *reinterpret_cast<f4 *>(gp + ((wave * 5 + rr) * 64 + lane) * 4) = p;
+                    }
+                    if (bias_strip) *reinterpret_cast<f4 *>(gp + ((wave * 5 + 4) * 64 + lane) * 4) = mb.read(settled);
+                }
+                __syncthreads();        // the waves' partial sums are there (and every wave has read the drawn quads)
+
+                f4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int v = 0; v < kSplitRowsWaves; ++v) {
+                    const f4 p = *reinterpret_cast<const f4 *>(gp + ((v * 5 + wave) * 64 + lane) * 4);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) sum[i] += p[i];
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    gm[i] += sum[i];
+                    gs[i] = __builtin_fmaf(sum[i], e[i], gs[i]);
+                }
+                if (bias_strip) {       // element rr of the fifth quad: sum over the wave's rows of dy_s[r][ob + 4 j + rr]; this wave's output: rr = wave
+                    float col = 0.0f;
+#pragma unroll
+                    for (int v = 0; v < kSplitRowsWaves; ++v)
+                        col += pick4(*reinterpret_cast<const f4 *>(gp + ((v * 5 + 4) * 64 + lane) * 4), wave);
+                    const f4 eb = eps_quad(a.bias_quad0 + ((ob + 4 * j) >> 2), s, a.rng);
+                    gbm += col;
+                    gbs = __builtin_fmaf(col, pick4(eb, wave), gbs);
+                }
+            }
+        }
+
+        if (ok) {
+            f4 om, os;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float u, v;
+                finish_pair_fp32(gm[i], gs[i], m4[i], sd4[i], gf, kf, u, v);
+                om[i] = u;
+                os[i] = v;
+            }
+            store4<true, false>(a.gmu_w + o_own * K + kq, om);
+            store4<true, false>(a.gsig_w + o_own * K + kq, os);
+        }
+        if (bias_strip && n == 0 && o_own < O) {
+            float u, v;
+            finish_pair_fp32(gbm, gbs, a.mu_b[o_own], a.sigma_b[o_own], gf, kf, u, v);
+            a.gmu_b[o_own] = u;
+            a.gsig_b[o_own] = v;
+        }
+    }
+
+    float *dst = a.x_parts > 1 ? a.ws + (size_t)part * (size_t)a.s_loc * (size_t)R * (size_t)K : a.dx;
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) {
+        if (s < a.s_loc) {
+            f4 acc[RBW][4];
+            {
+                const MfmaSettled settled;
+#pragma unroll
+                for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[rb][i] = mx[s][rb][i].read(settled);
+            }
+            store_dx_tile<RBW>(acc, dst, s, r0, k0, j, n, a);
+        }
+    }
+}
+
+// Launch shape of the two kernels above; rb == 0: the layer goes to the two separate kernels.
 struct OnePassPlan {
-    int rb, smax;
+    int rb, smax;       // split: 16-row blocks per wave; else per workgroup.  smax: samples a lane holds accumulators for
+    bool split;         // the waves split the rows and share the draws
     long parts, outs_per_part;
 };
+
+// Where the waves split the rows: 33 to 128 rows, one or two samples, half a million weights (measured against the two
+// separate kernels at 2 samples: 64 rows 1.5-1.7x at 516 x 2100 to 2160 x 8640, 1.17x at 8192 x 8192; 128 rows 1.45x at
+// 540 x 2160, 1.04x at 8192 x 8192; slower on smaller layers, whose few tiles leave the barriers exposed (100 x 260 x 1000:
+// 0.93x), with four samples (0.83x at 64 x 2048 x 2048: two waves per SIMD) and at 256 rows x 1 sample (0.88x)).  Up to
+// 64 rows it also beats a wave drawing whole tiles for all rows (8192 x 8192: 0.66 against 0.72 ms).
+constexpr int kSplitRowsFrom = kOnePassMaxRows + 1, kSplitRowsMaxRows = 128;
+constexpr long kSplitRowsMinWeights = 512 * 1024;
 
 // ws_bytes as in wgrad_shape
 OnePassPlan one_pass_plan(const hot_linear_desc *d, bool input_gradients, int64_t ws_bytes)
 {
-    OnePassPlan p{0, 0, 1, 0};
-    if (!input_gradients || d->rows > kOnePassMaxRows) return p;
-    const int rb = d->rows > 32 ? 4 : (d->rows > 16 ? 2 : 1);
-    const int smax = d->s_local <= 2 ? 2 : (d->s_local <= 4 ? 4 : 8);
-    if (d->s_local > 8 || rb * smax > kOnePassAccumulators) return p;
+    OnePassPlan p{0, 0, false, 1, 0};
+    if (!input_gradients || d->rows > kSplitRowsMaxRows) return p;
+    int rb, smax;
+    bool split = false;
+    long budget;        // workgroups that fill the chip once
+    if (d->rows >= kSplitRowsFrom) {
+        if (d->s_local > 2 || d->in_features * d->out_features < kSplitRowsMinWeights) return p;
+        split = true;
+        rb = d->rows > 64 ? 2 : 1;
+        smax = 2;
+        budget = 768;       // (three workgroups share a compute unit)
+    } else {
+        rb = d->rows > 16 ? 2 : 1;
+        smax = d->s_local <= 2 ? 2 : (d->s_local <= 4 ? 4 : 8);
+        if (d->s_local > 8 || rb * smax > kOnePassAccumulators) return p;
+        budget = rb * smax <= 4 ? 512 : 256;    // (the lighter shapes fit two workgroups on a compute unit)
+    }
     const long strips = (d->in_features + 63) / 64, tiles = (d->out_features + 15) / 16;
-    // A workgroup per compute unit and strip of inputs where the strips are that many; fewer strips cut the outputs into
-    // parts (a part keeps a tile per wave), whose blocks of dx go through the workspace.
-    long parts = (rb * smax <= 4 ? 512 : 256) / strips;    // (the lighter shapes fit two workgroups on a compute unit)
-    if (parts > tiles / kOnePassWaves) parts = tiles / kOnePassWaves;
+    // Workgroups for every compute unit from the strips of inputs alone where the strips are that many; fewer strips cut
+    // the outputs into parts (a part keeps a tile per wave, four tiles where the waves share them), whose blocks of dx go
+    // through the workspace.
+    long parts = budget / strips;
+    if (parts > tiles / 4) parts = tiles / 4;
     if (parts > 65535) parts = 65535;
     if (parts < 1) parts = 1;
     const int64_t block_bytes = (int64_t)d->s_local * d->rows * d->in_features * (int64_t)sizeof(float);
@@ -2142,6 +2350,7 @@ OnePassPlan one_pass_plan(const hot_linear_desc *d, bool input_gradients, int64_
     p.parts = (d->out_features + p.outs_per_part - 1) / p.outs_per_part;       // every part begins below O
     p.rb = rb;
     p.smax = smax;
+    p.split = split;
     return p;
 }
 
@@ -2152,6 +2361,15 @@ void one_pass_go(const OnePassPlan &p, hipStream_t s, const LinearGradArgs &a)
     const size_t tiles_bytes = (size_t)(kOnePassWaves - 1) * 16 * RB * 64 * sizeof(float);
     const dim3 grid((unsigned)((a.in_features + 63) / 64), (unsigned)p.parts);
     hot_linear_backward_one_pass_kernel<RB, SMAX><<<grid, dim3(64 * kOnePassWaves), strip_bytes > tiles_bytes ? strip_bytes : tiles_bytes, s>>>(a);
+}
+
+template <int RBW, int SMAX>
+void split_rows_go(const OnePassPlan &p, hipStream_t s, const LinearGradArgs &a)
+{
+    const int copies = a.x_sample_stride != 0 ? a.s_loc : 1;
+    const size_t lds = ((size_t)(4 + kSplitRowsWaves * 5) * 64 * 4 + (size_t)copies * 16 * RBW * kSplitRowsWaves * 64) * sizeof(float);
+    const dim3 grid((unsigned)((a.in_features + 63) / 64), (unsigned)p.parts);
+    hot_linear_backward_split_rows_kernel<RBW, SMAX><<<grid, dim3(64 * kSplitRowsWaves), lds, s>>>(a);
 }
 
 template <int RB>
@@ -2279,7 +2497,7 @@ int hot_linear_launch_shape(const hot_linear_desc *d, int which)
     if (d->out_features > (INT64_MAX / 8) / d->in_features || d->rows > (INT64_MAX / 8) / d->ldx) return HOT_EINVAL;
     if (which == 2) {
         const OnePassPlan p = one_pass_plan(d, true, -1);
-        return p.rb ? 10 * p.rb + p.smax : 0;
+        return p.rb ? (p.split ? 100 : 0) + 10 * p.rb + p.smax : 0;
     }
     auto code = [](const SlabShape &h, int st) { return h.waves ? 100 * h.waves + 10 * h.cbw + st : 0; };
     if (which == 1) return code(slab_input_grad_shape(d, true), 1);
@@ -2296,9 +2514,13 @@ int64_t hot_linear_backward_workspace_bytes(const hot_linear_desc *d)
     const int64_t for_weights = w.parts > 1 ? (int64_t)w.parts * wgrad_part_bytes(d) : 0;
     const int x_parts = xgrad_parts(d, -1);
     const int64_t for_inputs = x_parts > 1 ? (int64_t)x_parts * d->s_local * d->rows * d->in_features * (int64_t)sizeof(float) : 0;
-    if (const OnePassPlan plan = one_pass_plan(d, true, -1); plan.rb)   // (asked for input gradients or not: the query does not know)
-        return plan.parts > 1 ? plan.parts * (int64_t)d->s_local * d->rows * d->in_features * (int64_t)sizeof(float) : 0;
-    return for_weights > for_inputs ? for_weights : for_inputs;       // the two kernels use it one after the other
+    int64_t most = for_weights > for_inputs ? for_weights : for_inputs;     // the two kernels use it one after the other
+    // (whether input gradients will be asked for the query does not know: enough for either way)
+    if (const OnePassPlan plan = one_pass_plan(d, true, -1); plan.rb && plan.parts > 1) {
+        const int64_t for_one_pass = plan.parts * (int64_t)d->s_local * d->rows * d->in_features * (int64_t)sizeof(float);
+        if (for_one_pass > most) most = for_one_pass;
+    }
+    return most;
 }
 
 int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const float *x, const float *mu_w,
@@ -2485,8 +2707,10 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
         a.ws = static_cast<float *>(workspace);
         a.x_parts = (int)plan.parts;
         a.outs_per_part = plan.outs_per_part;
-        if (plan.rb == 4) one_pass_go<4, 2>(plan, s, a);
-        else if (plan.rb == 2 && plan.smax == 2) one_pass_go<2, 2>(plan, s, a);
+        if (plan.split) {
+            if (plan.rb == 2) split_rows_go<2, 2>(plan, s, a);
+            else split_rows_go<1, 2>(plan, s, a);
+        } else if (plan.rb == 2 && plan.smax == 2) one_pass_go<2, 2>(plan, s, a);
         else if (plan.rb == 2) one_pass_go<2, 4>(plan, s, a);
         else if (plan.smax == 2) one_pass_go<1, 2>(plan, s, a);
         else if (plan.smax == 4) one_pass_go<1, 4>(plan, s, a);

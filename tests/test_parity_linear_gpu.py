@@ -330,23 +330,25 @@ def test_backward_with_a_workspace_matches_oracle(oracle, hot, rows, k, o, s, xs
 
 
 # (rows, in, out, samples, per-sample x, bias, fraction of the wanted workspace, expected use of it, shape code)
-# every instantiation of the kernel (16-row blocks x samples held: 12, 14, 18, 22, 24, 42); inputs that are not a
-# multiple of 64 and outputs that are not a multiple of 16; a last row block with one row; half the workspace (fewer
-# parts); too little for two parts (the separate kernels run); 200 strips of inputs (one part, no workspace needed)
+# every instantiation of the two kernels (a wave draws whole tiles: 16-row blocks x samples held 12, 14, 18, 22, 24; the
+# waves split the rows: 112, 122); inputs that are not a multiple of 64 and outputs that are not a multiple of 16; a
+# last row block with one row, a wave without rows; half the workspace (fewer parts); too little for two parts (the
+# separate kernels run); 200 strips of inputs (one part, no workspace needed)
 ONE_PASS = [(16, 2052, 4100, 2, False, True, 1.0, True, 12), (5, 2160, 540, 1, True, True, 1.0, True, 12),
             (13, 132, 1000, 3, False, True, 1.0, True, 14), (9, 132, 1000, 7, True, False, 1.0, True, 18),
             (17, 36, 330, 2, False, True, 1.0, True, 22), (20, 4100, 2052, 3, True, False, 1.0, True, 24),
-            (50, 2052, 4100, 2, False, True, 1.0, True, 42), (64, 516, 2100, 2, True, True, 0.5, True, 42),
-            (49, 64, 640, 1, False, True, 1.0, True, 42), (16, 2052, 4100, 2, False, True, 0.05, False, 12),
-            (3, 12800, 40, 2, False, True, 1.0, False, 12)]
+            (16, 2052, 4100, 2, False, True, 0.05, False, 12), (3, 12800, 40, 2, False, True, 1.0, False, 12),
+            (50, 2052, 4100, 2, False, True, 1.0, True, 112), (64, 516, 2100, 2, True, True, 0.5, True, 112),
+            (33, 1028, 520, 1, False, False, 1.0, True, 112), (100, 260, 2100, 2, False, True, 1.0, True, 122),
+            (128, 516, 1100, 1, True, True, 1.0, True, 122), (70, 2052, 300, 2, True, False, 0.6, True, 122)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias,fraction,used,shape", ONE_PASS)
 def test_backward_in_one_pass_matches_oracle(oracle, hot, rows, k, o, s, xs, bias, fraction, used, shape):
-    """Up to 64 rows with dx wanted: hot_linear_backward_rng_ws takes weight, bias and input gradients in one pass
+    """Up to 128 rows with dx wanted: hot_linear_backward_rng_ws takes weight, bias and input gradients in one pass
     over the weights (every eps drawn once); same bounds against the oracle as the separate kernels."""
     assert hot.hot_linear_launch_shape(rows, k, o, s, 2, per_sample_x=xs) == shape
-    _backward_with_a_workspace(oracle, hot, rows, k, o, s, xs, bias, True, fraction, used, wants_none=(rows, k) == (3, 12800))
+    _backward_with_a_workspace(oracle, hot, rows, k, o, s, xs, bias, True, fraction, used, wants_none=((rows, k) == (3, 12800)))
 
 
 def _backward_with_a_workspace(oracle, hot, rows, k, o, s, xs, bias, want_dx, fraction, used, wants_none=None):
@@ -707,22 +709,24 @@ def test_random_layer_shapes_agree_with_and_without_a_workspace(hot):
 
 
 def test_random_few_row_layers_in_one_pass_agree_with_the_separate_kernels(hot):
-    """The kernel that takes both gradients in one pass (a workspace given) against the two separate kernels (none
-    given) on seeded random layers of 1 to 64 rows: every output, to the rounding of another order of summation
+    """The kernels that take both gradients in one pass (a workspace given) against the two separate kernels (none
+    given) on seeded random layers of 1 to 128 rows: every output, to the rounding of another order of summation
     and of the single-precision finish.  Reaches tile and strip counts beyond the oracle-checked cases."""
     rs = np.random.default_rng(23)
     done, in_one_pass, codes = 0, 0, set()
-    while done < 40:
-        rows = int(rs.integers(1, 65))
+    while done < 48:
+        rows = int(rs.choice([rs.integers(1, 33), rs.integers(33, 129)]))
         k = 4 * int(rs.choice([rs.integers(1, 40), rs.integers(40, 700), rs.integers(3200, 3400)]))
-        o = int(rs.choice([rs.integers(1, 130), rs.integers(130, 3000)]))
-        s = int(rs.choice([1, 2, 2, 3, 4, 6, 8]))
+        o = int(rs.choice([rs.integers(1, 130), rs.integers(130, 3000), rs.integers(1000, 3000)]))
+        s = int(rs.choice([1, 2, 2, 3, 4, 6, 8] if rows <= 32 else [1, 2, 2, 3]))
         bias, xs = bool(rs.integers(0, 2)), bool(rs.integers(0, 2))
         frac = float(rs.choice([1.0, 1.0, 0.6, 0.3]))
         if k * o > 6e6:
             continue
-        done += 1
         code = hot.hot_linear_launch_shape(rows, k, o, s, 2, per_sample_x=xs)
+        if code == 0 and rs.random() < 0.8:      # (mostly shapes that the kernels under test take)
+            continue
+        done += 1
         print("case", done, rows, k, o, s, bias, xs, frac, code, flush=True)
         g = torch.Generator(device=DEV).manual_seed(100 + done)
         x = torch.randn((s, rows, k) if xs else (rows, k), device=DEV, generator=g)
@@ -750,7 +754,7 @@ def test_random_few_row_layers_in_one_pass_agree_with_the_separate_kernels(hot):
         for a, b in zip(*outs):
             assert bool(torch.isfinite(a).all()) and bool(torch.isfinite(b).all())
             assert (a - b).abs().max().item() <= 1e-4 * max(a.abs().max().item(), 1e-6)
-    assert in_one_pass >= 10 and len(codes) >= 4, (in_one_pass, codes)      # (counted where the workspace was written)
+    assert in_one_pass >= 20 and len(codes) >= 6, (in_one_pass, codes)      # (counted where the workspace was written)
 
 
 def test_random_layer_shapes_forward_and_dx_against_materialised_weights(hot):

@@ -1965,7 +1965,15 @@ hot_linear_backward_one_pass_kernel(LinearGradArgs a)
                 } else {
                     fetch_dy(ob, s, dya, dyq);
                 }
-                // every load of this sample is on its way before its draw, whose arithmetic covers their latency
+                // every load of this sample, the rows of x from LDS among them, is on its way before its draw, whose
+                // arithmetic covers their latency
+                const float *xs = strip + (a.x_sample_stride != 0 ? s : 0) * (kStripQuads * 4);
+                constexpr bool kEarlyX = RB * SMAX <= 2;        // (registers for it only in the lightest shape)
+                f4 xq[4 * RB];
+                if constexpr (kEarlyX) {
+#pragma unroll
+                    for (int q = 0; q < 4 * RB; ++q) xq[q] = *reinterpret_cast<const f4 *>(xs + (4 * q + j) * 64 + 4 * n);
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 f4 e[4];
 #pragma unroll
@@ -1976,12 +1984,11 @@ hot_linear_backward_one_pass_kernel(LinearGradArgs a)
                     if (4 * q + j >= R) dya[q] = 0.0f;
 
                 Acc16x16 mg[4], mb;
-                const float *xs = strip + (a.x_sample_stride != 0 ? s : 0) * (kStripQuads * 4);
 #pragma unroll
                 for (int q = 0; q < 4 * RB; ++q) {
-                    const f4 xq = *reinterpret_cast<const f4 *>(xs + (4 * q + j) * 64 + 4 * n);
+                    if constexpr (!kEarlyX) xq[q] = *reinterpret_cast<const f4 *>(xs + (4 * q + j) * 64 + 4 * n);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) mg[i].mac(dya[q], xq[i]);
+                    for (int i = 0; i < 4; ++i) mg[i].mac(dya[q], xq[q][i]);
                 }
                 if (bias_strip) {               // column sums of dy: the same contraction against ones
 #pragma unroll

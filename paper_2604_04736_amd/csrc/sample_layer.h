@@ -241,14 +241,16 @@ inline void default_launches(hot_plan &p)
     // The drawing variants have no eps loads to keep in flight.  Forward: as above up to seven samples;
     // from eight on one chunk per thread (38 registers, eight waves per SIMD) hides the generator's
     // latencies better than four independent chains in five waves (10-20 % at 8 M to 25 M weights).
-    // Backward: two chunks and single rows from four samples on.
+    // Backward: single rows in flight at every size (two rows of draws in flight cost registers and with them waves:
+    // 209 M weights x 2 samples 1.07 ms against 0.81, 64 M x 3 0.38 against 0.30, 20 M x 8 0.178 against 0.169); four
+    // chunks per thread from 16 M weights on, below that two from four samples on (6.3 M x 16, 7.7 M x 13), else one.
     hot_launch &fr = p.cfg[HOT_KERNEL_FORWARD_RNG], &br = p.cfg[HOT_KERNEL_BACKWARD_RNG];
     fr = f;
     if (d.s_local >= 8) fr.chunks = 1;
     br = b;
-    br.chunks = d.s_local >= 4 ? 2 : (few_tiles ? 1 : 4);
+    br.chunks = few_tiles ? (d.s_local >= 4 ? 2 : 1) : 4;
     if (br.chunks > f.chunks) br.chunks = f.chunks;      // (f.chunks: what the number of tiles allows)
-    br.unroll = pick_unroll(d.s_local >= 4 ? 1 : 2, d.s_local);
+    br.unroll = 1;
 }
 
 // How the N columns are cut into tiles, one workgroup each (capped by the configured bound, beyond which workgroups

@@ -224,11 +224,13 @@ int hot_last_hip_error(const hot_plan *plan);
  * Up to a few hundred rows a wave draws the weights it multiplies (re-drawing eps per block of 64
  * rows is then cheaper than writing and re-reading w); from 256 rows on, given at least 128 workgroups
  * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS; where tiles of 256, 512
- * or 1024 rows x 32 to 128 outputs fill the chip (hot_linear_launch_shape tells), four, eight or sixteen waves
- * share it and x goes from memory straight into LDS (110-140 TFLOP/s, up to 89 % of the fp32
- * matrix peak).  The draw and the matrix instructions do not overlap on this chip; against writing w once
+ * or 1024 rows x 32 to 128 outputs fill the chip (hot_linear_launch_shape tells; the 256-row tiles from 129 rows
+ * on), four, eight or sixteen waves share it and x goes from memory straight into LDS (110-140 TFLOP/s, up to
+ * 89 % of the fp32 matrix peak).  The draw and the matrix instructions do not overlap on this chip; against writing w once
  * with hot_forward_rng and calling a library GEMM the call is 1.8-2.9x faster up to tens of rows, level at
- * 64 rows, 1.2-1.35x at the 7260 and 16640 rows of a Swin and a ViT layer, and level on the largest squares.
+ * 64 rows, 1.2-1.35x at the 7260 and 16640 rows of a Swin and a ViT layer, and level on the largest squares;
+ * between about 100 and 500 rows large layers stay behind that route (0.75-1.0x at 8192 x 8192, 0.7-0.9x at
+ * 2160 x 8640): one draw serves too few rows there and the two do not overlap.
  */
 typedef struct hot_linear_desc {
     int64_t rows;          /* R >= 1: rows of x (batch x tokens) */
@@ -267,12 +269,13 @@ int hot_linear_forward_rng(const hot_linear_desc *desc, const hot_rng *rng, cons
  * on, once per workgroup of 64 to 256 rows (its waves share the draws through LDS), or, where tiles of 512
  * or 1024 rows fill the chip, once per such tile (the forward pass's kernel for many rows with dy as its
  * input; it needs out_features to be a multiple of 4 and dy 16-byte aligned).  Large layers
- * (from 256 rows on, at least two tiles of 128 inputs x 128 outputs per compute unit) take their weight
+ * (from 129 rows on, at least two tiles of 128 inputs x 128 outputs per compute unit) take their weight
  * gradients from a kernel that stages x and dy through LDS (up to 138 TFLOP/s); it needs out_features to
  * be a multiple of 4 and rows * max(ldx, out_features) * 4 below 4 GiB, else the first kernel runs; with more
  * than two samples it adds up pairs of samples in grad_mu_w and grad_sigma_w themselves.  Against
- * library GEMMs for dx and G followed by hot_backward_rng the call is 1.1-3x faster up to tens of rows and at
- * 1.0-1.35x for thousands of rows.
+ * library GEMMs for dx and G followed by hot_backward_rng the call is 1.1-3x faster up to tens of rows (with a
+ * workspace, see below; 0.86-3x without) and at 1.0-1.35x for thousands of rows; between about 100 and 500 rows it
+ * stays behind on large layers (0.65-0.9x).
  */
 int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double dataset_size, uint32_t flags,
                             const hot_rng *rng, const float *x, const float *dy, const float *mu_w,

@@ -682,11 +682,12 @@ struct SlabShape {
 // re-read twice as often), one alone at that plus 600.  Against the kernels for few rows they win from a fill of 0.52 of the
 // compute units' last workgroup on (measured on 160 layer shapes of 256 to 7260 rows: 1.1-2.2x from there, 0.3-0.9x below).
 constexpr double kSlab4MinFill = 0.52;
+constexpr long kSlab4MinRows = 129;
 
 inline SlabShape slab_shape4(long rows, long outs, long passes, int st)
 {
     SlabShape best = {0, 0, 0.0};
-    if (passes < 1 || passes > 65535 || rows < 256) return best;
+    if (passes < 1 || passes > 65535 || rows < kSlab4MinRows) return best;
     for (int cbw = st == 2 ? 1 : 2; cbw >= 1; cbw /= 2) {
         const long col_tiles = (outs + 32 * cbw - 1) / (32 * cbw), wgs = col_tiles * ((rows + 255) / 256) * passes;
         const long per_cu = (wgs + kComputeUnits - 1) / kComputeUnits;
@@ -778,7 +779,7 @@ struct SlabForwardPlan {
 inline SlabForwardPlan slab_forward_plan(const hot_linear_desc *d)
 {
     SlabForwardPlan p = {0, SlabShape{0, 0, 0.0}, SlabShape{0, 0, 0.0}};
-    if (d->rows < 256 || !slab_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) return p;
+    if (d->rows < kSlab4MinRows || !slab_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) return p;
     const int S = d->s_local;
     if (d->x_sample_stride != 0 || S == 1) {
         const double bar = d->x_sample_stride != 0 ? kSlabMinFillForwardOwnX : kSlabMinFillForward;
@@ -820,7 +821,7 @@ inline SlabForwardPlan slab_forward_plan(const hot_linear_desc *d)
 // ... and the input gradients (dy is the input, read in 16-byte quads: rows of dy must allow that)
 inline SlabShape slab_input_grad_shape(const hot_linear_desc *d, bool dy_aligned)
 {
-    if (d->rows < 256 || (d->out_features & 3) != 0 || !dy_aligned ||
+    if (d->rows < kSlab4MinRows || (d->out_features & 3) != 0 || !dy_aligned ||
         !slab_kernel_fits(d->rows, d->out_features, d->in_features, d->out_features))
         return SlabShape{0, 0, 0.0};
     return slab_shape_singles(d->rows, d->in_features, d->s_local, kSlabMinFillInputGrad, kSlabMinFillInputGradNarrow);
@@ -2479,7 +2480,7 @@ WgradShape wgrad_shape(const hot_linear_desc *d, int64_t ws_bytes)
     const long tile_count = wgrad_tile_count(d), last_round = tile_count % 512;
     const bool fills = tile_count >= 512 ? (last_round == 0 || last_round >= 256 || tile_count >= 2048)
                                          : (tile_count > 230 && tile_count <= 256 && d->rows >= 1024);
-    if (wgrad_tile_fits(d) && d->rows >= 256 && fills) {
+    if (wgrad_tile_fits(d) && d->rows >= kSlab4MinRows && fills) {
         WgradShape w = wgrad_shape_with(d, 0, false);
         w.parts = 1;
         w.rows_per_part = 0;

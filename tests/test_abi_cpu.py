@@ -78,21 +78,21 @@ def test_workspace_query_over_many_shapes_is_consistent(hot):
 
 
 def test_launch_shape_query_over_many_shapes_is_consistent(hot):
-    """Host arithmetic only: the code names a shape the 256/512/1024-row kernel has, never for fewer than 256 rows (below 512 only its four-wave shapes), and for the
+    """Host arithmetic only: the code names a shape the 256/512/1024-row kernel has, never for fewer than 129 rows (below 512 only its four-wave shapes), and for the
     input gradients never where rows of dy cannot be read in quads."""
     import random
     r = random.Random(11)
     singles = {411, 421, 811, 821, 841, 1621}
     seen = set()
     for _ in range(4000):
-        rows = r.choice([1, 255, 256, 511, 512, 1000, 1530, 2048, 4096, 7260, 16640, 65536])
+        rows = r.choice([1, 128, 129, 255, 256, 511, 512, 1000, 1530, 2048, 4096, 7260, 16640, 65536])
         k = 4 * r.randint(1, 2200)
         o = r.randint(1, 9000)
         s = r.choice([1, 2, 3, 4, 16])
         own = r.random() < 0.4
         f = hot.hot_linear_launch_shape(rows, k, o, s, 0, per_sample_x=own)
         g = hot.hot_linear_launch_shape(rows, k, o, s, 1, per_sample_x=own)
-        if rows < 256:
+        if rows < 129:
             assert f == 0 and g == 0
         if rows < 512:
             assert f // 100 % 10 in (0, 4) and g // 100 in (0, 4), (rows, k, o, s, f, g)

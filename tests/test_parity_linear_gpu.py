@@ -90,14 +90,18 @@ SLAB_SHARED = [(2040, 36, 4090, 2, 1621), (2040, 16, 8180, 3, 1621),      # 1024
                # 256 rows per workgroup (four waves), for layers that tiles of 512 rows fill badly: two samples per pass, three
                # (the last one on tiles of 32 and of 64 outputs), one
                (300, 20, 3702, 2, 412), (760, 16, 4102, 2, 412), (300, 20, 3702, 3, 1412), (700, 20, 8202, 3, 2412),
-               (300, 20, 3702, 1, 411), (700, 20, 8202, 1, 421)]
+               (300, 20, 3702, 1, 411), (700, 20, 8202, 1, 421),
+               # ... from 129 rows on where the layer's outputs alone fill the chip with such workgroups (the last waves without rows)
+               (200, 36, 8192, 2, 412), (140, 20, 8192, 1, 411)]
 SLAB_PER_SAMPLE = [(2040, 24, 4090, 2, 1621), (1530, 24, 5300, 2, 841), (1530, 36, 7000, 2, 821),
-                   (7260, 20, 540, 2, 811), (300, 20, 1902, 2, 411), (300, 20, 4902, 3, 421), (700, 24, 5102, 2, 421)]
+                   (7260, 20, 540, 2, 811), (300, 20, 1902, 2, 411), (300, 20, 4902, 3, 421), (700, 24, 5102, 2, 421),
+                   (150, 20, 8192, 2, 411)]
 # (rows, in, out, samples, per-sample x, bias, launch shape of the input gradients): dy is the input there, its rows
 # are read in quads, and the weight tile is drawn transposed; 38 outputs are no multiple of 4: the other kernel
 SLAB_BACKWARD = [(2040, 4092, 36, 2, False, True, 1621), (1530, 5300, 36, 2, False, True, 841), (1530, 7000, 20, 2, True, False, 821),
                  (7260, 540, 20, 2, False, True, 811), (2040, 4092, 38, 2, False, True, 0),
-                 (300, 1904, 20, 2, False, True, 411), (300, 4904, 20, 3, True, False, 421), (700, 5104, 24, 2, False, True, 421)]
+                 (300, 1904, 20, 2, False, True, 411), (300, 4904, 20, 3, True, False, 421), (700, 5104, 24, 2, False, True, 421),
+                 (180, 8192, 24, 2, False, True, 411)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,shape", SLAB_SHARED)
@@ -894,7 +898,8 @@ def test_random_layers_on_the_256_to_1024_row_kernel_against_materialised_weight
 TILED = [(300, 2900, 4228, 2, False, True),      # 23 x 34 tiles of 128 x 128, ragged in rows, inputs and outputs
          (272, 2048, 4096, 3, True, False),      # 16 x 32 whole tiles, three samples with inputs of their own
          (257, 3000, 4092, 1, False, True),      # 24 x 32 tiles, both edges ragged, a single sample, an odd number of steps
-         (1030, 2048, 2000, 2, False, True)]     # one tile per compute unit, from a thousand rows on
+         (1030, 2048, 2000, 2, False, True),     # one tile per compute unit, from a thousand rows on
+         (150, 2048, 4096, 2, False, True)]      # fewer rows than one 256-row block (the kernel runs from 129 rows on)
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias", TILED)

@@ -272,7 +272,9 @@ int hot_linear_forward_rng(const hot_linear_desc *desc, const hot_rng *rng, cons
  * (from 129 rows on, at least two tiles of 128 inputs x 128 outputs per compute unit) take their weight
  * gradients from a kernel that stages x and dy through LDS (up to 138 TFLOP/s); it needs out_features to
  * be a multiple of 4 and rows * max(ldx, out_features) * 4 below 4 GiB, else the first kernel runs; with more
- * than two samples it adds up pairs of samples in grad_mu_w and grad_sigma_w themselves.  Against
+ * than two samples it adds up pairs of samples in grad_mu_w and grad_sigma_w themselves.  All of these kernels
+ * scale the sums and add the KL part in fp32 (g * sum + k * mu, g * sum + k * (sigma - 1/sigma) with the hardware's
+ * reciprocal: 1e-7 of each term), where hot_backward does it in fp64.  Against
  * library GEMMs for dx and G followed by hot_backward_rng the call is 1.1-3x faster up to tens of rows (with a
  * workspace, see below; 0.86-3x without) and at 1.0-1.35x for thousands of rows; between about 100 and 500 rows it
  * stays behind on large layers (0.65-0.9x).
@@ -315,8 +317,7 @@ int hot_linear_launch_shape(const hot_linear_desc *desc, int which);
  * weights and more, the four waves of a workgroup split the rows and share the draws through LDS (64 rows: 1.6x
  * at 2160 x 8640, 1.17x at 8192 x 8192).  A workgroup owns 64 inputs and keeps their dx in registers over all
  * outputs; layers with fewer than 256 such strips cut the outputs into parts, whose dx blocks go through the
- * workspace as above (s_local * rows * in_features * 4 bytes per part).  These kernels finish the gradients in
- * fp32 (1e-7 of each term more than the fp64 of the others).
+ * workspace as above (s_local * rows * in_features * 4 bytes per part).
  * hot_linear_backward_workspace_bytes(desc) returns the number of bytes with which the call splits as far
  * as it wants to (0: this shape would not use a workspace; HOT_EINVAL for a malformed desc).  workspace:
  * DEVICE, 16-byte aligned, owned by the caller, contents undefined afterwards, or NULL (then the call is

@@ -901,20 +901,12 @@ __device__ __forceinline__ void transpose_quads_over_j(f4 (&q)[4], int j, int n)
 }
 
 // grad_mu, grad_sigma of one parameter from its sums over the samples (gradient and averaging lines
-// of Algorithm 2; d KL / d mu = mu, d KL / d sigma = sigma - 1/sigma)
-__device__ __forceinline__ void finish_pair(float sum_g, float sum_ge, float m, float sd, double g, double k,
+// of Algorithm 2; d KL / d mu = mu, d KL / d sigma = sigma - 1/sigma).  In single precision: six operations per
+// parameter.  An fp64 form (the flat sample layer's, which is bound by memory) cost these kernels, bound by vector
+// arithmetic at few rows, about 1000 cycles per 16 x 64 tile, 40 % of a draw (8192^2 at 16 rows: weight gradients
+// 0.289 -> 0.271 ms; at 1024 rows 127.6 -> 130 TFLOP/s); each term is rounded once more, 1e-7 of its magnitude.
+__device__ __forceinline__ void finish_pair(float sum_g, float sum_ge, float m, float sd, float g, float k,
                                             float &gm, float &gs)
-{
-    const double kl_m = k != 0.0 ? k * (double)m : 0.0;
-    const double kl_s = k != 0.0 ? k * ((double)sd - (double)(1.0f / sd)) : 0.0;
-    gm = (float)fma(g, (double)sum_g, kl_m);
-    gs = (float)fma(g, (double)sum_ge, kl_s);
-}
-
-// The same in single precision, for the kernel whose time is vector arithmetic: six operations per parameter where
-// the fp64 form takes a few dozen cycles more; each term is rounded once more (1e-7 of its magnitude).
-__device__ __forceinline__ void finish_pair_fp32(float sum_g, float sum_ge, float m, float sd, float g, float k,
-                                                 float &gm, float &gs)
 {
     const float kl_m = k != 0.0f ? k * m : 0.0f;
     const float kl_s = k != 0.0f ? k * (sd - __builtin_amdgcn_rcpf(sd)) : 0.0f;
@@ -1200,7 +1192,7 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     float u, v;
-                    finish_pair(gm[b][t][c], gs[b][t][c], m4[c], sd4[c], a.g, a.k, u, v);
+                    finish_pair(gm[b][t][c], gs[b][t][c], m4[c], sd4[c], (float)a.g, (float)a.k, u, v);
                     om[c] = u;
                     os[c] = v;
                 }
@@ -1210,7 +1202,7 @@ hot_linear_wgrad_kernel(LinearGradArgs a)
         }
         if (bias_tile && j == 0 && o_ok[b]) {
             float u, v;
-            finish_pair(gb_m[b], gb_s[b], a.mu_b[o[b]], a.sigma_b[o[b]], a.g, a.k, u, v);
+            finish_pair(gb_m[b], gb_s[b], a.mu_b[o[b]], a.sigma_b[o[b]], (float)a.g, (float)a.k, u, v);
             a.gmu_b[o[b]] = u;
             a.gsig_b[o[b]] = v;
         }
@@ -1240,7 +1232,7 @@ hot_linear_wgrad_finish_kernel(LinearGradArgs a, int parts)
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             float u, v;
-            finish_pair(gm[c], gs[c], m4[c], sd4[c], a.g, a.k, u, v);
+            finish_pair(gm[c], gs[c], m4[c], sd4[c], (float)a.g, (float)a.k, u, v);
             om[c] = u;
             os[c] = v;
         }
@@ -1255,7 +1247,7 @@ hot_linear_wgrad_finish_kernel(LinearGradArgs a, int parts)
             gs += theirs[per + O * K + q];
         }
         float u, v;
-        finish_pair(gm, gs, a.mu_b[q], a.sigma_b[q], a.g, a.k, u, v);
+        finish_pair(gm, gs, a.mu_b[q], a.sigma_b[q], (float)a.g, (float)a.k, u, v);
         a.gmu_b[q] = u;
         a.gsig_b[q] = v;
     }
@@ -1524,7 +1516,7 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
 #pragma unroll
                             for (int c = 0; c < 4; ++c) {
                                 float pm, ps;
-                                finish_pair(om[c], os[c], m4[c], sd4[c], a.g, a.k, pm, ps);
+                                finish_pair(om[c], os[c], m4[c], sd4[c], (float)a.g, (float)a.k, pm, ps);
                                 om[c] = pm;
                                 os[c] = ps;
                             }
@@ -1558,7 +1550,7 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
             const long o = o0 + 64 * wo + 32 * j + l32;
             if (o < O) {
                 float p, r;
-                finish_pair(gb_m[j], gb_s[j], a.mu_b[o], a.sigma_b[o], a.g, a.k, p, r);
+                finish_pair(gb_m[j], gb_s[j], a.mu_b[o], a.sigma_b[o], (float)a.g, (float)a.k, p, r);
                 a.gmu_b[o] = p;
                 a.gsig_b[o] = r;
             }
@@ -2037,7 +2029,7 @@ hot_linear_backward_one_pass_kernel(LinearGradArgs a)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 float u, v;
-                finish_pair_fp32(gm[c][i], gs[c][i], m4[c][i], sd4[c][i], gf, kf, u, v);
+                finish_pair(gm[c][i], gs[c][i], m4[c][i], sd4[c][i], gf, kf, u, v);
                 om[c][i] = u;
                 os[c][i] = v;
             }
@@ -2047,7 +2039,7 @@ hot_linear_backward_one_pass_kernel(LinearGradArgs a)
             for (int rr = 0; rr < 4; ++rr) {
                 const long o = ob + 4 * j + rr < O ? ob + 4 * j + rr : O - 1;
                 float u, v;
-                finish_pair_fp32(gbm[rr], gbs[rr], a.mu_b[o], a.sigma_b[o], gf, kf, u, v);
+                finish_pair(gbm[rr], gbs[rr], a.mu_b[o], a.sigma_b[o], gf, kf, u, v);
                 ob_m[rr] = u;
                 ob_s[rr] = v;
             }
@@ -2272,7 +2264,7 @@ hot_linear_backward_split_rows_kernel(LinearGradArgs a)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 float u, v;
-                finish_pair_fp32(gm[i], gs[i], m4[i], sd4[i], gf, kf, u, v);
+                finish_pair(gm[i], gs[i], m4[i], sd4[i], gf, kf, u, v);
                 om[i] = u;
                 os[i] = v;
             }
@@ -2281,7 +2273,7 @@ hot_linear_backward_split_rows_kernel(LinearGradArgs a)
         }
         if (bias_strip && n == 0 && o_own < O) {
             float u, v;
-            finish_pair_fp32(gbm, gbs, a.mu_b[o_own], a.sigma_b[o_own], gf, kf, u, v);
+            finish_pair(gbm, gbs, a.mu_b[o_own], a.sigma_b[o_own], gf, kf, u, v);
             a.gmu_b[o_own] = u;
             a.gsig_b[o_own] = v;
         }

@@ -225,11 +225,11 @@ int hot_last_hip_error(const hot_plan *plan);
  * rows is then cheaper than writing and re-reading w); from 256 rows on, given at least 128 workgroups
  * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS; where tiles of 256, 512
  * or 1024 rows x 32 to 128 outputs fill the chip (hot_linear_launch_shape tells; the 256-row tiles from 129 rows
- * on), four, eight or sixteen waves share it and x goes from memory straight into LDS (110-140 TFLOP/s, up to
+ * on, tiles of 128 rows from 65 to 128), four, eight or sixteen waves share it and x goes from memory straight into LDS (110-140 TFLOP/s, up to
  * 89 % of the fp32 matrix peak).  The draw and the matrix instructions do not overlap on this chip; against writing w once
  * with hot_forward_rng and calling a library GEMM the call is 1.8-2.9x faster up to tens of rows, level at
  * 64 rows, 1.2-1.35x at the 7260 and 16640 rows of a Swin and a ViT layer, and level on the largest squares;
- * between about 100 and 500 rows large layers stay behind that route (0.75-1.0x at 8192 x 8192, 0.7-0.9x at
+ * between about 80 and 500 rows large layers stay behind that route (0.75-1.0x at 8192 x 8192, 0.7-0.95x at
  * 2160 x 8640): one draw serves too few rows there and the two do not overlap.
  */
 typedef struct hot_linear_desc {
@@ -291,7 +291,7 @@ int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double
  * to a few hundred rows per workgroup; else, for the kernel with 256, 512 or 1024 rows per workgroup (64 per wave),
  * 100 * waves + 10 * (outputs per workgroup / 32) + samples per pass of its (first) launch, e.g. 822: eight waves
  * (512 rows), 64 outputs, two samples per pass; 1621: sixteen waves (1024 rows), 64 outputs, one sample per pass;
- * 412: four waves (256 rows), 32 outputs, two samples per pass;
+ * 412: four waves (256 rows), 32 outputs, two samples per pass; 2xx: four waves of 32 rows each (128 rows), e.g. 212;
  * plus 1000 * (outputs per workgroup / 32) of a second launch that takes an odd last sample on its own.
  * which = 2: hot_linear_backward_rng_ws with dx wanted and all the workspace it asks for: 10 * (16-row blocks) +
  * (samples a lane holds accumulators for) of the kernel that takes both gradients in one pass, e.g. 12, 24, 18,

@@ -466,14 +466,17 @@ __device__ __forceinline__ int slab_swizzle(int r) { return ((r >> 1) & 3) ^ ((r
 // share a compute unit, one's matrix instructions covering what the others wait for); CBW: blocks of 32 outputs per
 // workgroup (every wave multiplies its 64 rows by all of them); ST samples per pass (they share the input tile); OWN:
 // every sample has an input of its own (then ST = 1).
-template <int WAVES, int CBW, int ST, bool OWN, bool TR>
+// RBW: blocks of 32 rows per wave; one only with four waves (128 rows per workgroup, for 65 to 128 rows: half the matrix
+// work per draw again).
+template <int WAVES, int CBW, int ST, bool OWN, bool TR, int RBW = 2>
 __global__ void __launch_bounds__(64 * WAVES, CBW * ST <= 2 ? 4 : 2)
 hot_linear_slab_kernel(SlabArgs a)
 {
     static_assert(ST == 1 || ST == 2, "one or two samples per pass");
     static_assert(!OWN || ST == 1, "one input per sample: one sample per pass");
     static_assert(WAVES == 8 || ((WAVES == 16 || WAVES == 4) && CBW * ST <= 2), "sixteen waves have 128 registers each, and so have four: four such workgroups share a compute unit");
-    constexpr int RBW = 2, WROWS = 32 * RBW, OUTS = 32 * CBW, KS = kSlabK;
+    static_assert(RBW == 2 || (RBW == 1 && WAVES == 4), "32 rows per wave only in workgroups of four waves");
+    constexpr int WROWS = 32 * RBW, OUTS = 32 * CBW, KS = kSlabK;
     constexpr int XW = WROWS * KS;           // floats of a wave's region of x
     constexpr int WT = OUTS * KS;            // floats of one sample's weight tile
     constexpr int NX = WROWS / 16;           // load instructions per wave and step
@@ -485,7 +488,7 @@ hot_linear_slab_kernel(SlabArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int C = (int)a.contract, N = (int)a.outs, R = (int)a.rows;
-    const int n0 = (int)blockIdx.x * OUTS, r0 = (int)blockIdx.y * (64 * WAVES);
+    const int n0 = (int)blockIdx.x * OUTS, r0 = (int)blockIdx.y * (WROWS * WAVES);
 
     // reading operands: lane (l32, half) holds, for half-step k8, inputs 8 k8 + 4 half .. + 3 of row / output l32 of a block of 32
     int op_off[2];
@@ -675,6 +678,7 @@ struct SlabShape {
     int waves;      // 4, 8 or 16; 0: none
     int cbw;        // blocks of 32 outputs per workgroup
     double cost;
+    int rbw = 2;    // blocks of 32 rows per wave (one: four waves of 32 rows, for 65 to 128 rows)
 };
 
 // Four waves: 256 rows x 32 or 64 output-samples.  Up to four such workgroups share a compute unit and run at the rate of
@@ -683,18 +687,29 @@ struct SlabShape {
 // compute units' last workgroup on (measured on 160 layer shapes of 256 to 7260 rows: 1.1-2.2x from there, 0.3-0.9x below).
 constexpr double kSlab4MinFill = 0.52;
 constexpr long kSlab4MinRows = 129;
+// From 65 to 128 rows the four waves take 32 rows each: half the matrix work per draw again, measured per step and
+// workgroup 1850 cycles for 64 output-samples and 1170 for 32, 300 more for one alone on its compute unit.  Against the
+// kernels for few rows, which draw every weight once per 64 rows: 96 and 128 rows x 8192^2 1.13-1.27x, x 2160 x 8640 with
+// one x per sample 1.2-1.28x; a narrow workgroup alone on its compute unit (one wave per SIMD) loses (96 x 4096^2: 0.87x),
+// so the shapes of 32 output-samples need two workgroups per compute unit.
+constexpr long kSlab4HalfMinRows = 65;
+constexpr double kSlab4HalfMinFill = 0.52;
 
 inline SlabShape slab_shape4(long rows, long outs, long passes, int st)
 {
     SlabShape best = {0, 0, 0.0};
-    if (passes < 1 || passes > 65535 || rows < kSlab4MinRows) return best;
+    if (passes < 1 || passes > 65535 || rows < kSlab4HalfMinRows) return best;
+    const bool half = rows <= 128;
+    const long tile_rows = half ? 128 : 256;
     for (int cbw = st == 2 ? 1 : 2; cbw >= 1; cbw /= 2) {
-        const long col_tiles = (outs + 32 * cbw - 1) / (32 * cbw), wgs = col_tiles * ((rows + 255) / 256) * passes;
+        const long col_tiles = (outs + 32 * cbw - 1) / (32 * cbw), wgs = col_tiles * ((rows + tile_rows - 1) / tile_rows) * passes;
         const long per_cu = (wgs + kComputeUnits - 1) / kComputeUnits;
-        const double exact = (double)outs / (32 * cbw) * (double)rows / 256.0 * (double)passes;
-        if (exact < kSlab4MinFill * (double)(per_cu * kComputeUnits)) continue;
-        const double cost = (double)per_cu * (cbw * st == 2 ? 2700.0 : 1600.0) + (per_cu == 1 ? 600.0 : 0.0);
-        if (best.waves == 0 || cost < best.cost) best = SlabShape{4, cbw, cost};
+        const double exact = (double)outs / (32 * cbw) * (double)rows / (double)tile_rows * (double)passes;
+        if (exact < (half ? kSlab4HalfMinFill : kSlab4MinFill) * (double)(per_cu * kComputeUnits)) continue;
+        if (half && cbw * st == 1 && wgs < 2 * kComputeUnits) continue;
+        const double wide = half ? 1850.0 : 2700.0, narrow = half ? 1170.0 : 1600.0;
+        const double cost = (double)per_cu * (cbw * st == 2 ? wide : narrow) + (per_cu == 1 ? (half ? 300.0 : 600.0) : 0.0);
+        if (best.waves == 0 || cost < best.cost) best = SlabShape{4, cbw, cost, half ? 1 : 2};
     }
     return best;
 }
@@ -730,14 +745,14 @@ inline double slab_full(long rows, long outs, long samples)
 }
 
 // Launches it for the samples s_begin .. s_end - 1, ST per pass, one pass per layer of the grid along z.
-template <int WAVES, int CBW, int ST, bool OWN, bool TR>
+template <int WAVES, int CBW, int ST, bool OWN, bool TR, int RBW = 2>
 void slab_go(hipStream_t s, SlabArgs a, int s_begin, int s_end)
 {
     a.s_begin = s_begin;
     a.s_end = s_end;
-    const dim3 grid((unsigned)((a.outs + 32 * CBW - 1) / (32 * CBW)), (unsigned)((a.rows + 64 * WAVES - 1) / (64 * WAVES)),
+    const dim3 grid((unsigned)((a.outs + 32 * CBW - 1) / (32 * CBW)), (unsigned)((a.rows + 32 * RBW * WAVES - 1) / (32 * RBW * WAVES)),
                     (unsigned)((s_end - s_begin + ST - 1) / ST));
-    hot_linear_slab_kernel<WAVES, CBW, ST, OWN, TR><<<grid, dim3(64 * WAVES), 0, s>>>(a);
+    hot_linear_slab_kernel<WAVES, CBW, ST, OWN, TR, RBW><<<grid, dim3(64 * WAVES), 0, s>>>(a);
 }
 
 // one sample per pass, in the shape chosen
@@ -745,6 +760,8 @@ template <bool OWN, bool TR>
 void slab_go_singles(const SlabShape &shape, hipStream_t s, const SlabArgs &a, int s_begin, int s_end)
 {
     if (shape.waves == 16) slab_go<16, 2, 1, OWN, TR>(s, a, s_begin, s_end);
+    else if (shape.waves == 4 && shape.rbw == 1 && shape.cbw == 2) slab_go<4, 2, 1, OWN, TR, 1>(s, a, s_begin, s_end);
+    else if (shape.waves == 4 && shape.rbw == 1) slab_go<4, 1, 1, OWN, TR, 1>(s, a, s_begin, s_end);
     else if (shape.waves == 4 && shape.cbw == 2) slab_go<4, 2, 1, OWN, TR>(s, a, s_begin, s_end);
     else if (shape.waves == 4) slab_go<4, 1, 1, OWN, TR>(s, a, s_begin, s_end);
     else if (shape.cbw == 4) slab_go<8, 4, 1, OWN, TR>(s, a, s_begin, s_end);
@@ -779,7 +796,7 @@ struct SlabForwardPlan {
 inline SlabForwardPlan slab_forward_plan(const hot_linear_desc *d)
 {
     SlabForwardPlan p = {0, SlabShape{0, 0, 0.0}, SlabShape{0, 0, 0.0}};
-    if (d->rows < kSlab4MinRows || !slab_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) return p;
+    if (d->rows < kSlab4HalfMinRows || !slab_kernel_fits(d->rows, d->in_features, d->out_features, d->ldx)) return p;
     const int S = d->s_local;
     if (d->x_sample_stride != 0 || S == 1) {
         const double bar = d->x_sample_stride != 0 ? kSlabMinFillForwardOwnX : kSlabMinFillForward;
@@ -821,7 +838,7 @@ inline SlabForwardPlan slab_forward_plan(const hot_linear_desc *d)
 // ... and the input gradients (dy is the input, read in 16-byte quads: rows of dy must allow that)
 inline SlabShape slab_input_grad_shape(const hot_linear_desc *d, bool dy_aligned)
 {
-    if (d->rows < kSlab4MinRows || (d->out_features & 3) != 0 || !dy_aligned ||
+    if (d->rows < kSlab4HalfMinRows || (d->out_features & 3) != 0 || !dy_aligned ||
         !slab_kernel_fits(d->rows, d->out_features, d->in_features, d->out_features))
         return SlabShape{0, 0, 0.0};
     return slab_shape_singles(d->rows, d->in_features, d->s_local, kSlabMinFillInputGrad, kSlabMinFillInputGradNarrow);
@@ -2499,7 +2516,7 @@ int hot_linear_launch_shape(const hot_linear_desc *d, int which)
         const OnePassPlan p = one_pass_plan(d, true, -1);
         return p.rb ? (p.split ? 100 : 0) + 10 * p.rb + p.smax : 0;
     }
-    auto code = [](const SlabShape &h, int st) { return h.waves ? 100 * h.waves + 10 * h.cbw + st : 0; };
+    auto code = [](const SlabShape &h, int st) { return h.waves ? 100 * (h.rbw == 1 ? 2 : h.waves) + 10 * h.cbw + st : 0; };
     if (which == 1) return code(slab_input_grad_shape(d, true), 1);
     const SlabForwardPlan p = slab_forward_plan(d);
     return p.two.waves ? code(p.two, 2) + 1000 * (p.one.waves ? p.one.cbw : 0) : code(p.one, 1);
@@ -2583,7 +2600,8 @@ int hot_linear_forward_rng(const hot_linear_desc *d, const hot_rng *rng, const f
         b.sigma_b = sigma_b;
         b.out = y;
         b.rng = r;
-        if (plan.two.waves == 4) slab_go<4, 1, 2, false, false>(s, b, 0, plan.pair_samples);
+        if (plan.two.waves == 4 && plan.two.rbw == 1) slab_go<4, 1, 2, false, false, 1>(s, b, 0, plan.pair_samples);
+        else if (plan.two.waves == 4) slab_go<4, 1, 2, false, false>(s, b, 0, plan.pair_samples);
         else if (plan.two.waves) {
             if (plan.two.cbw == 2) slab_go<8, 2, 2, false, false>(s, b, 0, plan.pair_samples);
             else slab_go<8, 1, 2, false, false>(s, b, 0, plan.pair_samples);

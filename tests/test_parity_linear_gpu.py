@@ -92,16 +92,18 @@ SLAB_SHARED = [(2040, 36, 4090, 2, 1621), (2040, 16, 8180, 3, 1621),      # 1024
                (300, 20, 3702, 2, 412), (760, 16, 4102, 2, 412), (300, 20, 3702, 3, 1412), (700, 20, 8202, 3, 2412),
                (300, 20, 3702, 1, 411), (700, 20, 8202, 1, 421),
                # ... from 129 rows on where the layer's outputs alone fill the chip with such workgroups (the last waves without rows)
-               (200, 36, 8192, 2, 412), (140, 20, 8192, 1, 411)]
+               (200, 36, 8192, 2, 412), (140, 20, 8192, 1, 411),
+               # 65 to 128 rows: four waves of 32 rows each (code 2xx): two samples per pass, a third on its own, one
+               (100, 20, 8192, 2, 212), (70, 8, 16384, 3, 2212), (120, 12, 16384, 1, 221)]
 SLAB_PER_SAMPLE = [(2040, 24, 4090, 2, 1621), (1530, 24, 5300, 2, 841), (1530, 36, 7000, 2, 821),
                    (7260, 20, 540, 2, 811), (300, 20, 1902, 2, 411), (300, 20, 4902, 3, 421), (700, 24, 5102, 2, 421),
-                   (150, 20, 8192, 2, 411)]
+                   (150, 20, 8192, 2, 411), (96, 12, 12288, 2, 211), (128, 20, 8192, 2, 221)]
 # (rows, in, out, samples, per-sample x, bias, launch shape of the input gradients): dy is the input there, its rows
 # are read in quads, and the weight tile is drawn transposed; 38 outputs are no multiple of 4: the other kernel
 SLAB_BACKWARD = [(2040, 4092, 36, 2, False, True, 1621), (1530, 5300, 36, 2, False, True, 841), (1530, 7000, 20, 2, True, False, 821),
                  (7260, 540, 20, 2, False, True, 811), (2040, 4092, 38, 2, False, True, 0),
                  (300, 1904, 20, 2, False, True, 411), (300, 4904, 20, 3, True, False, 421), (700, 5104, 24, 2, False, True, 421),
-                 (180, 8192, 24, 2, False, True, 411)]
+                 (180, 8192, 24, 2, False, True, 411), (100, 8192, 24, 2, False, True, 221)]
 
 
 @pytest.mark.parametrize("rows,k,o,s,shape", SLAB_SHARED)

@@ -679,6 +679,7 @@ struct SlabShape {
     int cbw;        // blocks of 32 outputs per workgroup
     double cost;
     int rbw = 2;    // blocks of 32 rows per wave (one: four waves of 32 rows, for 65 to 128 rows)
+    double fill = 1.0;      // four-wave shapes: the share of its compute units' workgroup slots that the launch fills
 };
 
 // Four waves: 256 rows x 32 or 64 output-samples.  Up to four such workgroups share a compute unit and run at the rate of
@@ -709,7 +710,7 @@ inline SlabShape slab_shape4(long rows, long outs, long passes, int st)
         if (half && cbw * st == 1 && wgs < 2 * kComputeUnits) continue;
         const double wide = half ? 1850.0 : 2700.0, narrow = half ? 1170.0 : 1600.0;
         const double cost = (double)per_cu * (cbw * st == 2 ? wide : narrow) + (per_cu == 1 ? (half ? 300.0 : 600.0) : 0.0);
-        if (best.waves == 0 || cost < best.cost) best = SlabShape{4, cbw, cost, half ? 1 : 2};
+        if (best.waves == 0 || cost < best.cost) best = SlabShape{4, cbw, cost, half ? 1 : 2, exact / (double)(per_cu * kComputeUnits)};
     }
     return best;
 }
@@ -2407,7 +2408,7 @@ inline long xgrad_outs_per_part(const hot_linear_desc *d, int parts)
 
 int xgrad_parts(const hot_linear_desc *d, int64_t ws_bytes)
 {
-    if (ws_bytes == 0 || d->rows < 256) return 1;
+    if (ws_bytes == 0 || d->rows < kSlab4MinRows) return 1;
     const long k_groups = (d->in_features + 63) / 64, gy = (d->rows + 255) / 256;
     const long wgs = k_groups * gy * d->s_local;
     if (wgs >= 256 || gy > 65535) return 1;
@@ -2777,7 +2778,10 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
     };
     // Hundreds to thousands of rows on a layer whose dx fills the chip with tiles of 512 rows: the kernel of the forward pass
     // with dy as its input and the weight tile drawn transposed (rows of dy are read in 16-byte quads).
-    if (const SlabShape one = slab_input_grad_shape(d, aligned16(dy)); one.waves) {
+    // (a workspace that lets the kernel below cut the outputs into parts beats a four-wave launch that leaves a quarter of
+    // its slots empty: 256 x 2160 x 8640, 136 workgroups of 256 rows x 32 inputs: the whole call 0.71 -> 0.53 ms)
+    const int parts_at_hand = xgrad_parts(d, workspace ? workspace_bytes : 0);
+    if (const SlabShape one = slab_input_grad_shape(d, aligned16(dy)); one.waves && !(parts_at_hand > 1 && one.waves == 4 && one.fill < 0.75)) {
         SlabArgs b;
         b.rows = d->rows;
         b.contract = d->out_features;
@@ -2798,7 +2802,7 @@ int hot_linear_backward_rng_ws(const hot_linear_desc *d, int32_t s_total, double
     }
     // many rows: the workgroup-shared draw, with as many rows per workgroup (256, 128, 64) as still give every
     // compute unit a workgroup
-    if (const int x_parts = xgrad_parts(d, workspace ? workspace_bytes : 0); x_parts > 1) {
+    if (const int x_parts = parts_at_hand; x_parts > 1) {
         // too few 256-row workgroups: the outputs are cut into parts, summed from the workspace afterwards
         a.ws = static_cast<float *>(workspace);
         a.x_parts = x_parts;

@@ -320,6 +320,8 @@ WITH_WORKSPACE = [(4200, 64, 48, 2, False, True, False, 1.0, True), (17000, 36, 
                   # workspace for fewer parts; none)
                   (1030, 132, 700, 2, False, True, True, 1.0, True), (300, 36, 333, 3, True, False, True, 1.0, True),
                   (1030, 132, 700, 2, False, True, True, 0.6, True), (1030, 132, 700, 2, False, True, True, 0.1, False),
+                  # ... from 129 rows on (one 256-row workgroup per 64 inputs, its last waves without rows)
+                  (200, 132, 700, 2, False, True, True, 1.0, True),
                   # the shape on which one accumulator register was once read before the matrix pipeline had written it
                   # (a partial last row block in a tile without biases; the kernels now wait explicitly)
                   (19549, 84, 1744, 1, False, True, False, 1.0, True)]

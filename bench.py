@@ -432,14 +432,19 @@ def mix_ceilings(hot, torch, dev, wl, in_kernel_eps: bool, fwd_ms: float, bwd_ms
     """Both kernels of a workload beside hot_probe_streams with their stream counts (no arithmetic)."""
     out = {}
     fb, bb = algorithmic_bytes(wl.n_weights, wl.s_local, in_kernel_eps)
-    stream_bytes = 4 * wl.n_weights // 16 * 16
+    # the probe's streams lie as the workload's rows do: at its pitch, off the 16-byte grid where that is (C5)
+    stream_bytes = 4 * wl.ld
     for which, (r, w), nbytes, ms in (("forward",) + (stream_mix(wl, in_kernel_eps)["forward"],) + (fb, fwd_ms),
                                       ("backward",) + (stream_mix(wl, in_kernel_eps)["backward"],) + (bb, bwd_ms)):
         if r > 64 or w > 64:
             continue
         m = mix_ceiling(hot, torch, dev, stream_bytes, r, w)
         out[which] = {"probe_GBps": m["GBps"], "probe_ms": m["ms"], "read_streams": r, "write_streams": w,
-                      "kernel_GBps": nbytes / ms / 1e6, "kernel_vs_probe": nbytes / ms / 1e6 / m["GBps"]}
+                      "stream_bytes": stream_bytes, "kernel_GBps": nbytes / ms / 1e6, "kernel_vs_probe": nbytes / ms / 1e6 / m["GBps"]}
+        if stream_bytes % 16:
+            a = mix_ceiling(hot, torch, dev, stream_bytes // 16 * 16, r, w)
+            out[which]["probe_on_the_16_byte_grid_GBps"] = a["GBps"]
+            out[which]["kernel_vs_probe_on_the_16_byte_grid"] = nbytes / ms / 1e6 / a["GBps"]
         torch.cuda.empty_cache()
     return out
 

@@ -480,7 +480,10 @@ int hot_probe_copy(void *dst, const void *src, int64_t bytes, int nontemporal, v
 
 /*
  * Measurement aid: `reads` (1..64) read streams and `writes` (0..64) write streams of
- * stream_bytes each (a multiple of 16), laid out back to back in `arena` (a DEVICE buffer
+ * stream_bytes each (a multiple of 4; with a multiple of 16 every stream keeps the arena's
+ * 16-byte alignment, otherwise the streams are as skewed against the 16- and 64-byte grids as
+ * the rows of a sample matrix with that pitch, their last 1 to 3 floats are left alone and
+ * writes must be >= 1), laid out back to back in `arena` (a DEVICE buffer
  * of (reads + writes) * stream_bytes bytes, 16-byte aligned; read streams first).  Every
  * write stream receives the element-wise sum of the read streams.  With the stream counts
  * of one of the kernels above it measures the machine's ceiling for that kernel's mix of

@@ -145,14 +145,18 @@ hot_probe_streams_kernel(ProbeStreams p, long n_vec)
 // The same for the stream counts of workloads with many samples (C3: 18 read + 16 write streams forward, 34 + 2
 // backward), which no thread can hold in registers at once: like the kernels, a thread walks the read streams
 // four at a time, adding them up, and then writes the sum to every write stream, one after the other.
+// AL = false: the streams only keep dword alignment (a pitch that is no multiple of 16 bytes, as the rows of a sample
+// matrix with an odd leading dimension): the same 16-byte accesses from dword addresses.
+template <bool AL>
 __global__ void __launch_bounds__(kBlock)
-hot_probe_many_streams_kernel(const f4 *__restrict__ arena, long stream_vec, int reads, int writes, long n_vec)
+hot_probe_many_streams_kernel(const float *__restrict__ arena, long stream_floats, int reads, int writes, long n_vec)
 {
     constexpr int kPer = 4;
     const long base = (long)blockIdx.x * (kBlock * kPer) + threadIdx.x;
     f4 acc[kPer];
 #pragma unroll
     for (int c = 0; c < kPer; ++c) acc[c] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    float *out = const_cast<float *>(arena) + (size_t)reads * (size_t)stream_floats;
     if (base + (long)(kPer - 1) * kBlock < n_vec) {       // a whole tile (uniform over the workgroup)
         int r = 0;
         for (; r + 4 <= reads; r += 4) {
@@ -161,7 +165,7 @@ hot_probe_many_streams_kernel(const f4 *__restrict__ arena, long stream_vec, int
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int c = 0; c < kPer; ++c)
-                    v[u][c] = __builtin_nontemporal_load(arena + (size_t)(r + u) * (size_t)stream_vec + base + (long)c * kBlock);
+                    v[u][c] = load4<AL, true>(arena + (size_t)(r + u) * (size_t)stream_floats + 4 * (base + (long)c * kBlock));
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -171,23 +175,21 @@ hot_probe_many_streams_kernel(const f4 *__restrict__ arena, long stream_vec, int
             f4 v[kPer];
 #pragma unroll
             for (int c = 0; c < kPer; ++c)
-                v[c] = __builtin_nontemporal_load(arena + (size_t)r * (size_t)stream_vec + base + (long)c * kBlock);
+                v[c] = load4<AL, true>(arena + (size_t)r * (size_t)stream_floats + 4 * (base + (long)c * kBlock));
 #pragma unroll
             for (int c = 0; c < kPer; ++c) acc[c] += v[c];
         }
-        f4 *out = const_cast<f4 *>(arena) + (size_t)reads * (size_t)stream_vec;
         for (int w = 0; w < writes; ++w)
 #pragma unroll
             for (int c = 0; c < kPer; ++c)
-                __builtin_nontemporal_store(acc[c], out + (size_t)w * (size_t)stream_vec + base + (long)c * kBlock);
+                store4<AL, true>(out + (size_t)w * (size_t)stream_floats + 4 * (base + (long)c * kBlock), acc[c]);
     } else {
         for (int c = 0; c < kPer; ++c) {
             const long at = base + (long)c * kBlock;
             if (at >= n_vec) continue;
             f4 sum = f4{0.0f, 0.0f, 0.0f, 0.0f};
-            for (int r = 0; r < reads; ++r) sum += arena[(size_t)r * (size_t)stream_vec + at];
-            f4 *out = const_cast<f4 *>(arena) + (size_t)reads * (size_t)stream_vec;
-            for (int w = 0; w < writes; ++w) out[(size_t)w * (size_t)stream_vec + at] = sum;
+            for (int r = 0; r < reads; ++r) sum += load4<AL, false>(arena + (size_t)r * (size_t)stream_floats + 4 * at);
+            for (int w = 0; w < writes; ++w) store4<AL, false>(out + (size_t)w * (size_t)stream_floats + 4 * at, sum);
         }
     }
 }
@@ -359,15 +361,18 @@ int hot_probe_copy(void *dst, const void *src, int64_t bytes, int nontemporal, v
 
 int hot_probe_streams(void *arena, int64_t stream_bytes, int reads, int writes, void *stream)
 {
-    if (!arena || !aligned16(arena) || stream_bytes < 16 || (stream_bytes & 15)) return HOT_EINVAL;
+    if (!arena || !aligned16(arena) || stream_bytes < 16 || (stream_bytes & 3)) return HOT_EINVAL;
     if (reads < 1 || reads > 64 || writes < 0 || writes > 64) return HOT_EINVAL;
-    const long n_vec = stream_bytes / 16;
+    const long n_vec = stream_bytes / 16;       // (a last partial quad of every stream is left alone)
     const long blocks = (n_vec + kBlock * 4 - 1) / (kBlock * 4);
     if (blocks > 0x7fffffffL) return HOT_EINVAL;
-    if (reads > 6 || writes > 2) {      // more streams than a thread holds at once: the looping kernel
+    const bool skewed = (stream_bytes & 15) != 0;
+    if (reads > 6 || writes > 2 || skewed) {      // more streams than a thread holds at once, or streams off the 16-byte grid: the looping kernel
         if (writes == 0) return HOT_EINVAL;
-        hot_probe_many_streams_kernel<<<dim3((unsigned)blocks), dim3(kBlock), 0, static_cast<hipStream_t>(stream)>>>(
-            static_cast<const f4 *>(arena), n_vec, reads, writes, n_vec);
+        const dim3 grid((unsigned)blocks), block(kBlock);
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        if (skewed) hot_probe_many_streams_kernel<false><<<grid, block, 0, s>>>(static_cast<const float *>(arena), stream_bytes / 4, reads, writes, n_vec);
+        else hot_probe_many_streams_kernel<true><<<grid, block, 0, s>>>(static_cast<const float *>(arena), stream_bytes / 4, reads, writes, n_vec);
         return hot_detail::note_hip(hipGetLastError());
     }
     ProbeStreams p;

@@ -317,8 +317,32 @@ def test_probe_streams_sums_its_read_streams(hot):
                 want += before[r * count:(r + 1) * count]
         for w in range(writes):
             assert torch.equal(arena[(reads + w) * count:(reads + w + 1) * count], want)
+    # streams off the 16-byte grid (a pitch of 4 * 100_003 bytes): whole quads of every stream summed, the last three
+    # floats of every write stream and everything else left alone
+    count = 100_003
+    for reads, writes in [(2, 1), (15, 13), (5, 2)]:
+        arena = torch.randn((reads + writes) * count + 8, device=DEV)
+        before = arena.clone()
+        hot.hot_probe_streams(arena, 4 * count, reads, writes)
+        torch.cuda.synchronize()
+        assert torch.equal(arena[:reads * count], before[:reads * count])
+        want = torch.zeros(count - 3, device=DEV)
+        for r0 in range(0, reads - reads % 4, 4):
+            for r in range(r0, r0 + 4):
+                want += before[r * count:(r + 1) * count - 3]
+        for r in range(reads - reads % 4, reads):
+            want += before[r * count:(r + 1) * count - 3]
+        for w in range(writes):
+            lo = (reads + w) * count
+            assert torch.equal(arena[lo:lo + count - 3], want)
+            assert torch.equal(arena[lo + count - 3:lo + count], before[lo + count - 3:lo + count])
+        assert torch.equal(arena[(reads + writes) * count:], before[(reads + writes) * count:])
     with pytest.raises(hot.HotError):
         hot.hot_probe_streams(torch.zeros(1024, device=DEV), 16, 65, 1)
+    with pytest.raises(hot.HotError):
+        hot.hot_probe_streams(torch.zeros(1024, device=DEV), 18, 2, 1)
+    with pytest.raises(hot.HotError):
+        hot.hot_probe_streams(torch.zeros(1024, device=DEV), 20, 2, 0)
     with pytest.raises(hot.HotError):
         hot.hot_probe_streams(torch.zeros(64, device=DEV), 16, 7, 0)
     with pytest.raises(ValueError):

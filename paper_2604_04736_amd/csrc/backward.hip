@@ -236,9 +236,24 @@ hot_backward_kernel(long n, long ld, int s_loc, long width, double g, double k,
         const long begin = tile * width;
         const long end = begin + width < n ? begin + width : n;
         if (end - begin == CHUNKS * kStep) {
-            backward_tile<CHUNKS, UNROLL, ALIGNED, NT, GEN, true>(begin, end, ld, s_loc, g, k, mu, sigma, eps, gw, epi, rng, acc);
+            // (four rows in flight, eps from its array: the full tile through windows too, which issues its 32 loads
+            // ahead of the sums; through plain pointers the compiler staggers them: 6.3 M x 16 0.153 against 0.143 ms)
+            backward_tile<CHUNKS, UNROLL, ALIGNED, NT, GEN, (GEN || UNROLL < 4)>(begin, end, ld, s_loc, g, k, mu, sigma, eps, gw, epi, rng, acc);
         } else {
-            backward_tile<CHUNKS, UNROLL, ALIGNED, NT, GEN, false>(begin, end, ld, s_loc, g, k, mu, sigma, eps, gw, epi, rng, acc);
+            // A narrower tile (the last one) goes through range-checked windows.  With eps from its array, chunk by chunk
+            // in a loop that is kept a loop on purpose: unrolled, the windowed body takes as many registers as the full
+            // one, and the compiler then staggers the full tile's loads instead of issuing them all ahead of the sums
+            // (209 M weights x 2 samples: 1.124 ms against 1.103).  With eps drawn, all chunks at once: there the same
+            // unrolled body leaves the full tile's code two waves per SIMD instead of three, and faster (0.805 ms
+            // against 0.824).
+            if constexpr (GEN) {
+                backward_tile<CHUNKS, UNROLL, ALIGNED, NT, GEN, false>(begin, end, ld, s_loc, g, k, mu, sigma, eps, gw, epi, rng, acc);
+            } else {
+#pragma unroll 1
+                for (long from = begin; from < end; from += kStep)
+                    backward_tile<1, UNROLL, ALIGNED, NT, GEN, false>(from, from + kStep < end ? from + kStep : end, ld, s_loc,
+                                                                      g, k, mu, sigma, eps, gw, epi, rng, acc);
+            }
             // the final 1..3 columns of the vector (n not a multiple of 4), one by one, by the thread whose quad they start
             if (end == n && (n & 3)) {
                 const long first = n & ~3L;

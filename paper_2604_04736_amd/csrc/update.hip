@@ -24,7 +24,13 @@ constexpr int kBlock = 256;
 // against 5.3 TB/s with one chunk and cached accesses).
 constexpr int kAdamChunks = 4;
 
-template <bool ALIGNED>
+// A workgroup takes tiles of kBlock * kAdamChunks quads; every array is read and written through a range-checked
+// window over the tile's whole quads (vec.h: a load beyond it returns zeros, a store beyond it is dropped), so no
+// thread branches around its accesses.  Behind branches (one per chunk, as this kernel had them) the compiler cannot
+// count the memory operations in flight across the joins and waits for all of them, loads and the previous chunk's
+// stores alike, before each chunk's stores.  Here the 32 loads of a tile are issued first and its 24 stores follow
+// the arithmetic without a wait between them.  The last one to three weights of a vector whose length is no
+// multiple of four are updated one by one by a single thread.
 __global__ void __launch_bounds__(kBlock)
 hot_adam_kernel(long n, AdamConst c, float *__restrict__ mu, float *__restrict__ sigma,
                 const float *__restrict__ gmu, const float *__restrict__ gsig, float *__restrict__ m_mu,
@@ -32,50 +38,53 @@ hot_adam_kernel(long n, AdamConst c, float *__restrict__ mu, float *__restrict__
 {
     constexpr int CH = kAdamChunks;
     constexpr bool NT = true;
-    const long n_chunks = (n + 3) / 4;
-    for (long chunk0 = (long)blockIdx.x * (kBlock * CH) + threadIdx.x; chunk0 < n_chunks; chunk0 += (long)gridDim.x * kBlock * CH) {
+    constexpr long kTile = (long)kBlock * 4 * CH;      // weights per tile
+    const long whole = n & ~3L;                         // weights in whole quads
+    const long n_tiles = (whole + kTile - 1) / kTile;
+    for (long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const long begin = tile * kTile;
+        const unsigned bytes = (unsigned)(((begin + kTile < whole ? begin + kTile : whole) - begin) * 4);
+        const window_t w_p0 = window(mu + begin, bytes), w_p1 = window(sigma + begin, bytes);
+        const window_t w_g0 = window(gmu + begin, bytes), w_g1 = window(gsig + begin, bytes);
+        const window_t w_m0 = window(m_mu + begin, bytes), w_v0 = window(v_mu + begin, bytes);
+        const window_t w_m1 = window(m_sig + begin, bytes), w_v1 = window(v_sig + begin, bytes);
         f4 p0[CH], p1[CH], g0[CH], g1[CH], m0[CH], v0[CH], m1[CH], v1[CH];
-        bool full[CH];
 #pragma unroll
         for (int q = 0; q < CH; ++q) {
-            const long col = (chunk0 + (long)q * kBlock) * 4;
-            full[q] = col + 4 <= n;
-            if (full[q]) {
-                p0[q] = load4<ALIGNED, NT>(mu + col); p1[q] = load4<ALIGNED, NT>(sigma + col);
-                g0[q] = load4<ALIGNED, NT>(gmu + col); g1[q] = load4<ALIGNED, NT>(gsig + col);
-                m0[q] = load4<ALIGNED, NT>(m_mu + col); v0[q] = load4<ALIGNED, NT>(v_mu + col);
-                m1[q] = load4<ALIGNED, NT>(m_sig + col); v1[q] = load4<ALIGNED, NT>(v_sig + col);
-            }
+            const unsigned off = threadIdx.x * 16u + (unsigned)q * (kBlock * 16u);
+            p0[q] = window_load4<NT>(w_p0, off); p1[q] = window_load4<NT>(w_p1, off);
+            g0[q] = window_load4<NT>(w_g0, off); g1[q] = window_load4<NT>(w_g1, off);
+            m0[q] = window_load4<NT>(w_m0, off); v0[q] = window_load4<NT>(w_v0, off);
+            m1[q] = window_load4<NT>(w_m1, off); v1[q] = window_load4<NT>(w_v1, off);
         }
 #pragma unroll
         for (int q = 0; q < CH; ++q) {
-            const long col = (chunk0 + (long)q * kBlock) * 4;
-            if (full[q]) {
+            const unsigned off = threadIdx.x * 16u + (unsigned)q * (kBlock * 16u);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float t = p0[q][j], a = m0[q][j], b = v0[q][j];
-                    adam_one(t, a, b, g0[q][j], c);
-                    p0[q][j] = t; m0[q][j] = a; v0[q][j] = b;
-                    t = p1[q][j]; a = m1[q][j]; b = v1[q][j];
-                    adam_one_sigma(t, a, b, g1[q][j], c);
-                    p1[q][j] = t; m1[q][j] = a; v1[q][j] = b;
-                }
-                store4<ALIGNED, NT>(mu + col, p0[q]);
-                store4<ALIGNED, NT>(sigma + col, p1[q]);
-                store4<ALIGNED, NT>(m_mu + col, m0[q]);
-                store4<ALIGNED, NT>(v_mu + col, v0[q]);
-                store4<ALIGNED, NT>(m_sig + col, m1[q]);
-                store4<ALIGNED, NT>(v_sig + col, v1[q]);
-            } else {
-                for (long i = col; i < n; ++i) {
-                    float t = mu[i], a = m_mu[i], b = v_mu[i];
-                    adam_one(t, a, b, gmu[i], c);
-                    mu[i] = t; m_mu[i] = a; v_mu[i] = b;
-                    t = sigma[i]; a = m_sig[i]; b = v_sig[i];
-                    adam_one_sigma(t, a, b, gsig[i], c);
-                    sigma[i] = t; m_sig[i] = a; v_sig[i] = b;
-                }
+            for (int j = 0; j < 4; ++j) {
+                float t = p0[q][j], a = m0[q][j], b = v0[q][j];
+                adam_one(t, a, b, g0[q][j], c);
+                p0[q][j] = t; m0[q][j] = a; v0[q][j] = b;
+                t = p1[q][j]; a = m1[q][j]; b = v1[q][j];
+                adam_one_sigma(t, a, b, g1[q][j], c);
+                p1[q][j] = t; m1[q][j] = a; v1[q][j] = b;
             }
+            window_store4<NT>(w_p0, off, p0[q]);
+            window_store4<NT>(w_p1, off, p1[q]);
+            window_store4<NT>(w_m0, off, m0[q]);
+            window_store4<NT>(w_v0, off, v0[q]);
+            window_store4<NT>(w_m1, off, m1[q]);
+            window_store4<NT>(w_v1, off, v1[q]);
+        }
+    }
+    if (whole < n && blockIdx.x == 0 && threadIdx.x == 0) {
+        for (long i = whole; i < n; ++i) {
+            float t = mu[i], a = m_mu[i], b = v_mu[i];
+            adam_one(t, a, b, gmu[i], c);
+            mu[i] = t; m_mu[i] = a; v_mu[i] = b;
+            t = sigma[i]; a = m_sig[i]; b = v_sig[i];
+            adam_one_sigma(t, a, b, gsig[i], c);
+            sigma[i] = t; m_sig[i] = a; v_sig[i] = b;
         }
     }
 }
@@ -208,15 +217,11 @@ int hot_adam_step(const hot_adam *p, int64_t n, float *mu, float *sigma, const f
     AdamConst c;
     if (!make_adam_const(p, c)) return HOT_EINVAL;
     const void *ptrs[8] = {mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma};
-    bool al = true;
-    for (const void *q : ptrs) {
+    for (const void *q : ptrs)
         if (!aligned4(q)) return HOT_EINVAL;
-        al = al && aligned16(q);
-    }
     const dim3 grid(blocks_for(((n + 3) / 4 + kAdamChunks - 1) / kAdamChunks)), block(kBlock);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (al) hot_adam_kernel<true><<<grid, block, 0, s>>>(n, c, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma);
-    else hot_adam_kernel<false><<<grid, block, 0, s>>>(n, c, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma);
+    hot_adam_kernel<<<grid, block, 0, s>>>(n, c, mu, sigma, grad_mu, grad_sigma, m_mu, v_mu, m_sigma, v_sigma);
     return hot_detail::note_hip(hipGetLastError());
 }
 

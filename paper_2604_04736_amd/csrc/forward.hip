@@ -17,8 +17,11 @@ namespace {
 //
 // NoPrologue: nothing (Algorithm 2's reparameterisation line on the parameters as they are).
 struct NoPrologue {
+    struct State {};
     template <bool ALIGNED>
-    __device__ __forceinline__ void quad(long, f4 &, f4 &) const {}
+    __device__ __forceinline__ void load(long, State &) const {}
+    template <bool ALIGNED>
+    __device__ __forceinline__ void apply(long, f4 &, f4 &, State &) const {}
     __device__ __forceinline__ void one(long, float &, float &) const {}
 };
 
@@ -30,27 +33,36 @@ struct AdamPrologue {
     const float *gmu, *gsig;
     float *m_mu, *v_mu, *m_sig, *v_sig;
     AdamConst c;
+    // In two steps, so that the kernel can issue the loads of all of a thread's chunks before the first store (the
+    // arrays are updated in place, and a load that follows a store to the same array in program order stays behind it).
+    struct State {
+        f4 g0, g1, a0, b0, a1, b1;
+    };
     template <bool ALIGNED>
-    __device__ __forceinline__ void quad(long col, f4 &m, f4 &sd) const
+    __device__ __forceinline__ void load(long col, State &st) const
     {
-        const f4 g0 = load4<ALIGNED, true>(gmu + col), g1 = load4<ALIGNED, true>(gsig + col);
-        f4 a0 = load4<ALIGNED, true>(m_mu + col), b0 = load4<ALIGNED, true>(v_mu + col);
-        f4 a1 = load4<ALIGNED, true>(m_sig + col), b1 = load4<ALIGNED, true>(v_sig + col);
+        st.g0 = load4<ALIGNED, true>(gmu + col); st.g1 = load4<ALIGNED, true>(gsig + col);
+        st.a0 = load4<ALIGNED, true>(m_mu + col); st.b0 = load4<ALIGNED, true>(v_mu + col);
+        st.a1 = load4<ALIGNED, true>(m_sig + col); st.b1 = load4<ALIGNED, true>(v_sig + col);
+    }
+    template <bool ALIGNED>
+    __device__ __forceinline__ void apply(long col, f4 &m, f4 &sd, State &st) const
+    {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            float t = m[j], a = a0[j], b = b0[j];
-            adam_one(t, a, b, g0[j], c);
-            m[j] = t; a0[j] = a; b0[j] = b;
-            t = sd[j]; a = a1[j]; b = b1[j];
-            adam_one_sigma(t, a, b, g1[j], c);
-            sd[j] = t; a1[j] = a; b1[j] = b;
+            float t = m[j], a = st.a0[j], b = st.b0[j];
+            adam_one(t, a, b, st.g0[j], c);
+            m[j] = t; st.a0[j] = a; st.b0[j] = b;
+            t = sd[j]; a = st.a1[j]; b = st.b1[j];
+            adam_one_sigma(t, a, b, st.g1[j], c);
+            sd[j] = t; st.a1[j] = a; st.b1[j] = b;
         }
         store4<ALIGNED, true>(mu + col, m);
         store4<ALIGNED, true>(sigma + col, sd);
-        store4<ALIGNED, true>(m_mu + col, a0);
-        store4<ALIGNED, true>(v_mu + col, b0);
-        store4<ALIGNED, true>(m_sig + col, a1);
-        store4<ALIGNED, true>(v_sig + col, b1);
+        store4<ALIGNED, true>(m_mu + col, st.a0);
+        store4<ALIGNED, true>(v_mu + col, st.b0);
+        store4<ALIGNED, true>(m_sig + col, st.a1);
+        store4<ALIGNED, true>(v_sig + col, st.b1);
     }
     __device__ __forceinline__ void one(long i, float &m, float &sd) const
     {
@@ -159,9 +171,13 @@ __device__ __forceinline__ void forward_tile(long begin, long end, long ld, int 
             sd[c] = window_load4<NT>(window(sigma + begin, bytes), threadIdx.x * 16u + c * (unsigned)(kStep * 4));
         }
     }
+    typename PRO::State st[CHUNKS];
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c)
-        if (ok[c]) pro.template quad<ALIGNED>(col0 + c * kStep, m[c], sd[c]);
+        if (ok[c]) pro.template load<ALIGNED>(col0 + c * kStep, st[c]);
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c)
+        if (ok[c]) pro.template apply<ALIGNED>(col0 + c * kStep, m[c], sd[c], st[c]);
     int s = 0;
     for (; s + UNROLL <= s_loc; s += UNROLL)
         forward_rows<CHUNKS, UNROLL, ALIGNED, NT, GEN, FULL>(s, begin, bytes, ld, m, sd, eps, w, rng);

@@ -26,18 +26,41 @@ struct StoreGrad {
     float *gmu, *gsig;
     int accumulate;
     static constexpr bool kReduces = false;   // no per-workgroup sum behind the tile loop
+    // Every epilogue works in two steps: load() for all of a thread's chunks, then quad() chunk by chunk.  A load
+    // that follows a store in program order can only be waited for together with that store, so what an epilogue
+    // reads is fetched before its first chunk is written.
+    // Here: what the outputs hold, if the gradients are to be added to it.  The loads go through a range-checked
+    // window (vec.h) that is empty unless accumulate is set: no branch, hence no join at which the compiler would
+    // have to wait for every outstanding access, the previous chunk's stores included.
+    struct State {
+        f4 om, os;
+    };
+    // tile: the tile's first column, bytes: its size, off: byte offset of this quad in the tile, col = tile + off / 4
     template <bool ALIGNED, bool NT>
-    __device__ __forceinline__ void quad(long col, f4, f4, const double (&gm)[4], const double (&gs)[4], double &) const
+    __device__ __forceinline__ void load(long tile, unsigned bytes, unsigned off, long, bool, State &st) const
     {
-        f4 om = {0.0f, 0.0f, 0.0f, 0.0f}, os = {0.0f, 0.0f, 0.0f, 0.0f};
+        const unsigned held = accumulate ? bytes : 0u;
+        st.om = window_load4<NT>(window(gmu + tile, held), off);
+        st.os = window_load4<NT>(window(gsig + tile, held), off);
+    }
+    // The same right before a chunk's stores, behind a branch: nothing is issued when there is nothing to add.
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void load_late(long col, State &st) const
+    {
+        st.om = st.os = f4{0.0f, 0.0f, 0.0f, 0.0f};
         if (accumulate) {
-            om = load4<ALIGNED, NT>(gmu + col);
-            os = load4<ALIGNED, NT>(gsig + col);
+            st.om = load4<ALIGNED, NT>(gmu + col);
+            st.os = load4<ALIGNED, NT>(gsig + col);
         }
+    }
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void quad(long col, f4, f4, const double (&gm)[4], const double (&gs)[4], double &, State &st) const
+    {
+        f4 om, os;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            om[j] = (float)(gm[j] + (double)om[j]);
-            os[j] = (float)(gs[j] + (double)os[j]);
+            om[j] = (float)(gm[j] + (double)st.om[j]);
+            os[j] = (float)(gs[j] + (double)st.os[j]);
         }
         store4<ALIGNED, NT>(gmu + col, om);
         store4<ALIGNED, NT>(gsig + col, os);
@@ -56,7 +79,15 @@ struct AdamUpdate {
     float *mu, *sigma, *m_mu, *v_mu, *m_sig, *v_sig;
     AdamConst c;
     static constexpr bool kReduces = false;
-    // updates m, sd (and the moments in memory) in place and stores them
+    // The moments are read chunk by chunk inside the update, not ahead of it: holding those of all four chunks
+    // costs the kernels with this epilogue a wave per SIMD (the one that also writes the next samples: 2.43 ->
+    // 2.60 ms at 209 M weights x 2 samples; backward + Adam at 6.3 M x 16: 0.186 -> 0.195 ms).
+    struct State {};
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void load(long, unsigned, unsigned, long, bool, State &) const {}
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void load_late(long, State &) const {}
+    // updates m, sd and the moments in place and stores them
     template <bool ALIGNED>
     __device__ __forceinline__ void update4(long col, f4 &m, f4 &sd, const double (&gm)[4], const double (&gs)[4]) const
     {
@@ -88,7 +119,7 @@ struct AdamUpdate {
         sigma[i] = sd; m_sig[i] = a; v_sig[i] = b;
     }
     template <bool ALIGNED, bool NT>
-    __device__ __forceinline__ void quad(long col, f4 m, f4 sd, const double (&gm)[4], const double (&gs)[4], double &) const
+    __device__ __forceinline__ void quad(long col, f4 m, f4 sd, const double (&gm)[4], const double (&gs)[4], double &, State &) const
     {
         update4<ALIGNED>(col, m, sd, gm, gs);
     }
@@ -110,8 +141,13 @@ struct AdamUpdateSample {
     Rng next;          // the draw of the next step
     double *partials;  // one KL partial per workgroup, or nullptr when no KL is wanted
     static constexpr bool kReduces = true;
+    using State = AdamUpdate::State;
     template <bool ALIGNED, bool NT>
-    __device__ __forceinline__ void quad(long col, f4 m, f4 sd, const double (&gm)[4], const double (&gs)[4], double &kl) const
+    __device__ __forceinline__ void load(long, unsigned, unsigned, long, bool, State &) const {}
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void load_late(long, State &) const {}
+    template <bool ALIGNED, bool NT>
+    __device__ __forceinline__ void quad(long col, f4 m, f4 sd, const double (&gm)[4], const double (&gs)[4], double &kl, State &) const
     {
         adam.template update4<ALIGNED>(col, m, sd, gm, gs);
         for (int s = 0; s < s_loc; ++s) {
@@ -211,13 +247,27 @@ __device__ __forceinline__ void backward_tile(long begin, long end, long ld, int
         backward_rows<CHUNKS, UNROLL, ALIGNED, NT, GEN, FULL>(s, begin, bytes, ld, sum_g, sum_ge, eps, gw, rng);
     for (; s < s_loc; ++s)
         backward_rows<CHUNKS, 1, ALIGNED, NT, GEN, FULL>(s, begin, bytes, ld, sum_g, sum_ge, eps, gw, rng);
+    // What the epilogue reads is fetched for all chunks ahead of the first chunk's stores where that measured
+    // faster (four rows in flight: 6.3 M x 16 0.143 -> 0.141 ms, 7.7 M x 13 0.155 -> 0.152; eps drawn: 0.803 ->
+    // 0.796 ms at 209 M x 2), chunk by chunk behind a branch where it did not (two rows in flight, eps from its
+    // array: 1.090 ms against 1.100 at 209 M x 2, where even loads from an empty window take their time).
+    constexpr bool kAhead = GEN || UNROLL >= 4;
+    constexpr unsigned kTileBytes = FULL ? (unsigned)(CHUNKS * kStep * 4) : 0u;
+    typename EPI::State st[CHUNKS];
+    if constexpr (kAhead) {
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c)
+            epi.template load<ALIGNED, NT>(begin, FULL ? kTileBytes : bytes, threadIdx.x * 16u + c * (unsigned)(kStep * 4),
+                                           col0 + c * kStep, ok[c], st[c]);
+    }
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c)
         if (ok[c]) {
+            if constexpr (!kAhead) epi.template load_late<ALIGNED, NT>(col0 + c * kStep, st[c]);
             double gm[4], gs[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) finish_grad(sum_g[c][j], sum_ge[c][j], m[c][j], sd[c][j], g, k, gm[j], gs[j]);
-            epi.template quad<ALIGNED, NT>(col0 + c * kStep, m[c], sd[c], gm, gs, acc);
+            epi.template quad<ALIGNED, NT>(col0 + c * kStep, m[c], sd[c], gm, gs, acc, st[c]);
         }
 }
 

@@ -267,6 +267,19 @@ def test_device_code_has_no_packed_instructions(tmp_path):
                 assert "s_nop 15" in m.group(2), m.group(1)
     assert kernels >= 10        # the instantiations of the kernels of the linear layer
 
+    # The backward kernel of the largest workload (four chunks, two rows in flight, eps from its array) issues the 16
+    # loads of a step of rows (2 rows x 4 chunks x (grad_w, eps)) ahead of the sums and then waits for the first.
+    # With the narrow last tile's code unrolled beside the full tile's, the compiler once staggered them (a load, a
+    # wait for it, the next load), which cost 2.5 % there.
+    text = open(tmp_path / "backward.hip.s").read()
+    name = r"_ZN\S*hot_backward_kernelILi4ELi2ELb1ELb1ELb0ENS_9StoreGradE\S*"
+    body = re.search(r"^(%s):[^\n]*\n(.*?)s_endpgm" % name, text, re.S | re.M).group(2)
+    shapes = []
+    for block in re.split(r"^\.LBB\S+:", body, flags=re.M):
+        ev = re.findall(r"(global_load_dwordx4|buffer_load_dwordx4)|s_waitcnt vmcnt\((\d+)\)", block)
+        shapes.append("".join("L" if ld else "w%s " % n for ld, n in ev))
+    assert any(re.search(r"L{16}w15 ", sh) for sh in shapes), [sh for sh in shapes if "LLLL" in sh]
+
     # ... and no kernel can read a result without them: the matrix builtins occur only inside MfmaAcc, whose
     # registers are private and handed out against an MfmaSettled alone, and only MfmaSettled's constructor
     # issues the wait states (so a read needs one constructed, i.e. the wait states issued).

@@ -683,10 +683,18 @@ def test_training_step_of_a_small_bayesian_mlp_matches_autograd(hot):
 
 @pytest.mark.parametrize("groups", [[1] * 6, [2, 4], [5, 1], [6]])
 @pytest.mark.parametrize("use_rng", [False, True])
-def test_backward_over_subsets_of_samples_accumulates_to_the_whole(oracle, hot, groups, use_rng):
-    n, ld, s, s_total, dsize = 50_003, 50_016, 6, 12, 777.0
+@pytest.mark.parametrize("n,ld,launch", [(50_003, 50_016, None), (70_001, 70_004, dict(chunks=4, unroll=4, nontemporal=1)),
+                                         (70_001, 70_001, dict(chunks=4, unroll=2)), (9_000, 9_000, dict(chunks=2, unroll=1))],
+                         ids=["default", "c4u4nt", "c4u2-unaligned", "c2u1"])
+def test_backward_over_subsets_of_samples_accumulates_to_the_whole(oracle, hot, groups, use_rng, n, ld, launch):
+    # (the launch shapes decide how the kernel fetches what it adds to: ahead of all stores through windows with
+    # four rows in flight or drawn eps, chunk by chunk otherwise; full tiles and the narrow last one)
+    s, s_total, dsize = 6, 12, 777.0
     x = _random_case(n, ld, s, seed=21)
     plan = hot.hot_create(n, ld, s, s_total, dsize, 0)
+    if launch:
+        for kern in (hot.HOT_KERNEL_BACKWARD, hot.HOT_KERNEL_BACKWARD_RNG):
+            hot.hot_set_launch(plan, kern, **launch)
     rng = hot.hot_rng(seed=8, step=3, first_sample=6)
     if use_rng:
         hot.hot_sample_eps(plan, rng, x["eps"])

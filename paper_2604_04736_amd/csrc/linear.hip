@@ -72,6 +72,7 @@ struct MfmaSettled {
 };
 
 typedef float f16v __attribute__((ext_vector_type(16)));
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 
 template <class V, int N>
 class MfmaAcc {
@@ -89,6 +90,8 @@ public:
         if constexpr (N == 4) v_ = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, v_, 0, 0, 0);
         else v_ = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, v_, 0, 0, 0);
     }
+    // the same over sixteen contraction indices of bf16 operands (32 x 32 blocks only)
+    __device__ __forceinline__ void mac(bf8 a, bf8 b) { v_ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, v_, 0, 0, 0); }
     __device__ __forceinline__ V read(const MfmaSettled &) const { return v_; }
 };
 typedef MfmaAcc<f4, 4> Acc16x16;        // v_mfma_f32_16x16x4_f32: four result registers per lane
@@ -437,6 +440,56 @@ typedef __attribute__((address_space(3))) float lds_float;
 typedef __attribute__((address_space(3))) f4 lds_f4;
 typedef __attribute__((address_space(3))) void lds_void;
 
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) unsigned short lds_ushort;
+typedef unsigned u2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) u2 lds_u2;
+typedef __attribute__((address_space(3))) bf8 lds_bf8;
+
+// The kernel's products on the bf16 matrix instruction (v_mfma_f32_32x32x16_bf16: sixteen contraction indices in half
+// the cycles that v_mfma_f32_32x32x2_f32 takes for two) at the accuracy of fp32: a float is the exact sum of three
+// pieces of at most eight significant bits each, x = x1 + x2 + x3 up to 2^-24 |x| (the first two remainders are exact,
+// the third piece is cut off), each piece is a bf16 number, and a product of two pieces is exact in the fp32
+// accumulator.  x w = x1 w1 + (x1 w2 + x2 w1) + (x1 w3 + x2 w2 + x3 w1) + terms below 2^-24 |x w|: six products, summed
+// from the smallest on.  The matrix pipe does 6 x 32 = 192 cycles of work per 32 x 32 x 16 block instead of 512.
+constexpr bool kSlabBf16 = true;
+
+__device__ __forceinline__ void split_bf16(float x, unsigned short &p1, unsigned short &p2, unsigned short &p3)
+{
+    const unsigned u1 = __builtin_bit_cast(unsigned, x) & 0xFFFF0000u;
+    const float r = x - __builtin_bit_cast(float, u1);
+    const unsigned u2_ = __builtin_bit_cast(unsigned, r) & 0xFFFF0000u;
+    const float r2 = r - __builtin_bit_cast(float, u2_);
+    p1 = (unsigned short)(u1 >> 16);
+    p2 = (unsigned short)(u2_ >> 16);
+    p3 = (unsigned short)(__builtin_bit_cast(unsigned, r2) >> 16);
+}
+
+// the pieces of eight floats (a then b), packed as the matrix instruction takes them
+__device__ __forceinline__ void split8_bf16(const f4 &a, const f4 &b, bf8 &p1, bf8 &p2, bf8 &p3)
+{
+    unsigned u1[8], u2_[8], u3[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float x = j < 4 ? a[j] : b[j - 4];
+        u1[j] = __builtin_bit_cast(unsigned, x) & 0xFFFF0000u;
+        const float r = x - __builtin_bit_cast(float, u1[j]);
+        u2_[j] = __builtin_bit_cast(unsigned, r) & 0xFFFF0000u;
+        const float r2 = r - __builtin_bit_cast(float, u2_[j]);
+        u3[j] = __builtin_bit_cast(unsigned, r2) & 0xFFFF0000u;
+    }
+    u4 q1, q2, q3;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        q1[j] = u1[2 * j + 1] | (u1[2 * j] >> 16);
+        q2[j] = u2_[2 * j + 1] | (u2_[2 * j] >> 16);
+        q3[j] = u3[2 * j + 1] | (u3[2 * j] >> 16);
+    }
+    p1 = __builtin_bit_cast(bf8, q1);
+    p2 = __builtin_bit_cast(bf8, q2);
+    p3 = __builtin_bit_cast(bf8, q3);
+}
+
 // What the kernel works on: out_s[row][n] = sum_c in_s[row][c] W_s(n, c) + bias_s[n] with W_s drawn.  Forward (TR = false):
 // in = x, c runs over the layer's inputs, n over its outputs, weight (n, c) has flat index n * C + c (the generator's
 // quads run along c).  Input gradients (TR = true): in = dy, c runs over the layer's outputs, n over its inputs, weight
@@ -468,8 +521,8 @@ __device__ __forceinline__ int slab_swizzle(int r) { return ((r >> 1) & 3) ^ ((r
 // every sample has an input of its own (then ST = 1).
 // RBW: blocks of 32 rows per wave; one only with four waves (128 rows per workgroup, for 65 to 128 rows: half the matrix
 // work per draw again).
-template <int WAVES, int CBW, int ST, bool OWN, bool TR, int RBW = 2>
-__global__ void __launch_bounds__(64 * WAVES, CBW * ST <= 2 ? 4 : 2)
+template <int WAVES, int CBW, int ST, bool OWN, bool TR, int RBW = 2, bool BF = (kSlabBf16 && RBW == 2)>
+__global__ void __launch_bounds__(64 * WAVES, CBW * ST <= 2 ? (BF && WAVES != 16 ? 3 : 4) : 2)
 hot_linear_slab_kernel(SlabArgs a)
 {
     static_assert(ST == 1 || ST == 2, "one or two samples per pass");
@@ -483,7 +536,8 @@ hot_linear_slab_kernel(SlabArgs a)
     constexpr int QUADS = ST * OUTS * 4;     // quads drawn per step
     static_assert(QUADS <= 64 * WAVES && QUADS % 64 == 0, "whole waves draw");
     __shared__ __attribute__((aligned(16))) float xs0[WAVES * XW], xs1[WAVES * XW];
-    __shared__ __attribute__((aligned(16))) float ws0[ST * WT], ws1[ST * WT];
+    // (BF: three planes of bf16 pieces instead of one of floats)
+    __shared__ __attribute__((aligned(16))) float ws0[ST * WT * (BF ? 3 : 2) / 2], ws1[ST * WT * (BF ? 3 : 2) / 2];
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int l32 = lane & 31, half = lane >> 5;
@@ -516,8 +570,16 @@ hot_linear_slab_kernel(SlabArgs a)
     const int d_cols = C - d_c;
     const long d_flat = TR ? (long)d_c * N + n0 + d_n : (long)(n0 + d_n) * C + d_c;
     const unsigned w_step = TR ? (unsigned)(KS * N * 4) : (unsigned)(KS * 4);      // bytes from one step's quad to the next
-    int d_put[TR ? 4 : 1];                   // where the drawn weights go in the tile (floats)
-    if constexpr (!TR) d_put[0] = d_st * WT + (4 * d_n + ((d_c >> 2) ^ slab_swizzle(d_n & 15))) * 4;
+    int d_put[TR ? 4 : 1];                   // where the drawn weights go in the tile (floats; BF: bytes within a plane)
+    if constexpr (BF) {
+        // A plane holds, per sample and output, 32 bytes: two chunks of eight bf16, chunk h with the contraction indices
+        // 4 h .. 4 h + 3 and 8 + 4 h .. 8 + 4 h + 3 (what lanes 32 h .. 32 h + 31 feed to one matrix instruction), stored
+        // as chunk h ^ bit 3 of the output (so that 16 consecutive outputs spread over all banks).
+        const int h = (d_c >> 2) & 1, part = d_c >> 3;
+#pragma unroll
+        for (int e = 0; e < (TR ? 4 : 1); ++e)
+            d_put[e] = (d_st * OUTS + d_n + e) * 32 + ((h ^ (((d_n + e) >> 3) & 1)) << 4) + part * 8 + (TR ? (d_c & 3) * 2 : 0);
+    } else if constexpr (!TR) d_put[0] = d_st * WT + (4 * d_n + ((d_c >> 2) ^ slab_swizzle(d_n & 15))) * 4;
     else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) d_put[e] = d_st * WT + (4 * (d_n + e) + ((d_c >> 2) ^ slab_swizzle((d_n + e) & 15))) * 4 + (d_c & 3);
@@ -554,7 +616,23 @@ hot_linear_slab_kernel(SlabArgs a)
 #pragma unroll
                     for (int c = 0; c < 4; ++c) w4[c] = __builtin_fmaf(sd4[c], e[c], m4[c]);
                 }
-                if constexpr (!TR) *(lds_f4 *)(wsb + d_put[0]) = w4;
+                if constexpr (BF) {
+                    // three bf16 pieces of every weight (see split_bf16): a quad along the contraction is 8 bytes per plane
+                    unsigned short pc[3][4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) split_bf16(w4[c], pc[0][c], pc[1][c], pc[2][c]);
+#pragma unroll
+                    for (int pl = 0; pl < 3; ++pl) {
+                        lds_char *plane = (lds_char *)wsb + pl * (ST * OUTS * 32);
+                        if constexpr (!TR) {
+                            const u2 v = {(unsigned)pc[pl][0] | ((unsigned)pc[pl][1] << 16), (unsigned)pc[pl][2] | ((unsigned)pc[pl][3] << 16)};
+                            *(lds_u2 *)(plane + d_put[0]) = v;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) *(lds_ushort *)(plane + d_put[e]) = pc[pl][e];
+                        }
+                    }
+                } else if constexpr (!TR) *(lds_f4 *)(wsb + d_put[0]) = w4;
                 else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) wsb[d_put[e]] = w4[e];
@@ -578,10 +656,12 @@ hot_linear_slab_kernel(SlabArgs a)
             const volatile lds_f4 *wp = (const volatile lds_f4 *)(wsb + op_off[k8]);
 #pragma unroll
             for (int rb = 0; rb < RBW; ++rb) xa[k8][rb] = xp[rb * 128];
+            if constexpr (!BF) {
 #pragma unroll
-            for (int st = 0; st < ST; ++st)
+                for (int st = 0; st < ST; ++st)
 #pragma unroll
-                for (int cb = 0; cb < CBW; ++cb) wb[k8][st][cb] = wp[(st * WT + cb * 512) / 4];
+                    for (int cb = 0; cb < CBW; ++cb) wb[k8][st][cb] = wp[(st * WT + cb * 512) / 4];
+            }
         };
         auto multiply = [&](int k8, int i0, int i1) {
 #pragma unroll
@@ -592,6 +672,35 @@ hot_linear_slab_kernel(SlabArgs a)
                     for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
                         for (int cb = 0; cb < CBW; ++cb) mm[st][rb][cb].mac(xa[k8][rb][i], wb[k8][st][cb][i]);
+        };
+        // BF: one step on the bf16 matrix instruction.  The operands of the step are read (x as floats, the weights
+        // as their three planes), x is cut into its pieces, and six products per block of 32 x 32 leave out only the
+        // terms below 2^-24 of the full product; then the barrier, behind which the buffers just read are refilled.
+        auto step_bf = [&](int cb0, lds_float *xsb, lds_float *wsb) {
+            read_ops(0, xsb, wsb);
+            read_ops(1, xsb, wsb);
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) {
+                bf8 a1, a2, a3;
+                split8_bf16(xa[0][rb], xa[1][rb], a1, a2, a3);
+#pragma unroll
+                for (int st = 0; st < ST; ++st)
+#pragma unroll
+                    for (int cb = 0; cb < CBW; ++cb) {
+                        const volatile lds_bf8 *wp = (const volatile lds_bf8 *)((const lds_char *)wsb + ((st * OUTS + cb * 32 + l32) * 32 + ((half ^ ((l32 >> 3) & 1)) << 4)));
+                        const bf8 b1 = wp[0], b2 = wp[ST * OUTS * 2], b3 = wp[2 * ST * OUTS * 2];
+                        mm[st][rb][cb].mac(a3, b1);
+                        mm[st][rb][cb].mac(a2, b2);
+                        mm[st][rb][cb].mac(a1, b3);
+                        mm[st][rb][cb].mac(a2, b1);
+                        mm[st][rb][cb].mac(a1, b2);
+                        mm[st][rb][cb].mac(a1, b1);
+                    }
+            }
+            everything_arrived_then_barrier();
+            put_w(cb0 + 2 * KS, wsb);
+            ask_w(cb0 + 3 * KS);
+            ask_x(cb0 + 2 * KS, xsb);
         };
         auto step = [&](int cb0, lds_float *xsb, lds_float *wsb, const lds_float *xsn, const lds_float *wsn) {
             read_ops(1, xsb, wsb);
@@ -613,10 +722,17 @@ hot_linear_slab_kernel(SlabArgs a)
         put_w(KS, W1);
         ask_w(2 * KS);
         everything_arrived_then_barrier();
-        read_ops(0, X0, W0);
-        for (int cb0 = 0; cb0 < C; cb0 += 2 * KS) {      // (an odd number of steps is followed by one on zeros)
-            step(cb0, X0, W0, X1, W1);
-            step(cb0 + KS, X1, W1, X0, W0);
+        if constexpr (BF) {
+            for (int cb0 = 0; cb0 < C; cb0 += 2 * KS) {
+                step_bf(cb0, X0, W0);
+                step_bf(cb0 + KS, X1, W1);
+            }
+        } else {
+            read_ops(0, X0, W0);
+            for (int cb0 = 0; cb0 < C; cb0 += 2 * KS) {      // (an odd number of steps is followed by one on zeros)
+                step(cb0, X0, W0, X1, W1);
+                step(cb0 + KS, X1, W1, X0, W0);
+            }
         }
         const MfmaSettled settled;
 

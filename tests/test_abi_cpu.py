@@ -290,7 +290,7 @@ def test_device_code_has_no_packed_instructions(tmp_path):
             assert calls == 0, src
             continue
         cls = re.search(r"class MfmaAcc \{(.*?)\n\};", code, re.S).group(1)
-        assert calls == len(re.findall(r"__builtin_amdgcn_mfma_", cls)) == 2
+        assert calls == len(re.findall(r"__builtin_amdgcn_mfma_", cls)) == 3      # 16x16x4 f32, 32x32x2 f32, 32x32x16 bf16
         assert re.search(r"\n    V v_;\n\npublic:", "\n" + cls) and "read(const MfmaSettled &) const { return v_; }" in cls
         assert len(re.findall(r"mfma_results_settle\(\)", code)) == 2      # its definition and MfmaSettled's constructor
         assert "MfmaSettled() { mfma_results_settle(); }" in code

@@ -7,7 +7,9 @@ Tolerance, per output y[s, r, o], with A = sum_k |x_k| (|mu_k| + sigma_k r_k) + 
 (the default fp32 tolerance, taken relative to the sum of addend magnitudes).  It covers the fp32
 draw (measured 2.6e-7 r), the rounding of w and the fp32 accumulation on the matrix cores, whose
 rounding errors grow like sqrt(K) * 2^-24 in practice: the worst error measured over the shapes
-below is 2.8e-7 * A at K = 2160."""
+below is 2.8e-7 * A at K = 2160.  The kernels with 64 rows per wave multiply bf16 pieces of both factors
+(six partial products, what they leave out is below 3 * 2^-24 of a product): the same bound holds, and
+test_products_from_bf16_pieces_keep_fp32_accuracy puts values to them that use every piece."""
 import numpy as np
 import pytest
 import torch
@@ -117,6 +119,41 @@ def test_fused_layer_on_the_512_row_kernel(oracle, hot, rows, k, o, s, shape):
     y = _run(hot, c, s, rng, w_off, b_off)
     worst = _check(oracle, c, y, s, rng, w_off, b_off)
     print("  worst error / magnitude sum: %.2e" % worst, flush=True)
+
+
+@pytest.mark.parametrize("rows,k,o,s,shape", [(1530, 20, 5400, 2, 822), (2040, 36, 4090, 2, 1621), (300, 20, 3702, 2, 412)])
+def test_products_from_bf16_pieces_keep_fp32_accuracy(oracle, hot, rows, k, o, s, shape):
+    """The kernels with 64 rows per wave form every product x w from three bf16 pieces of either factor (six of the
+    nine partial products).  Values that put the pieces to the test: small integers (one piece each: the result must
+    be the exact integer), full 24-bit mantissas (all three pieces of both factors carry bits), and magnitudes spread
+    over twelve decades within one row."""
+    assert hot.hot_linear_launch_shape(rows, k, o, s, 0) == shape
+    g = np.random.default_rng(rows + o)
+    rng = hot.hot_rng(seed=99, step=1, first_sample=0)
+    zero = np.zeros((o, k), np.float32)
+    # exact integers
+    c = dict(x=g.integers(-64, 65, size=(rows, k)).astype(np.float32), mu_w=g.integers(-8, 9, size=(o, k)).astype(np.float32),
+             sigma_w=zero, mu_b=np.zeros(o, np.float32), sigma_b=np.zeros(o, np.float32))
+    y = _run(hot, c, s, rng, 0, o * k)
+    want = c["x"].astype(np.int64) @ c["mu_w"].astype(np.int64).T
+    assert all(np.array_equal(y[i].astype(np.int64), want) and np.array_equal(y[i], np.rint(y[i])) for i in range(s))
+    # full mantissas: (2^24 - odd) * 2^e on both sides, sigma = 0: against the fp64 products
+    def full(shape_, lo, hi):
+        m = (2 ** 24 - 1 - 2 * g.integers(0, 2 ** 20, size=shape_)).astype(np.float64)
+        return (m * 2.0 ** g.integers(lo, hi, size=shape_) * g.choice([-1.0, 1.0], size=shape_)).astype(np.float32)
+    c = dict(x=full((rows, k), -30, -20), mu_w=full((o, k), -28, -22), sigma_w=zero, mu_b=np.zeros(o, np.float32), sigma_b=np.zeros(o, np.float32))
+    y = _run(hot, c, s, rng, 0, o * k)
+    want = c["x"].astype(np.float64) @ c["mu_w"].astype(np.float64).T
+    A = np.abs(c["x"].astype(np.float64)) @ np.abs(c["mu_w"].astype(np.float64)).T
+    worst = max(float(np.max(np.abs(y[i] - want) / A)) for i in range(s))
+    print("  full mantissas: worst error / magnitude sum %.2e" % worst, flush=True)
+    assert worst <= 1e-6        # (the six products leave out 3 * 2^-24; fp32 accumulation adds its own)
+    # twelve decades in a row, drawn weights: the oracle's tolerance
+    c = _layer(7, rows, k, o)
+    c["x"] = (c["x"] * 10.0 ** g.uniform(-6, 6, size=c["x"].shape)).astype(np.float32)
+    c["mu_w"] = (c["mu_w"] * 10.0 ** g.uniform(-3, 3, size=c["mu_w"].shape)).astype(np.float32)
+    y = _run(hot, c, s, rng, 8, 8 + ((o * k + 3) // 4) * 4)
+    print("  twelve decades: worst error / magnitude sum %.2e" % _check(oracle, c, y, s, rng, 8, 8 + ((o * k + 3) // 4) * 4), flush=True)
 
 
 @pytest.mark.parametrize("rows,k,o,s", SHAPES)

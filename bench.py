@@ -707,6 +707,11 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
                      "agrees_with_materialised": bool((y - y2).abs().max().item() <= 1e-5 * scale),
                      "backward": bwd}
         del x, mu, sg, y, y2, w
+    out["note"] = ("TFLOPs counts the layer's 2 S R K O fp32 operations. From 129 rows on, the forward call and the input "
+                   "gradients form every product from three bf16 pieces of both factors on v_mfma_f32_32x32x16_bf16 (six of "
+                   "the nine partial products: fp32 accuracy at 6/16 of the cycles of v_mfma_f32_32x32x2_f32), so "
+                   "frac_of_fp32_mfma_peak, which prices against the fp32 instruction's 157.3 TFLOP/s, can exceed 1; against "
+                   "the bf16 peak divided by six products the ceiling is 417 TFLOP/s. Weight gradients use the fp32 instruction.")
     return out
 
 

@@ -219,16 +219,19 @@ int hot_last_hip_error(const hot_plan *plan);
  * existing in memory.  x: [rows, ldx] or [s_local, rows, ldx]; mu_W, sigma_W: [out_features, in_features] packed
  * row-major; mu_b, sigma_b: [out_features] or both NULL; y: [s_local, rows, out_features]
  * packed, out.  All DEVICE pointers; x, mu_W, sigma_W 16-byte aligned; in_features, ldx,
- * weight_offset, bias_offset multiples of 4.  The contraction runs on the matrix cores in
- * fp32 (v_mfma_f32_16x16x4_f32, v_mfma_f32_32x32x2_f32).  Runs on the current device, asynchronous on `stream`.
+ * weight_offset, bias_offset multiples of 4.  The contraction runs on the matrix cores at fp32
+ * accuracy: on the fp32 instructions (v_mfma_f32_16x16x4_f32, v_mfma_f32_32x32x2_f32), or, in the tiles of 256 rows
+ * and more, on v_mfma_f32_32x32x16_bf16 with every product formed from three bf16 pieces of both factors (six
+ * partial products; what they leave out is below 3 * 2^-24 of a product; measured errors up to 7e-7 of the sum of
+ * addend magnitudes, against 3e-7 on the fp32 instruction).  Runs on the current device, asynchronous on `stream`.
  * Up to a few hundred rows a wave draws the weights it multiplies (re-drawing eps per block of 64
  * rows is then cheaper than writing and re-reading w); from 256 rows on, given at least 128 workgroups
  * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS; where tiles of 256, 512
  * or 1024 rows x 32 to 128 outputs fill the chip (hot_linear_launch_shape tells; the 256-row tiles from 129 rows
- * on, tiles of 128 rows from 65 to 128), four, eight or sixteen waves share it and x goes from memory straight into LDS (110-140 TFLOP/s, up to
- * 89 % of the fp32 matrix peak).  The draw and the matrix instructions do not overlap on this chip; against writing w once
+ * on, tiles of 128 rows from 65 to 128), four, eight or sixteen waves share it and x goes from memory straight into LDS (150-190 TFLOP/s
+ * of fp32 work on layers that fill the chip).  The draw and the matrix instructions do not overlap on this chip; against writing w once
  * with hot_forward_rng and calling a library GEMM the call is 1.8-2.9x faster up to tens of rows, level at
- * 64 rows, 1.2-1.35x at the 7260 and 16640 rows of a Swin and a ViT layer, and level on the largest squares;
+ * 64 rows, 1.8-2.0x at the 7260 and 16640 rows of a Swin and a ViT layer, and 1.4x on the largest squares;
  * between about 80 and 500 rows large layers stay behind that route (0.75-1.0x at 8192 x 8192, 0.7-0.95x at
  * 2160 x 8640): one draw serves too few rows there and the two do not overlap.
  */

@@ -711,7 +711,8 @@ def sampled_linear_lines(hot, torch, dev, iters: int = 20):
                    "gradients form every product from three bf16 pieces of both factors on v_mfma_f32_32x32x16_bf16 (six of "
                    "the nine partial products: fp32 accuracy at 6/16 of the cycles of v_mfma_f32_32x32x2_f32), so "
                    "frac_of_fp32_mfma_peak, which prices against the fp32 instruction's 157.3 TFLOP/s, can exceed 1; against "
-                   "the bf16 peak divided by six products the ceiling is 417 TFLOP/s. Weight gradients use the fp32 instruction.")
+                   "the bf16 peak divided by six products the ceiling is 417 TFLOP/s. The weight gradients of large layers (tiles of "
+                   "128 x 128) are formed the same way; the other weight-gradient kernels use the fp32 instructions.")
     return out
 
 

@@ -453,6 +453,7 @@ typedef __attribute__((address_space(3))) bf8 lds_bf8;
 // accumulator.  x w = x1 w1 + (x1 w2 + x2 w1) + (x1 w3 + x2 w2 + x3 w1) + terms below 2^-24 |x w|: six products, summed
 // from the smallest on.  The matrix pipe does 6 x 32 = 192 cycles of work per 32 x 32 x 16 block instead of 512.
 constexpr bool kSlabBf16 = true;
+constexpr bool kTileBf16 = true;      // the same in the weight-gradient tile kernel
 
 __device__ __forceinline__ void split_bf16(float x, unsigned short &p1, unsigned short &p2, unsigned short &p3)
 {
@@ -1558,6 +1559,50 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
         request(XB[1], DB[1], rows - kTileRows);
         request(XB[2], DB[2], rows - 2 * kTileRows);
         everything_arrived_then_barrier();
+        if constexpr (kTileBf16) {
+            // On the bf16 matrix instruction (see split_bf16): the 16 rows of a step are its contraction block.  Lanes
+            // 0-31 hold the even rows of a column, lanes 32-63 the odd ones, on both sides alike.  A step reads its
+            // operands, cuts them into pieces, multiplies, and meets the others at the barrier, behind which the
+            // buffers of the step before are refilled.
+            for (int left = rows; left > 0;) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    read_half(0, XB[b], DB[b]);
+                    read_half(1, XB[b], DB[b]);
+                    if (bias_wave) {
+#pragma unroll
+                        for (int p = 0; p < P; ++p) {
+                            sb[0] += bv[p][0];
+                            sb[1] += bv[p][1];
+                        }
+                    }
+                    bf8 a1[2], a2[2], a3[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        split8_bf16(f4{av[0][i], av[1][i], av[2][i], av[3][i]}, f4{av[4][i], av[5][i], av[6][i], av[7][i]}, a1[i], a2[i], a3[i]);
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        bf8 b1, b2, b3;
+                        split8_bf16(f4{bv[0][j], bv[1][j], bv[2][j], bv[3][j]}, f4{bv[4][j], bv[5][j], bv[6][j], bv[7][j]}, b1, b2, b3);
+#pragma unroll
+                        for (int i = 0; i < 2; ++i)
+                            if (WHOLE || ok[i][j]) {
+                                mm[i][j].mac(a3[i], b1);
+                                mm[i][j].mac(a2[i], b2);
+                                mm[i][j].mac(a1[i], b3);
+                                mm[i][j].mac(a2[i], b1);
+                                mm[i][j].mac(a1[i], b2);
+                                mm[i][j].mac(a1[i], b1);
+                            }
+                    }
+                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(XI + DI) : "memory");
+                    request(XB[(b + 3) % 4], DB[(b + 3) % 4], left - 3 * kTileRows);
+                    left -= kTileRows;
+                }
+            }
+            everything_arrived_then_barrier();       // every wave is done with the buffers
+            return;
+        }
         read_half(0, XB[0], DB[0]);
         for (int left = rows; left > 0;) {
 #pragma unroll

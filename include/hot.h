@@ -223,7 +223,9 @@ int hot_last_hip_error(const hot_plan *plan);
  * accuracy: on the fp32 instructions (v_mfma_f32_16x16x4_f32, v_mfma_f32_32x32x2_f32), or, in the tiles of 256 rows
  * and more, on v_mfma_f32_32x32x16_bf16 with every product formed from three bf16 pieces of both factors (six
  * partial products; what they leave out is below 3 * 2^-24 of a product; measured errors up to 7e-7 of the sum of
- * addend magnitudes, against 3e-7 on the fp32 instruction).  Runs on the current device, asynchronous on `stream`.
+ * addend magnitudes, against 3e-7 on the fp32 instruction; a factor below about 1e-33 in magnitude has pieces
+ * below bf16's normal range, which the instruction may flush, and an infinite factor gives NaN, not infinity).
+ * Runs on the current device, asynchronous on `stream`.
  * Up to a few hundred rows a wave draws the weights it multiplies (re-drawing eps per block of 64
  * rows is then cheaper than writing and re-reading w); from 256 rows on, given at least 128 workgroups
  * of 256 rows x 16 outputs, the four waves of a workgroup share every draw through LDS; where tiles of 256, 512

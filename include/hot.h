@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define HOT_VERSION 301 /* major*10000 + minor*100 + patch */
+#define HOT_VERSION 302 /* major*10000 + minor*100 + patch */
 
 enum {
     HOT_OK = 0,

@@ -148,7 +148,7 @@ def test_one_pass_backward_shape_query_and_its_workspace(hot):
 
 
 def test_host_only_entry_points(hot):
-    assert hot.hot_version() == 301
+    assert hot.hot_version() == 302
     assert hot.hot_strerror(0) == "success"
     assert "invalid" in hot.hot_strerror(hot.HOT_EINVAL)
     assert hot.hot_strerror(-99) == "unknown error code"

@@ -448,43 +448,38 @@ typedef __attribute__((address_space(3))) bf8 lds_bf8;
 
 // The kernel's products on the bf16 matrix instruction (v_mfma_f32_32x32x16_bf16: sixteen contraction indices in half
 // the cycles that v_mfma_f32_32x32x2_f32 takes for two) at the accuracy of fp32: a float is the exact sum of three
-// pieces of at most eight significant bits each, x = x1 + x2 + x3 up to 2^-24 |x| (the first two remainders are exact,
-// the third piece is cut off), each piece is a bf16 number, and a product of two pieces is exact in the fp32
+// pieces of at most eight significant bits each, x = x1 + x2 + x3 up to 2^-25 |x| (each piece is the remainder rounded
+// to bf16, both remainders are exact), each piece is a bf16 number, and a product of two pieces is exact in the fp32
 // accumulator.  x w = x1 w1 + (x1 w2 + x2 w1) + (x1 w3 + x2 w2 + x3 w1) + terms below 2^-24 |x w|: six products, summed
 // from the smallest on.  The matrix pipe does 6 x 32 = 192 cycles of work per 32 x 32 x 16 block instead of 512.
 constexpr bool kSlabBf16 = true;
 constexpr bool kTileBf16 = true;      // the same in the weight-gradient tile kernel
 
-__device__ __forceinline__ void split_bf16(float x, unsigned short &p1, unsigned short &p2, unsigned short &p3)
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+
+// the pieces of two floats, each piece pair packed in one register (v_cvt_pk_bf16_f32 rounds to nearest even)
+__device__ __forceinline__ void split2_bf16(float x0, float x1, unsigned &p1, unsigned &p2, unsigned &p3)
 {
-    const unsigned u1 = __builtin_bit_cast(unsigned, x) & 0xFFFF0000u;
-    const float r = x - __builtin_bit_cast(float, u1);
-    const unsigned u2_ = __builtin_bit_cast(unsigned, r) & 0xFFFF0000u;
-    const float r2 = r - __builtin_bit_cast(float, u2_);
-    p1 = (unsigned short)(u1 >> 16);
-    p2 = (unsigned short)(u2_ >> 16);
-    p3 = (unsigned short)(__builtin_bit_cast(unsigned, r2) >> 16);
+    p1 = __builtin_bit_cast(unsigned, __builtin_convertvector(f2{x0, x1}, bf2));
+    const float r0 = x0 - __builtin_bit_cast(float, p1 << 16), r1 = x1 - __builtin_bit_cast(float, p1 & 0xFFFF0000u);
+    p2 = __builtin_bit_cast(unsigned, __builtin_convertvector(f2{r0, r1}, bf2));
+    const float s0 = r0 - __builtin_bit_cast(float, p2 << 16), s1 = r1 - __builtin_bit_cast(float, p2 & 0xFFFF0000u);
+    p3 = __builtin_bit_cast(unsigned, __builtin_convertvector(f2{s0, s1}, bf2));
 }
 
 // the pieces of eight floats (a then b), packed as the matrix instruction takes them
 __device__ __forceinline__ void split8_bf16(const f4 &a, const f4 &b, bf8 &p1, bf8 &p2, bf8 &p3)
 {
-    unsigned u1[8], u2_[8], u3[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const float x = j < 4 ? a[j] : b[j - 4];
-        u1[j] = __builtin_bit_cast(unsigned, x) & 0xFFFF0000u;
-        const float r = x - __builtin_bit_cast(float, u1[j]);
-        u2_[j] = __builtin_bit_cast(unsigned, r) & 0xFFFF0000u;
-        const float r2 = r - __builtin_bit_cast(float, u2_[j]);
-        u3[j] = __builtin_bit_cast(unsigned, r2) & 0xFFFF0000u;
-    }
     u4 q1, q2, q3;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        q1[j] = u1[2 * j + 1] | (u1[2 * j] >> 16);
-        q2[j] = u2_[2 * j + 1] | (u2_[2 * j] >> 16);
-        q3[j] = u3[2 * j + 1] | (u3[2 * j] >> 16);
+        const float x0 = j < 2 ? a[2 * j] : b[2 * j - 4], x1 = j < 2 ? a[2 * j + 1] : b[2 * j - 3];
+        unsigned t1, t2, t3;
+        split2_bf16(x0, x1, t1, t2, t3);
+        q1[j] = t1;
+        q2[j] = t2;
+        q3[j] = t3;
     }
     p1 = __builtin_bit_cast(bf8, q1);
     p2 = __builtin_bit_cast(bf8, q2);
@@ -618,19 +613,17 @@ hot_linear_slab_kernel(SlabArgs a)
                     for (int c = 0; c < 4; ++c) w4[c] = __builtin_fmaf(sd4[c], e[c], m4[c]);
                 }
                 if constexpr (BF) {
-                    // three bf16 pieces of every weight (see split_bf16): a quad along the contraction is 8 bytes per plane
-                    unsigned short pc[3][4];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) split_bf16(w4[c], pc[0][c], pc[1][c], pc[2][c]);
+                    // three bf16 pieces of every weight (see split2_bf16): a quad along the contraction is 8 bytes per plane
+                    unsigned pc[3][2];
+                    split2_bf16(w4[0], w4[1], pc[0][0], pc[1][0], pc[2][0]);
+                    split2_bf16(w4[2], w4[3], pc[0][1], pc[1][1], pc[2][1]);
 #pragma unroll
                     for (int pl = 0; pl < 3; ++pl) {
                         lds_char *plane = (lds_char *)wsb + pl * (ST * OUTS * 32);
-                        if constexpr (!TR) {
-                            const u2 v = {(unsigned)pc[pl][0] | ((unsigned)pc[pl][1] << 16), (unsigned)pc[pl][2] | ((unsigned)pc[pl][3] << 16)};
-                            *(lds_u2 *)(plane + d_put[0]) = v;
-                        } else {
+                        if constexpr (!TR) *(lds_u2 *)(plane + d_put[0]) = u2{pc[pl][0], pc[pl][1]};
+                        else {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) *(lds_ushort *)(plane + d_put[e]) = pc[pl][e];
+                            for (int e = 0; e < 4; ++e) *(lds_ushort *)(plane + d_put[e]) = (unsigned short)(pc[pl][e >> 1] >> (16 * (e & 1)));
                         }
                     }
                 } else if constexpr (!TR) *(lds_f4 *)(wsb + d_put[0]) = w4;
@@ -1560,7 +1553,7 @@ __device__ __forceinline__ void wgrad_tile_body(const LinearGradArgs &a, lds_flo
         request(XB[2], DB[2], rows - 2 * kTileRows);
         everything_arrived_then_barrier();
         if constexpr (kTileBf16) {
-            // On the bf16 matrix instruction (see split_bf16): the 16 rows of a step are its contraction block.  Lanes
+            // On the bf16 matrix instruction (see split2_bf16): the 16 rows of a step are its contraction block.  Lanes
             // 0-31 hold the even rows of a column, lanes 32-63 the odd ones, on both sides alike.  A step reads its
             // operands, cuts them into pieces, multiplies, and meets the others at the barrier, behind which the
             // buffers of the step before are refilled.

@@ -2635,15 +2635,14 @@ WgradShape wgrad_shape_with(const hot_linear_desc *d, int64_t ws_bytes, bool wid
 
 WgradShape wgrad_shape(const hot_linear_desc *d, int64_t ws_bytes)
 {
-    // Large layers at hundreds of rows and more: the kernel with tiles of 128 x 128 (1024 x 8192^2: 100 -> 120
-    // TFLOP/s, 4096^3: 114 -> 134).  Two workgroups share a compute unit, so 512 tiles make a round, and a last
-    // round less than half full costs as much as a full one (2160 x 8640, 1156 tiles: level with the kernel above
-    // at every row count, which keeps it); one tile per compute unit pays from a thousand rows on (2048^2: 86 ->
-    // 100 TFLOP/s).  Layers with fewer tiles stay with the kernel above, whose smaller tiles and row split fill the
-    // chip better.
-    const long tile_count = wgrad_tile_count(d), last_round = tile_count % 512;
-    const bool fills = tile_count >= 512 ? (last_round == 0 || last_round >= 256 || tile_count >= 2048)
-                                         : (tile_count > 230 && tile_count <= 256 && d->rows >= 1024);
+    // Large layers at hundreds of rows and more: the kernel with tiles of 128 x 128.  Two workgroups share a compute
+    // unit, so 512 tiles make a round, and a last round that is nearly empty costs as much as a full one; since the
+    // kernel multiplies bf16 pieces it wins all the same (measured against the kernel above at 160 to 7260 rows: 1156
+    // tiles 1.2-1.6x, 520 to 576 tiles 1.05-1.5x), and from 140 tiles and 256 rows on too (144 to 306 tiles 1.0-1.4x;
+    // 128 tiles 0.8-0.95x, 85 tiles 0.5-0.8x: those stay with the kernel above, whose smaller tiles and row split fill
+    // the chip better, as do few-tile layers whose rows a workspace spreads over the chip).
+    const long tile_count = wgrad_tile_count(d);
+    const bool fills = tile_count >= 512 || (tile_count >= 140 && d->rows >= 256 && !(ws_bytes != 0 && d->rows >= 8192));
     if (wgrad_tile_fits(d) && d->rows >= kSlab4MinRows && fills) {
         WgradShape w = wgrad_shape_with(d, 0, false);
         w.parts = 1;

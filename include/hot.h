@@ -274,15 +274,16 @@ int hot_linear_forward_rng(const hot_linear_desc *desc, const hot_rng *rng, cons
  * on, once per workgroup of 64 to 256 rows (its waves share the draws through LDS), or, where tiles of 512
  * or 1024 rows fill the chip, once per such tile (the forward pass's kernel for many rows with dy as its
  * input; it needs out_features to be a multiple of 4 and dy 16-byte aligned).  Large layers
- * (from 129 rows on, at least two tiles of 128 inputs x 128 outputs per compute unit) take their weight
- * gradients from a kernel that stages x and dy through LDS (up to 138 TFLOP/s); it needs out_features to
+ * (from 129 rows on, at least 512 tiles of 128 inputs x 128 outputs, or from 256 rows on at least 140) take their
+ * weight gradients from a kernel that stages x and dy through LDS and multiplies bf16 pieces of both, as the
+ * forward call's large tiles do (up to 180 TFLOP/s of fp32 work); it needs out_features to
  * be a multiple of 4 and rows * max(ldx, out_features) * 4 below 4 GiB, else the first kernel runs; with more
  * than two samples it adds up pairs of samples in grad_mu_w and grad_sigma_w themselves.  All of these kernels
  * scale the sums and add the KL part in fp32 (g * sum + k * mu, g * sum + k * (sigma - 1/sigma) with the hardware's
  * reciprocal: 1e-7 of each term), where hot_backward does it in fp64.  Against
  * library GEMMs for dx and G followed by hot_backward_rng the call is 1.1-3x faster up to tens of rows (with a
- * workspace, see below; 0.86-3x without) and at 1.0-1.35x for thousands of rows; between about 100 and 500 rows it
- * stays behind on large layers (0.65-0.9x).
+ * workspace, see below; 0.8-3x without) and at 1.08-1.25x for thousands of rows; between about 100 and 450 rows it
+ * mostly stays behind on large layers (0.65-1.0x).
  */
 int hot_linear_backward_rng(const hot_linear_desc *desc, int32_t s_total, double dataset_size, uint32_t flags,
                             const hot_rng *rng, const float *x, const float *dy, const float *mu_w,

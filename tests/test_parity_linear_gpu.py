@@ -940,7 +940,9 @@ TILED = [(300, 2900, 4228, 2, False, True),      # 23 x 34 tiles of 128 x 128, r
          (272, 2048, 4096, 3, True, False),      # 16 x 32 whole tiles, three samples with inputs of their own
          (257, 3000, 4092, 1, False, True),      # 24 x 32 tiles, both edges ragged, a single sample, an odd number of steps
          (1030, 2048, 2000, 2, False, True),     # one tile per compute unit, from a thousand rows on
-         (150, 2048, 4096, 2, False, True)]      # fewer rows than one 256-row block (the kernel runs from 129 rows on)
+         (150, 2048, 4096, 2, False, True),      # fewer rows than one 256-row block (the kernel runs from 129 rows on)
+         (260, 1500, 2048, 2, False, True),      # 12 x 16 = 192 tiles: fewer than a round of 512 (the kernel takes these from 256 rows on)
+         (300, 2160, 8640, 2, False, False)]     # 17 x 68 = 1156 tiles: a last round of 512 that is a quarter full
 
 
 @pytest.mark.parametrize("rows,k,o,s,xs,bias", TILED)
